@@ -1,0 +1,192 @@
+"""CPU oracle for the sketch-query + linear path (TEST INFRASTRUCTURE ONLY).
+
+Thin numpy wrappers over ``sketch_oracle.c`` (plain C, built with gcc) plus
+the importance-aware width allocation of Sec. 3.2.  Nothing in the GPU
+library imports this package and this package imports nothing of the GPU
+library.  Callers: tests/, the smoke check, and the benchmark's CPU leg
+(offline sketch generator + cpu_baseline timing).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sketch_oracle.c")
+_LIB = os.path.join(_HERE, "libsketch_oracle.so")
+
+_u32p = ctypes.POINTER(ctypes.c_uint32)
+_u16p = ctypes.POINTER(ctypes.c_uint16)
+_f64p = ctypes.POINTER(ctypes.c_double)
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle (gcc -O2, no intrinsics, no OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.ora_half_to_double.restype = ctypes.c_double
+        L.ora_half_to_double.argtypes = [ctypes.c_uint16]
+        L.ora_bf16_to_double.restype = ctypes.c_double
+        L.ora_bf16_to_double.argtypes = [ctypes.c_uint16]
+        L.ora_select.restype = ctypes.c_uint32
+        L.ora_select.argtypes = [ctypes.c_uint32] * 4
+        L.ora_count_states.restype = ctypes.c_uint64
+        L.ora_count_states.argtypes = [ctypes.c_uint32] * 5 + [_u32p]
+        geom = [ctypes.c_uint32] * 5 + [_u32p, _u32p, _u32p]
+        L.ora_update.restype = ctypes.c_int
+        L.ora_update.argtypes = geom + [_u16p, _u16p, ctypes.c_uint64]
+        L.ora_query.restype = ctypes.c_int
+        L.ora_query.argtypes = geom + [_u16p, ctypes.c_uint64, _u16p]
+        L.ora_linear.restype = ctypes.c_int
+        L.ora_linear.argtypes = [ctypes.c_uint32, ctypes.c_uint32, _u16p, _u16p, ctypes.c_int,
+                                 ctypes.c_uint32, ctypes.c_uint64, _u32p, ctypes.c_uint32, _f64p]
+        _lib = L
+    return _lib
+
+
+def _p(a, ty):
+    return a.ctypes.data_as(ty)
+
+
+def _u32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.uint32))
+
+
+def _u16(a):
+    a = np.asarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    return np.ascontiguousarray(a, dtype=np.uint16)
+
+
+@dataclass
+class Sketch:
+    """A sketched linear layer: geometry, hash parameters, widths, states.
+
+    ``states`` holds binary16 bit patterns, group-major, then sketch row,
+    then index inside the row (Sec. 3.1 sketch state S, one per group)."""
+    in_features: int
+    out_features: int
+    tile_in: int
+    tile_out: int
+    d: int
+    hash_a: np.ndarray
+    hash_c: np.ndarray
+    group_width: np.ndarray
+    states: np.ndarray
+
+    @property
+    def n_groups(self):
+        return (self.in_features // self.tile_in) * (self.out_features // self.tile_out)
+
+    @property
+    def bits_per_weight(self):
+        return 16.0 * self.states.size / (self.in_features * self.out_features)
+
+
+def half_to_double(bits) -> np.ndarray:
+    L = _load()
+    b = np.asarray(bits, dtype=np.uint16).ravel()
+    return np.array([L.ora_half_to_double(int(v)) for v in b]).reshape(np.shape(bits))
+
+
+def select(A: int, C: int, K: int, a: int) -> int:
+    """Eq. (3): row-local state index of the weight at group offset ``a``."""
+    return int(_load().ora_select(A, C, K, a))
+
+
+def count_states(in_f, out_f, tj, to, d, width) -> int:
+    w = _u32(width)
+    return int(_load().ora_count_states(in_f, out_f, tj, to, d, _p(w, _u32p)))
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed: code {rc} "
+                         f"({ {1: 'bad argument', 2: 'non-finite value'}.get(rc, '?')})")
+
+
+def update(W, tile_in, tile_out, d, hash_a, hash_c, group_width) -> Sketch:
+    """Eq. (4): build the sketch states of W ([in][out] binary16)."""
+    Wb = _u16(W)
+    in_f, out_f = Wb.shape
+    A, C, wd = _u32(hash_a), _u32(hash_c), _u32(group_width).ravel()
+    assert A.size == d and C.size == d
+    n = count_states(in_f, out_f, tile_in, tile_out, d, wd)
+    if n == 0:
+        raise ValueError("bad geometry")
+    states = np.empty(n, dtype=np.uint16)
+    rc = _load().ora_update(in_f, out_f, tile_in, tile_out, d, _p(A, _u32p), _p(C, _u32p),
+                            _p(wd, _u32p), _p(Wb, _u16p), _p(states, _u16p), n)
+    _check(rc, "update")
+    return Sketch(in_f, out_f, tile_in, tile_out, d, A, C, wd, states)
+
+
+def query(sk: Sketch) -> np.ndarray:
+    """Eq. (5): reconstruct W_hat ([in][out] binary16 bit patterns)."""
+    W_hat = np.empty((sk.in_features, sk.out_features), dtype=np.uint16)
+    st = _u16(sk.states)
+    rc = _load().ora_query(sk.in_features, sk.out_features, sk.tile_in, sk.tile_out, sk.d,
+                           _p(_u32(sk.hash_a), _u32p), _p(_u32(sk.hash_c), _u32p),
+                           _p(_u32(sk.group_width), _u32p), _p(st, _u16p), st.size,
+                           _p(W_hat, _u16p))
+    _check(rc, "query")
+    return W_hat
+
+
+def linear(W_hat, x, x_kind: str = "f16", cols=None) -> np.ndarray:
+    """y = x W_hat in binary64 (Eq. (1)/(2): y = xW, W is d_in x d_out).
+
+    ``x``: [batch][in] bit patterns (uint16) or float16 array; ``x_kind``
+    'f16' or 'bf16' says how to read uint16 bit patterns.  ``cols`` limits
+    the result to the listed output channels."""
+    Wb = _u16(W_hat)
+    in_f, out_f = Wb.shape
+    xb = _u16(x)
+    if xb.ndim == 1:
+        xb = xb[None, :]
+    batch, ldx = xb.shape
+    assert ldx == in_f
+    kind = {"f16": 0, "bf16": 1}[x_kind]
+    if cols is None:
+        y = np.empty((batch, out_f), dtype=np.float64)
+        rc = _load().ora_linear(in_f, out_f, _p(Wb, _u16p), _p(xb, _u16p), kind, batch, ldx,
+                                None, 0, _p(y, _f64p))
+    else:
+        cc = _u32(cols)
+        y = np.empty((batch, cc.size), dtype=np.float64)
+        rc = _load().ora_linear(in_f, out_f, _p(Wb, _u16p), _p(xb, _u16p), kind, batch, ldx,
+                                _p(cc, _u32p), cc.size, _p(y, _f64p))
+    _check(rc, "linear")
+    return y
+
+
+def allocate_widths(importance, budget_states: int, d: int) -> np.ndarray:
+    """Importance-aware space allocation (Sec. 3.2): unit i receives the share
+    I_i / sum(I) of the total sketch space.  ``budget_states`` is the total
+    number of states of the layer, split evenly over the d sketch rows; the
+    per-row width is the floor of the share, at least 1."""
+    imp = np.asarray(importance, dtype=np.float64).ravel()
+    if imp.size == 0 or np.any(imp < 0) or not np.all(np.isfinite(imp)) or imp.sum() <= 0:
+        raise ValueError("importance must be finite, non-negative, not all zero")
+    share = imp / imp.sum()
+    k = np.floor(share * (budget_states / d)).astype(np.int64)
+    k = np.clip(k, 1, 65535)
+    return k.astype(np.uint32)

@@ -36,28 +36,32 @@ def build(force: bool = False) -> str:
 _lib = None
 
 
+def _bind(L):
+    """Declare the C signatures on a loaded oracle library."""
+    L.ora_half_to_double.restype = ctypes.c_double
+    L.ora_half_to_double.argtypes = [ctypes.c_uint16]
+    L.ora_bf16_to_double.restype = ctypes.c_double
+    L.ora_bf16_to_double.argtypes = [ctypes.c_uint16]
+    L.ora_select.restype = ctypes.c_uint32
+    L.ora_select.argtypes = [ctypes.c_uint32] * 4
+    L.ora_count_states.restype = ctypes.c_uint64
+    L.ora_count_states.argtypes = [ctypes.c_uint32] * 5 + [_u32p]
+    geom = [ctypes.c_uint32] * 5 + [_u32p, _u32p, _u32p]
+    L.ora_update.restype = ctypes.c_int
+    L.ora_update.argtypes = geom + [_u16p, _u16p, ctypes.c_uint64]
+    L.ora_query.restype = ctypes.c_int
+    L.ora_query.argtypes = geom + [_u16p, ctypes.c_uint64, _u16p]
+    L.ora_linear.restype = ctypes.c_int
+    L.ora_linear.argtypes = [ctypes.c_uint32, ctypes.c_uint32, _u16p, _u16p, ctypes.c_int,
+                             ctypes.c_uint32, ctypes.c_uint64, _u32p, ctypes.c_uint32, _f64p]
+    return L
+
+
 def _load():
     global _lib
     if _lib is None:
         build()
-        L = ctypes.CDLL(_LIB)
-        L.ora_half_to_double.restype = ctypes.c_double
-        L.ora_half_to_double.argtypes = [ctypes.c_uint16]
-        L.ora_bf16_to_double.restype = ctypes.c_double
-        L.ora_bf16_to_double.argtypes = [ctypes.c_uint16]
-        L.ora_select.restype = ctypes.c_uint32
-        L.ora_select.argtypes = [ctypes.c_uint32] * 4
-        L.ora_count_states.restype = ctypes.c_uint64
-        L.ora_count_states.argtypes = [ctypes.c_uint32] * 5 + [_u32p]
-        geom = [ctypes.c_uint32] * 5 + [_u32p, _u32p, _u32p]
-        L.ora_update.restype = ctypes.c_int
-        L.ora_update.argtypes = geom + [_u16p, _u16p, ctypes.c_uint64]
-        L.ora_query.restype = ctypes.c_int
-        L.ora_query.argtypes = geom + [_u16p, ctypes.c_uint64, _u16p]
-        L.ora_linear.restype = ctypes.c_int
-        L.ora_linear.argtypes = [ctypes.c_uint32, ctypes.c_uint32, _u16p, _u16p, ctypes.c_int,
-                                 ctypes.c_uint32, ctypes.c_uint64, _u32p, ctypes.c_uint32, _f64p]
-        _lib = L
+        _lib = _bind(ctypes.CDLL(_LIB))
     return _lib
 
 

@@ -205,23 +205,26 @@ def test_query_multi_row_via_matrix_forms(d):
     """Sec. 3.3: the multi-row case is d independent S and P; Eq. (5) then
     combines the d per-row results."""
     rng = np.random.default_rng(90 + d)
-    in_f, out_f, tj, to, K = 4, 24, 2, 12, 5
-    n_groups = (in_f // tj) * (out_f // to)
+    in_f, out_f, tj, to = 4, 36, 2, 12          # 2 x 3 groups, each with its own width
+    n_jb, n_ob = in_f // tj, out_f // to
+    widths = np.array([5, 2, 7, 3, 6, 4], dtype=np.uint32)
     A = 2 * rng.integers(0, 1 << 23, size=d) + 1
     C = rng.integers(0, 1 << 24, size=d)
-    st = (rng.integers(-3, 4, size=(n_groups, d, K)) * 0.25).astype(np.float16)   # many +/- ties
-    sk = oracle.Sketch(in_f, out_f, tj, to, d, A, C, np.full(n_groups, K, np.uint32), st.view(np.uint16).ravel())
+    tables = [(rng.integers(-3, 4, size=(d, int(K))) * 0.25).astype(np.float16) for K in widths]  # many +/- ties
+    flat = np.concatenate([t.ravel() for t in tables]).view(np.uint16)
+    sk = oracle.Sketch(in_f, out_f, tj, to, d, A, C, widths, flat)
     got = as_f16(oracle.query(sk))
     G = tj * to
-    for jb in range(in_f // tj):
-        for ob in range(out_f // to):
-            g = jb * (out_f // to) + ob
+    for jb in range(n_jb):
+        for ob in range(n_ob):
+            g = jb * n_ob + ob
+            K = int(widths[g])
             per_row = []
             for r in range(d):
                 P = np.zeros((G, K))
                 for a in range(G):
                     P[a, (((int(A[r]) * a + int(C[r])) % (1 << 24)) * K) >> 24] = 1.0
-                per_row.append(P @ st[g, r].astype(np.float64))
+                per_row.append(P @ tables[g][r].astype(np.float64))
             ref = absmax_ref(np.stack(per_row)).reshape(tj, to)
             blk = got[jb * tj:(jb + 1) * tj, ob * to:(ob + 1) * to].astype(np.float64)
             assert np.array_equal(blk, ref)

@@ -1,0 +1,163 @@
+/*
+ * sketch_linear.h -- C ABI of the fused sketch-query linear layer for
+ * AMD MI355X (gfx950).
+ *
+ * A layer's d_in x d_out weight matrix W exists only as a multi-row AbsMaxMin
+ * sketch (UltraSketchLLM, arXiv 2506.17255).  Every call below that touches
+ * weights reconstructs them on the fly,
+ *
+ *     W_hat[j][o] = Max_r  S_g[r][ H_r(Addr(j,o)) ]          (Sec. 3.1, Eq. 5)
+ *
+ * with the select function of Eq. 3 and per-group sketch widths (importance
+ * aware allocation, Sec. 3.2; "K may vary based on the importance metric",
+ * Sec. 3.3), and multiplies them into the activations, y = x W_hat
+ * (Sec. 2.1, Eq. 1/2: W is d_in x d_out, activations multiply from the left).
+ * W_hat is never written to device memory, except by the diagnostic call
+ * sketch_linear_reconstruct().
+ *
+ * Conventions fixed by this library where the paper is silent:
+ *   group     a tile of tile_in x tile_out weights; groups are numbered
+ *             g = (j / tile_in) * (d_out / tile_out) + (o / tile_out).
+ *   Addr      offset inside the group, a = (j % tile_in) * tile_out + (o % tile_out).
+ *   H_r       t = (hash_a[r] * a + hash_c[r]) mod 2^24;  H_r(a) = floor(t * K_g / 2^24),
+ *             K_g = group_width[g]; the same d pairs serve every group.
+ *   Max       by magnitude; of two candidates with equal magnitude the one
+ *             with the clear sign bit.
+ *   states    IEEE binary16 bit patterns, group-major, then sketch row r,
+ *             then index k:  states[base_g + r * K_g + k].
+ *
+ * General rules
+ *   - Every function returns a status code and never throws, aborts or
+ *     prints.  sketch_linear_last_error() returns a thread-local text for
+ *     the last non-OK status of the calling thread.
+ *   - Pointers are HOST pointers unless the parameter comment says DEVICE.
+ *   - The library never allocates device memory: dev_buf, workspace,
+ *     activations and outputs are caller-allocated, borrowed, and must stay
+ *     valid until the work enqueued on them has completed (dev_buf: until
+ *     sketch_linear_destroy).  Device pointers must be 16-byte aligned.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *     gemv / gemm / reconstruct only enqueue work and never synchronise;
+ *     create synchronises the stream once so that the host arrays may be
+ *     freed when it returns.
+ *   - Calls that use the same layer handle must be ordered on one stream
+ *     (the layer's device buffer holds scratch counters).
+ *   - All arguments are validated before anything is enqueued.
+ */
+#ifndef SKETCH_LINEAR_H
+#define SKETCH_LINEAR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SKL_API __attribute__((visibility("default")))
+
+typedef enum {
+    SKL_OK = 0,
+    SKL_ERR_INVALID_ARG = 1,      /* NULL pointer, bad size, misaligned pointer, bad dtype */
+    SKL_ERR_UNSUPPORTED = 2,      /* valid request outside what the kernels cover
+                                     (e.g. a group table that does not fit in LDS) */
+    SKL_ERR_BUFFER_TOO_SMALL = 3, /* dev_buf or workspace smaller than required */
+    SKL_ERR_NONFINITE = 4,        /* a state is NaN or infinite */
+    SKL_ERR_HIP = 5               /* a HIP runtime call failed; see last_error */
+} skl_status_t;
+
+typedef enum { SKL_F16 = 0, SKL_BF16 = 1, SKL_F32 = 2 } skl_dtype_t;
+
+/* Description of one sketched layer (all pointers HOST). */
+typedef struct {
+    uint32_t struct_size;      /* sizeof(skl_desc_t), for ABI checking */
+    uint32_t in_features;      /* d_in  >= 1 */
+    uint32_t out_features;     /* d_out >= 1 */
+    uint32_t tile_in;          /* divides in_features  */
+    uint32_t tile_out;         /* divides out_features; tile_in * tile_out <= 2^24 */
+    uint32_t d;                /* sketch rows, 1..8 */
+    uint32_t query_mode;       /* 0 = magnitude Max as described above; others reserved */
+    uint32_t flags;            /* bit 0: always hash per weight (path 0) even when the geometry
+                                  allows the row-sketch path; other bits must be 0 */
+    const uint32_t *hash_a;    /* [d], each < 2^24 */
+    const uint32_t *hash_c;    /* [d], each < 2^24 */
+    const uint32_t *group_width; /* [(in/tile_in) * (out/tile_out)], each 1..65535 */
+    const uint16_t *states;    /* [n_states] binary16 bit patterns, layout above */
+    uint64_t n_states;         /* must equal d * sum(group_width) */
+} skl_desc_t;
+
+typedef struct skl_layer skl_layer_t;   /* opaque host object */
+
+/* What create() decided; for diagnostics, tests and benchmarks. */
+typedef struct {
+    uint32_t struct_size;
+    uint32_t path;             /* 0 = per-weight hashing over 2-D groups;
+                                  1 = row sketches (tile_in = 1, tile_out = d_out):
+                                      index depends on the output channel only */
+    uint32_t n_units;          /* channel blocks (path 1) or group chunks (path 0): the
+                                  number of partial sums per output in the split reduction */
+    uint32_t max_table_bytes;  /* largest LDS-resident table of one workgroup */
+    uint64_t table_bytes;      /* bytes of sketch tables resident in dev_buf */
+    uint64_t n_weights;        /* in_features * out_features */
+    uint64_t n_states;
+} skl_info_t;
+
+/* Bytes of device memory create() needs for this description.
+ * Validates the whole description (Sec. 3.1 states must be finite). */
+SKL_API skl_status_t sketch_linear_device_bytes(const skl_desc_t *desc, uint64_t *bytes);
+
+/* Build a layer: validate, lay the tables out for the kernels (states are
+ * re-encoded as order keys and, for row sketches, transposed so that eight
+ * consecutive input channels of one state sit in one 16-byte word) and copy
+ * them into dev_buf (DEVICE, 256-byte aligned, >= device_bytes).  This is
+ * the sketch state S of Sec. 3.1 that "stays permanently in memory". */
+SKL_API skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_t dev_bytes,
+                                  void *hip_stream, skl_layer_t **out_layer);
+
+SKL_API skl_status_t sketch_linear_info(const skl_layer_t *layer, skl_info_t *info);
+
+/* Bytes of DEVICE workspace needed by gemv (op = 0, n = batch) or gemm
+ * (op = 1, n = tokens).  The workspace holds the partial sums of the split
+ * reduction (gemv) or the re-ordered fp16 activations (gemm); its contents
+ * are scratch. */
+SKL_API skl_status_t sketch_linear_workspace_bytes(const skl_layer_t *layer, uint32_t op, uint32_t n,
+                                           uint64_t *bytes);
+
+/* Decode:  y[b][o] = sum_j x[b][j] * W_hat[j][o],  b < batch (1..16).
+ *   x  DEVICE, binary16, [batch][ldx], ldx >= in_features  (x_dtype must be SKL_F16)
+ *   y  DEVICE, binary16 or float32, [batch][ldy], ldy >= out_features
+ * Products are exact, accumulation is float32, the result is rounded to
+ * nearest-even once.  The summation order is fixed: results are
+ * bit-identical from run to run.  (Sec. 3 inference flow: decompress then
+ * compute, here fused; Eq. 5 and Eq. 1/2.) */
+SKL_API skl_status_t sketch_linear_gemv(const skl_layer_t *layer, const void *x, skl_dtype_t x_dtype,
+                                uint32_t ldx, void *y, skl_dtype_t y_dtype, uint32_t ldy,
+                                uint32_t batch, void *workspace, uint64_t workspace_bytes,
+                                void *hip_stream);
+
+/* Prefill:  Y[t][o] = sum_j X[t][j] * W_hat[j][o],  t < tokens (>= 1).
+ *   X  DEVICE, bfloat16 or binary16, [tokens][ldx]; |X| must not exceed 65504:
+ *      bfloat16 inputs are converted to binary16 (exact inside that range,
+ *      down to the binary16 subnormal step) so that W_hat enters the matrix
+ *      cores unrounded.
+ *   Y  DEVICE, bfloat16, binary16 or float32, [tokens][ldy]
+ * float32 accumulation on the matrix cores (MFMA), one final rounding. */
+SKL_API skl_status_t sketch_linear_gemm(const skl_layer_t *layer, const void *X, skl_dtype_t x_dtype,
+                                uint32_t ldx, void *Y, skl_dtype_t y_dtype, uint32_t ldy,
+                                uint32_t tokens, void *workspace, uint64_t workspace_bytes,
+                                void *hip_stream);
+
+/* Diagnostic: write W_hat (Eq. 5) as binary16 bit patterns to
+ * W_hat_dev (DEVICE, [in_features][out_features], row major).  The only call
+ * that materialises the weights. */
+SKL_API skl_status_t sketch_linear_reconstruct(const skl_layer_t *layer, uint16_t *W_hat_dev,
+                                       void *hip_stream);
+
+/* Frees the host object only; dev_buf stays the caller's. NULL is accepted. */
+SKL_API void sketch_linear_destroy(skl_layer_t *layer);
+
+/* Text for the calling thread's last non-OK status ("" if none). */
+SKL_API const char *sketch_linear_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKETCH_LINEAR_H */

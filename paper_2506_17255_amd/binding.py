@@ -1,0 +1,181 @@
+"""ctypes binding of libsketch_linear.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see
+include/sketch_linear.h).  Device pointers and the HIP stream are plain
+integers (``tensor.data_ptr()``, ``torch.cuda.current_stream().cuda_stream``);
+this module imports neither torch nor numpy and holds no arithmetic of the
+method.  If the library has not been built the import of the symbols fails
+loudly: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from .build import lib_path
+
+SKL_OK = 0
+SKL_ERR_INVALID_ARG = 1
+SKL_ERR_UNSUPPORTED = 2
+SKL_ERR_BUFFER_TOO_SMALL = 3
+SKL_ERR_NONFINITE = 4
+SKL_ERR_HIP = 5
+
+SKL_F16, SKL_BF16, SKL_F32 = 0, 1, 2
+FLAG_HASH_PER_WEIGHT = 1
+
+STATUS_NAMES = {0: "SKL_OK", 1: "SKL_ERR_INVALID_ARG", 2: "SKL_ERR_UNSUPPORTED",
+                3: "SKL_ERR_BUFFER_TOO_SMALL", 4: "SKL_ERR_NONFINITE", 5: "SKL_ERR_HIP"}
+
+EXPORTS = ("sketch_linear_device_bytes", "sketch_linear_create", "sketch_linear_info",
+           "sketch_linear_workspace_bytes", "sketch_linear_gemv", "sketch_linear_gemm",
+           "sketch_linear_reconstruct", "sketch_linear_destroy", "sketch_linear_last_error")
+
+
+class SketchLinearError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+class skl_desc_t(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("in_features", ctypes.c_uint32),
+                ("out_features", ctypes.c_uint32), ("tile_in", ctypes.c_uint32),
+                ("tile_out", ctypes.c_uint32), ("d", ctypes.c_uint32),
+                ("query_mode", ctypes.c_uint32), ("flags", ctypes.c_uint32),
+                ("hash_a", ctypes.c_void_p), ("hash_c", ctypes.c_void_p),
+                ("group_width", ctypes.c_void_p), ("states", ctypes.c_void_p),
+                ("n_states", ctypes.c_uint64)]
+
+
+class skl_info_t(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("path", ctypes.c_uint32),
+                ("n_units", ctypes.c_uint32), ("max_table_bytes", ctypes.c_uint32),
+                ("table_bytes", ctypes.c_uint64), ("n_weights", ctypes.c_uint64),
+                ("n_states", ctypes.c_uint64)]
+
+
+_lib = None
+
+
+def load_library(path: str | None = None):
+    """Load the built library; raises if it is missing (build it first with
+    ``python -m paper_2506_17255_amd.build`` or ``__graft_entry__.build()``)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is not built; run __graft_entry__.build() first "
+                          "(there is no CPU fallback for the sketch-linear kernels)")
+    L = ctypes.CDLL(path)
+    vp, u32, u64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64
+    L.sketch_linear_device_bytes.argtypes = [ctypes.POINTER(skl_desc_t), ctypes.POINTER(u64)]
+    L.sketch_linear_create.argtypes = [ctypes.POINTER(skl_desc_t), vp, u64, vp, ctypes.POINTER(vp)]
+    L.sketch_linear_info.argtypes = [vp, ctypes.POINTER(skl_info_t)]
+    L.sketch_linear_workspace_bytes.argtypes = [vp, u32, u32, ctypes.POINTER(u64)]
+    L.sketch_linear_gemv.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
+    L.sketch_linear_gemm.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
+    L.sketch_linear_reconstruct.argtypes = [vp, vp, vp]
+    L.sketch_linear_destroy.argtypes = [vp]
+    L.sketch_linear_destroy.restype = None
+    L.sketch_linear_last_error.argtypes = []
+    L.sketch_linear_last_error.restype = ctypes.c_char_p
+    for n in EXPORTS[:7]:
+        getattr(L, n).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def sketch_linear_last_error() -> str:
+    return load_library().sketch_linear_last_error().decode()
+
+
+def _check(status: int):
+    if status != SKL_OK:
+        raise SketchLinearError(status, sketch_linear_last_error())
+
+
+def make_desc(in_features, out_features, tile_in, tile_out, d, hash_a, hash_c, group_width, states,
+              n_states=None, query_mode=0, flags=0, struct_size=None):
+    """Build a skl_desc_t from host arrays.  ``hash_a``, ``hash_c``,
+    ``group_width`` (uint32) and ``states`` (uint16) are objects exposing the
+    buffer protocol with those element types, or None; the returned
+    descriptor keeps them alive."""
+    desc = skl_desc_t()
+    desc.struct_size = ctypes.sizeof(skl_desc_t) if struct_size is None else struct_size
+    desc.in_features, desc.out_features = in_features, out_features
+    desc.tile_in, desc.tile_out, desc.d = tile_in, tile_out, d
+    desc.query_mode, desc.flags = query_mode, flags
+    keep = []
+
+    def ptr(buf, itemsize):
+        if buf is None:
+            return None
+        mv = memoryview(buf)
+        if not mv.c_contiguous or mv.itemsize != itemsize:
+            raise TypeError("descriptor arrays must be contiguous with the documented element size")
+        keep.append(buf)
+        if mv.nbytes == 0:
+            return None
+        arr = (ctypes.c_char * mv.nbytes).from_buffer_copy(mv) if mv.readonly else (ctypes.c_char * mv.nbytes).from_buffer(mv)
+        keep.append(arr)
+        return ctypes.cast(arr, ctypes.c_void_p).value
+
+    desc.hash_a = ptr(hash_a, 4)
+    desc.hash_c = ptr(hash_c, 4)
+    desc.group_width = ptr(group_width, 4)
+    desc.states = ptr(states, 2)
+    if n_states is None:
+        n_states = 0 if states is None else memoryview(states).nbytes // 2
+    desc.n_states = n_states
+    desc._keep = keep
+    return desc
+
+
+def sketch_linear_device_bytes(desc: skl_desc_t) -> int:
+    n = ctypes.c_uint64(0)
+    _check(load_library().sketch_linear_device_bytes(ctypes.byref(desc) if desc is not None else None, ctypes.byref(n)))
+    return n.value
+
+
+def sketch_linear_create(desc: skl_desc_t, dev_buf: int, dev_bytes: int, hip_stream: int = 0) -> int:
+    """Returns the opaque layer handle (an integer address)."""
+    h = ctypes.c_void_p(None)
+    _check(load_library().sketch_linear_create(ctypes.byref(desc) if desc is not None else None, dev_buf, dev_bytes,
+                                               hip_stream, ctypes.byref(h)))
+    return h.value
+
+
+def sketch_linear_info(layer: int) -> dict:
+    info = skl_info_t()
+    info.struct_size = ctypes.sizeof(skl_info_t)
+    _check(load_library().sketch_linear_info(layer, ctypes.byref(info)))
+    return {n: getattr(info, n) for n, _ in skl_info_t._fields_ if n != "struct_size"}
+
+
+def sketch_linear_workspace_bytes(layer: int, op: int, n: int) -> int:
+    b = ctypes.c_uint64(0)
+    _check(load_library().sketch_linear_workspace_bytes(layer, op, n, ctypes.byref(b)))
+    return b.value
+
+
+def sketch_linear_gemv(layer: int, x: int, x_dtype: int, ldx: int, y: int, y_dtype: int, ldy: int, batch: int,
+                       workspace: int, workspace_bytes: int, hip_stream: int = 0) -> None:
+    _check(load_library().sketch_linear_gemv(layer, x, x_dtype, ldx, y, y_dtype, ldy, batch, workspace,
+                                             workspace_bytes, hip_stream))
+
+
+def sketch_linear_gemm(layer: int, X: int, x_dtype: int, ldx: int, Y: int, y_dtype: int, ldy: int, tokens: int,
+                       workspace: int, workspace_bytes: int, hip_stream: int = 0) -> None:
+    _check(load_library().sketch_linear_gemm(layer, X, x_dtype, ldx, Y, y_dtype, ldy, tokens, workspace,
+                                             workspace_bytes, hip_stream))
+
+
+def sketch_linear_reconstruct(layer: int, W_hat_dev: int, hip_stream: int = 0) -> None:
+    _check(load_library().sketch_linear_reconstruct(layer, W_hat_dev, hip_stream))
+
+
+def sketch_linear_destroy(layer: int) -> None:
+    load_library().sketch_linear_destroy(layer)

@@ -1,0 +1,367 @@
+// Host side of the sketch-linear library: argument validation, the layout
+// plan (width metadata -> table offsets, Sec. 3.2 / 3.3 per-group widths),
+// re-encoding of the sketch states into order keys, and the C ABI.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "skl_internal.h"
+
+// ------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+void skl_set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+#define FAIL(code, ...)             \
+    do {                            \
+        skl_set_error(__VA_ARGS__); \
+        return (code);              \
+    } while (0)
+
+static inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- planning
+static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out)
+{
+    if (!d) FAIL(SKL_ERR_INVALID_ARG, "desc is NULL");
+    if (d->struct_size != sizeof(skl_desc_t))
+        FAIL(SKL_ERR_INVALID_ARG, "desc.struct_size is %u, expected %zu", d->struct_size, sizeof(skl_desc_t));
+    if (d->in_features == 0 || d->out_features == 0)
+        FAIL(SKL_ERR_INVALID_ARG, "in_features and out_features must be positive");
+    if (d->in_features > (1u << 30) || d->out_features > (1u << 30))
+        FAIL(SKL_ERR_UNSUPPORTED, "in_features / out_features above 2^30");
+    if (d->tile_in == 0 || d->tile_out == 0 || d->in_features % d->tile_in || d->out_features % d->tile_out)
+        FAIL(SKL_ERR_INVALID_ARG, "tile %ux%u does not divide the layer %ux%u", d->tile_in, d->tile_out,
+             d->in_features, d->out_features);
+    if ((uint64_t)d->tile_in * d->tile_out > (1ull << 24))
+        FAIL(SKL_ERR_INVALID_ARG, "group of %ux%u weights exceeds 2^24 addresses", d->tile_in, d->tile_out);
+    if (d->d < 1 || d->d > SKL_MAX_D) FAIL(SKL_ERR_INVALID_ARG, "d = %u sketch rows, must be 1..8", d->d);
+    if (d->query_mode != 0) FAIL(SKL_ERR_UNSUPPORTED, "query_mode %u is reserved", d->query_mode);
+    if (d->flags & ~1u) FAIL(SKL_ERR_INVALID_ARG, "unknown bits in flags: 0x%x", d->flags);
+    if (!d->hash_a || !d->hash_c || !d->group_width || !d->states)
+        FAIL(SKL_ERR_INVALID_ARG, "hash_a, hash_c, group_width and states must not be NULL");
+    for (uint32_t r = 0; r < d->d; ++r)
+        if (d->hash_a[r] >= (1u << 24) || d->hash_c[r] >= (1u << 24))
+            FAIL(SKL_ERR_INVALID_ARG, "hash parameters of row %u are not below 2^24", r);
+    const uint64_t n_groups = (uint64_t)(d->in_features / d->tile_in) * (d->out_features / d->tile_out);
+    uint64_t sum = 0;
+    for (uint64_t g = 0; g < n_groups; ++g) {
+        const uint32_t K = d->group_width[g];
+        if (K == 0 || K > 65535)
+            FAIL(SKL_ERR_INVALID_ARG, "group_width[%llu] = %u, must be 1..65535", (unsigned long long)g, K);
+        sum += K;
+    }
+    if (d->n_states != sum * d->d)
+        FAIL(SKL_ERR_INVALID_ARG, "n_states = %llu but d * sum(group_width) = %llu",
+             (unsigned long long)d->n_states, (unsigned long long)(sum * d->d));
+    if (d->n_states >= (1ull << 32)) FAIL(SKL_ERR_UNSUPPORTED, "more than 2^32 states in one layer");
+    for (uint64_t i = 0; i < d->n_states; ++i)
+        if ((d->states[i] & 0x7C00u) == 0x7C00u)
+            FAIL(SKL_ERR_NONFINITE, "states[%llu] = 0x%04x is NaN or infinite", (unsigned long long)i, d->states[i]);
+    *n_groups_out = n_groups;
+    return SKL_OK;
+}
+
+// Row-sketch plan.  Returns false when some width is too large for any block
+// layout (then the per-weight path is tried).
+static bool plan_rows(const skl_desc_t *d, skl_plan *P)
+{
+    skl_layer &L = P->L;
+    const uint32_t in = d->in_features;
+    std::vector<uint32_t> order(in);
+    std::iota(order.begin(), order.end(), 0u);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](uint32_t a, uint32_t b) { return d->group_width[a] < d->group_width[b]; });
+    P->bmeta.clear();
+    P->chan.clear();
+    uint64_t off16 = 0;
+    uint32_t max_table = 0;
+    static const uint32_t rs_options[4] = {9, 5, 3, 1};
+    uint32_t i = 0;
+    while (i < in) {
+        const uint32_t K = d->group_width[order[i]];
+        uint32_t e = i;
+        while (e < in && d->group_width[order[e]] == K) ++e;
+        uint32_t rs = 0;
+        for (uint32_t opt : rs_options)
+            if ((uint64_t)d->d * K * opt * 16u <= SKL_LDS_SOFT_TABLE_BYTES) { rs = opt; break; }
+        if (!rs) {
+            if ((uint64_t)d->d * K * 16u + 20480u > SKL_LDS_HARD_BYTES) return false;   // table + activation tile
+            rs = 1;
+        }
+        const uint32_t nb = rs == 1 ? 1 : rs - 1;
+        for (uint32_t s = i; s < e; s += 8 * nb) {
+            skl_block_meta bm{};
+            bm.table_off16 = (uint32_t)off16;
+            bm.K = K;
+            bm.rs = rs;
+            bm.nb = nb;
+            bm.chan_off = (uint32_t)P->chan.size();
+            for (uint32_t c = 0; c < 8 * nb; ++c)
+                P->chan.push_back(s + c < e ? order[s + c] : SKL_NO_CHANNEL);
+            const uint64_t words = (uint64_t)d->d * K * rs;
+            off16 += words;
+            if (off16 >= (1ull << 32)) return false;
+            max_table = std::max<uint32_t>(max_table, (uint32_t)(words * 16));
+            P->bmeta.push_back(bm);
+        }
+        i = e;
+    }
+    L.path = 1;
+    L.n_blocks = (uint32_t)P->bmeta.size();
+    L.n_packed = (uint32_t)P->chan.size();
+    L.n_units = L.n_blocks;
+    L.max_table_bytes = max_table;
+    L.table_bytes = off16 * 16;
+    L.n_otiles = (d->out_features + SKL_WG - 1) / SKL_WG;
+    // about three workgroups per CU on 256 CUs, split over blocks x output segments
+    uint32_t seg = (768 + L.n_blocks / 2) / L.n_blocks;
+    L.n_seg = std::min(std::max(seg, 1u), L.n_otiles);
+    return true;
+}
+
+static skl_status_t plan_tiles(const skl_desc_t *d, uint64_t n_groups, skl_plan *P)
+{
+    skl_layer &L = P->L;
+    P->gmeta.resize(n_groups);
+    uint64_t off = 0;
+    uint32_t max_K = 0;
+    for (uint64_t g = 0; g < n_groups; ++g) {
+        P->gmeta[g].key_off = (uint32_t)off;
+        P->gmeta[g].K = d->group_width[g];
+        off += (uint64_t)d->d * d->group_width[g];
+        max_K = std::max(max_K, d->group_width[g]);
+    }
+    if ((uint64_t)d->d * max_K * 2u + 16384u > SKL_LDS_HARD_BYTES)
+        FAIL(SKL_ERR_UNSUPPORTED, "a group table of %u rows x %u states does not fit in LDS", d->d, max_K);
+    L.path = 0;
+    L.n_jb = d->in_features / d->tile_in;
+    L.n_ob = d->out_features / d->tile_out;
+    L.max_K = max_K;
+    L.max_table_bytes = d->d * max_K * 2u;
+    L.table_bytes = off * 2;
+    const uint64_t noc = (d->tile_out + SKL_WG - 1) / SKL_WG;
+    uint64_t want = (1024 + n_groups * noc - 1) / (n_groups * noc);       // chunks per group
+    want = std::max<uint64_t>(1, std::min<uint64_t>(want, (d->tile_in + 7) / 8));
+    uint32_t rows = (uint32_t)((d->tile_in + want - 1) / want);
+    rows = std::min(std::max(rows, 1u), 512u);
+    L.jc_rows = rows;
+    L.n_jc = (d->tile_in + rows - 1) / rows;
+    if ((uint64_t)L.n_jb * L.n_jc > (1u << 20))
+        FAIL(SKL_ERR_UNSUPPORTED, "more than 2^20 partial sums per output");
+    L.n_units = L.n_jb * L.n_jc;
+    return SKL_OK;
+}
+
+skl_status_t skl_make_plan(const skl_desc_t *d, skl_plan *P)
+{
+    uint64_t n_groups = 0;
+    skl_status_t st = validate_desc(d, &n_groups);
+    if (st != SKL_OK) return st;
+    skl_layer &L = P->L;
+    L.in = d->in_features; L.out = d->out_features; L.tj = d->tile_in; L.to = d->tile_out; L.d = d->d;
+    for (uint32_t r = 0; r < d->d; ++r) { L.A[r] = d->hash_a[r]; L.C[r] = d->hash_c[r]; }
+    L.n_states = d->n_states;
+    const bool rows_ok = d->tile_in == 1 && d->tile_out == d->out_features && !(d->flags & 1u);
+    if (!(rows_ok && plan_rows(d, P))) {
+        st = plan_tiles(d, n_groups, P);
+        if (st != SKL_OK) return st;
+    }
+    // device layout: [scratch 4 KiB][metadata][channel list][tables], 256-byte aligned parts
+    uint64_t off = 4096;
+    if (L.path == 1) {
+        L.off_bmeta = off;  off = align_up(off + P->bmeta.size() * sizeof(skl_block_meta), 256);
+        L.off_chan = off;   off = align_up(off + P->chan.size() * sizeof(uint32_t), 256);
+        L.off_tables = off; off = align_up(off + L.table_bytes, 256);
+    } else {
+        L.off_gmeta = off;  off = align_up(off + P->gmeta.size() * sizeof(skl_group_meta), 256);
+        L.off_keys = off;   off = align_up(off + L.table_bytes + 16, 256);
+    }
+    P->dev_bytes = off;
+    return SKL_OK;
+}
+
+// -------------------------------------------------------------------- ABI
+extern "C" {
+
+const char *sketch_linear_last_error(void) { return g_err; }
+
+skl_status_t sketch_linear_device_bytes(const skl_desc_t *desc, uint64_t *bytes)
+{
+    if (!bytes) FAIL(SKL_ERR_INVALID_ARG, "bytes is NULL");
+    skl_plan P;
+    skl_status_t st = skl_make_plan(desc, &P);
+    if (st != SKL_OK) return st;
+    *bytes = P.dev_bytes;
+    return SKL_OK;
+}
+
+skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_t dev_bytes,
+                                  void *hip_stream, skl_layer_t **out_layer)
+{
+    if (!out_layer) FAIL(SKL_ERR_INVALID_ARG, "out_layer is NULL");
+    *out_layer = nullptr;
+    skl_plan P;
+    skl_status_t st = skl_make_plan(desc, &P);
+    if (st != SKL_OK) return st;
+    if (!dev_buf) FAIL(SKL_ERR_INVALID_ARG, "dev_buf is NULL");
+    if ((uintptr_t)dev_buf % 256) FAIL(SKL_ERR_INVALID_ARG, "dev_buf is not 256-byte aligned");
+    if (dev_bytes < P.dev_bytes)
+        FAIL(SKL_ERR_BUFFER_TOO_SMALL, "dev_buf holds %llu bytes, %llu needed", (unsigned long long)dev_bytes,
+             (unsigned long long)P.dev_bytes);
+
+    std::vector<uint8_t> img;
+    try {
+        img.assign(P.dev_bytes, 0);
+    } catch (const std::bad_alloc &) {
+        FAIL(SKL_ERR_INVALID_ARG, "out of host memory for a %llu-byte staging image", (unsigned long long)P.dev_bytes);
+    }
+    skl_layer &L = P.L;
+    if (L.path == 1) {
+        memcpy(img.data() + L.off_bmeta, P.bmeta.data(), P.bmeta.size() * sizeof(skl_block_meta));
+        memcpy(img.data() + L.off_chan, P.chan.data(), P.chan.size() * sizeof(uint32_t));
+        // state offset of every input channel (one group per channel)
+        std::vector<uint64_t> base(L.in + 1, 0);
+        for (uint32_t j = 0; j < L.in; ++j) base[j + 1] = base[j] + (uint64_t)L.d * desc->group_width[j];
+        uint16_t *tab = reinterpret_cast<uint16_t *>(img.data() + L.off_tables);
+        for (const skl_block_meta &bm : P.bmeta) {
+            uint16_t *t = tab + (uint64_t)bm.table_off16 * 8;
+            for (uint32_t c8 = 0; c8 < 8 * bm.nb; ++c8) {
+                const uint32_t ch = P.chan[bm.chan_off + c8];
+                const uint16_t *s = ch == SKL_NO_CHANNEL ? nullptr : desc->states + base[ch];
+                const uint32_t c = c8 / 8, i = c8 % 8;
+                for (uint32_t r = 0; r < L.d; ++r)
+                    for (uint32_t k = 0; k < bm.K; ++k) {
+                        const uint16_t key = s ? skl_key_of_half(s[(uint64_t)r * bm.K + k]) : (uint16_t)1;
+                        t[(((uint64_t)r * bm.K + k) * bm.rs + c) * 8 + i] = key;
+                    }
+            }
+        }
+    } else {
+        memcpy(img.data() + L.off_gmeta, P.gmeta.data(), P.gmeta.size() * sizeof(skl_group_meta));
+        uint16_t *keys = reinterpret_cast<uint16_t *>(img.data() + L.off_keys);
+        for (uint64_t i = 0; i < desc->n_states; ++i) keys[i] = skl_key_of_half(desc->states[i]);
+    }
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipMemcpyAsync(dev_buf, img.data(), P.dev_bytes, hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) FAIL(SKL_ERR_HIP, "copy of the layer image failed: %s", hipGetErrorString(e));
+
+    skl_layer *out = new (std::nothrow) skl_layer(L);
+    if (!out) FAIL(SKL_ERR_INVALID_ARG, "out of host memory");
+    out->dev = static_cast<uint8_t *>(dev_buf);
+    out->dev_bytes = P.dev_bytes;
+    *out_layer = out;
+    return SKL_OK;
+}
+
+void sketch_linear_destroy(skl_layer_t *layer) { delete layer; }
+
+skl_status_t sketch_linear_info(const skl_layer_t *L, skl_info_t *info)
+{
+    if (!L || !info) FAIL(SKL_ERR_INVALID_ARG, "layer or info is NULL");
+    if (info->struct_size != sizeof(skl_info_t)) FAIL(SKL_ERR_INVALID_ARG, "info.struct_size mismatch");
+    info->path = L->path;
+    info->n_units = L->n_units;
+    info->max_table_bytes = L->max_table_bytes;
+    info->table_bytes = L->table_bytes;
+    info->n_weights = (uint64_t)L->in * L->out;
+    info->n_states = L->n_states;
+    return SKL_OK;
+}
+
+skl_status_t sketch_linear_workspace_bytes(const skl_layer_t *L, uint32_t op, uint32_t n, uint64_t *bytes)
+{
+    if (!L || !bytes) FAIL(SKL_ERR_INVALID_ARG, "layer or bytes is NULL");
+    if (op == 0) {
+        if (n < 1 || n > 16) FAIL(SKL_ERR_INVALID_ARG, "batch = %u, must be 1..16", n);
+        *bytes = skl_gemv_workspace_bytes(L, n);
+    } else if (op == 1) {
+        if (n < 1) FAIL(SKL_ERR_INVALID_ARG, "tokens must be positive");
+        *bytes = skl_gemm_workspace_bytes(L, n);
+    } else {
+        FAIL(SKL_ERR_INVALID_ARG, "op = %u, must be 0 (gemv) or 1 (gemm)", op);
+    }
+    return SKL_OK;
+}
+
+static bool overlap(const void *a, uint64_t na, const void *b, uint64_t nb)
+{
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+static uint32_t dtype_size(skl_dtype_t t) { return t == SKL_F32 ? 4 : 2; }
+
+static skl_status_t check_io(const skl_layer_t *L, const void *x, uint32_t ldx, uint32_t x_size, const void *y,
+                             uint32_t ldy, uint32_t y_size, uint32_t rows, const void *ws, uint64_t ws_bytes,
+                             uint64_t ws_need)
+{
+    if (!x || !y) FAIL(SKL_ERR_INVALID_ARG, "activation or output pointer is NULL");
+    if ((uintptr_t)x % 16 || (uintptr_t)y % 16) FAIL(SKL_ERR_INVALID_ARG, "activation/output pointer not 16-byte aligned");
+    if (ldx < L->in) FAIL(SKL_ERR_INVALID_ARG, "ldx = %u is smaller than in_features = %u", ldx, L->in);
+    if (ldy < L->out) FAIL(SKL_ERR_INVALID_ARG, "ldy = %u is smaller than out_features = %u", ldy, L->out);
+    const uint64_t xb = ((uint64_t)(rows - 1) * ldx + L->in) * x_size;
+    const uint64_t yb = ((uint64_t)(rows - 1) * ldy + L->out) * y_size;
+    if (overlap(x, xb, y, yb)) FAIL(SKL_ERR_INVALID_ARG, "input and output overlap");
+    if (ws_need) {
+        if (!ws) FAIL(SKL_ERR_INVALID_ARG, "workspace is NULL (%llu bytes needed)", (unsigned long long)ws_need);
+        if ((uintptr_t)ws % 16) FAIL(SKL_ERR_INVALID_ARG, "workspace not 16-byte aligned");
+        if (ws_bytes < ws_need)
+            FAIL(SKL_ERR_BUFFER_TOO_SMALL, "workspace holds %llu bytes, %llu needed", (unsigned long long)ws_bytes,
+                 (unsigned long long)ws_need);
+        if (overlap(ws, ws_need, y, yb) || overlap(ws, ws_need, x, xb))
+            FAIL(SKL_ERR_INVALID_ARG, "workspace overlaps input or output");
+    }
+    return SKL_OK;
+}
+
+skl_status_t sketch_linear_gemv(const skl_layer_t *L, const void *x, skl_dtype_t x_dt, uint32_t ldx, void *y,
+                                skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *ws, uint64_t ws_bytes,
+                                void *stream)
+{
+    if (!L) FAIL(SKL_ERR_INVALID_ARG, "layer is NULL");
+    if (batch < 1 || batch > 16) FAIL(SKL_ERR_INVALID_ARG, "batch = %u, must be 1..16", batch);
+    if (x_dt != SKL_F16) FAIL(SKL_ERR_UNSUPPORTED, "gemv activations must be binary16");
+    if (y_dt != SKL_F16 && y_dt != SKL_F32) FAIL(SKL_ERR_UNSUPPORTED, "gemv output must be binary16 or float32");
+    skl_status_t st = check_io(L, x, ldx, 2, y, ldy, dtype_size(y_dt), batch, ws, ws_bytes,
+                               skl_gemv_workspace_bytes(L, batch));
+    if (st != SKL_OK) return st;
+    return skl_launch_gemv(L, x, ldx, y, y_dt, ldy, batch, ws, stream);
+}
+
+skl_status_t sketch_linear_gemm(const skl_layer_t *L, const void *X, skl_dtype_t x_dt, uint32_t ldx, void *Y,
+                                skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, void *ws, uint64_t ws_bytes,
+                                void *stream)
+{
+    if (!L) FAIL(SKL_ERR_INVALID_ARG, "layer is NULL");
+    if (tokens < 1) FAIL(SKL_ERR_INVALID_ARG, "tokens must be positive");
+    if (tokens > (1u << 24)) FAIL(SKL_ERR_UNSUPPORTED, "more than 2^24 tokens in one call");
+    if (x_dt != SKL_F16 && x_dt != SKL_BF16) FAIL(SKL_ERR_UNSUPPORTED, "gemm activations must be bfloat16 or binary16");
+    if (y_dt != SKL_F16 && y_dt != SKL_BF16 && y_dt != SKL_F32) FAIL(SKL_ERR_INVALID_ARG, "bad output dtype");
+    skl_status_t st = check_io(L, X, ldx, 2, Y, ldy, dtype_size(y_dt), tokens, ws, ws_bytes,
+                               skl_gemm_workspace_bytes(L, tokens));
+    if (st != SKL_OK) return st;
+    return skl_launch_gemm(L, X, x_dt, ldx, Y, y_dt, ldy, tokens, ws, stream);
+}
+
+skl_status_t sketch_linear_reconstruct(const skl_layer_t *L, uint16_t *W_hat_dev, void *stream)
+{
+    if (!L || !W_hat_dev) FAIL(SKL_ERR_INVALID_ARG, "layer or W_hat_dev is NULL");
+    if ((uintptr_t)W_hat_dev % 16) FAIL(SKL_ERR_INVALID_ARG, "W_hat_dev not 16-byte aligned");
+    return skl_launch_reconstruct(L, W_hat_dev, stream);
+}
+
+}  // extern "C"

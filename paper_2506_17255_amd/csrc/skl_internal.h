@@ -1,0 +1,94 @@
+// Internal declarations shared by the host side (skl_host.cpp) and the
+// kernels (skl_kernels.hip) of the sketch-linear library.  Not installed.
+#pragma once
+
+#include <stdint.h>
+#include <vector>
+
+#include "sketch_linear.h"
+
+#define SKL_MAX_D 8
+#define SKL_WG 256            // threads per workgroup: 4 wavefronts of 64
+#define SKL_NO_CHANNEL 0xFFFFFFFFu
+
+// LDS budgets.  A CU of gfx950 has 160 KiB of LDS; keeping a workgroup's
+// table at or below the soft limit lets three workgroups share a CU.
+#define SKL_LDS_SOFT_TABLE_BYTES 50688u
+#define SKL_LDS_HARD_BYTES 163840u
+
+// ---- path 0: 2-D groups, one hash evaluation per weight and sketch row ----
+struct skl_group_meta {
+    uint32_t key_off;   // first key of the group, in 16-bit units from the key base
+    uint32_t K;         // states per sketch row (Sec. 3.3: K may differ per group)
+};
+
+// ---- path 1: row sketches (tile_in = 1, tile_out = d_out) -------------------
+// Input channels are sorted by width and cut into blocks of 8*nb channels that
+// share one width K.  A block's table is laid out [r][k][rs] in 16-byte words:
+// word (r*K + k)*rs + c holds the keys of channels 8c..8c+7 of the block for
+// state (r,k); rs is odd so that consecutive k fall into different LDS bank
+// groups, and nb = rs - 1 words per state row are used (nb = 1 when rs = 1).
+struct skl_block_meta {
+    uint32_t table_off16;  // table start, in 16-byte words from the table base
+    uint32_t K;
+    uint32_t rs;           // words per state row: 1, 3, 5 or 9
+    uint32_t nb;           // used words per state row (8*nb channels per block)
+    uint32_t chan_off;     // first entry of the block in the channel list
+                           // (= first packed activation column of the block)
+    uint32_t pad[3];
+};
+
+struct skl_layer {
+    uint32_t in = 0, out = 0, tj = 0, to = 0, d = 0;
+    uint32_t A[SKL_MAX_D] = {0}, C[SKL_MAX_D] = {0};
+    uint32_t path = 0;
+    uint8_t *dev = nullptr;
+    uint64_t dev_bytes = 0;
+    uint64_t n_states = 0;
+    uint64_t table_bytes = 0;
+    uint32_t max_table_bytes = 0;   // largest per-workgroup table
+    uint32_t n_units = 0;           // partial sums per output in gemv
+
+    // path 0
+    uint32_t n_jb = 0, n_ob = 0, max_K = 0;
+    uint32_t jc_rows = 0, n_jc = 0; // a group's tile_in rows are cut into n_jc chunks
+    uint64_t off_gmeta = 0, off_keys = 0;
+
+    // path 1
+    uint32_t n_blocks = 0;
+    uint32_t n_packed = 0;          // channel-list length = sum of 8*nb over blocks
+    uint32_t n_otiles = 0, n_seg = 0;
+    uint64_t off_bmeta = 0, off_chan = 0, off_tables = 0;
+};
+
+// The host-side plan: everything create() copies to the device.
+struct skl_plan {
+    skl_layer L;
+    uint64_t dev_bytes = 0;
+    std::vector<skl_group_meta> gmeta;
+    std::vector<skl_block_meta> bmeta;
+    std::vector<uint32_t> chan;
+};
+
+// error text of the calling thread
+void skl_set_error(const char *fmt, ...);
+
+// validation + planning (host only); fills `plan` without touching `states`
+// beyond the finiteness check
+skl_status_t skl_make_plan(const skl_desc_t *desc, skl_plan *plan);
+
+// order key of a binary16 bit pattern: magnitude first, clear sign bit wins
+static inline uint16_t skl_key_of_half(uint16_t b)
+{
+    return (uint16_t)(((b & 0x7FFFu) << 1) | (1u - (b >> 15)));
+}
+
+// ---- launchers implemented in skl_kernels.hip (all enqueue only) -----------
+skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *stream);
+skl_status_t skl_launch_gemv(const skl_layer *L, const void *x, uint32_t ldx, void *y,
+                             skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *ws, void *stream);
+skl_status_t skl_launch_gemm(const skl_layer *L, const void *X, skl_dtype_t x_dt, uint32_t ldx,
+                             void *Y, skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, void *ws,
+                             void *stream);
+uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch);
+uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens);

@@ -1,0 +1,810 @@
+// HIP kernels (gfx950 only) of the sketch-linear library and their launchers.
+//
+// Common ground of every kernel here (Sec. 3.1 of the paper):
+//   select  Eq. 3   t = (A_r * a + C_r) mod 2^24,  k = floor(t * K / 2^24)
+//                   -> one 24-bit multiply-add and one 24-bit multiply-high
+//   gather          the d candidate states come from an LDS-resident copy of
+//                   the group's sketch table
+//   query   Eq. 5   the states are stored as 16-bit order keys
+//                   key = magnitude << 1 | (sign bit clear), so the AbsMaxMin
+//                   query is a plain unsigned 16-bit maximum (two weights per
+//                   packed instruction)
+//   decode          the winning key is turned back into binary16 with the
+//                   sign bit inverted: -w = (key >> 1) | (key << 15 & 0x8000);
+//                   the activations are negated once when they are staged, so
+//                   every product x * w keeps its sign and value.
+#include <hip/hip_runtime.h>
+
+#include "skl_internal.h"
+
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+
+extern __shared__ uint4 smem[];
+
+// --------------------------------------------------------------- helpers
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    ushort2v m = __builtin_elementwise_max(__builtin_bit_cast(ushort2v, a), __builtin_bit_cast(ushort2v, b));
+    return __builtin_bit_cast(uint32_t, m);
+}
+
+__device__ __forceinline__ uint4 pk_max_u16x8(uint4 a, uint4 b)
+{
+    return make_uint4(pk_max_u16(a.x, b.x), pk_max_u16(a.y, b.y), pk_max_u16(a.z, b.z), pk_max_u16(a.w, b.w));
+}
+
+// two keys -> two binary16 values with inverted sign bits
+__device__ __forceinline__ uint32_t keys_to_neg_half2(uint32_t k)
+{
+    return ((k >> 1) & 0x7FFF7FFFu) | ((k << 15) & 0x80008000u);
+}
+
+__device__ __forceinline__ uint4 keys_to_neg_half8(uint4 k)
+{
+    return make_uint4(keys_to_neg_half2(k.x), keys_to_neg_half2(k.y), keys_to_neg_half2(k.z), keys_to_neg_half2(k.w));
+}
+
+// Eq. 3: index inside a sketch row of width K; Kq = K << 8 (< 2^24).  Only the
+// low 24 bits of t count, so t may be kept as a wrapping 32-bit number.
+__device__ __forceinline__ uint32_t select_index(uint32_t t, uint32_t Kq)
+{
+    return (uint32_t)(((uint64_t)(t & 0xFFFFFFu) * (uint64_t)(Kq & 0xFFFFFFu)) >> 32);
+}
+
+__device__ __forceinline__ float dot2_acc(uint32_t w2, uint32_t x2, float acc)
+{
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, w2), __builtin_bit_cast(half2v, x2), acc, false);
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, h);
+}
+
+__device__ __forceinline__ uint16_t float_to_half_bits(float f)
+{
+    return __builtin_bit_cast(uint16_t, (_Float16)f);   // round to nearest even
+}
+
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);                                           // nearest even
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ void store_out(void *y, uint32_t dt, size_t idx, float v)
+{
+    if (dt == SKL_F32) static_cast<float *>(y)[idx] = v;
+    else if (dt == SKL_F16) static_cast<uint16_t *>(y)[idx] = float_to_half_bits(v);
+    else static_cast<uint16_t *>(y)[idx] = float_to_bf16_bits(v);
+}
+
+// activation element -> binary16 bits with the sign inverted
+__device__ __forceinline__ uint16_t load_neg_half(const uint16_t *X, uint32_t x_dt, size_t idx)
+{
+    uint16_t b = X[idx];
+    if (x_dt == SKL_BF16) b = float_to_half_bits(__builtin_bit_cast(float, (uint32_t)b << 16));
+    return b ^ 0x8000u;
+}
+
+struct HashArgs {
+    uint32_t A[SKL_MAX_D];
+    uint32_t C[SKL_MAX_D];
+};
+
+// ========================================================================
+// Path 1: row sketches.  One sketch per input channel over all d_out outputs,
+// so the state index of (j, o) depends on o and on the channel's width only.
+// ========================================================================
+struct RowArgs {
+    HashArgs h;
+    const skl_block_meta *bmeta;
+    const uint32_t *chan;
+    const uint4 *tables;
+    uint32_t in, out, n_blocks, n_otiles, n_seg;
+};
+
+__device__ __forceinline__ void stage_table(uint4 *dst, const uint4 *src, uint32_t n16)
+{
+    for (uint32_t i = threadIdx.x; i < n16; i += SKL_WG) dst[i] = src[i];
+}
+
+// word offsets (r*K + k_r(o)) * rs of output channel o in a block table
+template <int D>
+__device__ __forceinline__ void row_offsets(const HashArgs &h, uint32_t o, uint32_t K, uint32_t rs, uint32_t (&off)[D])
+{
+    const uint32_t Kq = K << 8;
+#pragma unroll
+    for (int r = 0; r < D; ++r) {
+        const uint32_t t = __umul24(h.A[r], o) + h.C[r];
+        off[r] = (r * K + select_index(t, Kq)) * rs;
+    }
+}
+
+// query for 8 consecutive channels of the block: word c of every row
+template <int D>
+__device__ __forceinline__ uint4 row_query8(const uint4 *tab, const uint32_t (&off)[D], uint32_t c)
+{
+    uint4 m = tab[off[0] + c];
+#pragma unroll
+    for (int r = 1; r < D; ++r) m = pk_max_u16x8(m, tab[off[r] + c]);
+    return m;
+}
+
+// ---- decode GEMV, batch 1: lanes along outputs, packed dot products ----
+template <int D, int RS>
+__device__ __forceinline__ void row_gemv1_body(const RowArgs &p, const skl_block_meta &bm, const uint4 *tab,
+                                               const uint4 *xs, float *partial_row)
+{
+    constexpr int NB = RS == 1 ? 1 : RS - 1;
+    uint4 xr[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) xr[c] = xs[c];
+    const uint32_t seg = blockIdx.y;
+    const uint32_t lo = (uint32_t)(((uint64_t)seg * p.n_otiles) / p.n_seg);
+    const uint32_t hi = (uint32_t)(((uint64_t)(seg + 1) * p.n_otiles) / p.n_seg);
+    for (uint32_t tile = lo; tile < hi; ++tile) {
+        const uint32_t o = tile * SKL_WG + threadIdx.x;
+        if (o < p.out) {
+            uint32_t off[D];
+            row_offsets<D>(p.h, o, bm.K, RS, off);
+            float acc = 0.f;
+#pragma unroll
+            for (int c = 0; c < NB; ++c) {
+                const uint4 w = keys_to_neg_half8(row_query8<D>(tab, off, c));
+                acc = dot2_acc(w.x, xr[c].x, acc);
+                acc = dot2_acc(w.y, xr[c].y, acc);
+                acc = dot2_acc(w.z, xr[c].z, acc);
+                acc = dot2_acc(w.w, xr[c].w, acc);
+            }
+            partial_row[o] = acc;
+        }
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(SKL_WG) void k_row_gemv1(RowArgs p, const uint16_t *__restrict__ x,
+                                                       float *__restrict__ partial)
+{
+    const skl_block_meta bm = p.bmeta[blockIdx.x];
+    const uint32_t n16 = D * bm.K * bm.rs;
+    stage_table(smem, p.tables + bm.table_off16, n16);
+    uint16_t *xs = reinterpret_cast<uint16_t *>(smem + n16);
+    if (threadIdx.x < 8 * bm.nb) {
+        const uint32_t ch = p.chan[bm.chan_off + threadIdx.x];
+        xs[threadIdx.x] = ch != SKL_NO_CHANNEL ? (uint16_t)(x[ch] ^ 0x8000u) : (uint16_t)0;
+    }
+    __syncthreads();
+    float *prow = partial + (size_t)blockIdx.x * p.out;
+    const uint4 *xs4 = reinterpret_cast<const uint4 *>(xs);
+    switch (bm.rs) {
+    case 9: row_gemv1_body<D, 9>(p, bm, smem, xs4, prow); break;
+    case 5: row_gemv1_body<D, 5>(p, bm, smem, xs4, prow); break;
+    case 3: row_gemv1_body<D, 3>(p, bm, smem, xs4, prow); break;
+    default: row_gemv1_body<D, 1>(p, bm, smem, xs4, prow); break;
+    }
+}
+
+// ---- decode GEMV, batch 2..16: reconstructed weights feed the matrix cores.
+// One 32x32x16 MFMA per 32 outputs x 16 channels; rows of the A operand are
+// the batch (rows >= batch are zero).
+#define XS_PAD 8   // halfs of padding per activation row in LDS
+
+template <int D, int RS>
+__device__ __forceinline__ void row_gemvN_body(const RowArgs &p, const skl_block_meta &bm, const uint4 *tab,
+                                               const uint16_t *xs, uint32_t batch, float *partial_blk)
+{
+    constexpr int NB = RS == 1 ? 1 : RS - 1;
+    constexpr int NS = (NB + 1) / 2;
+    constexpr int XS = 8 * NB + XS_PAD;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t n = lane & 31, q = lane >> 5;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    uint4 areg[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const uint32_t c = 2 * s + q;
+        areg[s] = (NB > 1 || c < NB) ? *reinterpret_cast<const uint4 *>(xs + n * XS + c * 8) : zero;
+    }
+    const uint32_t seg = blockIdx.y;
+    const uint32_t o_lo = (uint32_t)(((uint64_t)seg * p.n_otiles) / p.n_seg) * SKL_WG;
+    const uint32_t o_hi = min((uint32_t)(((uint64_t)(seg + 1) * p.n_otiles) / p.n_seg) * SKL_WG, p.out);
+    for (uint32_t og = o_lo + wave * 32; og < o_hi; og += 128) {
+        const uint32_t o = og + n;
+        uint32_t off[D];
+        row_offsets<D>(p.h, min(o, p.out - 1), bm.K, RS, off);
+        float16v acc = {0.f};
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const uint32_t c = 2 * s + q;
+            uint4 b = zero;
+            if (NB > 1 || c < NB) b = keys_to_neg_half8(row_query8<D>(tab, off, NB > 1 ? c : 0));
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, areg[s]),
+                                                          __builtin_bit_cast(half8v, b), acc, 0, 0, 0);
+        }
+        if (o < p.out) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t m = (i >> 2) * 8 + q * 4 + (i & 3);   // row of the 32x32 result held in acc[i]
+                if (m < batch) partial_blk[(size_t)m * p.out + o] = acc[i];
+            }
+        }
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(SKL_WG) void k_row_gemvN(RowArgs p, const uint16_t *__restrict__ x, uint32_t ldx,
+                                                       uint32_t batch, float *__restrict__ partial)
+{
+    const skl_block_meta bm = p.bmeta[blockIdx.x];
+    const uint32_t n16 = D * bm.K * bm.rs;
+    stage_table(smem, p.tables + bm.table_off16, n16);
+    uint16_t *xs = reinterpret_cast<uint16_t *>(smem + n16);
+    const uint32_t nch = 8 * bm.nb, XS = nch + XS_PAD;
+    for (uint32_t i = threadIdx.x; i < 32 * nch; i += SKL_WG) {
+        const uint32_t b = i / nch, c = i - b * nch;
+        uint16_t v = 0;
+        if (b < batch) {
+            const uint32_t ch = p.chan[bm.chan_off + c];
+            if (ch != SKL_NO_CHANNEL) v = x[(size_t)b * ldx + ch] ^ 0x8000u;
+        }
+        xs[b * XS + c] = v;
+    }
+    __syncthreads();
+    float *pblk = partial + (size_t)blockIdx.x * batch * p.out;
+    switch (bm.rs) {
+    case 9: row_gemvN_body<D, 9>(p, bm, smem, xs, batch, pblk); break;
+    case 5: row_gemvN_body<D, 5>(p, bm, smem, xs, batch, pblk); break;
+    case 3: row_gemvN_body<D, 3>(p, bm, smem, xs, batch, pblk); break;
+    default: row_gemvN_body<D, 1>(p, bm, smem, xs, batch, pblk); break;
+    }
+}
+
+// ---- reconstruct (diagnostic): the same table, offsets and query ----------
+template <int D, int RS>
+__device__ __forceinline__ void row_reconstruct_body(const RowArgs &p, const skl_block_meta &bm, const uint4 *tab,
+                                                     const uint32_t *chs, uint16_t *W_hat)
+{
+    constexpr int NB = RS == 1 ? 1 : RS - 1;
+    const uint32_t seg = blockIdx.y;
+    const uint32_t lo = (uint32_t)(((uint64_t)seg * p.n_otiles) / p.n_seg);
+    const uint32_t hi = (uint32_t)(((uint64_t)(seg + 1) * p.n_otiles) / p.n_seg);
+    for (uint32_t tile = lo; tile < hi; ++tile) {
+        const uint32_t o = tile * SKL_WG + threadIdx.x;
+        if (o >= p.out) continue;
+        uint32_t off[D];
+        row_offsets<D>(p.h, o, bm.K, RS, off);
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+            const uint4 w = keys_to_neg_half8(row_query8<D>(tab, off, c));
+            const uint32_t v[4] = {w.x ^ 0x80008000u, w.y ^ 0x80008000u, w.z ^ 0x80008000u, w.w ^ 0x80008000u};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t ch = chs[c * 8 + i];
+                if (ch != SKL_NO_CHANNEL) W_hat[(size_t)ch * p.out + o] = (uint16_t)(v[i >> 1] >> ((i & 1) * 16));
+            }
+        }
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(SKL_WG) void k_row_reconstruct(RowArgs p, uint16_t *__restrict__ W_hat)
+{
+    const skl_block_meta bm = p.bmeta[blockIdx.x];
+    const uint32_t n16 = D * bm.K * bm.rs;
+    stage_table(smem, p.tables + bm.table_off16, n16);
+    uint32_t *chs = reinterpret_cast<uint32_t *>(smem + n16);
+    if (threadIdx.x < 8 * bm.nb) chs[threadIdx.x] = p.chan[bm.chan_off + threadIdx.x];
+    __syncthreads();
+    switch (bm.rs) {
+    case 9: row_reconstruct_body<D, 9>(p, bm, smem, chs, W_hat); break;
+    case 5: row_reconstruct_body<D, 5>(p, bm, smem, chs, W_hat); break;
+    case 3: row_reconstruct_body<D, 3>(p, bm, smem, chs, W_hat); break;
+    default: row_reconstruct_body<D, 1>(p, bm, smem, chs, W_hat); break;
+    }
+}
+
+// ---- prefill GEMM ----------------------------------------------------------
+// Pre-pass: activations -> binary16, negated, columns in channel-list order
+// (pad columns are zero), so that the main kernel reads 16-byte words.
+__global__ __launch_bounds__(SKL_WG) void k_pack_activations(const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
+                                                              const uint32_t *__restrict__ chan, uint32_t n_packed,
+                                                              uint16_t *__restrict__ Xp)
+{
+    const uint32_t t = blockIdx.x;
+    const uint32_t pcol = blockIdx.y * SKL_WG + threadIdx.x;
+    if (pcol >= n_packed) return;
+    const uint32_t ch = chan[pcol];
+    Xp[(size_t)t * n_packed + pcol] = ch != SKL_NO_CHANNEL ? load_neg_half(X, x_dt, (size_t)t * ldx + ch) : (uint16_t)0;
+}
+
+#define GEMM_MT 128
+#define GEMM_NT 128
+#define GEMM_AS 72   // halfs per staged activation row: 64 + 8 (row stride of 9 words)
+
+template <int D, int RS>
+__device__ __forceinline__ void row_gemm_block(const uint4 *tab, const uint16_t *As, const uint32_t (&off)[2][D],
+                                               uint32_t wm, uint32_t n, uint32_t q, float16v (&acc)[2][2])
+{
+    constexpr int NB = RS == 1 ? 1 : RS - 1;
+    constexpr int NS = (NB + 1) / 2;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const uint32_t c = 2 * s + q;
+        uint4 a[2], b[2];
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            a[f] = zero;
+            b[f] = zero;
+            if (NB > 1 || c < NB) {
+                a[f] = *reinterpret_cast<const uint4 *>(As + (wm * 64 + f * 32 + n) * GEMM_AS + c * 8);
+                b[f] = keys_to_neg_half8(row_query8<D>(tab, off[f], NB > 1 ? c : 0));
+            }
+        }
+#pragma unroll
+        for (int mf = 0; mf < 2; ++mf)
+#pragma unroll
+            for (int nf = 0; nf < 2; ++nf)
+                acc[mf][nf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a[mf]),
+                                                                      __builtin_bit_cast(half8v, b[nf]), acc[mf][nf], 0, 0, 0);
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(SKL_WG) void k_row_gemm(RowArgs p, const uint16_t *__restrict__ Xp, uint32_t tokens,
+                                                      uint32_t n_packed, void *__restrict__ Y, uint32_t y_dt,
+                                                      uint32_t ldy, uint32_t table_words)
+{
+    uint4 *tab = smem;
+    uint16_t *As = reinterpret_cast<uint16_t *>(smem + table_words);
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t wm = wave >> 1, wn = wave & 1;
+    const uint32_t n = lane & 31, q = lane >> 5;
+    const uint32_t t0 = blockIdx.y * GEMM_MT, o0 = blockIdx.x * GEMM_NT;
+    float16v acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = (float16v){0.f};
+    uint32_t off[2][D];
+    uint32_t K_prev = 0, rs_prev = 0;
+    for (uint32_t blk = 0; blk < p.n_blocks; ++blk) {
+        const skl_block_meta bm = p.bmeta[blk];
+        __syncthreads();
+        stage_table(tab, p.tables + bm.table_off16, D * bm.K * bm.rs);
+        const uint32_t nb = bm.nb;
+        for (uint32_t i = threadIdx.x; i < GEMM_MT * nb; i += SKL_WG) {
+            const uint32_t r = i / nb, c = i - r * nb;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (t0 + r < tokens)
+                v = *reinterpret_cast<const uint4 *>(Xp + (size_t)(t0 + r) * n_packed + bm.chan_off + c * 8);
+            *reinterpret_cast<uint4 *>(As + r * GEMM_AS + c * 8) = v;
+        }
+        __syncthreads();
+        if (bm.K != K_prev || bm.rs != rs_prev) {
+#pragma unroll
+            for (int f = 0; f < 2; ++f)
+                row_offsets<D>(p.h, min(o0 + wn * 64 + f * 32 + n, p.out - 1), bm.K, bm.rs, off[f]);
+            K_prev = bm.K;
+            rs_prev = bm.rs;
+        }
+        switch (bm.rs) {
+        case 9: row_gemm_block<D, 9>(tab, As, off, wm, n, q, acc); break;
+        case 5: row_gemm_block<D, 5>(tab, As, off, wm, n, q, acc); break;
+        case 3: row_gemm_block<D, 3>(tab, As, off, wm, n, q, acc); break;
+        default: row_gemm_block<D, 1>(tab, As, off, wm, n, q, acc); break;
+        }
+    }
+#pragma unroll
+    for (int mf = 0; mf < 2; ++mf)
+#pragma unroll
+        for (int nf = 0; nf < 2; ++nf) {
+            const uint32_t o = o0 + wn * 64 + nf * 32 + n;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t t = t0 + wm * 64 + mf * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
+                if (t < tokens && o < p.out) store_out(Y, y_dt, (size_t)t * ldy + o, acc[mf][nf][i]);
+            }
+        }
+}
+
+// ========================================================================
+// Path 0: 2-D groups, one hash evaluation per weight and sketch row.
+// A workgroup owns (group, chunk of the group's input rows, 256 outputs).
+// ========================================================================
+struct TileArgs {
+    HashArgs h;
+    const skl_group_meta *gmeta;
+    const uint16_t *keys;
+    uint32_t in, out, tj, to, n_ob, jc_rows, n_jc;
+};
+
+__device__ __forceinline__ void stage_keys(uint16_t *dst, const uint16_t *src, uint32_t n)
+{
+    for (uint32_t i = threadIdx.x; i < n; i += SKL_WG) dst[i] = src[i];
+}
+
+struct TileUnit {
+    uint32_t g, jb, ob, jc, j_lo, j_hi, K, key_off;
+};
+
+__device__ __forceinline__ TileUnit tile_unit(const TileArgs &p, uint32_t unit)
+{
+    TileUnit u;
+    u.g = unit / p.n_jc;
+    u.jc = unit - u.g * p.n_jc;
+    u.jb = u.g / p.n_ob;
+    u.ob = u.g - u.jb * p.n_ob;
+    u.j_lo = u.jc * p.jc_rows;
+    u.j_hi = min(u.j_lo + p.jc_rows, p.tj);
+    const skl_group_meta gm = p.gmeta[u.g];
+    u.K = gm.K;
+    u.key_off = gm.key_off;
+    return u;
+}
+
+// running hash state of one lane: t_r for the current address, advanced by one
+// input row (tile_out addresses) per step
+template <int D>
+struct TileHash {
+    uint32_t t[D], step[D];
+    __device__ __forceinline__ void init(const HashArgs &h, uint32_t a0, uint32_t to)
+    {
+#pragma unroll
+        for (int r = 0; r < D; ++r) {
+            t[r] = __umul24(h.A[r], a0) + h.C[r];
+            step[r] = __umul24(h.A[r], to);
+        }
+    }
+    __device__ __forceinline__ uint16_t query(const uint16_t *tab, uint32_t K, uint32_t Kq)
+    {
+        uint16_t m = 0;
+#pragma unroll
+        for (int r = 0; r < D; ++r) {
+            const uint16_t k = tab[r * K + select_index(t[r], Kq)];
+            m = k > m ? k : m;
+            t[r] += step[r];
+        }
+        return m;
+    }
+};
+
+__device__ __forceinline__ uint16_t key_to_half_bits(uint16_t k)
+{
+    return (uint16_t)((k >> 1) | ((~k & 1u) << 15));
+}
+
+template <int D>
+__global__ __launch_bounds__(SKL_WG) void k_tile_reconstruct(TileArgs p, uint16_t *__restrict__ W_hat)
+{
+    uint16_t *tab = reinterpret_cast<uint16_t *>(smem);
+    const TileUnit u = tile_unit(p, blockIdx.x);
+    stage_keys(tab, p.keys + u.key_off, D * u.K);
+    __syncthreads();
+    const uint32_t ol = blockIdx.y * SKL_WG + threadIdx.x;
+    if (ol >= p.to) return;
+    TileHash<D> th;
+    th.init(p.h, u.j_lo * p.to + ol, p.to);
+    const uint32_t Kq = u.K << 8;
+    for (uint32_t jl = u.j_lo; jl < u.j_hi; ++jl) {
+        const uint16_t k = th.query(tab, u.K, Kq);
+        W_hat[(size_t)(u.jb * p.tj + jl) * p.out + u.ob * p.to + ol] = key_to_half_bits(k);
+    }
+}
+
+// decode GEMV for BT batch rows per pass (grid z walks the batch)
+template <int D, int BT>
+__global__ __launch_bounds__(SKL_WG) void k_tile_gemv(TileArgs p, const uint16_t *__restrict__ x, uint32_t ldx,
+                                                      uint32_t batch, float *__restrict__ partial, uint32_t key_words)
+{
+    uint16_t *tab = reinterpret_cast<uint16_t *>(smem);
+    float *xs = reinterpret_cast<float *>(smem + key_words);   // [BT][jc_rows]
+    const TileUnit u = tile_unit(p, blockIdx.x);
+    stage_keys(tab, p.keys + u.key_off, D * u.K);
+    const uint32_t b0 = blockIdx.z * BT;
+    const uint32_t rows = u.j_hi - u.j_lo;
+    for (uint32_t i = threadIdx.x; i < BT * rows; i += SKL_WG) {
+        const uint32_t b = i / rows, jr = i - b * rows;
+        xs[b * p.jc_rows + jr] =
+            b0 + b < batch ? half_bits_to_float(x[(size_t)(b0 + b) * ldx + u.jb * p.tj + u.j_lo + jr]) : 0.f;
+    }
+    __syncthreads();
+    const uint32_t ol = blockIdx.y * SKL_WG + threadIdx.x;
+    if (ol >= p.to) return;
+    TileHash<D> th;
+    th.init(p.h, u.j_lo * p.to + ol, p.to);
+    const uint32_t Kq = u.K << 8;
+    float acc[BT];
+#pragma unroll
+    for (int b = 0; b < BT; ++b) acc[b] = 0.f;
+    for (uint32_t jr = 0; jr < rows; ++jr) {
+        const float w = half_bits_to_float(key_to_half_bits(th.query(tab, u.K, Kq)));
+#pragma unroll
+        for (int b = 0; b < BT; ++b) acc[b] = fmaf(w, xs[b * p.jc_rows + jr], acc[b]);
+    }
+    const uint32_t unit = u.jb * p.n_jc + u.jc;   // partial-sum slot of this chunk
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+        if (b0 + b < batch)
+            partial[((size_t)unit * batch + b0 + b) * p.out + u.ob * p.to + ol] = acc[b];
+}
+
+// prefill GEMM on path 0: 64 tokens x 64 outputs per workgroup; per 16 input
+// rows the weights are reconstructed once into LDS (transposed, binary16 with
+// inverted sign) and fed to 32x32x16 MFMAs.
+#define TG_T 64
+#define TG_AS 24   // halfs per LDS row of the 16-wide operand tiles (16 + 8)
+
+template <int D>
+__global__ __launch_bounds__(SKL_WG) void k_tile_gemm(TileArgs p, const uint16_t *__restrict__ X, uint32_t x_dt,
+                                                      uint32_t ldx, uint32_t tokens, void *__restrict__ Y, uint32_t y_dt,
+                                                      uint32_t ldy, uint32_t key_words)
+{
+    uint16_t *tab = reinterpret_cast<uint16_t *>(smem);
+    uint16_t *As = reinterpret_cast<uint16_t *>(smem + key_words);   // [64 tokens][TG_AS]
+    uint16_t *Bs = As + TG_T * TG_AS;                                // [64 outputs][TG_AS]
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t wm = wave >> 1, wn = wave & 1;
+    const uint32_t n = lane & 31, q = lane >> 5;
+    const uint32_t n_oc = (p.to + TG_T - 1) / TG_T;       // 64-wide output chunks per group column
+    const uint32_t ob = blockIdx.x / n_oc, oc = blockIdx.x - ob * n_oc;
+    const uint32_t t0 = blockIdx.y * TG_T;
+    const uint32_t ol_b = oc * TG_T + (threadIdx.x & 63);   // output (inside the group) this thread reconstructs
+    const uint32_t jsub = threadIdx.x >> 6;                 // ... for input rows jsub*4 .. jsub*4+3 of each 16
+    float16v acc = {0.f};
+    const uint32_t n_jb = p.in / p.tj;
+    for (uint32_t jb = 0; jb < n_jb; ++jb) {
+        const skl_group_meta gm = p.gmeta[jb * p.n_ob + ob];
+        __syncthreads();
+        stage_keys(tab, p.keys + gm.key_off, D * gm.K);
+        __syncthreads();
+        const uint32_t Kq = gm.K << 8;
+        for (uint32_t j0 = 0; j0 < p.tj; j0 += 16) {
+            // reconstruct 16 x 64 weights: thread -> (output ol_b, rows j0 + jsub*4 .. +3)
+            {
+                TileHash<D> th;
+                const uint32_t olc = min(ol_b, p.to - 1);
+                th.init(p.h, (j0 + jsub * 4) * p.to + olc, p.to);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t jl = j0 + jsub * 4 + i;
+                    uint16_t v = 0;
+                    const uint16_t k = th.query(tab, gm.K, Kq);   // addresses past the group are never used below
+                    if (jl < p.tj && ol_b < p.to) v = key_to_half_bits(k) ^ 0x8000u;
+                    Bs[(threadIdx.x & 63) * TG_AS + jsub * 4 + i] = v;
+                }
+            }
+            // activations: 64 tokens x 16 input rows, thread -> (token, 4 rows)
+            {
+                const uint32_t tr = threadIdx.x >> 2, js = (threadIdx.x & 3) * 4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t jl = j0 + js + i;
+                    uint16_t v = 0;
+                    if (t0 + tr < tokens && jl < p.tj) v = load_neg_half(X, x_dt, (size_t)(t0 + tr) * ldx + jb * p.tj + jl);
+                    As[tr * TG_AS + js + i] = v;
+                }
+            }
+            __syncthreads();
+            const uint4 a = *reinterpret_cast<const uint4 *>(As + (wm * 32 + n) * TG_AS + q * 8);
+            const uint4 b = *reinterpret_cast<const uint4 *>(Bs + (wn * 32 + n) * TG_AS + q * 8);
+            // both operands carry an inverted sign: the product is x * w
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b), acc, 0, 0, 0);
+            __syncthreads();
+        }
+    }
+    const uint32_t ol = oc * TG_T + wn * 32 + n;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t t = t0 + wm * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
+        if (t < tokens && ol < p.to) store_out(Y, y_dt, (size_t)t * ldy + ob * p.to + ol, acc[i]);
+    }
+}
+
+// ---- second pass of the split reduction: y[b][o] = sum_u partial[u][b][o] ---
+__global__ __launch_bounds__(SKL_WG) void k_reduce_partials(const float *__restrict__ partial, uint32_t n_units,
+                                                             uint32_t batch, uint32_t out, void *__restrict__ y,
+                                                             uint32_t y_dt, uint32_t ldy)
+{
+    const uint32_t o = blockIdx.x * SKL_WG + threadIdx.x;
+    const uint32_t b = blockIdx.y;
+    if (o >= out) return;
+    float s = 0.f;
+    for (uint32_t u = 0; u < n_units; ++u) s += partial[((size_t)u * batch + b) * out + o];
+    store_out(y, y_dt, (size_t)b * ldy + o, s);
+}
+
+// ========================================================================
+// Launchers
+// ========================================================================
+static RowArgs make_row_args(const skl_layer *L)
+{
+    RowArgs a;
+    for (int r = 0; r < SKL_MAX_D; ++r) { a.h.A[r] = L->A[r]; a.h.C[r] = L->C[r]; }
+    a.bmeta = reinterpret_cast<const skl_block_meta *>(L->dev + L->off_bmeta);
+    a.chan = reinterpret_cast<const uint32_t *>(L->dev + L->off_chan);
+    a.tables = reinterpret_cast<const uint4 *>(L->dev + L->off_tables);
+    a.in = L->in; a.out = L->out; a.n_blocks = L->n_blocks; a.n_otiles = L->n_otiles; a.n_seg = L->n_seg;
+    return a;
+}
+
+static TileArgs make_tile_args(const skl_layer *L)
+{
+    TileArgs a;
+    for (int r = 0; r < SKL_MAX_D; ++r) { a.h.A[r] = L->A[r]; a.h.C[r] = L->C[r]; }
+    a.gmeta = reinterpret_cast<const skl_group_meta *>(L->dev + L->off_gmeta);
+    a.keys = reinterpret_cast<const uint16_t *>(L->dev + L->off_keys);
+    a.in = L->in; a.out = L->out; a.tj = L->tj; a.to = L->to; a.n_ob = L->n_ob;
+    a.jc_rows = L->jc_rows; a.n_jc = L->n_jc;
+    return a;
+}
+
+static skl_status_t check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        skl_set_error("launch of %s failed: %s", what, hipGetErrorString(e));
+        return SKL_ERR_HIP;
+    }
+    return SKL_OK;
+}
+
+template <typename K>
+static skl_status_t allow_lds(K kernel, size_t bytes)
+{
+    if (bytes > 65536) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) {
+            skl_set_error("cannot reserve %zu bytes of LDS: %s", bytes, hipGetErrorString(e));
+            return SKL_ERR_HIP;
+        }
+    }
+    return SKL_OK;
+}
+
+#define DISPATCH_D(d, CALL)                                         \
+    switch (d) {                                                    \
+    case 1: { constexpr int D = 1; CALL; } break;                   \
+    case 2: { constexpr int D = 2; CALL; } break;                   \
+    case 3: { constexpr int D = 3; CALL; } break;                   \
+    case 4: { constexpr int D = 4; CALL; } break;                   \
+    case 5: { constexpr int D = 5; CALL; } break;                   \
+    case 6: { constexpr int D = 6; CALL; } break;                   \
+    case 7: { constexpr int D = 7; CALL; } break;                   \
+    default: { constexpr int D = 8; CALL; } break;                  \
+    }
+
+static inline size_t tile_key_words(const skl_layer *L) { return ((size_t)L->d * L->max_K * 2 + 15) / 16; }
+
+uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch)
+{
+    return (uint64_t)L->n_units * batch * L->out * sizeof(float);
+}
+
+uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
+{
+    return L->path == 1 ? (uint64_t)tokens * L->n_packed * sizeof(uint16_t) : 0;
+}
+
+skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    skl_status_t st = SKL_OK;
+    if (L->path == 1) {
+        const RowArgs a = make_row_args(L);
+        const size_t lds = (size_t)L->max_table_bytes + 64 * sizeof(uint32_t);
+        const dim3 grid(L->n_blocks, L->n_seg);
+        DISPATCH_D(L->d, {
+            st = allow_lds(k_row_reconstruct<D>, lds);
+            if (st == SKL_OK) hipLaunchKernelGGL(k_row_reconstruct<D>, grid, dim3(SKL_WG), lds, stream, a, W_hat);
+        });
+    } else {
+        const TileArgs a = make_tile_args(L);
+        const size_t lds = tile_key_words(L) * 16;
+        const dim3 grid(L->n_jb * L->n_ob * L->n_jc, (L->to + SKL_WG - 1) / SKL_WG);
+        DISPATCH_D(L->d, {
+            st = allow_lds(k_tile_reconstruct<D>, lds);
+            if (st == SKL_OK) hipLaunchKernelGGL(k_tile_reconstruct<D>, grid, dim3(SKL_WG), lds, stream, a, W_hat);
+        });
+    }
+    return st == SKL_OK ? check_launch("reconstruct") : st;
+}
+
+skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, void *y, skl_dtype_t y_dt,
+                             uint32_t ldy, uint32_t batch, void *ws, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const uint16_t *x = static_cast<const uint16_t *>(x_);
+    float *partial = static_cast<float *>(ws);
+    skl_status_t st = SKL_OK;
+    if (L->path == 1) {
+        const RowArgs a = make_row_args(L);
+        const dim3 grid(L->n_blocks, L->n_seg);
+        if (batch == 1) {
+            const size_t lds = (size_t)L->max_table_bytes + 64 * sizeof(uint16_t);
+            DISPATCH_D(L->d, {
+                st = allow_lds(k_row_gemv1<D>, lds);
+                if (st == SKL_OK) hipLaunchKernelGGL(k_row_gemv1<D>, grid, dim3(SKL_WG), lds, stream, a, x, partial);
+            });
+        } else {
+            const size_t lds = (size_t)L->max_table_bytes + 32 * (64 + XS_PAD) * sizeof(uint16_t);
+            DISPATCH_D(L->d, {
+                st = allow_lds(k_row_gemvN<D>, lds);
+                if (st == SKL_OK)
+                    hipLaunchKernelGGL(k_row_gemvN<D>, grid, dim3(SKL_WG), lds, stream, a, x, ldx, batch, partial);
+            });
+        }
+    } else {
+        const TileArgs a = make_tile_args(L);
+        const uint32_t kw = (uint32_t)tile_key_words(L);
+        const uint32_t units = L->n_jb * L->n_ob * L->n_jc, noc = (L->to + SKL_WG - 1) / SKL_WG;
+        if (batch == 1) {
+            const size_t lds = (size_t)kw * 16 + (size_t)L->jc_rows * sizeof(float);
+            DISPATCH_D(L->d, {
+                st = allow_lds(k_tile_gemv<D, 1>, lds);
+                if (st == SKL_OK)
+                    hipLaunchKernelGGL((k_tile_gemv<D, 1>), dim3(units, noc, 1), dim3(SKL_WG), lds, stream, a, x, ldx,
+                                       batch, partial, kw);
+            });
+        } else {
+            const size_t lds = (size_t)kw * 16 + (size_t)4 * L->jc_rows * sizeof(float);
+            DISPATCH_D(L->d, {
+                st = allow_lds(k_tile_gemv<D, 4>, lds);
+                if (st == SKL_OK)
+                    hipLaunchKernelGGL((k_tile_gemv<D, 4>), dim3(units, noc, (batch + 3) / 4), dim3(SKL_WG), lds, stream,
+                                       a, x, ldx, batch, partial, kw);
+            });
+        }
+    }
+    if (st != SKL_OK) return st;
+    st = check_launch("gemv");
+    if (st != SKL_OK) return st;
+    hipLaunchKernelGGL(k_reduce_partials, dim3((L->out + SKL_WG - 1) / SKL_WG, batch), dim3(SKL_WG), 0, stream, partial,
+                       L->n_units, batch, L->out, y, (uint32_t)y_dt, ldy);
+    return check_launch("gemv reduction");
+}
+
+skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_dt, uint32_t ldx, void *Y,
+                             skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, void *ws, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const uint16_t *X = static_cast<const uint16_t *>(X_);
+    skl_status_t st = SKL_OK;
+    if (L->path == 1) {
+        uint16_t *Xp = static_cast<uint16_t *>(ws);
+        const RowArgs a = make_row_args(L);
+        hipLaunchKernelGGL(k_pack_activations, dim3(tokens, (L->n_packed + SKL_WG - 1) / SKL_WG), dim3(SKL_WG), 0, stream,
+                           X, (uint32_t)x_dt, ldx, a.chan, L->n_packed, Xp);
+        st = check_launch("activation packing");
+        if (st != SKL_OK) return st;
+        const uint32_t tw = L->max_table_bytes / 16;
+        const size_t lds = (size_t)tw * 16 + (size_t)GEMM_MT * GEMM_AS * sizeof(uint16_t);
+        const dim3 grid((L->out + GEMM_NT - 1) / GEMM_NT, (tokens + GEMM_MT - 1) / GEMM_MT);
+        DISPATCH_D(L->d, {
+            st = allow_lds(k_row_gemm<D>, lds);
+            if (st == SKL_OK)
+                hipLaunchKernelGGL(k_row_gemm<D>, grid, dim3(SKL_WG), lds, stream, a, Xp, tokens, L->n_packed, Y, (uint32_t)y_dt,
+                                   ldy, tw);
+        });
+    } else {
+        const TileArgs a = make_tile_args(L);
+        const uint32_t kw = (uint32_t)tile_key_words(L);
+        const size_t lds = (size_t)kw * 16 + (size_t)2 * TG_T * TG_AS * sizeof(uint16_t);
+        const uint32_t n_oc = (L->to + TG_T - 1) / TG_T;
+        const dim3 grid(L->n_ob * n_oc, (tokens + TG_T - 1) / TG_T);
+        DISPATCH_D(L->d, {
+            st = allow_lds(k_tile_gemm<D>, lds);
+            if (st == SKL_OK)
+                hipLaunchKernelGGL(k_tile_gemm<D>, grid, dim3(SKL_WG), lds, stream, a, X, (uint32_t)x_dt, ldx, tokens, Y,
+                                   (uint32_t)y_dt, ldy, kw);
+        });
+    }
+    return st == SKL_OK ? check_launch("gemm") : st;
+}

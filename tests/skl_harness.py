@@ -1,0 +1,131 @@
+"""Test-side plumbing: torch owns device memory and streams, the library is
+called through its C ABI binding, the oracle provides sketches and expected
+values.  Nothing here computes any step of the method."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+import paper_2506_17255_amd as skl
+import workloads as wk
+
+DT = {"f16": skl.SKL_F16, "bf16": skl.SKL_BF16, "f32": skl.SKL_F32}
+
+
+def torch_mod():
+    import torch
+    return torch
+
+
+def build_sketch(wl: wk.Workload, W=None, widths=None):
+    """(W, oracle.Sketch) for a workload: seeded weights, seeded hash
+    parameters, importance-aware widths, states from the oracle's update."""
+    W = wk.gen_weight(wl) if W is None else W
+    A, C = wk.gen_hash_params(wl)
+    if widths is None:
+        widths = oracle.allocate_widths(wk.gen_importance(wl), wl.budget_states, wl.d)
+    return W, oracle.update(W, wl.tile_in, wl.tile_out, wl.d, A, C, widths)
+
+
+def desc_of(sk: oracle.Sketch, flags: int = 0):
+    return skl.make_desc(sk.in_features, sk.out_features, sk.tile_in, sk.tile_out, sk.d,
+                         np.ascontiguousarray(sk.hash_a, dtype=np.uint32),
+                         np.ascontiguousarray(sk.hash_c, dtype=np.uint32),
+                         np.ascontiguousarray(sk.group_width, dtype=np.uint32),
+                         np.ascontiguousarray(sk.states, dtype=np.uint16), flags=flags)
+
+
+class GpuLayer:
+    """A layer resident on cuda:0 plus the buffers its calls need."""
+
+    def __init__(self, sk: oracle.Sketch, flags: int = 0):
+        torch = torch_mod()
+        if not torch.cuda.is_available():
+            raise RuntimeError("GPU tests need a GPU")
+        self.torch = torch
+        self.sk = sk
+        self.dev = torch.device("cuda:0")
+        desc = desc_of(sk, flags)
+        nbytes = skl.sketch_linear_device_bytes(desc)
+        self.dev_buf = torch.zeros(nbytes, dtype=torch.uint8, device=self.dev)
+        self.handle = skl.sketch_linear_create(desc, self.dev_buf.data_ptr(), nbytes, self.stream())
+        self.info = skl.sketch_linear_info(self.handle)
+        self._ws = None
+
+    def stream(self) -> int:
+        return self.torch.cuda.current_stream().cuda_stream
+
+    def close(self):
+        if self.handle:
+            self.torch.cuda.synchronize()
+            skl.sketch_linear_destroy(self.handle)
+            self.handle = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def workspace(self, op: int, n: int):
+        need = skl.sketch_linear_workspace_bytes(self.handle, op, n)
+        if self._ws is None or self._ws.numel() < max(need, 16):
+            self._ws = self.torch.empty(max(need, 16), dtype=self.torch.uint8, device=self.dev)
+        return self._ws, need
+
+    def reconstruct(self) -> np.ndarray:
+        t = self.torch
+        out = t.full((self.sk.in_features, self.sk.out_features), 0x7E00, dtype=t.int16, device=self.dev)
+        skl.sketch_linear_reconstruct(self.handle, out.data_ptr(), self.stream())
+        t.cuda.synchronize()
+        return out.cpu().numpy().view(np.uint16)
+
+    def gemv(self, x_f16: np.ndarray, y_dtype: str = "f32", ldx=None, ldy=None) -> np.ndarray:
+        t = self.torch
+        batch, in_f = x_f16.shape
+        ldx = ldx or in_f
+        ldy = ldy or self.sk.out_features
+        xb = np.zeros((batch, ldx), dtype=np.float16)
+        xb[:, :in_f] = x_f16
+        xd = t.from_numpy(xb.view(np.int16)).to(self.dev)
+        ydt = {"f32": t.float32, "f16": t.float16}[y_dtype]
+        yd = t.full((batch, ldy), float("nan"), dtype=ydt, device=self.dev)
+        ws, need = self.workspace(0, batch)
+        skl.sketch_linear_gemv(self.handle, xd.data_ptr(), skl.SKL_F16, ldx, yd.data_ptr(), DT[y_dtype], ldy,
+                               batch, ws.data_ptr(), ws.numel(), self.stream())
+        t.cuda.synchronize()
+        y = yd.cpu().numpy()
+        if ldy > self.sk.out_features:
+            assert np.all(np.isnan(y[:, self.sk.out_features:].astype(np.float32))), "wrote past out_features"
+        return y[:, :self.sk.out_features]
+
+    def gemm(self, X_bits: np.ndarray, x_dtype: str = "bf16", y_dtype: str = "f32", ldx=None, ldy=None) -> np.ndarray:
+        t = self.torch
+        tokens, in_f = X_bits.shape
+        ldx = ldx or in_f
+        ldy = ldy or self.sk.out_features
+        xb = np.zeros((tokens, ldx), dtype=np.uint16)
+        xb[:, :in_f] = X_bits
+        xd = t.from_numpy(xb.view(np.int16)).to(self.dev)
+        ydt = {"f32": t.float32, "f16": t.float16, "bf16": t.bfloat16}[y_dtype]
+        yd = t.full((tokens, ldy), float("nan"), dtype=ydt, device=self.dev)
+        ws, need = self.workspace(1, tokens)
+        skl.sketch_linear_gemm(self.handle, xd.data_ptr(), DT[x_dtype], ldx, yd.data_ptr(), DT[y_dtype], ldy,
+                               tokens, ws.data_ptr(), ws.numel(), self.stream())
+        t.cuda.synchronize()
+        y = yd.float().cpu().numpy() if y_dtype == "bf16" else yd.cpu().numpy()
+        if ldy > self.sk.out_features:
+            assert np.all(np.isnan(y[:, self.sk.out_features:].astype(np.float32))), "wrote past out_features"
+        return y[:, :self.sk.out_features]
+
+
+def rel_fro(got, ref) -> float:
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """fp64 -> float32 -> bfloat16 (nearest even) -> float64, to compare bf16
+    outputs with the oracle rounded the same way."""
+    return wk.bf16_bits_to_f32(wk.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))).astype(np.float64)

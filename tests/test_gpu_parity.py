@@ -1,0 +1,203 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle.
+
+Bars (also stated per test):
+  * reconstructed weights: bit-exact (integer compare of binary16 patterns);
+  * gemv / gemm outputs: relative Frobenius error <= 1e-3 against the fp64
+    oracle (float32 and binary16 outputs), and against the oracle rounded to
+    bfloat16 for bfloat16 outputs (the rounding alone is ~1.7e-3);
+  * one-hot activations: the float32 output must equal the reconstructed
+    weight exactly -- this checks the fused kernels' own query stage.
+"""
+import functools
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wk
+from skl_harness import GpuLayer, build_sketch, rel_fro, round_to_bf16
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-3
+
+
+# ------------------------------------------------------------------ layers
+def custom_layer(name, in_f, out_f, tj, to, d, widths, seed):
+    rng = np.random.default_rng(seed)
+    W = (rng.standard_normal((in_f, out_f)) * 0.02).astype(np.float16)
+    A = (2 * rng.integers(0, 1 << 23, size=d) + 1).astype(np.uint32)
+    C = rng.integers(0, 1 << 24, size=d).astype(np.uint32)
+    return W, oracle.update(W, tj, to, d, A, C, np.asarray(widths, dtype=np.uint32))
+
+
+@functools.lru_cache(maxsize=None)
+def small_case(name):
+    rng = np.random.default_rng(abs(hash(name)) % (1 << 31))
+    if name == "cfg1":                       # one 256x256 group, d=2, K=1024: per-weight hashing
+        return build_sketch(wk.cfg1())
+    if name == "row_ragged":                 # row sketches; in % 8 != 0, out % 32 != 0
+        return custom_layer(name, 100, 300, 1, 300, 4, [11] * 100, 1)
+    if name == "row_classes":                # four width classes -> all four table layouts in one layer
+        widths = np.array([11] * 150 + [100] * 20 + [200] * 13 + [300] * 9)
+        np.random.default_rng(2).shuffle(widths)
+        return custom_layer(name, 192, 520, 1, 520, 4, widths, 2)
+    if name == "row_d1":
+        return custom_layer(name, 64, 256, 1, 256, 1, [16] * 64, 3)
+    if name == "row_d2_importance":
+        widths = np.where(np.arange(72) % 9 == 0, 48, 12)
+        return custom_layer(name, 72, 1000, 1, 1000, 2, widths, 4)
+    if name == "row_d5":
+        return custom_layer(name, 40, 384, 1, 384, 5, [20] * 40, 5)
+    if name == "row_d8":
+        return custom_layer(name, 24, 130, 1, 130, 8, [9] * 24, 6)
+    if name == "row_big_table":              # one-word rows, table above 64 KiB of LDS
+        return custom_layer(name, 16, 2048, 1, 2048, 4, [1100] * 16, 7)
+    if name == "row_single":                 # degenerate: one input channel, one output
+        return custom_layer(name, 1, 1, 1, 1, 3, [1], 8)
+    if name == "tile_ragged":                # 2-D groups, per-group widths, tile_out < workgroup
+        return custom_layer(name, 96, 160, 32, 80, 3, rng.integers(5, 60, size=6), 9)
+    if name == "tile_wide":                  # tile_out above one workgroup of lanes, tile_in % 16 != 0
+        return custom_layer(name, 12, 600, 6, 300, 2, [37, 41, 43, 47], 10)
+    if name == "tile_d8_K1":                 # width 1: every weight of a group shares one state per row
+        return custom_layer(name, 16, 64, 8, 32, 8, [1, 2, 1, 3], 11)
+    if name == "tile_forced_1d":             # row geometry pushed through the per-weight path
+        return custom_layer(name, 40, 200, 1, 200, 3, [13] * 40, 12)
+    raise KeyError(name)
+
+
+SMALL = ["cfg1", "row_ragged", "row_classes", "row_d1", "row_d2_importance", "row_d5", "row_d8",
+         "row_big_table", "row_single", "tile_ragged", "tile_wide", "tile_d8_K1", "tile_forced_1d"]
+
+
+def flags_of(name):
+    return 1 if name == "tile_forced_1d" else 0
+
+
+@functools.lru_cache(maxsize=None)
+def expected_W_hat(name):
+    return oracle.query(small_case(name)[1])
+
+
+# ----------------------------------------------------------- reconstruct
+@pytest.mark.parametrize("name", SMALL)
+def test_reconstruct_bit_exact(name):
+    W, sk = small_case(name)
+    with GpuLayer(sk, flags_of(name)) as g:
+        assert g.info["path"] == (1 if name.startswith("row") else 0)
+        got = g.reconstruct()
+    assert np.array_equal(got, expected_W_hat(name))
+
+
+# ------------------------------------------------------------------ gemv
+@pytest.mark.parametrize("batch", [1, 2, 5, 8, 16])
+@pytest.mark.parametrize("name", SMALL)
+def test_gemv_matches_oracle(name, batch):
+    W, sk = small_case(name)
+    W_hat = expected_W_hat(name)
+    rng = np.random.default_rng(100 + batch)
+    x = rng.standard_normal((batch, sk.in_features)).astype(np.float16)
+    ref = oracle.linear(W_hat, x)
+    with GpuLayer(sk, flags_of(name)) as g:
+        y32 = g.gemv(x, "f32", ldx=sk.in_features + 8, ldy=sk.out_features + 24)
+        y16 = g.gemv(x, "f16")
+        again = g.gemv(x, "f32")
+    assert rel_fro(y32, ref) <= TOL, rel_fro(y32, ref)
+    assert rel_fro(y16, ref) <= TOL, rel_fro(y16, ref)
+    assert rel_fro(y32, ref) <= 1e-5          # float32 accumulation: far inside the bar
+    assert np.array_equal(y32, again), "summation order must not change from run to run"
+
+
+@pytest.mark.parametrize("batch", [1, 16])
+@pytest.mark.parametrize("name", SMALL)
+def test_gemv_one_hot_probe_is_exact(name, batch):
+    """x = e_j  =>  y = W_hat[j][:] exactly: one exact product, all other terms zero."""
+    W, sk = small_case(name)
+    W_hat = expected_W_hat(name).view(np.float16).astype(np.float32)
+    rng = np.random.default_rng(7)
+    js = rng.choice(sk.in_features, size=min(batch, sk.in_features), replace=False)
+    x = np.zeros((batch, sk.in_features), dtype=np.float16)
+    for b, j in enumerate(js):
+        x[b, j] = 1.0
+    with GpuLayer(sk, flags_of(name)) as g:
+        y = g.gemv(x, "f32")
+    for b, j in enumerate(js):
+        assert np.array_equal(y[b], W_hat[j]), (name, b, j)
+    assert np.all(y[len(js):] == 0)
+
+
+# ------------------------------------------------------------------ gemm
+@pytest.mark.parametrize("tokens", [1, 70, 200])
+@pytest.mark.parametrize("name", SMALL)
+def test_gemm_matches_oracle(name, tokens):
+    W, sk = small_case(name)
+    W_hat = expected_W_hat(name)
+    rng = np.random.default_rng(200 + tokens)
+    Xf = rng.standard_normal((tokens, sk.in_features)).astype(np.float32)
+    Xb = wk.f32_to_bf16_bits(Xf)
+    ref = oracle.linear(W_hat, Xb, x_kind="bf16")
+    with GpuLayer(sk, flags_of(name)) as g:
+        y32 = g.gemm(Xb, "bf16", "f32", ldx=sk.in_features + 8, ldy=sk.out_features + 8)
+        ybf = g.gemm(Xb, "bf16", "bf16")
+        y16 = g.gemm(Xb, "bf16", "f16")
+        Xh = Xf.astype(np.float16)
+        yh = g.gemm(Xh.view(np.uint16), "f16", "f32")
+    assert rel_fro(y32, ref) <= 1e-5, rel_fro(y32, ref)
+    assert rel_fro(y16, ref) <= TOL
+    assert rel_fro(ybf, round_to_bf16(ref)) <= TOL, rel_fro(ybf, round_to_bf16(ref))
+    assert rel_fro(yh, oracle.linear(W_hat, Xh)) <= 1e-5
+
+
+@pytest.mark.parametrize("name", ["row_ragged", "row_classes", "tile_ragged", "cfg1"])
+def test_gemm_identity_probe_is_exact(name):
+    """X = I  =>  Y = W_hat exactly (float32 output)."""
+    W, sk = small_case(name)
+    W_hat = expected_W_hat(name).view(np.float16).astype(np.float32)
+    X = np.eye(sk.in_features, dtype=np.float32)
+    with GpuLayer(sk, flags_of(name)) as g:
+        y = g.gemm(wk.f32_to_bf16_bits(X), "bf16", "f32")
+    assert np.array_equal(y, W_hat)
+
+
+def test_gemm_row_equals_gemv():
+    W, sk = small_case("row_classes")
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((3, sk.in_features)).astype(np.float16)
+    with GpuLayer(sk) as g:
+        Y = g.gemm(X.view(np.uint16), "f16", "f32")
+        y = g.gemv(X, "f32")
+    assert rel_fro(Y, y) <= 1e-5
+
+
+# ----------------------------------------------------------- error paths
+def test_call_time_validation():
+    import paper_2506_17255_amd as skl
+    W, sk = small_case("row_ragged")
+    with GpuLayer(sk) as g:
+        t = g.torch
+        x = t.zeros(16, sk.in_features, dtype=t.float16, device=g.dev)
+        y = t.zeros(16, sk.out_features, dtype=t.float32, device=g.dev)
+        ws, need = g.workspace(0, 16)
+        args = dict(layer=g.handle, x=x.data_ptr(), x_dtype=skl.SKL_F16, ldx=sk.in_features, y=y.data_ptr(),
+                    y_dtype=skl.SKL_F32, ldy=sk.out_features, batch=16, workspace=ws.data_ptr(),
+                    workspace_bytes=need, hip_stream=g.stream())
+
+        def status(**over):
+            try:
+                skl.sketch_linear_gemv(**{**args, **over})
+                return 0
+            except skl.SketchLinearError as e:
+                return e.status
+        assert status() == 0
+        assert status(batch=0) == skl.SKL_ERR_INVALID_ARG
+        assert status(batch=17) == skl.SKL_ERR_INVALID_ARG
+        assert status(x_dtype=skl.SKL_BF16) == skl.SKL_ERR_UNSUPPORTED
+        assert status(y_dtype=skl.SKL_BF16) == skl.SKL_ERR_UNSUPPORTED
+        assert status(ldx=sk.in_features - 1) == skl.SKL_ERR_INVALID_ARG
+        assert status(ldy=sk.out_features - 1) == skl.SKL_ERR_INVALID_ARG
+        assert status(workspace_bytes=need - 1) == skl.SKL_ERR_BUFFER_TOO_SMALL
+        assert status(workspace=0) == skl.SKL_ERR_INVALID_ARG
+        assert status(x=x.data_ptr() + 2) == skl.SKL_ERR_INVALID_ARG
+        assert status(y=x.data_ptr()) == skl.SKL_ERR_INVALID_ARG          # aliasing
+        assert status(x=0) == skl.SKL_ERR_INVALID_ARG
+        t.cuda.synchronize()

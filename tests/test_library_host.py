@@ -1,0 +1,133 @@
+"""Host-only checks of the C ABI library: it loads, exports every symbol the
+header declares, validates descriptions without touching a device, and plans
+layouts that respect the LDS budget.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2506_17255_amd as skl
+from paper_2506_17255_amd import build as skl_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def built():
+    if not os.path.exists(skl_build.lib_path()):
+        skl_build.build_library()
+    skl.load_library()
+
+
+def header_symbols():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            txt = open(os.path.join(ROOT, "include", fn)).read()
+            txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+            names |= set(re.findall(r"\b(sketch_linear_\w+)\s*\(", txt))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    L = skl.load_library()
+    decl = header_symbols()
+    assert decl == set(skl.EXPORTS)
+    for n in decl:
+        assert hasattr(L, n), n
+
+
+def test_struct_sizes_match_header_layout():
+    assert ctypes.sizeof(skl.skl_desc_t) == 72
+    assert ctypes.sizeof(skl.skl_info_t) == 40
+
+
+def good(**over):
+    kw = dict(in_features=8, out_features=16, tile_in=4, tile_out=8, d=2,
+              hash_a=np.uint32([3, 5]), hash_c=np.uint32([7, 11]),
+              group_width=np.uint32([3, 4, 5, 6]), states=np.zeros(2 * 18, dtype=np.uint16))
+    kw.update(over)
+    return skl.make_desc(**kw)
+
+
+def status_of(desc):
+    try:
+        skl.sketch_linear_device_bytes(desc)
+        return skl.SKL_OK
+    except skl.SketchLinearError as e:
+        assert e.message, "every failure carries a message"
+        return e.status
+
+
+def test_valid_description_is_accepted():
+    assert status_of(good()) == skl.SKL_OK
+    assert skl.sketch_linear_device_bytes(good()) >= 4096 + 2 * 36
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(struct_size=8), skl.SKL_ERR_INVALID_ARG),
+    (dict(in_features=0), skl.SKL_ERR_INVALID_ARG),
+    (dict(tile_in=3), skl.SKL_ERR_INVALID_ARG),
+    (dict(tile_out=5), skl.SKL_ERR_INVALID_ARG),
+    (dict(d=0), skl.SKL_ERR_INVALID_ARG),
+    (dict(d=9), skl.SKL_ERR_INVALID_ARG),
+    (dict(query_mode=1), skl.SKL_ERR_UNSUPPORTED),
+    (dict(flags=2), skl.SKL_ERR_INVALID_ARG),
+    (dict(hash_a=None), skl.SKL_ERR_INVALID_ARG),
+    (dict(states=None, n_states=36), skl.SKL_ERR_INVALID_ARG),
+    (dict(hash_a=np.uint32([1 << 24, 5])), skl.SKL_ERR_INVALID_ARG),
+    (dict(hash_c=np.uint32([7, 1 << 24])), skl.SKL_ERR_INVALID_ARG),
+    (dict(group_width=np.uint32([3, 0, 5, 6]), states=np.zeros(28, dtype=np.uint16)), skl.SKL_ERR_INVALID_ARG),
+    (dict(group_width=np.uint32([3, 65536, 5, 6])), skl.SKL_ERR_INVALID_ARG),
+    (dict(n_states=35), skl.SKL_ERR_INVALID_ARG),
+    (dict(states=np.uint16([0] * 35 + [0x7C00])), skl.SKL_ERR_NONFINITE),
+    (dict(states=np.uint16([0xFE00] + [0] * 35)), skl.SKL_ERR_NONFINITE),
+])
+def test_bad_descriptions_are_rejected(over, status):
+    assert status_of(good(**over)) == status
+
+
+def test_group_address_space_limit():
+    d = good(in_features=1 << 13, out_features=1 << 12, tile_in=1 << 13, tile_out=1 << 12,
+             group_width=np.uint32([1]), states=np.zeros(2, dtype=np.uint16))
+    assert status_of(d) == skl.SKL_ERR_INVALID_ARG          # 2^25 addresses in one group
+
+
+def test_table_too_large_for_lds_is_unsupported():
+    K = 65535
+    d = good(in_features=4, out_features=4, tile_in=4, tile_out=4, d=8,
+             hash_a=np.arange(1, 9, dtype=np.uint32), hash_c=np.arange(8, dtype=np.uint32),
+             group_width=np.uint32([K]), states=np.zeros(8 * K, dtype=np.uint16))
+    assert status_of(d) == skl.SKL_ERR_UNSUPPORTED
+
+
+def test_null_arguments():
+    L = skl.load_library()
+    n = ctypes.c_uint64(0)
+    assert L.sketch_linear_device_bytes(None, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_device_bytes(ctypes.byref(good()), None) == skl.SKL_ERR_INVALID_ARG
+    h = ctypes.c_void_p(None)
+    assert L.sketch_linear_create(ctypes.byref(good()), None, 1 << 20, None, ctypes.byref(h)) == skl.SKL_ERR_INVALID_ARG
+    assert "dev_buf" in skl.sketch_linear_last_error()
+    assert L.sketch_linear_create(ctypes.byref(good()), 4096, 16, None, ctypes.byref(h)) == skl.SKL_ERR_BUFFER_TOO_SMALL
+    assert L.sketch_linear_create(ctypes.byref(good()), 4097, 1 << 20, None, ctypes.byref(h)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_create(ctypes.byref(good()), 4096, 1 << 20, None, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_gemv(None, 16, 0, 8, 32, 2, 16, 1, 64, 0, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_gemm(None, 16, 0, 8, 32, 2, 16, 1, 64, 0, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_reconstruct(None, 16, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_workspace_bytes(None, 0, 1, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_info(None, None) == skl.SKL_ERR_INVALID_ARG
+    L.sketch_linear_destroy(None)
+
+
+def test_device_bytes_scale_with_the_sketch_not_with_the_layer():
+    # 0.5 bit/weight row sketches of a 4096 x 11008 layer: tables of about
+    # 1/16 byte per weight (plus row padding), far below the 2 bytes of fp16
+    in_f, out_f, d, K = 4096, 11008, 4, 86
+    desc = skl.make_desc(in_f, out_f, 1, out_f, d, np.uint32([3, 5, 7, 9]), np.uint32([1, 2, 3, 4]),
+                         np.full(in_f, K, dtype=np.uint32), np.zeros(in_f * d * K, dtype=np.uint16))
+    nbytes = skl.sketch_linear_device_bytes(desc)
+    assert in_f * d * K * 2 <= nbytes <= 1.3 * in_f * d * K * 2
+    assert nbytes < 0.08 * in_f * out_f

@@ -608,16 +608,49 @@ __global__ __launch_bounds__(SKL_WG) void k_tile_gemm(TileArgs p, const uint16_t
 }
 
 // ---- second pass of the split reduction: y[b][o] = sum_u partial[u][b][o] ---
+// A workgroup owns 64 outputs (16 lanes x 4 consecutive outputs) of one batch
+// row; its 16 lane rows each sum every 16th partial, then the 16 slices are
+// added in a fixed order, so the result is the same on every run.
+#define RED_O 64
 __global__ __launch_bounds__(SKL_WG) void k_reduce_partials(const float *__restrict__ partial, uint32_t n_units,
                                                              uint32_t batch, uint32_t out, void *__restrict__ y,
                                                              uint32_t y_dt, uint32_t ldy)
 {
-    const uint32_t o = blockIdx.x * SKL_WG + threadIdx.x;
+    __shared__ float4 red[16][16];
+    const uint32_t oq = threadIdx.x & 15, slice = threadIdx.x >> 4;
+    const uint32_t o = blockIdx.x * RED_O + oq * 4;
     const uint32_t b = blockIdx.y;
-    if (o >= out) return;
-    float s = 0.f;
-    for (uint32_t u = 0; u < n_units; ++u) s += partial[((size_t)u * batch + b) * out + o];
-    store_out(y, y_dt, (size_t)b * ldy + o, s);
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (o < out) {
+        const bool vec = (out & 3u) == 0;   // rows of `partial` are 16-byte aligned
+        for (uint32_t u = slice; u < n_units; u += 16) {
+            const float *p = partial + ((size_t)u * batch + b) * out + o;
+            if (vec) {
+                const float4 v = *reinterpret_cast<const float4 *>(p);
+                s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            } else {
+                s.x += p[0];
+                if (o + 1 < out) s.y += p[1];
+                if (o + 2 < out) s.z += p[2];
+                if (o + 3 < out) s.w += p[3];
+            }
+        }
+    }
+    red[slice][oq] = s;
+    __syncthreads();
+    if (slice == 0 && o < out) {
+        float4 t = red[0][oq];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) {
+            const float4 v = red[i][oq];
+            t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+        }
+        const size_t base = (size_t)b * ldy + o;
+        store_out(y, y_dt, base, t.x);
+        if (o + 1 < out) store_out(y, y_dt, base + 1, t.y);
+        if (o + 2 < out) store_out(y, y_dt, base + 2, t.z);
+        if (o + 3 < out) store_out(y, y_dt, base + 3, t.w);
+    }
 }
 
 // ========================================================================
@@ -766,7 +799,7 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
     if (st != SKL_OK) return st;
     st = check_launch("gemv");
     if (st != SKL_OK) return st;
-    hipLaunchKernelGGL(k_reduce_partials, dim3((L->out + SKL_WG - 1) / SKL_WG, batch), dim3(SKL_WG), 0, stream, partial,
+    hipLaunchKernelGGL(k_reduce_partials, dim3((L->out + RED_O - 1) / RED_O, batch), dim3(SKL_WG), 0, stream, partial,
                        L->n_units, batch, L->out, y, (uint32_t)y_dt, ldy);
     return check_launch("gemv reduction");
 }

@@ -24,6 +24,8 @@ def build_library(verbose: bool = False) -> str:
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument", "-Wno-ignored-attributes",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    if os.environ.get("SKL_DEV_D4_ONLY"):
+        cmd += ["-DSKL_DEV_D4_ONLY"]      # development builds: only the d = 4 kernels
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     cmd += ["-o", LIB]
     if verbose:

@@ -4,8 +4,10 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -73,6 +75,76 @@ static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out)
     return SKL_OK;
 }
 
+// Decode plan for row sketches: cut the layer into n_sseg output segments x
+// n_bg block groups, one 1024-thread workgroup each and at most one workgroup
+// per CU.  The kernels are bound by LDS gathers, so what counts is the work of
+// the busiest workgroup (segment wave-units x 16-byte words per state row of
+// its blocks); among equal splits the one with fewer segments stages fewer
+// table bytes.
+static void plan_decode(const skl_desc_t *d, skl_plan *P)
+{
+    skl_layer &L = P->L;
+    const uint32_t units = (d->out_features + 63) / 64;
+    const uint32_t nblk = L.n_blocks;
+    std::vector<uint32_t> cum(nblk + 1, 0);
+    for (uint32_t b = 0; b < nblk; ++b) cum[b + 1] = cum[b] + P->bmeta[b].nb;
+    const uint32_t total_nb = cum[nblk];
+    uint32_t force_s = 0, force_g = 0;
+    if (const char *e = getenv("SKL_DECODE_SEGMENTS")) force_s = (uint32_t)atoi(e);
+    if (const char *e = getenv("SKL_DECODE_GROUPS")) force_g = (uint32_t)atoi(e);
+    // Cost model (microseconds, fitted to measurements on MI355X): a workgroup
+    // pays a start-up latency and then 0.033 us per (64-output wave unit x
+    // 16-byte word per state row) of its share; fewer than six active
+    // wavefronts cannot keep the LDS pipeline busy.  Workgroups are dealt
+    // round-robin to the 8 XCDs of 32 CUs each and a group's segments all land
+    // on one XCD, so ceil(G/8)*S workgroups compete for 32 CUs.
+    double best = 1e300;
+    uint32_t best_s = 1, best_g = 1;
+    for (uint32_t S = 1; S <= units; ++S) {
+        const uint32_t seg_units = (units + S - 1) / S;
+        if (seg_units > 16) continue;                       // one output per lane of a 1024-thread workgroup
+        if (force_s && S != force_s) continue;
+        const uint32_t g_min = (nblk + 47) / 48;            // at most 64 blocks in a group (48 on average)
+        for (uint32_t G = g_min; G <= nblk; ++G) {
+            if (force_g && G != std::max(std::min(force_g, nblk), g_min)) continue;
+            const uint32_t per_xcd = ((G + 7) / 8) * S;
+            const uint32_t rounds = (per_xcd + 31) / 32;
+            const double share = std::ceil((double)total_nb / G + 0.5 * P->bmeta[0].nb);   // groups end on block boundaries
+            const double t = rounds * (1.8 + 0.033 * std::max(seg_units, 6u) * share) + 0.02 * G;
+            if (t < best) { best = t; best_s = S; best_g = G; }
+        }
+    }
+    L.n_sseg = best_s;
+    L.n_bg = best_g;
+    L.n_wunits = units;
+    L.opl = ((units + best_s - 1) / best_s + 15) / 16;
+    // group boundaries: equal shares of the 16-byte words per state row
+    P->bg_start.assign(best_g + 1, 0);
+    uint32_t b = 0;
+    for (uint32_t g = 0; g < best_g; ++g) {
+        P->bg_start[g] = b;
+        const uint64_t target = (uint64_t)total_nb * (g + 1) / best_g;
+        while (b < nblk && (cum[b + 1] <= target || b == P->bg_start[g])) ++b;
+        if (nblk - b < best_g - 1 - g) b = nblk - (best_g - 1 - g);    // leave a block for every later group
+    }
+    P->bg_start[best_g] = nblk;
+    uint32_t max_chan = 0;
+    P->ginfo.assign(best_g, skl_group_info{});
+    for (uint32_t g = 0; g < best_g; ++g) {
+        const uint32_t lo = P->bg_start[g], hi = P->bg_start[g + 1];
+        const uint32_t c_lo = P->bmeta[lo].chan_off;
+        const uint32_t c_hi = hi < nblk ? P->bmeta[hi].chan_off : (uint32_t)P->chan.size();
+        max_chan = std::max(max_chan, c_hi - c_lo);
+        P->ginfo[g] = skl_group_info{lo, hi, c_lo, c_hi, P->bmeta[lo].K, P->bmeta[lo].rs,
+                                     P->bmeta[lo].table_off16, P->bmeta[lo].chan_off};
+    }
+    L.max_group_chan = max_chan;
+    // LDS: two table buffers + 32 activation rows of the group (batched decode)
+    const uint64_t act = (uint64_t)32 * (max_chan + 8) * 2;
+    L.two_bufs = 2ull * L.max_table_bytes + act + 256 <= SKL_LDS_HARD_BYTES ? 1 : 0;
+    L.n_units = L.n_bg;
+}
+
 // Row-sketch plan.  Returns false when some width is too large for any block
 // layout (then the per-weight path is tried).
 static bool plan_rows(const skl_desc_t *d, skl_plan *P)
@@ -128,6 +200,7 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
     // about three workgroups per CU on 256 CUs, split over blocks x output segments
     uint32_t seg = (768 + L.n_blocks / 2) / L.n_blocks;
     L.n_seg = std::min(std::max(seg, 1u), L.n_otiles);
+    plan_decode(d, P);
     return true;
 }
 
@@ -183,6 +256,7 @@ skl_status_t skl_make_plan(const skl_desc_t *d, skl_plan *P)
     if (L.path == 1) {
         L.off_bmeta = off;  off = align_up(off + P->bmeta.size() * sizeof(skl_block_meta), 256);
         L.off_chan = off;   off = align_up(off + P->chan.size() * sizeof(uint32_t), 256);
+        L.off_ginfo = off;  off = align_up(off + P->ginfo.size() * sizeof(skl_group_info), 256);
         L.off_tables = off; off = align_up(off + L.table_bytes, 256);
     } else {
         L.off_gmeta = off;  off = align_up(off + P->gmeta.size() * sizeof(skl_group_meta), 256);
@@ -231,6 +305,7 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
     if (L.path == 1) {
         memcpy(img.data() + L.off_bmeta, P.bmeta.data(), P.bmeta.size() * sizeof(skl_block_meta));
         memcpy(img.data() + L.off_chan, P.chan.data(), P.chan.size() * sizeof(uint32_t));
+        memcpy(img.data() + L.off_ginfo, P.ginfo.data(), P.ginfo.size() * sizeof(skl_group_info));
         // state offset of every input channel (one group per channel)
         std::vector<uint64_t> base(L.in + 1, 0);
         for (uint32_t j = 0; j < L.in; ++j) base[j + 1] = base[j] + (uint64_t)L.d * desc->group_width[j];

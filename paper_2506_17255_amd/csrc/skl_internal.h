@@ -9,6 +9,8 @@
 
 #define SKL_MAX_D 8
 #define SKL_WG 256            // threads per workgroup: 4 wavefronts of 64
+#define SKL_SWG 1024          // threads per workgroup of the streaming decode kernels
+#define SKL_N_CU 256          // compute units of the target (MI355X)
 #define SKL_NO_CHANNEL 0xFFFFFFFFu
 
 // LDS budgets.  A CU of gfx950 has 160 KiB of LDS; keeping a workgroup's
@@ -35,7 +37,15 @@ struct skl_block_meta {
     uint32_t nb;           // used words per state row (8*nb channels per block)
     uint32_t chan_off;     // first entry of the block in the channel list
                            // (= first packed activation column of the block)
-    uint32_t pad[3];
+    uint32_t pad0, pad1, pad2;
+};
+
+// One block group of the decode plan: consecutive blocks [b_lo, b_hi), their
+// channel-list range [c_lo, c_hi), and the first block's metadata so that a
+// workgroup needs one load before it can fetch its first table.
+struct skl_group_info {
+    uint32_t b_lo, b_hi, c_lo, c_hi;
+    uint32_t K0, rs0, table_off16_0, chan_off0;
 };
 
 struct skl_layer {
@@ -59,6 +69,14 @@ struct skl_layer {
     uint32_t n_packed = 0;          // channel-list length = sum of 8*nb over blocks
     uint32_t n_otiles = 0, n_seg = 0;
     uint64_t off_bmeta = 0, off_chan = 0, off_tables = 0;
+    // decode plan: workgroup (s, g) owns output segment s (a range of 64-output
+    // wave units) and block group g (consecutive channel blocks bg_start[g] ..
+    // bg_start[g+1]); n_sseg * n_bg workgroups of 1024 threads, one per CU
+    uint32_t n_sseg = 0, n_bg = 0, n_wunits = 0;
+    uint32_t max_group_chan = 0;    // most channel-list entries in one block group
+    uint32_t opl = 1;               // outputs per lane: ceil(segment length / 1024)
+    uint32_t two_bufs = 1;          // double-buffered tables fit in LDS
+    uint64_t off_ginfo = 0;
 };
 
 // The host-side plan: everything create() copies to the device.
@@ -68,6 +86,8 @@ struct skl_plan {
     std::vector<skl_group_meta> gmeta;
     std::vector<skl_block_meta> bmeta;
     std::vector<uint32_t> chan;
+    std::vector<uint32_t> bg_start;
+    std::vector<skl_group_info> ginfo;
 };
 
 // error text of the calling thread

@@ -15,6 +15,9 @@
 //                   every product x * w keeps its sign and value.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+#include <unordered_map>
+
 #include "skl_internal.h"
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
@@ -92,6 +95,8 @@ __device__ __forceinline__ uint16_t load_neg_half(const uint16_t *X, uint32_t x_
     return b ^ 0x8000u;
 }
 
+static_assert(sizeof(skl_block_meta) == 32, "block metadata is read as two 16-byte words");
+
 struct HashArgs {
     uint32_t A[SKL_MAX_D];
     uint32_t C[SKL_MAX_D];
@@ -136,132 +141,282 @@ __device__ __forceinline__ uint4 row_query8(const uint4 *tab, const uint32_t (&o
     return m;
 }
 
-// ---- decode GEMV, batch 1: lanes along outputs, packed dot products ----
+// ---- decode GEMV -----------------------------------------------------------
+// One 1024-thread workgroup per CU owns an output segment and a group of
+// consecutive channel blocks.  Lanes run along outputs; the block tables are
+// streamed through two LDS buffers (the next table is fetched into registers
+// while the current one is being gathered from), and the per-output sums stay
+// in registers across the blocks, so a workgroup emits one partial sum per
+// output for its whole block group.
+#define PF_WORDS 4          // prefetch registers per thread: tables up to 64 KiB
+
+struct StreamArgs {
+    RowArgs r;
+    const skl_group_info *ginfo;
+    uint32_t n_wunits;      // 64-output wave units of the layer
+    uint32_t n_sseg;        // output segments
+    uint32_t n_bg;          // block groups
+    uint32_t buf_words;     // 16-byte words per table buffer
+    uint32_t two_bufs;
+};
+
+
+struct StreamCtx {
+    uint32_t s, g, b_lo, b_hi, c_lo, c_hi, o_lo, o_hi;
+    uint32_t K0, rs0, toff0, chan_off0;
+    bool live;
+};
+
+// Workgroup id -> (segment, group).  Consecutive workgroup ids go to
+// different XCDs (8 of them, each with its own L2), so all segments of one
+// block group are given ids that are equal modulo 8: a group's tables are
+// then fetched from HBM into one L2 only.
+__device__ __forceinline__ StreamCtx stream_ctx(const StreamArgs &p)
+{
+    StreamCtx c;
+    const uint32_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const uint32_t s = slot % p.n_sseg;
+    c.s = s;
+    c.g = (slot / p.n_sseg) * 8 + xcd;
+    c.live = c.g < p.n_bg;
+    const skl_group_info gi = p.ginfo[min(c.g, p.n_bg - 1)];
+    c.b_lo = gi.b_lo; c.b_hi = gi.b_hi; c.c_lo = gi.c_lo; c.c_hi = gi.c_hi;
+    c.K0 = gi.K0; c.rs0 = gi.rs0; c.toff0 = gi.table_off16_0; c.chan_off0 = gi.chan_off0;
+    c.o_lo = (uint32_t)(((uint64_t)s * p.n_wunits) / p.n_sseg) * 64;
+    c.o_hi = min((uint32_t)(((uint64_t)(s + 1) * p.n_wunits) / p.n_sseg) * 64, p.r.out);
+    return c;
+}
+
+// Copy a table into LDS.  Up to four words per thread are requested before any
+// is stored, so the copy costs one memory latency, not one per word.
+__device__ __forceinline__ void stage_table_swg(uint4 *dst, const uint4 *src, uint32_t n16)
+{
+    if (n16 == 0) return;
+    for (uint32_t base = 0; base < n16; base += PF_WORDS * SKL_SWG) {
+        const uint32_t i0 = base + threadIdx.x, i1 = i0 + SKL_SWG, i2 = i1 + SKL_SWG, i3 = i2 + SKL_SWG;
+        const uint32_t last = n16 - 1;
+        const uint4 v0 = src[min(i0, last)], v1 = src[min(i1, last)], v2 = src[min(i2, last)], v3 = src[min(i3, last)];
+        if (i0 < n16) dst[i0] = v0;
+        if (i1 < n16) dst[i1] = v1;
+        if (i2 < n16) dst[i2] = v2;
+        if (i3 < n16) dst[i3] = v3;
+    }
+}
+
+// The loop over the blocks of a group.  `pre` runs after the first table has
+// been requested and before the first barrier (activation staging); `body`
+// is called once per block with that block's LDS table.  Block metadata is
+// read one block ahead of the table prefetch, which is itself one block ahead
+// of the gathers, so no load sits on the critical path after start-up.
+#define SKL_MAX_GROUP_BLOCKS 64   // blocks per group (metadata kept in LDS)
+
+template <int D, typename Pre, typename Body>
+__device__ __forceinline__ void stream_blocks(const StreamArgs &p, const StreamCtx &c, uint4 *buf0, uint4 *buf1, Pre &&pre,
+                                              Body &&body)
+{
+    // metadata of the group's blocks: one round of loads at start-up, LDS reads afterwards
+    __shared__ uint4 sm_meta[SKL_MAX_GROUP_BLOCKS][2];
+    const uint32_t nblk = c.b_hi - c.b_lo;
+    const bool meta_in_lds = nblk <= SKL_MAX_GROUP_BLOCKS;      // larger groups read it from memory
+    const uint4 *gmeta = reinterpret_cast<const uint4 *>(p.r.bmeta + c.b_lo);
+    if (meta_in_lds && threadIdx.x < 2 * nblk) (&sm_meta[0][0])[threadIdx.x] = gmeta[threadIdx.x];
+    uint32_t K = c.K0, rs = c.rs0, chan_off = c.chan_off0;
+    stage_table_swg(buf0, p.r.tables + c.toff0, D * K * rs);
+    pre();
+    __syncthreads();
+    for (uint32_t bi = 0; bi < nblk; ++bi) {
+        uint4 *cur = (bi & 1) ? buf1 : buf0;
+        uint4 *nxt = (bi & 1) ? buf0 : buf1;
+        const bool more = bi + 1 < nblk;
+        const uint32_t bn = min(bi + 1, nblk - 1);
+        const uint4 mn = meta_in_lds ? sm_meta[bn][0] : gmeta[2 * bn];              // {table_off16, K, rs, nb}
+        const uint32_t chan_offn = meta_in_lds ? sm_meta[bn][1].x : gmeta[2 * bn + 1].x;
+        const uint32_t Kn = mn.y, rsn = mn.z;
+        const uint32_t n_next = more ? D * Kn * rsn : 0;
+        const uint4 *src = p.r.tables + mn.x;
+        const bool prefetch = more && p.two_bufs && n_next <= PF_WORDS * SKL_SWG;
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        uint4 pf0 = zero, pf1 = zero, pf2 = zero, pf3 = zero;
+        const uint32_t i0 = threadIdx.x, i1 = i0 + SKL_SWG, i2 = i1 + SKL_SWG, i3 = i2 + SKL_SWG;
+        if (prefetch) {
+            // unconditional, clamped loads: the number of loads in flight is known when the stores wait for them
+            const uint32_t last = n_next - 1;
+            pf0 = src[min(i0, last)];
+            pf1 = src[min(i1, last)];
+            pf2 = src[min(i2, last)];
+            pf3 = src[min(i3, last)];
+        }
+        body(K, rs, chan_off, cur);
+        if (prefetch) {
+            if (i0 < n_next) nxt[i0] = pf0;
+            if (i1 < n_next) nxt[i1] = pf1;
+            if (i2 < n_next) nxt[i2] = pf2;
+            if (i3 < n_next) nxt[i3] = pf3;
+        } else if (more) {
+            __syncthreads();                 // everyone is done with the buffer that is overwritten
+            stage_table_swg(p.two_bufs ? nxt : cur, src, n_next);
+        }
+        __syncthreads();
+        K = Kn; rs = rsn; chan_off = chan_offn;
+    }
+}
+
+// dot product of one output with the 8*NB channels of a block (batch 1)
 template <int D, int RS>
-__device__ __forceinline__ void row_gemv1_body(const RowArgs &p, const skl_block_meta &bm, const uint4 *tab,
-                                               const uint4 *xs, float *partial_row)
+__device__ __forceinline__ float row_block_dot(const uint4 *tab, const uint32_t (&off)[D], const uint4 *xs)
 {
     constexpr int NB = RS == 1 ? 1 : RS - 1;
-    uint4 xr[NB];
+    float acc = 0.f;
 #pragma unroll
-    for (int c = 0; c < NB; ++c) xr[c] = xs[c];
-    const uint32_t seg = blockIdx.y;
-    const uint32_t lo = (uint32_t)(((uint64_t)seg * p.n_otiles) / p.n_seg);
-    const uint32_t hi = (uint32_t)(((uint64_t)(seg + 1) * p.n_otiles) / p.n_seg);
-    for (uint32_t tile = lo; tile < hi; ++tile) {
-        const uint32_t o = tile * SKL_WG + threadIdx.x;
-        if (o < p.out) {
-            uint32_t off[D];
-            row_offsets<D>(p.h, o, bm.K, RS, off);
-            float acc = 0.f;
-#pragma unroll
-            for (int c = 0; c < NB; ++c) {
-                const uint4 w = keys_to_neg_half8(row_query8<D>(tab, off, c));
-                acc = dot2_acc(w.x, xr[c].x, acc);
-                acc = dot2_acc(w.y, xr[c].y, acc);
-                acc = dot2_acc(w.z, xr[c].z, acc);
-                acc = dot2_acc(w.w, xr[c].w, acc);
-            }
-            partial_row[o] = acc;
-        }
+    for (int c = 0; c < NB; ++c) {
+        const uint4 w = keys_to_neg_half8(row_query8<D>(tab, off, c));
+        const uint4 xv = xs[c];
+        acc = dot2_acc(w.x, xv.x, acc);
+        acc = dot2_acc(w.y, xv.y, acc);
+        acc = dot2_acc(w.z, xv.z, acc);
+        acc = dot2_acc(w.w, xv.w, acc);
     }
+    return acc;
 }
 
-template <int D>
-__global__ __launch_bounds__(SKL_WG) void k_row_gemv1(RowArgs p, const uint16_t *__restrict__ x,
-                                                       float *__restrict__ partial)
+template <int D, int OPL>
+__global__ __launch_bounds__(SKL_SWG) void k_row_gemv1(StreamArgs p, const uint16_t *__restrict__ x,
+                                                        float *__restrict__ partial)
 {
-    const skl_block_meta bm = p.bmeta[blockIdx.x];
-    const uint32_t n16 = D * bm.K * bm.rs;
-    stage_table(smem, p.tables + bm.table_off16, n16);
-    uint16_t *xs = reinterpret_cast<uint16_t *>(smem + n16);
-    if (threadIdx.x < 8 * bm.nb) {
-        const uint32_t ch = p.chan[bm.chan_off + threadIdx.x];
-        xs[threadIdx.x] = ch != SKL_NO_CHANNEL ? (uint16_t)(x[ch] ^ 0x8000u) : (uint16_t)0;
+    const StreamCtx c = stream_ctx(p);
+    if (!c.live) return;
+    uint4 *buf0 = smem, *buf1 = smem + (p.two_bufs ? p.buf_words : 0);
+    uint16_t *xs = reinterpret_cast<uint16_t *>(smem + (p.two_bufs ? 2 : 1) * p.buf_words);
+    auto stage_x = [&]() {
+        for (uint32_t i = threadIdx.x; i < c.c_hi - c.c_lo; i += SKL_SWG) {
+            const uint32_t ch = p.r.chan[c.c_lo + i];
+            xs[i] = ch != SKL_NO_CHANNEL ? (uint16_t)(x[ch] ^ 0x8000u) : (uint16_t)0;
+        }
+    };
+    uint32_t o[OPL];
+    float acc[OPL];
+    uint32_t off[OPL][D];
+#pragma unroll
+    for (int i = 0; i < OPL; ++i) {
+        o[i] = c.o_lo + i * SKL_SWG + threadIdx.x;
+        acc[i] = 0.f;
     }
-    __syncthreads();
-    float *prow = partial + (size_t)blockIdx.x * p.out;
-    const uint4 *xs4 = reinterpret_cast<const uint4 *>(xs);
-    switch (bm.rs) {
-    case 9: row_gemv1_body<D, 9>(p, bm, smem, xs4, prow); break;
-    case 5: row_gemv1_body<D, 5>(p, bm, smem, xs4, prow); break;
-    case 3: row_gemv1_body<D, 3>(p, bm, smem, xs4, prow); break;
-    default: row_gemv1_body<D, 1>(p, bm, smem, xs4, prow); break;
-    }
+    uint32_t K_prev = 0, rs_prev = 0;
+    stream_blocks<D>(p, c, buf0, buf1, stage_x, [&](uint32_t K, uint32_t rs, uint32_t chan_off, const uint4 *tab) {
+        if (K != K_prev || rs != rs_prev) {
+#pragma unroll
+            for (int i = 0; i < OPL; ++i) row_offsets<D>(p.r.h, min(o[i], p.r.out - 1), K, rs, off[i]);
+            K_prev = K;
+            rs_prev = rs;
+        }
+        const uint4 *xb = reinterpret_cast<const uint4 *>(xs + (chan_off - c.c_lo));
+#pragma unroll
+        for (int i = 0; i < OPL; ++i) {
+            if (o[i] < c.o_hi) {
+                switch (rs) {
+                case 9: acc[i] += row_block_dot<D, 9>(tab, off[i], xb); break;
+                case 5: acc[i] += row_block_dot<D, 5>(tab, off[i], xb); break;
+                case 3: acc[i] += row_block_dot<D, 3>(tab, off[i], xb); break;
+                default: acc[i] += row_block_dot<D, 1>(tab, off[i], xb); break;
+                }
+            }
+        }
+    });
+    float *prow = partial + (size_t)c.g * p.r.out;
+#pragma unroll
+    for (int i = 0; i < OPL; ++i)
+        if (o[i] < c.o_hi) prow[o[i]] = acc[i];
 }
 
-// ---- decode GEMV, batch 2..16: reconstructed weights feed the matrix cores.
-// One 32x32x16 MFMA per 32 outputs x 16 channels; rows of the A operand are
-// the batch (rows >= batch are zero).
+// ---- decode GEMV, batch 2..16: the reconstructed weights feed the matrix
+// cores.  One 32x32x16 MFMA per 32 outputs x 16 channels; the rows of the A
+// operand are the batch (rows >= batch are zero).  A wavefront owns OG groups
+// of 32 outputs.
 #define XS_PAD 8   // halfs of padding per activation row in LDS
 
-template <int D, int RS>
-__device__ __forceinline__ void row_gemvN_body(const RowArgs &p, const skl_block_meta &bm, const uint4 *tab,
-                                               const uint16_t *xs, uint32_t batch, float *partial_blk)
+template <int D, int RS, int OG>
+__device__ __forceinline__ void row_block_mfma(const uint4 *tab, const uint32_t (&off)[OG][D], const uint16_t *xrow,
+                                               uint32_t q, uint32_t n_groups, float16v (&acc)[OG])
 {
     constexpr int NB = RS == 1 ? 1 : RS - 1;
     constexpr int NS = (NB + 1) / 2;
-    constexpr int XS = 8 * NB + XS_PAD;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t n = lane & 31, q = lane >> 5;
     const uint4 zero = make_uint4(0, 0, 0, 0);
-    uint4 areg[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         const uint32_t c = 2 * s + q;
-        areg[s] = (NB > 1 || c < NB) ? *reinterpret_cast<const uint4 *>(xs + n * XS + c * 8) : zero;
-    }
-    const uint32_t seg = blockIdx.y;
-    const uint32_t o_lo = (uint32_t)(((uint64_t)seg * p.n_otiles) / p.n_seg) * SKL_WG;
-    const uint32_t o_hi = min((uint32_t)(((uint64_t)(seg + 1) * p.n_otiles) / p.n_seg) * SKL_WG, p.out);
-    for (uint32_t og = o_lo + wave * 32; og < o_hi; og += 128) {
-        const uint32_t o = og + n;
-        uint32_t off[D];
-        row_offsets<D>(p.h, min(o, p.out - 1), bm.K, RS, off);
-        float16v acc = {0.f};
+        const bool live = NB > 1 || c < NB;
+        const uint4 a = live ? *reinterpret_cast<const uint4 *>(xrow + (NB > 1 ? c : 0) * 8) : zero;
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            const uint32_t c = 2 * s + q;
-            uint4 b = zero;
-            if (NB > 1 || c < NB) b = keys_to_neg_half8(row_query8<D>(tab, off, NB > 1 ? c : 0));
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, areg[s]),
-                                                          __builtin_bit_cast(half8v, b), acc, 0, 0, 0);
-        }
-        if (o < p.out) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const uint32_t m = (i >> 2) * 8 + q * 4 + (i & 3);   // row of the 32x32 result held in acc[i]
-                if (m < batch) partial_blk[(size_t)m * p.out + o] = acc[i];
+        for (int g = 0; g < OG; ++g) {
+            if ((uint32_t)g < n_groups) {
+                uint4 b = zero;
+                if (live) b = keys_to_neg_half8(row_query8<D>(tab, off[g], NB > 1 ? c : 0));
+                acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b),
+                                                                 acc[g], 0, 0, 0);
             }
         }
     }
 }
 
-template <int D>
-__global__ __launch_bounds__(SKL_WG) void k_row_gemvN(RowArgs p, const uint16_t *__restrict__ x, uint32_t ldx,
-                                                       uint32_t batch, float *__restrict__ partial)
+template <int D, int OG>
+__global__ __launch_bounds__(SKL_SWG) void k_row_gemvN(StreamArgs p, const uint16_t *__restrict__ x, uint32_t ldx,
+                                                        uint32_t batch, float *__restrict__ partial)
 {
-    const skl_block_meta bm = p.bmeta[blockIdx.x];
-    const uint32_t n16 = D * bm.K * bm.rs;
-    stage_table(smem, p.tables + bm.table_off16, n16);
-    uint16_t *xs = reinterpret_cast<uint16_t *>(smem + n16);
-    const uint32_t nch = 8 * bm.nb, XS = nch + XS_PAD;
-    for (uint32_t i = threadIdx.x; i < 32 * nch; i += SKL_WG) {
-        const uint32_t b = i / nch, c = i - b * nch;
-        uint16_t v = 0;
-        if (b < batch) {
-            const uint32_t ch = p.chan[bm.chan_off + c];
-            if (ch != SKL_NO_CHANNEL) v = x[(size_t)b * ldx + ch] ^ 0x8000u;
+    const StreamCtx c = stream_ctx(p);
+    if (!c.live) return;
+    uint4 *buf0 = smem, *buf1 = smem + (p.two_bufs ? p.buf_words : 0);
+    uint16_t *xs = reinterpret_cast<uint16_t *>(smem + (p.two_bufs ? 2 : 1) * p.buf_words);
+    const uint32_t nch = c.c_hi - c.c_lo, XS = nch + XS_PAD;     // 32 rows of XS halfs
+    auto stage_x = [&]() {
+        for (uint32_t i = threadIdx.x; i < 32 * nch; i += SKL_SWG) {
+            const uint32_t b = i / nch, cc = i - b * nch;
+            uint16_t v = 0;
+            if (b < batch) {
+                const uint32_t ch = p.r.chan[c.c_lo + cc];
+                if (ch != SKL_NO_CHANNEL) v = x[(size_t)b * ldx + ch] ^ 0x8000u;
+            }
+            xs[b * XS + cc] = v;
         }
-        xs[b * XS + c] = v;
-    }
-    __syncthreads();
-    float *pblk = partial + (size_t)blockIdx.x * batch * p.out;
-    switch (bm.rs) {
-    case 9: row_gemvN_body<D, 9>(p, bm, smem, xs, batch, pblk); break;
-    case 5: row_gemvN_body<D, 5>(p, bm, smem, xs, batch, pblk); break;
-    case 3: row_gemvN_body<D, 3>(p, bm, smem, xs, batch, pblk); break;
-    default: row_gemvN_body<D, 1>(p, bm, smem, xs, batch, pblk); break;
+    };
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t n = lane & 31, q = lane >> 5;
+    // output groups of this wavefront: o = o_lo + g*512 + wave*32 + n
+    uint32_t n_groups = 0;
+#pragma unroll
+    for (int g = 0; g < OG; ++g)
+        if (c.o_lo + g * 512 + wave * 32 < c.o_hi) n_groups = g + 1;
+    float16v acc[OG];
+    uint32_t off[OG][D];
+#pragma unroll
+    for (int g = 0; g < OG; ++g) acc[g] = (float16v){0.f};
+    uint32_t K_prev = 0, rs_prev = 0;
+    stream_blocks<D>(p, c, buf0, buf1, stage_x, [&](uint32_t K, uint32_t rs, uint32_t chan_off, const uint4 *tab) {
+        if (K != K_prev || rs != rs_prev) {
+#pragma unroll
+            for (int g = 0; g < OG; ++g)
+                row_offsets<D>(p.r.h, min(c.o_lo + g * 512 + wave * 32 + n, p.r.out - 1), K, rs, off[g]);
+            K_prev = K;
+            rs_prev = rs;
+        }
+        const uint16_t *xrow = xs + n * XS + (chan_off - c.c_lo);
+        switch (rs) {
+        case 9: row_block_mfma<D, 9, OG>(tab, off, xrow, q, n_groups, acc); break;
+        case 5: row_block_mfma<D, 5, OG>(tab, off, xrow, q, n_groups, acc); break;
+        case 3: row_block_mfma<D, 3, OG>(tab, off, xrow, q, n_groups, acc); break;
+        default: row_block_mfma<D, 1, OG>(tab, off, xrow, q, n_groups, acc); break;
+        }
+    });
+    float *pblk = partial + (size_t)c.g * batch * p.r.out;
+#pragma unroll
+    for (int g = 0; g < OG; ++g) {
+        const uint32_t o = c.o_lo + g * 512 + wave * 32 + n;
+        if (o < c.o_hi) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t m = (i >> 2) * 8 + q * 4 + (i & 3);   // row of the 32x32 result held in acc[g][i]
+                if (m < batch) pblk[(size_t)m * p.r.out + o] = acc[g][i];
+            }
+        }
     }
 }
 
@@ -688,20 +843,29 @@ static skl_status_t check_launch(const char *what)
     return SKL_OK;
 }
 
+// Kernels that need more than 64 KiB of dynamic LDS must be told so once.
 template <typename K>
 static skl_status_t allow_lds(K kernel, size_t bytes)
 {
-    if (bytes > 65536) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-        if (e != hipSuccess) {
-            skl_set_error("cannot reserve %zu bytes of LDS: %s", bytes, hipGetErrorString(e));
-            return SKL_ERR_HIP;
-        }
+    if (bytes <= 65536) return SKL_OK;
+    static std::mutex mu;
+    static std::unordered_map<const void *, size_t> granted;
+    const void *fn = reinterpret_cast<const void *>(kernel);
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = granted.find(fn);
+    if (it != granted.end() && it->second >= bytes) return SKL_OK;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) {
+        skl_set_error("cannot reserve %zu bytes of LDS: %s", bytes, hipGetErrorString(e));
+        return SKL_ERR_HIP;
     }
+    granted[fn] = bytes;
     return SKL_OK;
 }
 
+#ifdef SKL_DEV_D4_ONLY
+#define DISPATCH_D(d, CALL) { constexpr int D = 4; CALL; }
+#else
 #define DISPATCH_D(d, CALL)                                         \
     switch (d) {                                                    \
     case 1: { constexpr int D = 1; CALL; } break;                   \
@@ -713,6 +877,7 @@ static skl_status_t allow_lds(K kernel, size_t bytes)
     case 7: { constexpr int D = 7; CALL; } break;                   \
     default: { constexpr int D = 8; CALL; } break;                  \
     }
+#endif
 
 static inline size_t tile_key_words(const skl_layer *L) { return ((size_t)L->d * L->max_K * 2 + 15) / 16; }
 
@@ -758,21 +923,33 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
     float *partial = static_cast<float *>(ws);
     skl_status_t st = SKL_OK;
     if (L->path == 1) {
-        const RowArgs a = make_row_args(L);
-        const dim3 grid(L->n_blocks, L->n_seg);
+        StreamArgs a;
+        a.r = make_row_args(L);
+        a.ginfo = reinterpret_cast<const skl_group_info *>(L->dev + L->off_ginfo);
+        a.n_wunits = L->n_wunits; a.n_sseg = L->n_sseg; a.n_bg = L->n_bg; a.buf_words = L->max_table_bytes / 16;
+        a.two_bufs = L->two_bufs;
+        const dim3 grid(8 * ((L->n_bg + 7) / 8) * L->n_sseg);
+        const size_t tab_bytes = (size_t)(L->two_bufs ? 2 : 1) * L->max_table_bytes;
         if (batch == 1) {
-            const size_t lds = (size_t)L->max_table_bytes + 64 * sizeof(uint16_t);
-            DISPATCH_D(L->d, {
-                st = allow_lds(k_row_gemv1<D>, lds);
-                if (st == SKL_OK) hipLaunchKernelGGL(k_row_gemv1<D>, grid, dim3(SKL_WG), lds, stream, a, x, partial);
-            });
+            const size_t lds = tab_bytes + (size_t)L->max_group_chan * sizeof(uint16_t) + 16;
+#define LAUNCH1(OPL)                                                                                               \
+    DISPATCH_D(L->d, {                                                                                             \
+        st = allow_lds(k_row_gemv1<D, OPL>, lds);                                                                  \
+        if (st == SKL_OK)                                                                                          \
+            hipLaunchKernelGGL((k_row_gemv1<D, OPL>), grid, dim3(SKL_SWG), lds, stream, a, x, partial);            \
+    })
+            LAUNCH1(1)
+#undef LAUNCH1
         } else {
-            const size_t lds = (size_t)L->max_table_bytes + 32 * (64 + XS_PAD) * sizeof(uint16_t);
-            DISPATCH_D(L->d, {
-                st = allow_lds(k_row_gemvN<D>, lds);
-                if (st == SKL_OK)
-                    hipLaunchKernelGGL(k_row_gemvN<D>, grid, dim3(SKL_WG), lds, stream, a, x, ldx, batch, partial);
-            });
+            const size_t lds = tab_bytes + (size_t)32 * (L->max_group_chan + XS_PAD) * sizeof(uint16_t) + 16;
+#define LAUNCHN(OG)                                                                                                \
+    DISPATCH_D(L->d, {                                                                                             \
+        st = allow_lds(k_row_gemvN<D, OG>, lds);                                                                   \
+        if (st == SKL_OK)                                                                                          \
+            hipLaunchKernelGGL((k_row_gemvN<D, OG>), grid, dim3(SKL_SWG), lds, stream, a, x, ldx, batch, partial); \
+    })
+            LAUNCHN(2)     // two groups of 512 outputs per segment
+#undef LAUNCHN
         }
     } else {
         const TileArgs a = make_tile_args(L);

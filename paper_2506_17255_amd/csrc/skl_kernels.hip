@@ -50,6 +50,34 @@ __device__ __forceinline__ uint4 keys_to_neg_half8(uint4 k)
     return make_uint4(keys_to_neg_half2(k.x), keys_to_neg_half2(k.y), keys_to_neg_half2(k.z), keys_to_neg_half2(k.w));
 }
 
+// value or zero, component by component (a select of whole 16-byte objects
+// would be turned into a select of addresses and spill the object to memory)
+__device__ __forceinline__ uint4 keep_if(bool keep, uint4 v)
+{
+    return make_uint4(keep ? v.x : 0u, keep ? v.y : 0u, keep ? v.z : 0u, keep ? v.w : 0u);
+}
+
+// Asynchronous copy global -> LDS without passing through registers
+// (global_load_lds_dwordx4): a wavefront moves 64 consecutive 16-byte words,
+// lane i's word landing at dst + i.  All NWAVES wavefronts of the workgroup
+// take part.  The copy is complete after wait_async_copies() by the issuing
+// wavefront (and a barrier for everybody else).
+typedef __attribute__((address_space(3))) void lds_void;
+
+template <int NWAVES>
+__device__ __forceinline__ void copy_to_lds_async(uint4 *dst, const uint4 *src, uint32_t n16)
+{
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (uint32_t base = wave * 64; base < n16; base += 64 * NWAVES)
+        if (base + lane < n16)
+            __builtin_amdgcn_global_load_lds(static_cast<const void *>(src + base + lane), (lds_void *)(dst + base), 16, 0, 0);
+}
+
+__device__ __forceinline__ void wait_async_copies()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), other counters untouched
+}
+
 // Eq. 3: index inside a sketch row of width K; Kq = K << 8 (< 2^24).  Only the
 // low 24 bits of t count, so t may be kept as a wrapping 32-bit number.
 __device__ __forceinline__ uint32_t select_index(uint32_t t, uint32_t Kq)
@@ -148,8 +176,6 @@ __device__ __forceinline__ uint4 row_query8(const uint4 *tab, const uint32_t (&o
 // while the current one is being gathered from), and the per-output sums stay
 // in registers across the blocks, so a workgroup emits one partial sum per
 // output for its whole block group.
-#define PF_WORDS 4          // prefetch registers per thread: tables up to 64 KiB
-
 struct StreamArgs {
     RowArgs r;
     const skl_group_info *ginfo;
@@ -187,33 +213,17 @@ __device__ __forceinline__ StreamCtx stream_ctx(const StreamArgs &p)
     return c;
 }
 
-// Copy a table into LDS.  Up to four words per thread are requested before any
-// is stored, so the copy costs one memory latency, not one per word.
-__device__ __forceinline__ void stage_table_swg(uint4 *dst, const uint4 *src, uint32_t n16)
-{
-    if (n16 == 0) return;
-    for (uint32_t base = 0; base < n16; base += PF_WORDS * SKL_SWG) {
-        const uint32_t i0 = base + threadIdx.x, i1 = i0 + SKL_SWG, i2 = i1 + SKL_SWG, i3 = i2 + SKL_SWG;
-        const uint32_t last = n16 - 1;
-        const uint4 v0 = src[min(i0, last)], v1 = src[min(i1, last)], v2 = src[min(i2, last)], v3 = src[min(i3, last)];
-        if (i0 < n16) dst[i0] = v0;
-        if (i1 < n16) dst[i1] = v1;
-        if (i2 < n16) dst[i2] = v2;
-        if (i3 < n16) dst[i3] = v3;
-    }
-}
-
 // The loop over the blocks of a group.  `pre` runs after the first table has
 // been requested and before the first barrier (activation staging); `body`
-// is called once per block with that block's LDS table.  Block metadata is
-// read one block ahead of the table prefetch, which is itself one block ahead
-// of the gathers, so no load sits on the critical path after start-up.
-#define SKL_MAX_GROUP_BLOCKS 64   // blocks per group (metadata kept in LDS)
+// is called once per block with that block's LDS table.  While a block is
+// being gathered from, the next block's table streams into the other buffer.
+#define SKL_MAX_GROUP_BLOCKS 64   // blocks per group whose metadata is kept in LDS
 
 template <int D, typename Pre, typename Body>
 __device__ __forceinline__ void stream_blocks(const StreamArgs &p, const StreamCtx &c, uint4 *buf0, uint4 *buf1, Pre &&pre,
                                               Body &&body)
 {
+    constexpr int NW = SKL_SWG / 64;
     // metadata of the group's blocks: one round of loads at start-up, LDS reads afterwards
     __shared__ uint4 sm_meta[SKL_MAX_GROUP_BLOCKS][2];
     const uint32_t nblk = c.b_hi - c.b_lo;
@@ -221,41 +231,25 @@ __device__ __forceinline__ void stream_blocks(const StreamArgs &p, const StreamC
     const uint4 *gmeta = reinterpret_cast<const uint4 *>(p.r.bmeta + c.b_lo);
     if (meta_in_lds && threadIdx.x < 2 * nblk) (&sm_meta[0][0])[threadIdx.x] = gmeta[threadIdx.x];
     uint32_t K = c.K0, rs = c.rs0, chan_off = c.chan_off0;
-    stage_table_swg(buf0, p.r.tables + c.toff0, D * K * rs);
+    copy_to_lds_async<NW>(buf0, p.r.tables + c.toff0, D * K * rs);
     pre();
+    wait_async_copies();
     __syncthreads();
     for (uint32_t bi = 0; bi < nblk; ++bi) {
-        uint4 *cur = (bi & 1) ? buf1 : buf0;
-        uint4 *nxt = (bi & 1) ? buf0 : buf1;
+        uint4 *cur = (bi & 1) && p.two_bufs ? buf1 : buf0;
+        uint4 *nxt = (bi & 1) || !p.two_bufs ? buf0 : buf1;
         const bool more = bi + 1 < nblk;
         const uint32_t bn = min(bi + 1, nblk - 1);
         const uint4 mn = meta_in_lds ? sm_meta[bn][0] : gmeta[2 * bn];              // {table_off16, K, rs, nb}
         const uint32_t chan_offn = meta_in_lds ? sm_meta[bn][1].x : gmeta[2 * bn + 1].x;
         const uint32_t Kn = mn.y, rsn = mn.z;
-        const uint32_t n_next = more ? D * Kn * rsn : 0;
-        const uint4 *src = p.r.tables + mn.x;
-        const bool prefetch = more && p.two_bufs && n_next <= PF_WORDS * SKL_SWG;
-        const uint4 zero = make_uint4(0, 0, 0, 0);
-        uint4 pf0 = zero, pf1 = zero, pf2 = zero, pf3 = zero;
-        const uint32_t i0 = threadIdx.x, i1 = i0 + SKL_SWG, i2 = i1 + SKL_SWG, i3 = i2 + SKL_SWG;
-        if (prefetch) {
-            // unconditional, clamped loads: the number of loads in flight is known when the stores wait for them
-            const uint32_t last = n_next - 1;
-            pf0 = src[min(i0, last)];
-            pf1 = src[min(i1, last)];
-            pf2 = src[min(i2, last)];
-            pf3 = src[min(i3, last)];
-        }
+        if (more && p.two_bufs) copy_to_lds_async<NW>(nxt, p.r.tables + mn.x, D * Kn * rsn);
         body(K, rs, chan_off, cur);
-        if (prefetch) {
-            if (i0 < n_next) nxt[i0] = pf0;
-            if (i1 < n_next) nxt[i1] = pf1;
-            if (i2 < n_next) nxt[i2] = pf2;
-            if (i3 < n_next) nxt[i3] = pf3;
-        } else if (more) {
-            __syncthreads();                 // everyone is done with the buffer that is overwritten
-            stage_table_swg(p.two_bufs ? nxt : cur, src, n_next);
+        if (more && !p.two_bufs) {
+            __syncthreads();                 // everyone is done with the only buffer
+            copy_to_lds_async<NW>(nxt, p.r.tables + mn.x, D * Kn * rsn);
         }
+        wait_async_copies();
         __syncthreads();
         K = Kn; rs = rsn; chan_off = chan_offn;
     }
@@ -345,12 +339,11 @@ __device__ __forceinline__ void row_block_mfma(const uint4 *tab, const uint32_t 
     for (int s = 0; s < NS; ++s) {
         const uint32_t c = 2 * s + q;
         const bool live = NB > 1 || c < NB;
-        const uint4 a = live ? *reinterpret_cast<const uint4 *>(xrow + (NB > 1 ? c : 0) * 8) : zero;
+        const uint4 a = keep_if(live, *reinterpret_cast<const uint4 *>(xrow + (NB > 1 ? c : 0) * 8));
 #pragma unroll
         for (int g = 0; g < OG; ++g) {
             if ((uint32_t)g < n_groups) {
-                uint4 b = zero;
-                if (live) b = keys_to_neg_half8(row_query8<D>(tab, off[g], NB > 1 ? c : 0));
+                const uint4 b = keep_if(live, keys_to_neg_half8(row_query8<D>(tab, off[g], NB > 1 ? c : 0)));
                 acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b),
                                                                  acc[g], 0, 0, 0);
             }
@@ -478,95 +471,153 @@ __global__ __launch_bounds__(SKL_WG) void k_pack_activations(const uint16_t *__r
     Xp[(size_t)t * n_packed + pcol] = ch != SKL_NO_CHANNEL ? load_neg_half(X, x_dt, (size_t)t * ldx + ch) : (uint16_t)0;
 }
 
-#define GEMM_MT 128
-#define GEMM_NT 128
-#define GEMM_AS 72   // halfs per staged activation row: 64 + 8 (row stride of 9 words)
+// Main kernel.  A workgroup of four wavefronts owns 256 tokens x (128*NF)
+// outputs; wavefront w owns all 256 tokens of its own 32*NF outputs, so every
+// reconstructed weight fragment is built exactly once per workgroup and feeds
+// eight 32x32x16 MFMAs straight from registers.  The channel blocks are walked
+// in units of up to four 16-byte words (32 channels).  The activations of the
+// next unit and the table of the next block stream into the other LDS buffers
+// (asynchronous global -> LDS copies) while the current unit runs.
+//
+// Activation tile in LDS: 256 rows of 4 words; word c of row r sits at position
+// c ^ ((r >> 2) & 3), so the 16 rows a quarter-wavefront reads fall into 16
+// different bank groups without any padding (the copy lands lane i's word at
+// base + i, so the swizzle is applied to the global address instead).
+#define GM_MT 256            // tokens per workgroup
 
-template <int D, int RS>
-__device__ __forceinline__ void row_gemm_block(const uint4 *tab, const uint16_t *As, const uint32_t (&off)[2][D],
-                                               uint32_t wm, uint32_t n, uint32_t q, float16v (&acc)[2][2])
+// One unit: nc (1..4) words of 8 channels.  Lanes 0..31 take the even words,
+// lanes 32..63 the odd ones; a lane without a word contributes zeros.  A
+// single code path for every nc keeps the 128*NF accumulators in place.
+template <int D, int NF>
+__device__ __forceinline__ void gemm_unit(const uint4 *tab, const uint32_t (&off)[NF][D], const uint4 *As, uint32_t c_base,
+                                          uint32_t nc, uint32_t n, uint32_t q, float16v (&acc)[8][NF])
 {
-    constexpr int NB = RS == 1 ? 1 : RS - 1;
-    constexpr int NS = (NB + 1) / 2;
-    const uint4 zero = make_uint4(0, 0, 0, 0);
+    const uint32_t ns = (nc + 1) >> 1;
+    for (uint32_t s = 0; s < ns; ++s) {
+        const uint32_t cw = 2 * s + q;
+        const bool live = cw < nc;
+        const uint32_t cl = min(cw, nc - 1);
+        uint4 b[NF];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        const uint32_t c = 2 * s + q;
-        uint4 a[2], b[2];
+        for (int nf = 0; nf < NF; ++nf)
+            b[nf] = keep_if(live, keys_to_neg_half8(row_query8<D>(tab, off[nf], c_base + cl)));
 #pragma unroll
-        for (int f = 0; f < 2; ++f) {
-            a[f] = zero;
-            b[f] = zero;
-            if (NB > 1 || c < NB) {
-                a[f] = *reinterpret_cast<const uint4 *>(As + (wm * 64 + f * 32 + n) * GEMM_AS + c * 8);
-                b[f] = keys_to_neg_half8(row_query8<D>(tab, off[f], NB > 1 ? c : 0));
-            }
-        }
+        for (int mf = 0; mf < 8; ++mf) {
+            const uint32_t m = mf * 32 + n;
+            const uint4 a = keep_if(live, As[m * 4 + (cl ^ ((m >> 2) & 3))]);
 #pragma unroll
-        for (int mf = 0; mf < 2; ++mf)
-#pragma unroll
-            for (int nf = 0; nf < 2; ++nf)
-                acc[mf][nf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a[mf]),
+            for (int nf = 0; nf < NF; ++nf)
+                acc[mf][nf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a),
                                                                       __builtin_bit_cast(half8v, b[nf]), acc[mf][nf], 0, 0, 0);
+        }
     }
 }
 
-template <int D>
-__global__ __launch_bounds__(SKL_WG) void k_row_gemm(RowArgs p, const uint16_t *__restrict__ Xp, uint32_t tokens,
-                                                      uint32_t n_packed, void *__restrict__ Y, uint32_t y_dt,
-                                                      uint32_t ldy, uint32_t table_words)
+// asynchronous copy of one unit of activations: rows t0 .. t0+255 (clamped to
+// the last token), words col0/8 .. col0/8 + 3 (clamped to the nc valid ones)
+__device__ __forceinline__ void copy_activations_async(uint4 *As, const uint16_t *Xp, uint32_t n_packed, uint32_t t0,
+                                                       uint32_t tokens, uint32_t col0, uint32_t nc)
 {
-    uint4 *tab = smem;
-    uint16_t *As = reinterpret_cast<uint16_t *>(smem + table_words);
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t wm = wave >> 1, wn = wave & 1;
-    const uint32_t n = lane & 31, q = lane >> 5;
-    const uint32_t t0 = blockIdx.y * GEMM_MT, o0 = blockIdx.x * GEMM_NT;
-    float16v acc[2][2];
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = (float16v){0.f};
-    uint32_t off[2][D];
-    uint32_t K_prev = 0, rs_prev = 0;
-    for (uint32_t blk = 0; blk < p.n_blocks; ++blk) {
-        const skl_block_meta bm = p.bmeta[blk];
-        __syncthreads();
-        stage_table(tab, p.tables + bm.table_off16, D * bm.K * bm.rs);
-        const uint32_t nb = bm.nb;
-        for (uint32_t i = threadIdx.x; i < GEMM_MT * nb; i += SKL_WG) {
-            const uint32_t r = i / nb, c = i - r * nb;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (t0 + r < tokens)
-                v = *reinterpret_cast<const uint4 *>(Xp + (size_t)(t0 + r) * n_packed + bm.chan_off + c * 8);
-            *reinterpret_cast<uint4 *>(As + r * GEMM_AS + c * 8) = v;
-        }
-        __syncthreads();
-        if (bm.K != K_prev || bm.rs != rs_prev) {
-#pragma unroll
-            for (int f = 0; f < 2; ++f)
-                row_offsets<D>(p.h, min(o0 + wn * 64 + f * 32 + n, p.out - 1), bm.K, bm.rs, off[f]);
-            K_prev = bm.K;
-            rs_prev = bm.rs;
-        }
-        switch (bm.rs) {
-        case 9: row_gemm_block<D, 9>(tab, As, off, wm, n, q, acc); break;
-        case 5: row_gemm_block<D, 5>(tab, As, off, wm, n, q, acc); break;
-        case 3: row_gemm_block<D, 3>(tab, As, off, wm, n, q, acc); break;
-        default: row_gemm_block<D, 1>(tab, As, off, wm, n, q, acc); break;
-        }
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t r = (wave * 4 + j) * 16 + (lane >> 2);        // 16 rows per wavefront copy
+        const uint32_t c = min((lane & 3) ^ ((r >> 2) & 3), nc - 1);
+        const uint16_t *src = Xp + (size_t)min(t0 + r, tokens - 1) * n_packed + col0 + c * 8;
+        __builtin_amdgcn_global_load_lds(static_cast<const void *>(src), (lds_void *)(As + (wave * 4 + j) * 64), 16, 0, 0);
     }
+}
+
+// epilogue: acc[mf][nf][i] is the output of token t0 + mf*32 + (i/4)*8 + q*4 + i%4
+// and output channel o_wave + nf*32 + n; one rounding to the output type
+template <int NF, int DT>
+__device__ __forceinline__ void gemm_store(const float16v (&acc)[8][NF], void *Y, uint32_t ldy, uint32_t t0, uint32_t tokens,
+                                           uint32_t o_wave, uint32_t out, uint32_t n, uint32_t q)
+{
 #pragma unroll
-    for (int mf = 0; mf < 2; ++mf)
+    for (int nf = 0; nf < NF; ++nf) {
+        const uint32_t o = o_wave + nf * 32 + n;
+        if (o >= out) continue;
 #pragma unroll
-        for (int nf = 0; nf < 2; ++nf) {
-            const uint32_t o = o0 + wn * 64 + nf * 32 + n;
+        for (int mf = 0; mf < 8; ++mf) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const uint32_t t = t0 + wm * 64 + mf * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
-                if (t < tokens && o < p.out) store_out(Y, y_dt, (size_t)t * ldy + o, acc[mf][nf][i]);
+                const uint32_t t = t0 + mf * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
+                if (t < tokens) {
+                    const size_t idx = (size_t)t * ldy + o;
+                    const float v = acc[mf][nf][i];
+                    if (DT == SKL_F32) static_cast<float *>(Y)[idx] = v;
+                    else if (DT == SKL_F16) static_cast<uint16_t *>(Y)[idx] = float_to_half_bits(v);
+                    else static_cast<uint16_t *>(Y)[idx] = float_to_bf16_bits(v);
+                }
             }
         }
+    }
+}
+
+template <int D, int NF>
+__global__ __launch_bounds__(SKL_WG) void k_row_gemm(RowArgs p, const uint16_t *__restrict__ Xp, uint32_t tokens,
+                                                      uint32_t n_packed, void *__restrict__ Y, uint32_t y_dt,
+                                                      uint32_t ldy, uint32_t table_words, uint32_t two_tabs)
+{
+    uint4 *tab_cur = smem;
+    uint4 *tab_nxt = smem + (two_tabs ? table_words : 0);
+    uint4 *A_cur = smem + (two_tabs ? 2 : 1) * table_words;
+    uint4 *A_nxt = A_cur + GM_MT * 4;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t n = lane & 31, q = lane >> 5;
+    const uint32_t t0 = blockIdx.y * GM_MT;
+    const uint32_t o_wave = blockIdx.x * (128 * NF) + wave * (32 * NF);
+
+    float16v acc[8][NF];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < NF; ++j) acc[i][j] = (float16v){0.f};
+
+    const skl_block_meta *bmeta = p.bmeta;
+    uint32_t K = bmeta[0].K, rs = bmeta[0].rs, nb = bmeta[0].nb, chan_off = bmeta[0].chan_off;
+    copy_to_lds_async<4>(tab_cur, p.tables + bmeta[0].table_off16, D * K * rs);
+    copy_activations_async(A_cur, Xp, n_packed, t0, tokens, chan_off, min(nb, 4u));
+    wait_async_copies();
+    __syncthreads();
+
+    uint32_t off[NF][D];
+    uint32_t K_prev = 0, rs_prev = 0;
+    for (uint32_t blk = 0; blk < p.n_blocks; ++blk) {
+        const bool more_blk = blk + 1 < p.n_blocks;
+        const uint32_t bn = more_blk ? blk + 1 : blk;
+        const uint32_t Kn = bmeta[bn].K, rsn = bmeta[bn].rs, nbn = bmeta[bn].nb, chan_offn = bmeta[bn].chan_off;
+        const uint4 *tsrc = p.tables + bmeta[bn].table_off16;
+        if (more_blk && two_tabs) copy_to_lds_async<4>(tab_nxt, tsrc, D * Kn * rsn);
+        if (K != K_prev || rs != rs_prev) {
+#pragma unroll
+            for (int nf = 0; nf < NF; ++nf) row_offsets<D>(p.h, min(o_wave + nf * 32 + n, p.out - 1), K, rs, off[nf]);
+            K_prev = K;
+            rs_prev = rs;
+        }
+        const uint32_t n_half = nb > 4 ? 2 : 1;
+        for (uint32_t h = 0; h < n_half; ++h) {
+            const bool last_half = h + 1 == n_half;
+            if (!last_half) copy_activations_async(A_nxt, Xp, n_packed, t0, tokens, chan_off + 32 * (h + 1), nb - 4 * (h + 1));
+            else if (more_blk) copy_activations_async(A_nxt, Xp, n_packed, t0, tokens, chan_offn, min(nbn, 4u));
+            const uint32_t nc = min(nb - 4 * h, 4u);
+            gemm_unit<D, NF>(tab_cur, off, A_cur, 4 * h, nc, n, q, acc);
+            if (last_half && more_blk && !two_tabs) {
+                __syncthreads();                 // single table buffer: everyone is done with it
+                copy_to_lds_async<4>(tab_cur, tsrc, D * Kn * rsn);
+            }
+            wait_async_copies();
+            __syncthreads();
+            uint4 *t = A_cur; A_cur = A_nxt; A_nxt = t;
+        }
+        if (two_tabs) { uint4 *t = tab_cur; tab_cur = tab_nxt; tab_nxt = t; }
+        K = Kn; rs = rsn; nb = nbn; chan_off = chan_offn;
+    }
+
+    if (y_dt == SKL_F32) gemm_store<NF, SKL_F32>(acc, Y, ldy, t0, tokens, o_wave, p.out, n, q);
+    else if (y_dt == SKL_F16) gemm_store<NF, SKL_F16>(acc, Y, ldy, t0, tokens, o_wave, p.out, n, q);
+    else gemm_store<NF, SKL_BF16>(acc, Y, ldy, t0, tokens, o_wave, p.out, n, q);
 }
 
 // ========================================================================
@@ -995,14 +1046,29 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
         st = check_launch("activation packing");
         if (st != SKL_OK) return st;
         const uint32_t tw = L->max_table_bytes / 16;
-        const size_t lds = (size_t)tw * 16 + (size_t)GEMM_MT * GEMM_AS * sizeof(uint16_t);
-        const dim3 grid((L->out + GEMM_NT - 1) / GEMM_NT, (tokens + GEMM_MT - 1) / GEMM_MT);
-        DISPATCH_D(L->d, {
-            st = allow_lds(k_row_gemm<D>, lds);
-            if (st == SKL_OK)
-                hipLaunchKernelGGL(k_row_gemm<D>, grid, dim3(SKL_WG), lds, stream, a, Xp, tokens, L->n_packed, Y, (uint32_t)y_dt,
-                                   ldy, tw);
-        });
+        const size_t a_bytes = (size_t)2 * GM_MT * 4 * 16;
+        const uint32_t two_tabs = (size_t)2 * tw * 16 + a_bytes <= SKL_LDS_HARD_BYTES ? 1 : 0;
+        const size_t lds = (size_t)(two_tabs ? 2 : 1) * tw * 16 + a_bytes;
+        // 256 x 256 tiles amortise the reconstruction best; 256 x 128 tiles fill the CUs on narrow layers
+        const uint32_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
+        uint32_t nf = (uint64_t)m_tiles * ((L->out + 255) / 256) >= SKL_N_CU ? 2 : 1;
+        if (const char *e = getenv("SKL_GEMM_NF")) nf = (uint32_t)atoi(e) == 2 ? 2 : 1;
+        const dim3 grid((L->out + 128 * nf - 1) / (128 * nf), m_tiles);
+        if (nf == 2) {
+            DISPATCH_D(L->d, {
+                st = allow_lds(k_row_gemm<D, 2>, lds);
+                if (st == SKL_OK)
+                    hipLaunchKernelGGL((k_row_gemm<D, 2>), grid, dim3(SKL_WG), lds, stream, a, Xp, tokens, L->n_packed, Y,
+                                       (uint32_t)y_dt, ldy, tw, two_tabs);
+            });
+        } else {
+            DISPATCH_D(L->d, {
+                st = allow_lds(k_row_gemm<D, 1>, lds);
+                if (st == SKL_OK)
+                    hipLaunchKernelGGL((k_row_gemm<D, 1>), grid, dim3(SKL_WG), lds, stream, a, Xp, tokens, L->n_packed, Y,
+                                       (uint32_t)y_dt, ldy, tw, two_tabs);
+            });
+        }
     } else {
         const TileArgs a = make_tile_args(L);
         const uint32_t kw = (uint32_t)tile_key_words(L);

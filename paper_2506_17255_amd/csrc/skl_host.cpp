@@ -145,6 +145,44 @@ static void plan_decode(const skl_desc_t *d, skl_plan *P)
     L.n_units = L.n_bg;
 }
 
+// Prefill plan for row sketches.  LDS holds two table buffers (one if the
+// tables are too large) and a ring of activation tiles of 256 rows x uw words;
+// 8-word units with a ring of at least three tiles when that fits, else
+// 4-word units.  A deeper ring hides more of the global -> LDS latency.
+static void plan_prefill(const skl_desc_t *d, skl_plan *P)
+{
+    skl_layer &L = P->L;
+    const uint64_t tab = L.max_table_bytes;
+    auto ring_for = [&](uint32_t uw, uint32_t n_tab) -> uint32_t {
+        const uint64_t tile = 256ull * uw * 16;
+        if (n_tab * tab + 2 * tile > SKL_LDS_HARD_BYTES) return 0;
+        return (uint32_t)std::min<uint64_t>(4, (SKL_LDS_HARD_BYTES - n_tab * tab) / tile);
+    };
+    // no wider than the words per state row of the class that holds most channels
+    uint32_t nb_main = 1, best_count = 0;
+    for (uint32_t nb : {1u, 2u, 4u, 8u}) {
+        uint32_t count = 0;
+        for (const skl_block_meta &bm : P->bmeta) count += bm.nb == nb ? bm.nb : 0;
+        if (count > best_count) { best_count = count; nb_main = nb; }
+    }
+    uint32_t uw = std::min(8u, std::max(nb_main, 2u)), two = 1, ring = ring_for(uw, 2);
+    if (ring < 3 && uw == 8) { uw = 4; ring = ring_for(4, 2); }
+    if (ring < 2) { two = 0; uw = std::min(uw, 4u); ring = ring_for(uw, 1); }
+    L.gemm_uw = uw; L.gemm_ring = ring; L.gemm_two_tabs = two;
+    P->gunits.clear();
+    for (size_t b = 0; b < P->bmeta.size(); ++b) {
+        const skl_block_meta &bm = P->bmeta[b];
+        const bool has_next = b + 1 < P->bmeta.size();
+        const uint32_t nt_off = has_next ? P->bmeta[b + 1].table_off16 : 0;
+        const uint32_t nt_words = has_next ? d->d * P->bmeta[b + 1].K * P->bmeta[b + 1].rs : 0;
+        for (uint32_t c = 0; c < bm.nb; c += uw)
+            P->gunits.push_back(skl_gemm_unit{bm.chan_off + 8 * c, std::min(bm.nb - c, uw), c, bm.K, bm.rs,
+                                              bm.table_off16, c == 0 ? 1u : 0u, c == 0 ? nt_off : 0u,
+                                              c == 0 ? nt_words : 0u, 0u});
+    }
+    L.n_gunits = (uint32_t)P->gunits.size();
+}
+
 // Row-sketch plan.  Returns false when some width is too large for any block
 // layout (then the per-weight path is tried).
 static bool plan_rows(const skl_desc_t *d, skl_plan *P)
@@ -169,7 +207,7 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
         for (uint32_t opt : rs_options)
             if ((uint64_t)d->d * K * opt * 16u <= SKL_LDS_SOFT_TABLE_BYTES) { rs = opt; break; }
         if (!rs) {
-            if ((uint64_t)d->d * K * 16u + 20480u > SKL_LDS_HARD_BYTES) return false;   // table + activation tile
+            if ((uint64_t)d->d * K * 16u + 33792u > SKL_LDS_HARD_BYTES) return false;   // table + two activation tiles of the prefill kernel
             rs = 1;
         }
         const uint32_t nb = rs == 1 ? 1 : rs - 1;
@@ -201,6 +239,7 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
     uint32_t seg = (768 + L.n_blocks / 2) / L.n_blocks;
     L.n_seg = std::min(std::max(seg, 1u), L.n_otiles);
     plan_decode(d, P);
+    plan_prefill(d, P);
     return true;
 }
 
@@ -257,6 +296,7 @@ skl_status_t skl_make_plan(const skl_desc_t *d, skl_plan *P)
         L.off_bmeta = off;  off = align_up(off + P->bmeta.size() * sizeof(skl_block_meta), 256);
         L.off_chan = off;   off = align_up(off + P->chan.size() * sizeof(uint32_t), 256);
         L.off_ginfo = off;  off = align_up(off + P->ginfo.size() * sizeof(skl_group_info), 256);
+        L.off_gunits = off; off = align_up(off + P->gunits.size() * sizeof(skl_gemm_unit), 256);
         L.off_tables = off; off = align_up(off + L.table_bytes, 256);
     } else {
         L.off_gmeta = off;  off = align_up(off + P->gmeta.size() * sizeof(skl_group_meta), 256);
@@ -306,6 +346,7 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         memcpy(img.data() + L.off_bmeta, P.bmeta.data(), P.bmeta.size() * sizeof(skl_block_meta));
         memcpy(img.data() + L.off_chan, P.chan.data(), P.chan.size() * sizeof(uint32_t));
         memcpy(img.data() + L.off_ginfo, P.ginfo.data(), P.ginfo.size() * sizeof(skl_group_info));
+        memcpy(img.data() + L.off_gunits, P.gunits.data(), P.gunits.size() * sizeof(skl_gemm_unit));
         // state offset of every input channel (one group per channel)
         std::vector<uint64_t> base(L.in + 1, 0);
         for (uint32_t j = 0; j < L.in; ++j) base[j + 1] = base[j] + (uint64_t)L.d * desc->group_width[j];

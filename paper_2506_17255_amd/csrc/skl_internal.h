@@ -48,6 +48,19 @@ struct skl_group_info {
     uint32_t K0, rs0, table_off16_0, chan_off0;
 };
 
+// One unit of the prefill walk over the channel blocks: `w` 16-byte words
+// (8*w channels) of one block, starting at word c_base of its state rows.
+struct skl_gemm_unit {
+    uint32_t chan0;        // first entry of the unit in the channel list
+    uint32_t w;            // words in the unit (1, 2, 4 or 8; at most gemm_uw)
+    uint32_t c_base;       // first word inside the block's state rows
+    uint32_t K, rs;        // width class of the block
+    uint32_t table_off16;  // the block's table
+    uint32_t first;        // 1: the unit opens its block (a new table)
+    uint32_t next_table_off16, next_table_words;   // units that open a block: the following block's table (0 words: none)
+    uint32_t pad;
+};
+
 struct skl_layer {
     uint32_t in = 0, out = 0, tj = 0, to = 0, d = 0;
     uint32_t A[SKL_MAX_D] = {0}, C[SKL_MAX_D] = {0};
@@ -77,6 +90,9 @@ struct skl_layer {
     uint32_t opl = 1;               // outputs per lane: ceil(segment length / 1024)
     uint32_t two_bufs = 1;          // double-buffered tables fit in LDS
     uint64_t off_ginfo = 0;
+    // prefill plan: unit width (words), activation ring depth, unit list
+    uint32_t gemm_uw = 0, gemm_ring = 0, gemm_two_tabs = 0, n_gunits = 0;
+    uint64_t off_gunits = 0;
 };
 
 // The host-side plan: everything create() copies to the device.
@@ -88,6 +104,7 @@ struct skl_plan {
     std::vector<uint32_t> chan;
     std::vector<uint32_t> bg_start;
     std::vector<skl_group_info> ginfo;
+    std::vector<skl_gemm_unit> gunits;
 };
 
 // error text of the calling thread

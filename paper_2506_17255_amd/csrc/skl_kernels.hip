@@ -15,6 +15,7 @@
 //                   every product x * w keeps its sign and value.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <mutex>
 #include <unordered_map>
 
@@ -64,13 +65,24 @@ __device__ __forceinline__ uint4 keep_if(bool keep, uint4 v)
 // wavefront (and a barrier for everybody else).
 typedef __attribute__((address_space(3))) void lds_void;
 
+// One global_load_lds_dwordx4: every active lane moves 16 bytes from its own
+// global address to lds_dst + lane (lds_dst is the same for the whole
+// wavefront).  Written as inline assembly on purpose: the compiler then does
+// not know that LDS is being written behind its back and does not force the
+// copy to complete before the next LDS read; completion is awaited explicitly
+// (wait_async_copies / wait_vmcnt_le) before a barrier publishes the data.
+__device__ __forceinline__ void lds_dma_16(const void *gptr, uint4 *lds_dst)
+{
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void *)lds_dst);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory", "m0");
+}
+
 template <int NWAVES>
 __device__ __forceinline__ void copy_to_lds_async(uint4 *dst, const uint4 *src, uint32_t n16)
 {
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (uint32_t base = wave * 64; base < n16; base += 64 * NWAVES)
-        if (base + lane < n16)
-            __builtin_amdgcn_global_load_lds(static_cast<const void *>(src + base + lane), (lds_void *)(dst + base), 16, 0, 0);
+        if (base + lane < n16) lds_dma_16(src + base + lane, dst + base);
 }
 
 __device__ __forceinline__ void wait_async_copies()
@@ -458,166 +470,282 @@ __global__ __launch_bounds__(SKL_WG) void k_row_reconstruct(RowArgs p, uint16_t 
 }
 
 // ---- prefill GEMM ----------------------------------------------------------
-// Pre-pass: activations -> binary16, negated, columns in channel-list order
-// (pad columns are zero), so that the main kernel reads 16-byte words.
+// A workgroup of eight wavefronts owns 256 tokens x 128 outputs.  Wavefronts
+// 0..3 compute: wavefront w owns all 256 tokens of its own 32 outputs, so every
+// reconstructed weight fragment is built exactly once per workgroup and feeds
+// eight 32x32x16 MFMAs straight from registers.  Wavefronts 4..7 only move
+// data: all operand traffic is asynchronous global -> LDS copies, and a
+// wavefront that issues them stalls while the copy queue is full, so the
+// compute wavefronts never touch global memory inside the loop.
+//
+// The channel blocks are walked in units of up to UW 16-byte words (8*UW
+// channels, listed by the host in skl_gemm_unit); a unit is UW/2 MFMA steps
+// of 16 channels.  LDS holds two table buffers (the next block's table is
+// requested when a block starts) and a ring of `ring` activation tiles,
+// requested ring-1 units ahead.  One barrier per unit: the copy wavefronts
+// arrive once their part of this unit's data has landed, the compute
+// wavefronts once they are done with the previous unit.  A copy wavefront
+// counts the copy instructions it has issued; they complete in order, so
+// "this unit has landed" is a bound on the number still outstanding
+// (s_waitcnt vmcnt(n)) and younger copies stay in flight across the barrier.
+// Inside a unit the operands of step s+1 (gathers, query, decode, activation
+// fragments) are fetched while the MFMAs of step s run.
+//
+// Activations are prepared by a pre-pass: binary16, negated, one contiguous
+// tile of 256 rows x UW words per (token tile, unit), word c of row r at
+// position c ^ ((r >> sh) & (UW-1)), sh = log2(16/UW): the 16 rows a
+// quarter-wavefront reads then fall into 16 different LDS bank groups, and a
+// tile is a flat copy.
+#define GM_MT 256            // tokens per workgroup
+#define GM_NT 128            // outputs per workgroup
+#define GM_THREADS 512       // four compute + four copy wavefronts
+
+template <int UW>
+__device__ __forceinline__ uint32_t a_tile_word(uint32_t m, uint32_t c)
+{
+    constexpr int SH = UW == 8 ? 1 : UW == 4 ? 2 : 3;
+    return m * UW + (c ^ ((m >> SH) & (UW - 1)));
+}
+
+// grid (unit, token tile); thread -> channel tid % (8*UW) of rows tid / (8*UW) + k * (256 / (8*UW))
+template <int UW>
 __global__ __launch_bounds__(SKL_WG) void k_pack_activations(const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
-                                                              const uint32_t *__restrict__ chan, uint32_t n_packed,
+                                                              uint32_t tokens, const uint32_t *__restrict__ chan,
+                                                              const skl_gemm_unit *__restrict__ units, uint32_t n_units,
                                                               uint16_t *__restrict__ Xp)
 {
-    const uint32_t t = blockIdx.x;
-    const uint32_t pcol = blockIdx.y * SKL_WG + threadIdx.x;
-    if (pcol >= n_packed) return;
-    const uint32_t ch = chan[pcol];
-    Xp[(size_t)t * n_packed + pcol] = ch != SKL_NO_CHANNEL ? load_neg_half(X, x_dt, (size_t)t * ldx + ch) : (uint16_t)0;
-}
-
-// Main kernel.  A workgroup of four wavefronts owns 256 tokens x (128*NF)
-// outputs; wavefront w owns all 256 tokens of its own 32*NF outputs, so every
-// reconstructed weight fragment is built exactly once per workgroup and feeds
-// eight 32x32x16 MFMAs straight from registers.  The channel blocks are walked
-// in units of up to four 16-byte words (32 channels).  The activations of the
-// next unit and the table of the next block stream into the other LDS buffers
-// (asynchronous global -> LDS copies) while the current unit runs.
-//
-// Activation tile in LDS: 256 rows of 4 words; word c of row r sits at position
-// c ^ ((r >> 2) & 3), so the 16 rows a quarter-wavefront reads fall into 16
-// different bank groups without any padding (the copy lands lane i's word at
-// base + i, so the swizzle is applied to the global address instead).
-#define GM_MT 256            // tokens per workgroup
-
-// One unit: nc (1..4) words of 8 channels.  Lanes 0..31 take the even words,
-// lanes 32..63 the odd ones; a lane without a word contributes zeros.  A
-// single code path for every nc keeps the 128*NF accumulators in place.
-template <int D, int NF>
-__device__ __forceinline__ void gemm_unit(const uint4 *tab, const uint32_t (&off)[NF][D], const uint4 *As, uint32_t c_base,
-                                          uint32_t nc, uint32_t n, uint32_t q, float16v (&acc)[8][NF])
-{
-    const uint32_t ns = (nc + 1) >> 1;
-    for (uint32_t s = 0; s < ns; ++s) {
-        const uint32_t cw = 2 * s + q;
-        const bool live = cw < nc;
-        const uint32_t cl = min(cw, nc - 1);
-        uint4 b[NF];
-#pragma unroll
-        for (int nf = 0; nf < NF; ++nf)
-            b[nf] = keep_if(live, keys_to_neg_half8(row_query8<D>(tab, off[nf], c_base + cl)));
-#pragma unroll
-        for (int mf = 0; mf < 8; ++mf) {
-            const uint32_t m = mf * 32 + n;
-            const uint4 a = keep_if(live, As[m * 4 + (cl ^ ((m >> 2) & 3))]);
-#pragma unroll
-            for (int nf = 0; nf < NF; ++nf)
-                acc[mf][nf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a),
-                                                                      __builtin_bit_cast(half8v, b[nf]), acc[mf][nf], 0, 0, 0);
-        }
+    constexpr int CPU = 8 * UW;                  // channels per unit
+    constexpr int RSTEP = SKL_WG / CPU;
+    const skl_gemm_unit un = units[blockIdx.x];
+    const uint32_t c8 = threadIdx.x % CPU, c = c8 >> 3, e = c8 & 7;
+    const uint32_t ch = c < un.w ? chan[un.chan0 + c8] : SKL_NO_CHANNEL;
+    uint16_t *tile = Xp + ((size_t)blockIdx.y * n_units + blockIdx.x) * (GM_MT * UW * 8);
+    for (uint32_t r = threadIdx.x / CPU; r < GM_MT; r += RSTEP) {
+        const uint32_t t = blockIdx.y * GM_MT + r;
+        uint16_t v = 0;
+        if (ch != SKL_NO_CHANNEL && t < tokens) v = load_neg_half(X, x_dt, (size_t)t * ldx + ch);
+        tile[a_tile_word<UW>(r, c) * 8 + e] = v;
     }
 }
 
-// asynchronous copy of one unit of activations: rows t0 .. t0+255 (clamped to
-// the last token), words col0/8 .. col0/8 + 3 (clamped to the nc valid ones)
-__device__ __forceinline__ void copy_activations_async(uint4 *As, const uint16_t *Xp, uint32_t n_packed, uint32_t t0,
-                                                       uint32_t tokens, uint32_t col0, uint32_t nc)
+template <int D>
+struct GemmOperands {
+    uint4 a[8];          // activation fragments: rows mf*32 + n, 8 channels
+    uint4 g[D];          // gathered keys of the d sketch rows (before the query)
+    uint4 b;             // reconstructed weights (after query + decode)
+};
+
+// Issue the LDS reads of one step: word cw of the unit for this lane (even
+// words for lanes 0..31, odd words for lanes 32..63).  Words past the unit's
+// last one (w_last) are zero in the activation tile; the gather is clamped to
+// a valid word so that the product is a clean zero.
+template <int D, int UW>
+__device__ __forceinline__ void gemm_issue(GemmOperands<D> &f, const uint4 *tab, const uint32_t (&off)[D], const uint4 *As,
+                                           uint32_t c_base, uint32_t cw, uint32_t w_last)
 {
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t n = threadIdx.x & 31;
+    const uint32_t cb = c_base + min(cw, w_last);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t r = (wave * 4 + j) * 16 + (lane >> 2);        // 16 rows per wavefront copy
-        const uint32_t c = min((lane & 3) ^ ((r >> 2) & 3), nc - 1);
-        const uint16_t *src = Xp + (size_t)min(t0 + r, tokens - 1) * n_packed + col0 + c * 8;
-        __builtin_amdgcn_global_load_lds(static_cast<const void *>(src), (lds_void *)(As + (wave * 4 + j) * 64), 16, 0, 0);
-    }
+    for (int r = 0; r < D; ++r) f.g[r] = tab[off[r] + cb];
+#pragma unroll
+    for (int mf = 0; mf < 8; ++mf) f.a[mf] = As[a_tile_word<UW>(mf * 32 + n, cw)];
 }
 
-// epilogue: acc[mf][nf][i] is the output of token t0 + mf*32 + (i/4)*8 + q*4 + i%4
-// and output channel o_wave + nf*32 + n; one rounding to the output type
-template <int NF, int DT>
-__device__ __forceinline__ void gemm_store(const float16v (&acc)[8][NF], void *Y, uint32_t ldy, uint32_t t0, uint32_t tokens,
-                                           uint32_t o_wave, uint32_t out, uint32_t n, uint32_t q)
+// query (Eq. 5) and decode of the gathered keys
+template <int D>
+__device__ __forceinline__ void gemm_finish(GemmOperands<D> &f)
 {
+    uint4 m = f.g[0];
 #pragma unroll
-    for (int nf = 0; nf < NF; ++nf) {
-        const uint32_t o = o_wave + nf * 32 + n;
-        if (o >= out) continue;
+    for (int r = 1; r < D; ++r) m = pk_max_u16x8(m, f.g[r]);
+    f.b = keys_to_neg_half8(m);
+}
+
+// asynchronous flat copy by the four copy wavefronts (pw = 0..3); returns the
+// number of copy instructions this wavefront issued
+__device__ __forceinline__ uint32_t copy_counted(uint4 *dst, const uint4 *src, uint32_t n16, uint32_t pw)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    uint32_t issued = 0;
+    for (uint32_t base = pw * 64; base < n16; base += 256) {
+        if (base + lane < n16) lds_dma_16(src + base + lane, dst + base);
+        ++issued;
+    }
+    return issued;
+}
+
+// wait until at most n of this wavefront's vector-memory operations are outstanding
+__device__ __forceinline__ void wait_vmcnt_le(uint32_t n)
+{
+#define SKL_VMCNT_CASE(k) case k: __builtin_amdgcn_s_waitcnt(0x0F70 | ((k) & 15) | (((k) >> 4) << 14)); break;
+    switch (n) {
+        SKL_VMCNT_CASE(0) SKL_VMCNT_CASE(1) SKL_VMCNT_CASE(2) SKL_VMCNT_CASE(3) SKL_VMCNT_CASE(4) SKL_VMCNT_CASE(5)
+        SKL_VMCNT_CASE(6) SKL_VMCNT_CASE(7) SKL_VMCNT_CASE(8) SKL_VMCNT_CASE(9) SKL_VMCNT_CASE(10) SKL_VMCNT_CASE(11)
+        SKL_VMCNT_CASE(12) SKL_VMCNT_CASE(13) SKL_VMCNT_CASE(14) SKL_VMCNT_CASE(15) SKL_VMCNT_CASE(16) SKL_VMCNT_CASE(17)
+        SKL_VMCNT_CASE(18) SKL_VMCNT_CASE(19) SKL_VMCNT_CASE(20) SKL_VMCNT_CASE(21) SKL_VMCNT_CASE(22) SKL_VMCNT_CASE(23)
+        SKL_VMCNT_CASE(24) SKL_VMCNT_CASE(25) SKL_VMCNT_CASE(26) SKL_VMCNT_CASE(27) SKL_VMCNT_CASE(28) SKL_VMCNT_CASE(29)
+        SKL_VMCNT_CASE(30) SKL_VMCNT_CASE(31) SKL_VMCNT_CASE(32) SKL_VMCNT_CASE(33) SKL_VMCNT_CASE(34) SKL_VMCNT_CASE(35)
+        SKL_VMCNT_CASE(36) SKL_VMCNT_CASE(37) SKL_VMCNT_CASE(38) SKL_VMCNT_CASE(39) SKL_VMCNT_CASE(40)
+    default: __builtin_amdgcn_s_waitcnt(0x0F70 | (40 & 15) | ((40 >> 4) << 14)); break;   // fewer outstanding than allowed is always safe
+    }
+#undef SKL_VMCNT_CASE
+}
+
+// epilogue: acc[mf][i] is the output of token t0 + mf*32 + (i/4)*8 + q*4 + i%4
+// and output channel o; one rounding to the output type
+template <int DT>
+__device__ __forceinline__ void gemm_store(const float16v (&acc)[8], void *Y, uint32_t ldy, uint32_t t0, uint32_t tokens,
+                                           uint32_t o, uint32_t out, uint32_t q)
+{
+    if (o >= out) return;
 #pragma unroll
-        for (int mf = 0; mf < 8; ++mf) {
+    for (int mf = 0; mf < 8; ++mf) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const uint32_t t = t0 + mf * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
-                if (t < tokens) {
-                    const size_t idx = (size_t)t * ldy + o;
-                    const float v = acc[mf][nf][i];
-                    if (DT == SKL_F32) static_cast<float *>(Y)[idx] = v;
-                    else if (DT == SKL_F16) static_cast<uint16_t *>(Y)[idx] = float_to_half_bits(v);
-                    else static_cast<uint16_t *>(Y)[idx] = float_to_bf16_bits(v);
-                }
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t t = t0 + mf * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
+            if (t < tokens) {
+                const size_t idx = (size_t)t * ldy + o;
+                const float v = acc[mf][i];
+                if (DT == SKL_F32) static_cast<float *>(Y)[idx] = v;
+                else if (DT == SKL_F16) static_cast<uint16_t *>(Y)[idx] = float_to_half_bits(v);
+                else static_cast<uint16_t *>(Y)[idx] = float_to_bf16_bits(v);
             }
         }
     }
 }
 
-template <int D, int NF>
-__global__ __launch_bounds__(SKL_WG) void k_row_gemm(RowArgs p, const uint16_t *__restrict__ Xp, uint32_t tokens,
-                                                      uint32_t n_packed, void *__restrict__ Y, uint32_t y_dt,
-                                                      uint32_t ldy, uint32_t table_words, uint32_t two_tabs)
+struct GemmArgs {
+    HashArgs h;
+    const uint4 *tables;
+    const skl_gemm_unit *units;
+    const uint4 *Xp;
+    void *Y;
+    uint32_t n_units, tokens, out, y_dt, ldy, table_words, two_tabs, ring, n_col, m_tiles;
+};
+
+// the copy wavefronts' side of the unit loop
+template <int D, int UW>
+__device__ __forceinline__ void gemm_copy_loop(const GemmArgs &p, uint4 *tab_buf, uint4 *a_buf, const uint4 *Xt, uint32_t pw)
 {
-    uint4 *tab_cur = smem;
-    uint4 *tab_nxt = smem + (two_tabs ? table_words : 0);
-    uint4 *A_cur = smem + (two_tabs ? 2 : 1) * table_words;
-    uint4 *A_nxt = A_cur + GM_MT * 4;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t n = lane & 31, q = lane >> 5;
-    const uint32_t t0 = blockIdx.y * GM_MT;
-    const uint32_t o_wave = blockIdx.x * (128 * NF) + wave * (32 * NF);
-
-    float16v acc[8][NF];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < NF; ++j) acc[i][j] = (float16v){0.f};
-
-    const skl_block_meta *bmeta = p.bmeta;
-    uint32_t K = bmeta[0].K, rs = bmeta[0].rs, nb = bmeta[0].nb, chan_off = bmeta[0].chan_off;
-    copy_to_lds_async<4>(tab_cur, p.tables + bmeta[0].table_off16, D * K * rs);
-    copy_activations_async(A_cur, Xp, n_packed, t0, tokens, chan_off, min(nb, 4u));
-    wait_async_copies();
-    __syncthreads();
-
-    uint32_t off[NF][D];
-    uint32_t K_prev = 0, rs_prev = 0;
-    for (uint32_t blk = 0; blk < p.n_blocks; ++blk) {
-        const bool more_blk = blk + 1 < p.n_blocks;
-        const uint32_t bn = more_blk ? blk + 1 : blk;
-        const uint32_t Kn = bmeta[bn].K, rsn = bmeta[bn].rs, nbn = bmeta[bn].nb, chan_offn = bmeta[bn].chan_off;
-        const uint4 *tsrc = p.tables + bmeta[bn].table_off16;
-        if (more_blk && two_tabs) copy_to_lds_async<4>(tab_nxt, tsrc, D * Kn * rsn);
-        if (K != K_prev || rs != rs_prev) {
-#pragma unroll
-            for (int nf = 0; nf < NF; ++nf) row_offsets<D>(p.h, min(o_wave + nf * 32 + n, p.out - 1), K, rs, off[nf]);
-            K_prev = K;
-            rs_prev = rs;
+    constexpr uint32_t TILE = GM_MT * UW;
+    const uint32_t la = p.ring - 1;
+    // instructions issued so far (mod 256), and the count right after the last instruction
+    // of each activation tile (one byte per ring slot) and of the most recent table
+    uint32_t issued = 0, mark_a = 0, mark_t = 0;
+    auto set_mark_a = [&](uint32_t slot) { mark_a = (mark_a & ~(0xFFu << (8 * slot))) | ((issued & 0xFFu) << (8 * slot)); };
+    {
+        const skl_gemm_unit u0 = p.units[0];
+        issued += copy_counted(tab_buf, p.tables + u0.table_off16, D * u0.K * u0.rs, pw);
+        mark_t = issued;
+        for (uint32_t v = 0; v < la && v < p.n_units; ++v) {
+            issued += copy_counted(a_buf + v * TILE, Xt + (size_t)v * TILE, TILE, pw);
+            set_mark_a(v);
         }
-        const uint32_t n_half = nb > 4 ? 2 : 1;
-        for (uint32_t h = 0; h < n_half; ++h) {
-            const bool last_half = h + 1 == n_half;
-            if (!last_half) copy_activations_async(A_nxt, Xp, n_packed, t0, tokens, chan_off + 32 * (h + 1), nb - 4 * (h + 1));
-            else if (more_blk) copy_activations_async(A_nxt, Xp, n_packed, t0, tokens, chan_offn, min(nbn, 4u));
-            const uint32_t nc = min(nb - 4 * h, 4u);
-            gemm_unit<D, NF>(tab_cur, off, A_cur, 4 * h, nc, n, q, acc);
-            if (last_half && more_blk && !two_tabs) {
-                __syncthreads();                 // single table buffer: everyone is done with it
-                copy_to_lds_async<4>(tab_cur, tsrc, D * Kn * rsn);
-            }
-            wait_async_copies();
+    }
+    uint32_t tpar = 0;
+    skl_gemm_unit un = p.units[0], un_next = un;
+    for (uint32_t u = 0; u < p.n_units; ++u, un = un_next) {
+        un_next = p.units[min(u + 1, p.n_units - 1)];      // requested a whole unit before it is needed
+        const uint32_t slot = u % p.ring;
+        if (un.first && u != 0) tpar ^= 1;
+        {
+            uint32_t need = (mark_a >> (8 * slot)) & 0xFFu;
+            if (un.first && p.two_tabs && ((issued - mark_t) & 0xFFu) < ((issued - need) & 0xFFu)) need = mark_t;
+            wait_vmcnt_le((issued - need) & 0xFFu);
+        }
+        __syncthreads();                                   // unit u is in LDS; the buffers of unit u-1 are free
+        if (un.first && !p.two_tabs && u != 0) {           // single table buffer: fetch this block's table now
+            issued += copy_counted(tab_buf, p.tables + un.table_off16, D * un.K * un.rs, pw);
+            wait_vmcnt_le(0);
             __syncthreads();
-            uint4 *t = A_cur; A_cur = A_nxt; A_nxt = t;
         }
-        if (two_tabs) { uint4 *t = tab_cur; tab_cur = tab_nxt; tab_nxt = t; }
-        K = Kn; rs = rsn; nb = nbn; chan_off = chan_offn;
+        if (un.first && p.two_tabs && un.next_table_words) {
+            issued += copy_counted(tab_buf + (tpar ^ 1) * p.table_words, p.tables + un.next_table_off16, un.next_table_words, pw);
+            mark_t = issued;
+        }
+        if (u + la < p.n_units) {
+            const uint32_t s2 = (u + la) % p.ring;
+            issued += copy_counted(a_buf + s2 * TILE, Xt + (size_t)(u + la) * TILE, TILE, pw);
+            set_mark_a(s2);
+        }
+    }
+}
+
+template <int D, int UW>
+__global__ __launch_bounds__(GM_THREADS) void k_row_gemm(GemmArgs p)
+{
+    // Workgroup id -> (token tile, output tile).  Consecutive ids go to different XCDs; all
+    // workgroups of one token tile get ids that are equal modulo 8, so a token tile's
+    // activations are fetched into one L2 only (and walked in step by its workgroups).
+    const uint32_t xcd = blockIdx.x & 7, slot0 = blockIdx.x >> 3;
+    const uint32_t tile_m = (slot0 / p.n_col) * 8 + xcd, tile_n = slot0 % p.n_col;
+    if (tile_m >= p.m_tiles) return;
+    constexpr uint32_t TILE = GM_MT * UW;                  // words per activation tile
+    uint4 *tab_buf = smem;
+    uint4 *a_buf = smem + (p.two_tabs ? 2 : 1) * p.table_words;
+    const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint4 *Xt = p.Xp + (size_t)tile_m * p.n_units * TILE;      // this token tile's activation tiles
+    if (wave >= 4) {
+        gemm_copy_loop<D, UW>(p, tab_buf, a_buf, Xt, wave - 4);
+        return;
     }
 
-    if (y_dt == SKL_F32) gemm_store<NF, SKL_F32>(acc, Y, ldy, t0, tokens, o_wave, p.out, n, q);
-    else if (y_dt == SKL_F16) gemm_store<NF, SKL_F16>(acc, Y, ldy, t0, tokens, o_wave, p.out, n, q);
-    else gemm_store<NF, SKL_BF16>(acc, Y, ldy, t0, tokens, o_wave, p.out, n, q);
+    const uint32_t n = lane & 31, q = lane >> 5;
+    const uint32_t t0 = tile_m * GM_MT;
+    const uint32_t o = tile_n * GM_NT + wave * 32 + n;
+    float16v acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = (float16v){0.f};
+    uint32_t off[D];
+    uint32_t K_prev = 0, rs_prev = 0, tpar = 0;
+    skl_gemm_unit un = p.units[0], un_next = un;
+    for (uint32_t u = 0; u < p.n_units; ++u, un = un_next) {
+        un_next = p.units[min(u + 1, p.n_units - 1)];      // requested a whole unit before it is needed
+        if (un.first && u != 0) tpar ^= 1;
+        __syncthreads();                                   // unit u is in LDS (see gemm_copy_loop)
+        if (un.first && !p.two_tabs && u != 0) __syncthreads();
+        if (un.K != K_prev || un.rs != rs_prev) {
+            row_offsets<D>(p.h, min(o, p.out - 1), un.K, un.rs, off);
+            K_prev = un.K;
+            rs_prev = un.rs;
+        }
+        const uint4 *tab = tab_buf + (p.two_tabs ? tpar * p.table_words : 0);
+        const uint4 *As = a_buf + (u % p.ring) * TILE;
+        // max(UW/2, 1) steps, straight-line.  A unit with fewer than UW words runs the same
+        // steps: its missing words are zero in the activation tile and the gathers are clamped
+        // to its last word.  Step s+1's LDS reads are issued before step s's MFMAs and may not
+        // sink below them; its query/decode VALU work is spread between the later MFMAs.
+        constexpr int NS = UW >= 2 ? UW / 2 : 1;
+        constexpr int NV = 4 * (D - 1) + 12;               // VALU instructions of gemm_finish
+        const uint32_t w_last = un.w - 1;
+        GemmOperands<D> f[2];
+        gemm_issue<D, UW>(f[0], tab, off, As, un.c_base, q, w_last);
+        gemm_finish<D>(f[0]);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (s + 1 < NS) {
+                gemm_issue<D, UW>(f[(s + 1) & 1], tab, off, As, un.c_base, 2 * (s + 1) + q, w_last);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int mf = 0; mf < 8; ++mf)
+                acc[mf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, f[s & 1].a[mf]),
+                                                                  __builtin_bit_cast(half8v, f[s & 1].b), acc[mf], 0, 0, 0);
+            if (s + 1 < NS) {
+                gemm_finish<D>(f[(s + 1) & 1]);
+                __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);      // three MFMAs cover the gather latency
+#pragma unroll
+                for (int i = 0; i < 5; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x002, (NV + 4) / 5, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    if (p.y_dt == SKL_F32) gemm_store<SKL_F32>(acc, p.Y, p.ldy, t0, p.tokens, o, p.out, q);
+    else if (p.y_dt == SKL_F16) gemm_store<SKL_F16>(acc, p.Y, p.ldy, t0, p.tokens, o, p.out, q);
+    else gemm_store<SKL_BF16>(acc, p.Y, p.ldy, t0, p.tokens, o, p.out, q);
 }
 
 // ========================================================================
@@ -939,7 +1067,8 @@ uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch)
 
 uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
 {
-    return L->path == 1 ? (uint64_t)tokens * L->n_packed * sizeof(uint16_t) : 0;
+    // one tile of 256 rows x gemm_uw words per (token tile, unit)
+    return L->path == 1 ? (uint64_t)((tokens + GM_MT - 1) / GM_MT) * L->n_gunits * GM_MT * L->gemm_uw * 16 : 0;
 }
 
 skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *stream_)
@@ -1041,34 +1170,38 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
     if (L->path == 1) {
         uint16_t *Xp = static_cast<uint16_t *>(ws);
         const RowArgs a = make_row_args(L);
-        hipLaunchKernelGGL(k_pack_activations, dim3(tokens, (L->n_packed + SKL_WG - 1) / SKL_WG), dim3(SKL_WG), 0, stream,
-                           X, (uint32_t)x_dt, ldx, a.chan, L->n_packed, Xp);
+        const skl_gemm_unit *units = reinterpret_cast<const skl_gemm_unit *>(L->dev + L->off_gunits);
+        const uint32_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
+        if (m_tiles > 65535) {
+            skl_set_error("more than 65535 token tiles in one call");
+            return SKL_ERR_UNSUPPORTED;
+        }
+#define LAUNCH_PACK(UW_)                                                                                             \
+    hipLaunchKernelGGL(k_pack_activations<UW_>, dim3(L->n_gunits, m_tiles), dim3(SKL_WG), 0, stream, X, (uint32_t)x_dt,  \
+                       ldx, tokens, a.chan, units, L->n_gunits, Xp)
+        if (L->gemm_uw == 8) LAUNCH_PACK(8);
+        else if (L->gemm_uw == 4) LAUNCH_PACK(4);
+        else LAUNCH_PACK(2);
+#undef LAUNCH_PACK
         st = check_launch("activation packing");
         if (st != SKL_OK) return st;
         const uint32_t tw = L->max_table_bytes / 16;
-        const size_t a_bytes = (size_t)2 * GM_MT * 4 * 16;
-        const uint32_t two_tabs = (size_t)2 * tw * 16 + a_bytes <= SKL_LDS_HARD_BYTES ? 1 : 0;
-        const size_t lds = (size_t)(two_tabs ? 2 : 1) * tw * 16 + a_bytes;
-        // 256 x 256 tiles amortise the reconstruction best; 256 x 128 tiles fill the CUs on narrow layers
-        const uint32_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
-        uint32_t nf = (uint64_t)m_tiles * ((L->out + 255) / 256) >= SKL_N_CU ? 2 : 1;
-        if (const char *e = getenv("SKL_GEMM_NF")) nf = (uint32_t)atoi(e) == 2 ? 2 : 1;
-        const dim3 grid((L->out + 128 * nf - 1) / (128 * nf), m_tiles);
-        if (nf == 2) {
-            DISPATCH_D(L->d, {
-                st = allow_lds(k_row_gemm<D, 2>, lds);
-                if (st == SKL_OK)
-                    hipLaunchKernelGGL((k_row_gemm<D, 2>), grid, dim3(SKL_WG), lds, stream, a, Xp, tokens, L->n_packed, Y,
-                                       (uint32_t)y_dt, ldy, tw, two_tabs);
-            });
-        } else {
-            DISPATCH_D(L->d, {
-                st = allow_lds(k_row_gemm<D, 1>, lds);
-                if (st == SKL_OK)
-                    hipLaunchKernelGGL((k_row_gemm<D, 1>), grid, dim3(SKL_WG), lds, stream, a, Xp, tokens, L->n_packed, Y,
-                                       (uint32_t)y_dt, ldy, tw, two_tabs);
-            });
-        }
+        const size_t lds = (size_t)(L->gemm_two_tabs ? 2 : 1) * tw * 16 + (size_t)L->gemm_ring * GM_MT * L->gemm_uw * 16;
+        GemmArgs g;
+        g.h = a.h; g.tables = a.tables; g.units = units; g.Xp = reinterpret_cast<const uint4 *>(Xp); g.Y = Y;
+        g.n_units = L->n_gunits; g.tokens = tokens; g.out = L->out; g.y_dt = (uint32_t)y_dt; g.ldy = ldy;
+        g.table_words = tw; g.two_tabs = L->gemm_two_tabs; g.ring = L->gemm_ring;
+        g.n_col = (L->out + GM_NT - 1) / GM_NT; g.m_tiles = m_tiles;
+        const dim3 grid(8 * ((m_tiles + 7) / 8) * g.n_col);
+#define LAUNCH_GEMM(UW_)                                                                                            \
+    DISPATCH_D(L->d, {                                                                                              \
+        st = allow_lds(k_row_gemm<D, UW_>, lds);                                                                    \
+        if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemm<D, UW_>), grid, dim3(GM_THREADS), lds, stream, g);         \
+    })
+        if (L->gemm_uw == 8) LAUNCH_GEMM(8)
+        else if (L->gemm_uw == 4) LAUNCH_GEMM(4)
+        else LAUNCH_GEMM(2)
+#undef LAUNCH_GEMM
     } else {
         const TileArgs a = make_tile_args(L);
         const uint32_t kw = (uint32_t)tile_key_words(L);

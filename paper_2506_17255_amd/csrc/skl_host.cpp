@@ -81,7 +81,7 @@ static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out)
 // the busiest workgroup (segment wave-units x 16-byte words per state row of
 // its blocks); among equal splits the one with fewer segments stages fewer
 // table bytes.
-static void plan_decode(const skl_desc_t *d, skl_plan *P)
+static bool plan_decode(const skl_desc_t *d, skl_plan *P)
 {
     skl_layer &L = P->L;
     const uint32_t units = (d->out_features + 63) / 64;
@@ -89,9 +89,22 @@ static void plan_decode(const skl_desc_t *d, skl_plan *P)
     std::vector<uint32_t> cum(nblk + 1, 0);
     for (uint32_t b = 0; b < nblk; ++b) cum[b + 1] = cum[b] + P->bmeta[b].nb;
     const uint32_t total_nb = cum[nblk];
-    uint32_t force_s = 0, force_g = 0;
-    if (const char *e = getenv("SKL_DECODE_SEGMENTS")) force_s = (uint32_t)atoi(e);
-    if (const char *e = getenv("SKL_DECODE_GROUPS")) force_g = (uint32_t)atoi(e);
+    // group boundaries for G groups: equal shares of the 16-byte words per state
+    // row, every group at least one block; returns the most blocks in a group
+    auto cut_groups = [&](uint32_t G, std::vector<uint32_t> &start) -> uint32_t {
+        start.assign(G + 1, 0);
+        uint32_t b = 0, most = 0;
+        for (uint32_t g = 0; g < G; ++g) {
+            start[g] = b;
+            const uint64_t target = (uint64_t)total_nb * (g + 1) / G;
+            while (b < nblk && (cum[b + 1] <= target || b == start[g])) ++b;
+            if (nblk - b < G - 1 - g) b = nblk - (G - 1 - g);    // leave a block for every later group
+            if (g + 1 == G) b = nblk;
+            most = std::max(most, b - start[g]);
+        }
+        start[G] = nblk;
+        return most;
+    };
     // Cost model (microseconds, fitted to measurements on MI355X): a workgroup
     // pays a start-up latency and then 0.033 us per (64-output wave unit x
     // 16-byte word per state row) of its share; fewer than six active
@@ -99,17 +112,17 @@ static void plan_decode(const skl_desc_t *d, skl_plan *P)
     // round-robin to the 8 XCDs of 32 CUs each and a group's segments all land
     // on one XCD, so ceil(G/8)*S workgroups compete for 32 CUs.
     double best = 1e300;
-    uint32_t best_s = 1, best_g = 1;
-    for (uint32_t S = 1; S <= units; ++S) {
-        const uint32_t seg_units = (units + S - 1) / S;
-        if (seg_units > 16) continue;                       // one output per lane of a 1024-thread workgroup
-        if (force_s && S != force_s) continue;
-        const uint32_t g_min = (nblk + 47) / 48;            // at most 64 blocks in a group (48 on average)
-        for (uint32_t G = g_min; G <= nblk; ++G) {
-            if (force_g && G != std::max(std::min(force_g, nblk), g_min)) continue;
+    uint32_t best_s = 1, best_g = nblk;
+    std::vector<uint32_t> scratch_start;
+    for (uint32_t G = (nblk + SKL_MAX_GROUP_BLOCKS - 1) / SKL_MAX_GROUP_BLOCKS; G <= nblk; ++G) {
+        if (cut_groups(G, scratch_start) > SKL_MAX_GROUP_BLOCKS) continue;   // block metadata of a group sits in LDS
+        const double share = std::ceil((double)total_nb / G + 0.5 * P->bmeta[0].nb);   // groups end on block boundaries
+        // one 64-output unit per wavefront of a 1024-thread workgroup: 16 at most; fewer than 6 never pays
+        for (uint32_t want = 16; want >= 6; --want) {
+            const uint32_t S = (units + want - 1) / want;
+            const uint32_t seg_units = (units + S - 1) / S;
             const uint32_t per_xcd = ((G + 7) / 8) * S;
             const uint32_t rounds = (per_xcd + 31) / 32;
-            const double share = std::ceil((double)total_nb / G + 0.5 * P->bmeta[0].nb);   // groups end on block boundaries
             const double t = rounds * (1.8 + 0.033 * std::max(seg_units, 6u) * share) + 0.02 * G;
             if (t < best) { best = t; best_s = S; best_g = G; }
         }
@@ -117,17 +130,8 @@ static void plan_decode(const skl_desc_t *d, skl_plan *P)
     L.n_sseg = best_s;
     L.n_bg = best_g;
     L.n_wunits = units;
-    L.opl = ((units + best_s - 1) / best_s + 15) / 16;
-    // group boundaries: equal shares of the 16-byte words per state row
-    P->bg_start.assign(best_g + 1, 0);
-    uint32_t b = 0;
-    for (uint32_t g = 0; g < best_g; ++g) {
-        P->bg_start[g] = b;
-        const uint64_t target = (uint64_t)total_nb * (g + 1) / best_g;
-        while (b < nblk && (cum[b + 1] <= target || b == P->bg_start[g])) ++b;
-        if (nblk - b < best_g - 1 - g) b = nblk - (best_g - 1 - g);    // leave a block for every later group
-    }
-    P->bg_start[best_g] = nblk;
+    L.opl = 1;
+    cut_groups(best_g, P->bg_start);
     uint32_t max_chan = 0;
     P->ginfo.assign(best_g, skl_group_info{});
     for (uint32_t g = 0; g < best_g; ++g) {
@@ -136,13 +140,22 @@ static void plan_decode(const skl_desc_t *d, skl_plan *P)
         const uint32_t c_hi = hi < nblk ? P->bmeta[hi].chan_off : (uint32_t)P->chan.size();
         max_chan = std::max(max_chan, c_hi - c_lo);
         P->ginfo[g] = skl_group_info{lo, hi, c_lo, c_hi, P->bmeta[lo].K, P->bmeta[lo].rs,
-                                     P->bmeta[lo].table_off16, P->bmeta[lo].chan_off};
+                                     P->bmeta[lo].table_off16, P->bmeta[lo].chan_off, P->bmeta[lo].ptable_off16,
+                                     0u, 0u, 0u};
     }
     L.max_group_chan = max_chan;
     // LDS: two table buffers + 32 activation rows of the group (batched decode)
     const uint64_t act = (uint64_t)32 * (max_chan + 8) * 2;
     L.two_bufs = 2ull * L.max_table_bytes + act + 256 <= SKL_LDS_HARD_BYTES ? 1 : 0;
+    const uint64_t g1_fixed = 6144 + 4096ull * d->d;   // output sums, block metadata, state-row addresses
+    // batch-1 kernel: the second buffer sits SKL_PBUF_DIST bytes after the first
+    // (reachable through the offset field of an LDS read), followed by the
+    // per-output sums and the group's activations
+    L.two_pbufs = L.max_ptable_bytes <= SKL_PBUF_DIST &&
+                  2ull * SKL_PBUF_DIST + g1_fixed + 2ull * (max_chan + 64) <= SKL_LDS_HARD_BYTES ? 1 : 0;
     L.n_units = L.n_bg;
+    // a single table buffer must at least fit beside the sums and activations
+    return L.two_pbufs || (uint64_t)L.max_ptable_bytes + g1_fixed + 2ull * (max_chan + 64) <= SKL_LDS_HARD_BYTES;
 }
 
 // Prefill plan for row sketches.  LDS holds two table buffers (one if the
@@ -195,7 +208,7 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
                      [&](uint32_t a, uint32_t b) { return d->group_width[a] < d->group_width[b]; });
     P->bmeta.clear();
     P->chan.clear();
-    uint64_t off16 = 0;
+    uint64_t off16 = 0, poff16 = 0;
     uint32_t max_table = 0;
     static const uint32_t rs_options[4] = {9, 5, 3, 1};
     uint32_t i = 0;
@@ -204,8 +217,10 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
         uint32_t e = i;
         while (e < in && d->group_width[order[e]] == K) ++e;
         uint32_t rs = 0;
-        for (uint32_t opt : rs_options)
+        for (uint32_t opt : rs_options) {
+            if (opt == 9 && d->d > 6) continue;   // 8 words x 7 or 8 rows: too many row addresses per lane for the batch-1 kernel's registers
             if ((uint64_t)d->d * K * opt * 16u <= SKL_LDS_SOFT_TABLE_BYTES) { rs = opt; break; }
+        }
         if (!rs) {
             if ((uint64_t)d->d * K * 16u + 33792u > SKL_LDS_HARD_BYTES) return false;   // table + two activation tiles of the prefill kernel
             rs = 1;
@@ -218,6 +233,8 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
             bm.rs = rs;
             bm.nb = nb;
             bm.chan_off = (uint32_t)P->chan.size();
+            bm.ptable_off16 = (uint32_t)poff16;
+            poff16 += ((uint64_t)d->d * K * nb + 63) / 64 * 64;    // whole 64-word chunks: copied without bounds checks
             for (uint32_t c = 0; c < 8 * nb; ++c)
                 P->chan.push_back(s + c < e ? order[s + c] : SKL_NO_CHANNEL);
             const uint64_t words = (uint64_t)d->d * K * rs;
@@ -234,11 +251,15 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
     L.n_units = L.n_blocks;
     L.max_table_bytes = max_table;
     L.table_bytes = off16 * 16;
+    L.ptable_bytes = poff16 * 16;
+    L.max_ptable_bytes = 0;
+    for (const skl_block_meta &bm : P->bmeta)
+        L.max_ptable_bytes = std::max<uint32_t>(L.max_ptable_bytes, (d->d * bm.K * bm.nb + 63) / 64 * 1024u);
     L.n_otiles = (d->out_features + SKL_WG - 1) / SKL_WG;
     // about three workgroups per CU on 256 CUs, split over blocks x output segments
     uint32_t seg = (768 + L.n_blocks / 2) / L.n_blocks;
     L.n_seg = std::min(std::max(seg, 1u), L.n_otiles);
-    plan_decode(d, P);
+    if (!plan_decode(d, P)) return false;
     plan_prefill(d, P);
     return true;
 }
@@ -298,6 +319,7 @@ skl_status_t skl_make_plan(const skl_desc_t *d, skl_plan *P)
         L.off_ginfo = off;  off = align_up(off + P->ginfo.size() * sizeof(skl_group_info), 256);
         L.off_gunits = off; off = align_up(off + P->gunits.size() * sizeof(skl_gemm_unit), 256);
         L.off_tables = off; off = align_up(off + L.table_bytes, 256);
+        L.off_ptables = off; off = align_up(off + L.ptable_bytes, 256);
     } else {
         L.off_gmeta = off;  off = align_up(off + P->gmeta.size() * sizeof(skl_group_meta), 256);
         L.off_keys = off;   off = align_up(off + L.table_bytes + 16, 256);
@@ -351,8 +373,10 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         std::vector<uint64_t> base(L.in + 1, 0);
         for (uint32_t j = 0; j < L.in; ++j) base[j + 1] = base[j] + (uint64_t)L.d * desc->group_width[j];
         uint16_t *tab = reinterpret_cast<uint16_t *>(img.data() + L.off_tables);
+        uint16_t *ptab = reinterpret_cast<uint16_t *>(img.data() + L.off_ptables);
         for (const skl_block_meta &bm : P.bmeta) {
             uint16_t *t = tab + (uint64_t)bm.table_off16 * 8;
+            uint16_t *pt = ptab + (uint64_t)bm.ptable_off16 * 8;
             for (uint32_t c8 = 0; c8 < 8 * bm.nb; ++c8) {
                 const uint32_t ch = P.chan[bm.chan_off + c8];
                 const uint16_t *s = ch == SKL_NO_CHANNEL ? nullptr : desc->states + base[ch];
@@ -361,6 +385,7 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
                     for (uint32_t k = 0; k < bm.K; ++k) {
                         const uint16_t key = s ? skl_key_of_half(s[(uint64_t)r * bm.K + k]) : (uint16_t)1;
                         t[(((uint64_t)r * bm.K + k) * bm.rs + c) * 8 + i] = key;
+                        pt[(((uint64_t)r * bm.K + k) * bm.nb + c) * 8 + i] = key;
                     }
             }
         }

@@ -12,11 +12,15 @@
 #define SKL_SWG 1024          // threads per workgroup of the streaming decode kernels
 #define SKL_N_CU 256          // compute units of the target (MI355X)
 #define SKL_NO_CHANNEL 0xFFFFFFFFu
+#define SKL_MAX_GROUP_BLOCKS 64   // most channel blocks in one block group of the decode plan (metadata kept in LDS)
 
 // LDS budgets.  A CU of gfx950 has 160 KiB of LDS; keeping a workgroup's
 // table at or below the soft limit lets three workgroups share a CU.
 #define SKL_LDS_SOFT_TABLE_BYTES 50688u
 #define SKL_LDS_HARD_BYTES 163840u
+// Distance between the two table buffers of the batch-1 decode kernel: below
+// 2^16, so that the buffer is chosen by the offset field of the LDS reads.
+#define SKL_PBUF_DIST 65280u
 
 // ---- path 0: 2-D groups, one hash evaluation per weight and sketch row ----
 struct skl_group_meta {
@@ -37,7 +41,8 @@ struct skl_block_meta {
     uint32_t nb;           // used words per state row (8*nb channels per block)
     uint32_t chan_off;     // first entry of the block in the channel list
                            // (= first packed activation column of the block)
-    uint32_t pad0, pad1, pad2;
+    uint32_t ptable_off16; // the block's table in the unpadded copy ([r][k][nb] words)
+    uint32_t pad1, pad2;
 };
 
 // One block group of the decode plan: consecutive blocks [b_lo, b_hi), their
@@ -46,6 +51,7 @@ struct skl_block_meta {
 struct skl_group_info {
     uint32_t b_lo, b_hi, c_lo, c_hi;
     uint32_t K0, rs0, table_off16_0, chan_off0;
+    uint32_t ptable_off16_0, pad0, pad1, pad2;
 };
 
 // One unit of the prefill walk over the channel blocks: `w` 16-byte words
@@ -82,13 +88,18 @@ struct skl_layer {
     uint32_t n_packed = 0;          // channel-list length = sum of 8*nb over blocks
     uint32_t n_otiles = 0, n_seg = 0;
     uint64_t off_bmeta = 0, off_chan = 0, off_tables = 0;
+    // second copy of the tables without the padding word per state row, for
+    // the batch-1 decode kernel whose lanes read whole state rows
+    uint64_t off_ptables = 0, ptable_bytes = 0;
+    uint32_t max_ptable_bytes = 0;
     // decode plan: workgroup (s, g) owns output segment s (a range of 64-output
     // wave units) and block group g (consecutive channel blocks bg_start[g] ..
     // bg_start[g+1]); n_sseg * n_bg workgroups of 1024 threads, one per CU
     uint32_t n_sseg = 0, n_bg = 0, n_wunits = 0;
     uint32_t max_group_chan = 0;    // most channel-list entries in one block group
     uint32_t opl = 1;               // outputs per lane: ceil(segment length / 1024)
-    uint32_t two_bufs = 1;          // double-buffered tables fit in LDS
+    uint32_t two_bufs = 1;          // double-buffered tables fit in LDS (batched decode, padded tables)
+    uint32_t two_pbufs = 1;         // the same for the batch-1 kernel and the unpadded tables
     uint64_t off_ginfo = 0;
     // prefill plan: unit width (words), activation ring depth, unit list
     uint32_t gemm_uw = 0, gemm_ring = 0, gemm_two_tabs = 0, n_gunits = 0;

@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 #include <mutex>
 #include <unordered_map>
 
@@ -44,6 +45,18 @@ __device__ __forceinline__ uint4 pk_max_u16x8(uint4 a, uint4 b)
 __device__ __forceinline__ uint32_t keys_to_neg_half2(uint32_t k)
 {
     return ((k >> 1) & 0x7FFF7FFFu) | ((k << 15) & 0x80008000u);
+}
+
+// The same in two instructions instead of three, for loops bound by the vector
+// ALU: per 16-bit half, (k >> 1) + k * 0x8000 (the product keeps bit 0 of k in
+// bit 15; the two terms share no bit).  The compiler turns the multiply back
+// into a shift and an OR, hence the explicit packed multiply-add.
+__device__ __forceinline__ uint32_t keys_to_neg_half2_mad(uint32_t k)
+{
+    uint32_t t, r;
+    asm("v_pk_lshrrev_b16 %0, 1, %1 op_sel_hi:[0,1]" : "=v"(t) : "v"(k));
+    asm("v_pk_mad_u16 %0, %1, %2, %3" : "=v"(r) : "v"(k), "s"(0x80008000u), "v"(t));
+    return r;
 }
 
 __device__ __forceinline__ uint4 keys_to_neg_half8(uint4 k)
@@ -83,6 +96,15 @@ __device__ __forceinline__ void copy_to_lds_async(uint4 *dst, const uint4 *src, 
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (uint32_t base = wave * 64; base < n16; base += 64 * NWAVES)
         if (base + lane < n16) lds_dma_16(src + base + lane, dst + base);
+}
+
+// The same for a source padded to whole 64-word chunks (no bounds check per
+// lane) and a workgroup of nw wavefronts: wavefront w moves chunks w, w + nw, ..
+__device__ __forceinline__ void copy_chunks_to_lds_async(uint4 *dst, const uint4 *src, uint32_t n16, uint32_t nw)
+{
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t n_chunks = (n16 + 63) >> 6;
+    for (uint32_t ch = wave; ch < n_chunks; ch += nw) lds_dma_16(src + ch * 64 + lane, dst + ch * 64);
 }
 
 __device__ __forceinline__ void wait_async_copies()
@@ -201,7 +223,7 @@ struct StreamArgs {
 
 struct StreamCtx {
     uint32_t s, g, b_lo, b_hi, c_lo, c_hi, o_lo, o_hi;
-    uint32_t K0, rs0, toff0, chan_off0;
+    uint32_t K0, rs0, toff0, chan_off0, ptoff0;
     bool live;
 };
 
@@ -220,6 +242,7 @@ __device__ __forceinline__ StreamCtx stream_ctx(const StreamArgs &p)
     const skl_group_info gi = p.ginfo[min(c.g, p.n_bg - 1)];
     c.b_lo = gi.b_lo; c.b_hi = gi.b_hi; c.c_lo = gi.c_lo; c.c_hi = gi.c_hi;
     c.K0 = gi.K0; c.rs0 = gi.rs0; c.toff0 = gi.table_off16_0; c.chan_off0 = gi.chan_off0;
+    c.ptoff0 = gi.ptable_off16_0;
     c.o_lo = (uint32_t)(((uint64_t)s * p.n_wunits) / p.n_sseg) * 64;
     c.o_hi = min((uint32_t)(((uint64_t)(s + 1) * p.n_wunits) / p.n_sseg) * 64, p.r.out);
     return c;
@@ -229,7 +252,6 @@ __device__ __forceinline__ StreamCtx stream_ctx(const StreamArgs &p)
 // been requested and before the first barrier (activation staging); `body`
 // is called once per block with that block's LDS table.  While a block is
 // being gathered from, the next block's table streams into the other buffer.
-#define SKL_MAX_GROUP_BLOCKS 64   // blocks per group whose metadata is kept in LDS
 
 template <int D, typename Pre, typename Body>
 __device__ __forceinline__ void stream_blocks(const StreamArgs &p, const StreamCtx &c, uint4 *buf0, uint4 *buf1, Pre &&pre,
@@ -267,71 +289,240 @@ __device__ __forceinline__ void stream_blocks(const StreamArgs &p, const StreamC
     }
 }
 
-// dot product of one output with the 8*NB channels of a block (batch 1)
-template <int D, int RS>
-__device__ __forceinline__ float row_block_dot(const uint4 *tab, const uint32_t (&off)[D], const uint4 *xs)
+// ---- decode GEMV, batch 1 ---------------------------------------------------
+// This kernel reads the unpadded copy of the tables ([r][k][nb] words) and
+// spreads a wavefront over (output, word) pairs: with nb words per state row,
+// lane l works on word l % nb of 64/nb outputs at a time, so the lanes that
+// share an output read one contiguous state row (128 bytes for nb = 8) instead
+// of 64 lanes reading 64 unrelated rows.  Measured on MI355X the gather then
+// stops being bound by LDS bank conflicts (35 instead of 46 clocks per
+// 512 weights and CU) and runs at the rate of the vector ALU.  A lane keeps nb
+// partial sums (one per output it visits) across all blocks of a width class;
+// they are folded across the nb lanes of an output and parked in LDS when the
+// class changes and at the end.
+//
+// LDS: [table buffer 0][table buffer 1 at SKL_PBUF_DIST][1024 sums][block
+// metadata][state-row addresses, 1024 x d][activations].  The kernel has no static LDS, so the dynamic region
+// starts at LDS address 0 and the second buffer is reached through the 16-bit
+// offset field of the read instruction: no address arithmetic per gather.
+#define SKL_G1_FIXED_LDS(d) (SKL_SWG * 4 + SKL_MAX_GROUP_BLOCKS * 32 + SKL_SWG * 4 * (d))
+
+// 16 bytes at an absolute LDS address
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 lds_word_at(uint32_t addr)
 {
-    constexpr int NB = RS == 1 ? 1 : RS - 1;
-    float acc = 0.f;
-#pragma unroll
-    for (int c = 0; c < NB; ++c) {
-        const uint4 w = keys_to_neg_half8(row_query8<D>(tab, off, c));
-        const uint4 xv = xs[c];
-        acc = dot2_acc(w.x, xv.x, acc);
-        acc = dot2_acc(w.y, xv.y, acc);
-        acc = dot2_acc(w.z, xv.z, acc);
-        acc = dot2_acc(w.w, xv.w, acc);
-    }
-    return acc;
+    const u32x4v v = *(const __attribute__((address_space(3))) u32x4v *)(uintptr_t)addr;
+    return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-template <int D, int OPL>
+template <int D, int NB>
+__device__ __forceinline__ void lane_offsets(const HashArgs &h, uint32_t o_base, uint32_t out, uint32_t K, uint32_t lane,
+                                             uint32_t *row_addr_w, uint32_t (&off)[NB][D])
+{
+    constexpr uint32_t OPI = 64 / NB;               // outputs per instruction
+    const uint32_t sub = lane / NB, cw = lane % NB;
+    const uint32_t Kq = K << 8;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void *)smem;
+    // The hash values A*o + C do not depend on K; hide that from the compiler,
+    // which would otherwise keep them in registers across the block loop.
+    asm volatile("" : "+v"(o_base));
+    // every lane hashes one output (Eq. 3 for the D rows) and leaves the LDS
+    // addresses of its state rows (first buffer, word cw = 0) in the wavefront's
+    // scratch area [64][D] ...
+    const uint32_t o = min(o_base + lane, out - 1);
+#pragma unroll
+    for (int r = 0; r < D; ++r) {
+        const uint32_t t = __umul24(h.A[r], o) + h.C[r];
+        row_addr_w[lane * D + r] = lds0 + (r * K + select_index(t, Kq)) * (NB * 16);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    // ... and picks up the rows of the NB outputs it works on
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+#pragma unroll
+        for (int r = 0; r < D; ++r) off[i][r] = row_addr_w[(sub + OPI * i) * D + r] + cw * 16;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+}
+
+// sum over the NB adjacent lanes of an output (data-parallel primitives, no LDS)
+template <int NB>
+__device__ __forceinline__ float sum_over_words(float v)
+{
+    if (NB >= 2)    // lane ^ 1
+        v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+    if (NB >= 4)    // lane ^ 2
+        v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+    if (NB >= 8)    // mirror inside 8 lanes: the other quad
+        v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
+    return v;
+}
+
+// one block: NB outputs per lane, one 16-byte word (8 channels) of each.
+// The D gathers of the next output are issued before the arithmetic of the
+// current one (the scheduling barriers keep them there); left alone, the
+// compiler waits for every single gather right after issuing it.
+template <int D, int NB, uint32_t BUF_OFF>
+__device__ __forceinline__ void lane_block_dot(const uint32_t (&off)[NB][D], uint4 xv, float (&acc)[NB])
+{
+    constexpr bool PIPELINED = D <= 4;       // more rows would not leave registers for a second set of gathers
+    uint4 cur[D], nxt[D];
+#pragma unroll
+    for (int r = 0; r < D; ++r) cur[r] = lds_word_at(off[0][r] + BUF_OFF);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        if (PIPELINED && i + 1 < NB) {
+#pragma unroll
+            for (int r = 0; r < D; ++r) nxt[r] = lds_word_at(off[i + 1][r] + BUF_OFF);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        uint4 m = cur[0];
+#pragma unroll
+        for (int r = 1; r < D; ++r) m = pk_max_u16x8(m, cur[r]);
+        acc[i] = dot2_acc(keys_to_neg_half2_mad(m.x), xv.x, acc[i]);
+        acc[i] = dot2_acc(keys_to_neg_half2_mad(m.y), xv.y, acc[i]);
+        acc[i] = dot2_acc(keys_to_neg_half2_mad(m.z), xv.z, acc[i]);
+        acc[i] = dot2_acc(keys_to_neg_half2_mad(m.w), xv.w, acc[i]);
+        if (i + 1 < NB) {
+            if (PIPELINED) {
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < D; ++r) cur[r] = nxt[r];
+            } else {
+#pragma unroll
+                for (int r = 0; r < D; ++r) cur[r] = lds_word_at(off[i + 1][r] + BUF_OFF);
+            }
+        }
+    }
+}
+
+// The block loop of one workgroup, shared by all width classes.
+struct G1Walk {
+    const uint4 *sm_meta;    // metadata of the group's blocks in LDS (two 16-byte words each)
+    const uint16_t *xs;      // the group's activations (negated binary16) in LDS
+    float *yw;               // the wavefront's 64 output sums in LDS
+    uint32_t *row_addr_w;    // the wavefront's scratch for state-row addresses, [64][D]
+    uint32_t nblk, bi;       // blocks of the group, current block
+    uint32_t K, rs, chan_off;   // current block
+    uint32_t lane, o_base;
+    bool wave_live;
+};
+
+// A run of consecutive blocks of one width class (NB words per state row).
+// The partial sums and the table offsets of the run live in registers.
+template <int D, int NB>
+__device__ __forceinline__ void g1_run(const StreamArgs &p, const StreamCtx &c, G1Walk &w)
+{
+    const uint32_t nw = blockDim.x >> 6;
+    constexpr uint32_t OPI = 64 / NB;
+    uint4 *const buf0 = smem, *const buf1 = smem + SKL_PBUF_DIST / 16;
+    float acc[NB];
+    uint32_t off[NB][D];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) acc[i] = 0.f;
+    uint32_t K_prev = 0;
+    const uint32_t rs_run = w.rs;
+    // one block out of the buffer at byte offset BO (a compile-time constant, so
+    // that it ends up in the offset field of the LDS reads); meanwhile the
+    // next block's table streams into the other buffer
+    auto step = [&](auto bo_tag) {
+        constexpr uint32_t BO = decltype(bo_tag)::value;
+        uint4 *nxt = BO || !p.two_bufs ? buf0 : buf1;
+        const bool more = w.bi + 1 < w.nblk;
+        const uint32_t bn = min(w.bi + 1, w.nblk - 1);
+        const uint4 m0 = w.sm_meta[2 * bn];          // {table_off16, K, rs, nb}
+        const uint4 m1 = w.sm_meta[2 * bn + 1];      // {chan_off, ptable_off16, ..}
+        if (more && p.two_bufs) copy_chunks_to_lds_async(nxt, p.r.tables + m1.y, D * m0.y * m0.w, nw);
+        if (w.wave_live) {
+            if (w.K != K_prev) {
+                lane_offsets<D, NB>(p.r.h, w.o_base, p.r.out, w.K, w.lane, w.row_addr_w, off);
+                K_prev = w.K;
+            }
+            const uint4 xv = reinterpret_cast<const uint4 *>(w.xs + (w.chan_off - c.c_lo))[w.lane % NB];
+            lane_block_dot<D, NB, BO>(off, xv, acc);
+        }
+        if (more && !p.two_bufs) {
+            __syncthreads();                 // everyone is done with the only buffer
+            copy_chunks_to_lds_async(nxt, p.r.tables + m1.y, D * m0.y * m0.w, nw);
+        }
+        wait_async_copies();
+        __syncthreads();
+        w.K = m0.y; w.rs = m0.z; w.chan_off = m1.x;
+        ++w.bi;
+    };
+    const std::integral_constant<uint32_t, 0> first_buf;
+    const std::integral_constant<uint32_t, SKL_PBUF_DIST> second_buf;
+    auto in_run = [&]() { return w.bi < w.nblk && w.rs == rs_run; };
+    if (p.two_bufs) {
+        // even blocks sit in the first buffer, odd blocks in the second
+        if (w.bi & 1) step(second_buf);
+        while (in_run()) {
+            step(first_buf);
+            if (!in_run()) break;
+            step(second_buf);
+        }
+    } else {
+        while (in_run()) step(first_buf);
+    }
+    // fold the NB lanes of every output, add the totals to the wavefront's sums
+    if (w.wave_live) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            // LDS add without a returned value: nothing to wait for between the NB updates
+            const float v = sum_over_words<NB>(acc[i]);
+            if (w.lane % NB == 0)
+                __hip_atomic_fetch_add(&w.yw[w.lane / NB + OPI * i], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    }
+}
+
+template <int D>
 __global__ __launch_bounds__(SKL_SWG) void k_row_gemv1(StreamArgs p, const uint16_t *__restrict__ x,
                                                         float *__restrict__ partial)
 {
     const StreamCtx c = stream_ctx(p);
     if (!c.live) return;
-    uint4 *buf0 = smem, *buf1 = smem + (p.two_bufs ? p.buf_words : 0);
-    uint16_t *xs = reinterpret_cast<uint16_t *>(smem + (p.two_bufs ? 2 : 1) * p.buf_words);
-    auto stage_x = [&]() {
-        for (uint32_t i = threadIdx.x; i < c.c_hi - c.c_lo; i += SKL_SWG) {
-            const uint32_t ch = p.r.chan[c.c_lo + i];
-            xs[i] = ch != SKL_NO_CHANNEL ? (uint16_t)(x[ch] ^ 0x8000u) : (uint16_t)0;
-        }
-    };
-    uint32_t o[OPL];
-    float acc[OPL];
-    uint32_t off[OPL][D];
-#pragma unroll
-    for (int i = 0; i < OPL; ++i) {
-        o[i] = c.o_lo + i * SKL_SWG + threadIdx.x;
-        acc[i] = 0.f;
+    char *lds = reinterpret_cast<char *>(smem);
+    const uint32_t tab_bytes = p.two_bufs ? 2 * SKL_PBUF_DIST : p.buf_words * 16;
+    float *ysum = reinterpret_cast<float *>(lds + tab_bytes);
+    uint4 *sm_meta = reinterpret_cast<uint4 *>(lds + tab_bytes + SKL_SWG * 4);
+    uint32_t *row_addr = reinterpret_cast<uint32_t *>(lds + tab_bytes + SKL_SWG * 4 + SKL_MAX_GROUP_BLOCKS * 32);
+    uint16_t *xs = reinterpret_cast<uint16_t *>(lds + tab_bytes + SKL_G1_FIXED_LDS(D));
+    G1Walk w;
+    w.lane = threadIdx.x & 63;
+    const uint32_t wave = threadIdx.x >> 6;
+    w.o_base = c.o_lo + wave * 64;
+    w.wave_live = w.o_base < c.o_hi;
+    w.yw = ysum + wave * 64;
+    w.row_addr_w = row_addr + wave * 64 * D;
+    w.xs = xs;
+    w.nblk = min(c.b_hi - c.b_lo, (uint32_t)SKL_MAX_GROUP_BLOCKS);
+    w.bi = 0;
+    w.sm_meta = sm_meta;
+    w.K = c.K0; w.rs = c.rs0; w.chan_off = c.chan_off0;
+    copy_chunks_to_lds_async(smem, p.r.tables + c.ptoff0, D * w.K * (w.rs == 1 ? 1u : w.rs - 1), blockDim.x >> 6);
+    // the plan keeps a group at SKL_MAX_GROUP_BLOCKS blocks or fewer
+    for (uint32_t i = threadIdx.x; i < 2 * w.nblk; i += blockDim.x) sm_meta[i] = reinterpret_cast<const uint4 *>(p.r.bmeta + c.b_lo)[i];
+    w.yw[w.lane] = 0.f;
+    for (uint32_t i = threadIdx.x; i < c.c_hi - c.c_lo; i += blockDim.x) {
+        const uint32_t ch = p.r.chan[c.c_lo + i];
+        xs[i] = ch != SKL_NO_CHANNEL ? (uint16_t)(x[ch] ^ 0x8000u) : (uint16_t)0;
     }
-    uint32_t K_prev = 0, rs_prev = 0;
-    stream_blocks<D>(p, c, buf0, buf1, stage_x, [&](uint32_t K, uint32_t rs, uint32_t chan_off, const uint4 *tab) {
-        if (K != K_prev || rs != rs_prev) {
-#pragma unroll
-            for (int i = 0; i < OPL; ++i) row_offsets<D>(p.r.h, min(o[i], p.r.out - 1), K, rs, off[i]);
-            K_prev = K;
-            rs_prev = rs;
+    wait_async_copies();
+    __syncthreads();
+    while (w.bi < w.nblk) {
+        switch (w.rs) {
+        case 9: g1_run<D, 8>(p, c, w); break;
+        case 5: g1_run<D, 4>(p, c, w); break;
+        case 3: g1_run<D, 2>(p, c, w); break;
+        default: g1_run<D, 1>(p, c, w); break;
         }
-        const uint4 *xb = reinterpret_cast<const uint4 *>(xs + (chan_off - c.c_lo));
-#pragma unroll
-        for (int i = 0; i < OPL; ++i) {
-            if (o[i] < c.o_hi) {
-                switch (rs) {
-                case 9: acc[i] += row_block_dot<D, 9>(tab, off[i], xb); break;
-                case 5: acc[i] += row_block_dot<D, 5>(tab, off[i], xb); break;
-                case 3: acc[i] += row_block_dot<D, 3>(tab, off[i], xb); break;
-                default: acc[i] += row_block_dot<D, 1>(tab, off[i], xb); break;
-                }
-            }
-        }
-    });
-    float *prow = partial + (size_t)c.g * p.r.out;
-#pragma unroll
-    for (int i = 0; i < OPL; ++i)
-        if (o[i] < c.o_hi) prow[o[i]] = acc[i];
+    }
+    if (w.wave_live) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const uint32_t o = w.o_base + w.lane;
+        if (o < c.o_hi) partial[(size_t)c.g * p.r.out + o] = w.yw[w.lane];
+    }
 }
 
 // ---- decode GEMV, batch 2..16: the reconstructed weights feed the matrix
@@ -1111,15 +1302,18 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
         const dim3 grid(8 * ((L->n_bg + 7) / 8) * L->n_sseg);
         const size_t tab_bytes = (size_t)(L->two_bufs ? 2 : 1) * L->max_table_bytes;
         if (batch == 1) {
-            const size_t lds = tab_bytes + (size_t)L->max_group_chan * sizeof(uint16_t) + 16;
-#define LAUNCH1(OPL)                                                                                               \
-    DISPATCH_D(L->d, {                                                                                             \
-        st = allow_lds(k_row_gemv1<D, OPL>, lds);                                                                  \
-        if (st == SKL_OK)                                                                                          \
-            hipLaunchKernelGGL((k_row_gemv1<D, OPL>), grid, dim3(SKL_SWG), lds, stream, a, x, partial);            \
-    })
-            LAUNCH1(1)
-#undef LAUNCH1
+            // unpadded tables; buffers at fixed LDS addresses
+            a.r.tables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables);
+            a.buf_words = L->max_ptable_bytes / 16;
+            a.two_bufs = L->two_pbufs;
+            // one wavefront per 64-output unit of the longest segment (at least two for the start-up loads)
+            const uint32_t g1_waves = std::max(2u, (L->n_wunits + L->n_sseg - 1) / L->n_sseg);
+            const size_t lds = (L->two_pbufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_ptable_bytes) + SKL_G1_FIXED_LDS(L->d) +
+                               (size_t)(L->max_group_chan + 64) * sizeof(uint16_t);
+            DISPATCH_D(L->d, {
+                st = allow_lds(k_row_gemv1<D>, lds);
+                if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemv1<D>), grid, dim3(64 * g1_waves), lds, stream, a, x, partial);
+            })
         } else {
             const size_t lds = tab_bytes + (size_t)32 * (L->max_group_chan + XS_PAD) * sizeof(uint16_t) + 16;
 #define LAUNCHN(OG)                                                                                                \

@@ -1,22 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the sketch-linear hot path on one MI355X.
 
-A step is one decode GEMV (batch 1) through sketch_linear_gemv on the headline
-layer: Llama-2-7B MLP up-projection shape 4096 -> 11008, d = 4 sketch rows,
-0.5 bit/weight binary16 states, 1 % outlier input channels with 4x sketch
-width.  The tables, activations, output and workspace are resident in HBM
-before the timed region.  The same run also reports (extra keys of the one
-JSON line): decode at batch 8 and 16, the prefill GEMM at 2048 tokens, dense
-bf16 GEMV/GEMM of the same shape via torch.matmul, and the CPU oracle timed
-on the host cores.
+A step is one pass of the whole decode path -- sketch_linear_gemv at batch 1:
+hash (Eq. 3), gather from the LDS-resident tables, AbsMaxMin query (Eq. 5),
+fused dot products, split reduction, store -- on the headline layer: Llama-2-7B
+MLP up-projection shape 4096 -> 11008, d = 4 sketch rows, 0.5 bit/weight
+binary16 states, 1 % outlier input channels with 4x sketch width.  Tables,
+activations, output and workspace are resident in HBM before the timed region.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--quick]
+The one JSON line also carries (extra keys): the dominant kernel timed by
+itself (sketch_linear_gemv_partials) with its roofline, decode at batch 8 and
+16, the prefill GEMM at 2048 tokens with its MFMA roofline, dense bf16
+GEMV/GEMM of the same shapes via torch.matmul, and the CPU oracle timed on the
+host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--quick] [--no-cpu] [--calib-copy]
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -27,15 +32,18 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 # MI355X figures used for the roofline fractions
 N_CU = 256
 CLOCK_HZ = 2.4e9
-LDS_BYTES_PER_CLK_CU = 128          # LDS read bandwidth per CU and clock
-LDS_PEAK = N_CU * CLOCK_HZ * LDS_BYTES_PER_CLK_CU    # 78.6 TB/s
+VALU_LANE_INSTR_PEAK = N_CU * 4 * 16 * CLOCK_HZ     # 4 SIMDs of 16 lanes per CU: 39.3 T lane-instructions/s
+ALU_PEAK_OPS = VALU_LANE_INSTR_PEAK * 4             # packed pair x multiply-add = 4 ops per lane-instruction: 157.3 TOP/s
+LDS_PEAK = N_CU * CLOCK_HZ * 256                    # 64 banks x 4 B per CU and clock: 157.3 TB/s
 HBM_PEAK = 8.0e12
 MFMA_F16_PEAK = 2.5e15
+CALIB_COPY_BYTES = 256 << 20
 
 
 def time_launches(torch, fn, steps, warmup):
-    """Time `steps` back-to-back calls of fn on the current stream with HIP
-    events, after `warmup` untimed calls.  Returns seconds per call."""
+    """Time `steps` back-to-back calls of fn with HIP events on the stream the
+    kernels are launched on (torch's current stream), after `warmup` untimed
+    calls.  Returns (seconds per call from the events, from the host clock)."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -51,7 +59,7 @@ def time_launches(torch, fn, steps, warmup):
     return e0.elapsed_time(e1) * 1e-3 / steps, wall / steps
 
 
-def cpu_baseline(W_hat_shape, sk, x, budget_s=20.0):
+def cpu_baseline(sk, x, budget_s=20.0):
     """The oracle as it stands (single thread, plain C): query (Eq. 5) then
     the fp64 linear layer, on the same layer and activations."""
     import oracle
@@ -70,13 +78,27 @@ def cpu_baseline(W_hat_shape, sk, x, budget_s=20.0):
                       f"layer at batch 1, best {best:.2f} s", "us_per_gemv": best * 1e6}
 
 
+def measured_traffic(name):
+    """HBM bytes per launch of the dominant kernel from the committed counter
+    summary (two rocprofv3 --pmc runs, scaled by a copy of known size)."""
+    try:
+        txt = open(os.path.join(ROOT, "profiles", name)).read()
+    except OSError:
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", txt, re.M)
+    return float(m.group(1)) if m else None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--quick", action="store_true", help="decode GEMV only (for profiling runs)")
+    ap.add_argument("--quick", action="store_true", help="decode GEMV at batch 1 only (for profiling runs)")
+    ap.add_argument("--prefill-only", action="store_true", help="prefill GEMM 4096x11008 only (for profiling runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help=f"also run one device copy of {CALIB_COPY_BYTES >> 20} MiB (scale for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one GPU per box, no collectives); run with --gpus 1",
@@ -94,13 +116,51 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def prefill(out_f, steps, warmup):
+        wl4 = wk.cfg4(out_f, 0.5)
+        _, sk4 = build_sketch(wl4)
+        g4 = GpuLayer(sk4)
+        X = torch.from_numpy(wk.gen_X_bf16(wl4, wl4.tokens).view(np.int16)).to(dev)
+        Y = torch.empty(wl4.tokens, out_f, dtype=torch.bfloat16, device=dev)
+        need = skl.sketch_linear_workspace_bytes(g4.handle, 1, wl4.tokens)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+        a4 = (g4.handle, X.data_ptr(), skl.SKL_BF16, wl4.in_features, Y.data_ptr(), skl.SKL_BF16, out_f,
+              wl4.tokens, ws.data_ptr(), ws.numel(), stream)
+        s_gemm, _ = time_launches(torch, lambda: skl.sketch_linear_gemm(*a4), steps, warmup)
+        Xd = X.view(torch.bfloat16)
+        Wd4 = torch.randn(wl4.in_features, out_f, device=dev).to(torch.bfloat16)
+        s_dense, _ = time_launches(torch, lambda: torch.matmul(Xd, Wd4), steps, warmup)
+        flops = 2.0 * wl4.tokens * wl4.in_features * out_f
+        g4.close()
+        return {"sketch_us": s_gemm * 1e6, "tflops": flops / s_gemm / 1e12,
+                "dense_bf16_us": s_dense * 1e6, "dense_tflops": flops / s_dense / 1e12,
+                "speedup_vs_dense": s_dense / s_gemm,
+                "roofline": {"bound": "mfma", "achieved": flops / s_gemm / 1e12, "peak": MFMA_F16_PEAK / 1e12,
+                             "unit": "TFLOP/s", "frac": flops / s_gemm / MFMA_F16_PEAK,
+                             "traffic": measured_traffic("gemm_row_4096x11008_t2048_pmc.txt") if out_f == 11008 else None,
+                             "note": "whole entry point: activation pre-pass + fused reconstruct/MFMA kernel"}}
+
+    def calib_copy():
+        a = torch.empty(CALIB_COPY_BYTES, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+
+    if args.prefill_only:
+        print(json.dumps({"prefill_2048_tokens": {"4096x11008": prefill(11008, max(args.steps // 10, 5), 3)}}))
+        if args.calib_copy:
+            calib_copy()
+        return
+
     wl = wk.cfg3("up")
     # Offline part (out of the timed region): the sketch is built by the
     # oracle's generator (update, Eq. 4); the library only ever sees states.
     W, sk = build_sketch(wl)
     g = GpuLayer(sk)
-    stream = g.stream()
     n_w = wl.n_weights
+    d = wl.d
 
     def gemv_runner(batch):
         x = torch.from_numpy(wk.gen_x(wl, batch).view(np.int16)).to(dev)
@@ -109,26 +169,43 @@ def main():
         ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
         args_ = (g.handle, x.data_ptr(), skl.SKL_F16, wl.in_features, y.data_ptr(), skl.SKL_F16, wl.out_features,
                  batch, ws.data_ptr(), ws.numel(), stream)
-        return (lambda: skl.sketch_linear_gemv(*args_)), (x, y, ws)
+        part_ = (g.handle, x.data_ptr(), skl.SKL_F16, wl.in_features, batch, ws.data_ptr(), ws.numel(), stream)
+        return (lambda: skl.sketch_linear_gemv(*args_)), (lambda: skl.sketch_linear_gemv_partials(*part_)), (x, y, ws)
 
-    fn1, keep1 = gemv_runner(1)
+    fn1, part1, keep1 = gemv_runner(1)
     sec, wall = time_launches(torch, fn1, args.steps, args.warmup)
-    d = wl.d
-    lds_bytes = 2.0 * d * n_w                      # d two-byte state gathers per reconstructed weight
+    # the dominant kernel by itself: gather + query + dot products, no reduction
+    sec_k, _ = time_launches(torch, part1, args.steps, args.warmup)
+    if args.calib_copy:
+        calib_copy()
+
+    # Work the method needs per reconstructed weight (d = 4): d-1 16-bit maxima,
+    # a 2-instruction decode, one multiply-add, all on packed pairs: 3 vector
+    # lane-instructions or 8 elementary operations; d two-byte LDS gathers.
+    ops_per_weight = (d - 1) + 3 + 2          # maxima + (shift, multiply, add) + multiply-add
+    lane_instr_per_weight = ((d - 1) + 2 + 1) / 2.0
+    lds_bytes = 2.0 * d * n_w
+    # HBM side of the kernel: the tables once (2 bytes per state), x, and the partial sums it writes
+    hbm_alg = 2.0 * g.info["n_states"] + 2 * wl.in_features + 4 * wl.out_features * g.info["n_units"]
     result = {
-        "metric": "reconstructed weights/s, fused sketch-query decode GEMV (batch 1)",
+        "metric": "sketch-linear decode: reconstructed weights/s through the fused query + GEMV (batch 1)",
         "value": n_w / sec, "unit": "weights/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 states and activations, f32 accumulate", "data": "synthetic",
-        "config": {"workload": f"cfg3 MLP up 4096->11008, d=4, {sk.bits_per_weight:.3f} bit/weight, "
-                               "1% outlier channels at 4x width, row sketches (tile_in=1)",
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"configs[2] Llama-7B MLP up 4096->11008, d=4, {sk.bits_per_weight:.3f} bit/weight, "
+                               "1% outlier channels (x20) at 4x sketch width, row sketches (tile_in=1), decode batch 1",
                    "batch": 1, "path": g.info["path"], "partial_sums_per_output": g.info["n_units"]},
         "us_per_gemv": sec * 1e6, "us_per_gemv_wall": wall * 1e6,
-        "roofline": {"bound": "lds", "achieved": lds_bytes / sec / 1e9, "peak": LDS_PEAK / 1e9, "unit": "GB/s",
-                     "frac": lds_bytes / sec / LDS_PEAK, "traffic": None,
-                     "note": "2*d bytes of LDS gather per weight; whole step (gather kernel + partial-sum reduction)"},
-        "hbm": {"algorithmic_bytes": g.info["table_bytes"] + 2 * wl.in_features + 2 * wl.out_features,
-                "achieved_GBps": (g.info["table_bytes"] + 2 * wl.in_features + 2 * wl.out_features) / sec / 1e9},
+        "roofline": {"bound": "alu", "kernel": "k_row_gemv1<4>", "us_per_launch": sec_k * 1e6,
+                     "achieved": ops_per_weight * n_w / sec_k / 1e12, "peak": ALU_PEAK_OPS / 1e12, "unit": "TOP/s",
+                     "frac": ops_per_weight * n_w / sec_k / ALU_PEAK_OPS,
+                     "traffic": measured_traffic("gemv_row_4096x11008_b1_pmc.txt"),
+                     "valu_issue_frac": lane_instr_per_weight * n_w / sec_k / VALU_LANE_INSTR_PEAK,
+                     "note": "packed 16-bit vector ALU: 256 CUs x 64 lanes x 2.4 GHz x 4 ops (pair x multiply-add); "
+                             f"{ops_per_weight} ops and {lane_instr_per_weight} lane-instructions per weight"},
+        "lds": {"algorithmic_bytes": lds_bytes, "achieved_GBps": lds_bytes / sec_k / 1e9, "peak_GBps": LDS_PEAK / 1e9,
+                "frac": lds_bytes / sec_k / LDS_PEAK},
+        "hbm": {"algorithmic_bytes": hbm_alg, "achieved_GBps": hbm_alg / sec_k / 1e9, "frac": hbm_alg / sec_k / HBM_PEAK},
     }
 
     if not args.quick:
@@ -138,39 +215,17 @@ def main():
         for batch in (1, 8, 16):
             xd = torch.randn(batch, wl.in_features, device=dev).to(torch.bfloat16)
             s_dense, _ = time_launches(torch, lambda: torch.matmul(xd, Wd), args.steps, args.warmup)
-            fnb, keepb = (fn1, keep1) if batch == 1 else gemv_runner(batch)
+            fnb, _, keepb = (fn1, part1, keep1) if batch == 1 else gemv_runner(batch)
             s_skl = sec if batch == 1 else time_launches(torch, fnb, args.steps, args.warmup)[0]
             extra[f"batch{batch}"] = {"sketch_us": s_skl * 1e6, "dense_bf16_us": s_dense * 1e6,
                                       "weights_per_s": n_w / s_skl, "speedup_vs_dense": s_dense / s_skl}
         result["decode"] = extra
-        # prefill GEMM, 2048 tokens (cfg4: uniform widths, 0.5 bit/weight)
-        pre = {}
-        for out_f in (4096, 11008):
-            wl4 = wk.cfg4(out_f, 0.5)
-            W4, sk4 = build_sketch(wl4)
-            g4 = GpuLayer(sk4)
-            X = torch.from_numpy(wk.gen_X_bf16(wl4, wl4.tokens).view(np.int16)).to(dev)
-            Y = torch.empty(wl4.tokens, out_f, dtype=torch.bfloat16, device=dev)
-            need = skl.sketch_linear_workspace_bytes(g4.handle, 1, wl4.tokens)
-            ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
-            a4 = (g4.handle, X.data_ptr(), skl.SKL_BF16, wl4.in_features, Y.data_ptr(), skl.SKL_BF16, out_f,
-                  wl4.tokens, ws.data_ptr(), ws.numel(), stream)
-            s_gemm, _ = time_launches(torch, lambda: skl.sketch_linear_gemm(*a4), max(args.steps // 10, 5), 3)
-            Xd = X.view(torch.bfloat16)
-            Wd4 = torch.randn(wl4.in_features, out_f, device=dev).to(torch.bfloat16)
-            s_dense, _ = time_launches(torch, lambda: torch.matmul(Xd, Wd4), max(args.steps // 10, 5), 3)
-            flops = 2.0 * wl4.tokens * wl4.in_features * out_f
-            pre[f"4096x{out_f}"] = {"sketch_us": s_gemm * 1e6, "tflops": flops / s_gemm / 1e12,
-                                    "dense_bf16_us": s_dense * 1e6, "dense_tflops": flops / s_dense / 1e12,
-                                    "roofline": {"bound": "mfma", "achieved": flops / s_gemm / 1e12,
-                                                 "peak": MFMA_F16_PEAK / 1e12, "unit": "TFLOP/s",
-                                                 "frac": flops / s_gemm / MFMA_F16_PEAK}}
-            g4.close()
-        result["prefill_2048_tokens"] = pre
+        # prefill GEMM, 2048 tokens (uniform widths, 0.5 bit/weight)
+        result["prefill_2048_tokens"] = {f"4096x{o}": prefill(o, max(args.steps // 10, 5), 3) for o in (4096, 11008)}
         result["context"] = ("paper: matrix-form sketch op up to 14.9x faster than its per-weight hash op, "
                              "hardware unstated (context only, not a target)")
     if not args.no_cpu and not args.quick:
-        result["cpu_baseline"] = cpu_baseline(None, sk, wk.gen_x(wl, 1))
+        result["cpu_baseline"] = cpu_baseline(sk, wk.gen_x(wl, 1))
     else:
         result["cpu_baseline"] = None
     g.close()

@@ -39,8 +39,7 @@
  *     gemv / gemm / reconstruct only enqueue work and never synchronise;
  *     create synchronises the stream once so that the host arrays may be
  *     freed when it returns.
- *   - Calls that use the same layer handle must be ordered on one stream
- *     (the layer's device buffer holds scratch counters).
+ *   - Calls that share a workspace must be ordered on one stream.
  *   - All arguments are validated before anything is enqueued.
  */
 #ifndef SKETCH_LINEAR_H
@@ -132,6 +131,14 @@ SKL_API skl_status_t sketch_linear_gemv(const skl_layer_t *layer, const void *x,
                                 uint32_t ldx, void *y, skl_dtype_t y_dtype, uint32_t ldy,
                                 uint32_t batch, void *workspace, uint64_t workspace_bytes,
                                 void *hip_stream);
+
+/* Diagnostic: only the first of the two kernels behind sketch_linear_gemv
+ * (query, Eq. 5, fused with the products; one partial sum per output and
+ * block group left in workspace), without the reduction that produces y.
+ * For timing that kernel by itself; same argument rules as gemv. */
+SKL_API skl_status_t sketch_linear_gemv_partials(const skl_layer_t *layer, const void *x, skl_dtype_t x_dtype,
+                                         uint32_t ldx, uint32_t batch, void *workspace,
+                                         uint64_t workspace_bytes, void *hip_stream);
 
 /* Prefill:  Y[t][o] = sum_j X[t][j] * W_hat[j][o],  t < tokens (>= 1).
  *   X  DEVICE, bfloat16 or binary16, [tokens][ldx]; |X| must not exceed 65504:

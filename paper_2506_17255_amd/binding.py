@@ -29,7 +29,8 @@ STATUS_NAMES = {0: "SKL_OK", 1: "SKL_ERR_INVALID_ARG", 2: "SKL_ERR_UNSUPPORTED",
 
 EXPORTS = ("sketch_linear_device_bytes", "sketch_linear_create", "sketch_linear_info",
            "sketch_linear_workspace_bytes", "sketch_linear_gemv", "sketch_linear_gemm",
-           "sketch_linear_reconstruct", "sketch_linear_destroy", "sketch_linear_last_error")
+           "sketch_linear_reconstruct", "sketch_linear_gemv_partials", "sketch_linear_destroy",
+           "sketch_linear_last_error")
 
 
 class SketchLinearError(RuntimeError):
@@ -78,11 +79,12 @@ def load_library(path: str | None = None):
     L.sketch_linear_gemv.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_gemm.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_reconstruct.argtypes = [vp, vp, vp]
+    L.sketch_linear_gemv_partials.argtypes = [vp, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_destroy.argtypes = [vp]
     L.sketch_linear_destroy.restype = None
     L.sketch_linear_last_error.argtypes = []
     L.sketch_linear_last_error.restype = ctypes.c_char_p
-    for n in EXPORTS[:7]:
+    for n in EXPORTS[:8]:
         getattr(L, n).restype = ctypes.c_int
     _lib = L
     return L
@@ -171,6 +173,12 @@ def sketch_linear_gemm(layer: int, X: int, x_dtype: int, ldx: int, Y: int, y_dty
                        workspace: int, workspace_bytes: int, hip_stream: int = 0) -> None:
     _check(load_library().sketch_linear_gemm(layer, X, x_dtype, ldx, Y, y_dtype, ldy, tokens, workspace,
                                              workspace_bytes, hip_stream))
+
+
+def sketch_linear_gemv_partials(layer: int, x: int, x_dtype: int, ldx: int, batch: int, workspace: int,
+                                workspace_bytes: int, hip_stream: int = 0) -> None:
+    _check(load_library().sketch_linear_gemv_partials(layer, x, x_dtype, ldx, batch, workspace, workspace_bytes,
+                                                      hip_stream))
 
 
 def sketch_linear_reconstruct(layer: int, W_hat_dev: int, hip_stream: int = 0) -> None:

@@ -480,7 +480,25 @@ skl_status_t sketch_linear_gemv(const skl_layer_t *L, const void *x, skl_dtype_t
     skl_status_t st = check_io(L, x, ldx, 2, y, ldy, dtype_size(y_dt), batch, ws, ws_bytes,
                                skl_gemv_workspace_bytes(L, batch));
     if (st != SKL_OK) return st;
-    return skl_launch_gemv(L, x, ldx, y, y_dt, ldy, batch, ws, stream);
+    return skl_launch_gemv(L, x, ldx, y, y_dt, ldy, batch, ws, stream, true);
+}
+
+skl_status_t sketch_linear_gemv_partials(const skl_layer_t *L, const void *x, skl_dtype_t x_dt, uint32_t ldx,
+                                         uint32_t batch, void *ws, uint64_t ws_bytes, void *stream)
+{
+    if (!L) FAIL(SKL_ERR_INVALID_ARG, "layer is NULL");
+    if (batch < 1 || batch > 16) FAIL(SKL_ERR_INVALID_ARG, "batch = %u, must be 1..16", batch);
+    if (x_dt != SKL_F16) FAIL(SKL_ERR_UNSUPPORTED, "gemv activations must be binary16");
+    const uint64_t need = skl_gemv_workspace_bytes(L, batch);
+    if (!x || !ws) FAIL(SKL_ERR_INVALID_ARG, "activation or workspace pointer is NULL");
+    if ((uintptr_t)x % 16 || (uintptr_t)ws % 16) FAIL(SKL_ERR_INVALID_ARG, "activation/workspace pointer not 16-byte aligned");
+    if (ldx < L->in) FAIL(SKL_ERR_INVALID_ARG, "ldx = %u is smaller than in_features = %u", ldx, L->in);
+    if (ws_bytes < need)
+        FAIL(SKL_ERR_BUFFER_TOO_SMALL, "workspace holds %llu bytes, %llu needed", (unsigned long long)ws_bytes,
+             (unsigned long long)need);
+    if (overlap(ws, need, x, ((uint64_t)(batch - 1) * ldx + L->in) * 2))
+        FAIL(SKL_ERR_INVALID_ARG, "workspace overlaps the activations");
+    return skl_launch_gemv(L, x, ldx, nullptr, SKL_F32, 0, batch, ws, stream, false);
 }
 
 skl_status_t sketch_linear_gemm(const skl_layer_t *L, const void *X, skl_dtype_t x_dt, uint32_t ldx, void *Y,

@@ -133,8 +133,10 @@ static inline uint16_t skl_key_of_half(uint16_t b)
 
 // ---- launchers implemented in skl_kernels.hip (all enqueue only) -----------
 skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *stream);
+// with_reduction = false: partial sums only (y, y_dt, ldy unused)
 skl_status_t skl_launch_gemv(const skl_layer *L, const void *x, uint32_t ldx, void *y,
-                             skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *ws, void *stream);
+                             skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *ws, void *stream,
+                             bool with_reduction);
 skl_status_t skl_launch_gemm(const skl_layer *L, const void *X, skl_dtype_t x_dt, uint32_t ldx,
                              void *Y, skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, void *ws,
                              void *stream);

@@ -362,37 +362,34 @@ __device__ __forceinline__ float sum_over_words(float v)
 // The D gathers of the next output are issued before the arithmetic of the
 // current one (the scheduling barriers keep them there); left alone, the
 // compiler waits for every single gather right after issuing it.
-template <int D, int NB, uint32_t BUF_OFF>
+template <int D, int NB, uint32_t BUF_OFF, int MAXW>
 __device__ __forceinline__ void lane_block_dot(const uint32_t (&off)[NB][D], uint4 xv, float (&acc)[NB])
 {
-    constexpr bool PIPELINED = D <= 4;       // more rows would not leave registers for a second set of gathers
-    uint4 cur[D], nxt[D];
+    // Outputs whose gathers are in flight ahead of the arithmetic, as far as
+    // the registers allow: a workgroup of at most 12 wavefronts may use 168
+    // registers per lane, one of 16 wavefronts 128.
+    constexpr int AHEAD = MAXW <= 12 ? (D <= 4 ? 2 : 1) : (D <= 4 ? 1 : 0);
+    constexpr int RING = AHEAD + 1;
+    uint4 q[RING][D];
 #pragma unroll
-    for (int r = 0; r < D; ++r) cur[r] = lds_word_at(off[0][r] + BUF_OFF);
+    for (int a = 0; a < AHEAD && a < NB; ++a)
+#pragma unroll
+        for (int r = 0; r < D; ++r) q[a][r] = lds_word_at(off[a][r] + BUF_OFF);
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-        if (PIPELINED && i + 1 < NB) {
+        if (i + AHEAD < NB) {
 #pragma unroll
-            for (int r = 0; r < D; ++r) nxt[r] = lds_word_at(off[i + 1][r] + BUF_OFF);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < D; ++r) q[(i + AHEAD) % RING][r] = lds_word_at(off[i + AHEAD][r] + BUF_OFF);
         }
-        uint4 m = cur[0];
+        if (AHEAD) __builtin_amdgcn_sched_barrier(0);
+        uint4 m = q[i % RING][0];
 #pragma unroll
-        for (int r = 1; r < D; ++r) m = pk_max_u16x8(m, cur[r]);
+        for (int r = 1; r < D; ++r) m = pk_max_u16x8(m, q[i % RING][r]);
         acc[i] = dot2_acc(keys_to_neg_half2_mad(m.x), xv.x, acc[i]);
         acc[i] = dot2_acc(keys_to_neg_half2_mad(m.y), xv.y, acc[i]);
         acc[i] = dot2_acc(keys_to_neg_half2_mad(m.z), xv.z, acc[i]);
         acc[i] = dot2_acc(keys_to_neg_half2_mad(m.w), xv.w, acc[i]);
-        if (i + 1 < NB) {
-            if (PIPELINED) {
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int r = 0; r < D; ++r) cur[r] = nxt[r];
-            } else {
-#pragma unroll
-                for (int r = 0; r < D; ++r) cur[r] = lds_word_at(off[i + 1][r] + BUF_OFF);
-            }
-        }
+        if (AHEAD) __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -410,7 +407,7 @@ struct G1Walk {
 
 // A run of consecutive blocks of one width class (NB words per state row).
 // The partial sums and the table offsets of the run live in registers.
-template <int D, int NB>
+template <int D, int NB, int MAXW>
 __device__ __forceinline__ void g1_run(const StreamArgs &p, const StreamCtx &c, G1Walk &w)
 {
     const uint32_t nw = blockDim.x >> 6;
@@ -439,7 +436,7 @@ __device__ __forceinline__ void g1_run(const StreamArgs &p, const StreamCtx &c, 
                 K_prev = w.K;
             }
             const uint4 xv = reinterpret_cast<const uint4 *>(w.xs + (w.chan_off - c.c_lo))[w.lane % NB];
-            lane_block_dot<D, NB, BO>(off, xv, acc);
+            lane_block_dot<D, NB, BO, MAXW>(off, xv, acc);
         }
         if (more && !p.two_bufs) {
             __syncthreads();                 // everyone is done with the only buffer
@@ -476,9 +473,9 @@ __device__ __forceinline__ void g1_run(const StreamArgs &p, const StreamCtx &c, 
     }
 }
 
-template <int D>
-__global__ __launch_bounds__(SKL_SWG) void k_row_gemv1(StreamArgs p, const uint16_t *__restrict__ x,
-                                                        float *__restrict__ partial)
+template <int D, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void k_row_gemv1(StreamArgs p, const uint16_t *__restrict__ x,
+                                                          float *__restrict__ partial)
 {
     const StreamCtx c = stream_ctx(p);
     if (!c.live) return;
@@ -512,16 +509,20 @@ __global__ __launch_bounds__(SKL_SWG) void k_row_gemv1(StreamArgs p, const uint1
     __syncthreads();
     while (w.bi < w.nblk) {
         switch (w.rs) {
-        case 9: g1_run<D, 8>(p, c, w); break;
-        case 5: g1_run<D, 4>(p, c, w); break;
-        case 3: g1_run<D, 2>(p, c, w); break;
-        default: g1_run<D, 1>(p, c, w); break;
+        case 9:
+            if constexpr (D <= 6) {      // the plan uses 8-word blocks for d <= 6 only
+                g1_run<D, 8, MAXW>(p, c, w);
+                break;
+            }
+        case 5: g1_run<D, 4, MAXW>(p, c, w); break;
+        case 3: g1_run<D, 2, MAXW>(p, c, w); break;
+        default: g1_run<D, 1, MAXW>(p, c, w); break;
         }
     }
     if (w.wave_live) {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         const uint32_t o = w.o_base + w.lane;
-        if (o < c.o_hi) partial[(size_t)c.g * p.r.out + o] = w.yw[w.lane];
+        if (o < c.o_hi) __builtin_nontemporal_store(w.yw[w.lane], &partial[(size_t)c.g * p.r.out + o]);
     }
 }
 
@@ -1287,7 +1288,7 @@ skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *s
 }
 
 skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, void *y, skl_dtype_t y_dt,
-                             uint32_t ldy, uint32_t batch, void *ws, void *stream_)
+                             uint32_t ldy, uint32_t batch, void *ws, void *stream_, bool with_reduction)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const uint16_t *x = static_cast<const uint16_t *>(x_);
@@ -1310,10 +1311,19 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
             const uint32_t g1_waves = std::max(2u, (L->n_wunits + L->n_sseg - 1) / L->n_sseg);
             const size_t lds = (L->two_pbufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_ptable_bytes) + SKL_G1_FIXED_LDS(L->d) +
                                (size_t)(L->max_group_chan + 64) * sizeof(uint16_t);
-            DISPATCH_D(L->d, {
-                st = allow_lds(k_row_gemv1<D>, lds);
-                if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemv1<D>), grid, dim3(64 * g1_waves), lds, stream, a, x, partial);
-            })
+            if (g1_waves <= 12) {
+                DISPATCH_D(L->d, {
+                    st = allow_lds(k_row_gemv1<D, 12>, lds);
+                    if (st == SKL_OK)
+                        hipLaunchKernelGGL((k_row_gemv1<D, 12>), grid, dim3(64 * g1_waves), lds, stream, a, x, partial);
+                })
+            } else {
+                DISPATCH_D(L->d, {
+                    st = allow_lds(k_row_gemv1<D, 16>, lds);
+                    if (st == SKL_OK)
+                        hipLaunchKernelGGL((k_row_gemv1<D, 16>), grid, dim3(64 * g1_waves), lds, stream, a, x, partial);
+                })
+            }
         } else {
             const size_t lds = tab_bytes + (size_t)32 * (L->max_group_chan + XS_PAD) * sizeof(uint16_t) + 16;
 #define LAUNCHN(OG)                                                                                                \
@@ -1349,7 +1359,7 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
     }
     if (st != SKL_OK) return st;
     st = check_launch("gemv");
-    if (st != SKL_OK) return st;
+    if (st != SKL_OK || !with_reduction) return st;
     hipLaunchKernelGGL(k_reduce_partials, dim3((L->out + RED_O - 1) / RED_O, batch), dim3(SKL_WG), 0, stream, partial,
                        L->n_units, batch, L->out, y, (uint32_t)y_dt, ldy);
     return check_launch("gemv reduction");

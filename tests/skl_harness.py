@@ -80,6 +80,19 @@ class GpuLayer:
         t.cuda.synchronize()
         return out.cpu().numpy().view(np.uint16)
 
+    def gemv_partials(self, x_f16: np.ndarray) -> np.ndarray:
+        """The partial sums the first gemv kernel leaves in the workspace, as float32 [n_units][batch][out]."""
+        t = self.torch
+        batch, in_f = x_f16.shape
+        xd = t.from_numpy(np.ascontiguousarray(x_f16).view(np.int16)).to(self.dev)
+        ws, need = self.workspace(0, batch)
+        ws.zero_()
+        skl.sketch_linear_gemv_partials(self.handle, xd.data_ptr(), skl.SKL_F16, in_f, batch, ws.data_ptr(),
+                                        ws.numel(), self.stream())
+        t.cuda.synchronize()
+        n = self.info["n_units"] * batch * self.sk.out_features
+        return ws[:4 * n].view(t.float32).cpu().numpy().reshape(self.info["n_units"], batch, self.sk.out_features)
+
     def gemv(self, x_f16: np.ndarray, y_dtype: str = "f32", ldx=None, ldy=None) -> np.ndarray:
         t = self.torch
         batch, in_f = x_f16.shape

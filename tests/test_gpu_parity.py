@@ -108,6 +108,21 @@ def test_gemv_matches_oracle(name, batch):
     assert np.array_equal(y32, again), "summation order must not change from run to run"
 
 
+@pytest.mark.parametrize("batch", [1, 5])
+@pytest.mark.parametrize("name", SMALL)
+def test_gemv_partials_sum_to_the_output(name, batch):
+    """The diagnostic first stage alone: its per-unit partial sums add up to y."""
+    W, sk = small_case(name)
+    W_hat = expected_W_hat(name)
+    rng = np.random.default_rng(300 + batch)
+    x = rng.standard_normal((batch, sk.in_features)).astype(np.float16)
+    ref = oracle.linear(W_hat, x)
+    with GpuLayer(sk, flags_of(name)) as g:
+        parts = g.gemv_partials(x)
+    y = parts.astype(np.float64).sum(axis=0)
+    assert rel_fro(y, ref) <= 1e-5, rel_fro(y, ref)
+
+
 @pytest.mark.parametrize("batch", [1, 16])
 @pytest.mark.parametrize("name", SMALL)
 def test_gemv_one_hot_probe_is_exact(name, batch):

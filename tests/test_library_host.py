@@ -119,6 +119,7 @@ def test_null_arguments():
     assert L.sketch_linear_reconstruct(None, 16, None) == skl.SKL_ERR_INVALID_ARG
     assert L.sketch_linear_workspace_bytes(None, 0, 1, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
     assert L.sketch_linear_info(None, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_gemv_partials(None, None, 0, 0, 1, None, 0, None) == skl.SKL_ERR_INVALID_ARG
     L.sketch_linear_destroy(None)
 
 

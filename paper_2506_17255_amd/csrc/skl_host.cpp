@@ -194,6 +194,18 @@ static void plan_prefill(const skl_desc_t *d, skl_plan *P)
                                               c == 0 ? nt_words : 0u, 0u});
     }
     L.n_gunits = (uint32_t)P->gunits.size();
+    // step list of the second kernel: ceil(nb / 2) steps of 16 channels per block
+    P->gsteps.clear();
+    for (skl_block_meta &bm : P->bmeta) {
+        bm.step_off = (uint32_t)P->gsteps.size();
+        for (uint32_t c = 0; c < bm.nb; c += 2)
+            P->gsteps.push_back(skl_gemm_step{bm.chan_off + 8 * c, std::min(bm.nb - c, 2u)});
+    }
+    L.n_gsteps = (uint32_t)P->gsteps.size();
+    L.gemm_ns = 1;
+    for (const skl_block_meta &bm : P->bmeta) L.gemm_ns = std::max(L.gemm_ns, (bm.nb + 1) / 2);
+    L.gemm_v2 = P->bmeta.size() <= SKL_G2_MAX_BLOCKS &&
+                2ull * L.max_ptable_bytes + 2ull * SKL_G2_SLOT_BYTES + 32ull * P->bmeta.size() + 256 <= SKL_LDS_HARD_BYTES ? 1 : 0;
 }
 
 // Row-sketch plan.  Returns false when some width is too large for any block
@@ -318,6 +330,7 @@ skl_status_t skl_make_plan(const skl_desc_t *d, skl_plan *P)
         L.off_chan = off;   off = align_up(off + P->chan.size() * sizeof(uint32_t), 256);
         L.off_ginfo = off;  off = align_up(off + P->ginfo.size() * sizeof(skl_group_info), 256);
         L.off_gunits = off; off = align_up(off + P->gunits.size() * sizeof(skl_gemm_unit), 256);
+        L.off_gsteps = off; off = align_up(off + P->gsteps.size() * sizeof(skl_gemm_step), 256);
         L.off_tables = off; off = align_up(off + L.table_bytes, 256);
         L.off_ptables = off; off = align_up(off + L.ptable_bytes, 256);
     } else {
@@ -369,6 +382,7 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         memcpy(img.data() + L.off_chan, P.chan.data(), P.chan.size() * sizeof(uint32_t));
         memcpy(img.data() + L.off_ginfo, P.ginfo.data(), P.ginfo.size() * sizeof(skl_group_info));
         memcpy(img.data() + L.off_gunits, P.gunits.data(), P.gunits.size() * sizeof(skl_gemm_unit));
+        memcpy(img.data() + L.off_gsteps, P.gsteps.data(), P.gsteps.size() * sizeof(skl_gemm_step));
         // state offset of every input channel (one group per channel)
         std::vector<uint64_t> base(L.in + 1, 0);
         for (uint32_t j = 0; j < L.in; ++j) base[j + 1] = base[j] + (uint64_t)L.d * desc->group_width[j];

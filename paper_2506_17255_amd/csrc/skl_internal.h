@@ -21,6 +21,11 @@
 // Distance between the two table buffers of the batch-1 decode kernel: below
 // 2^16, so that the buffer is chosen by the offset field of the LDS reads.
 #define SKL_PBUF_DIST 65280u
+// Second prefill kernel: bytes of one reconstructed-operand slot (4 column
+// blocks x 8 rows of 32 lanes x 16 bytes, rows padded to 34 words) and the
+// most blocks whose metadata it keeps in LDS.
+#define SKL_G2_SLOT_BYTES (4u * 8u * 34u * 16u)
+#define SKL_G2_MAX_BLOCKS 512u
 
 // ---- path 0: 2-D groups, one hash evaluation per weight and sketch row ----
 struct skl_group_meta {
@@ -42,7 +47,8 @@ struct skl_block_meta {
     uint32_t chan_off;     // first entry of the block in the channel list
                            // (= first packed activation column of the block)
     uint32_t ptable_off16; // the block's table in the unpadded copy ([r][k][nb] words)
-    uint32_t pad1, pad2;
+    uint32_t step_off;     // first 16-channel MFMA step of the block in the prefill walk
+    uint32_t pad2;
 };
 
 // One block group of the decode plan: consecutive blocks [b_lo, b_hi), their
@@ -65,6 +71,13 @@ struct skl_gemm_unit {
     uint32_t first;        // 1: the unit opens its block (a new table)
     uint32_t next_table_off16, next_table_words;   // units that open a block: the following block's table (0 words: none)
     uint32_t pad;
+};
+
+// One 16-channel step of the prefill walk: two 16-byte words of a block (one
+// for blocks with a single word per state row).
+struct skl_gemm_step {
+    uint32_t chan0;        // first entry of the step in the channel list
+    uint32_t n_words;      // 1 or 2
 };
 
 struct skl_layer {
@@ -104,6 +117,11 @@ struct skl_layer {
     // prefill plan: unit width (words), activation ring depth, unit list
     uint32_t gemm_uw = 0, gemm_ring = 0, gemm_two_tabs = 0, n_gunits = 0;
     uint64_t off_gunits = 0;
+    // second prefill kernel (weights rebuilt once per workgroup by producer
+    // wavefronts): usable when two unpadded tables, two operand slots and the
+    // block metadata fit in LDS
+    uint32_t gemm_v2 = 0, n_gsteps = 0, gemm_ns = 1;   // gemm_ns: steps per block of the widest class
+    uint64_t off_gsteps = 0;
 };
 
 // The host-side plan: everything create() copies to the device.
@@ -116,6 +134,7 @@ struct skl_plan {
     std::vector<uint32_t> bg_start;
     std::vector<skl_group_info> ginfo;
     std::vector<skl_gemm_unit> gunits;
+    std::vector<skl_gemm_step> gsteps;
 };
 
 // error text of the calling thread

@@ -940,6 +940,301 @@ __global__ __launch_bounds__(GM_THREADS) void k_row_gemm(GemmArgs p)
     else gemm_store<SKL_BF16>(acc, p.Y, p.ldy, t0, p.tokens, o, p.out, q);
 }
 
+// ---- prefill, second kernel ------------------------------------------------
+// Used when two unpadded block tables fit in LDS next to two operand slots.
+// A workgroup of 8 wavefronts owns 256 tokens x 128 outputs.
+//   * Wavefronts 4..7 (producers) rebuild the weights: producer p owns the 32
+//     outputs of column block p; per channel block it gathers whole state rows
+//     from the unpadded table (lanes = (output, word) pairs, as in the batch-1
+//     decode kernel), takes the query maximum (Eq. 5), decodes, and writes the
+//     16-byte MFMA operand words into an LDS slot -- every weight of the tile
+//     is rebuilt once per workgroup.  They also issue the asynchronous
+//     global -> LDS copy of the table two blocks ahead.
+//   * Wavefronts 0..3 (consumers) own 64 tokens each: per 16-channel step they
+//     read the four operand words of the step from the slot, take their two
+//     activation words straight from global memory (re-ordered by the pre-pass
+//     so that a wavefront's load is one contiguous KiB, requested two blocks
+//     ahead into a register ring) and issue eight 32x32x16 MFMAs.
+// One workgroup barrier per channel block hands the slots and tables over.
+//
+// Operand slot: word (cb, row = 2*step + k-group, n) at ((cb*8 + row)*34 + n);
+// 34 instead of 32 words per row keeps the producers' scattered writes (eight
+// rows, two neighbouring n per 16 lanes) on distinct banks.
+#define G2_ROW 34u
+#define G2_CB_WORDS (8u * G2_ROW)
+
+// grid (ceil(steps / 4), 8 * token tiles); a workgroup re-orders 32 tokens x 4 steps
+__global__ __launch_bounds__(SKL_WG) void k_pack_activations2(const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
+                                                               uint32_t tokens, const uint32_t *__restrict__ chan,
+                                                               const skl_gemm_step *__restrict__ steps, uint32_t n_steps,
+                                                               uint4 *__restrict__ Xp)
+{
+    const uint32_t g = threadIdx.x & 7, n = threadIdx.x >> 3;      // k-group (step, half) and token of the 32-token row block
+    const uint32_t step = blockIdx.x * 4 + (g >> 1), q = g & 1;
+    if (step >= n_steps) return;
+    const uint32_t rb = blockIdx.y & 7, tile_m = blockIdx.y >> 3;
+    const uint32_t t = tile_m * GM_MT + rb * 32 + n;
+    const skl_gemm_step st = steps[step];
+    uint16_t v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        v[i] = 0;
+        if (q < st.n_words && t < tokens) {
+            const uint32_t ch = chan[st.chan0 + 8 * q + i];
+            if (ch != SKL_NO_CHANNEL) v[i] = load_neg_half(X, x_dt, (size_t)t * ldx + ch);
+        }
+    }
+    uint4 w;
+    w.x = v[0] | ((uint32_t)v[1] << 16); w.y = v[2] | ((uint32_t)v[3] << 16);
+    w.z = v[4] | ((uint32_t)v[5] << 16); w.w = v[6] | ((uint32_t)v[7] << 16);
+    Xp[(((size_t)tile_m * n_steps + step) * 8 + rb) * 64 + q * 32 + n] = w;
+}
+
+// epilogue of the second kernel: acc[rb*4+cb][i] is token t0 + rb*32 + (i/4)*8 + q*4 + i%4,
+// output o0 + cb*32; one rounding to the output type
+template <int DT>
+__device__ __forceinline__ void gemm2_store(const float16v (&acc)[8], void *Y, uint32_t ldy, uint32_t t0, uint32_t tokens,
+                                            uint32_t o0, uint32_t out, uint32_t q)
+{
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+        const uint32_t o = o0 + cb * 32;
+        if (o >= out) continue;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t t = t0 + rb * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
+                if (t < tokens) {
+                    const size_t idx = (size_t)t * ldy + o;
+                    const float v = acc[rb * 4 + cb][i];
+                    if (DT == SKL_F32) static_cast<float *>(Y)[idx] = v;
+                    else if (DT == SKL_F16) static_cast<uint16_t *>(Y)[idx] = float_to_half_bits(v);
+                    else static_cast<uint16_t *>(Y)[idx] = float_to_bf16_bits(v);
+                }
+            }
+        }
+    }
+}
+
+struct Gemm2Args {
+    HashArgs h;
+    const uint4 *ptables;
+    const skl_block_meta *bmeta;
+    const uint4 *Xp;
+    const uint4 *zeros;        // at least 1 KiB of zero bytes
+    void *Y;
+    uint32_t n_blocks, n_steps, tokens, out, y_dt, ldy, tab_words, n_col, m_tiles;
+};
+
+// producers: table offsets (bytes from the table start) of the rows this lane gathers
+template <int D, int NB>
+__device__ __forceinline__ void g2_offsets(const HashArgs &h, uint32_t o_first, uint32_t out, uint32_t K, uint32_t lane,
+                                           uint32_t (&off)[4][D])
+{
+    constexpr uint32_t OPI = 64 / NB;                       // outputs per gather instruction
+    constexpr int SETS = NB >= 2 ? NB / 2 : 1;              // instructions for the 32 outputs of a column block
+    const uint32_t sub = lane / NB, cw = lane % NB;
+    const uint32_t Kq = K << 8;
+    asm volatile("" : "+v"(o_first));                       // keep the hashes out of the loop-invariant registers
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) {
+        const uint32_t o = min(o_first + min(OPI * s + sub, 31u), out - 1);
+#pragma unroll
+        for (int r = 0; r < D; ++r) {
+            const uint32_t t = __umul24(h.A[r], o) + h.C[r];
+            off[s][r] = ((r * K + select_index(t, Kq)) * NB + cw) * 16;
+        }
+    }
+}
+
+// producers: rebuild the operand words of one block for column block cb
+template <int D, int NB>
+__device__ __forceinline__ void g2_build(const uint32_t (&off)[4][D], uint32_t tab_addr, uint32_t slot_addr, uint32_t cb,
+                                         uint32_t lane)
+{
+    constexpr uint32_t OPI = 64 / NB;
+    constexpr int SETS = NB >= 2 ? NB / 2 : 1;
+    const uint32_t sub = lane / NB, cw = lane % NB;
+    uint4 q[2][D];
+#pragma unroll
+    for (int r = 0; r < D; ++r) q[0][r] = lds_word_at(tab_addr + off[0][r]);
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) {
+        if (s + 1 < SETS) {
+#pragma unroll
+            for (int r = 0; r < D; ++r) q[(s + 1) & 1][r] = lds_word_at(tab_addr + off[s + 1][r]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        uint4 m = q[s & 1][0];
+#pragma unroll
+        for (int r = 1; r < D; ++r) m = pk_max_u16x8(m, q[s & 1][r]);
+        u32x4v w;
+        w.x = keys_to_neg_half2_mad(m.x); w.y = keys_to_neg_half2_mad(m.y);
+        w.z = keys_to_neg_half2_mad(m.z); w.w = keys_to_neg_half2_mad(m.w);
+        const uint32_t n = OPI * s + sub;
+        if (NB > 1 || n < 32)
+            *(__attribute__((address_space(3))) u32x4v *)(uintptr_t)(slot_addr + ((cb * 8 + cw) * G2_ROW + n) * 16) = w;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// NS: 16-channel steps per block of the layer's widest class (4, 2 or 1)
+template <int D, int NS>
+__global__ __launch_bounds__(GM_THREADS) void k_row_gemm2(Gemm2Args p)
+{
+    const uint32_t xcd = blockIdx.x & 7, slot0 = blockIdx.x >> 3;
+    const uint32_t tile_m = (slot0 / p.n_col) * 8 + xcd, tile_n = slot0 % p.n_col;
+    if (tile_m >= p.m_tiles) return;
+    const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void *)smem;
+    const uint32_t tab_bytes = p.tab_words * 16;
+    const uint32_t slot_base = lds0 + 2 * tab_bytes;                       // two operand slots
+    const uint4 *sm_meta = smem + (2 * tab_bytes + 2 * SKL_G2_SLOT_BYTES) / 16;   // block metadata, two words per block
+    {
+        uint4 *meta_w = smem + (2 * tab_bytes + 2 * SKL_G2_SLOT_BYTES) / 16;
+        const uint4 *gm = reinterpret_cast<const uint4 *>(p.bmeta);
+        for (uint32_t i = threadIdx.x; i < 2 * p.n_blocks; i += GM_THREADS) meta_w[i] = gm[i];
+        uint4 *slots = smem + 2 * tab_bytes / 16;                          // stale bits must not reach the MFMAs as NaN
+        for (uint32_t i = threadIdx.x; i < 2 * SKL_G2_SLOT_BYTES / 16; i += GM_THREADS) slots[i] = make_uint4(0, 0, 0, 0);
+    }
+    __syncthreads();
+
+    if (wave >= 4) {
+        // ------------------------------------------------------------ producers
+        const uint32_t pw = wave - 4;                      // column block of this wavefront
+        const uint32_t o_first = tile_n * GM_NT + pw * 32;
+        auto table_copy = [&](uint32_t b) {               // asynchronous copy of block b's table into buffer b % 2
+            const uint4 m0 = sm_meta[2 * b], m1 = sm_meta[2 * b + 1];
+            const uint32_t n_chunks = (D * m0.y * m0.w + 63) >> 6;
+            uint4 *dst = smem + (b & 1) * p.tab_words;
+            const uint4 *src = p.ptables + m1.y;
+            for (uint32_t ch = pw; ch < n_chunks; ch += 4) lds_dma_16(src + ch * 64 + lane, dst + ch * 64);
+        };
+        uint32_t off[4][D];
+        uint32_t K_prev = 0, nb_prev = 0;
+        auto build = [&](uint32_t b) {                     // operand words of block b into slot b % 2
+            const uint4 m0 = sm_meta[2 * b];               // {table_off16, K, rs, nb}
+            const uint32_t K = m0.y, nb = m0.w;
+            const bool fresh = K != K_prev || nb != nb_prev;
+            K_prev = K; nb_prev = nb;
+            const uint32_t tab_addr = lds0 + (b & 1) * tab_bytes, slot_addr = slot_base + (b & 1) * SKL_G2_SLOT_BYTES;
+            switch (nb) {
+            case 8:
+                if constexpr (D <= 6) {
+                    if (fresh) g2_offsets<D, 8>(p.h, o_first, p.out, K, lane, off);
+                    g2_build<D, 8>(off, tab_addr, slot_addr, pw, lane);
+                    break;
+                }
+            case 4:
+                if (fresh) g2_offsets<D, 4>(p.h, o_first, p.out, K, lane, off);
+                g2_build<D, 4>(off, tab_addr, slot_addr, pw, lane);
+                break;
+            case 2:
+                if (fresh) g2_offsets<D, 2>(p.h, o_first, p.out, K, lane, off);
+                g2_build<D, 2>(off, tab_addr, slot_addr, pw, lane);
+                break;
+            default:
+                if (fresh) g2_offsets<D, 1>(p.h, o_first, p.out, K, lane, off);
+                g2_build<D, 1>(off, tab_addr, slot_addr, pw, lane);
+                break;
+            }
+        };
+        table_copy(0);
+        wait_async_copies();
+        __syncthreads();                                   // table 0 is in LDS
+        if (p.n_blocks > 1) table_copy(1);
+        build(0);
+        wait_async_copies();
+        __syncthreads();                                   // operands of block 0 and table 1 are in LDS
+        for (uint32_t k = 0; k < p.n_blocks; ++k) {
+            if (k + 2 < p.n_blocks) table_copy(k + 2);     // into the buffer of table k, not read any more
+            if (k + 1 < p.n_blocks) build(k + 1);
+            wait_async_copies();
+            __syncthreads();                               // block k consumed; operands k+1 and table k+2 in place
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------- consumers
+    const uint32_t n = lane & 31, q = lane >> 5;
+    const uint32_t t0 = tile_m * GM_MT + wave * 64;        // first token of this wavefront
+    float16v acc[8];                                       // [row block][column block]
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = (float16v){0.f};
+    // activation words: Xp[((tile_m * n_steps + step) * 8 + row block) * 64 + lane]
+    const uint4 *xa = p.Xp + ((size_t)tile_m * p.n_steps * 8 + wave * 2) * 64 + lane;
+    uint4 a[2][NS][2];                                     // [block parity][step][row block]
+    // Request the activation words of block b.  Always 2*NS loads, so that the
+    // number of loads in flight is the same on every path and the waits can be
+    // counted: steps a block does not have (fewer words per state row than the
+    // widest class of the layer) read a page of zeros and contribute nothing;
+    // past the last block the last block is read again and never used.
+    auto load_a = [&](uint32_t b, auto par) {
+        constexpr int P = decltype(par)::value;
+        b = min(b, p.n_blocks - 1);
+        const uint4 m0 = sm_meta[2 * b], m1 = sm_meta[2 * b + 1];
+        const uint32_t ns = (m0.w + 1) >> 1, s0 = m1.z;    // steps of the block, first step
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const uint4 *src = (uint32_t)s < ns ? xa + (size_t)(s0 + s) * 512 : p.zeros + lane;
+            const uint4 *src1 = (uint32_t)s < ns ? src + 64 : src;
+            a[P][s][0] = src[0];
+            a[P][s][1] = src1[0];
+        }
+    };
+    const uint32_t b_lane = slot_base + (q * G2_ROW + n) * 16;
+    // NS steps of one block, straight-line: the operand words of step s+1 are
+    // read from LDS before the MFMAs of step s are issued
+    auto block_mma = [&](auto par) {
+        constexpr int P = decltype(par)::value;
+        const uint32_t baddr = b_lane + P * SKL_G2_SLOT_BYTES;
+        uint4 bw[2][4];
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) bw[0][cb] = lds_word_at(baddr + cb * G2_CB_WORDS * 16);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (s + 1 < NS) {
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb)
+                    bw[(s + 1) & 1][cb] = lds_word_at(baddr + (cb * G2_CB_WORDS + 2 * (s + 1) * G2_ROW) * 16);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb)
+                    acc[rb * 4 + cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                        __builtin_bit_cast(half8v, a[P][s][rb]), __builtin_bit_cast(half8v, bw[s & 1][cb]), acc[rb * 4 + cb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    const std::integral_constant<int, 0> even;
+    const std::integral_constant<int, 1> odd;
+    load_a(0, even);
+    load_a(1, odd);
+    __syncthreads();                                       // (table 0)
+    __syncthreads();                                       // operands of block 0
+    // blocks in pairs (both register sets in fixed roles, the same number of
+    // loads in flight on every path round the loop), an odd last block after it
+    uint32_t k = 0;
+    for (; k + 1 < p.n_blocks; k += 2) {
+        block_mma(even);
+        load_a(k + 2, even);
+        __syncthreads();
+        block_mma(odd);
+        load_a(k + 3, odd);
+        __syncthreads();
+    }
+    if (k < p.n_blocks) {
+        block_mma(even);
+        __syncthreads();
+    }
+    if (p.y_dt == SKL_F32) gemm2_store<SKL_F32>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM_NT + n, p.out, q);
+    else if (p.y_dt == SKL_F16) gemm2_store<SKL_F16>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM_NT + n, p.out, q);
+    else gemm2_store<SKL_BF16>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM_NT + n, p.out, q);
+}
+
 // ========================================================================
 // Path 0: 2-D groups, one hash evaluation per weight and sketch row.
 // A workgroup owns (group, chunk of the group's input rows, 256 outputs).
@@ -1259,8 +1554,11 @@ uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch)
 
 uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
 {
-    // one tile of 256 rows x gemm_uw words per (token tile, unit)
-    return L->path == 1 ? (uint64_t)((tokens + GM_MT - 1) / GM_MT) * L->n_gunits * GM_MT * L->gemm_uw * 16 : 0;
+    if (L->path != 1) return 0;
+    const uint64_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
+    // second kernel: 8 row blocks of 64 lanes x 16 bytes per (token tile, step);
+    // first kernel: one tile of 256 rows x gemm_uw words per (token tile, unit)
+    return L->gemm_v2 ? m_tiles * L->n_gsteps * 8192ull : m_tiles * L->n_gunits * GM_MT * L->gemm_uw * 16;
 }
 
 skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *stream_)
@@ -1376,9 +1674,34 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
         const RowArgs a = make_row_args(L);
         const skl_gemm_unit *units = reinterpret_cast<const skl_gemm_unit *>(L->dev + L->off_gunits);
         const uint32_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
-        if (m_tiles > 65535) {
-            skl_set_error("more than 65535 token tiles in one call");
+        if (m_tiles > 8191) {
+            skl_set_error("more than 8191 token tiles in one call");
             return SKL_ERR_UNSUPPORTED;
+        }
+        if (L->gemm_v2) {
+            const skl_gemm_step *steps = reinterpret_cast<const skl_gemm_step *>(L->dev + L->off_gsteps);
+            hipLaunchKernelGGL(k_pack_activations2, dim3((L->n_gsteps + 3) / 4, 8 * m_tiles), dim3(SKL_WG), 0, stream, X,
+                               (uint32_t)x_dt, ldx, tokens, a.chan, steps, L->n_gsteps, static_cast<uint4 *>(ws));
+            st = check_launch("activation packing");
+            if (st != SKL_OK) return st;
+            Gemm2Args g;
+            g.h = a.h; g.ptables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables); g.bmeta = a.bmeta;
+            g.Xp = static_cast<const uint4 *>(ws); g.Y = Y;
+            g.n_blocks = L->n_blocks; g.n_steps = L->n_gsteps; g.tokens = tokens; g.out = L->out; g.y_dt = (uint32_t)y_dt;
+            g.ldy = ldy; g.tab_words = L->max_ptable_bytes / 16; g.n_col = (L->out + GM_NT - 1) / GM_NT; g.m_tiles = m_tiles;
+            const size_t lds = 2 * (size_t)L->max_ptable_bytes + 2 * (size_t)SKL_G2_SLOT_BYTES + 32 * (size_t)L->n_blocks;
+            const dim3 grid(8 * ((m_tiles + 7) / 8) * g.n_col);
+            g.zeros = reinterpret_cast<const uint4 *>(L->dev);       // the reserved head of the layer buffer stays zero
+#define LAUNCH_GEMM2(NS_)                                                                                            \
+    DISPATCH_D(L->d, {                                                                                               \
+        st = allow_lds(k_row_gemm2<D, NS_>, lds);                                                                    \
+        if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemm2<D, NS_>), grid, dim3(GM_THREADS), lds, stream, g);         \
+    })
+            if (L->gemm_ns == 4) LAUNCH_GEMM2(4)
+            else if (L->gemm_ns == 2) LAUNCH_GEMM2(2)
+            else LAUNCH_GEMM2(1)
+#undef LAUNCH_GEMM2
+            return st == SKL_OK ? check_launch("gemm") : st;
         }
 #define LAUNCH_PACK(UW_)                                                                                             \
     hipLaunchKernelGGL(k_pack_activations<UW_>, dim3(L->n_gunits, m_tiles), dim3(SKL_WG), 0, stream, X, (uint32_t)x_dt,  \

@@ -144,9 +144,9 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
                                      0u, 0u, 0u};
     }
     L.max_group_chan = max_chan;
-    // LDS: two table buffers + 32 activation rows of the group (batched decode)
-    const uint64_t act = (uint64_t)32 * (max_chan + 8) * 2;
-    L.two_bufs = 2ull * L.max_table_bytes + act + 256 <= SKL_LDS_HARD_BYTES ? 1 : 0;
+    // batched decode (padded tables): two buffers SKL_PBUF_DIST apart, block metadata, 16 activation rows of the group
+    const uint64_t act = 16ull * (max_chan + 16) * 2 + 2048;
+    L.two_bufs = L.max_table_bytes <= SKL_PBUF_DIST && 2ull * SKL_PBUF_DIST + act <= SKL_LDS_HARD_BYTES ? 1 : 0;
     const uint64_t g1_fixed = 6144 + 4096ull * d->d;   // output sums, block metadata, state-row addresses
     // batch-1 kernel: the second buffer sits SKL_PBUF_DIST bytes after the first
     // (reachable through the offset field of an LDS read), followed by the
@@ -155,7 +155,8 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
                   2ull * SKL_PBUF_DIST + g1_fixed + 2ull * (max_chan + 64) <= SKL_LDS_HARD_BYTES ? 1 : 0;
     L.n_units = L.n_bg;
     // a single table buffer must at least fit beside the sums and activations
-    return L.two_pbufs || (uint64_t)L.max_ptable_bytes + g1_fixed + 2ull * (max_chan + 64) <= SKL_LDS_HARD_BYTES;
+    return (L.two_pbufs || (uint64_t)L.max_ptable_bytes + g1_fixed + 2ull * (max_chan + 64) <= SKL_LDS_HARD_BYTES) &&
+           (L.two_bufs || (uint64_t)L.max_table_bytes + act <= SKL_LDS_HARD_BYTES);
 }
 
 // Prefill plan for row sketches.  LDS holds two table buffers (one if the

@@ -73,9 +73,9 @@ __device__ __forceinline__ uint4 keep_if(bool keep, uint4 v)
 
 // Asynchronous copy global -> LDS without passing through registers
 // (global_load_lds_dwordx4): a wavefront moves 64 consecutive 16-byte words,
-// lane i's word landing at dst + i.  All NWAVES wavefronts of the workgroup
-// take part.  The copy is complete after wait_async_copies() by the issuing
-// wavefront (and a barrier for everybody else).
+// lane i's word landing at dst + i.  The copy is complete after
+// wait_async_copies() by the issuing wavefront (and a barrier for everybody
+// else).
 typedef __attribute__((address_space(3))) void lds_void;
 
 // One global_load_lds_dwordx4: every active lane moves 16 bytes from its own
@@ -90,16 +90,8 @@ __device__ __forceinline__ void lds_dma_16(const void *gptr, uint4 *lds_dst)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory", "m0");
 }
 
-template <int NWAVES>
-__device__ __forceinline__ void copy_to_lds_async(uint4 *dst, const uint4 *src, uint32_t n16)
-{
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (uint32_t base = wave * 64; base < n16; base += 64 * NWAVES)
-        if (base + lane < n16) lds_dma_16(src + base + lane, dst + base);
-}
-
-// The same for a source padded to whole 64-word chunks (no bounds check per
-// lane) and a workgroup of nw wavefronts: wavefront w moves chunks w, w + nw, ..
+// A source padded to whole 64-word chunks (no bounds check per lane), copied
+// by a workgroup of nw wavefronts: wavefront w moves chunks w, w + nw, ..
 __device__ __forceinline__ void copy_chunks_to_lds_async(uint4 *dst, const uint4 *src, uint32_t n16, uint32_t nw)
 {
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -204,12 +196,12 @@ __device__ __forceinline__ uint4 row_query8(const uint4 *tab, const uint32_t (&o
 }
 
 // ---- decode GEMV -----------------------------------------------------------
-// One 1024-thread workgroup per CU owns an output segment and a group of
-// consecutive channel blocks.  Lanes run along outputs; the block tables are
-// streamed through two LDS buffers (the next table is fetched into registers
-// while the current one is being gathered from), and the per-output sums stay
-// in registers across the blocks, so a workgroup emits one partial sum per
-// output for its whole block group.
+// One workgroup per CU (one wavefront per 64 outputs, up to 16) owns an output
+// segment and a group of consecutive channel blocks.  The block tables are
+// streamed through two LDS buffers (the next table is copied in while the
+// current one is being gathered from), and the per-output sums stay on chip
+// across the blocks, so a workgroup emits one partial sum per output for its
+// whole block group.
 struct StreamArgs {
     RowArgs r;
     const skl_group_info *ginfo;
@@ -246,47 +238,6 @@ __device__ __forceinline__ StreamCtx stream_ctx(const StreamArgs &p)
     c.o_lo = (uint32_t)(((uint64_t)s * p.n_wunits) / p.n_sseg) * 64;
     c.o_hi = min((uint32_t)(((uint64_t)(s + 1) * p.n_wunits) / p.n_sseg) * 64, p.r.out);
     return c;
-}
-
-// The loop over the blocks of a group.  `pre` runs after the first table has
-// been requested and before the first barrier (activation staging); `body`
-// is called once per block with that block's LDS table.  While a block is
-// being gathered from, the next block's table streams into the other buffer.
-
-template <int D, typename Pre, typename Body>
-__device__ __forceinline__ void stream_blocks(const StreamArgs &p, const StreamCtx &c, uint4 *buf0, uint4 *buf1, Pre &&pre,
-                                              Body &&body)
-{
-    constexpr int NW = SKL_SWG / 64;
-    // metadata of the group's blocks: one round of loads at start-up, LDS reads afterwards
-    __shared__ uint4 sm_meta[SKL_MAX_GROUP_BLOCKS][2];
-    const uint32_t nblk = c.b_hi - c.b_lo;
-    const bool meta_in_lds = nblk <= SKL_MAX_GROUP_BLOCKS;      // larger groups read it from memory
-    const uint4 *gmeta = reinterpret_cast<const uint4 *>(p.r.bmeta + c.b_lo);
-    if (meta_in_lds && threadIdx.x < 2 * nblk) (&sm_meta[0][0])[threadIdx.x] = gmeta[threadIdx.x];
-    uint32_t K = c.K0, rs = c.rs0, chan_off = c.chan_off0;
-    copy_to_lds_async<NW>(buf0, p.r.tables + c.toff0, D * K * rs);
-    pre();
-    wait_async_copies();
-    __syncthreads();
-    for (uint32_t bi = 0; bi < nblk; ++bi) {
-        uint4 *cur = (bi & 1) && p.two_bufs ? buf1 : buf0;
-        uint4 *nxt = (bi & 1) || !p.two_bufs ? buf0 : buf1;
-        const bool more = bi + 1 < nblk;
-        const uint32_t bn = min(bi + 1, nblk - 1);
-        const uint4 mn = meta_in_lds ? sm_meta[bn][0] : gmeta[2 * bn];              // {table_off16, K, rs, nb}
-        const uint32_t chan_offn = meta_in_lds ? sm_meta[bn][1].x : gmeta[2 * bn + 1].x;
-        const uint32_t Kn = mn.y, rsn = mn.z;
-        if (more && p.two_bufs) copy_to_lds_async<NW>(nxt, p.r.tables + mn.x, D * Kn * rsn);
-        body(K, rs, chan_off, cur);
-        if (more && !p.two_bufs) {
-            __syncthreads();                 // everyone is done with the only buffer
-            copy_to_lds_async<NW>(nxt, p.r.tables + mn.x, D * Kn * rsn);
-        }
-        wait_async_copies();
-        __syncthreads();
-        K = Kn; rs = rsn; chan_off = chan_offn;
-    }
 }
 
 // ---- decode GEMV, batch 1 ---------------------------------------------------
@@ -527,91 +478,203 @@ __global__ __launch_bounds__(MAXW * 64) void k_row_gemv1(StreamArgs p, const uin
 }
 
 // ---- decode GEMV, batch 2..16: the reconstructed weights feed the matrix
-// cores.  One 32x32x16 MFMA per 32 outputs x 16 channels; the rows of the A
-// operand are the batch (rows >= batch are zero).  A wavefront owns OG groups
-// of 32 outputs.
-#define XS_PAD 8   // halfs of padding per activation row in LDS
+// cores.  Same plan, table streaming and buffer scheme as the batch-1 kernel,
+// but on the padded tables with lanes = outputs, which is the layout the MFMA
+// operand wants: v_mfma_f32_16x16x32_f16 takes the batch as the 16 rows of A
+// and, from lane l, the 8 weights of output l % 16 for the channels of word
+// l / 16 as B.  A wavefront owns 64 outputs (four 16-output sub-blocks); per
+// 32 channels it gathers/queries/decodes four operand words and issues four
+// MFMAs.  The sums stay in registers for the whole block group.
+typedef float float4v __attribute__((ext_vector_type(4)));
 
-template <int D, int RS, int OG>
-__device__ __forceinline__ void row_block_mfma(const uint4 *tab, const uint32_t (&off)[OG][D], const uint16_t *xrow,
-                                               uint32_t q, uint32_t n_groups, float16v (&acc)[OG])
+template <int D, int NB>
+__device__ __forceinline__ void gn_offsets(const HashArgs &h, uint32_t o_base, uint32_t out, uint32_t K, uint32_t lane,
+                                           uint32_t (&off)[4][D])
 {
-    constexpr int NB = RS == 1 ? 1 : RS - 1;
-    constexpr int NS = (NB + 1) / 2;
-    const uint4 zero = make_uint4(0, 0, 0, 0);
+    constexpr uint32_t RS = NB == 1 ? 1 : NB + 1;
+    const uint32_t n = lane & 15, kg = lane >> 4;
+    const uint32_t word = min(kg, (uint32_t)NB - 1);       // classes with fewer than 4 words: lanes past the last word re-read it, their activations are zero
+    const uint32_t Kq = K << 8;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void *)smem;
+    asm volatile("" : "+v"(o_base));                        // keep the hashes out of the loop-invariant registers
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        const uint32_t c = 2 * s + q;
-        const bool live = NB > 1 || c < NB;
-        const uint4 a = keep_if(live, *reinterpret_cast<const uint4 *>(xrow + (NB > 1 ? c : 0) * 8));
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t o = min(o_base + 16 * j + n, out - 1);
 #pragma unroll
-        for (int g = 0; g < OG; ++g) {
-            if ((uint32_t)g < n_groups) {
-                const uint4 b = keep_if(live, keys_to_neg_half8(row_query8<D>(tab, off[g], NB > 1 ? c : 0)));
-                acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b),
-                                                                 acc[g], 0, 0, 0);
-            }
+        for (int r = 0; r < D; ++r) {
+            const uint32_t t = __umul24(h.A[r], o) + h.C[r];
+            off[j][r] = lds0 + ((r * K + select_index(t, Kq)) * RS + word) * 16;
         }
     }
 }
 
-template <int D, int OG>
+// one block: NB words = NB/4 (at least one) slabs of 32 channels x 4 output sub-blocks
+template <int D, int NB, uint32_t BUF_OFF>
+__device__ __forceinline__ void gn_block(const uint32_t (&off)[4][D], uint32_t x_addr, bool x_live, float4v (&acc)[4])
+{
+    constexpr int NH = NB == 8 ? 2 : 1;
+    constexpr int NP = 4 * NH;                              // (slab, sub-block) pairs
+    uint4 a[NH];
+#pragma unroll
+    for (int hh = 0; hh < NH; ++hh) a[hh] = keep_if(x_live, lds_word_at(x_addr + hh * 64));
+    constexpr bool PIPE = D <= 5;                           // gathers of the next pair in flight during the arithmetic (registers allowing)
+    uint4 q[PIPE ? 2 : 1][D];
+#pragma unroll
+    for (int r = 0; r < D; ++r) q[0][r] = lds_word_at(off[0][r] + BUF_OFF);
+#pragma unroll
+    for (int pr = 0; pr < NP; ++pr) {
+        if (PIPE && pr + 1 < NP) {
+#pragma unroll
+            for (int r = 0; r < D; ++r) q[(pr + 1) & 1][r] = lds_word_at(off[(pr + 1) & 3][r] + BUF_OFF + ((pr + 1) >> 2) * 64);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        uint4 m = q[PIPE ? pr & 1 : 0][0];
+#pragma unroll
+        for (int r = 1; r < D; ++r) m = pk_max_u16x8(m, q[PIPE ? pr & 1 : 0][r]);
+        uint4 w;
+        w.x = keys_to_neg_half2_mad(m.x); w.y = keys_to_neg_half2_mad(m.y);
+        w.z = keys_to_neg_half2_mad(m.z); w.w = keys_to_neg_half2_mad(m.w);
+        acc[pr & 3] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a[pr >> 2]), __builtin_bit_cast(half8v, w),
+                                                              acc[pr & 3], 0, 0, 0);
+        if (PIPE && pr + 1 < NP) __builtin_amdgcn_sched_barrier(0);
+        if (!PIPE && pr + 1 < NP) {
+#pragma unroll
+            for (int r = 0; r < D; ++r) q[0][r] = lds_word_at(off[(pr + 1) & 3][r] + BUF_OFF + ((pr + 1) >> 2) * 64);
+        }
+    }
+}
+
+struct GnWalk {
+    const uint4 *sm_meta;    // metadata of the group's blocks in LDS
+    uint32_t xs_addr;        // LDS address of this lane's activation row (batch row lane % 16)
+    uint32_t nblk, bi;
+    uint32_t K, rs, chan_off;
+    uint32_t lane, o_base;
+    bool wave_live;
+};
+
+template <int D, int NB>
+__device__ __forceinline__ void gn_run(const StreamArgs &p, const StreamCtx &c, GnWalk &w, float4v (&acc)[4])
+{
+    const uint32_t nw = blockDim.x >> 6;
+    uint4 *const buf0 = smem, *const buf1 = smem + SKL_PBUF_DIST / 16;
+    uint32_t off[4][D];
+    uint32_t K_prev = 0;
+    const uint32_t rs_run = w.rs;
+    const bool x_live = NB >= 4 || (w.lane >> 4) < (uint32_t)NB;
+    auto copy_next = [&](uint4 *dst, const uint4 *src, uint32_t n16) {
+        const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        for (uint32_t base = wave * 64; base < n16; base += 64 * nw)
+            if (base + lane < n16) lds_dma_16(src + base + lane, dst + base);
+    };
+    auto step = [&](auto bo_tag) {
+        constexpr uint32_t BO = decltype(bo_tag)::value;
+        uint4 *nxt = BO || !p.two_bufs ? buf0 : buf1;
+        const bool more = w.bi + 1 < w.nblk;
+        const uint32_t bn = min(w.bi + 1, w.nblk - 1);
+        const uint4 m0 = w.sm_meta[2 * bn];          // {table_off16, K, rs, nb}
+        const uint4 m1 = w.sm_meta[2 * bn + 1];      // {chan_off, ..}
+        if (more && p.two_bufs) copy_next(nxt, p.r.tables + m0.x, D * m0.y * m0.z);
+        if (w.wave_live) {
+            if (w.K != K_prev) {
+                gn_offsets<D, NB>(p.r.h, w.o_base, p.r.out, w.K, w.lane, off);
+                K_prev = w.K;
+            }
+            gn_block<D, NB, BO>(off, w.xs_addr + (w.chan_off - c.c_lo) * 2 + (x_live ? (w.lane >> 4) * 16 : 0), x_live, acc);
+        }
+        if (more && !p.two_bufs) {
+            __syncthreads();                 // everyone is done with the only buffer
+            copy_next(nxt, p.r.tables + m0.x, D * m0.y * m0.z);
+        }
+        wait_async_copies();
+        __syncthreads();
+        w.K = m0.y; w.rs = m0.z; w.chan_off = m1.x;
+        ++w.bi;
+    };
+    const std::integral_constant<uint32_t, 0> first_buf;
+    const std::integral_constant<uint32_t, SKL_PBUF_DIST> second_buf;
+    auto in_run = [&]() { return w.bi < w.nblk && w.rs == rs_run; };
+    if (p.two_bufs) {
+        if (w.bi & 1) step(second_buf);
+        while (in_run()) {
+            step(first_buf);
+            if (!in_run()) break;
+            step(second_buf);
+        }
+    } else {
+        while (in_run()) step(first_buf);
+    }
+}
+
+#define SKL_GN_FIXED_LDS (SKL_MAX_GROUP_BLOCKS * 32)
+
+template <int D>
 __global__ __launch_bounds__(SKL_SWG) void k_row_gemvN(StreamArgs p, const uint16_t *__restrict__ x, uint32_t ldx,
-                                                        uint32_t batch, float *__restrict__ partial)
+                                                        uint32_t batch, uint32_t xs_stride, float *__restrict__ partial)
 {
     const StreamCtx c = stream_ctx(p);
     if (!c.live) return;
-    uint4 *buf0 = smem, *buf1 = smem + (p.two_bufs ? p.buf_words : 0);
-    uint16_t *xs = reinterpret_cast<uint16_t *>(smem + (p.two_bufs ? 2 : 1) * p.buf_words);
-    const uint32_t nch = c.c_hi - c.c_lo, XS = nch + XS_PAD;     // 32 rows of XS halfs
-    auto stage_x = [&]() {
-        for (uint32_t i = threadIdx.x; i < 32 * nch; i += SKL_SWG) {
-            const uint32_t b = i / nch, cc = i - b * nch;
-            uint16_t v = 0;
-            if (b < batch) {
-                const uint32_t ch = p.r.chan[c.c_lo + cc];
-                if (ch != SKL_NO_CHANNEL) v = x[(size_t)b * ldx + ch] ^ 0x8000u;
-            }
-            xs[b * XS + cc] = v;
+    char *lds = reinterpret_cast<char *>(smem);
+    const uint32_t tab_bytes = p.two_bufs ? 2 * SKL_PBUF_DIST : p.buf_words * 16;
+    uint4 *sm_meta = reinterpret_cast<uint4 *>(lds + tab_bytes);
+    uint16_t *xs = reinterpret_cast<uint16_t *>(lds + tab_bytes + SKL_GN_FIXED_LDS);   // 16 rows of xs_stride halfs
+    GnWalk w;
+    w.lane = threadIdx.x & 63;
+    const uint32_t wave = threadIdx.x >> 6;
+    w.o_base = c.o_lo + wave * 64;
+    w.wave_live = w.o_base < c.o_hi;
+    w.nblk = min(c.b_hi - c.b_lo, (uint32_t)SKL_MAX_GROUP_BLOCKS);
+    w.bi = 0;
+    w.sm_meta = sm_meta;
+    w.K = c.K0; w.rs = c.rs0; w.chan_off = c.chan_off0;
+    w.xs_addr = (uint32_t)(uintptr_t)(lds_void *)xs + (w.lane & 15) * xs_stride * 2;
+    {
+        const uint32_t nwv = blockDim.x >> 6, n16 = D * w.K * w.rs;
+        for (uint32_t base = wave * 64; base < n16; base += 64 * nwv)
+            if (base + w.lane < n16) lds_dma_16(p.r.tables + c.toff0 + base + w.lane, smem + base);
+    }
+    for (uint32_t i = threadIdx.x; i < 2 * w.nblk; i += blockDim.x) sm_meta[i] = reinterpret_cast<const uint4 *>(p.r.bmeta + c.b_lo)[i];
+    // activations of the group's channels, 16 rows (rows >= batch are zero): one
+    // thread per (channel, half of the rows), so that the channel number is
+    // fetched once and the eight activation loads that depend on it go out together
+    const uint32_t nch = c.c_hi - c.c_lo;
+    for (uint32_t i = threadIdx.x; i < 2 * nch; i += blockDim.x) {
+        const uint32_t cc = i >> 1, b0 = (i & 1) * 8;
+        const uint32_t ch = p.r.chan[c.c_lo + cc];
+        uint16_t v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            v[k] = 0;
+            if (ch != SKL_NO_CHANNEL && b0 + k < batch) v[k] = x[(size_t)(b0 + k) * ldx + ch] ^ 0x8000u;
         }
-    };
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t n = lane & 31, q = lane >> 5;
-    // output groups of this wavefront: o = o_lo + g*512 + wave*32 + n
-    uint32_t n_groups = 0;
 #pragma unroll
-    for (int g = 0; g < OG; ++g)
-        if (c.o_lo + g * 512 + wave * 32 < c.o_hi) n_groups = g + 1;
-    float16v acc[OG];
-    uint32_t off[OG][D];
+        for (int k = 0; k < 8; ++k) xs[(b0 + k) * xs_stride + cc] = v[k];
+    }
+    wait_async_copies();
+    __syncthreads();
+    float4v acc[4];
 #pragma unroll
-    for (int g = 0; g < OG; ++g) acc[g] = (float16v){0.f};
-    uint32_t K_prev = 0, rs_prev = 0;
-    stream_blocks<D>(p, c, buf0, buf1, stage_x, [&](uint32_t K, uint32_t rs, uint32_t chan_off, const uint4 *tab) {
-        if (K != K_prev || rs != rs_prev) {
-#pragma unroll
-            for (int g = 0; g < OG; ++g)
-                row_offsets<D>(p.r.h, min(c.o_lo + g * 512 + wave * 32 + n, p.r.out - 1), K, rs, off[g]);
-            K_prev = K;
-            rs_prev = rs;
+    for (int j = 0; j < 4; ++j) acc[j] = (float4v){0.f, 0.f, 0.f, 0.f};
+    while (w.bi < w.nblk) {
+        switch (w.rs) {
+        case 9: gn_run<D, 8>(p, c, w, acc); break;
+        case 5: gn_run<D, 4>(p, c, w, acc); break;
+        case 3: gn_run<D, 2>(p, c, w, acc); break;
+        default: gn_run<D, 1>(p, c, w, acc); break;
         }
-        const uint16_t *xrow = xs + n * XS + (chan_off - c.c_lo);
-        switch (rs) {
-        case 9: row_block_mfma<D, 9, OG>(tab, off, xrow, q, n_groups, acc); break;
-        case 5: row_block_mfma<D, 5, OG>(tab, off, xrow, q, n_groups, acc); break;
-        case 3: row_block_mfma<D, 3, OG>(tab, off, xrow, q, n_groups, acc); break;
-        default: row_block_mfma<D, 1, OG>(tab, off, xrow, q, n_groups, acc); break;
-        }
-    });
-    float *pblk = partial + (size_t)c.g * batch * p.r.out;
+    }
+    if (w.wave_live) {
+        // acc[j][i]: batch row 4 * (lane / 16) + i, output o_base + 16 * j + lane % 16
+        float *pblk = partial + (size_t)c.g * batch * p.r.out;
 #pragma unroll
-    for (int g = 0; g < OG; ++g) {
-        const uint32_t o = c.o_lo + g * 512 + wave * 32 + n;
-        if (o < c.o_hi) {
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t o = w.o_base + 16 * j + (w.lane & 15);
+            if (o < c.o_hi) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const uint32_t m = (i >> 2) * 8 + q * 4 + (i & 3);   // row of the 32x32 result held in acc[g][i]
-                if (m < batch) pblk[(size_t)m * p.r.out + o] = acc[g][i];
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t m = 4 * (w.lane >> 4) + i;
+                    if (m < batch) __builtin_nontemporal_store(acc[j][i], &pblk[(size_t)m * p.r.out + o]);
+                }
             }
         }
     }
@@ -1599,7 +1662,6 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
         a.n_wunits = L->n_wunits; a.n_sseg = L->n_sseg; a.n_bg = L->n_bg; a.buf_words = L->max_table_bytes / 16;
         a.two_bufs = L->two_bufs;
         const dim3 grid(8 * ((L->n_bg + 7) / 8) * L->n_sseg);
-        const size_t tab_bytes = (size_t)(L->two_bufs ? 2 : 1) * L->max_table_bytes;
         if (batch == 1) {
             // unpadded tables; buffers at fixed LDS addresses
             a.r.tables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables);
@@ -1623,15 +1685,17 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
                 })
             }
         } else {
-            const size_t lds = tab_bytes + (size_t)32 * (L->max_group_chan + XS_PAD) * sizeof(uint16_t) + 16;
-#define LAUNCHN(OG)                                                                                                \
-    DISPATCH_D(L->d, {                                                                                             \
-        st = allow_lds(k_row_gemvN<D, OG>, lds);                                                                   \
-        if (st == SKL_OK)                                                                                          \
-            hipLaunchKernelGGL((k_row_gemvN<D, OG>), grid, dim3(SKL_SWG), lds, stream, a, x, ldx, batch, partial); \
-    })
-            LAUNCHN(2)     // two groups of 512 outputs per segment
-#undef LAUNCHN
+            // padded tables; 16 activation rows of xs_stride halfs, xs_stride / 8 odd (bank spread of the MFMA A reads)
+            const uint32_t xs_stride = (L->max_group_chan / 8 | 1u) * 8;
+            a.two_bufs = L->two_bufs;
+            const uint32_t gn_waves = std::max(2u, (L->n_wunits + L->n_sseg - 1) / L->n_sseg);
+            const size_t lds = (L->two_bufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_table_bytes) + SKL_GN_FIXED_LDS +
+                               (size_t)16 * xs_stride * sizeof(uint16_t);
+            DISPATCH_D(L->d, {
+                st = allow_lds(k_row_gemvN<D>, lds);
+                if (st == SKL_OK)
+                    hipLaunchKernelGGL((k_row_gemvN<D>), grid, dim3(64 * gn_waves), lds, stream, a, x, ldx, batch, xs_stride, partial);
+            })
         }
     } else {
         const TileArgs a = make_tile_args(L);

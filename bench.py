@@ -78,6 +78,53 @@ def cpu_baseline(sk, x, budget_s=20.0):
                       f"layer at batch 1, best {best:.2f} s", "us_per_gemv": best * 1e6}
 
 
+def stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream, n_blocks=32, passes=5):
+    """Batch-1 decode through a Llama-2-7B-shaped stack of linear layers: n_blocks x {q, k, v, o, gate, up,
+    down}, all sketched at 0.5 bit/weight with importance widths.  The seven layers of one block are built
+    (own seed each) and every block gets its own device copy, so a pass walks 224 distinct table sets
+    (about 1.3 GB with both layouts) and no layer finds its tables in a cache.  Per-layer times from HIP
+    events between the launches."""
+    shapes = wk.cfg5_stack(1)
+    sketches = [build_sketch(wl)[1] for wl in shapes]
+    layers = [[GpuLayer(sk) for sk in sketches] for _ in range(n_blocks)]
+    xin = {f: torch.from_numpy(wk.gen_x(wl, 1).view(np.int16)).to(dev) for wl in shapes for f in [wl.in_features]}
+    yout = {f: torch.empty(1, f, dtype=torch.float16, device=dev) for f in {wl.out_features for wl in shapes}}
+    need = max(skl.sketch_linear_workspace_bytes(g.handle, 0, 1) for g in layers[0])
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    calls = []
+    for blk in layers:
+        for wl, g in zip(shapes, blk):
+            calls.append((g.handle, xin[wl.in_features].data_ptr(), skl.SKL_F16, wl.in_features,
+                          yout[wl.out_features].data_ptr(), skl.SKL_F16, wl.out_features, 1, ws.data_ptr(), ws.numel(), stream))
+    n = len(calls)
+    for _ in range(2):
+        for a in calls:
+            skl.sketch_linear_gemv(*a)
+    torch.cuda.synchronize()
+    per_layer = np.zeros(n)
+    total = 0.0
+    for _ in range(passes):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        ev[0].record()
+        for i, a in enumerate(calls):
+            skl.sketch_linear_gemv(*a)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        per_layer += np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(n)]) * 1e3
+        total += ev[0].elapsed_time(ev[n]) * 1e3
+    per_layer /= passes
+    names = [wl.name.split("_")[-1] for wl in shapes]
+    by_name = {nm: float(per_layer[i::len(shapes)].mean()) for i, nm in enumerate(names)}
+    weights = sum(wl.n_weights for wl in shapes) * n_blocks
+    for blk in layers:
+        for g in blk:
+            g.close()
+    return {"layers": n, "us_per_pass": total / passes, "us_per_layer_mean": float(per_layer.mean()),
+            "us_per_layer_by_kind": by_name, "weights_per_s": weights / (total / passes * 1e-6),
+            "note": "224 distinct device copies (7 sketches x 32 blocks), tables not cache-resident; "
+                    "event recording between launches adds to each figure"}
+
+
 def measured_traffic(name):
     """HBM bytes per launch of the dominant kernel from the committed counter
     summary (two rocprofv3 --pmc runs, scaled by a copy of known size)."""
@@ -222,6 +269,7 @@ def main():
         result["decode"] = extra
         # prefill GEMM, 2048 tokens (uniform widths, 0.5 bit/weight)
         result["prefill_2048_tokens"] = {f"4096x{o}": prefill(o, max(args.steps // 10, 5), 3) for o in (4096, 11008)}
+        result["stack"] = stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream)
         result["context"] = ("paper: matrix-form sketch op up to 14.9x faster than its per-weight hash op, "
                              "hardware unstated (context only, not a target)")
     if not args.no_cpu and not args.quick:

@@ -61,3 +61,44 @@ def test_prefill_layers(key):
         t = int(rows[0])
         xh = wk.bf16_bits_to_f32(X[t:t + 1]).astype(np.float16)
         assert rel_fro(y32[t:t + 1], g.gemv(xh, "f32")) <= 1e-5
+
+
+@pytest.mark.parametrize("index", range(7))
+def test_stack_block_layers(index):
+    """The seven linear layers of the first decoder block of the Llama-2-7B-shaped stack (q, k, v, o, gate,
+    up, down; own seed each): bit-exact weights and batch-1 decode against the oracle."""
+    wl = wk.cfg5_stack(1)[index]
+    W, sk = build_sketch(wl)
+    W_hat = oracle.query(sk)
+    print(f"[full-size] {wl.name}: {sk.bits_per_weight:.4f} bit/weight", flush=True)
+    x = wk.gen_x(wl, 1)
+    with GpuLayer(sk) as g:
+        assert np.array_equal(g.reconstruct(), W_hat)
+        y = g.gemv(x, "f32")
+        y16 = g.gemv(x, "f16")
+    ref = oracle.linear(W_hat, x)
+    assert rel_fro(y, ref) <= 1e-5
+    assert rel_fro(y16, ref) <= TOL
+
+
+def test_70b_shaped_layer():
+    """8192 x 28672, d = 4, 0.5 bit/weight with importance widths: decode at batch 1 over all outputs and the
+    2048-token prefill on sampled rows and columns; narrow blocks (two words per state row) at full size."""
+    wl = wk.cfg5_70b()
+    W, sk = build_sketch(wl)
+    W_hat = oracle.query(sk)
+    print(f"[full-size] {wl.name}: {sk.bits_per_weight:.4f} bit/weight", flush=True)
+    x = wk.gen_x(wl, 1)
+    X = wk.gen_X_bf16(wl, wl.tokens)
+    rng = np.random.default_rng(5)
+    rows = np.sort(rng.choice(wl.tokens, size=16, replace=False))
+    cols = np.sort(rng.choice(wl.out_features, size=128, replace=False))
+    with GpuLayer(sk) as g:
+        assert np.array_equal(g.reconstruct(), W_hat)
+        y = g.gemv(x, "f32")
+        y32 = g.gemm(X, "bf16", "f32")[np.ix_(rows, cols)]
+        ybf = g.gemm(X, "bf16", "bf16")[np.ix_(rows, cols)]
+    assert rel_fro(y, oracle.linear(W_hat, x)) <= 1e-5
+    ref = oracle.linear(W_hat, X[rows], x_kind="bf16", cols=cols)
+    assert rel_fro(y32, ref) <= 1e-5
+    assert rel_fro(ybf, round_to_bf16(ref)) <= TOL

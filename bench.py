@@ -270,6 +270,36 @@ def main():
         # prefill GEMM, 2048 tokens (uniform widths, 0.5 bit/weight)
         result["prefill_2048_tokens"] = {f"4096x{o}": prefill(o, max(args.steps // 10, 5), 3) for o in (4096, 11008)}
         result["stack"] = stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream)
+        # one 70B-shaped layer, 8192 -> 28672: decode at batch 1 and prefill at 2048 tokens
+        wl7 = wk.cfg5_70b()
+        _, sk7 = build_sketch(wl7)
+        g7 = GpuLayer(sk7)
+        x7 = torch.from_numpy(wk.gen_x(wl7, 1).view(np.int16)).to(dev)
+        y7 = torch.empty(1, wl7.out_features, dtype=torch.float16, device=dev)
+        ws7 = torch.empty(max(skl.sketch_linear_workspace_bytes(g7.handle, 0, 1),
+                              skl.sketch_linear_workspace_bytes(g7.handle, 1, wl7.tokens)), dtype=torch.uint8, device=dev)
+        a7 = (g7.handle, x7.data_ptr(), skl.SKL_F16, wl7.in_features, y7.data_ptr(), skl.SKL_F16, wl7.out_features, 1,
+              ws7.data_ptr(), ws7.numel(), stream)
+        s7, _ = time_launches(torch, lambda: skl.sketch_linear_gemv(*a7), args.steps, args.warmup)
+        Wd7 = torch.randn(wl7.in_features, wl7.out_features, device=dev).to(torch.bfloat16)
+        xd7 = torch.randn(1, wl7.in_features, device=dev).to(torch.bfloat16)
+        s7d, _ = time_launches(torch, lambda: torch.matmul(xd7, Wd7), args.steps, args.warmup)
+        X7 = torch.from_numpy(wk.gen_X_bf16(wl7, wl7.tokens).view(np.int16)).to(dev)
+        Y7 = torch.empty(wl7.tokens, wl7.out_features, dtype=torch.bfloat16, device=dev)
+        b7 = (g7.handle, X7.data_ptr(), skl.SKL_BF16, wl7.in_features, Y7.data_ptr(), skl.SKL_BF16, wl7.out_features,
+              wl7.tokens, ws7.data_ptr(), ws7.numel(), stream)
+        p7, _ = time_launches(torch, lambda: skl.sketch_linear_gemm(*b7), 5, 2)
+        X7d = X7.view(torch.bfloat16)
+        p7d, _ = time_launches(torch, lambda: torch.matmul(X7d, Wd7), 5, 2)
+        fl7 = 2.0 * wl7.tokens * wl7.n_weights
+        result["layer_8192x28672"] = {
+            "bits_per_weight": sk7.bits_per_weight,
+            "decode_batch1": {"sketch_us": s7 * 1e6, "dense_bf16_us": s7d * 1e6, "weights_per_s": wl7.n_weights / s7,
+                              "speedup_vs_dense": s7d / s7},
+            "prefill_2048_tokens": {"sketch_us": p7 * 1e6, "tflops": fl7 / p7 / 1e12, "dense_bf16_us": p7d * 1e6,
+                                    "dense_tflops": fl7 / p7d / 1e12, "speedup_vs_dense": p7d / p7}}
+        g7.close()
+        del Wd7, X7, Y7, ws7
         result["context"] = ("paper: matrix-form sketch op up to 14.9x faster than its per-weight hash op, "
                              "hardware unstated (context only, not a target)")
     if not args.no_cpu and not args.quick:

@@ -205,6 +205,9 @@ static void plan_prefill(const skl_desc_t *d, skl_plan *P)
     L.n_gsteps = (uint32_t)P->gsteps.size();
     L.gemm_ns = 1;
     for (const skl_block_meta &bm : P->bmeta) L.gemm_ns = std::max(L.gemm_ns, (bm.nb + 1) / 2);
+    // third kernel: operand slots of 8 column blocks (34816 B each), a 1 KiB dummy row, tables of at most 48 chunks
+    L.gemm_v3 = L.max_ptable_bytes <= 48 * 1024 &&
+                2ull * L.max_ptable_bytes + 2ull * 34816 + 1024 + 32ull * P->bmeta.size() + 256 <= SKL_LDS_HARD_BYTES ? 1 : 0;
     L.gemm_v2 = P->bmeta.size() <= SKL_G2_MAX_BLOCKS &&
                 2ull * L.max_ptable_bytes + 2ull * SKL_G2_SLOT_BYTES + 32ull * P->bmeta.size() + 256 <= SKL_LDS_HARD_BYTES ? 1 : 0;
 }

@@ -120,6 +120,7 @@ struct skl_layer {
     // second prefill kernel (weights rebuilt once per workgroup by producer
     // wavefronts): usable when two unpadded tables, two operand slots and the
     // block metadata fit in LDS
+    uint32_t gemm_v3 = 0;     // third prefill kernel (256 x 256 tile): two tables and two wide operand slots fit in LDS, at most 12 KiB of table per wavefront
     uint32_t gemm_v2 = 0, n_gsteps = 0, gemm_ns = 1;   // gemm_ns: steps per block of the widest class
     uint64_t off_gsteps = 0;
 };

@@ -1298,6 +1298,259 @@ __global__ __launch_bounds__(GM_THREADS) void k_row_gemm2(Gemm2Args p)
     else gemm2_store<SKL_BF16>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM_NT + n, p.out, q);
 }
 
+// ---- prefill, third kernel: 256 tokens x 256 outputs per workgroup ---------
+// The table stream of a workgroup does not depend on the width of its tile, so
+// a tile twice as wide halves the traffic between L2 and the CUs, which is what
+// bounds the second kernel.  65536 accumulators need all 512 registers of four
+// wavefronts (one per SIMD), so there are no separate producer wavefronts:
+// every wavefront owns 64 tokens x 256 outputs (16 accumulator blocks), and
+// while its 64 MFMAs of block k run it rebuilds the operand words of block k+1
+// for two of the eight column blocks (gather/query/decode between the MFMAs),
+// fetches the table of block k+2 through registers and requests its
+// activation words two blocks ahead.  Blocks with fewer than eight words per
+// state row are rebuilt before the MFMAs instead (rare classes).
+#define GM3_NT 256
+#define G3_CB_WORDS (8u * G2_ROW)
+#define G3_SLOT_BYTES (8u * G3_CB_WORDS * 16u)
+
+template <int DT>
+__device__ __forceinline__ void gemm3_store(const float16v (&acc)[16], void *Y, uint32_t ldy, uint32_t t0, uint32_t tokens,
+                                            uint32_t o0, uint32_t out, uint32_t q)
+{
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+        const uint32_t o = o0 + cb * 32;
+        if (o >= out) continue;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t t = t0 + rb * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
+                if (t < tokens) {
+                    const size_t idx = (size_t)t * ldy + o;
+                    const float v = acc[rb * 8 + cb][i];
+                    if (DT == SKL_F32) static_cast<float *>(Y)[idx] = v;
+                    else if (DT == SKL_F16) static_cast<uint16_t *>(Y)[idx] = float_to_half_bits(v);
+                    else static_cast<uint16_t *>(Y)[idx] = float_to_bf16_bits(v);
+                }
+            }
+        }
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_row_gemm3(Gemm2Args p)
+{
+    const uint32_t xcd = blockIdx.x & 7, slot0 = blockIdx.x >> 3;
+    const uint32_t tile_m = (slot0 / p.n_col) * 8 + xcd, tile_n = slot0 % p.n_col;
+    if (tile_m >= p.m_tiles) return;
+    const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void *)smem;
+    const uint32_t tab_bytes = p.tab_words * 16;
+    const uint32_t slot_base = lds0 + 2 * tab_bytes;                               // two operand slots
+    const uint32_t dummy_addr = slot_base + 2 * G3_SLOT_BYTES + lane * 16;         // 1 KiB nobody reads
+    const uint32_t meta_word = (2 * tab_bytes + 2 * G3_SLOT_BYTES + 1024) / 16;
+    const uint4 *sm_meta = smem + meta_word;                                       // block metadata, two words per block
+    {
+        uint4 *meta_w = smem + meta_word;
+        const uint4 *gm = reinterpret_cast<const uint4 *>(p.bmeta);
+        for (uint32_t i = threadIdx.x; i < 2 * p.n_blocks; i += 256) meta_w[i] = gm[i];
+        uint4 *slots = smem + 2 * tab_bytes / 16;                                  // stale bits must not reach the MFMAs as NaN
+        for (uint32_t i = threadIdx.x; i < (2 * G3_SLOT_BYTES + 1024) / 16; i += 256) slots[i] = make_uint4(0, 0, 0, 0);
+    }
+    __syncthreads();
+
+    const uint32_t n = lane & 31, q = lane >> 5;
+    const uint32_t sub = lane >> 3, cw = lane & 7;              // (output, word) of the rebuild gathers, 8 words per state row
+    const uint32_t t0 = tile_m * GM_MT + wave * 64;
+    const uint32_t o_first = tile_n * GM3_NT + wave * 64;       // this wavefront rebuilds column blocks 2*wave and 2*wave + 1
+    float16v acc[16];                                           // [row block][column block]
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = (float16v){0.f};
+
+    // ---- table of a block: global -> registers -> LDS, this wavefront's quarter of the 1 KiB chunks
+    // (12 at most), three per MFMA step so that only three registers' worth is in flight at a time
+    auto table_step_load = [&](const uint4 *src, uint32_t last, int s, uint4 (&tr)[3]) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) tr[i] = src[(size_t)min(wave + 4 * (3 * s + i), last) * 64];   // past the end: the last chunk again
+    };
+    auto table_step_store = [&](uint4 *dst, uint32_t last, int s, const uint4 (&tr)[3]) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i) dst[min(wave + 4 * (3 * s + i), last) * 64] = tr[i];
+    };
+    // source, destination and last chunk of block b's table (b clamped to the last block)
+    auto table_of = [&](uint32_t b, const uint4 *&src, uint4 *&dst, uint32_t &last) {
+        b = min(b, p.n_blocks - 1);
+        const uint4 m0 = sm_meta[2 * b], m1 = sm_meta[2 * b + 1];
+        last = ((D * m0.y * m0.w + 63) >> 6) - 1;
+        src = p.ptables + m1.y + lane;
+        dst = smem + (b & 1) * p.tab_words + lane;
+    };
+    auto table_whole = [&](uint32_t b) {                        // start-up only
+        const uint4 *src; uint4 *dst; uint32_t last;
+        table_of(b, src, dst, last);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            uint4 tr[3];
+            table_step_load(src, last, s, tr);
+            table_step_store(dst, last, s, tr);
+        }
+    };
+    // ---- activation words
+    const uint4 *xa = p.Xp + ((size_t)tile_m * p.n_steps * 8 + wave * 2) * 64 + lane;
+    uint4 a[4][2];                                              // [step][row block] of the block being multiplied
+    // request the activation words of step s of block b (a page of zeros for steps the block does not
+    // have, the last block again past the end: every path issues the same loads)
+    auto load_a_step = [&](uint32_t ns, uint32_t s0, int s) {      // ns steps from step s0 on
+        const uint4 *src = (uint32_t)s < ns ? xa + (size_t)(s0 + s) * 512 : p.zeros + lane;
+        const uint4 *src1 = (uint32_t)s < ns ? src + 64 : src;
+        a[s][0] = src[0];
+        a[s][1] = src1[0];
+    };
+    // ---- rebuild state for 8-word blocks: LDS byte offsets inside a table, [column block][set][row]
+    uint32_t off[2][4][D];
+#pragma unroll
+    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+#pragma unroll
+            for (int r = 0; r < D; ++r) off[c2][st][r] = cw * 16;
+    uint32_t K_prev = 0;
+    auto fast_offsets = [&](uint32_t K) {
+        if (K == K_prev) return;
+        K_prev = K;
+        const uint32_t Kq = K << 8;
+        uint32_t of = o_first;
+        asm volatile("" : "+v"(of));
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                const uint32_t o = min(of + c2 * 32 + st * 8 + sub, p.out - 1);
+#pragma unroll
+                for (int r = 0; r < D; ++r) {
+                    const uint32_t t = __umul24(p.h.A[r], o) + p.h.C[r];
+                    off[c2][st][r] = ((r * K + select_index(t, Kq)) * 8 + cw) * 16;
+                }
+            }
+    };
+    // rebuild before the MFMAs (first block, and blocks of the narrow classes)
+    auto build_plain = [&](uint32_t b) {
+        const uint4 m0 = sm_meta[2 * b];
+        const uint32_t K = m0.y, nb = m0.w;
+        const uint32_t tab_addr = lds0 + (b & 1) * tab_bytes, slot_addr = slot_base + (b & 1) * G3_SLOT_BYTES;
+        uint32_t o2[4][D];
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2) {
+            const uint32_t of = o_first + c2 * 32, cb = wave * 2 + c2;
+            if (nb == 8) {
+                if constexpr (D <= 6) { g2_offsets<D, 8>(p.h, of, p.out, K, lane, o2); g2_build<D, 8>(o2, tab_addr, slot_addr, cb, lane); }
+            } else if (nb == 4) { g2_offsets<D, 4>(p.h, of, p.out, K, lane, o2); g2_build<D, 4>(o2, tab_addr, slot_addr, cb, lane);
+            } else if (nb == 2) { g2_offsets<D, 2>(p.h, of, p.out, K, lane, o2); g2_build<D, 2>(o2, tab_addr, slot_addr, cb, lane);
+            } else { g2_offsets<D, 1>(p.h, of, p.out, K, lane, o2); g2_build<D, 1>(o2, tab_addr, slot_addr, cb, lane); }
+        }
+    };
+    const uint32_t b_lane = slot_base + (q * G2_ROW + n) * 16;
+    // Table chunks travel global -> registers -> LDS one group of three per MFMA step; a group is
+    // requested at the start of one step and written at the end of the next, so that about two
+    // steps of MFMAs cover its latency.  Group 0 of table b + 2 is requested in the last step of
+    // block b - 1, groups 1..3 in the first three steps of block b; all four are written during block b.
+    uint4 tc0, tc1, tc2;
+    auto chunk_at = [&](uint32_t grp, uint32_t i, uint32_t last) { return min(wave + 4 * (3 * grp + i), last) * 64; };
+    uint4 *const dummy_w = smem + (dummy_addr - lds0) / 16;
+    // ---- the MFMAs of block b with everything else of the pipeline between them: operand words of
+    // the next step, the rebuild of the next block's operand words for this wavefront's two column
+    // blocks (when that block has eight words per state row), table chunks, activation words
+    auto block_mma = [&](uint32_t b) {
+        const uint32_t P = b & 1;
+        const uint32_t bn = min(b + 1, p.n_blocks - 1);
+        const bool fast = b + 1 < p.n_blocks && sm_meta[2 * bn].w == 8 && D <= 6;
+        if (b + 1 < p.n_blocks && !fast) build_plain(b + 1);
+        if (fast) fast_offsets(sm_meta[2 * bn].y);
+        const uint32_t baddr = b_lane + P * G3_SLOT_BYTES;
+        const uint32_t tab_next = lds0 + (bn & 1) * tab_bytes;
+        const uint32_t slot_next = slot_base + (bn & 1) * G3_SLOT_BYTES;
+        const uint32_t a_ns = (sm_meta[2 * bn].w + 1) >> 1, a_s0 = sm_meta[2 * bn + 1].z;     // next block's activation steps
+        const uint4 *src2, *src3; uint4 *dst2, *dst3; uint32_t last2, last3;
+        table_of(b + 2, src2, dst2, last2);
+        table_of(b + 3, src3, dst3, last3);
+        const bool t_store = b + 2 < p.n_blocks;
+        uint4 bw[8];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            __builtin_amdgcn_sched_barrier(0);
+            // -- requests of the step: a table group, (first step) the operand words, the gathers of two rebuild sets
+            const uint4 *ls = s < 3 ? src2 : src3;
+            const uint32_t ll = s < 3 ? last2 : last3;
+            const uint4 tn0 = ls[chunk_at((s + 1) & 3, 0, ll)], tn1 = ls[chunk_at((s + 1) & 3, 1, ll)],
+                        tn2 = ls[chunk_at((s + 1) & 3, 2, ll)];
+            if (s == 0) {
+#pragma unroll
+                for (int cb = 0; cb < 8; ++cb) bw[cb] = lds_word_at(baddr + (cb * G3_CB_WORDS) * 16);
+            }
+            uint4 g[2][D];                          // rebuild: column block s / 2, sets 2 * (s % 2) and 2 * (s % 2) + 1
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int r = 0; r < D; ++r) g[h][r] = lds_word_at(tab_next + off[s >> 1][2 * (s & 1) + h][r]);
+            __builtin_amdgcn_sched_barrier(0);
+            uint4 m[2];
+            u32x4v w[2];
+#pragma unroll
+            for (int cb = 0; cb < 8; ++cb) {
+                acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                    __builtin_bit_cast(half8v, a[s][0]), __builtin_bit_cast(half8v, bw[cb]), acc[cb], 0, 0, 0);
+                acc[8 + cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                    __builtin_bit_cast(half8v, a[s][1]), __builtin_bit_cast(half8v, bw[cb]), acc[8 + cb], 0, 0, 0);
+                if (s < 3) bw[cb] = lds_word_at(baddr + (cb * G3_CB_WORDS + 2 * (s + 1) * G2_ROW) * 16);
+                if (cb == 2 || cb == 4) {           // query of one set
+                    const int h = (cb - 2) >> 1;
+                    m[h] = g[h][0];
+#pragma unroll
+                    for (int r = 1; r < D; ++r) m[h] = pk_max_u16x8(m[h], g[h][r]);
+                }
+                if (cb == 3 || cb == 5) {           // its decode and its operand word
+                    const int h = (cb - 3) >> 1;
+                    w[h].x = keys_to_neg_half2_mad(m[h].x); w[h].y = keys_to_neg_half2_mad(m[h].y);
+                    w[h].z = keys_to_neg_half2_mad(m[h].z); w[h].w = keys_to_neg_half2_mad(m[h].w);
+                    const uint32_t cbn = wave * 2 + (s >> 1), nn = (2 * (s & 1) + h) * 8 + sub;
+                    const uint32_t dst = fast ? slot_next + ((cbn * 8 + cw) * G2_ROW + nn) * 16 : dummy_addr;
+                    *(__attribute__((address_space(3))) u32x4v *)(uintptr_t)dst = w[h];
+                }
+                if (cb == 6) {                      // the table group requested a step ago
+                    uint4 *d0 = t_store ? dst2 + chunk_at(s, 0, last2) : dummy_w;
+                    uint4 *d1 = t_store ? dst2 + chunk_at(s, 1, last2) : dummy_w;
+                    uint4 *d2 = t_store ? dst2 + chunk_at(s, 2, last2) : dummy_w;
+                    *d0 = tc0; *d1 = tc1; *d2 = tc2;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // -- next block's activation words into the registers just used
+            load_a_step(a_ns, a_s0, s);
+            tc0 = tn0; tc1 = tn1; tc2 = tn2;
+        }
+    };
+    {
+        const uint4 *src; uint4 *dst; uint32_t last;
+        table_of(2, src, dst, last);
+        tc0 = src[chunk_at(0, 0, last)]; tc1 = src[chunk_at(0, 1, last)]; tc2 = src[chunk_at(0, 2, last)];
+    }
+    table_whole(0);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) load_a_step((sm_meta[0].w + 1) >> 1, sm_meta[1].z, s);
+    __syncthreads();                                            // table 0 in LDS
+    build_plain(0);
+    if (p.n_blocks > 1) table_whole(1);
+    __syncthreads();                                            // operands of block 0, table 1
+    for (uint32_t k = 0; k < p.n_blocks; ++k) {
+        block_mma(k);
+        __syncthreads();
+    }
+    if (p.y_dt == SKL_F32) gemm3_store<SKL_F32>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT + n, p.out, q);
+    else if (p.y_dt == SKL_F16) gemm3_store<SKL_F16>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT + n, p.out, q);
+    else gemm3_store<SKL_BF16>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT + n, p.out, q);
+}
+
 // ========================================================================
 // Path 0: 2-D groups, one hash evaluation per weight and sketch row.
 // A workgroup owns (group, chunk of the group's input rows, 256 outputs).
@@ -1621,7 +1874,7 @@ uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
     const uint64_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
     // second kernel: 8 row blocks of 64 lanes x 16 bytes per (token tile, step);
     // first kernel: one tile of 256 rows x gemm_uw words per (token tile, unit)
-    return L->gemm_v2 ? m_tiles * L->n_gsteps * 8192ull : m_tiles * L->n_gunits * GM_MT * L->gemm_uw * 16;
+    return L->gemm_v2 || L->gemm_v3 ? m_tiles * L->n_gsteps * 8192ull : m_tiles * L->n_gunits * GM_MT * L->gemm_uw * 16;
 }
 
 skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *stream_)
@@ -1741,6 +1994,26 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
         if (m_tiles > 8191) {
             skl_set_error("more than 8191 token tiles in one call");
             return SKL_ERR_UNSUPPORTED;
+        }
+        if (L->gemm_v3) {
+            const skl_gemm_step *steps = reinterpret_cast<const skl_gemm_step *>(L->dev + L->off_gsteps);
+            hipLaunchKernelGGL(k_pack_activations2, dim3((L->n_gsteps + 3) / 4, 8 * m_tiles), dim3(SKL_WG), 0, stream, X,
+                               (uint32_t)x_dt, ldx, tokens, a.chan, steps, L->n_gsteps, static_cast<uint4 *>(ws));
+            st = check_launch("activation packing");
+            if (st != SKL_OK) return st;
+            Gemm2Args g;
+            g.h = a.h; g.ptables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables); g.bmeta = a.bmeta;
+            g.Xp = static_cast<const uint4 *>(ws); g.Y = Y;
+            g.zeros = reinterpret_cast<const uint4 *>(L->dev);       // the reserved head of the layer buffer stays zero
+            g.n_blocks = L->n_blocks; g.n_steps = L->n_gsteps; g.tokens = tokens; g.out = L->out; g.y_dt = (uint32_t)y_dt;
+            g.ldy = ldy; g.tab_words = L->max_ptable_bytes / 16; g.n_col = (L->out + GM3_NT - 1) / GM3_NT; g.m_tiles = m_tiles;
+            const size_t lds = 2 * (size_t)L->max_ptable_bytes + 2 * (size_t)G3_SLOT_BYTES + 1024 + 32 * (size_t)L->n_blocks;
+            const dim3 grid(8 * ((m_tiles + 7) / 8) * g.n_col);
+            DISPATCH_D(L->d, {
+                st = allow_lds(k_row_gemm3<D>, lds);
+                if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemm3<D>), grid, dim3(256), lds, stream, g);
+            })
+            return st == SKL_OK ? check_launch("gemm") : st;
         }
         if (L->gemm_v2) {
             const skl_gemm_step *steps = reinterpret_cast<const skl_gemm_step *>(L->dev + L->off_gsteps);

@@ -128,10 +128,10 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float f)
 
 __device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
 {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);                                           // nearest even
-    return (uint16_t)(u >> 16);
+    const uint32_t u = __builtin_bit_cast(uint32_t, f);
+    const uint32_t nan = (u >> 16) | 0x40u;                                    // NaN stays NaN
+    const uint32_t rne = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;               // nearest even
+    return (uint16_t)((u & 0x7FFFFFFFu) > 0x7F800000u ? nan : rne);
 }
 
 __device__ __forceinline__ void store_out(void *y, uint32_t dt, size_t idx, float v)
@@ -1088,6 +1088,9 @@ struct Gemm2Args {
     const uint4 *zeros;        // at least 1 KiB of zero bytes
     void *Y;
     uint32_t n_blocks, n_steps, tokens, out, y_dt, ldy, tab_words, n_col, m_tiles;
+    float *parts;              // third kernel: partial tiles
+    uint32_t T, gx, l_max, p_cap;
+    uint32_t rows_aligned;     // every row of Y starts on a 16-byte boundary
 };
 
 // producers: table offsets (bytes from the table start) of the rows this lane gathers
@@ -1313,6 +1316,46 @@ __global__ __launch_bounds__(GM_THREADS) void k_row_gemm2(Gemm2Args p)
 #define G3_CB_WORDS (8u * G2_ROW)
 #define G3_SLOT_BYTES (8u * G3_CB_WORDS * 16u)
 
+// Work split of the third kernel.  Tile t = tile_n * m_tiles + tile_m belongs to XCD t % 8 (workgroup
+// ids go round the XCDs, so with eight or more token tiles an XCD keeps one token tile's activations
+// in its L2).  An XCD runs gx workgroups; its tiles are dealt out in rounds of gx whole tiles, and the
+// blocks of the tiles left over after the last whole round are cut into equal contiguous shares, one
+// per workgroup, so that every workgroup multiplies the same number of blocks (within one).  A share
+// that covers part of a tile leaves a float32 partial in the workspace; the fix-up kernel adds a
+// tile's partials in workgroup order, which keeps the result independent of timing.
+struct G3Split {
+    uint32_t T, m_tiles, nb, gx;        // tiles, token tiles, blocks per tile, workgroups per XCD
+    uint32_t l_max, p_cap;              // workspace slots: [xcd][l_max leftover tiles][p_cap parts]
+    __host__ __device__ uint32_t tiles_of(uint32_t x) const { return T > x ? (T - x + 7) / 8 : 0; }
+    __host__ __device__ uint32_t rounds(uint32_t x) const { return tiles_of(x) / gx; }
+    __host__ __device__ uint32_t left(uint32_t x) const { return tiles_of(x) - rounds(x) * gx; }
+    __host__ __device__ uint32_t units(uint32_t x) const { return left(x) * nb; }
+    // workgroups that take a share of the leftover units: every share holds at least one unit
+    __host__ __device__ uint32_t sharers(uint32_t x) const { const uint32_t u = units(x); return u < gx ? u : gx; }
+    __host__ __device__ uint32_t share_begin(uint32_t x, uint32_t j) const
+    {
+        const uint32_t g = sharers(x);
+        return j >= g ? units(x) : (uint32_t)(((uint64_t)j * units(x)) / g);
+    }
+    // the workgroup whose share holds unit v
+    __host__ __device__ uint32_t owner(uint32_t x, uint32_t v) const
+    {
+        return (uint32_t)((((uint64_t)v + 1) * sharers(x) - 1) / units(x));
+    }
+    __host__ __device__ uint32_t parts(uint32_t x, uint32_t l) const { return owner(x, (l + 1) * nb - 1) - owner(x, l * nb) + 1; }
+    __host__ __device__ size_t slot(uint32_t x, uint32_t l, uint32_t part) const { return ((size_t)x * l_max + l) * p_cap + part; }
+};
+#define G3_SLOT_FLOATS 65536u           // one 256 x 256 partial
+
+// One accumulator element, read where it is used.  Left to itself the compiler copies all 256
+// elements out of the accumulation registers after the block loop and parks half of them in scratch memory.
+__device__ __forceinline__ float acc_elem(float v)
+{
+    float r;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(v));
+    return r;
+}
+
 template <int DT>
 __device__ __forceinline__ void gemm3_store(const float16v (&acc)[16], void *Y, uint32_t ldy, uint32_t t0, uint32_t tokens,
                                             uint32_t o0, uint32_t out, uint32_t q)
@@ -1328,7 +1371,7 @@ __device__ __forceinline__ void gemm3_store(const float16v (&acc)[16], void *Y, 
                 const uint32_t t = t0 + rb * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
                 if (t < tokens) {
                     const size_t idx = (size_t)t * ldy + o;
-                    const float v = acc[rb * 8 + cb][i];
+                    const float v = acc_elem(acc[rb * 8 + cb][i]);
                     if (DT == SKL_F32) static_cast<float *>(Y)[idx] = v;
                     else if (DT == SKL_F16) static_cast<uint16_t *>(Y)[idx] = float_to_half_bits(v);
                     else static_cast<uint16_t *>(Y)[idx] = float_to_bf16_bits(v);
@@ -1338,12 +1381,69 @@ __device__ __forceinline__ void gemm3_store(const float16v (&acc)[16], void *Y, 
     }
 }
 
+// Row-major epilogue of the third kernel: a wavefront turns its 64 x 256 results round in a private LDS
+// area, one group of rows at a time, and stores 16-byte pieces, so that every store instruction writes
+// whole 512-byte (1 KiB for float32) rows of Y instead of 2-byte elements.  Needs 16-byte aligned rows.
+#define G3_EPI_BYTES 16896u             // per wavefront: 32 rows x (512 + 16) bytes, or 16 rows x (1024 + 16)
+static_assert(4 * G3_EPI_BYTES <= 2 * G3_SLOT_BYTES + 1024, "the epilogue areas must end below the block metadata");
+template <int DT>
+__device__ __forceinline__ void gemm3_store_rows(const float16v (&acc)[16], uint32_t lds_wave, void *Y, uint32_t ldy,
+                                                 uint32_t t0, uint32_t tokens, uint32_t o_tile, uint32_t out, uint32_t lane)
+{
+    constexpr uint32_t ES = DT == SKL_F32 ? 4 : 2;
+    constexpr uint32_t ROWB = 256 * ES + 16;                    // padded: the two token groups of a store land on other banks
+    constexpr int GROUPS = DT == SKL_F32 ? 2 : 1;               // row groups per 32-row block
+    constexpr uint32_t ROWS = 32 / GROUPS, CH = 256 * ES / 16;  // rows per group, 16-byte pieces per row
+    const uint32_t n = lane & 31, q = lane >> 5;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int gr = 0; gr < GROUPS; ++gr) {
+#pragma unroll
+            for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+                for (int ii = 0; ii < 16 / GROUPS; ++ii) {
+                    const int i = gr * (16 / GROUPS) + ii;
+                    const uint32_t row = (ii >> 2) * 8 + q * 4 + (ii & 3);
+                    const uint32_t addr = lds_wave + row * ROWB + (cb * 32 + n) * ES;
+                    const float v = acc_elem(acc[rb * 8 + cb][i]);
+                    if (DT == SKL_F32) *(__attribute__((address_space(3))) float *)(uintptr_t)addr = v;
+                    else *(__attribute__((address_space(3))) uint16_t *)(uintptr_t)addr =
+                        DT == SKL_F16 ? float_to_half_bits(v) : float_to_bf16_bits(v);
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (uint32_t it = 0; it < ROWS * CH / 64; ++it) {
+                const uint32_t idx = it * 64 + lane, row = idx / CH, c = idx % CH;
+                const uint4 w = lds_word_at(lds_wave + row * ROWB + c * 16);
+                const uint32_t t = t0 + rb * 32 + gr * ROWS + row, o = o_tile + c * (16 / ES);
+                if (t < tokens && o < out) {
+                    char *dst = static_cast<char *>(Y) + ((size_t)t * ldy + o) * ES;
+                    if (o + 16 / ES <= out) {
+                        *reinterpret_cast<uint4 *>(dst) = w;
+                    } else {                                    // ragged last piece of the layer
+                        const uint32_t e[4] = {w.x, w.y, w.z, w.w};
+                        for (uint32_t b = 0; b < (out - o) * ES; b += 2)
+                            *reinterpret_cast<uint16_t *>(dst + b) = (uint16_t)(e[b >> 2] >> ((b & 2) * 8));
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+}
+
 template <int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_row_gemm3(Gemm2Args p)
 {
-    const uint32_t xcd = blockIdx.x & 7, slot0 = blockIdx.x >> 3;
-    const uint32_t tile_m = (slot0 / p.n_col) * 8 + xcd, tile_n = slot0 % p.n_col;
-    if (tile_m >= p.m_tiles) return;
+    const uint32_t xcd = blockIdx.x & 7, wg = blockIdx.x >> 3;
+    G3Split sp;
+    sp.T = p.T; sp.m_tiles = p.m_tiles; sp.nb = p.n_blocks; sp.gx = p.gx; sp.l_max = p.l_max; sp.p_cap = p.p_cap;
+    const uint32_t n_rounds = sp.rounds(xcd);
+    const uint32_t u_end = sp.share_begin(xcd, wg + 1);
+    uint32_t u_next = sp.share_begin(xcd, wg);
+    if (n_rounds == 0 && u_next >= u_end) return;
     const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void *)smem;
     const uint32_t tab_bytes = p.tab_words * 16;
@@ -1355,18 +1455,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         uint4 *meta_w = smem + meta_word;
         const uint4 *gm = reinterpret_cast<const uint4 *>(p.bmeta);
         for (uint32_t i = threadIdx.x; i < 2 * p.n_blocks; i += 256) meta_w[i] = gm[i];
-        uint4 *slots = smem + 2 * tab_bytes / 16;                                  // stale bits must not reach the MFMAs as NaN
-        for (uint32_t i = threadIdx.x; i < (2 * G3_SLOT_BYTES + 1024) / 16; i += 256) slots[i] = make_uint4(0, 0, 0, 0);
     }
     __syncthreads();
 
     const uint32_t n = lane & 31, q = lane >> 5;
     const uint32_t sub = lane >> 3, cw = lane & 7;              // (output, word) of the rebuild gathers, 8 words per state row
-    const uint32_t t0 = tile_m * GM_MT + wave * 64;
-    const uint32_t o_first = tile_n * GM3_NT + wave * 64;       // this wavefront rebuilds column blocks 2*wave and 2*wave + 1
+    uint32_t t0 = 0, o_first = 0;                               // of the current tile: first token of the wavefront; first
+                                                                // output of the two column blocks it rebuilds (2*wave, 2*wave + 1)
     float16v acc[16];                                           // [row block][column block]
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = (float16v){0.f};
 
     // ---- table of a block: global -> registers -> LDS, this wavefront's quarter of the 1 KiB chunks
     // (12 at most), three per MFMA step so that only three registers' worth is in flight at a time
@@ -1397,7 +1493,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
     };
     // ---- activation words
-    const uint4 *xa = p.Xp + ((size_t)tile_m * p.n_steps * 8 + wave * 2) * 64 + lane;
+    const uint4 *xa = p.Xp;
     uint4 a[4][2];                                              // [step][row block] of the block being multiplied
     // request the activation words of step s of block b (a page of zeros for steps the block does not
     // have, the last block again past the end: every path issues the same loads)
@@ -1530,25 +1626,115 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             tc0 = tn0; tc1 = tn1; tc2 = tn2;
         }
     };
-    {
-        const uint4 *src; uint4 *dst; uint32_t last;
-        table_of(2, src, dst, last);
-        tc0 = src[chunk_at(0, 0, last)]; tc1 = src[chunk_at(0, 1, last)]; tc2 = src[chunk_at(0, 2, last)];
-    }
-    table_whole(0);
+    // ---- the segments of this workgroup: whole tiles first, then its share of the leftover blocks
+    uint32_t round = 0;
+    for (;;) {
+        uint32_t k, k0, k1;
+        size_t part_slot = 0;
+        bool whole;
+        if (round < n_rounds) {
+            k = wg + round * sp.gx; k0 = 0; k1 = p.n_blocks; whole = true;
+            ++round;
+        } else if (u_next < u_end) {
+            const uint32_t l = u_next / p.n_blocks;
+            k0 = u_next - l * p.n_blocks;
+            k1 = min(p.n_blocks, k0 + (u_end - u_next));
+            k = n_rounds * sp.gx + l;
+            whole = k0 == 0 && k1 == p.n_blocks;
+            part_slot = sp.slot(xcd, l, wg - sp.owner(xcd, l * p.n_blocks));
+            u_next += k1 - k0;
+        } else {
+            break;
+        }
+        const uint32_t t = xcd + 8 * k, tile_m = t % p.m_tiles, tile_n = t / p.m_tiles;
+        t0 = tile_m * GM_MT + wave * 64;
+        o_first = tile_n * GM3_NT + wave * 64;
+        xa = p.Xp + ((size_t)tile_m * p.n_steps * 8 + wave * 2) * 64 + lane;
+        K_prev = 0;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) load_a_step((sm_meta[0].w + 1) >> 1, sm_meta[1].z, s);
-    __syncthreads();                                            // table 0 in LDS
-    build_plain(0);
-    if (p.n_blocks > 1) table_whole(1);
-    __syncthreads();                                            // operands of block 0, table 1
-    for (uint32_t k = 0; k < p.n_blocks; ++k) {
-        block_mma(k);
-        __syncthreads();
+        for (int i = 0; i < 16; ++i) acc[i] = (float16v){0.f};
+        {
+            uint4 *slots = smem + 2 * tab_bytes / 16;           // words no rebuild writes meet zero activations: they must not be NaN
+            for (uint32_t i = threadIdx.x; i < (2 * G3_SLOT_BYTES + 1024) / 16; i += 256) slots[i] = make_uint4(0, 0, 0, 0);
+        }
+        table_whole(k0);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) load_a_step((sm_meta[2 * k0].w + 1) >> 1, sm_meta[2 * k0 + 1].z, s);
+        __syncthreads();                                        // table k0 in LDS
+        build_plain(k0);
+        if (k0 + 1 < p.n_blocks) table_whole(k0 + 1);
+        {
+            const uint4 *src; uint4 *dst; uint32_t last;
+            table_of(k0 + 2, src, dst, last);
+            tc0 = src[chunk_at(0, 0, last)]; tc1 = src[chunk_at(0, 1, last)]; tc2 = src[chunk_at(0, 2, last)];
+        }
+        __syncthreads();                                        // operands of block k0, table k0 + 1
+        for (uint32_t kb = k0; kb < k1; ++kb) {
+            block_mma(kb);
+            __syncthreads();
+        }
+        // the addresses of the epilogue are formed here, from a lane number the compiler cannot trace back:
+        // hoisted out of the segment loop they would sit in scratch memory while the MFMA loop holds every register
+        uint32_t ln = lane;
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(ln));       // also: the last MFMA has left the pipeline
+        if (whole && p.rows_aligned) {
+            const uint32_t lw = lds0 + wave * G3_EPI_BYTES;
+            if (p.y_dt == SKL_F32) gemm3_store_rows<SKL_F32>(acc, lw, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT, p.out, ln);
+            else if (p.y_dt == SKL_F16) gemm3_store_rows<SKL_F16>(acc, lw, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT, p.out, ln);
+            else gemm3_store_rows<SKL_BF16>(acc, lw, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT, p.out, ln);
+        } else if (whole) {
+            const uint32_t ne = ln & 31, qe = ln >> 5;
+            if (p.y_dt == SKL_F32) gemm3_store<SKL_F32>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT + ne, p.out, qe);
+            else if (p.y_dt == SKL_F16) gemm3_store<SKL_F16>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT + ne, p.out, qe);
+            else gemm3_store<SKL_BF16>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT + ne, p.out, qe);
+        } else {
+            // partial tile: [wavefront][accumulator block][4 elements][lane], whole 1 KiB rows per store
+            float4 *dst = reinterpret_cast<float4 *>(p.parts + part_slot * G3_SLOT_FLOATS) + (size_t)wave * 4096 + ln;
+#pragma unroll
+            for (int ab = 0; ab < 16; ++ab)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4)
+                    dst[(ab * 4 + i4) * 64] = make_float4(acc_elem(acc[ab][4 * i4]), acc_elem(acc[ab][4 * i4 + 1]),
+                                                          acc_elem(acc[ab][4 * i4 + 2]), acc_elem(acc[ab][4 * i4 + 3]));
+        }
+        __syncthreads();                                        // the epilogue's LDS areas are free again
     }
-    if (p.y_dt == SKL_F32) gemm3_store<SKL_F32>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT + n, p.out, q);
-    else if (p.y_dt == SKL_F16) gemm3_store<SKL_F16>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT + n, p.out, q);
-    else gemm3_store<SKL_BF16>(acc, p.Y, p.ldy, t0, p.tokens, tile_n * GM3_NT + n, p.out, q);
+}
+
+// adds the partials of one accumulator block of a leftover tile in workgroup order and stores it;
+// grid (8 * l_max, 16), 256 threads laid out as in the third kernel
+__global__ __launch_bounds__(256) void k_gemm3_fixup(G3Split sp, const float *__restrict__ parts, void *Y, uint32_t y_dt,
+                                                     uint32_t ldy, uint32_t tokens, uint32_t out)
+{
+    const uint32_t xcd = blockIdx.x / sp.l_max, l = blockIdx.x % sp.l_max, ab = blockIdx.y;
+    if (l >= sp.left(xcd)) return;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, q = lane >> 5;
+    const uint32_t k = sp.rounds(xcd) * sp.gx + l, t = xcd + 8 * k, tile_m = t % sp.m_tiles, tile_n = t / sp.m_tiles;
+    const uint32_t n_parts = sp.parts(xcd, l);
+    float4 v[4];
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) v[i4] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (uint32_t part = 0; part < n_parts; ++part) {
+        const float4 *src = reinterpret_cast<const float4 *>(parts + sp.slot(xcd, l, part) * G3_SLOT_FLOATS) +
+                            (size_t)wave * 4096 + ab * 256 + lane;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const float4 w = src[i4 * 64];
+            v[i4].x += w.x; v[i4].y += w.y; v[i4].z += w.z; v[i4].w += w.w;
+        }
+    }
+    const uint32_t rb = ab >> 3, cb = ab & 7;
+    const uint32_t o = tile_n * GM3_NT + cb * 32 + n;
+    if (o >= out) return;
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+        const float e[4] = {v[i4].x, v[i4].y, v[i4].z, v[i4].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t tk = tile_m * GM_MT + wave * 64 + rb * 32 + i4 * 8 + q * 4 + c;
+            if (tk < tokens) store_out(Y, y_dt, (size_t)tk * ldy + o, e[c]);
+        }
+    }
 }
 
 // ========================================================================
@@ -1868,13 +2054,41 @@ uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch)
     return (uint64_t)L->n_units * batch * L->out * sizeof(float);
 }
 
+// split of the third prefill kernel for a call with this many tokens (256 CUs: 32 workgroups per XCD,
+// fewer when an XCD's share of the work is under four blocks per workgroup)
+static G3Split gemm3_split(const skl_layer *L, uint32_t tokens)
+{
+    G3Split sp;
+    sp.m_tiles = (tokens + GM_MT - 1) / GM_MT;
+    sp.T = sp.m_tiles * ((L->out + GM3_NT - 1) / GM3_NT);
+    sp.nb = L->n_blocks;
+    const uint64_t units0 = (uint64_t)((sp.T + 7) / 8) * sp.nb;
+    sp.gx = (uint32_t)std::min<uint64_t>(32, std::max<uint64_t>(1, units0 / 4));
+    sp.l_max = 0; sp.p_cap = 0;
+    for (uint32_t x = 0; x < 8; ++x) {
+        sp.l_max = std::max(sp.l_max, sp.left(x));
+        for (uint32_t l = 0; l < sp.left(x); ++l) sp.p_cap = std::max(sp.p_cap, sp.parts(x, l));
+    }
+    return sp;
+}
+
+static uint64_t gemm_pack_bytes(const skl_layer *L, uint32_t tokens)
+{
+    const uint64_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
+    // second and third kernel: 8 row blocks of 64 lanes x 16 bytes per (token tile, step);
+    // first kernel: one tile of 256 rows x gemm_uw words per (token tile, unit)
+    return L->gemm_v2 || L->gemm_v3 ? m_tiles * L->n_gsteps * 8192ull : m_tiles * L->n_gunits * GM_MT * L->gemm_uw * 16;
+}
+
 uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
 {
     if (L->path != 1) return 0;
-    const uint64_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
-    // second kernel: 8 row blocks of 64 lanes x 16 bytes per (token tile, step);
-    // first kernel: one tile of 256 rows x gemm_uw words per (token tile, unit)
-    return L->gemm_v2 || L->gemm_v3 ? m_tiles * L->n_gsteps * 8192ull : m_tiles * L->n_gunits * GM_MT * L->gemm_uw * 16;
+    uint64_t bytes = gemm_pack_bytes(L, tokens);
+    if (L->gemm_v3) {
+        const G3Split sp = gemm3_split(L, tokens);
+        bytes += 8ull * sp.l_max * sp.p_cap * G3_SLOT_FLOATS * sizeof(float);      // partial tiles
+    }
+    return bytes;
 }
 
 skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *stream_)
@@ -2007,13 +2221,21 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
             g.zeros = reinterpret_cast<const uint4 *>(L->dev);       // the reserved head of the layer buffer stays zero
             g.n_blocks = L->n_blocks; g.n_steps = L->n_gsteps; g.tokens = tokens; g.out = L->out; g.y_dt = (uint32_t)y_dt;
             g.ldy = ldy; g.tab_words = L->max_ptable_bytes / 16; g.n_col = (L->out + GM3_NT - 1) / GM3_NT; g.m_tiles = m_tiles;
+            const G3Split sp = gemm3_split(L, tokens);
+            g.parts = reinterpret_cast<float *>(static_cast<char *>(ws) + gemm_pack_bytes(L, tokens));
+            g.T = sp.T; g.gx = sp.gx; g.l_max = sp.l_max; g.p_cap = sp.p_cap;
+            g.rows_aligned = ((size_t)ldy * (y_dt == SKL_F32 ? 4 : 2)) % 16 == 0;
             const size_t lds = 2 * (size_t)L->max_ptable_bytes + 2 * (size_t)G3_SLOT_BYTES + 1024 + 32 * (size_t)L->n_blocks;
-            const dim3 grid(8 * ((m_tiles + 7) / 8) * g.n_col);
+            const dim3 grid(8 * sp.gx);
             DISPATCH_D(L->d, {
                 st = allow_lds(k_row_gemm3<D>, lds);
                 if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemm3<D>), grid, dim3(256), lds, stream, g);
             })
-            return st == SKL_OK ? check_launch("gemm") : st;
+            if (st == SKL_OK) st = check_launch("gemm");
+            if (st != SKL_OK || sp.l_max == 0) return st;
+            hipLaunchKernelGGL(k_gemm3_fixup, dim3(8 * sp.l_max, 16), dim3(256), 0, stream, sp, g.parts, Y, (uint32_t)y_dt, ldy,
+                               tokens, L->out);
+            return check_launch("gemm fix-up");
         }
         if (L->gemm_v2) {
             const skl_gemm_step *steps = reinterpret_cast<const skl_gemm_step *>(L->dev + L->off_gsteps);

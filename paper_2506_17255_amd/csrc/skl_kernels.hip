@@ -1053,6 +1053,73 @@ __global__ __launch_bounds__(SKL_WG) void k_pack_activations2(const uint16_t *__
     Xp[(((size_t)tile_m * n_steps + step) * 8 + rb) * 64 + q * 32 + n] = w;
 }
 
+// The same re-ordering with the rows staged in LDS: a workgroup reads TOK whole token rows with
+// coalesced loads (converting them to negated binary16 once), then gathers every step's channels from
+// LDS.
+// grid (ceil(tokens / TOK)); TOK divides 32; LDS TOK * (in + 4) * 2 bytes.
+template <int TOK>
+__global__ __launch_bounds__(SKL_WG) void k_pack_activations3(const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
+                                                               uint32_t tokens, uint32_t in, const uint32_t *__restrict__ chan,
+                                                               const skl_gemm_step *__restrict__ steps, uint32_t n_steps,
+                                                               uint4 *__restrict__ Xp)
+{
+    uint16_t *rows = reinterpret_cast<uint16_t *>(smem);
+    const uint32_t stride = ((in + 1) & ~1u) + 2;               // elements: even, and off the power-of-two bank pattern
+    const uint32_t t_first = blockIdx.x * TOK;
+    const bool vec = ldx % 8 == 0;
+    for (uint32_t j = 0; j < TOK; ++j) {
+        const uint32_t t = t_first + j;
+        if (t >= tokens) break;
+        const uint16_t *src = X + (size_t)t * ldx;
+        uint16_t *dst = rows + j * stride;
+        if (vec) {
+            for (uint32_t c = threadIdx.x * 8; c < in; c += SKL_WG * 8) {
+                if (c + 8 <= in) {
+                    const uint4 w = *reinterpret_cast<const uint4 *>(src + c);
+                    const uint32_t e[4] = {w.x, w.y, w.z, w.w};
+                    uint32_t *d32 = reinterpret_cast<uint32_t *>(dst + c);      // rows and c are even: dword aligned
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        uint32_t lo = e[i] & 0xFFFFu, hi = e[i] >> 16;
+                        if (x_dt == SKL_BF16) {
+                            lo = float_to_half_bits(__builtin_bit_cast(float, lo << 16));
+                            hi = float_to_half_bits(__builtin_bit_cast(float, hi << 16));
+                        }
+                        d32[i] = (lo | (hi << 16)) ^ 0x80008000u;
+                    }
+                } else {
+                    for (uint32_t i = c; i < in; ++i) dst[i] = load_neg_half(src, x_dt, i);
+                }
+            }
+        } else {
+            for (uint32_t c = threadIdx.x; c < in; c += SKL_WG) dst[c] = load_neg_half(src, x_dt, c);
+        }
+    }
+    __syncthreads();
+    // a thread takes one 8-channel word position and fills it for all TOK tokens: its channel list is
+    // read once, and its TOK words are neighbours in the packed layout
+    const uint32_t tile_m = t_first / GM_MT, rb = (t_first % GM_MT) / 32, n0 = t_first % 32;
+    for (uint32_t item = threadIdx.x; item < 2 * n_steps; item += SKL_WG) {
+        const uint32_t step = item >> 1, q = item & 1;
+        const skl_gemm_step st = steps[step];
+        uint32_t ch[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ch[i] = q < st.n_words ? chan[st.chan0 + 8 * q + i] : SKL_NO_CHANNEL;
+        uint4 *dst = Xp + (((size_t)tile_m * n_steps + step) * 8 + rb) * 64 + q * 32 + n0;
+#pragma unroll
+        for (uint32_t j = 0; j < TOK; ++j) {
+            const uint16_t *row = rows + j * stride;
+            uint16_t v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = ch[i] != SKL_NO_CHANNEL && t_first + j < tokens ? row[ch[i]] : (uint16_t)0;
+            uint4 w;
+            w.x = v[0] | ((uint32_t)v[1] << 16); w.y = v[2] | ((uint32_t)v[3] << 16);
+            w.z = v[4] | ((uint32_t)v[5] << 16); w.w = v[6] | ((uint32_t)v[7] << 16);
+            dst[j] = w;
+        }
+    }
+}
+
 // epilogue of the second kernel: acc[rb*4+cb][i] is token t0 + rb*32 + (i/4)*8 + q*4 + i%4,
 // output o0 + cb*32; one rounding to the output type
 template <int DT>
@@ -1572,6 +1639,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         table_of(b + 3, src3, dst3, last3);
         const bool t_store = b + 2 < p.n_blocks;
         uint4 bw[8];
+        uint4 g[2][D];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             __builtin_amdgcn_sched_barrier(0);
@@ -1584,11 +1652,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
                 for (int cb = 0; cb < 8; ++cb) bw[cb] = lds_word_at(baddr + (cb * G3_CB_WORDS) * 16);
             }
-            uint4 g[2][D];                          // rebuild: column block s / 2, sets 2 * (s % 2) and 2 * (s % 2) + 1
+            // rebuild: step s does column block s / 2, sets 2 * (s % 2) and 2 * (s % 2) + 1.  Its gathers went
+            // out late in the step before (the wavefront has nobody to hide an LDS round trip behind); those
+            // of the first step cannot: the table is complete only after the block's barrier
+            if (s == 0) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+                for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int r = 0; r < D; ++r) g[h][r] = lds_word_at(tab_next + off[s >> 1][2 * (s & 1) + h][r]);
+                    for (int r = 0; r < D; ++r) g[h][r] = lds_word_at(tab_next + off[0][h][r]);
+            }
             __builtin_amdgcn_sched_barrier(0);
             uint4 m[2];
             u32x4v w[2];
@@ -1599,21 +1671,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 acc[8 + cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
                     __builtin_bit_cast(half8v, a[s][1]), __builtin_bit_cast(half8v, bw[cb]), acc[8 + cb], 0, 0, 0);
                 if (s < 3) bw[cb] = lds_word_at(baddr + (cb * G3_CB_WORDS + 2 * (s + 1) * G2_ROW) * 16);
-                if (cb == 2 || cb == 4) {           // query of one set
-                    const int h = (cb - 2) >> 1;
+                if (cb == 3 || cb == 5) {           // query of one set
+                    const int h = (cb - 3) >> 1;
                     m[h] = g[h][0];
 #pragma unroll
                     for (int r = 1; r < D; ++r) m[h] = pk_max_u16x8(m[h], g[h][r]);
                 }
-                if (cb == 3 || cb == 5) {           // its decode and its operand word
-                    const int h = (cb - 3) >> 1;
+                if (cb == 4 || cb == 6) {           // its decode and its operand word
+                    const int h = (cb - 4) >> 1;
                     w[h].x = keys_to_neg_half2_mad(m[h].x); w[h].y = keys_to_neg_half2_mad(m[h].y);
                     w[h].z = keys_to_neg_half2_mad(m[h].z); w[h].w = keys_to_neg_half2_mad(m[h].w);
                     const uint32_t cbn = wave * 2 + (s >> 1), nn = (2 * (s & 1) + h) * 8 + sub;
                     const uint32_t dst = fast ? slot_next + ((cbn * 8 + cw) * G2_ROW + nn) * 16 : dummy_addr;
                     *(__attribute__((address_space(3))) u32x4v *)(uintptr_t)dst = w[h];
                 }
-                if (cb == 6) {                      // the table group requested a step ago
+                if (cb == 6 && s < 3) {             // the next step's gathers
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int r = 0; r < D; ++r) g[h][r] = lds_word_at(tab_next + off[(s + 1) >> 1][2 * ((s + 1) & 1) + h][r]);
+                }
+                if (cb == 7) {                      // the table group requested a step ago
                     uint4 *d0 = t_store ? dst2 + chunk_at(s, 0, last2) : dummy_w;
                     uint4 *d1 = t_store ? dst2 + chunk_at(s, 1, last2) : dummy_w;
                     uint4 *d2 = t_store ? dst2 + chunk_at(s, 2, last2) : dummy_w;
@@ -2194,6 +2272,26 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
     return check_launch("gemv reduction");
 }
 
+// activation re-ordering for the second and third prefill kernels: rows staged in LDS when four
+// of them fit, else gathered from global memory
+static skl_status_t launch_pack(const skl_layer *L, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx, uint32_t tokens,
+                                const uint32_t *chan, const skl_gemm_step *steps, uint4 *Xp, hipStream_t stream)
+{
+    const uint32_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
+    const size_t row_bytes = ((size_t)L->in + 4) * 2;           // an even number of elements plus one dword of padding
+    skl_status_t st = SKL_OK;
+    if (4 * row_bytes <= 160 * 1024) {                          // up to 10 KiB rows: four workgroups per CU overlap their phases
+        st = allow_lds(k_pack_activations3<4>, 4 * row_bytes);
+        if (st != SKL_OK) return st;
+        hipLaunchKernelGGL(k_pack_activations3<4>, dim3((tokens + 3) / 4), dim3(SKL_WG), 4 * row_bytes, stream, X, (uint32_t)x_dt,
+                           ldx, tokens, L->in, chan, steps, L->n_gsteps, Xp);
+    } else {
+        hipLaunchKernelGGL(k_pack_activations2, dim3((L->n_gsteps + 3) / 4, 8 * m_tiles), dim3(SKL_WG), 0, stream, X,
+                           (uint32_t)x_dt, ldx, tokens, chan, steps, L->n_gsteps, Xp);
+    }
+    return check_launch("activation packing");
+}
+
 skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_dt, uint32_t ldx, void *Y,
                              skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, void *ws, void *stream_)
 {
@@ -2211,9 +2309,7 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
         }
         if (L->gemm_v3) {
             const skl_gemm_step *steps = reinterpret_cast<const skl_gemm_step *>(L->dev + L->off_gsteps);
-            hipLaunchKernelGGL(k_pack_activations2, dim3((L->n_gsteps + 3) / 4, 8 * m_tiles), dim3(SKL_WG), 0, stream, X,
-                               (uint32_t)x_dt, ldx, tokens, a.chan, steps, L->n_gsteps, static_cast<uint4 *>(ws));
-            st = check_launch("activation packing");
+            st = launch_pack(L, X, x_dt, ldx, tokens, a.chan, steps, static_cast<uint4 *>(ws), stream);
             if (st != SKL_OK) return st;
             Gemm2Args g;
             g.h = a.h; g.ptables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables); g.bmeta = a.bmeta;
@@ -2239,9 +2335,7 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
         }
         if (L->gemm_v2) {
             const skl_gemm_step *steps = reinterpret_cast<const skl_gemm_step *>(L->dev + L->off_gsteps);
-            hipLaunchKernelGGL(k_pack_activations2, dim3((L->n_gsteps + 3) / 4, 8 * m_tiles), dim3(SKL_WG), 0, stream, X,
-                               (uint32_t)x_dt, ldx, tokens, a.chan, steps, L->n_gsteps, static_cast<uint4 *>(ws));
-            st = check_launch("activation packing");
+            st = launch_pack(L, X, x_dt, ldx, tokens, a.chan, steps, static_cast<uint4 *>(ws), stream);
             if (st != SKL_OK) return st;
             Gemm2Args g;
             g.h = a.h; g.ptables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables); g.bmeta = a.bmeta;

@@ -152,6 +152,24 @@ SKL_API skl_status_t sketch_linear_gemm(const skl_layer_t *layer, const void *X,
                                 uint32_t tokens, void *workspace, uint64_t workspace_bytes,
                                 void *hip_stream);
 
+/* Diagnostic, host only (no GPU call): how sketch_linear_gemm divides a
+ * prefill of `tokens` tokens through a row-sketch layer with `out_features`
+ * outputs and `n_blocks` input-channel blocks over the workgroups of its main
+ * kernel.  Output tiles are 256 tokens x 256 outputs; every (tile, block)
+ * product belongs to exactly one segment.  Each segment is eight words in
+ * `segments` (HOST, room for `capacity` segments): XCD, workgroup within the
+ * XCD, token tile, output tile, first block, end block, 1 if the segment is a
+ * whole tile (stored directly) else 0, and the float32 partial-tile slot a
+ * partial segment leaves for the fix-up pass (partials of one tile occupy
+ * consecutive slots in workgroup order, which fixes the summation order).
+ * *n_segments receives the number of segments (also when it exceeds
+ * `capacity`; then only the first `capacity` are written).  `shape` (HOST,
+ * 4 words, may be NULL) receives workgroups per XCD, partial tiles per XCD,
+ * slots per partial tile, and the tile count. */
+SKL_API skl_status_t sketch_linear_prefill_split(uint32_t out_features, uint32_t n_blocks, uint32_t tokens,
+                                         uint32_t *segments, uint64_t capacity, uint64_t *n_segments,
+                                         uint32_t *shape);
+
 /* Diagnostic: write W_hat (Eq. 5) as binary16 bit patterns to
  * W_hat_dev (DEVICE, [in_features][out_features], row major).  The only call
  * that materialises the weights. */

@@ -29,8 +29,8 @@ STATUS_NAMES = {0: "SKL_OK", 1: "SKL_ERR_INVALID_ARG", 2: "SKL_ERR_UNSUPPORTED",
 
 EXPORTS = ("sketch_linear_device_bytes", "sketch_linear_create", "sketch_linear_info",
            "sketch_linear_workspace_bytes", "sketch_linear_gemv", "sketch_linear_gemm",
-           "sketch_linear_reconstruct", "sketch_linear_gemv_partials", "sketch_linear_destroy",
-           "sketch_linear_last_error")
+           "sketch_linear_reconstruct", "sketch_linear_gemv_partials", "sketch_linear_prefill_split",
+           "sketch_linear_destroy", "sketch_linear_last_error")
 
 
 class SketchLinearError(RuntimeError):
@@ -80,11 +80,13 @@ def load_library(path: str | None = None):
     L.sketch_linear_gemm.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_reconstruct.argtypes = [vp, vp, vp]
     L.sketch_linear_gemv_partials.argtypes = [vp, vp, ctypes.c_int, u32, u32, vp, u64, vp]
+    L.sketch_linear_prefill_split.argtypes = [u32, u32, u32, ctypes.POINTER(u32), u64, ctypes.POINTER(u64),
+                                              ctypes.POINTER(u32)]
     L.sketch_linear_destroy.argtypes = [vp]
     L.sketch_linear_destroy.restype = None
     L.sketch_linear_last_error.argtypes = []
     L.sketch_linear_last_error.restype = ctypes.c_char_p
-    for n in EXPORTS[:8]:
+    for n in EXPORTS[:9]:
         getattr(L, n).restype = ctypes.c_int
     _lib = L
     return L
@@ -179,6 +181,20 @@ def sketch_linear_gemv_partials(layer: int, x: int, x_dtype: int, ldx: int, batc
                                 workspace_bytes: int, hip_stream: int = 0) -> None:
     _check(load_library().sketch_linear_gemv_partials(layer, x, x_dtype, ldx, batch, workspace, workspace_bytes,
                                                       hip_stream))
+
+
+def sketch_linear_prefill_split(out_features: int, n_blocks: int, tokens: int):
+    """Host only.  Returns (segments, shape): segments is a list of 8-tuples (xcd, workgroup, token tile,
+    output tile, first block, end block, whole, slot), shape is (workgroups per XCD, partial tiles per XCD,
+    slots per partial tile, tiles)."""
+    L = load_library()
+    n = ctypes.c_uint64(0)
+    shape = (ctypes.c_uint32 * 4)()
+    _check(L.sketch_linear_prefill_split(out_features, n_blocks, tokens, None, 0, ctypes.byref(n), shape))
+    buf = (ctypes.c_uint32 * (8 * max(n.value, 1)))()
+    _check(L.sketch_linear_prefill_split(out_features, n_blocks, tokens, buf, n.value, ctypes.byref(n), shape))
+    segs = [tuple(buf[8 * i:8 * i + 8]) for i in range(n.value)]
+    return segs, tuple(shape)
 
 
 def sketch_linear_reconstruct(layer: int, W_hat_dev: int, hip_stream: int = 0) -> None:

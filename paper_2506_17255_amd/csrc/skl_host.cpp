@@ -534,6 +534,17 @@ skl_status_t sketch_linear_gemm(const skl_layer_t *L, const void *X, skl_dtype_t
     return skl_launch_gemm(L, X, x_dt, ldx, Y, y_dt, ldy, tokens, ws, stream);
 }
 
+skl_status_t sketch_linear_prefill_split(uint32_t out_features, uint32_t n_blocks, uint32_t tokens, uint32_t *segments,
+                                         uint64_t capacity, uint64_t *n_segments, uint32_t *shape)
+{
+    if (!n_segments) FAIL(SKL_ERR_INVALID_ARG, "n_segments is NULL");
+    if (!segments && capacity) FAIL(SKL_ERR_INVALID_ARG, "segments is NULL with a non-zero capacity");
+    if (out_features < 1 || n_blocks < 1 || tokens < 1) FAIL(SKL_ERR_INVALID_ARG, "out_features, n_blocks and tokens must be positive");
+    if (tokens > (1u << 24)) FAIL(SKL_ERR_UNSUPPORTED, "more than 2^24 tokens in one call");
+    *n_segments = skl_gemm3_segments(out_features, n_blocks, tokens, segments, capacity, shape);
+    return SKL_OK;
+}
+
 skl_status_t sketch_linear_reconstruct(const skl_layer_t *L, uint16_t *W_hat_dev, void *stream)
 {
     if (!L || !W_hat_dev) FAIL(SKL_ERR_INVALID_ARG, "layer or W_hat_dev is NULL");

@@ -162,3 +162,4 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X, skl_dtype_t x_dt
                              void *stream);
 uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch);
 uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens);
+uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, uint32_t *segs, uint64_t cap, uint32_t *shape);

@@ -1411,6 +1411,28 @@ struct G3Split {
     }
     __host__ __device__ uint32_t parts(uint32_t x, uint32_t l) const { return owner(x, (l + 1) * nb - 1) - owner(x, l * nb) + 1; }
     __host__ __device__ size_t slot(uint32_t x, uint32_t l, uint32_t part) const { return ((size_t)x * l_max + l) * p_cap + part; }
+    // next segment of workgroup wg of XCD x: blocks [k0, k1) of the XCD's k-th tile.  round and u_next
+    // carry the position (start: 0 and share_begin(x, wg)); false when the workgroup is done.
+    struct Seg { uint32_t k, k0, k1, whole; size_t part_slot; };
+    __host__ __device__ bool next(uint32_t x, uint32_t wg, uint32_t &round, uint32_t &u_next, Seg &sg) const
+    {
+        const uint32_t n_rounds = rounds(x), u_end = share_begin(x, wg + 1);
+        sg.part_slot = 0;
+        if (round < n_rounds) {
+            sg.k = wg + round * gx; sg.k0 = 0; sg.k1 = nb; sg.whole = 1;
+            ++round;
+            return true;
+        }
+        if (u_next >= u_end) return false;
+        const uint32_t l = u_next / nb;
+        sg.k0 = u_next - l * nb;
+        sg.k1 = sg.k0 + (u_end - u_next) < nb ? sg.k0 + (u_end - u_next) : nb;
+        sg.k = n_rounds * gx + l;
+        sg.whole = sg.k0 == 0 && sg.k1 == nb;
+        sg.part_slot = slot(x, l, wg - owner(x, l * nb));
+        u_next += sg.k1 - sg.k0;
+        return true;
+    }
 };
 #define G3_SLOT_FLOATS 65536u           // one 256 x 256 partial
 
@@ -1507,10 +1529,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const uint32_t xcd = blockIdx.x & 7, wg = blockIdx.x >> 3;
     G3Split sp;
     sp.T = p.T; sp.m_tiles = p.m_tiles; sp.nb = p.n_blocks; sp.gx = p.gx; sp.l_max = p.l_max; sp.p_cap = p.p_cap;
-    const uint32_t n_rounds = sp.rounds(xcd);
-    const uint32_t u_end = sp.share_begin(xcd, wg + 1);
-    uint32_t u_next = sp.share_begin(xcd, wg);
-    if (n_rounds == 0 && u_next >= u_end) return;
+    uint32_t round = 0, u_next = sp.share_begin(xcd, wg);
+    if (sp.rounds(xcd) == 0 && u_next >= sp.share_begin(xcd, wg + 1)) return;
     const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void *)smem;
     const uint32_t tab_bytes = p.tab_words * 16;
@@ -1705,25 +1725,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
     };
     // ---- the segments of this workgroup: whole tiles first, then its share of the leftover blocks
-    uint32_t round = 0;
     for (;;) {
-        uint32_t k, k0, k1;
-        size_t part_slot = 0;
-        bool whole;
-        if (round < n_rounds) {
-            k = wg + round * sp.gx; k0 = 0; k1 = p.n_blocks; whole = true;
-            ++round;
-        } else if (u_next < u_end) {
-            const uint32_t l = u_next / p.n_blocks;
-            k0 = u_next - l * p.n_blocks;
-            k1 = min(p.n_blocks, k0 + (u_end - u_next));
-            k = n_rounds * sp.gx + l;
-            whole = k0 == 0 && k1 == p.n_blocks;
-            part_slot = sp.slot(xcd, l, wg - sp.owner(xcd, l * p.n_blocks));
-            u_next += k1 - k0;
-        } else {
-            break;
-        }
+        G3Split::Seg sg;
+        if (!sp.next(xcd, wg, round, u_next, sg)) break;
+        const uint32_t k = sg.k, k0 = sg.k0, k1 = sg.k1;
+        const bool whole = sg.whole != 0;
+        const size_t part_slot = sg.part_slot;
         const uint32_t t = xcd + 8 * k, tile_m = t % p.m_tiles, tile_n = t / p.m_tiles;
         t0 = tile_m * GM_MT + wave * 64;
         o_first = tile_n * GM3_NT + wave * 64;
@@ -2148,6 +2155,32 @@ static G3Split gemm3_split(const skl_layer *L, uint32_t tokens)
         for (uint32_t l = 0; l < sp.left(x); ++l) sp.p_cap = std::max(sp.p_cap, sp.parts(x, l));
     }
     return sp;
+}
+
+// every segment of the split, eight words each: xcd, workgroup, token tile, output tile, first block,
+// end block, whole-tile flag, partial slot; returns the number of segments (writes at most cap of them)
+uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, uint32_t *segs, uint64_t cap, uint32_t *shape)
+{
+    skl_layer L;
+    L.out = out; L.n_blocks = n_blocks;
+    const G3Split sp = gemm3_split(&L, tokens);
+    if (shape) { shape[0] = sp.gx; shape[1] = sp.l_max; shape[2] = sp.p_cap; shape[3] = sp.T; }
+    uint64_t n = 0;
+    for (uint32_t x = 0; x < 8; ++x)
+        for (uint32_t wg = 0; wg < sp.gx; ++wg) {
+            uint32_t round = 0, u_next = sp.share_begin(x, wg);
+            G3Split::Seg sg;
+            while (sp.next(x, wg, round, u_next, sg)) {
+                if (n < cap) {
+                    const uint32_t t = x + 8 * sg.k;
+                    uint32_t *o = segs + 8 * n;
+                    o[0] = x; o[1] = wg; o[2] = t % sp.m_tiles; o[3] = t / sp.m_tiles; o[4] = sg.k0; o[5] = sg.k1;
+                    o[6] = sg.whole; o[7] = (uint32_t)sg.part_slot;
+                }
+                ++n;
+            }
+        }
+    return n;
 }
 
 static uint64_t gemm_pack_bytes(const skl_layer *L, uint32_t tokens)

@@ -1,0 +1,121 @@
+"""Host-side checks of the prefill work split (no GPU call is made).
+
+The main prefill kernel multiplies 256 x 256 output tiles, one input-channel
+block at a time.  The split hands every workgroup whole tiles plus an equal
+share of the blocks of the tiles left over; shares that cover part of a tile
+leave float32 partials in numbered slots.  These tests enumerate the split
+through the C ABI and check the properties the kernels rely on.
+"""
+import itertools
+
+import pytest
+
+import paper_2506_17255_amd as skl
+
+
+def split(out_features, n_blocks, tokens):
+    segs, shape = skl.sketch_linear_prefill_split(out_features, n_blocks, tokens)
+    return segs, shape
+
+
+SHAPES = [
+    (11008, 64, 2048),    # the benchmark layer: 344 tiles on 256 workgroups
+    (4096, 64, 2048),     # fewer tiles than workgroups: every tile is shared
+    (4096, 172, 2048),    # the down projection's block count
+    (28672, 128, 2048),   # 896 tiles: three whole rounds and a leftover
+    (256, 1, 1),          # a single tile of a single block
+    (300, 3, 257),        # ragged in both directions, tiny
+    (11008, 64, 1),       # decode-sized call through the prefill path
+    (5000, 7, 1000),
+    (65536, 5, 4096),
+    (256 * 33, 64, 2048), # one tile more than a whole round on one XCD
+]
+
+
+@pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES)
+def test_every_block_of_every_tile_is_multiplied_once(out_features, n_blocks, tokens):
+    segs, (gx, l_max, p_cap, n_tiles) = split(out_features, n_blocks, tokens)
+    m_tiles = (tokens + 255) // 256
+    n_col = (out_features + 255) // 256
+    assert n_tiles == m_tiles * n_col
+    seen = {}
+    for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
+        assert xcd < 8 and wg < gx
+        assert tm < m_tiles and tn < n_col
+        assert 0 <= k0 < k1 <= n_blocks
+        assert whole == int(k0 == 0 and k1 == n_blocks)
+        assert (tn * m_tiles + tm) % 8 == xcd          # a tile stays on one XCD
+        for b in range(k0, k1):
+            assert (tm, tn, b) not in seen
+            seen[(tm, tn, b)] = (xcd, wg)
+    assert len(seen) == n_tiles * n_blocks
+
+
+@pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES)
+def test_partial_slots_are_distinct_dense_and_in_workgroup_order(out_features, n_blocks, tokens):
+    segs, (gx, l_max, p_cap, n_tiles) = split(out_features, n_blocks, tokens)
+    by_tile = {}
+    slots = set()
+    for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
+        if whole:
+            continue
+        assert slot < 8 * l_max * p_cap                 # inside the workspace the library asks for
+        assert slot not in slots
+        slots.add(slot)
+        by_tile.setdefault((tm, tn), []).append((slot, wg, k0, k1))
+    for parts in by_tile.values():
+        parts.sort()
+        base = parts[0][0]
+        assert base % p_cap == 0                        # a tile's slots start at its own row of the slot table
+        assert [s for s, *_ in parts] == list(range(base, base + len(parts)))
+        assert len(parts) <= p_cap
+        wgs = [w for _, w, *_ in parts]
+        assert wgs == sorted(wgs) and len(set(wgs)) == len(wgs)
+        # consecutive block ranges covering the whole tile
+        assert parts[0][2] == 0 and parts[-1][3] == n_blocks
+        for (_, _, _, e), (_, _, b, _) in zip(parts, parts[1:]):
+            assert e == b
+
+
+@pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES)
+def test_workgroups_get_equal_work(out_features, n_blocks, tokens):
+    segs, (gx, l_max, p_cap, n_tiles) = split(out_features, n_blocks, tokens)
+    load = {}
+    for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
+        load[(xcd, wg)] = load.get((xcd, wg), 0) + k1 - k0
+    for xcd in range(8):
+        mine = [v for (x, _), v in load.items() if x == xcd]
+        if mine:
+            # within an XCD: whole rounds are equal, leftover shares differ by at most one block;
+            # workgroups without a share (fewer leftover blocks than workgroups) do one block less at most
+            assert max(mine) - min(mine) <= 1 or len(mine) < gx
+    total = sum(load.values())
+    assert total == n_tiles * n_blocks
+    # the busiest workgroup is close to the ideal share when there is enough work to go round
+    if total >= 8 * gx * 8:
+        assert max(load.values()) <= total / (8 * gx) + n_blocks / 8 + 1
+
+
+def test_small_exhaustive_sweep():
+    for n_tiles_out, n_blocks, tokens in itertools.product(range(1, 41), (1, 2, 5, 31, 64), (1, 256, 257, 2048)):
+        out_features = 256 * n_tiles_out - 3
+        segs, (gx, l_max, p_cap, n_tiles) = split(out_features, n_blocks, tokens)
+        covered = sum(k1 - k0 for *_, k0, k1, _, _ in segs)
+        assert covered == n_tiles * n_blocks
+        keys = set()
+        for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
+            for b in range(k0, k1):
+                keys.add((tm, tn, b))
+        assert len(keys) == covered
+
+
+def test_argument_errors():
+    L = skl.load_library()
+    import ctypes
+    n = ctypes.c_uint64(0)
+    assert L.sketch_linear_prefill_split(4096, 64, 2048, None, 0, None, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_prefill_split(4096, 64, 2048, None, 5, ctypes.byref(n), None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_prefill_split(0, 64, 2048, None, 0, ctypes.byref(n), None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_prefill_split(4096, 64, 0, None, 0, ctypes.byref(n), None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_prefill_split(4096, 64, 2048, None, 0, ctypes.byref(n), None) == skl.SKL_OK
+    assert n.value >= 8

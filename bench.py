@@ -187,7 +187,8 @@ def main():
                 "roofline": {"bound": "mfma", "achieved": flops / s_gemm / 1e12, "peak": MFMA_F16_PEAK / 1e12,
                              "unit": "TFLOP/s", "frac": flops / s_gemm / MFMA_F16_PEAK,
                              "traffic": measured_traffic("gemm_row_4096x11008_t2048_pmc.txt") if out_f == 11008 else None,
-                             "note": "whole entry point: activation pre-pass + fused reconstruct/MFMA kernel"}}
+                             "note": "time of the whole entry point (activation re-ordering, fused query/MFMA kernel, "
+                                     "fix-up of shared tiles); traffic is the fused kernel's"}}
 
     def calib_copy():
         a = torch.empty(CALIB_COPY_BYTES, dtype=torch.uint8, device=dev)

@@ -163,6 +163,40 @@ def test_gemm_matches_oracle(name, tokens):
     assert rel_fro(yh, oracle.linear(W_hat, Xh)) <= 1e-5
 
 
+@pytest.mark.parametrize("name", ["row_ragged", "row_classes", "row_d5", "row_big_table", "row_single"])
+def test_gemm_strides_and_several_token_tiles(name):
+    """Three token tiles with a ragged last one (the work split then shares tiles between workgroups),
+    rows of X that are not 16-byte aligned, rows of Y that are and that are not."""
+    W, sk = small_case(name)
+    W_hat = expected_W_hat(name)
+    tokens = 600
+    rng = np.random.default_rng(77)
+    Xf = rng.standard_normal((tokens, sk.in_features)).astype(np.float32)
+    Xb = wk.f32_to_bf16_bits(Xf)
+    ref = oracle.linear(W_hat, Xb, x_kind="bf16")
+    pad = (-sk.out_features) % 8
+    with GpuLayer(sk, flags_of(name)) as g:
+        y_odd = g.gemm(Xb, "bf16", "bf16", ldx=sk.in_features + 3, ldy=sk.out_features + pad + 5)
+        y_al = g.gemm(Xb, "bf16", "bf16", ldx=sk.in_features + 8, ldy=sk.out_features + pad + 16)
+        y16 = g.gemm(Xb, "bf16", "f16", ldy=sk.out_features + pad + 8)
+        y32 = g.gemm(Xb, "bf16", "f32", ldx=sk.in_features + 1, ldy=sk.out_features + pad + 4)
+        y32_odd = g.gemm(Xb, "bf16", "f32", ldy=sk.out_features + pad + 3)
+    assert rel_fro(y32, ref) <= 1e-5
+    assert np.array_equal(y32, y32_odd)                 # the two store paths round the same sums
+    assert np.array_equal(y_odd, y_al)
+    assert rel_fro(y_al, round_to_bf16(ref)) <= TOL
+    assert rel_fro(y16, ref) <= TOL
+
+
+def test_gemm_is_bit_identical_from_run_to_run():
+    W, sk = small_case("row_classes")
+    rng = np.random.default_rng(78)
+    Xb = wk.f32_to_bf16_bits(rng.standard_normal((700, sk.in_features)).astype(np.float32))
+    with GpuLayer(sk) as g:
+        runs = [g.gemm(Xb, "bf16", "f32") for _ in range(3)]
+    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
+
+
 @pytest.mark.parametrize("name", ["row_ragged", "row_classes", "tile_ragged", "cfg1"])
 def test_gemm_identity_probe_is_exact(name):
     """X = I  =>  Y = W_hat exactly (float32 output)."""

@@ -113,6 +113,34 @@ def stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream, n_bloc
         per_layer += np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(n)]) * 1e3
         total += ev[0].elapsed_time(ev[n]) * 1e3
     per_layer /= passes
+    # the same pass without events between the launches, then captured once in a HIP graph and replayed
+    # (the path records only kernel nodes; every replay is checked against the eager outputs)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(passes):
+        for a in calls:
+            skl.sketch_linear_gemv(*a)
+    e1.record()
+    torch.cuda.synchronize()
+    plain_us = e0.elapsed_time(e1) * 1e3 / passes
+    eager_out = {f: y.clone() for f, y in yout.items()}
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cap = torch.cuda.current_stream().cuda_stream
+        for a in calls:
+            skl.sketch_linear_gemv(*(a[:-1] + (cap,)))
+    graph_us, graph_ok = 0.0, True
+    for _ in range(passes):
+        for y in yout.values():
+            y.zero_()
+        torch.cuda.synchronize()
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        graph_us += e0.elapsed_time(e1) * 1e3 / passes
+        graph_ok = graph_ok and all(torch.equal(yout[f], eager_out[f]) for f in yout)
+    del graph
     names = [wl.name.split("_")[-1] for wl in shapes]
     by_name = {nm: float(per_layer[i::len(shapes)].mean()) for i, nm in enumerate(names)}
     weights = sum(wl.n_weights for wl in shapes) * n_blocks
@@ -121,6 +149,8 @@ def stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream, n_bloc
             g.close()
     return {"layers": n, "us_per_pass": total / passes, "us_per_layer_mean": float(per_layer.mean()),
             "us_per_layer_by_kind": by_name, "weights_per_s": weights / (total / passes * 1e-6),
+            "us_per_pass_without_events": plain_us, "us_per_pass_hip_graph": graph_us,
+            "hip_graph_replays_match_eager": bool(graph_ok),
             "note": "224 distinct device copies (7 sketches x 32 blocks), tables not cache-resident; "
                     "event recording between launches adds to each figure"}
 
@@ -144,6 +174,7 @@ def main():
     ap.add_argument("--quick", action="store_true", help="decode GEMV at batch 1 only (for profiling runs)")
     ap.add_argument("--prefill-only", action="store_true", help="prefill GEMM 4096x11008 only (for profiling runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--stack-only", action="store_true", help="the 224-layer decode stack only")
     ap.add_argument("--calib-copy", action="store_true",
                     help=f"also run one device copy of {CALIB_COPY_BYTES >> 20} MiB (scale for HBM byte counters)")
     args = ap.parse_args()
@@ -196,6 +227,9 @@ def main():
         b.copy_(a)
         torch.cuda.synchronize()
 
+    if args.stack_only:
+        print(json.dumps({"stack": stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream)}))
+        return
     if args.prefill_only:
         print(json.dumps({"prefill_2048_tokens": {"4096x11008": prefill(11008, max(args.steps // 10, 5), 3)}}))
         if args.calib_copy:

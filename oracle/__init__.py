@@ -51,6 +51,12 @@ def _bind(L):
     L.ora_update.argtypes = geom + [_u16p, _u16p, ctypes.c_uint64]
     L.ora_query.restype = ctypes.c_int
     L.ora_query.argtypes = geom + [_u16p, ctypes.c_uint64, _u16p]
+    _i8p = ctypes.POINTER(ctypes.c_int8)
+    qgeom = [ctypes.c_uint32] * 5 + [_u32p]
+    L.ora_quantize_states.restype = ctypes.c_int
+    L.ora_quantize_states.argtypes = qgeom + [_u16p, ctypes.c_uint64, ctypes.c_int, _i8p, _u16p]
+    L.ora_dequantize_states.restype = ctypes.c_int
+    L.ora_dequantize_states.argtypes = qgeom + [ctypes.c_int, _i8p, _u16p, _u16p, ctypes.c_uint64]
     L.ora_linear.restype = ctypes.c_int
     L.ora_linear.argtypes = [ctypes.c_uint32, ctypes.c_uint32, _u16p, _u16p, ctypes.c_int,
                              ctypes.c_uint32, ctypes.c_uint64, _u32p, ctypes.c_uint32, _f64p]
@@ -105,6 +111,20 @@ class Sketch:
         return 16.0 * self.states.size / (self.in_features * self.out_features)
 
 
+@dataclass
+class QuantSketch(Sketch):
+    """A sketch whose states are kept as low-bit codes (Sec. 3.3, last paragraph): ``codes`` holds one
+    signed integer per state (int8, also for 4 bit), ``scales`` one binary16 pattern per (group, sketch
+    row); ``states`` are the binary16 states the codes stand for, so query and linear apply unchanged."""
+    bits: int = 8
+    codes: np.ndarray = None
+    scales: np.ndarray = None
+
+    @property
+    def bits_per_weight(self):
+        return (self.bits * self.codes.size + 16.0 * self.scales.size) / (self.in_features * self.out_features)
+
+
 def half_to_double(bits) -> np.ndarray:
     L = _load()
     b = np.asarray(bits, dtype=np.uint16).ravel()
@@ -153,6 +173,36 @@ def query(sk: Sketch) -> np.ndarray:
                            _p(W_hat, _u16p))
     _check(rc, "query")
     return W_hat
+
+
+def dequantize_states(in_f, out_f, tile_in, tile_out, d, group_width, bits, codes, scales) -> np.ndarray:
+    """The binary16 states that low-bit codes stand for: q * scale / qmax, rounded once (nearest even)."""
+    wd = _u32(group_width).ravel()
+    cd = np.ascontiguousarray(np.asarray(codes, dtype=np.int8))
+    sc = _u16(scales).ravel()
+    n = count_states(in_f, out_f, tile_in, tile_out, d, wd)
+    assert cd.size == n and sc.size == wd.size * d
+    states = np.empty(n, dtype=np.uint16)
+    rc = _load().ora_dequantize_states(in_f, out_f, tile_in, tile_out, d, _p(wd, _u32p), bits,
+                                       _p(cd, ctypes.POINTER(ctypes.c_int8)), _p(sc, _u16p), _p(states, _u16p), n)
+    _check(rc, "dequantize_states")
+    return states
+
+
+def quantize(sk: Sketch, bits: int) -> QuantSketch:
+    """Low-bit copy of a sketch: per (group, sketch row) scale = largest state magnitude, codes =
+    round-half-even(state * qmax / scale), qmax = 127 (8 bit) or 7 (4 bit)."""
+    st = _u16(sk.states)
+    wd = _u32(sk.group_width).ravel()
+    codes = np.empty(st.size, dtype=np.int8)
+    scales = np.empty(wd.size * sk.d, dtype=np.uint16)
+    rc = _load().ora_quantize_states(sk.in_features, sk.out_features, sk.tile_in, sk.tile_out, sk.d,
+                                     _p(wd, _u32p), _p(st, _u16p), st.size, bits,
+                                     _p(codes, ctypes.POINTER(ctypes.c_int8)), _p(scales, _u16p))
+    _check(rc, "quantize_states")
+    deq = dequantize_states(sk.in_features, sk.out_features, sk.tile_in, sk.tile_out, sk.d, wd, bits, codes, scales)
+    return QuantSketch(sk.in_features, sk.out_features, sk.tile_in, sk.tile_out, sk.d, sk.hash_a, sk.hash_c,
+                       wd, deq, bits, codes, scales)
 
 
 def linear(W_hat, x, x_kind: str = "f16", cols=None) -> np.ndarray:

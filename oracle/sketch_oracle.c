@@ -31,6 +31,14 @@
  *   - Update ties (|S| == |w|) keep the older value (Eq. (4) is strict).
  *   - States that no weight ever reached are written as +0.0 at the end of
  *     the update stream (no query can reach them).
+ *   - Low-bit states (Sec. 3.3, last paragraph, and Sec. 4: sketch states
+ *     kept in 4-bit / 8-bit types).  The paper names a third-party scalar
+ *     quantiser and gives no format.  Here: one binary16 scale per sketch
+ *     row of a group, equal to the largest state magnitude of that row;
+ *     codes are signed integers q in [-qmax, qmax], qmax = 127 (8 bit) or
+ *     7 (4 bit); q = round-half-even(state * qmax / scale); the state a
+ *     code stands for is q * scale / qmax rounded once to binary16
+ *     (nearest even).  Query and linear layer then run on those states.
  *
  * Precision: weights/states are IEEE binary16 bit patterns and are never
  * rounded here; the linear layer accumulates in binary64 in ascending j.
@@ -39,6 +47,8 @@
  * sort-based brute force of Eq. (4), one-hot matrix forms Eq. (8)/(9),
  * under-estimate / membership / row-order / more-rows invariants, the
  * bucket-minimum survival law behind Eq. (6), numpy fp64 matmul.
+ * Low-bit states: exact rational arithmetic (Python fractions), error
+ * bound of half a step, end points, symmetry, hand-worked codes.
  * Absolute accuracy or latency figures: parity unpinned (the paper prints
  * no value for this path).
  */
@@ -200,6 +210,91 @@ int ora_query(uint32_t in, uint32_t out, uint32_t tj, uint32_t to, uint32_t d,
                 }
             base += (uint64_t)d * K;
         }
+    return ORA_OK;
+}
+
+/* ---- low-bit states (Sec. 3.3 last paragraph; Sec. 4 ablation "sketch
+ * states in low-bit types") ---------------------------------------------- */
+
+/* double -> binary16 bit pattern, round to nearest even; |v| must be finite
+ * and below the binary16 overflow threshold (callers pass |v| <= 65504). */
+static uint16_t double_to_half_rne(double v)
+{
+    uint16_t sign = signbit(v) ? 0x8000 : 0;
+    double a = fabs(v);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                 /* a = f * 2^e, 0.5 <= f < 1 */
+    int ex = e - 1;                     /* a = 1.xxx * 2^ex */
+    if (ex < -14) ex = -14;             /* subnormal range: fixed step 2^-24 */
+    double step = ldexp(1.0, ex - 10);  /* spacing of binary16 around a */
+    double q = nearbyint(a / step);     /* default rounding mode: half to even; a/step is exact */
+    double r = q * step;                /* may carry into the next binade: still representable */
+    int e2;
+    double f2 = frexp(r, &e2);
+    if (r < ldexp(1.0, -14)) return (uint16_t)(sign | (uint16_t)(r / ldexp(1.0, -24)));
+    uint32_t mant = (uint32_t)(f2 * 2048.0) - 1024;   /* f2 in [0.5,1): f2*2048 in [1024,2048) */
+    return (uint16_t)(sign | ((uint32_t)(e2 - 1 + 15) << 10) | mant);
+}
+
+static int qmax_of(int bits) { return bits == 8 ? 127 : bits == 4 ? 7 : 0; }
+
+/* codes: one int8 per state (also for 4 bit: the packing into nibbles is a
+ * storage matter of the caller); scales: binary16, [n_groups][d]. */
+int ora_quantize_states(uint32_t in, uint32_t out, uint32_t tj, uint32_t to, uint32_t d,
+                        const uint32_t *width, const uint16_t *states, uint64_t n_states,
+                        int bits, int8_t *codes, uint16_t *scales)
+{
+    int qmax = qmax_of(bits);
+    if (!qmax || !width || !states || !codes || !scales || !tj || !to || in % tj || out % to) return ORA_BAD_ARG;
+    if (n_states != ora_count_states(in, out, tj, to, d, width)) return ORA_BAD_ARG;
+    for (uint64_t i = 0; i < n_states; ++i)
+        if (!half_is_finite(states[i])) return ORA_NONFINITE;
+    uint64_t n_groups = (uint64_t)(in / tj) * (out / to), base = 0;
+    for (uint64_t g = 0; g < n_groups; ++g) {
+        uint32_t K = width[g];
+        for (uint32_t r = 0; r < d; ++r) {
+            const uint16_t *S = states + base + (uint64_t)r * K;
+            uint16_t top = 0;                               /* largest magnitude: integer order of the low 15 bits */
+            for (uint32_t k = 0; k < K; ++k)
+                if ((S[k] & 0x7FFF) > top) top = S[k] & 0x7FFF;
+            scales[g * d + r] = top;
+            double sc = ora_half_to_double(top);
+            for (uint32_t k = 0; k < K; ++k) {
+                double q = sc > 0.0 ? nearbyint(ora_half_to_double(S[k]) * (double)qmax / sc) : 0.0;
+                if (q > qmax) q = qmax;
+                if (q < -qmax) q = -qmax;
+                codes[base + (uint64_t)r * K + k] = (int8_t)q;
+            }
+        }
+        base += (uint64_t)d * K;
+    }
+    return ORA_OK;
+}
+
+int ora_dequantize_states(uint32_t in, uint32_t out, uint32_t tj, uint32_t to, uint32_t d,
+                          const uint32_t *width, int bits, const int8_t *codes,
+                          const uint16_t *scales, uint16_t *states, uint64_t n_states)
+{
+    int qmax = qmax_of(bits);
+    if (!qmax || !width || !states || !codes || !scales || !tj || !to || in % tj || out % to) return ORA_BAD_ARG;
+    if (n_states != ora_count_states(in, out, tj, to, d, width)) return ORA_BAD_ARG;
+    uint64_t n_groups = (uint64_t)(in / tj) * (out / to), base = 0;
+    for (uint64_t g = 0; g < n_groups; ++g) {
+        uint32_t K = width[g];
+        for (uint32_t r = 0; r < d; ++r) {
+            if (!half_is_finite(scales[g * d + r]) || (scales[g * d + r] >> 15)) return ORA_BAD_ARG;
+            double sc = ora_half_to_double(scales[g * d + r]);
+            for (uint32_t k = 0; k < K; ++k) {
+                int q = codes[base + (uint64_t)r * K + k];
+                if (q > qmax || q < -qmax) return ORA_BAD_ARG;
+                /* q * sc is exact in binary64; the quotient is within 2^-53 of the true value, far
+                 * closer than any binary16 rounding boundary that the true value does not hit exactly */
+                states[base + (uint64_t)r * K + k] = double_to_half_rne((double)q * sc / (double)qmax);
+            }
+        }
+        base += (uint64_t)d * K;
+    }
     return ORA_OK;
 }
 

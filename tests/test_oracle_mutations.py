@@ -9,6 +9,7 @@ import subprocess
 import pytest
 
 import oracle
+import test_oracle_lowbit as lowbit
 import test_oracle_pins as pins
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "sketch_oracle.c")
@@ -41,7 +42,7 @@ MUTANTS = {
     "rows share the first row's table":
         ("best = absmax_pick(best, S[(uint64_t)r * K + ora_select", "best = absmax_pick(best, S[ora_select"),
     "group base advances by one row only":
-        ("base += (uint64_t)d * K;\n        }\n    return ORA_OK;\n}\n\n/* ---- linear", "base += K;\n        }\n    return ORA_OK;\n}\n\n/* ---- linear"),
+        ("base += (uint64_t)d * K;\n        }\n    return ORA_OK;\n}\n\n/* ---- low-bit", "base += K;\n        }\n    return ORA_OK;\n}\n\n/* ---- low-bit"),
     "groups are numbered column-major":
         ("uint32_t K = width[(uint64_t)jb * g.n_ob + ob];\n            const uint16_t *S", "uint32_t K = width[(uint64_t)ob * g.n_jb + jb];\n            const uint16_t *S"),
     "linear reads W transposed":
@@ -56,6 +57,18 @@ MUTANTS = {
         ("ldexp((double)(m + 1024), e - 25)", "ldexp((double)(m), e - 25)"),
     "never-reached states are left at +inf":
         ("if (states[i] == 0x7C00) states[i] = 0x0000;", ""),
+    "low-bit codes round half away from zero":
+        ("nearbyint(ora_half_to_double(S[k]) * (double)qmax / sc)", "round(ora_half_to_double(S[k]) * (double)qmax / sc)"),
+    "low-bit step divides by qmax + 1":
+        ("(double)q * sc / (double)qmax", "(double)q * sc / (double)(qmax + 1)"),
+    "low-bit scale is the first state of the row":
+        ("if ((S[k] & 0x7FFF) > top) top = S[k] & 0x7FFF;", "if (k == 0) top = S[k] & 0x7FFF;"),
+    "low-bit state is truncated to binary16":
+        ("double q = nearbyint(a / step);", "double q = floor(a / step);"),
+    "low-bit scale of the first row serves the whole group":
+        ("double sc = ora_half_to_double(scales[g * d + r]);", "double sc = ora_half_to_double(scales[g * d]);"),
+    "low-bit four-bit codes use the eight-bit range":
+        ("return bits == 8 ? 127 : bits == 4 ? 7 : 0;", "return bits == 8 ? 127 : bits == 4 ? 127 : 0;"),
 }
 
 PIN_FUNCS = [
@@ -99,6 +112,19 @@ def _run_pins():
         pins.test_identity_hash_reproduces_W(2)
     except (AssertionError, ValueError, IndexError):
         failed.append("test_identity_hash_reproduces_W")
+    for fn in (lowbit.test_hand_worked_codes_four_bit, lowbit.test_hand_worked_codes_eight_bit,
+               lowbit.test_hand_worked_non_integer_step):
+        try:
+            fn()
+        except (AssertionError, ValueError, IndexError):
+            failed.append(fn.__name__)
+    for bits in (8, 4):
+        for fn in (lowbit.test_end_points_symmetry_and_order,
+                   lowbit.test_scale_is_the_row_maximum_and_error_is_at_most_half_a_step):
+            try:
+                fn(bits)
+            except (AssertionError, ValueError, IndexError):
+                failed.append(fn.__name__)
     return failed
 
 

@@ -25,6 +25,16 @@
  *             with the clear sign bit.
  *   states    IEEE binary16 bit patterns, group-major, then sketch row r,
  *             then index k:  states[base_g + r * K_g + k].
+ *   low-bit   states may instead be given as 8- or 4-bit codes (the paper
+ *   states    combines the sketch with 4-/8-bit scalar quantisation, Sec. 3.3
+ *             last paragraph and Sec. 4, without fixing a format; this is the
+ *             format fixed here): one binary16 scale per sketch row of a
+ *             group, scales[g * d + r] >= 0, and signed codes q in
+ *             [-qmax, qmax], qmax = 127 (8 bit) or 7 (4 bit), in the order of
+ *             `states`.  The state a code stands for is q * scale / qmax
+ *             rounded once to binary16 (nearest even).  Such a layer keeps
+ *             only codes and scales resident in dev_buf; every call expands
+ *             them into the kernels' 16-bit tables inside its workspace.
  *
  * General rules
  *   - Every function returns a status code and never throws, aborts or
@@ -79,9 +89,19 @@ typedef struct {
     const uint32_t *hash_a;    /* [d], each < 2^24 */
     const uint32_t *hash_c;    /* [d], each < 2^24 */
     const uint32_t *group_width; /* [(in/tile_in) * (out/tile_out)], each 1..65535 */
-    const uint16_t *states;    /* [n_states] binary16 bit patterns, layout above */
+    const uint16_t *states;    /* [n_states] binary16 bit patterns, layout above
+                                  (NULL when state_bits is 8 or 4) */
     uint64_t n_states;         /* must equal d * sum(group_width) */
+    /* -- end of the first version of this struct (72 bytes, still accepted: binary16 states) -- */
+    uint32_t state_bits;       /* 0 or 16: binary16 `states`;  8 or 4: `codes` and `scales` */
+    uint32_t reserved;         /* must be 0 */
+    const void *codes;         /* state_bits 8: int8 [n_states];  4: two's-complement nibbles, state i in
+                                  byte i / 2, low nibble for even i, [(n_states + 1) / 2] bytes; the codes
+                                  -128 and -8 are invalid */
+    const uint16_t *scales;    /* binary16, finite, sign bit clear, [n_groups * d] */
 } skl_desc_t;
+
+#define SKL_DESC_SIZE_V1 72u
 
 typedef struct skl_layer skl_layer_t;   /* opaque host object */
 
@@ -94,7 +114,7 @@ typedef struct {
     uint32_t n_units;          /* channel blocks (path 1) or group chunks (path 0): the
                                   number of partial sums per output in the split reduction */
     uint32_t max_table_bytes;  /* largest LDS-resident table of one workgroup */
-    uint64_t table_bytes;      /* bytes of sketch tables resident in dev_buf */
+    uint64_t table_bytes;      /* bytes of sketch tables (or of codes and scales) resident in dev_buf */
     uint64_t n_weights;        /* in_features * out_features */
     uint64_t n_states;
 } skl_info_t;
@@ -113,10 +133,11 @@ SKL_API skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf,
 
 SKL_API skl_status_t sketch_linear_info(const skl_layer_t *layer, skl_info_t *info);
 
-/* Bytes of DEVICE workspace needed by gemv (op = 0, n = batch) or gemm
- * (op = 1, n = tokens).  The workspace holds the partial sums of the split
- * reduction (gemv) or the re-ordered fp16 activations (gemm); its contents
- * are scratch. */
+/* Bytes of DEVICE workspace needed by gemv (op = 0, n = batch), gemm
+ * (op = 1, n = tokens) or reconstruct (op = 2, n ignored).  The workspace
+ * holds the partial sums of the split reduction (gemv), the re-ordered fp16
+ * activations and partial tiles (gemm) and, for layers with low-bit states,
+ * the 16-bit tables expanded for the call; its contents are scratch. */
 SKL_API skl_status_t sketch_linear_workspace_bytes(const skl_layer_t *layer, uint32_t op, uint32_t n,
                                            uint64_t *bytes);
 
@@ -172,9 +193,10 @@ SKL_API skl_status_t sketch_linear_prefill_split(uint32_t out_features, uint32_t
 
 /* Diagnostic: write W_hat (Eq. 5) as binary16 bit patterns to
  * W_hat_dev (DEVICE, [in_features][out_features], row major).  The only call
- * that materialises the weights. */
-SKL_API skl_status_t sketch_linear_reconstruct(const skl_layer_t *layer, uint16_t *W_hat_dev,
-                                       void *hip_stream);
+ * that materialises the weights.  The workspace (op = 2) is needed only by
+ * layers with low-bit states and may be NULL otherwise. */
+SKL_API skl_status_t sketch_linear_reconstruct(const skl_layer_t *layer, uint16_t *W_hat_dev, void *workspace,
+                                       uint64_t workspace_bytes, void *hip_stream);
 
 /* Frees the host object only; dev_buf stays the caller's. NULL is accepted. */
 SKL_API void sketch_linear_destroy(skl_layer_t *layer);

@@ -47,7 +47,13 @@ class skl_desc_t(ctypes.Structure):
                 ("query_mode", ctypes.c_uint32), ("flags", ctypes.c_uint32),
                 ("hash_a", ctypes.c_void_p), ("hash_c", ctypes.c_void_p),
                 ("group_width", ctypes.c_void_p), ("states", ctypes.c_void_p),
-                ("n_states", ctypes.c_uint64)]
+                ("n_states", ctypes.c_uint64),
+                # end of the first version of the struct (SKL_DESC_SIZE_V1 bytes)
+                ("state_bits", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+                ("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p)]
+
+
+SKL_DESC_SIZE_V1 = 72
 
 
 class skl_info_t(ctypes.Structure):
@@ -78,7 +84,7 @@ def load_library(path: str | None = None):
     L.sketch_linear_workspace_bytes.argtypes = [vp, u32, u32, ctypes.POINTER(u64)]
     L.sketch_linear_gemv.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_gemm.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
-    L.sketch_linear_reconstruct.argtypes = [vp, vp, vp]
+    L.sketch_linear_reconstruct.argtypes = [vp, vp, vp, u64, vp]
     L.sketch_linear_gemv_partials.argtypes = [vp, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_prefill_split.argtypes = [u32, u32, u32, ctypes.POINTER(u32), u64, ctypes.POINTER(u64),
                                               ctypes.POINTER(u32)]
@@ -102,11 +108,13 @@ def _check(status: int):
 
 
 def make_desc(in_features, out_features, tile_in, tile_out, d, hash_a, hash_c, group_width, states,
-              n_states=None, query_mode=0, flags=0, struct_size=None):
+              n_states=None, query_mode=0, flags=0, struct_size=None, state_bits=0, codes=None, scales=None):
     """Build a skl_desc_t from host arrays.  ``hash_a``, ``hash_c``,
     ``group_width`` (uint32) and ``states`` (uint16) are objects exposing the
     buffer protocol with those element types, or None; the returned
-    descriptor keeps them alive."""
+    descriptor keeps them alive.  Low-bit states: ``state_bits`` 8 or 4,
+    ``codes`` (bytes: int8 per state, or packed nibbles) and ``scales``
+    (uint16), ``states`` None and ``n_states`` given."""
     desc = skl_desc_t()
     desc.struct_size = ctypes.sizeof(skl_desc_t) if struct_size is None else struct_size
     desc.in_features, desc.out_features = in_features, out_features
@@ -131,6 +139,9 @@ def make_desc(in_features, out_features, tile_in, tile_out, d, hash_a, hash_c, g
     desc.hash_c = ptr(hash_c, 4)
     desc.group_width = ptr(group_width, 4)
     desc.states = ptr(states, 2)
+    desc.state_bits = state_bits
+    desc.codes = ptr(codes, 1)
+    desc.scales = ptr(scales, 2)
     if n_states is None:
         n_states = 0 if states is None else memoryview(states).nbytes // 2
     desc.n_states = n_states
@@ -197,8 +208,9 @@ def sketch_linear_prefill_split(out_features: int, n_blocks: int, tokens: int):
     return segs, tuple(shape)
 
 
-def sketch_linear_reconstruct(layer: int, W_hat_dev: int, hip_stream: int = 0) -> None:
-    _check(load_library().sketch_linear_reconstruct(layer, W_hat_dev, hip_stream))
+def sketch_linear_reconstruct(layer: int, W_hat_dev: int, workspace: int = 0, workspace_bytes: int = 0,
+                              hip_stream: int = 0) -> None:
+    _check(load_library().sketch_linear_reconstruct(layer, W_hat_dev, workspace, workspace_bytes, hip_stream))
 
 
 def sketch_linear_destroy(layer: int) -> None:

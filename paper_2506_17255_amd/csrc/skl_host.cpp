@@ -34,11 +34,28 @@ void skl_set_error(const char *fmt, ...)
 static inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
 // ---------------------------------------------------------------- planning
+// the caller's struct (first or current version) copied into the current layout
+static skl_status_t normalize_desc(const skl_desc_t *user, skl_desc_t *d)
+{
+    if (!user) FAIL(SKL_ERR_INVALID_ARG, "desc is NULL");
+    if (user->struct_size != sizeof(skl_desc_t) && user->struct_size != SKL_DESC_SIZE_V1)
+        FAIL(SKL_ERR_INVALID_ARG, "desc.struct_size is %u, expected %zu (or %u, the first version)", user->struct_size,
+             sizeof(skl_desc_t), SKL_DESC_SIZE_V1);
+    memset(d, 0, sizeof *d);
+    memcpy(d, user, user->struct_size);
+    return SKL_OK;
+}
+
+static int code_at(const skl_desc_t *d, uint64_t i)
+{
+    if (d->state_bits == 8) return static_cast<const int8_t *>(d->codes)[i];
+    const uint8_t b = static_cast<const uint8_t *>(d->codes)[i >> 1];
+    const int nib = (i & 1) ? b >> 4 : b & 15;
+    return nib >= 8 ? nib - 16 : nib;
+}
+
 static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out)
 {
-    if (!d) FAIL(SKL_ERR_INVALID_ARG, "desc is NULL");
-    if (d->struct_size != sizeof(skl_desc_t))
-        FAIL(SKL_ERR_INVALID_ARG, "desc.struct_size is %u, expected %zu", d->struct_size, sizeof(skl_desc_t));
     if (d->in_features == 0 || d->out_features == 0)
         FAIL(SKL_ERR_INVALID_ARG, "in_features and out_features must be positive");
     if (d->in_features > (1u << 30) || d->out_features > (1u << 30))
@@ -51,8 +68,15 @@ static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out)
     if (d->d < 1 || d->d > SKL_MAX_D) FAIL(SKL_ERR_INVALID_ARG, "d = %u sketch rows, must be 1..8", d->d);
     if (d->query_mode != 0) FAIL(SKL_ERR_UNSUPPORTED, "query_mode %u is reserved", d->query_mode);
     if (d->flags & ~1u) FAIL(SKL_ERR_INVALID_ARG, "unknown bits in flags: 0x%x", d->flags);
-    if (!d->hash_a || !d->hash_c || !d->group_width || !d->states)
-        FAIL(SKL_ERR_INVALID_ARG, "hash_a, hash_c, group_width and states must not be NULL");
+    if (d->state_bits != 0 && d->state_bits != 16 && d->state_bits != 8 && d->state_bits != 4)
+        FAIL(SKL_ERR_INVALID_ARG, "state_bits = %u, must be 0, 16, 8 or 4", d->state_bits);
+    if (d->reserved != 0) FAIL(SKL_ERR_INVALID_ARG, "desc.reserved must be 0");
+    const bool low_bit = d->state_bits == 8 || d->state_bits == 4;
+    if (!d->hash_a || !d->hash_c || !d->group_width)
+        FAIL(SKL_ERR_INVALID_ARG, "hash_a, hash_c and group_width must not be NULL");
+    if (!low_bit && !d->states) FAIL(SKL_ERR_INVALID_ARG, "states must not be NULL");
+    if (low_bit && (!d->codes || !d->scales || d->states))
+        FAIL(SKL_ERR_INVALID_ARG, "low-bit states need codes and scales, and states must be NULL");
     for (uint32_t r = 0; r < d->d; ++r)
         if (d->hash_a[r] >= (1u << 24) || d->hash_c[r] >= (1u << 24))
             FAIL(SKL_ERR_INVALID_ARG, "hash parameters of row %u are not below 2^24", r);
@@ -68,9 +92,23 @@ static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out)
         FAIL(SKL_ERR_INVALID_ARG, "n_states = %llu but d * sum(group_width) = %llu",
              (unsigned long long)d->n_states, (unsigned long long)(sum * d->d));
     if (d->n_states >= (1ull << 32)) FAIL(SKL_ERR_UNSUPPORTED, "more than 2^32 states in one layer");
-    for (uint64_t i = 0; i < d->n_states; ++i)
-        if ((d->states[i] & 0x7C00u) == 0x7C00u)
-            FAIL(SKL_ERR_NONFINITE, "states[%llu] = 0x%04x is NaN or infinite", (unsigned long long)i, d->states[i]);
+    if (!low_bit) {
+        for (uint64_t i = 0; i < d->n_states; ++i)
+            if ((d->states[i] & 0x7C00u) == 0x7C00u)
+                FAIL(SKL_ERR_NONFINITE, "states[%llu] = 0x%04x is NaN or infinite", (unsigned long long)i, d->states[i]);
+    } else {
+        if (n_groups * d->d >= (1ull << 32)) FAIL(SKL_ERR_UNSUPPORTED, "more than 2^32 scales in one layer");
+        for (uint64_t i = 0; i < n_groups * d->d; ++i) {
+            if ((d->scales[i] & 0x7C00u) == 0x7C00u)
+                FAIL(SKL_ERR_NONFINITE, "scales[%llu] = 0x%04x is NaN or infinite", (unsigned long long)i, d->scales[i]);
+            if (d->scales[i] & 0x8000u)
+                FAIL(SKL_ERR_INVALID_ARG, "scales[%llu] = 0x%04x has its sign bit set", (unsigned long long)i, d->scales[i]);
+        }
+        const int lowest = d->state_bits == 8 ? -128 : -8;
+        for (uint64_t i = 0; i < d->n_states; ++i)
+            if (code_at(d, i) == lowest)
+                FAIL(SKL_ERR_INVALID_ARG, "codes[%llu] = %d is outside [-qmax, qmax]", (unsigned long long)i, lowest);
+    }
     *n_groups_out = n_groups;
     return SKL_OK;
 }
@@ -313,12 +351,18 @@ static skl_status_t plan_tiles(const skl_desc_t *d, uint64_t n_groups, skl_plan 
     return SKL_OK;
 }
 
-skl_status_t skl_make_plan(const skl_desc_t *d, skl_plan *P)
+skl_status_t skl_make_plan(const skl_desc_t *user, skl_plan *P)
 {
     uint64_t n_groups = 0;
-    skl_status_t st = validate_desc(d, &n_groups);
+    skl_status_t st = normalize_desc(user, &P->desc);
+    if (st != SKL_OK) return st;
+    const skl_desc_t *d = &P->desc;
+    st = validate_desc(d, &n_groups);
     if (st != SKL_OK) return st;
     skl_layer &L = P->L;
+    L.qbits = d->state_bits == 8 || d->state_bits == 4 ? d->state_bits : 0;
+    L.n_groups = (uint32_t)n_groups;
+    L.code_bytes = L.qbits == 8 ? d->n_states : L.qbits == 4 ? (d->n_states + 1) / 2 : 0;
     L.in = d->in_features; L.out = d->out_features; L.tj = d->tile_in; L.to = d->tile_out; L.d = d->d;
     for (uint32_t r = 0; r < d->d; ++r) { L.A[r] = d->hash_a[r]; L.C[r] = d->hash_c[r]; }
     L.n_states = d->n_states;
@@ -335,11 +379,20 @@ skl_status_t skl_make_plan(const skl_desc_t *d, skl_plan *P)
         L.off_ginfo = off;  off = align_up(off + P->ginfo.size() * sizeof(skl_group_info), 256);
         L.off_gunits = off; off = align_up(off + P->gunits.size() * sizeof(skl_gemm_unit), 256);
         L.off_gsteps = off; off = align_up(off + P->gsteps.size() * sizeof(skl_gemm_step), 256);
-        L.off_tables = off; off = align_up(off + L.table_bytes, 256);
-        L.off_ptables = off; off = align_up(off + L.ptable_bytes, 256);
+        if (!L.qbits) {
+            L.off_tables = off; off = align_up(off + L.table_bytes, 256);
+            L.off_ptables = off; off = align_up(off + L.ptable_bytes, 256);
+        } else {
+            L.off_choff = off;  off = align_up(off + ((uint64_t)L.in + 1) * sizeof(uint32_t), 256);
+        }
     } else {
         L.off_gmeta = off;  off = align_up(off + P->gmeta.size() * sizeof(skl_group_meta), 256);
-        L.off_keys = off;   off = align_up(off + L.table_bytes + 16, 256);
+        if (!L.qbits) { L.off_keys = off;   off = align_up(off + L.table_bytes + 16, 256); }
+    }
+    if (L.qbits) {
+        if (n_groups >= (1ull << 32) / SKL_MAX_D) FAIL(SKL_ERR_UNSUPPORTED, "too many groups for low-bit states");
+        L.off_codes = off;  off = align_up(off + L.code_bytes + 16, 256);
+        L.off_scales = off; off = align_up(off + n_groups * d->d * sizeof(uint16_t), 256);
     }
     P->dev_bytes = off;
     return SKL_OK;
@@ -381,6 +434,11 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         FAIL(SKL_ERR_INVALID_ARG, "out of host memory for a %llu-byte staging image", (unsigned long long)P.dev_bytes);
     }
     skl_layer &L = P.L;
+    desc = &P.desc;                 // from here on: the description in the current struct layout
+    if (L.qbits) {
+        memcpy(img.data() + L.off_codes, desc->codes, L.code_bytes);
+        memcpy(img.data() + L.off_scales, desc->scales, (uint64_t)L.n_groups * L.d * sizeof(uint16_t));
+    }
     if (L.path == 1) {
         memcpy(img.data() + L.off_bmeta, P.bmeta.data(), P.bmeta.size() * sizeof(skl_block_meta));
         memcpy(img.data() + L.off_chan, P.chan.data(), P.chan.size() * sizeof(uint32_t));
@@ -390,9 +448,14 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         // state offset of every input channel (one group per channel)
         std::vector<uint64_t> base(L.in + 1, 0);
         for (uint32_t j = 0; j < L.in; ++j) base[j + 1] = base[j] + (uint64_t)L.d * desc->group_width[j];
+        if (L.qbits) {
+            uint32_t *choff = reinterpret_cast<uint32_t *>(img.data() + L.off_choff);
+            for (uint32_t j = 0; j <= L.in; ++j) choff[j] = (uint32_t)base[j];
+        }
         uint16_t *tab = reinterpret_cast<uint16_t *>(img.data() + L.off_tables);
         uint16_t *ptab = reinterpret_cast<uint16_t *>(img.data() + L.off_ptables);
         for (const skl_block_meta &bm : P.bmeta) {
+            if (L.qbits) break;     // tables are expanded on the device, per call
             uint16_t *t = tab + (uint64_t)bm.table_off16 * 8;
             uint16_t *pt = ptab + (uint64_t)bm.ptable_off16 * 8;
             for (uint32_t c8 = 0; c8 < 8 * bm.nb; ++c8) {
@@ -409,8 +472,10 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         }
     } else {
         memcpy(img.data() + L.off_gmeta, P.gmeta.data(), P.gmeta.size() * sizeof(skl_group_meta));
-        uint16_t *keys = reinterpret_cast<uint16_t *>(img.data() + L.off_keys);
-        for (uint64_t i = 0; i < desc->n_states; ++i) keys[i] = skl_key_of_half(desc->states[i]);
+        if (!L.qbits) {
+            uint16_t *keys = reinterpret_cast<uint16_t *>(img.data() + L.off_keys);
+            for (uint64_t i = 0; i < desc->n_states; ++i) keys[i] = skl_key_of_half(desc->states[i]);
+        }
     }
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -435,7 +500,7 @@ skl_status_t sketch_linear_info(const skl_layer_t *L, skl_info_t *info)
     info->path = L->path;
     info->n_units = L->n_units;
     info->max_table_bytes = L->max_table_bytes;
-    info->table_bytes = L->table_bytes;
+    info->table_bytes = L->qbits ? L->code_bytes + (uint64_t)L->n_groups * L->d * sizeof(uint16_t) : L->table_bytes;
     info->n_weights = (uint64_t)L->in * L->out;
     info->n_states = L->n_states;
     return SKL_OK;
@@ -450,8 +515,10 @@ skl_status_t sketch_linear_workspace_bytes(const skl_layer_t *L, uint32_t op, ui
     } else if (op == 1) {
         if (n < 1) FAIL(SKL_ERR_INVALID_ARG, "tokens must be positive");
         *bytes = skl_gemm_workspace_bytes(L, n);
+    } else if (op == 2) {
+        *bytes = skl_reconstruct_workspace_bytes(L);
     } else {
-        FAIL(SKL_ERR_INVALID_ARG, "op = %u, must be 0 (gemv) or 1 (gemm)", op);
+        FAIL(SKL_ERR_INVALID_ARG, "op = %u, must be 0 (gemv), 1 (gemm) or 2 (reconstruct)", op);
     }
     return SKL_OK;
 }
@@ -545,11 +612,22 @@ skl_status_t sketch_linear_prefill_split(uint32_t out_features, uint32_t n_block
     return SKL_OK;
 }
 
-skl_status_t sketch_linear_reconstruct(const skl_layer_t *L, uint16_t *W_hat_dev, void *stream)
+skl_status_t sketch_linear_reconstruct(const skl_layer_t *L, uint16_t *W_hat_dev, void *ws, uint64_t ws_bytes,
+                                       void *stream)
 {
     if (!L || !W_hat_dev) FAIL(SKL_ERR_INVALID_ARG, "layer or W_hat_dev is NULL");
     if ((uintptr_t)W_hat_dev % 16) FAIL(SKL_ERR_INVALID_ARG, "W_hat_dev not 16-byte aligned");
-    return skl_launch_reconstruct(L, W_hat_dev, stream);
+    const uint64_t need = skl_reconstruct_workspace_bytes(L);
+    if (need) {
+        if (!ws) FAIL(SKL_ERR_INVALID_ARG, "workspace is NULL (%llu bytes needed)", (unsigned long long)need);
+        if ((uintptr_t)ws % 16) FAIL(SKL_ERR_INVALID_ARG, "workspace not 16-byte aligned");
+        if (ws_bytes < need)
+            FAIL(SKL_ERR_BUFFER_TOO_SMALL, "workspace holds %llu bytes, %llu needed", (unsigned long long)ws_bytes,
+                 (unsigned long long)need);
+        if (overlap(ws, need, W_hat_dev, (uint64_t)L->in * L->out * 2))
+            FAIL(SKL_ERR_INVALID_ARG, "workspace overlaps W_hat_dev");
+    }
+    return skl_launch_reconstruct(L, W_hat_dev, ws, stream);
 }
 
 }  // extern "C"

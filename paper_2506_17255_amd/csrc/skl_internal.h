@@ -123,11 +123,18 @@ struct skl_layer {
     uint32_t gemm_v3 = 0;     // third prefill kernel (256 x 256 tile): two tables and two wide operand slots fit in LDS, at most 12 KiB of table per wavefront
     uint32_t gemm_v2 = 0, n_gsteps = 0, gemm_ns = 1;   // gemm_ns: steps per block of the widest class
     uint64_t off_gsteps = 0;
+
+    // low-bit states: only codes, scales and (path 1) the state offset of every input channel are
+    // resident; every call expands them into 16-bit tables at the end of its workspace
+    uint32_t qbits = 0;             // 0 (binary16 states), 8 or 4
+    uint64_t off_codes = 0, off_scales = 0, off_choff = 0, code_bytes = 0;
+    uint32_t n_groups = 0;
 };
 
 // The host-side plan: everything create() copies to the device.
 struct skl_plan {
     skl_layer L;
+    skl_desc_t desc;                // the caller's description in the current layout of the struct
     uint64_t dev_bytes = 0;
     std::vector<skl_group_meta> gmeta;
     std::vector<skl_block_meta> bmeta;
@@ -152,7 +159,10 @@ static inline uint16_t skl_key_of_half(uint16_t b)
 }
 
 // ---- launchers implemented in skl_kernels.hip (all enqueue only) -----------
-skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *stream);
+skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *ws, void *stream);
+// bytes of expanded tables at the end of every workspace of a layer with low-bit states (else 0)
+uint64_t skl_dequant_bytes(const skl_layer *L);
+uint64_t skl_reconstruct_workspace_bytes(const skl_layer *L);
 // with_reduction = false: partial sums only (y, y_dt, ldy unused)
 skl_status_t skl_launch_gemv(const skl_layer *L, const void *x, uint32_t ldx, void *y,
                              skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *ws, void *stream,

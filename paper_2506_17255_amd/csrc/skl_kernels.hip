@@ -2062,25 +2062,142 @@ __global__ __launch_bounds__(SKL_WG) void k_reduce_partials(const float *__restr
 }
 
 // ========================================================================
+// Low-bit states: codes -> order keys.  A layer with 8- or 4-bit states keeps
+// only codes and one binary16 scale per (group, sketch row) resident; every
+// call first expands them into the 16-bit tables its kernels read (the same
+// layouts create() builds on the host for binary16 states).  The state a code
+// stands for is q * scale / qmax rounded once to binary16: the product is
+// exact in float32 (7 x 11 significant bits), the correctly rounded float32
+// quotient is either exact or far from any binary16 rounding boundary (qmax is
+// odd), so the second rounding never changes the result.
+// ========================================================================
+template <int BITS>
+__device__ __forceinline__ int code_at(const uint8_t *codes, uint32_t i)
+{
+    if (BITS == 8) return static_cast<int8_t>(codes[i]);
+    const uint32_t b = codes[i >> 1];
+    return (int)(((i & 1) ? b >> 4 : b & 15u) ^ 8u) - 8;      // sign-extend the nibble
+}
+
+template <int BITS>
+__device__ __forceinline__ uint16_t key_of_code(int q, uint16_t scale_bits)
+{
+    const float v = __fdiv_rn((float)q * half_bits_to_float(scale_bits), BITS == 8 ? 127.0f : 7.0f);
+    const uint16_t h = float_to_half_bits(v);
+    return (uint16_t)(((h & 0x7FFFu) << 1) | (1u - (h >> 15)));
+}
+
+// row sketches: grid (channel blocks), word (r, k, c) of a block holds the keys of channels 8c .. 8c + 7;
+// writes the padded layout, the unpadded one, or both
+template <int BITS>
+__global__ __launch_bounds__(SKL_WG) void k_expand_rows(const skl_block_meta *__restrict__ bmeta, const uint32_t *__restrict__ chan,
+                                                         const uint32_t *__restrict__ choff, const uint8_t *__restrict__ codes,
+                                                         const uint16_t *__restrict__ scales, uint32_t d,
+                                                         uint4 *__restrict__ padded, uint4 *__restrict__ unpadded)
+{
+    const skl_block_meta bm = bmeta[blockIdx.x];
+    const uint32_t K = bm.K, nb = bm.nb, n = d * nb * K;
+    for (uint32_t idx = threadIdx.x; idx < n; idx += SKL_WG) {
+        const uint32_t k = idx % K, c = (idx / K) % nb, r = idx / (K * nb);     // k fastest: neighbouring lanes read neighbouring codes
+        uint32_t key[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t ch = chan[bm.chan_off + 8 * c + i];
+            key[i] = 1;                                                          // a channel slot past the end: +0.0
+            if (ch != SKL_NO_CHANNEL)
+                key[i] = key_of_code<BITS>(code_at<BITS>(codes, choff[ch] + r * K + k), scales[ch * d + r]);
+        }
+        const uint4 w = make_uint4(key[0] | key[1] << 16, key[2] | key[3] << 16, key[4] | key[5] << 16, key[6] | key[7] << 16);
+        if (padded) padded[bm.table_off16 + (size_t)(r * K + k) * bm.rs + c] = w;
+        if (unpadded) unpadded[bm.ptable_off16 + (size_t)(r * K + k) * nb + c] = w;
+    }
+}
+
+// 2-D groups: keys in the caller's state order; grid (groups)
+template <int BITS>
+__global__ __launch_bounds__(SKL_WG) void k_expand_groups(const skl_group_meta *__restrict__ gmeta, const uint8_t *__restrict__ codes,
+                                                           const uint16_t *__restrict__ scales, uint32_t d, uint16_t *__restrict__ keys)
+{
+    const skl_group_meta gm = gmeta[blockIdx.x];
+    for (uint32_t idx = threadIdx.x; idx < d * gm.K; idx += SKL_WG)
+        keys[gm.key_off + idx] = key_of_code<BITS>(code_at<BITS>(codes, gm.key_off + idx), scales[blockIdx.x * d + idx / gm.K]);
+}
+
+// ========================================================================
 // Launchers
 // ========================================================================
-static RowArgs make_row_args(const skl_layer *L)
+static skl_status_t check_launch(const char *what);
+
+// the tables a call's kernels read: the resident ones, or for low-bit states their expansion in `area`
+struct TableSrc {
+    const uint4 *tables = nullptr, *ptables = nullptr;
+    const uint16_t *keys = nullptr;
+};
+
+static uint64_t round256(uint64_t v) { return (v + 255) / 256 * 256; }
+
+uint64_t skl_dequant_bytes(const skl_layer *L)
+{
+    if (!L->qbits) return 0;
+    return L->path == 1 ? round256(L->table_bytes) + round256(L->ptable_bytes) : round256(L->table_bytes + 16);
+}
+
+static skl_status_t table_source(const skl_layer *L, void *area, bool want_padded, bool want_unpadded, hipStream_t stream,
+                                 TableSrc *src)
+{
+    if (!L->qbits) {
+        if (L->path == 1) {
+            src->tables = reinterpret_cast<const uint4 *>(L->dev + L->off_tables);
+            src->ptables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables);
+        } else {
+            src->keys = reinterpret_cast<const uint16_t *>(L->dev + L->off_keys);
+        }
+        return SKL_OK;
+    }
+    const uint8_t *codes = L->dev + L->off_codes;
+    const uint16_t *scales = reinterpret_cast<const uint16_t *>(L->dev + L->off_scales);
+    if (L->path == 1) {
+        uint4 *padded = static_cast<uint4 *>(area);
+        uint4 *unpadded = reinterpret_cast<uint4 *>(static_cast<char *>(area) + round256(L->table_bytes));
+        src->tables = padded; src->ptables = unpadded;
+        const skl_block_meta *bmeta = reinterpret_cast<const skl_block_meta *>(L->dev + L->off_bmeta);
+        const uint32_t *chan = reinterpret_cast<const uint32_t *>(L->dev + L->off_chan);
+        const uint32_t *choff = reinterpret_cast<const uint32_t *>(L->dev + L->off_choff);
+        if (L->qbits == 8)
+            hipLaunchKernelGGL(k_expand_rows<8>, dim3(L->n_blocks), dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
+                               L->d, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
+        else
+            hipLaunchKernelGGL(k_expand_rows<4>, dim3(L->n_blocks), dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
+                               L->d, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
+    } else {
+        uint16_t *keys = static_cast<uint16_t *>(area);
+        src->keys = keys;
+        const skl_group_meta *gmeta = reinterpret_cast<const skl_group_meta *>(L->dev + L->off_gmeta);
+        if (L->qbits == 8)
+            hipLaunchKernelGGL(k_expand_groups<8>, dim3(L->n_groups), dim3(SKL_WG), 0, stream, gmeta, codes, scales, L->d, keys);
+        else
+            hipLaunchKernelGGL(k_expand_groups<4>, dim3(L->n_groups), dim3(SKL_WG), 0, stream, gmeta, codes, scales, L->d, keys);
+    }
+    return check_launch("expansion of low-bit states");
+}
+
+static RowArgs make_row_args(const skl_layer *L, const TableSrc &src)
 {
     RowArgs a;
     for (int r = 0; r < SKL_MAX_D; ++r) { a.h.A[r] = L->A[r]; a.h.C[r] = L->C[r]; }
     a.bmeta = reinterpret_cast<const skl_block_meta *>(L->dev + L->off_bmeta);
     a.chan = reinterpret_cast<const uint32_t *>(L->dev + L->off_chan);
-    a.tables = reinterpret_cast<const uint4 *>(L->dev + L->off_tables);
+    a.tables = src.tables;
     a.in = L->in; a.out = L->out; a.n_blocks = L->n_blocks; a.n_otiles = L->n_otiles; a.n_seg = L->n_seg;
     return a;
 }
 
-static TileArgs make_tile_args(const skl_layer *L)
+static TileArgs make_tile_args(const skl_layer *L, const TableSrc &src)
 {
     TileArgs a;
     for (int r = 0; r < SKL_MAX_D; ++r) { a.h.A[r] = L->A[r]; a.h.C[r] = L->C[r]; }
     a.gmeta = reinterpret_cast<const skl_group_meta *>(L->dev + L->off_gmeta);
-    a.keys = reinterpret_cast<const uint16_t *>(L->dev + L->off_keys);
+    a.keys = src.keys;
     a.in = L->in; a.out = L->out; a.tj = L->tj; a.to = L->to; a.n_ob = L->n_ob;
     a.jc_rows = L->jc_rows; a.n_jc = L->n_jc;
     return a;
@@ -2134,10 +2251,20 @@ static skl_status_t allow_lds(K kernel, size_t bytes)
 
 static inline size_t tile_key_words(const skl_layer *L) { return ((size_t)L->d * L->max_K * 2 + 15) / 16; }
 
-uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch)
+// partial sums of the split reduction
+static uint64_t gemv_partial_bytes(const skl_layer *L, uint32_t batch)
 {
     return (uint64_t)L->n_units * batch * L->out * sizeof(float);
 }
+
+// low-bit states: the expanded tables follow the call's own scratch
+uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch)
+{
+    const uint64_t own = gemv_partial_bytes(L, batch);
+    return L->qbits ? round256(own) + skl_dequant_bytes(L) : own;
+}
+
+uint64_t skl_reconstruct_workspace_bytes(const skl_layer *L) { return skl_dequant_bytes(L); }
 
 // split of the third prefill kernel for a call with this many tokens (256 CUs: 32 workgroups per XCD,
 // fewer when an XCD's share of the work is under four blocks per workgroup)
@@ -2191,7 +2318,7 @@ static uint64_t gemm_pack_bytes(const skl_layer *L, uint32_t tokens)
     return L->gemm_v2 || L->gemm_v3 ? m_tiles * L->n_gsteps * 8192ull : m_tiles * L->n_gunits * GM_MT * L->gemm_uw * 16;
 }
 
-uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
+static uint64_t gemm_own_bytes(const skl_layer *L, uint32_t tokens)
 {
     if (L->path != 1) return 0;
     uint64_t bytes = gemm_pack_bytes(L, tokens);
@@ -2202,12 +2329,20 @@ uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
     return bytes;
 }
 
-skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *stream_)
+uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
+{
+    const uint64_t own = gemm_own_bytes(L, tokens);
+    return L->qbits ? round256(own) + skl_dequant_bytes(L) : own;
+}
+
+skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *ws, void *stream_)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    skl_status_t st = SKL_OK;
+    TableSrc src;
+    skl_status_t st = table_source(L, ws, true, false, stream, &src);
+    if (st != SKL_OK) return st;
     if (L->path == 1) {
-        const RowArgs a = make_row_args(L);
+        const RowArgs a = make_row_args(L, src);
         const size_t lds = (size_t)L->max_table_bytes + 64 * sizeof(uint32_t);
         const dim3 grid(L->n_blocks, L->n_seg);
         DISPATCH_D(L->d, {
@@ -2215,7 +2350,7 @@ skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *s
             if (st == SKL_OK) hipLaunchKernelGGL(k_row_reconstruct<D>, grid, dim3(SKL_WG), lds, stream, a, W_hat);
         });
     } else {
-        const TileArgs a = make_tile_args(L);
+        const TileArgs a = make_tile_args(L, src);
         const size_t lds = tile_key_words(L) * 16;
         const dim3 grid(L->n_jb * L->n_ob * L->n_jc, (L->to + SKL_WG - 1) / SKL_WG);
         DISPATCH_D(L->d, {
@@ -2232,17 +2367,20 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const uint16_t *x = static_cast<const uint16_t *>(x_);
     float *partial = static_cast<float *>(ws);
-    skl_status_t st = SKL_OK;
+    TableSrc src;
+    skl_status_t st = table_source(L, static_cast<char *>(ws) + round256(gemv_partial_bytes(L, batch)),
+                                   L->path == 1 && batch > 1, L->path == 1 && batch == 1, stream, &src);
+    if (st != SKL_OK) return st;
     if (L->path == 1) {
         StreamArgs a;
-        a.r = make_row_args(L);
+        a.r = make_row_args(L, src);
         a.ginfo = reinterpret_cast<const skl_group_info *>(L->dev + L->off_ginfo);
         a.n_wunits = L->n_wunits; a.n_sseg = L->n_sseg; a.n_bg = L->n_bg; a.buf_words = L->max_table_bytes / 16;
         a.two_bufs = L->two_bufs;
         const dim3 grid(8 * ((L->n_bg + 7) / 8) * L->n_sseg);
         if (batch == 1) {
             // unpadded tables; buffers at fixed LDS addresses
-            a.r.tables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables);
+            a.r.tables = src.ptables;
             a.buf_words = L->max_ptable_bytes / 16;
             a.two_bufs = L->two_pbufs;
             // one wavefront per 64-output unit of the longest segment (at least two for the start-up loads)
@@ -2276,7 +2414,7 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
             })
         }
     } else {
-        const TileArgs a = make_tile_args(L);
+        const TileArgs a = make_tile_args(L, src);
         const uint32_t kw = (uint32_t)tile_key_words(L);
         const uint32_t units = L->n_jb * L->n_ob * L->n_jc, noc = (L->to + SKL_WG - 1) / SKL_WG;
         if (batch == 1) {
@@ -2330,10 +2468,14 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const uint16_t *X = static_cast<const uint16_t *>(X_);
-    skl_status_t st = SKL_OK;
+    const bool rebuilt_once = L->gemm_v3 || L->gemm_v2;      // the kernels that read the unpadded tables
+    TableSrc src;
+    skl_status_t st = table_source(L, static_cast<char *>(ws) + round256(gemm_own_bytes(L, tokens)),
+                                   L->path == 1 && !rebuilt_once, L->path == 1 && rebuilt_once, stream, &src);
+    if (st != SKL_OK) return st;
     if (L->path == 1) {
         uint16_t *Xp = static_cast<uint16_t *>(ws);
-        const RowArgs a = make_row_args(L);
+        const RowArgs a = make_row_args(L, src);
         const skl_gemm_unit *units = reinterpret_cast<const skl_gemm_unit *>(L->dev + L->off_gunits);
         const uint32_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
         if (m_tiles > 8191) {
@@ -2345,7 +2487,7 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
             st = launch_pack(L, X, x_dt, ldx, tokens, a.chan, steps, static_cast<uint4 *>(ws), stream);
             if (st != SKL_OK) return st;
             Gemm2Args g;
-            g.h = a.h; g.ptables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables); g.bmeta = a.bmeta;
+            g.h = a.h; g.ptables = src.ptables; g.bmeta = a.bmeta;
             g.Xp = static_cast<const uint4 *>(ws); g.Y = Y;
             g.zeros = reinterpret_cast<const uint4 *>(L->dev);       // the reserved head of the layer buffer stays zero
             g.n_blocks = L->n_blocks; g.n_steps = L->n_gsteps; g.tokens = tokens; g.out = L->out; g.y_dt = (uint32_t)y_dt;
@@ -2371,7 +2513,7 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
             st = launch_pack(L, X, x_dt, ldx, tokens, a.chan, steps, static_cast<uint4 *>(ws), stream);
             if (st != SKL_OK) return st;
             Gemm2Args g;
-            g.h = a.h; g.ptables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables); g.bmeta = a.bmeta;
+            g.h = a.h; g.ptables = src.ptables; g.bmeta = a.bmeta;
             g.Xp = static_cast<const uint4 *>(ws); g.Y = Y;
             g.n_blocks = L->n_blocks; g.n_steps = L->n_gsteps; g.tokens = tokens; g.out = L->out; g.y_dt = (uint32_t)y_dt;
             g.ldy = ldy; g.tab_words = L->max_ptable_bytes / 16; g.n_col = (L->out + GM_NT - 1) / GM_NT; g.m_tiles = m_tiles;
@@ -2416,7 +2558,7 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
         else LAUNCH_GEMM(2)
 #undef LAUNCH_GEMM
     } else {
-        const TileArgs a = make_tile_args(L);
+        const TileArgs a = make_tile_args(L, src);
         const uint32_t kw = (uint32_t)tile_key_words(L);
         const size_t lds = (size_t)kw * 16 + (size_t)2 * TG_T * TG_AS * sizeof(uint16_t);
         const uint32_t n_oc = (L->to + TG_T - 1) / TG_T;

@@ -28,6 +28,15 @@ def build_sketch(wl: wk.Workload, W=None, widths=None):
 
 
 def desc_of(sk: oracle.Sketch, flags: int = 0):
+    if isinstance(sk, oracle.QuantSketch):
+        codes = np.ascontiguousarray(sk.codes, dtype=np.int8)
+        packed = codes.view(np.uint8) if sk.bits == 8 else wk.pack_nibbles(codes)
+        return skl.make_desc(sk.in_features, sk.out_features, sk.tile_in, sk.tile_out, sk.d,
+                             np.ascontiguousarray(sk.hash_a, dtype=np.uint32),
+                             np.ascontiguousarray(sk.hash_c, dtype=np.uint32),
+                             np.ascontiguousarray(sk.group_width, dtype=np.uint32), None, n_states=codes.size,
+                             flags=flags, state_bits=sk.bits, codes=packed,
+                             scales=np.ascontiguousarray(sk.scales, dtype=np.uint16))
     return skl.make_desc(sk.in_features, sk.out_features, sk.tile_in, sk.tile_out, sk.d,
                          np.ascontiguousarray(sk.hash_a, dtype=np.uint32),
                          np.ascontiguousarray(sk.hash_c, dtype=np.uint32),
@@ -76,7 +85,8 @@ class GpuLayer:
     def reconstruct(self) -> np.ndarray:
         t = self.torch
         out = t.full((self.sk.in_features, self.sk.out_features), 0x7E00, dtype=t.int16, device=self.dev)
-        skl.sketch_linear_reconstruct(self.handle, out.data_ptr(), self.stream())
+        ws, need = self.workspace(2, 0)
+        skl.sketch_linear_reconstruct(self.handle, out.data_ptr(), ws.data_ptr(), ws.numel(), self.stream())
         t.cuda.synchronize()
         return out.cpu().numpy().view(np.uint16)
 

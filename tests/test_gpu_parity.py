@@ -218,6 +218,66 @@ def test_gemm_row_equals_gemv():
     assert rel_fro(Y, y) <= 1e-5
 
 
+# ------------------------------------------------------- low-bit states
+LOWBIT = ["cfg1", "row_ragged", "row_classes", "row_d1", "row_d5", "row_d8", "row_big_table", "row_single",
+          "tile_ragged", "tile_d8_K1", "tile_forced_1d"]
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("name", LOWBIT)
+def test_low_bit_states_match_oracle(name, bits):
+    """States kept as 8-/4-bit codes with one scale per sketch row (Sec. 3.3, last paragraph): the
+    library expands them on the device per call; reconstructed weights are bit-exact against the
+    oracle's query over the states the codes stand for, outputs within the floating-point bar."""
+    W, sk = small_case(name)
+    q = oracle.quantize(sk, bits)
+    W_hat = oracle.query(q)
+    rng = np.random.default_rng(300 + bits)
+    x = rng.standard_normal((5, sk.in_features)).astype(np.float16)
+    Xf = rng.standard_normal((300, sk.in_features)).astype(np.float32)
+    Xb = wk.f32_to_bf16_bits(Xf)
+    with GpuLayer(q, flags_of(name)) as g:
+        got = g.reconstruct()
+        assert np.array_equal(got, W_hat), (name, bits, int(np.sum(got != W_hat)))
+        y1 = g.gemv(x[:1], "f32")
+        y5 = g.gemv(x, "f32", ldx=sk.in_features + 8, ldy=sk.out_features + 24)
+        y16 = g.gemv(x, "f16")
+        Y = g.gemm(Xb, "bf16", "f32")
+        Ybf = g.gemm(Xb[:70], "bf16", "bf16")
+        full = GpuLayer(oracle.Sketch(q.in_features, q.out_features, q.tile_in, q.tile_out, q.d, q.hash_a, q.hash_c,
+                                      q.group_width, q.states), flags_of(name))
+        with full as f:
+            # the same states given as binary16: the kernels see identical tables, so identical results
+            assert np.array_equal(f.gemv(x, "f32"), g.gemv(x, "f32"))
+            assert np.array_equal(f.gemm(Xb, "bf16", "f32"), Y)
+            assert g.info["table_bytes"] < f.info["table_bytes"] or sk.states.size < 64
+    ref = oracle.linear(W_hat, x)
+    assert rel_fro(y1, ref[:1]) <= 1e-5
+    assert rel_fro(y5, ref) <= 1e-5
+    assert rel_fro(y16, ref) <= TOL
+    refX = oracle.linear(W_hat, Xb, x_kind="bf16")
+    assert rel_fro(Y, refX) <= 1e-5
+    assert rel_fro(Ybf, round_to_bf16(refX[:70])) <= TOL
+
+
+def test_low_bit_workspace_holds_the_expanded_tables():
+    import paper_2506_17255_amd as skl
+    W, sk = small_case("row_classes")
+    q = oracle.quantize(sk, 4)
+    with GpuLayer(q) as g, GpuLayer(sk) as f:
+        for op, n in ((0, 1), (0, 16), (1, 300), (2, 0)):
+            need_q = skl.sketch_linear_workspace_bytes(g.handle, op, n)
+            need_f = skl.sketch_linear_workspace_bytes(f.handle, op, n)
+            assert need_q >= need_f + 2 * sk.states.size        # room for the 16-bit tables
+        assert skl.sketch_linear_workspace_bytes(f.handle, 2, 0) == 0
+        t = g.torch
+        out = t.zeros(sk.in_features * sk.out_features, dtype=t.int16, device=g.dev)
+        lib = skl.load_library()
+        assert lib.sketch_linear_reconstruct(g.handle, out.data_ptr(), None, 0, None) == skl.SKL_ERR_INVALID_ARG
+        small = t.zeros(16, dtype=t.uint8, device=g.dev)
+        assert lib.sketch_linear_reconstruct(g.handle, out.data_ptr(), small.data_ptr(), 16, None) == skl.SKL_ERR_BUFFER_TOO_SMALL
+
+
 # ----------------------------------------------------------- error paths
 def test_call_time_validation():
     import paper_2506_17255_amd as skl

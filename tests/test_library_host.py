@@ -40,7 +40,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_header_layout():
-    assert ctypes.sizeof(skl.skl_desc_t) == 72
+    assert ctypes.sizeof(skl.skl_desc_t) == 96
+    assert skl.skl_desc_t.state_bits.offset == skl.SKL_DESC_SIZE_V1 == 72
     assert ctypes.sizeof(skl.skl_info_t) == 40
 
 
@@ -116,7 +117,7 @@ def test_null_arguments():
     assert L.sketch_linear_create(ctypes.byref(good()), 4096, 1 << 20, None, None) == skl.SKL_ERR_INVALID_ARG
     assert L.sketch_linear_gemv(None, 16, 0, 8, 32, 2, 16, 1, 64, 0, None) == skl.SKL_ERR_INVALID_ARG
     assert L.sketch_linear_gemm(None, 16, 0, 8, 32, 2, 16, 1, 64, 0, None) == skl.SKL_ERR_INVALID_ARG
-    assert L.sketch_linear_reconstruct(None, 16, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_reconstruct(None, 16, None, 0, None) == skl.SKL_ERR_INVALID_ARG
     assert L.sketch_linear_workspace_bytes(None, 0, 1, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
     assert L.sketch_linear_info(None, None) == skl.SKL_ERR_INVALID_ARG
     assert L.sketch_linear_gemv_partials(None, None, 0, 0, 1, None, 0, None) == skl.SKL_ERR_INVALID_ARG
@@ -133,3 +134,61 @@ def test_device_bytes_scale_with_the_sketch_not_with_the_layer():
     nbytes = skl.sketch_linear_device_bytes(desc)
     assert 2 * in_f * d * K * 2 <= nbytes <= 2.3 * in_f * d * K * 2
     assert nbytes < 0.15 * in_f * out_f
+
+
+# ------------------------------------------------------------ low-bit states
+def good_lowbit(bits=4, **over):
+    n = 2 * 18
+    codes = np.zeros(n if bits == 8 else (n + 1) // 2, dtype=np.uint8)
+    kw = dict(states=None, n_states=n, state_bits=bits, codes=codes, scales=np.zeros(4 * 2, dtype=np.uint16))
+    kw.update(over)
+    return good(**kw)
+
+
+def test_first_version_of_the_descriptor_is_still_accepted():
+    assert status_of(good(struct_size=skl.SKL_DESC_SIZE_V1)) == skl.SKL_OK
+    # in the first layout the trailing fields do not exist: whatever follows the struct is not read
+    d = good(struct_size=skl.SKL_DESC_SIZE_V1, state_bits=4)
+    assert status_of(d) == skl.SKL_OK
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_low_bit_description_is_accepted_and_smaller(bits):
+    assert status_of(good_lowbit(bits)) == skl.SKL_OK
+    in_f, out_f, d, K = 4096, 11008, 4, 86
+    n = in_f * d * K
+    args = (in_f, out_f, 1, out_f, d, np.uint32([3, 5, 7, 9]), np.uint32([1, 2, 3, 4]), np.full(in_f, K, dtype=np.uint32))
+    full = skl.sketch_linear_device_bytes(skl.make_desc(*args, np.zeros(n, dtype=np.uint16)))
+    low = skl.sketch_linear_device_bytes(skl.make_desc(*args, None, n_states=n, state_bits=bits,
+                                                       codes=np.zeros(n * bits // 8, dtype=np.uint8),
+                                                       scales=np.zeros(in_f * d, dtype=np.uint16)))
+    # resident: codes, scales and metadata only (the 16-bit tables are expanded per call in the workspace)
+    assert n * bits // 8 <= low <= n * bits // 8 + 400 * 1024
+    assert low < full * (bits / 32 + 0.05)
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(state_bits=5), skl.SKL_ERR_INVALID_ARG),
+    (dict(reserved_=1), skl.SKL_ERR_INVALID_ARG),
+    (dict(codes=None), skl.SKL_ERR_INVALID_ARG),
+    (dict(scales=None), skl.SKL_ERR_INVALID_ARG),
+    (dict(states=np.zeros(36, dtype=np.uint16)), skl.SKL_ERR_INVALID_ARG),       # both forms at once
+    (dict(scales=np.uint16([0, 0, 0x7C00, 0, 0, 0, 0, 0])), skl.SKL_ERR_NONFINITE),
+    (dict(scales=np.uint16([0, 0, 0xBC00, 0, 0, 0, 0, 0])), skl.SKL_ERR_INVALID_ARG),
+    (dict(codes=np.uint8([0] * 17 + [0x80])), skl.SKL_ERR_INVALID_ARG),          # the nibble -8
+    (dict(codes=np.uint8([0x08] + [0] * 17)), skl.SKL_ERR_INVALID_ARG),
+    (dict(n_states=35), skl.SKL_ERR_INVALID_ARG),
+])
+def test_bad_low_bit_descriptions_are_rejected(over, status):
+    reserved = over.pop("reserved_", 0)
+    d = good_lowbit(4, **over)
+    d.reserved = reserved
+    assert status_of(d) == status
+
+
+def test_eight_bit_code_minus_128_is_rejected():
+    codes = np.zeros(36, dtype=np.uint8)
+    codes[7] = 0x80
+    assert status_of(good_lowbit(8, codes=codes)) == skl.SKL_ERR_INVALID_ARG
+    codes[7] = 0x81                                          # -127 is the end code
+    assert status_of(good_lowbit(8, codes=codes)) == skl.SKL_OK

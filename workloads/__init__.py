@@ -176,3 +176,12 @@ def small(name: str, in_features: int, out_features: int, tile_in: int, tile_out
     """Small ad-hoc layers for parity tests (configuration number 0)."""
     return Workload(name, 0, in_features, out_features, tile_in, tile_out, d, bpw,
                     layer_index=layer_index, **kw)
+
+
+def pack_nibbles(codes) -> np.ndarray:
+    """Storage format of 4-bit codes: two's-complement nibbles, element i in byte i // 2, low nibble for
+    even i (a trailing odd element leaves the high nibble of the last byte zero)."""
+    c = np.asarray(codes, dtype=np.int8).astype(np.uint8) & 0xF
+    if c.size % 2:
+        c = np.concatenate([c, np.zeros(1, dtype=np.uint8)])
+    return np.ascontiguousarray(c[0::2] | (c[1::2] << 4))

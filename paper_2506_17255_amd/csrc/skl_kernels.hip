@@ -2087,8 +2087,8 @@ __device__ __forceinline__ uint16_t key_of_code(int q, uint16_t scale_bits)
     return (uint16_t)(((h & 0x7FFFu) << 1) | (1u - (h >> 15)));
 }
 
-// row sketches: grid (channel blocks), word (r, k, c) of a block holds the keys of channels 8c .. 8c + 7;
-// writes the padded layout, the unpadded one, or both
+// row sketches: grid (channel blocks, chunks of 256 words), one thread per 16-byte word: word (r, k, c) of a
+// block holds the keys of channels 8c .. 8c + 7; writes the padded layout, the unpadded one, or both
 template <int BITS>
 __global__ __launch_bounds__(SKL_WG) void k_expand_rows(const skl_block_meta *__restrict__ bmeta, const uint32_t *__restrict__ chan,
                                                          const uint32_t *__restrict__ choff, const uint8_t *__restrict__ codes,
@@ -2096,21 +2096,28 @@ __global__ __launch_bounds__(SKL_WG) void k_expand_rows(const skl_block_meta *__
                                                          uint4 *__restrict__ padded, uint4 *__restrict__ unpadded)
 {
     const skl_block_meta bm = bmeta[blockIdx.x];
-    const uint32_t K = bm.K, nb = bm.nb, n = d * nb * K;
-    for (uint32_t idx = threadIdx.x; idx < n; idx += SKL_WG) {
-        const uint32_t k = idx % K, c = (idx / K) % nb, r = idx / (K * nb);     // k fastest: neighbouring lanes read neighbouring codes
-        uint32_t key[8];
+    const uint32_t K = bm.K, nb = bm.nb;
+    const uint32_t idx = blockIdx.y * SKL_WG + threadIdx.x;
+    if (idx >= d * nb * K) return;
+    const uint32_t k = idx % K, c = (idx / K) % nb, r = idx / (K * nb);         // k fastest: neighbouring lanes read neighbouring codes
+    uint32_t ch[8], at[8], sc[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t ch = chan[bm.chan_off + 8 * c + i];
-            key[i] = 1;                                                          // a channel slot past the end: +0.0
-            if (ch != SKL_NO_CHANNEL)
-                key[i] = key_of_code<BITS>(code_at<BITS>(codes, choff[ch] + r * K + k), scales[ch * d + r]);
-        }
-        const uint4 w = make_uint4(key[0] | key[1] << 16, key[2] | key[3] << 16, key[4] | key[5] << 16, key[6] | key[7] << 16);
-        if (padded) padded[bm.table_off16 + (size_t)(r * K + k) * bm.rs + c] = w;
-        if (unpadded) unpadded[bm.ptable_off16 + (size_t)(r * K + k) * nb + c] = w;
+    for (int i = 0; i < 8; ++i) ch[i] = chan[bm.chan_off + 8 * c + i];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t cc = ch[i] != SKL_NO_CHANNEL ? ch[i] : 0;                // every lane issues the same loads; unused ones are dropped below
+        at[i] = choff[cc] + r * K + k;
+        sc[i] = scales[cc * d + r];
     }
+    uint32_t key[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t kk = key_of_code<BITS>(code_at<BITS>(codes, at[i]), (uint16_t)sc[i]);
+        key[i] = ch[i] != SKL_NO_CHANNEL ? kk : 1u;                              // a channel slot past the end: +0.0
+    }
+    const uint4 w = make_uint4(key[0] | key[1] << 16, key[2] | key[3] << 16, key[4] | key[5] << 16, key[6] | key[7] << 16);
+    if (padded) padded[bm.table_off16 + (size_t)(r * K + k) * bm.rs + c] = w;
+    if (unpadded) unpadded[bm.ptable_off16 + (size_t)(r * K + k) * nb + c] = w;
 }
 
 // 2-D groups: keys in the caller's state order; grid (groups)
@@ -2163,11 +2170,13 @@ static skl_status_t table_source(const skl_layer *L, void *area, bool want_padde
         const skl_block_meta *bmeta = reinterpret_cast<const skl_block_meta *>(L->dev + L->off_bmeta);
         const uint32_t *chan = reinterpret_cast<const uint32_t *>(L->dev + L->off_chan);
         const uint32_t *choff = reinterpret_cast<const uint32_t *>(L->dev + L->off_choff);
+        // max_ptable_bytes: the largest block's unpadded table, rounded up to KiB: 16-byte words per block
+        const dim3 grid(L->n_blocks, (L->max_ptable_bytes / 16 + SKL_WG - 1) / SKL_WG);
         if (L->qbits == 8)
-            hipLaunchKernelGGL(k_expand_rows<8>, dim3(L->n_blocks), dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
+            hipLaunchKernelGGL(k_expand_rows<8>, grid, dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
                                L->d, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
         else
-            hipLaunchKernelGGL(k_expand_rows<4>, dim3(L->n_blocks), dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
+            hipLaunchKernelGGL(k_expand_rows<4>, grid, dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
                                L->d, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
     } else {
         uint16_t *keys = static_cast<uint16_t *>(area);

@@ -102,3 +102,29 @@ def test_70b_shaped_layer():
     ref = oracle.linear(W_hat, X[rows], x_kind="bf16", cols=cols)
     assert rel_fro(y32, ref) <= 1e-5
     assert rel_fro(ybf, round_to_bf16(ref)) <= TOL
+
+
+@pytest.mark.parametrize("bits,mult", [(4, 4.0), (8, 2.0)])
+def test_low_bit_layer(bits, mult):
+    """The up projection with low-bit states at 0.5 bit/weight: 4-bit codes with four times the states
+    (one state per eight weights, the paper's recipe, Sec. 4) and 8-bit codes with twice the states."""
+    import dataclasses
+    wl = dataclasses.replace(wk.cfg3("up"), bpw=0.5 * mult)
+    W, sk = build_sketch(wl)
+    q = oracle.quantize(sk, bits)
+    print(f"[full-size] {wl.name} {bits}-bit states: {q.bits_per_weight:.4f} bit/weight", flush=True)
+    assert 0.49 < q.bits_per_weight < 0.52
+    W_hat = oracle.query(q)
+    x = wk.gen_x(wl, 16)
+    X = wk.gen_X_bf16(wl, 2048)
+    rng = np.random.default_rng(bits)
+    rows = np.sort(rng.choice(2048, size=16, replace=False))
+    cols = np.sort(rng.choice(wl.out_features, size=128, replace=False))
+    with GpuLayer(q) as g:
+        assert np.array_equal(g.reconstruct(), W_hat)
+        assert rel_fro(g.gemv(x[:1], "f32"), oracle.linear(W_hat, x[:1])) <= 1e-5
+        y16 = g.gemv(x, "f32")
+        assert rel_fro(y16[:, cols], oracle.linear(W_hat, x, cols=cols)) <= 1e-5
+        Y = g.gemm(X, "bf16", "f32")
+        assert rel_fro(Y[np.ix_(rows, cols)], oracle.linear(W_hat, X[rows], x_kind="bf16", cols=cols)) <= 1e-5
+        assert g.info["table_bytes"] * 8 <= 0.52 * wl.in_features * wl.out_features

@@ -202,6 +202,7 @@ def main():
     ap.add_argument("--prefill-only", action="store_true", help="prefill GEMM 4096x11008 only (for profiling runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--stack-only", action="store_true", help="the 224-layer decode stack only")
+    ap.add_argument("--low-bit-only", action="store_true", help="decode with low-bit sketch states only (for profiling runs)")
     ap.add_argument("--calib-copy", action="store_true",
                     help=f"also run one device copy of {CALIB_COPY_BYTES >> 20} MiB (scale for HBM byte counters)")
     args = ap.parse_args()
@@ -254,6 +255,11 @@ def main():
         b.copy_(a)
         torch.cuda.synchronize()
 
+    if args.low_bit_only:
+        import oracle as _oracle
+        print(json.dumps({"low_bit_states": low_bit_states(torch, np, skl, wk, _oracle, GpuLayer, build_sketch, dev, stream,
+                                                           args.steps, args.warmup)}))
+        return
     if args.stack_only:
         print(json.dumps({"stack": stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream)}))
         return

@@ -182,6 +182,70 @@ def low_bit_states(torch, np, skl, wk, oracle, GpuLayer, build_sketch, dev, stre
     return out
 
 
+def paper_decompression_forms(torch, np, sk, g, dev, steps, warmup):
+    """The two decompression forms the paper compares (Sec. 3.3 and the decompression-speed-up figure of
+    Sec. 4), composed from framework operations on this machine and checked against the library's
+    reconstruction: (a) the hash operation -- per-weight index arithmetic (Eq. 3) and gathers, then the query
+    maximum (Eq. 5); (b) the matrix form of Eq. (9) -- W_g = S P^T with a cached one-hot projection matrix per
+    sketch row.  Both materialise W_hat in HBM; the layer itself is a dense GEMV on top."""
+    in_f, out_f, d = sk.in_features, sk.out_features, sk.d
+    widths = np.asarray(sk.group_width, dtype=np.int64)
+    base = np.concatenate([[0], np.cumsum(widths * d)])
+    A = [int(v) for v in sk.hash_a]
+    C = [int(v) for v in sk.hash_c]
+    o = torch.arange(out_f, dtype=torch.int64, device=dev)
+    classes = []
+    for K in sorted(set(int(k) for k in widths)):
+        chs = np.nonzero(widths == K)[0]
+        S = np.stack([sk.states[base[j]: base[j] + d * K].reshape(d, K) for j in chs]).view(np.float16)
+        P = []
+        for r in range(d):
+            idx = (((A[r] * np.arange(out_f, dtype=np.int64) + C[r]) & 0xFFFFFF) * K) >> 24
+            Pm = np.zeros((K, out_f), dtype=np.float16)
+            Pm[idx, np.arange(out_f)] = 1
+            P.append(torch.from_numpy(Pm).to(dev))
+        classes.append((K, torch.from_numpy(chs).to(dev), torch.from_numpy(S).to(dev), P))
+    W = torch.empty(in_f, out_f, dtype=torch.float16, device=dev)
+
+    def pick(best, cand):                      # magnitude maximum, clear sign bit wins a tie (Eq. 5 reading)
+        if best is None:
+            return cand
+        ab, ac = best.abs(), cand.abs()
+        return torch.where((ac > ab) | ((ac == ab) & ~torch.signbit(cand)), cand, best)
+
+    def hash_op():
+        for K, chs, S, _ in classes:
+            best = None
+            for r in range(d):
+                idx = (((A[r] * o + C[r]) & 0xFFFFFF) * K) >> 24
+                best = pick(best, S[:, r, :].index_select(1, idx))
+            W[chs] = best
+
+    def matrix_form():
+        for K, chs, S, P in classes:
+            best = None
+            for r in range(d):
+                best = pick(best, torch.matmul(S[:, r, :], P[r]))
+            W[chs] = best
+
+    ref = torch.empty(in_f, out_f, dtype=torch.float16, device=dev)
+    import paper_2506_17255_amd as skl
+    skl.sketch_linear_reconstruct(g.handle, ref.data_ptr(), 0, 0, torch.cuda.current_stream().cuda_stream)
+    out = {}
+    for name, fn in (("hash_operation", hash_op), ("matrix_form", matrix_form)):
+        W.zero_()
+        fn()
+        torch.cuda.synchronize()
+        same = bool(torch.equal(W, ref))          # as values: the one-hot product turns a state of -0.0 into +0.0
+        sec, _ = time_launches(torch, fn, max(steps // 10, 5), 2)
+        out[name] = {"decompress_us": sec * 1e6, "equals_library_reconstruction": same}
+    out["hash_over_matrix"] = out["hash_operation"]["decompress_us"] / out["matrix_form"]["decompress_us"]
+    out["note"] = ("framework-level forms of the paper's two decompression operators on this machine; in both, the "
+                   "element-wise magnitude maximum over the d rows dominates, so their ratio says little about the "
+                   "paper's 14.9x (unstated hardware); add the dense GEMV to either for a decode step")
+    return out
+
+
 def measured_traffic(name):
     """HBM bytes per launch of the dominant kernel from the committed counter
     summary (two rocprofv3 --pmc runs, scaled by a copy of known size)."""
@@ -348,6 +412,11 @@ def main():
             "note": "decompress -> compute -> release per layer as in the paper's inference flow; 90 MB of weights "
                     "written to HBM and read back per call"}
         del Wm
+        forms = paper_decompression_forms(torch, np, sk, g, dev, args.steps, args.warmup)
+        for k in ("hash_operation", "matrix_form"):
+            forms[k]["decode_batch1_us"] = forms[k]["decompress_us"] + s_mm * 1e6
+            forms[k]["fused_speedup"] = forms[k]["decode_batch1_us"] / (sec * 1e6)
+        result["paper_decompression_forms"] = forms
         # prefill GEMM, 2048 tokens (uniform widths, 0.5 bit/weight)
         result["prefill_2048_tokens"] = {f"4096x{o}": prefill(o, max(args.steps // 10, 5), 3) for o in (4096, 11008)}
         result["stack"] = stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream)

@@ -191,6 +191,21 @@ SKL_API skl_status_t sketch_linear_prefill_split(uint32_t out_features, uint32_t
                                          uint32_t *segments, uint64_t capacity, uint64_t *n_segments,
                                          uint32_t *shape);
 
+/* Sketch construction on the device (Sec. 3.1, Eq. 4: a state keeps the
+ * weight of smallest magnitude that maps to it, the first one in address order
+ * among equals; Sec. 3.3, Eq. 8 and Alg. 1 compute the same states).  Builds
+ * the binary16 states of the weights W_dev (DEVICE, [in_features][out_features]
+ * binary16, row major, finite) for the geometry, hash parameters and widths
+ * of `desc` (its states / codes / scales fields are ignored; n_states must be
+ * d * sum(group_width)) and writes them to states_dev (DEVICE, [n_states], the
+ * order `states` has in the description); states no weight reaches are +0.0.
+ * Offline step: the call synchronises hip_stream once before it returns.
+ * The result is independent of timing.  Workspace (DEVICE, 256-byte aligned):
+ * sketch_linear_build_workspace_bytes. */
+SKL_API skl_status_t sketch_linear_build_workspace_bytes(const skl_desc_t *desc, uint64_t *bytes);
+SKL_API skl_status_t sketch_linear_build_states(const skl_desc_t *desc, const uint16_t *W_dev, uint16_t *states_dev,
+                                        void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
 /* Diagnostic: write W_hat (Eq. 5) as binary16 bit patterns to
  * W_hat_dev (DEVICE, [in_features][out_features], row major).  The only call
  * that materialises the weights.  The workspace (op = 2) is needed only by

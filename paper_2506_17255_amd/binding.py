@@ -30,6 +30,7 @@ STATUS_NAMES = {0: "SKL_OK", 1: "SKL_ERR_INVALID_ARG", 2: "SKL_ERR_UNSUPPORTED",
 EXPORTS = ("sketch_linear_device_bytes", "sketch_linear_create", "sketch_linear_info",
            "sketch_linear_workspace_bytes", "sketch_linear_gemv", "sketch_linear_gemm",
            "sketch_linear_reconstruct", "sketch_linear_gemv_partials", "sketch_linear_prefill_split",
+           "sketch_linear_build_workspace_bytes", "sketch_linear_build_states",
            "sketch_linear_destroy", "sketch_linear_last_error")
 
 
@@ -88,11 +89,13 @@ def load_library(path: str | None = None):
     L.sketch_linear_gemv_partials.argtypes = [vp, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_prefill_split.argtypes = [u32, u32, u32, ctypes.POINTER(u32), u64, ctypes.POINTER(u64),
                                               ctypes.POINTER(u32)]
+    L.sketch_linear_build_workspace_bytes.argtypes = [ctypes.POINTER(skl_desc_t), ctypes.POINTER(u64)]
+    L.sketch_linear_build_states.argtypes = [ctypes.POINTER(skl_desc_t), vp, vp, vp, u64, vp]
     L.sketch_linear_destroy.argtypes = [vp]
     L.sketch_linear_destroy.restype = None
     L.sketch_linear_last_error.argtypes = []
     L.sketch_linear_last_error.restype = ctypes.c_char_p
-    for n in EXPORTS[:9]:
+    for n in EXPORTS[:11]:
         getattr(L, n).restype = ctypes.c_int
     _lib = L
     return L
@@ -206,6 +209,18 @@ def sketch_linear_prefill_split(out_features: int, n_blocks: int, tokens: int):
     _check(L.sketch_linear_prefill_split(out_features, n_blocks, tokens, buf, n.value, ctypes.byref(n), shape))
     segs = [tuple(buf[8 * i:8 * i + 8]) for i in range(n.value)]
     return segs, tuple(shape)
+
+
+def sketch_linear_build_workspace_bytes(desc: skl_desc_t) -> int:
+    n = ctypes.c_uint64(0)
+    _check(load_library().sketch_linear_build_workspace_bytes(ctypes.byref(desc), ctypes.byref(n)))
+    return n.value
+
+
+def sketch_linear_build_states(desc: skl_desc_t, W_dev: int, states_dev: int, workspace: int, workspace_bytes: int,
+                               hip_stream: int = 0) -> None:
+    _check(load_library().sketch_linear_build_states(ctypes.byref(desc), W_dev, states_dev, workspace, workspace_bytes,
+                                                     hip_stream))
 
 
 def sketch_linear_reconstruct(layer: int, W_hat_dev: int, workspace: int = 0, workspace_bytes: int = 0,

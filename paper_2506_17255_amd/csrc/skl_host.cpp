@@ -54,7 +54,8 @@ static int code_at(const skl_desc_t *d, uint64_t i)
     return nib >= 8 ? nib - 16 : nib;
 }
 
-static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out)
+// geometry_only: the description of a sketch still to be built (no states, codes or scales yet)
+static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out, bool geometry_only = false)
 {
     if (d->in_features == 0 || d->out_features == 0)
         FAIL(SKL_ERR_INVALID_ARG, "in_features and out_features must be positive");
@@ -74,9 +75,11 @@ static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out)
     const bool low_bit = d->state_bits == 8 || d->state_bits == 4;
     if (!d->hash_a || !d->hash_c || !d->group_width)
         FAIL(SKL_ERR_INVALID_ARG, "hash_a, hash_c and group_width must not be NULL");
-    if (!low_bit && !d->states) FAIL(SKL_ERR_INVALID_ARG, "states must not be NULL");
-    if (low_bit && (!d->codes || !d->scales || d->states))
-        FAIL(SKL_ERR_INVALID_ARG, "low-bit states need codes and scales, and states must be NULL");
+    if (!geometry_only) {
+        if (!low_bit && !d->states) FAIL(SKL_ERR_INVALID_ARG, "states must not be NULL");
+        if (low_bit && (!d->codes || !d->scales || d->states))
+            FAIL(SKL_ERR_INVALID_ARG, "low-bit states need codes and scales, and states must be NULL");
+    }
     for (uint32_t r = 0; r < d->d; ++r)
         if (d->hash_a[r] >= (1u << 24) || d->hash_c[r] >= (1u << 24))
             FAIL(SKL_ERR_INVALID_ARG, "hash parameters of row %u are not below 2^24", r);
@@ -92,6 +95,10 @@ static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out)
         FAIL(SKL_ERR_INVALID_ARG, "n_states = %llu but d * sum(group_width) = %llu",
              (unsigned long long)d->n_states, (unsigned long long)(sum * d->d));
     if (d->n_states >= (1ull << 32)) FAIL(SKL_ERR_UNSUPPORTED, "more than 2^32 states in one layer");
+    if (geometry_only) {
+        *n_groups_out = n_groups;
+        return SKL_OK;
+    }
     if (!low_bit) {
         for (uint64_t i = 0; i < d->n_states; ++i)
             if ((d->states[i] & 0x7C00u) == 0x7C00u)
@@ -599,6 +606,51 @@ skl_status_t sketch_linear_gemm(const skl_layer_t *L, const void *X, skl_dtype_t
                                skl_gemm_workspace_bytes(L, tokens));
     if (st != SKL_OK) return st;
     return skl_launch_gemm(L, X, x_dt, ldx, Y, y_dt, ldy, tokens, ws, stream);
+}
+
+// ---- sketch construction on the device ------------------------------------
+static uint64_t build_workspace_bytes(const skl_desc_t *d, uint64_t n_groups)
+{
+    // 64-bit keys of all states, then the state offset and the width of every group
+    return align_up(d->n_states * 8, 256) + align_up((n_groups + 1) * 8, 256) + align_up(n_groups * 4, 256);
+}
+
+skl_status_t sketch_linear_build_workspace_bytes(const skl_desc_t *user, uint64_t *bytes)
+{
+    if (!bytes) FAIL(SKL_ERR_INVALID_ARG, "bytes is NULL");
+    skl_desc_t d;
+    skl_status_t st = normalize_desc(user, &d);
+    if (st != SKL_OK) return st;
+    uint64_t n_groups = 0;
+    st = validate_desc(&d, &n_groups, true);
+    if (st != SKL_OK) return st;
+    *bytes = build_workspace_bytes(&d, n_groups);
+    return SKL_OK;
+}
+
+skl_status_t sketch_linear_build_states(const skl_desc_t *user, const uint16_t *W_dev, uint16_t *states_dev, void *ws,
+                                        uint64_t ws_bytes, void *stream_)
+{
+    skl_desc_t d;
+    skl_status_t st = normalize_desc(user, &d);
+    if (st != SKL_OK) return st;
+    uint64_t n_groups = 0;
+    st = validate_desc(&d, &n_groups, true);
+    if (st != SKL_OK) return st;
+    if (!W_dev || !states_dev || !ws) FAIL(SKL_ERR_INVALID_ARG, "W_dev, states_dev or workspace is NULL");
+    if ((uintptr_t)W_dev % 16 || (uintptr_t)states_dev % 2 || (uintptr_t)ws % 256)
+        FAIL(SKL_ERR_INVALID_ARG, "W_dev must be 16-byte, states_dev 2-byte, workspace 256-byte aligned");
+    const uint64_t need = build_workspace_bytes(&d, n_groups);
+    if (ws_bytes < need)
+        FAIL(SKL_ERR_BUFFER_TOO_SMALL, "workspace holds %llu bytes, %llu needed", (unsigned long long)ws_bytes,
+             (unsigned long long)need);
+    const uint64_t w_bytes = (uint64_t)d.in_features * d.out_features * 2;
+    if (overlap(ws, need, W_dev, w_bytes) || overlap(ws, need, states_dev, d.n_states * 2) ||
+        overlap(W_dev, w_bytes, states_dev, d.n_states * 2))
+        FAIL(SKL_ERR_INVALID_ARG, "W_dev, states_dev and workspace overlap");
+    std::vector<uint64_t> base(n_groups + 1, 0);
+    for (uint64_t g = 0; g < n_groups; ++g) base[g + 1] = base[g] + (uint64_t)d.d * d.group_width[g];
+    return skl_launch_build(&d, n_groups, base.data(), W_dev, states_dev, ws, stream_);
 }
 
 skl_status_t sketch_linear_prefill_split(uint32_t out_features, uint32_t n_blocks, uint32_t tokens, uint32_t *segments,

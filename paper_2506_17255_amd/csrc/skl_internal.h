@@ -172,4 +172,7 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X, skl_dtype_t x_dt
                              void *stream);
 uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch);
 uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens);
+// sketch construction: group_base holds n_groups + 1 state offsets (host); synchronises the stream once
+skl_status_t skl_launch_build(const skl_desc_t *d, uint64_t n_groups, const uint64_t *group_base, const uint16_t *W,
+                              uint16_t *states, void *ws, void *stream);
 uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, uint32_t *segs, uint64_t cap, uint32_t *shape);

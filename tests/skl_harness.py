@@ -152,3 +152,22 @@ def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """fp64 -> float32 -> bfloat16 (nearest even) -> float64, to compare bf16
     outputs with the oracle rounded the same way."""
     return wk.bf16_bits_to_f32(wk.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))).astype(np.float64)
+
+
+def build_states_on_gpu(W: np.ndarray, tile_in, tile_out, d, hash_a, hash_c, widths) -> np.ndarray:
+    """Sketch states of W ([in][out] binary16) built by the library on cuda:0 (uint16 bit patterns)."""
+    t = torch_mod()
+    dev = t.device("cuda:0")
+    in_f, out_f = W.shape
+    wd = np.ascontiguousarray(widths, dtype=np.uint32).ravel()
+    n_states = int(wd.sum()) * d
+    desc = skl.make_desc(in_f, out_f, tile_in, tile_out, d, np.ascontiguousarray(hash_a, dtype=np.uint32),
+                         np.ascontiguousarray(hash_c, dtype=np.uint32), wd, None, n_states=n_states)
+    Wd = t.from_numpy(np.ascontiguousarray(W).view(np.int16)).to(dev)
+    states = t.full((n_states,), 0x7E00, dtype=t.int16, device=dev)
+    need = skl.sketch_linear_build_workspace_bytes(desc)
+    ws = t.empty(need + 256, dtype=t.uint8, device=dev)
+    off = (-ws.data_ptr()) % 256
+    skl.sketch_linear_build_states(desc, Wd.data_ptr(), states.data_ptr(), ws.data_ptr() + off, need,
+                                   t.cuda.current_stream().cuda_stream)
+    return states.cpu().numpy().view(np.uint16)

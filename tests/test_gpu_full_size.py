@@ -128,3 +128,12 @@ def test_low_bit_layer(bits, mult):
         Y = g.gemm(X, "bf16", "f32")
         assert rel_fro(Y[np.ix_(rows, cols)], oracle.linear(W_hat, X[rows], x_kind="bf16", cols=cols)) <= 1e-5
         assert g.info["table_bytes"] * 8 <= 0.52 * wl.in_features * wl.out_features
+
+
+def test_sketch_construction_of_the_up_projection():
+    """All 45 M weights of the benchmark layer through the device-side update (Eq. 4)."""
+    from skl_harness import build_states_on_gpu
+    wl = wk.cfg3("up")
+    W, sk = build_sketch(wl)
+    got = build_states_on_gpu(W, sk.tile_in, sk.tile_out, sk.d, sk.hash_a, sk.hash_c, sk.group_width)
+    assert np.array_equal(got, sk.states)

@@ -278,6 +278,35 @@ def test_low_bit_workspace_holds_the_expanded_tables():
         assert lib.sketch_linear_reconstruct(g.handle, out.data_ptr(), small.data_ptr(), 16, None) == skl.SKL_ERR_BUFFER_TOO_SMALL
 
 
+# ------------------------------------------------- sketch construction
+@pytest.mark.parametrize("name", SMALL)
+def test_states_built_on_the_gpu_equal_the_oracle_update(name):
+    """Eq. 4 on the device: bit-identical states to the oracle's sequential update stream."""
+    from skl_harness import build_states_on_gpu
+    W, sk = small_case(name)
+    got = build_states_on_gpu(W, sk.tile_in, sk.tile_out, sk.d, sk.hash_a, sk.hash_c, sk.group_width)
+    assert np.array_equal(got, sk.states), (name, int(np.sum(got != sk.states)))
+
+
+@pytest.mark.parametrize("geom", [(48, 96, 1, 96, 3, 7), (32, 64, 8, 32, 4, 5), (40, 40, 40, 40, 2, 300)])
+def test_states_built_on_the_gpu_with_many_magnitude_ties(geom):
+    """Weights from a handful of values of both signs: almost every bucket sees equal magnitudes, so the
+    first-arrival rule of Eq. 4 (and the sign the state keeps) decides most states."""
+    from skl_harness import build_states_on_gpu
+    in_f, out_f, tj, to, d, K = geom
+    rng = np.random.default_rng(in_f * 1000 + out_f)
+    W = rng.choice(np.array([-2.0, -1.0, -0.5, 0.0, 0.5, 1.0, 2.0], dtype=np.float16), size=(in_f, out_f))
+    W[rng.random((in_f, out_f)) < 0.05] = np.float16(-0.0)
+    A = rng.integers(1, 1 << 24, d) | 1
+    C = rng.integers(0, 1 << 24, d)
+    widths = np.full((in_f // tj) * (out_f // to), K, dtype=np.uint32)
+    sk = oracle.update(W, tj, to, d, A, C, widths)
+    got = build_states_on_gpu(W, tj, to, d, A, C, widths)
+    assert np.array_equal(got, sk.states)
+    twice = build_states_on_gpu(W, tj, to, d, A, C, widths)
+    assert np.array_equal(got, twice)                  # independent of the order in which threads arrive
+
+
 # ----------------------------------------------------------- error paths
 def test_call_time_validation():
     import paper_2506_17255_amd as skl

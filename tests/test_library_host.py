@@ -192,3 +192,19 @@ def test_eight_bit_code_minus_128_is_rejected():
     assert status_of(good_lowbit(8, codes=codes)) == skl.SKL_ERR_INVALID_ARG
     codes[7] = 0x81                                          # -127 is the end code
     assert status_of(good_lowbit(8, codes=codes)) == skl.SKL_OK
+
+
+# ------------------------------------------------------ sketch construction
+def test_build_workspace_and_argument_checks():
+    geom = good(states=None, n_states=36)                    # a description without states: enough for construction
+    need = skl.sketch_linear_build_workspace_bytes(geom)
+    assert need >= 36 * 8 + 5 * 8 + 4 * 4
+    L = skl.load_library()
+    n = ctypes.c_uint64(0)
+    assert L.sketch_linear_build_workspace_bytes(None, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_build_workspace_bytes(ctypes.byref(geom), None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_build_states(ctypes.byref(geom), None, None, None, 0, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_build_states(ctypes.byref(geom), 4096, 8192, 256 * 64, 8, None) == skl.SKL_ERR_BUFFER_TOO_SMALL
+    assert L.sketch_linear_build_states(ctypes.byref(geom), 4096 + 2, 8192, 256 * 64, need, None) == skl.SKL_ERR_INVALID_ARG
+    bad = good(states=None, n_states=35)
+    assert L.sketch_linear_build_workspace_bytes(ctypes.byref(bad), ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG

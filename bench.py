@@ -141,6 +141,37 @@ def stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream, n_bloc
         graph_us += e0.elapsed_time(e1) * 1e3 / passes
         graph_ok = graph_ok and all(torch.equal(yout[f], eager_out[f]) for f in yout)
     del graph
+    # the layers of a block that share their input (q, k, v and gate, up) through sketch_linear_gemv_group:
+    # one pair of launches per group; every kind of layer gets its own output buffer here
+    kinds = [wl.name.split("_")[-1] for wl in shapes]
+    yk = {k: torch.empty(1, wl.out_features, dtype=torch.float16, device=dev) for k, wl in zip(kinds, shapes)}
+    yr = {k: torch.empty_like(v) for k, v in yk.items()}
+    for i, kind in enumerate(kinds):                          # reference: the last block, layer by layer
+        a = calls[(n_blocks - 1) * len(kinds) + i]
+        skl.sketch_linear_gemv(*(a[:4] + (yr[kind].data_ptr(),) + a[5:]))
+    groups = []
+    for blk in layers:
+        h = dict(zip(kinds, blk))
+        x4, x11 = xin[shapes[0].in_features].data_ptr(), xin[shapes[-1].in_features].data_ptr()
+        groups.append([([h[k].handle for k in ("q", "k", "v")], x4, [yk[k].data_ptr() for k in ("q", "k", "v")]),
+                       ([h["o"].handle], x4, [yk["o"].data_ptr()]),
+                       ([h[k].handle for k in ("gate", "up")], x4, [yk[k].data_ptr() for k in ("gate", "up")]),
+                       ([h["down"].handle], x11, [yk["down"].data_ptr()])])
+    need_g = max(skl.sketch_linear_gemv_group_workspace_bytes(hs) for hs, _, _ in groups[0])
+    ws_g = torch.empty(need_g, dtype=torch.uint8, device=dev)
+    def grouped_pass():
+        for blk in groups:
+            for hs, xp, ys in blk:
+                skl.sketch_linear_gemv_group(hs, xp, skl.SKL_F16, ys, skl.SKL_F16, ws_g.data_ptr(), ws_g.numel(), stream)
+    grouped_pass()
+    torch.cuda.synchronize()
+    grouped_ok = all(torch.equal(yk[k], yr[k]) for k in yk)
+    e0.record()
+    for _ in range(passes):
+        grouped_pass()
+    e1.record()
+    torch.cuda.synchronize()
+    grouped_us = e0.elapsed_time(e1) * 1e3 / passes
     names = [wl.name.split("_")[-1] for wl in shapes]
     by_name = {nm: float(per_layer[i::len(shapes)].mean()) for i, nm in enumerate(names)}
     weights = sum(wl.n_weights for wl in shapes) * n_blocks
@@ -151,6 +182,7 @@ def stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream, n_bloc
             "us_per_layer_by_kind": by_name, "weights_per_s": weights / (total / passes * 1e-6),
             "us_per_pass_without_events": plain_us, "us_per_pass_hip_graph": graph_us,
             "hip_graph_replays_match_eager": bool(graph_ok),
+            "us_per_pass_grouped_qkv_gateup": grouped_us, "grouped_outputs_match": bool(grouped_ok),
             "note": "224 distinct device copies (7 sketches x 32 blocks), tables not cache-resident; "
                     "event recording between launches adds to each figure"}
 

@@ -153,6 +153,20 @@ SKL_API skl_status_t sketch_linear_gemv(const skl_layer_t *layer, const void *x,
                                 uint32_t batch, void *workspace, uint64_t workspace_bytes,
                                 void *hip_stream);
 
+/* Decode at batch 1 through 1..4 layers that read the same activations (the
+ * q/k/v or the gate/up projections of a block; Sec. 2.1, Eq. 1/2) in one pair
+ * of launches:  ys[i][o] = sum_j x[j] * W_hat_i[j][o].  The layers must be
+ * row-sketch layers with binary16 states and the same in_features,
+ * out_features and d (SKL_ERR_UNSUPPORTED otherwise); x DEVICE binary16
+ * [in_features]; ys HOST array of n_layers DEVICE pointers, each
+ * [out_features] of y_dtype (binary16 or float32), not overlapping.  Results
+ * are bit-identical to n_layers calls of sketch_linear_gemv. */
+SKL_API skl_status_t sketch_linear_gemv_group_workspace_bytes(const skl_layer_t *const *layers, uint32_t n_layers,
+                                                      uint64_t *bytes);
+SKL_API skl_status_t sketch_linear_gemv_group(const skl_layer_t *const *layers, uint32_t n_layers, const void *x,
+                                      skl_dtype_t x_dtype, void *const *ys, skl_dtype_t y_dtype,
+                                      void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
 /* Diagnostic: only the first of the two kernels behind sketch_linear_gemv
  * (query, Eq. 5, fused with the products; one partial sum per output and
  * block group left in workspace), without the reduction that produces y.

@@ -608,6 +608,37 @@ skl_status_t sketch_linear_gemm(const skl_layer_t *L, const void *X, skl_dtype_t
     return skl_launch_gemm(L, X, x_dt, ldx, Y, y_dt, ldy, tokens, ws, stream);
 }
 
+// ---- several layers on the same activations, one launch --------------------
+skl_status_t sketch_linear_gemv_group_workspace_bytes(const skl_layer_t *const *layers, uint32_t n_layers, uint64_t *bytes)
+{
+    if (!layers || !bytes) FAIL(SKL_ERR_INVALID_ARG, "layers or bytes is NULL");
+    if (n_layers < 1 || n_layers > 4) FAIL(SKL_ERR_INVALID_ARG, "n_layers = %u, must be 1..4", n_layers);
+    for (uint32_t i = 0; i < n_layers; ++i)
+        if (!layers[i]) FAIL(SKL_ERR_INVALID_ARG, "layers[%u] is NULL", i);
+    *bytes = skl_gemv_group_workspace_bytes(layers, n_layers);
+    return SKL_OK;
+}
+
+skl_status_t sketch_linear_gemv_group(const skl_layer_t *const *layers, uint32_t n_layers, const void *x, skl_dtype_t x_dt,
+                                      void *const *ys, skl_dtype_t y_dt, void *ws, uint64_t ws_bytes, void *stream)
+{
+    if (!layers || !ys) FAIL(SKL_ERR_INVALID_ARG, "layers or ys is NULL");
+    if (n_layers < 1 || n_layers > 4) FAIL(SKL_ERR_INVALID_ARG, "n_layers = %u, must be 1..4", n_layers);
+    for (uint32_t i = 0; i < n_layers; ++i)
+        if (!layers[i] || !ys[i]) FAIL(SKL_ERR_INVALID_ARG, "layers[%u] or ys[%u] is NULL", i, i);
+    if (x_dt != SKL_F16) FAIL(SKL_ERR_UNSUPPORTED, "gemv activations must be binary16");
+    if (y_dt != SKL_F16 && y_dt != SKL_F32) FAIL(SKL_ERR_UNSUPPORTED, "gemv output must be binary16 or float32");
+    const uint64_t need = skl_gemv_group_workspace_bytes(layers, n_layers);
+    for (uint32_t i = 0; i < n_layers; ++i) {
+        skl_status_t st = check_io(layers[i], x, layers[i]->in, 2, ys[i], layers[i]->out, dtype_size(y_dt), 1, ws, ws_bytes, need);
+        if (st != SKL_OK) return st;
+        for (uint32_t k = 0; k < i; ++k)
+            if (overlap(ys[i], (uint64_t)layers[i]->out * dtype_size(y_dt), ys[k], (uint64_t)layers[k]->out * dtype_size(y_dt)))
+                FAIL(SKL_ERR_INVALID_ARG, "outputs %u and %u overlap", k, i);
+    }
+    return skl_launch_gemv_group(layers, n_layers, x, ys, y_dt, ws, stream);
+}
+
 // ---- sketch construction on the device ------------------------------------
 static uint64_t build_workspace_bytes(const skl_desc_t *d, uint64_t n_groups)
 {

@@ -425,8 +425,7 @@ __device__ __forceinline__ void g1_run(const StreamArgs &p, const StreamCtx &c, 
 }
 
 template <int D, int MAXW>
-__global__ __launch_bounds__(MAXW * 64) void k_row_gemv1(StreamArgs p, const uint16_t *__restrict__ x,
-                                                          float *__restrict__ partial)
+__device__ __forceinline__ void gemv1_body(const StreamArgs &p, const uint16_t *__restrict__ x, float *__restrict__ partial)
 {
     const StreamCtx c = stream_ctx(p);
     if (!c.live) return;
@@ -475,6 +474,29 @@ __global__ __launch_bounds__(MAXW * 64) void k_row_gemv1(StreamArgs p, const uin
         const uint32_t o = w.o_base + w.lane;
         if (o < c.o_hi) __builtin_nontemporal_store(w.yw[w.lane], &partial[(size_t)c.g * p.r.out + o]);
     }
+}
+
+template <int D, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void k_row_gemv1(StreamArgs p, const uint16_t *__restrict__ x,
+                                                          float *__restrict__ partial)
+{
+    gemv1_body<D, MAXW>(p, x, partial);
+}
+
+// Several layers that read the same activations in one launch (q/k/v, gate/up): grid row y runs layer y.
+// The layers' workgroups follow each other on the CUs without a kernel boundary, so the start-up and drain
+// of one layer overlap the main loop of another and two or three launches become one.
+#define SKL_MAX_GROUP_LAYERS 4
+struct GroupArgs {
+    StreamArgs a[SKL_MAX_GROUP_LAYERS];
+    uint64_t partial_stride;        // floats between the partial sums of consecutive layers
+};
+
+template <int D, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void k_row_gemv1_group(GroupArgs m, const uint16_t *__restrict__ x,
+                                                                float *__restrict__ partial)
+{
+    gemv1_body<D, MAXW>(m.a[blockIdx.y], x, partial + blockIdx.y * m.partial_stride);
 }
 
 // ---- decode GEMV, batch 2..16: the reconstructed weights feed the matrix
@@ -2020,9 +2042,8 @@ __global__ __launch_bounds__(SKL_WG) void k_tile_gemm(TileArgs p, const uint16_t
 // row; its 16 lane rows each sum every 16th partial, then the 16 slices are
 // added in a fixed order, so the result is the same on every run.
 #define RED_O 64
-__global__ __launch_bounds__(SKL_WG) void k_reduce_partials(const float *__restrict__ partial, uint32_t n_units,
-                                                             uint32_t batch, uint32_t out, void *__restrict__ y,
-                                                             uint32_t y_dt, uint32_t ldy)
+__device__ __forceinline__ void reduce_body(const float *__restrict__ partial, uint32_t n_units, uint32_t batch, uint32_t out,
+                                            void *__restrict__ y, uint32_t y_dt, uint32_t ldy)
 {
     __shared__ float4 red[16][16];
     const uint32_t oq = threadIdx.x & 15, slice = threadIdx.x >> 4;
@@ -2059,6 +2080,26 @@ __global__ __launch_bounds__(SKL_WG) void k_reduce_partials(const float *__restr
         if (o + 2 < out) store_out(y, y_dt, base + 2, t.z);
         if (o + 3 < out) store_out(y, y_dt, base + 3, t.w);
     }
+}
+
+__global__ __launch_bounds__(SKL_WG) void k_reduce_partials(const float *__restrict__ partial, uint32_t n_units,
+                                                             uint32_t batch, uint32_t out, void *__restrict__ y,
+                                                             uint32_t y_dt, uint32_t ldy)
+{
+    reduce_body(partial, n_units, batch, out, y, y_dt, ldy);
+}
+
+// the reductions of a group of layers (batch 1): grid (ceil(out / 64), 1, layers)
+struct GroupReduceArgs {
+    void *y[SKL_MAX_GROUP_LAYERS];
+    uint32_t n_units[SKL_MAX_GROUP_LAYERS];
+    uint64_t partial_stride;
+};
+
+__global__ __launch_bounds__(SKL_WG) void k_reduce_partials_group(const float *__restrict__ partial, GroupReduceArgs g,
+                                                                   uint32_t out, uint32_t y_dt)
+{
+    reduce_body(partial + blockIdx.z * g.partial_stride, g.n_units[blockIdx.z], 1, out, g.y[blockIdx.z], y_dt, out);
 }
 
 // ========================================================================
@@ -2567,6 +2608,76 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
     hipLaunchKernelGGL(k_reduce_partials, dim3((L->out + RED_O - 1) / RED_O, batch), dim3(SKL_WG), 0, stream, partial,
                        L->n_units, batch, L->out, y, (uint32_t)y_dt, ldy);
     return check_launch("gemv reduction");
+}
+
+// ---- batch-1 decode of up to four layers that share their activations --------
+static bool group_layer_ok(const skl_layer *L, const skl_layer *first)
+{
+    return L->path == 1 && !L->qbits && L->in == first->in && L->out == first->out && L->d == first->d;
+}
+
+uint64_t skl_gemv_group_workspace_bytes(const skl_layer *const *layers, uint32_t n)
+{
+    uint64_t stride = 0;
+    for (uint32_t i = 0; i < n; ++i) stride = std::max(stride, round256(gemv_partial_bytes(layers[i], 1)));
+    return stride * n;
+}
+
+skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, const void *x_, void *const *ys, skl_dtype_t y_dt,
+                                   void *ws, void *stream_)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const skl_layer *F = layers[0];
+    for (uint32_t i = 0; i < n; ++i)
+        if (!group_layer_ok(layers[i], F)) {
+            skl_set_error("layer %u of the group is not a row-sketch layer with binary16 states of the first layer's shape", i);
+            return SKL_ERR_UNSUPPORTED;
+        }
+    GroupArgs m;
+    GroupReduceArgs gr;
+    m.partial_stride = gr.partial_stride = skl_gemv_group_workspace_bytes(layers, n) / n / sizeof(float);
+    uint32_t grid_x = 0, waves = 2;
+    size_t lds = 0;
+    for (uint32_t i = 0; i < SKL_MAX_GROUP_LAYERS; ++i) {
+        const skl_layer *L = layers[i < n ? i : 0];            // unused slots repeat the first layer
+        TableSrc src;
+        table_source(L, nullptr, false, true, stream, &src);   // binary16 states: resident tables, nothing is enqueued
+        StreamArgs &a = m.a[i];
+        a.r = make_row_args(L, src);
+        a.r.tables = src.ptables;
+        a.ginfo = reinterpret_cast<const skl_group_info *>(L->dev + L->off_ginfo);
+        a.n_wunits = L->n_wunits; a.n_sseg = L->n_sseg; a.n_bg = L->n_bg;
+        a.buf_words = L->max_ptable_bytes / 16;
+        a.two_bufs = L->two_pbufs;
+        gr.y[i] = ys[i < n ? i : 0];
+        gr.n_units[i] = L->n_units;
+        if (i >= n) continue;
+        grid_x = std::max(grid_x, 8 * ((L->n_bg + 7) / 8) * L->n_sseg);
+        waves = std::max(waves, (L->n_wunits + L->n_sseg - 1) / L->n_sseg);
+        lds = std::max(lds, (L->two_pbufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_ptable_bytes) + SKL_G1_FIXED_LDS(L->d) +
+                                (size_t)(L->max_group_chan + 64) * sizeof(uint16_t));
+    }
+    const uint16_t *x = static_cast<const uint16_t *>(x_);
+    float *partial = static_cast<float *>(ws);
+    skl_status_t st = SKL_OK;
+    const dim3 grid(grid_x, n);
+    if (waves <= 12) {
+        DISPATCH_D(F->d, {
+            st = allow_lds(k_row_gemv1_group<D, 12>, lds);
+            if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemv1_group<D, 12>), grid, dim3(64 * waves), lds, stream, m, x, partial);
+        })
+    } else {
+        DISPATCH_D(F->d, {
+            st = allow_lds(k_row_gemv1_group<D, 16>, lds);
+            if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemv1_group<D, 16>), grid, dim3(64 * waves), lds, stream, m, x, partial);
+        })
+    }
+    if (st != SKL_OK) return st;
+    st = check_launch("grouped gemv");
+    if (st != SKL_OK) return st;
+    hipLaunchKernelGGL(k_reduce_partials_group, dim3((F->out + RED_O - 1) / RED_O, 1, n), dim3(SKL_WG), 0, stream, partial, gr,
+                       F->out, (uint32_t)y_dt);
+    return check_launch("grouped gemv reduction");
 }
 
 // activation re-ordering for the second and third prefill kernels: rows staged in LDS when four

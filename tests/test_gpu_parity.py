@@ -278,6 +278,78 @@ def test_low_bit_workspace_holds_the_expanded_tables():
         assert lib.sketch_linear_reconstruct(g.handle, out.data_ptr(), small.data_ptr(), 16, None) == skl.SKL_ERR_BUFFER_TOO_SMALL
 
 
+# ------------------------------------------------------- grouped decode
+@pytest.mark.parametrize("n_layers", [1, 2, 3, 4])
+def test_grouped_decode_equals_separate_calls(n_layers):
+    """q/k/v-style groups: layers of one shape with their own sketches (different widths, so different plans)
+    on the same activations, one launch; bit-identical to one sketch_linear_gemv per layer and within the
+    floating-point bar of the oracle."""
+    import paper_2506_17255_amd as skl
+    in_f, out_f, d = 192, 520, 4
+    rng = np.random.default_rng(40 + n_layers)
+    x = rng.standard_normal((1, in_f)).astype(np.float16)
+    cases = []
+    for i in range(n_layers):
+        widths = rng.choice([11, 40, 100, 300], size=in_f, p=[0.7, 0.15, 0.1, 0.05])
+        cases.append(custom_layer(f"group{i}", in_f, out_f, 1, out_f, d, widths, 500 + 10 * n_layers + i))
+    layers = [GpuLayer(sk) for _, sk in cases]
+    try:
+        g0 = layers[0]
+        t = g0.torch
+        xd = t.from_numpy(x.view(np.int16)).to(g0.dev)
+        for ydt, tdt in ((skl.SKL_F32, t.float32), (skl.SKL_F16, t.float16)):
+            ys = [t.full((out_f,), float("nan"), dtype=tdt, device=g0.dev) for _ in layers]
+            need = skl.sketch_linear_gemv_group_workspace_bytes([g.handle for g in layers])
+            ws = t.empty(max(need, 16), dtype=t.uint8, device=g0.dev)
+            skl.sketch_linear_gemv_group([g.handle for g in layers], xd.data_ptr(), skl.SKL_F16, [y.data_ptr() for y in ys],
+                                         ydt, ws.data_ptr(), ws.numel(), g0.stream())
+            t.cuda.synchronize()
+            for g, y, (W, sk) in zip(layers, ys, cases):
+                alone = g.gemv(x, "f32" if ydt == skl.SKL_F32 else "f16")
+                assert np.array_equal(y.cpu().numpy(), alone[0])
+                ref = oracle.linear(oracle.query(sk), x)
+                assert rel_fro(y.float().cpu().numpy()[None, :], ref) <= (1e-5 if ydt == skl.SKL_F32 else TOL)
+    finally:
+        for g in layers:
+            g.close()
+
+
+def test_grouped_decode_rejects_mixed_shapes_and_bad_arguments():
+    import ctypes
+    import paper_2506_17255_amd as skl
+    _, a = custom_layer("ga", 64, 256, 1, 256, 4, [16] * 64, 1)
+    _, b = custom_layer("gb", 64, 128, 1, 128, 4, [16] * 64, 2)
+    _, c = small_case("tile_ragged")
+    with GpuLayer(a) as ga, GpuLayer(b) as gb, GpuLayer(c) as gc, GpuLayer(oracle.quantize(a, 8)) as gq:
+        t = ga.torch
+        x = t.zeros(96, dtype=t.float16, device=ga.dev)
+        y = [t.zeros(256, dtype=t.float32, device=ga.dev) for _ in range(2)]
+        ws = t.zeros(1 << 20, dtype=t.uint8, device=ga.dev)
+
+        def status(layers, ys=None, x_dt=skl.SKL_F16, y_dt=skl.SKL_F32, nbytes=1 << 20):
+            ys = ys or [v.data_ptr() for v in y[:len(layers)]]
+            try:
+                skl.sketch_linear_gemv_group([g.handle for g in layers], x.data_ptr(), x_dt, ys, y_dt, ws.data_ptr(), nbytes,
+                                             ga.stream())
+                return skl.SKL_OK
+            except skl.SketchLinearError as e:
+                return e.status
+
+        assert status([ga, ga]) == skl.SKL_OK
+        assert status([ga, gb]) == skl.SKL_ERR_UNSUPPORTED            # different out_features
+        assert status([gc]) == skl.SKL_ERR_UNSUPPORTED                # not a row-sketch layer
+        assert status([ga, gq]) == skl.SKL_ERR_UNSUPPORTED            # low-bit states
+        assert status([ga, ga], ys=[y[0].data_ptr(), y[0].data_ptr()]) == skl.SKL_ERR_INVALID_ARG   # outputs overlap
+        assert status([ga], x_dt=skl.SKL_BF16) == skl.SKL_ERR_UNSUPPORTED
+        assert status([ga], y_dt=skl.SKL_BF16) == skl.SKL_ERR_UNSUPPORTED
+        assert status([ga, ga], nbytes=64) == skl.SKL_ERR_BUFFER_TOO_SMALL
+        L = skl.load_library()
+        assert L.sketch_linear_gemv_group(None, 1, None, 0, None, 0, None, 0, None) == skl.SKL_ERR_INVALID_ARG
+        five = (ctypes.c_void_p * 5)(*[ga.handle] * 5)
+        assert L.sketch_linear_gemv_group(five, 5, x.data_ptr(), 0, five, 2, ws.data_ptr(), 1 << 20, None) == skl.SKL_ERR_INVALID_ARG
+        t.cuda.synchronize()
+
+
 # ------------------------------------------------- sketch construction
 @pytest.mark.parametrize("name", SMALL)
 def test_states_built_on_the_gpu_equal_the_oracle_update(name):

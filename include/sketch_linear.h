@@ -167,6 +167,16 @@ SKL_API skl_status_t sketch_linear_gemv_group(const skl_layer_t *const *layers, 
                                       skl_dtype_t x_dtype, void *const *ys, skl_dtype_t y_dtype,
                                       void *workspace, uint64_t workspace_bytes, void *hip_stream);
 
+/* The first half of a feed-forward block at batch 1 (Sec. 2.1, Eq. 2, with
+ * SiLU as the activation, as in the Llama-shaped configurations):
+ *     h[o] = SiLU(sum_j x[j] W_hat_gate[j][o]) * (sum_j x[j] W_hat_up[j][o]),
+ * SiLU(a) = a / (1 + exp(-a)) in float32.  Same layer requirements, workspace
+ * (sketch_linear_gemv_group_workspace_bytes of {gate, up}) and argument rules
+ * as sketch_linear_gemv_group; h DEVICE [out_features], binary16 or float32. */
+SKL_API skl_status_t sketch_linear_gemv_gate_up(const skl_layer_t *gate, const skl_layer_t *up, const void *x,
+                                        skl_dtype_t x_dtype, void *h, skl_dtype_t h_dtype, void *workspace,
+                                        uint64_t workspace_bytes, void *hip_stream);
+
 /* Diagnostic: only the first of the two kernels behind sketch_linear_gemv
  * (query, Eq. 5, fused with the products; one partial sum per output and
  * block group left in workspace), without the reduction that produces y.

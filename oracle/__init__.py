@@ -244,3 +244,11 @@ def allocate_widths(importance, budget_states: int, d: int) -> np.ndarray:
     k = np.floor(share * (budget_states / d)).astype(np.int64)
     k = np.clip(k, 1, 65535)
     return k.astype(np.uint32)
+
+
+def gate_up(gate, up) -> np.ndarray:
+    """First half of the feed-forward block, Eq. (2): Activation(x W_gate) * (x W_up), element-wise, in
+    binary64.  The paper leaves the activation open; the Llama-shaped configurations use SiLU,
+    SiLU(a) = a / (1 + exp(-a))."""
+    a = np.asarray(gate, dtype=np.float64)
+    return a / (1.0 + np.exp(-a)) * np.asarray(up, dtype=np.float64)

@@ -31,7 +31,7 @@ EXPORTS = ("sketch_linear_device_bytes", "sketch_linear_create", "sketch_linear_
            "sketch_linear_workspace_bytes", "sketch_linear_gemv", "sketch_linear_gemm",
            "sketch_linear_reconstruct", "sketch_linear_gemv_partials", "sketch_linear_prefill_split",
            "sketch_linear_build_workspace_bytes", "sketch_linear_build_states",
-           "sketch_linear_gemv_group_workspace_bytes", "sketch_linear_gemv_group",
+           "sketch_linear_gemv_group_workspace_bytes", "sketch_linear_gemv_group", "sketch_linear_gemv_gate_up",
            "sketch_linear_destroy", "sketch_linear_last_error")
 
 
@@ -94,11 +94,12 @@ def load_library(path: str | None = None):
     L.sketch_linear_build_states.argtypes = [ctypes.POINTER(skl_desc_t), vp, vp, vp, u64, vp]
     L.sketch_linear_gemv_group_workspace_bytes.argtypes = [ctypes.POINTER(vp), u32, ctypes.POINTER(u64)]
     L.sketch_linear_gemv_group.argtypes = [ctypes.POINTER(vp), u32, vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.c_int, vp, u64, vp]
+    L.sketch_linear_gemv_gate_up.argtypes = [vp, vp, vp, ctypes.c_int, vp, ctypes.c_int, vp, u64, vp]
     L.sketch_linear_destroy.argtypes = [vp]
     L.sketch_linear_destroy.restype = None
     L.sketch_linear_last_error.argtypes = []
     L.sketch_linear_last_error.restype = ctypes.c_char_p
-    for n in EXPORTS[:13]:
+    for n in EXPORTS[:14]:
         getattr(L, n).restype = ctypes.c_int
     _lib = L
     return L
@@ -229,6 +230,11 @@ def sketch_linear_gemv_group(layers, x: int, x_dtype: int, ys, y_dtype: int, wor
     """``layers``: handles; ``ys``: device addresses of the outputs, one per layer."""
     _check(load_library().sketch_linear_gemv_group(_ptr_array(layers), len(layers), x, x_dtype, _ptr_array(ys), y_dtype,
                                                    workspace, workspace_bytes, hip_stream))
+
+
+def sketch_linear_gemv_gate_up(gate: int, up: int, x: int, x_dtype: int, h: int, h_dtype: int, workspace: int,
+                               workspace_bytes: int, hip_stream: int = 0) -> None:
+    _check(load_library().sketch_linear_gemv_gate_up(gate, up, x, x_dtype, h, h_dtype, workspace, workspace_bytes, hip_stream))
 
 
 def sketch_linear_build_workspace_bytes(desc: skl_desc_t) -> int:

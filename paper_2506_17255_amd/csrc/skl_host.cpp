@@ -636,7 +636,21 @@ skl_status_t sketch_linear_gemv_group(const skl_layer_t *const *layers, uint32_t
             if (overlap(ys[i], (uint64_t)layers[i]->out * dtype_size(y_dt), ys[k], (uint64_t)layers[k]->out * dtype_size(y_dt)))
                 FAIL(SKL_ERR_INVALID_ARG, "outputs %u and %u overlap", k, i);
     }
-    return skl_launch_gemv_group(layers, n_layers, x, ys, y_dt, ws, stream);
+    return skl_launch_gemv_group(layers, n_layers, x, ys, y_dt, ws, stream, false);
+}
+
+skl_status_t sketch_linear_gemv_gate_up(const skl_layer_t *gate, const skl_layer_t *up, const void *x, skl_dtype_t x_dt, void *h,
+                                        skl_dtype_t h_dt, void *ws, uint64_t ws_bytes, void *stream)
+{
+    if (!gate || !up) FAIL(SKL_ERR_INVALID_ARG, "gate or up layer is NULL");
+    if (x_dt != SKL_F16) FAIL(SKL_ERR_UNSUPPORTED, "gemv activations must be binary16");
+    if (h_dt != SKL_F16 && h_dt != SKL_F32) FAIL(SKL_ERR_UNSUPPORTED, "gemv output must be binary16 or float32");
+    const skl_layer_t *layers[2] = {gate, up};
+    const uint64_t need = skl_gemv_group_workspace_bytes(layers, 2);
+    skl_status_t st = check_io(gate, x, gate->in, 2, h, gate->out, dtype_size(h_dt), 1, ws, ws_bytes, need);
+    if (st != SKL_OK) return st;
+    void *ys[2] = {h, h};
+    return skl_launch_gemv_group(layers, 2, x, ys, h_dt, ws, stream, true);
 }
 
 // ---- sketch construction on the device ------------------------------------

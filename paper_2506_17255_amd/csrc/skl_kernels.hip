@@ -2096,6 +2096,53 @@ struct GroupReduceArgs {
     uint64_t partial_stride;
 };
 
+// gate/up pair of a feed-forward block (Sec. 2.1, Eq. 2 with SiLU as the activation): both reductions and
+// h[o] = SiLU(gate[o]) * up[o] in one pass; layer 0 of the group is the gate, layer 1 the up projection
+__global__ __launch_bounds__(SKL_WG) void k_reduce_gate_up(const float *__restrict__ partial, GroupReduceArgs g, uint32_t out,
+                                                            void *__restrict__ h, uint32_t h_dt)
+{
+    __shared__ float4 red[2][16][16];
+    const uint32_t oq = threadIdx.x & 15, slice = threadIdx.x >> 4;
+    const uint32_t o = blockIdx.x * RED_O + oq * 4;
+    const bool vec = (out & 3u) == 0;
+#pragma unroll
+    for (int l = 0; l < 2; ++l) {
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (o < out) {
+            for (uint32_t u = slice; u < g.n_units[l]; u += 16) {
+                const float *p = partial + l * g.partial_stride + (size_t)u * out + o;
+                if (vec) {
+                    const float4 v = *reinterpret_cast<const float4 *>(p);
+                    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+                } else {
+                    s.x += p[0];
+                    if (o + 1 < out) s.y += p[1];
+                    if (o + 2 < out) s.z += p[2];
+                    if (o + 3 < out) s.w += p[3];
+                }
+            }
+        }
+        red[l][slice][oq] = s;
+    }
+    __syncthreads();
+    if (slice == 0 && o < out) {
+        float4 t[2];
+#pragma unroll
+        for (int l = 0; l < 2; ++l) {
+            t[l] = red[l][0][oq];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) {
+                const float4 v = red[l][i][oq];
+                t[l].x += v.x; t[l].y += v.y; t[l].z += v.z; t[l].w += v.w;
+            }
+        }
+        const float a[4] = {t[0].x, t[0].y, t[0].z, t[0].w}, b[4] = {t[1].x, t[1].y, t[1].z, t[1].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (o + i < out) store_out(h, h_dt, o + i, a[i] / (1.0f + expf(-a[i])) * b[i]);
+    }
+}
+
 __global__ __launch_bounds__(SKL_WG) void k_reduce_partials_group(const float *__restrict__ partial, GroupReduceArgs g,
                                                                    uint32_t out, uint32_t y_dt)
 {
@@ -2624,7 +2671,7 @@ uint64_t skl_gemv_group_workspace_bytes(const skl_layer *const *layers, uint32_t
 }
 
 skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, const void *x_, void *const *ys, skl_dtype_t y_dt,
-                                   void *ws, void *stream_)
+                                   void *ws, void *stream_, bool gate_up)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const skl_layer *F = layers[0];
@@ -2675,8 +2722,12 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
     if (st != SKL_OK) return st;
     st = check_launch("grouped gemv");
     if (st != SKL_OK) return st;
-    hipLaunchKernelGGL(k_reduce_partials_group, dim3((F->out + RED_O - 1) / RED_O, 1, n), dim3(SKL_WG), 0, stream, partial, gr,
-                       F->out, (uint32_t)y_dt);
+    if (gate_up)
+        hipLaunchKernelGGL(k_reduce_gate_up, dim3((F->out + RED_O - 1) / RED_O), dim3(SKL_WG), 0, stream, partial, gr, F->out, ys[0],
+                           (uint32_t)y_dt);
+    else
+        hipLaunchKernelGGL(k_reduce_partials_group, dim3((F->out + RED_O - 1) / RED_O, 1, n), dim3(SKL_WG), 0, stream, partial, gr,
+                           F->out, (uint32_t)y_dt);
     return check_launch("grouped gemv reduction");
 }
 

@@ -314,6 +314,35 @@ def test_grouped_decode_equals_separate_calls(n_layers):
             g.close()
 
 
+@pytest.mark.parametrize("h_dtype", ["f32", "f16"])
+def test_gate_up_epilogue_matches_oracle(h_dtype):
+    """Eq. (2), first half: h = SiLU(x W_gate) * (x W_up) from one grouped launch."""
+    import paper_2506_17255_amd as skl
+    in_f, out_f, d = 160, 777, 4
+    rng = np.random.default_rng(61)
+    x = (rng.standard_normal((1, in_f)) * 4).astype(np.float16)
+    (Wg, skg), (Wu, sku) = (custom_layer("gate", in_f, out_f, 1, out_f, d, rng.choice([11, 60, 200], size=in_f), 70),
+                            custom_layer("up", in_f, out_f, 1, out_f, d, [25] * in_f, 71))
+    ref = oracle.gate_up(oracle.linear(oracle.query(skg), x), oracle.linear(oracle.query(sku), x))
+    with GpuLayer(skg) as gg, GpuLayer(sku) as gu:
+        t = gg.torch
+        xd = t.from_numpy(x.view(np.int16)).to(gg.dev)
+        tdt, sdt = (t.float32, skl.SKL_F32) if h_dtype == "f32" else (t.float16, skl.SKL_F16)
+        h = t.full((out_f + 3,), float("nan"), dtype=tdt, device=gg.dev)
+        need = skl.sketch_linear_gemv_group_workspace_bytes([gg.handle, gu.handle])
+        ws = t.empty(need, dtype=t.uint8, device=gg.dev)
+        skl.sketch_linear_gemv_gate_up(gg.handle, gu.handle, xd.data_ptr(), skl.SKL_F16, h.data_ptr(), sdt, ws.data_ptr(),
+                                       ws.numel(), gg.stream())
+        t.cuda.synchronize()
+        got = h.float().cpu().numpy()
+        assert np.all(np.isnan(got[out_f:]))                   # nothing written past the layer's outputs
+        # composition of the separate calls in float32 (same sums, same activation formula)
+        yg, yu = gg.gemv(x, "f32")[0].astype(np.float32), gu.gemv(x, "f32")[0].astype(np.float32)
+    assert rel_fro(got[None, :out_f], ref) <= (1e-5 if h_dtype == "f32" else TOL)
+    sep = yg / (1 + np.exp(-yg.astype(np.float64))) * yu
+    assert rel_fro(got[None, :out_f], sep[None, :]) <= (1e-6 if h_dtype == "f32" else TOL)
+
+
 def test_grouped_decode_rejects_mixed_shapes_and_bad_arguments():
     import ctypes
     import paper_2506_17255_amd as skl

@@ -382,3 +382,20 @@ def test_oracle_rejects_bad_input():
     sk = oracle.Sketch(4, 4, 4, 4, 1, np.uint32([1]), np.uint32([0]), np.uint32([4]), np.uint16([0x7C00] * 4))
     with pytest.raises(ValueError):
         oracle.query(sk)
+
+
+def test_gate_up_against_a_library_sigmoid_and_closed_forms():
+    """Eq. (2) with SiLU: a * sigmoid(a) * b.  Pinned by scipy's logistic function, by SiLU(a) - SiLU(-a) = a,
+    by SiLU(0) = 0 and by the large-argument limits."""
+    from scipy.special import expit
+    rng = np.random.default_rng(12)
+    a = rng.standard_normal(1000) * 6
+    b = rng.standard_normal(1000)
+    got = oracle.gate_up(a, b)
+    assert np.allclose(got, a * expit(a) * b, rtol=1e-14, atol=0)
+    ones = np.ones_like(a)
+    assert np.allclose(oracle.gate_up(a, ones) - oracle.gate_up(-a, ones), a, rtol=1e-13, atol=1e-15)
+    assert oracle.gate_up(0.0, 5.0) == 0.0
+    assert oracle.gate_up(40.0, 2.0) == pytest.approx(80.0, rel=1e-15)
+    assert abs(oracle.gate_up(-40.0, 2.0)) < 1e-15
+    assert oracle.gate_up(1.0, 1.0) == pytest.approx(0.7310585786300049, rel=1e-15)     # 1 / (1 + 1/e)

@@ -1,0 +1,25 @@
+"""Host-side checks of bench.py's command line (no GPU needed)."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def run(*args):
+    return subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *args], capture_output=True, text=True,
+                          timeout=120, cwd=ROOT)
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = run("--gpus", "2")
+    assert r.returncode == 2
+    assert "single-GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_documented_flags_exist():
+    r = run("--help")
+    assert r.returncode == 0
+    for flag in ("--gpus", "--steps", "--warmup", "--quick", "--prefill-only", "--stack-only", "--low-bit-only",
+                 "--no-cpu", "--calib-copy"):
+        assert flag in r.stdout

@@ -343,6 +343,31 @@ def test_gate_up_epilogue_matches_oracle(h_dtype):
     assert rel_fro(got[None, :out_f], sep[None, :]) <= (1e-6 if h_dtype == "f32" else TOL)
 
 
+@pytest.mark.parametrize("shape", [(16, 2048, 4, 1100), (64, 4096, 3, 16), (8, 64, 8, 5), (3, 1, 2, 1)])
+def test_grouped_decode_other_shapes(shape):
+    """Wide outputs (more than twelve wavefronts per workgroup), tables above 64 KiB, d = 8, a 1-output layer."""
+    import paper_2506_17255_amd as skl
+    in_f, out_f, d, K = shape
+    rng = np.random.default_rng(in_f + out_f)
+    x = rng.standard_normal((1, in_f)).astype(np.float16)
+    cases = [custom_layer(f"gs{i}", in_f, out_f, 1, out_f, d, [K] * in_f, 900 + i) for i in range(2)]
+    layers = [GpuLayer(sk) for _, sk in cases]
+    try:
+        t = layers[0].torch
+        xd = t.from_numpy(x.view(np.int16)).to(layers[0].dev)
+        ys = [t.full((out_f,), float("nan"), dtype=t.float32, device=layers[0].dev) for _ in layers]
+        need = skl.sketch_linear_gemv_group_workspace_bytes([g.handle for g in layers])
+        ws = t.empty(max(need, 16), dtype=t.uint8, device=layers[0].dev)
+        skl.sketch_linear_gemv_group([g.handle for g in layers], xd.data_ptr(), skl.SKL_F16, [y.data_ptr() for y in ys],
+                                     skl.SKL_F32, ws.data_ptr(), ws.numel(), layers[0].stream())
+        t.cuda.synchronize()
+        for g, y in zip(layers, ys):
+            assert np.array_equal(y.cpu().numpy(), g.gemv(x, "f32")[0])
+    finally:
+        for g in layers:
+            g.close()
+
+
 def test_grouped_decode_rejects_mixed_shapes_and_bad_arguments():
     import ctypes
     import paper_2506_17255_amd as skl

@@ -507,12 +507,19 @@ def main():
         X7d = X7.view(torch.bfloat16)
         p7d, _ = time_launches(torch, lambda: torch.matmul(X7d, Wd7), 5, 2)
         fl7 = 2.0 * wl7.tokens * wl7.n_weights
+        # the decompress - compute - release flow on this layer: reconstruct into a binary16 matrix, dense matmul
+        Wm7 = torch.empty(wl7.in_features, wl7.out_features, dtype=torch.float16, device=dev)
+        r7, _ = time_launches(torch, lambda: skl.sketch_linear_reconstruct(g7.handle, Wm7.data_ptr(), 0, 0, stream), 5, 2)
+        X7h = X7d.to(torch.float16)
+        m7, _ = time_launches(torch, lambda: torch.matmul(X7h, Wm7), 5, 2)
+        del Wm7
         result["layer_8192x28672"] = {
             "bits_per_weight": sk7.bits_per_weight,
             "decode_batch1": {"sketch_us": s7 * 1e6, "dense_bf16_us": s7d * 1e6, "weights_per_s": wl7.n_weights / s7,
                               "speedup_vs_dense": s7d / s7},
             "prefill_2048_tokens": {"sketch_us": p7 * 1e6, "tflops": fl7 / p7 / 1e12, "dense_bf16_us": p7d * 1e6,
-                                    "dense_tflops": fl7 / p7d / 1e12, "speedup_vs_dense": p7d / p7}}
+                                    "dense_tflops": fl7 / p7d / 1e12, "speedup_vs_dense": p7d / p7,
+                                    "reconstruct_us": r7 * 1e6, "reconstruct_then_dense_f16_us": (r7 + m7) * 1e6}}
         g7.close()
         del Wd7, X7, Y7, ws7
         result["context"] = ("paper: matrix-form sketch op up to 14.9x faster than its per-weight hash op, "

@@ -433,6 +433,57 @@ def test_states_built_on_the_gpu_with_many_magnitude_ties(geom):
     assert np.array_equal(got, twice)                  # independent of the order in which threads arrive
 
 
+# ------------------------------------------------------------ HIP graphs
+def test_calls_replay_correctly_from_a_hip_graph():
+    """Every entry point only enqueues kernels (no memset or copy nodes), so a caller may capture it: decode,
+    grouped decode, prefill and a low-bit layer captured once, replayed three times with eager work and
+    synchronisation in between, each replay compared with the eager results."""
+    import paper_2506_17255_amd as skl
+    W, sk = small_case("row_classes")
+    q = oracle.quantize(sk, 4)
+    rng = np.random.default_rng(90)
+    with GpuLayer(sk) as g, GpuLayer(q) as gq:
+        t = g.torch
+        dev = g.dev
+        x = t.from_numpy(rng.standard_normal((1, sk.in_features)).astype(np.float16).view(np.int16)).to(dev)
+        X = t.from_numpy(wk.f32_to_bf16_bits(rng.standard_normal((300, sk.in_features)).astype(np.float32)).view(np.int16)).to(dev)
+        y = {k: t.zeros(sk.out_features, dtype=t.float32, device=dev) for k in ("gemv", "grp0", "grp1", "lowbit")}
+        Y = t.zeros(300, sk.out_features, dtype=t.float32, device=dev)
+        sizes = [skl.sketch_linear_workspace_bytes(g.handle, 0, 1), skl.sketch_linear_workspace_bytes(g.handle, 1, 300),
+                 skl.sketch_linear_workspace_bytes(gq.handle, 0, 1), skl.sketch_linear_gemv_group_workspace_bytes([g.handle] * 2)]
+        ws = [t.empty(n, dtype=t.uint8, device=dev) for n in sizes]
+
+        def enqueue(stream):
+            skl.sketch_linear_gemv(g.handle, x.data_ptr(), skl.SKL_F16, sk.in_features, y["gemv"].data_ptr(), skl.SKL_F32,
+                                   sk.out_features, 1, ws[0].data_ptr(), sizes[0], stream)
+            skl.sketch_linear_gemm(g.handle, X.data_ptr(), skl.SKL_BF16, sk.in_features, Y.data_ptr(), skl.SKL_F32,
+                                   sk.out_features, 300, ws[1].data_ptr(), sizes[1], stream)
+            skl.sketch_linear_gemv(gq.handle, x.data_ptr(), skl.SKL_F16, sk.in_features, y["lowbit"].data_ptr(), skl.SKL_F32,
+                                   sk.out_features, 1, ws[2].data_ptr(), sizes[2], stream)
+            skl.sketch_linear_gemv_group([g.handle, g.handle], x.data_ptr(), skl.SKL_F16,
+                                         [y["grp0"].data_ptr(), y["grp1"].data_ptr()], skl.SKL_F32, ws[3].data_ptr(), sizes[3], stream)
+
+        enqueue(g.stream())                                   # eager (also the one-time kernel attribute calls)
+        t.cuda.synchronize()
+        want = {k: v.clone() for k, v in y.items()}
+        want_Y = Y.clone()
+        graph = t.cuda.CUDAGraph()
+        with t.cuda.graph(graph):
+            enqueue(t.cuda.current_stream().cuda_stream)
+        for rep in range(3):
+            for v in y.values():
+                v.fill_(float(rep))                           # eager work between the replays
+            Y.zero_()
+            t.cuda.synchronize()
+            graph.replay()
+            t.cuda.synchronize()
+            for k in y:
+                assert t.equal(y[k], want[k]), (rep, k)
+            assert t.equal(Y, want_Y), rep
+        assert t.equal(want["grp0"], want["gemv"]) and t.equal(want["grp1"], want["gemv"])
+        del graph
+
+
 # ----------------------------------------------------------- error paths
 def test_call_time_validation():
     import paper_2506_17255_amd as skl

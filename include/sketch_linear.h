@@ -156,8 +156,8 @@ SKL_API skl_status_t sketch_linear_gemv(const skl_layer_t *layer, const void *x,
 /* Decode at batch 1 through 1..4 layers that read the same activations (the
  * q/k/v or the gate/up projections of a block; Sec. 2.1, Eq. 1/2) in one pair
  * of launches:  ys[i][o] = sum_j x[j] * W_hat_i[j][o].  The layers must be
- * row-sketch layers with binary16 states and the same in_features,
- * out_features and d (SKL_ERR_UNSUPPORTED otherwise); x DEVICE binary16
+ * row-sketch layers with the same in_features, out_features and d
+ * (SKL_ERR_UNSUPPORTED otherwise; binary16 and low-bit states may be mixed); x DEVICE binary16
  * [in_features]; ys HOST array of n_layers DEVICE pointers, each
  * [out_features] of y_dtype (binary16 or float32), not overlapping.  Results
  * are bit-identical to n_layers calls of sketch_linear_gemv. */

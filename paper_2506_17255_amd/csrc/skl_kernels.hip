@@ -2660,14 +2660,24 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
 // ---- batch-1 decode of up to four layers that share their activations --------
 static bool group_layer_ok(const skl_layer *L, const skl_layer *first)
 {
-    return L->path == 1 && !L->qbits && L->in == first->in && L->out == first->out && L->d == first->d;
+    return L->path == 1 && L->in == first->in && L->out == first->out && L->d == first->d;
 }
 
 uint64_t skl_gemv_group_workspace_bytes(const skl_layer *const *layers, uint32_t n)
 {
+    uint64_t stride = 0, expanded = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        stride = std::max(stride, round256(gemv_partial_bytes(layers[i], 1)));
+        expanded += skl_dequant_bytes(layers[i]);              // low-bit layers: their tables, after all partial sums
+    }
+    return stride * n + expanded;
+}
+
+static uint64_t group_partial_stride(const skl_layer *const *layers, uint32_t n)
+{
     uint64_t stride = 0;
     for (uint32_t i = 0; i < n; ++i) stride = std::max(stride, round256(gemv_partial_bytes(layers[i], 1)));
-    return stride * n;
+    return stride;
 }
 
 skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, const void *x_, void *const *ys, skl_dtype_t y_dt,
@@ -2677,18 +2687,25 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
     const skl_layer *F = layers[0];
     for (uint32_t i = 0; i < n; ++i)
         if (!group_layer_ok(layers[i], F)) {
-            skl_set_error("layer %u of the group is not a row-sketch layer with binary16 states of the first layer's shape", i);
+            skl_set_error("layer %u of the group is not a row-sketch layer of the first layer's shape", i);
             return SKL_ERR_UNSUPPORTED;
         }
     GroupArgs m;
     GroupReduceArgs gr;
-    m.partial_stride = gr.partial_stride = skl_gemv_group_workspace_bytes(layers, n) / n / sizeof(float);
+    const uint64_t stride_bytes = group_partial_stride(layers, n);
+    m.partial_stride = gr.partial_stride = stride_bytes / sizeof(float);
     uint32_t grid_x = 0, waves = 2;
     size_t lds = 0;
+    char *area = static_cast<char *>(ws) + stride_bytes * n;
+    TableSrc srcs[SKL_MAX_GROUP_LAYERS];
+    for (uint32_t i = 0; i < n; ++i) {                          // low-bit layers: expand their unpadded tables first
+        skl_status_t st0 = table_source(layers[i], area, false, true, stream, &srcs[i]);
+        if (st0 != SKL_OK) return st0;
+        area += skl_dequant_bytes(layers[i]);
+    }
     for (uint32_t i = 0; i < SKL_MAX_GROUP_LAYERS; ++i) {
         const skl_layer *L = layers[i < n ? i : 0];            // unused slots repeat the first layer
-        TableSrc src;
-        table_source(L, nullptr, false, true, stream, &src);   // binary16 states: resident tables, nothing is enqueued
+        const TableSrc &src = srcs[i < n ? i : 0];
         StreamArgs &a = m.a[i];
         a.r = make_row_args(L, src);
         a.r.tables = src.ptables;

@@ -368,6 +368,29 @@ def test_grouped_decode_other_shapes(shape):
             g.close()
 
 
+def test_grouped_decode_with_low_bit_layers():
+    import paper_2506_17255_amd as skl
+    W, sk = small_case("row_classes")
+    q4, q8 = oracle.quantize(sk, 4), oracle.quantize(sk, 8)
+    rng = np.random.default_rng(95)
+    x = rng.standard_normal((1, sk.in_features)).astype(np.float16)
+    with GpuLayer(sk) as g, GpuLayer(q4) as g4, GpuLayer(q8) as g8:
+        t = g.torch
+        xd = t.from_numpy(x.view(np.int16)).to(g.dev)
+        layers = [g4, g, g8]
+        ys = [t.full((sk.out_features,), float("nan"), dtype=t.float32, device=g.dev) for _ in layers]
+        need = skl.sketch_linear_gemv_group_workspace_bytes([l.handle for l in layers])
+        assert need >= 2 * 2 * sk.states.size
+        ws = t.empty(need, dtype=t.uint8, device=g.dev)
+        skl.sketch_linear_gemv_group([l.handle for l in layers], xd.data_ptr(), skl.SKL_F16, [y.data_ptr() for y in ys],
+                                     skl.SKL_F32, ws.data_ptr(), ws.numel(), g.stream())
+        t.cuda.synchronize()
+        for l, y in zip(layers, ys):
+            assert np.array_equal(y.cpu().numpy(), l.gemv(x, "f32")[0])
+        for l, y, s_ in zip(layers, ys, (q4, sk, q8)):
+            assert rel_fro(y.cpu().numpy()[None, :], oracle.linear(oracle.query(s_), x)) <= 1e-5
+
+
 def test_grouped_decode_rejects_mixed_shapes_and_bad_arguments():
     import ctypes
     import paper_2506_17255_amd as skl
@@ -392,7 +415,7 @@ def test_grouped_decode_rejects_mixed_shapes_and_bad_arguments():
         assert status([ga, ga]) == skl.SKL_OK
         assert status([ga, gb]) == skl.SKL_ERR_UNSUPPORTED            # different out_features
         assert status([gc]) == skl.SKL_ERR_UNSUPPORTED                # not a row-sketch layer
-        assert status([ga, gq]) == skl.SKL_ERR_UNSUPPORTED            # low-bit states
+        assert status([ga, gq]) == skl.SKL_OK                         # low-bit states may join a group
         assert status([ga, ga], ys=[y[0].data_ptr(), y[0].data_ptr()]) == skl.SKL_ERR_INVALID_ARG   # outputs overlap
         assert status([ga], x_dt=skl.SKL_BF16) == skl.SKL_ERR_UNSUPPORTED
         assert status([ga], y_dt=skl.SKL_BF16) == skl.SKL_ERR_UNSUPPORTED

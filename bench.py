@@ -158,11 +158,14 @@ def stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream, n_bloc
                        ([h[k].handle for k in ("gate", "up")], x4, [yk[k].data_ptr() for k in ("gate", "up")]),
                        ([h["down"].handle], x11, [yk["down"].data_ptr()])])
     need_g = max(skl.sketch_linear_gemv_group_workspace_bytes(hs) for hs, _, _ in groups[0])
+    in_of = {xin[f].data_ptr(): f for f in xin}
+    out_of = {yk[k].data_ptr(): wl.out_features for k, wl in zip(kinds, shapes)}
     ws_g = torch.empty(need_g, dtype=torch.uint8, device=dev)
     def grouped_pass():
         for blk in groups:
             for hs, xp, ys in blk:
-                skl.sketch_linear_gemv_group(hs, xp, skl.SKL_F16, ys, skl.SKL_F16, ws_g.data_ptr(), ws_g.numel(), stream)
+                skl.sketch_linear_gemv_group(hs, xp, skl.SKL_F16, in_of[xp], ys, skl.SKL_F16, out_of[ys[0]], 1, ws_g.data_ptr(),
+                                             ws_g.numel(), stream)
     grouped_pass()
     torch.cuda.synchronize()
     grouped_ok = all(torch.equal(yk[k], yr[k]) for k in yk)

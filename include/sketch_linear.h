@@ -153,29 +153,32 @@ SKL_API skl_status_t sketch_linear_gemv(const skl_layer_t *layer, const void *x,
                                 uint32_t batch, void *workspace, uint64_t workspace_bytes,
                                 void *hip_stream);
 
-/* Decode at batch 1 through 1..4 layers that read the same activations (the
- * q/k/v or the gate/up projections of a block; Sec. 2.1, Eq. 1/2) in one pair
- * of launches:  ys[i][o] = sum_j x[j] * W_hat_i[j][o].  The layers must be
- * row-sketch layers with the same in_features, out_features and d
- * (SKL_ERR_UNSUPPORTED otherwise; binary16 and low-bit states may be mixed); x DEVICE binary16
- * [in_features]; ys HOST array of n_layers DEVICE pointers, each
- * [out_features] of y_dtype (binary16 or float32), not overlapping.  Results
- * are bit-identical to n_layers calls of sketch_linear_gemv. */
+/* Decode through 1..4 layers that read the same activations (the q/k/v or
+ * the gate/up projections of a block; Sec. 2.1, Eq. 1/2) in one pair of
+ * launches:  ys[i][b][o] = sum_j x[b][j] * W_hat_i[j][o],  b < batch (1..16).
+ * The layers must be row-sketch layers with the same in_features,
+ * out_features and d (SKL_ERR_UNSUPPORTED otherwise; binary16 and low-bit
+ * states may be mixed); x as for sketch_linear_gemv; ys HOST array of
+ * n_layers DEVICE pointers, each [batch][ldy] of y_dtype (binary16 or
+ * float32), not overlapping.  Results are bit-identical to n_layers calls of
+ * sketch_linear_gemv. */
 SKL_API skl_status_t sketch_linear_gemv_group_workspace_bytes(const skl_layer_t *const *layers, uint32_t n_layers,
-                                                      uint64_t *bytes);
+                                                      uint32_t batch, uint64_t *bytes);
 SKL_API skl_status_t sketch_linear_gemv_group(const skl_layer_t *const *layers, uint32_t n_layers, const void *x,
-                                      skl_dtype_t x_dtype, void *const *ys, skl_dtype_t y_dtype,
-                                      void *workspace, uint64_t workspace_bytes, void *hip_stream);
+                                      skl_dtype_t x_dtype, uint32_t ldx, void *const *ys, skl_dtype_t y_dtype,
+                                      uint32_t ldy, uint32_t batch, void *workspace, uint64_t workspace_bytes,
+                                      void *hip_stream);
 
-/* The first half of a feed-forward block at batch 1 (Sec. 2.1, Eq. 2, with
- * SiLU as the activation, as in the Llama-shaped configurations):
- *     h[o] = SiLU(sum_j x[j] W_hat_gate[j][o]) * (sum_j x[j] W_hat_up[j][o]),
+/* The first half of a feed-forward block (Sec. 2.1, Eq. 2, with SiLU as the
+ * activation, as in the Llama-shaped configurations):
+ *     h[b][o] = SiLU(sum_j x[b][j] W_hat_gate[j][o]) * (sum_j x[b][j] W_hat_up[j][o]),
  * SiLU(a) = a / (1 + exp(-a)) in float32.  Same layer requirements, workspace
  * (sketch_linear_gemv_group_workspace_bytes of {gate, up}) and argument rules
- * as sketch_linear_gemv_group; h DEVICE [out_features], binary16 or float32. */
+ * as sketch_linear_gemv_group; h DEVICE [batch][ldh], binary16 or float32. */
 SKL_API skl_status_t sketch_linear_gemv_gate_up(const skl_layer_t *gate, const skl_layer_t *up, const void *x,
-                                        skl_dtype_t x_dtype, void *h, skl_dtype_t h_dtype, void *workspace,
-                                        uint64_t workspace_bytes, void *hip_stream);
+                                        skl_dtype_t x_dtype, uint32_t ldx, void *h, skl_dtype_t h_dtype,
+                                        uint32_t ldh, uint32_t batch, void *workspace, uint64_t workspace_bytes,
+                                        void *hip_stream);
 
 /* Diagnostic: only the first of the two kernels behind sketch_linear_gemv
  * (query, Eq. 5, fused with the products; one partial sum per output and

@@ -92,9 +92,10 @@ def load_library(path: str | None = None):
                                               ctypes.POINTER(u32)]
     L.sketch_linear_build_workspace_bytes.argtypes = [ctypes.POINTER(skl_desc_t), ctypes.POINTER(u64)]
     L.sketch_linear_build_states.argtypes = [ctypes.POINTER(skl_desc_t), vp, vp, vp, u64, vp]
-    L.sketch_linear_gemv_group_workspace_bytes.argtypes = [ctypes.POINTER(vp), u32, ctypes.POINTER(u64)]
-    L.sketch_linear_gemv_group.argtypes = [ctypes.POINTER(vp), u32, vp, ctypes.c_int, ctypes.POINTER(vp), ctypes.c_int, vp, u64, vp]
-    L.sketch_linear_gemv_gate_up.argtypes = [vp, vp, vp, ctypes.c_int, vp, ctypes.c_int, vp, u64, vp]
+    L.sketch_linear_gemv_group_workspace_bytes.argtypes = [ctypes.POINTER(vp), u32, u32, ctypes.POINTER(u64)]
+    L.sketch_linear_gemv_group.argtypes = [ctypes.POINTER(vp), u32, vp, ctypes.c_int, u32, ctypes.POINTER(vp), ctypes.c_int, u32,
+                                           u32, vp, u64, vp]
+    L.sketch_linear_gemv_gate_up.argtypes = [vp, vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_destroy.argtypes = [vp]
     L.sketch_linear_destroy.restype = None
     L.sketch_linear_last_error.argtypes = []
@@ -219,22 +220,23 @@ def _ptr_array(values):
     return (ctypes.c_void_p * len(values))(*values)
 
 
-def sketch_linear_gemv_group_workspace_bytes(layers) -> int:
+def sketch_linear_gemv_group_workspace_bytes(layers, batch: int = 1) -> int:
     n = ctypes.c_uint64(0)
-    _check(load_library().sketch_linear_gemv_group_workspace_bytes(_ptr_array(layers), len(layers), ctypes.byref(n)))
+    _check(load_library().sketch_linear_gemv_group_workspace_bytes(_ptr_array(layers), len(layers), batch, ctypes.byref(n)))
     return n.value
 
 
-def sketch_linear_gemv_group(layers, x: int, x_dtype: int, ys, y_dtype: int, workspace: int, workspace_bytes: int,
-                             hip_stream: int = 0) -> None:
-    """``layers``: handles; ``ys``: device addresses of the outputs, one per layer."""
-    _check(load_library().sketch_linear_gemv_group(_ptr_array(layers), len(layers), x, x_dtype, _ptr_array(ys), y_dtype,
-                                                   workspace, workspace_bytes, hip_stream))
+def sketch_linear_gemv_group(layers, x: int, x_dtype: int, ldx: int, ys, y_dtype: int, ldy: int, batch: int, workspace: int,
+                             workspace_bytes: int, hip_stream: int = 0) -> None:
+    """``layers``: handles; ``ys``: device addresses of the outputs ([batch][ldy] each), one per layer."""
+    _check(load_library().sketch_linear_gemv_group(_ptr_array(layers), len(layers), x, x_dtype, ldx, _ptr_array(ys), y_dtype,
+                                                   ldy, batch, workspace, workspace_bytes, hip_stream))
 
 
-def sketch_linear_gemv_gate_up(gate: int, up: int, x: int, x_dtype: int, h: int, h_dtype: int, workspace: int,
-                               workspace_bytes: int, hip_stream: int = 0) -> None:
-    _check(load_library().sketch_linear_gemv_gate_up(gate, up, x, x_dtype, h, h_dtype, workspace, workspace_bytes, hip_stream))
+def sketch_linear_gemv_gate_up(gate: int, up: int, x: int, x_dtype: int, ldx: int, h: int, h_dtype: int, ldh: int, batch: int,
+                               workspace: int, workspace_bytes: int, hip_stream: int = 0) -> None:
+    _check(load_library().sketch_linear_gemv_gate_up(gate, up, x, x_dtype, ldx, h, h_dtype, ldh, batch, workspace,
+                                                     workspace_bytes, hip_stream))
 
 
 def sketch_linear_build_workspace_bytes(desc: skl_desc_t) -> int:

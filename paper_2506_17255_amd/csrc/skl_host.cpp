@@ -609,48 +609,62 @@ skl_status_t sketch_linear_gemm(const skl_layer_t *L, const void *X, skl_dtype_t
 }
 
 // ---- several layers on the same activations, one launch --------------------
-skl_status_t sketch_linear_gemv_group_workspace_bytes(const skl_layer_t *const *layers, uint32_t n_layers, uint64_t *bytes)
+static skl_status_t check_group(const skl_layer_t *const *layers, uint32_t n_layers, uint32_t batch)
 {
-    if (!layers || !bytes) FAIL(SKL_ERR_INVALID_ARG, "layers or bytes is NULL");
+    if (!layers) FAIL(SKL_ERR_INVALID_ARG, "layers is NULL");
     if (n_layers < 1 || n_layers > 4) FAIL(SKL_ERR_INVALID_ARG, "n_layers = %u, must be 1..4", n_layers);
+    if (batch < 1 || batch > 16) FAIL(SKL_ERR_INVALID_ARG, "batch = %u, must be 1..16", batch);
     for (uint32_t i = 0; i < n_layers; ++i)
         if (!layers[i]) FAIL(SKL_ERR_INVALID_ARG, "layers[%u] is NULL", i);
-    *bytes = skl_gemv_group_workspace_bytes(layers, n_layers);
+    return SKL_OK;
+}
+
+skl_status_t sketch_linear_gemv_group_workspace_bytes(const skl_layer_t *const *layers, uint32_t n_layers, uint32_t batch,
+                                                      uint64_t *bytes)
+{
+    if (!bytes) FAIL(SKL_ERR_INVALID_ARG, "bytes is NULL");
+    skl_status_t st = check_group(layers, n_layers, batch);
+    if (st != SKL_OK) return st;
+    *bytes = skl_gemv_group_workspace_bytes(layers, n_layers, batch);
     return SKL_OK;
 }
 
 skl_status_t sketch_linear_gemv_group(const skl_layer_t *const *layers, uint32_t n_layers, const void *x, skl_dtype_t x_dt,
-                                      void *const *ys, skl_dtype_t y_dt, void *ws, uint64_t ws_bytes, void *stream)
+                                      uint32_t ldx, void *const *ys, skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *ws,
+                                      uint64_t ws_bytes, void *stream)
 {
-    if (!layers || !ys) FAIL(SKL_ERR_INVALID_ARG, "layers or ys is NULL");
-    if (n_layers < 1 || n_layers > 4) FAIL(SKL_ERR_INVALID_ARG, "n_layers = %u, must be 1..4", n_layers);
-    for (uint32_t i = 0; i < n_layers; ++i)
-        if (!layers[i] || !ys[i]) FAIL(SKL_ERR_INVALID_ARG, "layers[%u] or ys[%u] is NULL", i, i);
+    skl_status_t st = check_group(layers, n_layers, batch);
+    if (st != SKL_OK) return st;
+    if (!ys) FAIL(SKL_ERR_INVALID_ARG, "ys is NULL");
     if (x_dt != SKL_F16) FAIL(SKL_ERR_UNSUPPORTED, "gemv activations must be binary16");
     if (y_dt != SKL_F16 && y_dt != SKL_F32) FAIL(SKL_ERR_UNSUPPORTED, "gemv output must be binary16 or float32");
-    const uint64_t need = skl_gemv_group_workspace_bytes(layers, n_layers);
+    const uint64_t need = skl_gemv_group_workspace_bytes(layers, n_layers, batch);
     for (uint32_t i = 0; i < n_layers; ++i) {
-        skl_status_t st = check_io(layers[i], x, layers[i]->in, 2, ys[i], layers[i]->out, dtype_size(y_dt), 1, ws, ws_bytes, need);
+        if (!ys[i]) FAIL(SKL_ERR_INVALID_ARG, "ys[%u] is NULL", i);
+        st = check_io(layers[i], x, ldx, 2, ys[i], ldy, dtype_size(y_dt), batch, ws, ws_bytes, need);
         if (st != SKL_OK) return st;
+        const uint64_t yb = ((uint64_t)(batch - 1) * ldy + layers[i]->out) * dtype_size(y_dt);
         for (uint32_t k = 0; k < i; ++k)
-            if (overlap(ys[i], (uint64_t)layers[i]->out * dtype_size(y_dt), ys[k], (uint64_t)layers[k]->out * dtype_size(y_dt)))
+            if (overlap(ys[i], yb, ys[k], ((uint64_t)(batch - 1) * ldy + layers[k]->out) * dtype_size(y_dt)))
                 FAIL(SKL_ERR_INVALID_ARG, "outputs %u and %u overlap", k, i);
     }
-    return skl_launch_gemv_group(layers, n_layers, x, ys, y_dt, ws, stream, false);
+    return skl_launch_gemv_group(layers, n_layers, x, ldx, ys, y_dt, ldy, batch, ws, stream, false);
 }
 
-skl_status_t sketch_linear_gemv_gate_up(const skl_layer_t *gate, const skl_layer_t *up, const void *x, skl_dtype_t x_dt, void *h,
-                                        skl_dtype_t h_dt, void *ws, uint64_t ws_bytes, void *stream)
+skl_status_t sketch_linear_gemv_gate_up(const skl_layer_t *gate, const skl_layer_t *up, const void *x, skl_dtype_t x_dt,
+                                        uint32_t ldx, void *h, skl_dtype_t h_dt, uint32_t ldh, uint32_t batch, void *ws,
+                                        uint64_t ws_bytes, void *stream)
 {
     if (!gate || !up) FAIL(SKL_ERR_INVALID_ARG, "gate or up layer is NULL");
+    if (batch < 1 || batch > 16) FAIL(SKL_ERR_INVALID_ARG, "batch = %u, must be 1..16", batch);
     if (x_dt != SKL_F16) FAIL(SKL_ERR_UNSUPPORTED, "gemv activations must be binary16");
     if (h_dt != SKL_F16 && h_dt != SKL_F32) FAIL(SKL_ERR_UNSUPPORTED, "gemv output must be binary16 or float32");
     const skl_layer_t *layers[2] = {gate, up};
-    const uint64_t need = skl_gemv_group_workspace_bytes(layers, 2);
-    skl_status_t st = check_io(gate, x, gate->in, 2, h, gate->out, dtype_size(h_dt), 1, ws, ws_bytes, need);
+    const uint64_t need = skl_gemv_group_workspace_bytes(layers, 2, batch);
+    skl_status_t st = check_io(gate, x, ldx, 2, h, ldh, dtype_size(h_dt), batch, ws, ws_bytes, need);
     if (st != SKL_OK) return st;
     void *ys[2] = {h, h};
-    return skl_launch_gemv_group(layers, 2, x, ys, h_dt, ws, stream, true);
+    return skl_launch_gemv_group(layers, 2, x, ldx, ys, h_dt, ldh, batch, ws, stream, true);
 }
 
 // ---- sketch construction on the device ------------------------------------

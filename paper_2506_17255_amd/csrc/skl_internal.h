@@ -172,11 +172,10 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X, skl_dtype_t x_dt
                              void *stream);
 uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch);
 uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens);
-// batch-1 decode of 1..4 row-sketch layers of one shape that share x (dense outputs, ldy = out)
-uint64_t skl_gemv_group_workspace_bytes(const skl_layer *const *layers, uint32_t n);
-// gate_up: n = 2 (gate, up); ys[0] receives SiLU(gate) * up
-skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, const void *x, void *const *ys, skl_dtype_t y_dt,
-                                   void *ws, void *stream, bool gate_up);
+// decode of 1..4 row-sketch layers of one shape that share x; gate_up: n = 2 (gate, up), ys[0] receives SiLU(gate) * up
+uint64_t skl_gemv_group_workspace_bytes(const skl_layer *const *layers, uint32_t n, uint32_t batch);
+skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, const void *x, uint32_t ldx, void *const *ys,
+                                   skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *ws, void *stream, bool gate_up);
 // sketch construction: group_base holds n_groups + 1 state offsets (host); synchronises the stream once
 skl_status_t skl_launch_build(const skl_desc_t *d, uint64_t n_groups, const uint64_t *group_base, const uint16_t *W,
                               uint16_t *states, void *ws, void *stream);

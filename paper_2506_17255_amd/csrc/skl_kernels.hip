@@ -490,6 +490,7 @@ __global__ __launch_bounds__(MAXW * 64) void k_row_gemv1(StreamArgs p, const uin
 struct GroupArgs {
     StreamArgs a[SKL_MAX_GROUP_LAYERS];
     uint64_t partial_stride;        // floats between the partial sums of consecutive layers
+    uint32_t xs_stride[SKL_MAX_GROUP_LAYERS];   // batched kernel: halfs per staged activation row
 };
 
 template <int D, int MAXW>
@@ -631,8 +632,8 @@ __device__ __forceinline__ void gn_run(const StreamArgs &p, const StreamCtx &c, 
 #define SKL_GN_FIXED_LDS (SKL_MAX_GROUP_BLOCKS * 32)
 
 template <int D>
-__global__ __launch_bounds__(SKL_SWG) void k_row_gemvN(StreamArgs p, const uint16_t *__restrict__ x, uint32_t ldx,
-                                                        uint32_t batch, uint32_t xs_stride, float *__restrict__ partial)
+__device__ __forceinline__ void gemvN_body(const StreamArgs &p, const uint16_t *__restrict__ x, uint32_t ldx, uint32_t batch,
+                                           uint32_t xs_stride, float *__restrict__ partial)
 {
     const StreamCtx c = stream_ctx(p);
     if (!c.live) return;
@@ -700,6 +701,21 @@ __global__ __launch_bounds__(SKL_SWG) void k_row_gemvN(StreamArgs p, const uint1
             }
         }
     }
+}
+
+template <int D>
+__global__ __launch_bounds__(SKL_SWG) void k_row_gemvN(StreamArgs p, const uint16_t *__restrict__ x, uint32_t ldx,
+                                                        uint32_t batch, uint32_t xs_stride, float *__restrict__ partial)
+{
+    gemvN_body<D>(p, x, ldx, batch, xs_stride, partial);
+}
+
+// the batched kernel for a group of layers on the same activations: grid row y runs layer y
+template <int D>
+__global__ __launch_bounds__(SKL_SWG) void k_row_gemvN_group(GroupArgs m, const uint16_t *__restrict__ x, uint32_t ldx,
+                                                              uint32_t batch, float *__restrict__ partial)
+{
+    gemvN_body<D>(m.a[blockIdx.y], x, ldx, batch, m.xs_stride[blockIdx.y], partial + blockIdx.y * m.partial_stride);
 }
 
 // ---- reconstruct (diagnostic): the same table, offsets and query ----------
@@ -2089,7 +2105,7 @@ __global__ __launch_bounds__(SKL_WG) void k_reduce_partials(const float *__restr
     reduce_body(partial, n_units, batch, out, y, y_dt, ldy);
 }
 
-// the reductions of a group of layers (batch 1): grid (ceil(out / 64), 1, layers)
+// the reductions of a group of layers: grid (ceil(out / 64), batch, layers)
 struct GroupReduceArgs {
     void *y[SKL_MAX_GROUP_LAYERS];
     uint32_t n_units[SKL_MAX_GROUP_LAYERS];
@@ -2098,19 +2114,20 @@ struct GroupReduceArgs {
 
 // gate/up pair of a feed-forward block (Sec. 2.1, Eq. 2 with SiLU as the activation): both reductions and
 // h[o] = SiLU(gate[o]) * up[o] in one pass; layer 0 of the group is the gate, layer 1 the up projection
-__global__ __launch_bounds__(SKL_WG) void k_reduce_gate_up(const float *__restrict__ partial, GroupReduceArgs g, uint32_t out,
-                                                            void *__restrict__ h, uint32_t h_dt)
+// grid (ceil(out / 64), batch)
+__global__ __launch_bounds__(SKL_WG) void k_reduce_gate_up(const float *__restrict__ partial, GroupReduceArgs g, uint32_t batch,
+                                                            uint32_t out, void *__restrict__ h, uint32_t h_dt, uint32_t ldh)
 {
     __shared__ float4 red[2][16][16];
     const uint32_t oq = threadIdx.x & 15, slice = threadIdx.x >> 4;
-    const uint32_t o = blockIdx.x * RED_O + oq * 4;
+    const uint32_t o = blockIdx.x * RED_O + oq * 4, b = blockIdx.y;
     const bool vec = (out & 3u) == 0;
 #pragma unroll
     for (int l = 0; l < 2; ++l) {
         float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
         if (o < out) {
             for (uint32_t u = slice; u < g.n_units[l]; u += 16) {
-                const float *p = partial + l * g.partial_stride + (size_t)u * out + o;
+                const float *p = partial + l * g.partial_stride + ((size_t)u * batch + b) * out + o;
                 if (vec) {
                     const float4 v = *reinterpret_cast<const float4 *>(p);
                     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
@@ -2136,17 +2153,17 @@ __global__ __launch_bounds__(SKL_WG) void k_reduce_gate_up(const float *__restri
                 t[l].x += v.x; t[l].y += v.y; t[l].z += v.z; t[l].w += v.w;
             }
         }
-        const float a[4] = {t[0].x, t[0].y, t[0].z, t[0].w}, b[4] = {t[1].x, t[1].y, t[1].z, t[1].w};
+        const float a[4] = {t[0].x, t[0].y, t[0].z, t[0].w}, bb[4] = {t[1].x, t[1].y, t[1].z, t[1].w};
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (o + i < out) store_out(h, h_dt, o + i, a[i] / (1.0f + expf(-a[i])) * b[i]);
+            if (o + i < out) store_out(h, h_dt, (size_t)b * ldh + o + i, a[i] / (1.0f + expf(-a[i])) * bb[i]);
     }
 }
 
 __global__ __launch_bounds__(SKL_WG) void k_reduce_partials_group(const float *__restrict__ partial, GroupReduceArgs g,
-                                                                   uint32_t out, uint32_t y_dt)
+                                                                   uint32_t batch, uint32_t out, uint32_t y_dt, uint32_t ldy)
 {
-    reduce_body(partial + blockIdx.z * g.partial_stride, g.n_units[blockIdx.z], 1, out, g.y[blockIdx.z], y_dt, out);
+    reduce_body(partial + blockIdx.z * g.partial_stride, g.n_units[blockIdx.z], batch, out, g.y[blockIdx.z], y_dt, ldy);
 }
 
 // ========================================================================
@@ -2663,25 +2680,22 @@ static bool group_layer_ok(const skl_layer *L, const skl_layer *first)
     return L->path == 1 && L->in == first->in && L->out == first->out && L->d == first->d;
 }
 
-uint64_t skl_gemv_group_workspace_bytes(const skl_layer *const *layers, uint32_t n)
-{
-    uint64_t stride = 0, expanded = 0;
-    for (uint32_t i = 0; i < n; ++i) {
-        stride = std::max(stride, round256(gemv_partial_bytes(layers[i], 1)));
-        expanded += skl_dequant_bytes(layers[i]);              // low-bit layers: their tables, after all partial sums
-    }
-    return stride * n + expanded;
-}
-
-static uint64_t group_partial_stride(const skl_layer *const *layers, uint32_t n)
+static uint64_t group_partial_stride(const skl_layer *const *layers, uint32_t n, uint32_t batch)
 {
     uint64_t stride = 0;
-    for (uint32_t i = 0; i < n; ++i) stride = std::max(stride, round256(gemv_partial_bytes(layers[i], 1)));
+    for (uint32_t i = 0; i < n; ++i) stride = std::max(stride, round256(gemv_partial_bytes(layers[i], batch)));
     return stride;
 }
 
-skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, const void *x_, void *const *ys, skl_dtype_t y_dt,
-                                   void *ws, void *stream_, bool gate_up)
+uint64_t skl_gemv_group_workspace_bytes(const skl_layer *const *layers, uint32_t n, uint32_t batch)
+{
+    uint64_t expanded = 0;
+    for (uint32_t i = 0; i < n; ++i) expanded += skl_dequant_bytes(layers[i]);     // low-bit layers: their tables, after all partial sums
+    return group_partial_stride(layers, n, batch) * n + expanded;
+}
+
+skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, const void *x_, uint32_t ldx, void *const *ys,
+                                   skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *ws, void *stream_, bool gate_up)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const skl_layer *F = layers[0];
@@ -2690,16 +2704,17 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
             skl_set_error("layer %u of the group is not a row-sketch layer of the first layer's shape", i);
             return SKL_ERR_UNSUPPORTED;
         }
+    const bool one = batch == 1;                               // the batch-1 kernel reads the unpadded tables
     GroupArgs m;
     GroupReduceArgs gr;
-    const uint64_t stride_bytes = group_partial_stride(layers, n);
+    const uint64_t stride_bytes = group_partial_stride(layers, n, batch);
     m.partial_stride = gr.partial_stride = stride_bytes / sizeof(float);
     uint32_t grid_x = 0, waves = 2;
     size_t lds = 0;
     char *area = static_cast<char *>(ws) + stride_bytes * n;
     TableSrc srcs[SKL_MAX_GROUP_LAYERS];
-    for (uint32_t i = 0; i < n; ++i) {                          // low-bit layers: expand their unpadded tables first
-        skl_status_t st0 = table_source(layers[i], area, false, true, stream, &srcs[i]);
+    for (uint32_t i = 0; i < n; ++i) {                          // low-bit layers: expand their tables first
+        skl_status_t st0 = table_source(layers[i], area, !one, one, stream, &srcs[i]);
         if (st0 != SKL_OK) return st0;
         area += skl_dequant_bytes(layers[i]);
     }
@@ -2708,24 +2723,41 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
         const TableSrc &src = srcs[i < n ? i : 0];
         StreamArgs &a = m.a[i];
         a.r = make_row_args(L, src);
-        a.r.tables = src.ptables;
         a.ginfo = reinterpret_cast<const skl_group_info *>(L->dev + L->off_ginfo);
         a.n_wunits = L->n_wunits; a.n_sseg = L->n_sseg; a.n_bg = L->n_bg;
-        a.buf_words = L->max_ptable_bytes / 16;
-        a.two_bufs = L->two_pbufs;
+        const uint32_t xs_stride = (L->max_group_chan / 8 | 1u) * 8;
+        m.xs_stride[i] = xs_stride;
+        size_t need;
+        if (one) {
+            a.r.tables = src.ptables;
+            a.buf_words = L->max_ptable_bytes / 16;
+            a.two_bufs = L->two_pbufs;
+            need = (L->two_pbufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_ptable_bytes) + SKL_G1_FIXED_LDS(L->d) +
+                   (size_t)(L->max_group_chan + 64) * sizeof(uint16_t);
+        } else {
+            a.buf_words = L->max_table_bytes / 16;
+            a.two_bufs = L->two_bufs;
+            need = (L->two_bufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_table_bytes) + SKL_GN_FIXED_LDS +
+                   (size_t)16 * xs_stride * sizeof(uint16_t);
+        }
         gr.y[i] = ys[i < n ? i : 0];
         gr.n_units[i] = L->n_units;
         if (i >= n) continue;
         grid_x = std::max(grid_x, 8 * ((L->n_bg + 7) / 8) * L->n_sseg);
         waves = std::max(waves, (L->n_wunits + L->n_sseg - 1) / L->n_sseg);
-        lds = std::max(lds, (L->two_pbufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_ptable_bytes) + SKL_G1_FIXED_LDS(L->d) +
-                                (size_t)(L->max_group_chan + 64) * sizeof(uint16_t));
+        lds = std::max(lds, need);
     }
     const uint16_t *x = static_cast<const uint16_t *>(x_);
     float *partial = static_cast<float *>(ws);
     skl_status_t st = SKL_OK;
     const dim3 grid(grid_x, n);
-    if (waves <= 12) {
+    if (!one) {
+        DISPATCH_D(F->d, {
+            st = allow_lds(k_row_gemvN_group<D>, lds);
+            if (st == SKL_OK)
+                hipLaunchKernelGGL((k_row_gemvN_group<D>), grid, dim3(64 * waves), lds, stream, m, x, ldx, batch, partial);
+        })
+    } else if (waves <= 12) {
         DISPATCH_D(F->d, {
             st = allow_lds(k_row_gemv1_group<D, 12>, lds);
             if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemv1_group<D, 12>), grid, dim3(64 * waves), lds, stream, m, x, partial);
@@ -2740,11 +2772,11 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
     st = check_launch("grouped gemv");
     if (st != SKL_OK) return st;
     if (gate_up)
-        hipLaunchKernelGGL(k_reduce_gate_up, dim3((F->out + RED_O - 1) / RED_O), dim3(SKL_WG), 0, stream, partial, gr, F->out, ys[0],
-                           (uint32_t)y_dt);
+        hipLaunchKernelGGL(k_reduce_gate_up, dim3((F->out + RED_O - 1) / RED_O, batch), dim3(SKL_WG), 0, stream, partial, gr, batch,
+                           F->out, ys[0], (uint32_t)y_dt, ldy);
     else
-        hipLaunchKernelGGL(k_reduce_partials_group, dim3((F->out + RED_O - 1) / RED_O, 1, n), dim3(SKL_WG), 0, stream, partial, gr,
-                           F->out, (uint32_t)y_dt);
+        hipLaunchKernelGGL(k_reduce_partials_group, dim3((F->out + RED_O - 1) / RED_O, batch, n), dim3(SKL_WG), 0, stream, partial, gr,
+                           batch, F->out, (uint32_t)y_dt, ldy);
     return check_launch("grouped gemv reduction");
 }
 

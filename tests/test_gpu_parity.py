@@ -301,8 +301,8 @@ def test_grouped_decode_equals_separate_calls(n_layers):
             ys = [t.full((out_f,), float("nan"), dtype=tdt, device=g0.dev) for _ in layers]
             need = skl.sketch_linear_gemv_group_workspace_bytes([g.handle for g in layers])
             ws = t.empty(max(need, 16), dtype=t.uint8, device=g0.dev)
-            skl.sketch_linear_gemv_group([g.handle for g in layers], xd.data_ptr(), skl.SKL_F16, [y.data_ptr() for y in ys],
-                                         ydt, ws.data_ptr(), ws.numel(), g0.stream())
+            skl.sketch_linear_gemv_group([g.handle for g in layers], xd.data_ptr(), skl.SKL_F16, in_f, [y.data_ptr() for y in ys],
+                                         ydt, out_f, 1, ws.data_ptr(), ws.numel(), g0.stream())
             t.cuda.synchronize()
             for g, y, (W, sk) in zip(layers, ys, cases):
                 alone = g.gemv(x, "f32" if ydt == skl.SKL_F32 else "f16")
@@ -331,8 +331,8 @@ def test_gate_up_epilogue_matches_oracle(h_dtype):
         h = t.full((out_f + 3,), float("nan"), dtype=tdt, device=gg.dev)
         need = skl.sketch_linear_gemv_group_workspace_bytes([gg.handle, gu.handle])
         ws = t.empty(need, dtype=t.uint8, device=gg.dev)
-        skl.sketch_linear_gemv_gate_up(gg.handle, gu.handle, xd.data_ptr(), skl.SKL_F16, h.data_ptr(), sdt, ws.data_ptr(),
-                                       ws.numel(), gg.stream())
+        skl.sketch_linear_gemv_gate_up(gg.handle, gu.handle, xd.data_ptr(), skl.SKL_F16, in_f, h.data_ptr(), sdt, out_f, 1,
+                                       ws.data_ptr(), ws.numel(), gg.stream())
         t.cuda.synchronize()
         got = h.float().cpu().numpy()
         assert np.all(np.isnan(got[out_f:]))                   # nothing written past the layer's outputs
@@ -358,11 +358,56 @@ def test_grouped_decode_other_shapes(shape):
         ys = [t.full((out_f,), float("nan"), dtype=t.float32, device=layers[0].dev) for _ in layers]
         need = skl.sketch_linear_gemv_group_workspace_bytes([g.handle for g in layers])
         ws = t.empty(max(need, 16), dtype=t.uint8, device=layers[0].dev)
-        skl.sketch_linear_gemv_group([g.handle for g in layers], xd.data_ptr(), skl.SKL_F16, [y.data_ptr() for y in ys],
-                                     skl.SKL_F32, ws.data_ptr(), ws.numel(), layers[0].stream())
+        skl.sketch_linear_gemv_group([g.handle for g in layers], xd.data_ptr(), skl.SKL_F16, in_f, [y.data_ptr() for y in ys],
+                                     skl.SKL_F32, out_f, 1, ws.data_ptr(), ws.numel(), layers[0].stream())
         t.cuda.synchronize()
         for g, y in zip(layers, ys):
             assert np.array_equal(y.cpu().numpy(), g.gemv(x, "f32")[0])
+    finally:
+        for g in layers:
+            g.close()
+
+
+@pytest.mark.parametrize("batch", [2, 5, 16])
+def test_grouped_decode_batched(batch):
+    """The batched (MFMA) decode kernel for a group of layers, with row strides, and the gate/up epilogue."""
+    import paper_2506_17255_amd as skl
+    in_f, out_f, d = 192, 520, 4
+    rng = np.random.default_rng(70 + batch)
+    x = rng.standard_normal((batch, in_f)).astype(np.float16)
+    cases = [custom_layer(f"gb{i}", in_f, out_f, 1, out_f, d, rng.choice([11, 40, 100, 300], size=in_f, p=[0.7, 0.15, 0.1, 0.05]),
+                          600 + i) for i in range(3)]
+    layers = [GpuLayer(sk) for _, sk in cases]
+    try:
+        g0 = layers[0]
+        t = g0.torch
+        ldx, ldy = in_f + 8, out_f + 24
+        xb = np.zeros((batch, ldx), dtype=np.float16)
+        xb[:, :in_f] = x
+        xd = t.from_numpy(xb.view(np.int16)).to(g0.dev)
+        ys = [t.full((batch, ldy), float("nan"), dtype=t.float32, device=g0.dev) for _ in layers]
+        need = skl.sketch_linear_gemv_group_workspace_bytes([g.handle for g in layers], batch)
+        ws = t.empty(need, dtype=t.uint8, device=g0.dev)
+        skl.sketch_linear_gemv_group([g.handle for g in layers], xd.data_ptr(), skl.SKL_F16, ldx, [y.data_ptr() for y in ys],
+                                     skl.SKL_F32, ldy, batch, ws.data_ptr(), ws.numel(), g0.stream())
+        t.cuda.synchronize()
+        alone = []
+        for g, y, (W, sk) in zip(layers, ys, cases):
+            got = y.cpu().numpy()
+            assert np.all(np.isnan(got[:, out_f:]))
+            a = g.gemv(x, "f32")
+            alone.append(a)
+            assert np.array_equal(got[:, :out_f], a)
+            assert rel_fro(got[:, :out_f], oracle.linear(oracle.query(sk), x)) <= 1e-5
+        h = t.full((batch, ldy), float("nan"), dtype=t.float32, device=g0.dev)
+        need2 = skl.sketch_linear_gemv_group_workspace_bytes([layers[0].handle, layers[1].handle], batch)
+        skl.sketch_linear_gemv_gate_up(layers[0].handle, layers[1].handle, xd.data_ptr(), skl.SKL_F16, ldx, h.data_ptr(),
+                                       skl.SKL_F32, ldy, batch, ws.data_ptr(), max(need2, 16), g0.stream())
+        t.cuda.synchronize()
+        hh = h.cpu().numpy()
+        assert np.all(np.isnan(hh[:, out_f:]))
+        ref = oracle.gate_up(oracle.linear(oracle.query(cases[0][1]), x), oracle.linear(oracle.query(cases[1][1]), x))
+        assert rel_fro(hh[:, :out_f], ref) <= 1e-5
     finally:
         for g in layers:
             g.close()
@@ -382,8 +427,9 @@ def test_grouped_decode_with_low_bit_layers():
         need = skl.sketch_linear_gemv_group_workspace_bytes([l.handle for l in layers])
         assert need >= 2 * 2 * sk.states.size
         ws = t.empty(need, dtype=t.uint8, device=g.dev)
-        skl.sketch_linear_gemv_group([l.handle for l in layers], xd.data_ptr(), skl.SKL_F16, [y.data_ptr() for y in ys],
-                                     skl.SKL_F32, ws.data_ptr(), ws.numel(), g.stream())
+        skl.sketch_linear_gemv_group([l.handle for l in layers], xd.data_ptr(), skl.SKL_F16, sk.in_features,
+                                     [y.data_ptr() for y in ys], skl.SKL_F32, sk.out_features, 1, ws.data_ptr(), ws.numel(),
+                                     g.stream())
         t.cuda.synchronize()
         for l, y in zip(layers, ys):
             assert np.array_equal(y.cpu().numpy(), l.gemv(x, "f32")[0])
@@ -403,11 +449,11 @@ def test_grouped_decode_rejects_mixed_shapes_and_bad_arguments():
         y = [t.zeros(256, dtype=t.float32, device=ga.dev) for _ in range(2)]
         ws = t.zeros(1 << 20, dtype=t.uint8, device=ga.dev)
 
-        def status(layers, ys=None, x_dt=skl.SKL_F16, y_dt=skl.SKL_F32, nbytes=1 << 20):
+        def status(layers, ys=None, x_dt=skl.SKL_F16, y_dt=skl.SKL_F32, nbytes=1 << 20, batch=1):
             ys = ys or [v.data_ptr() for v in y[:len(layers)]]
             try:
-                skl.sketch_linear_gemv_group([g.handle for g in layers], x.data_ptr(), x_dt, ys, y_dt, ws.data_ptr(), nbytes,
-                                             ga.stream())
+                skl.sketch_linear_gemv_group([g.handle for g in layers], x.data_ptr(), x_dt, 96, ys, y_dt, 256, batch,
+                                             ws.data_ptr(), nbytes, ga.stream())
                 return skl.SKL_OK
             except skl.SketchLinearError as e:
                 return e.status
@@ -420,10 +466,12 @@ def test_grouped_decode_rejects_mixed_shapes_and_bad_arguments():
         assert status([ga], x_dt=skl.SKL_BF16) == skl.SKL_ERR_UNSUPPORTED
         assert status([ga], y_dt=skl.SKL_BF16) == skl.SKL_ERR_UNSUPPORTED
         assert status([ga, ga], nbytes=64) == skl.SKL_ERR_BUFFER_TOO_SMALL
+        assert status([ga], batch=17) == skl.SKL_ERR_INVALID_ARG
+        assert status([ga], batch=0) == skl.SKL_ERR_INVALID_ARG
         L = skl.load_library()
-        assert L.sketch_linear_gemv_group(None, 1, None, 0, None, 0, None, 0, None) == skl.SKL_ERR_INVALID_ARG
+        assert L.sketch_linear_gemv_group(None, 1, None, 0, 0, None, 0, 0, 1, None, 0, None) == skl.SKL_ERR_INVALID_ARG
         five = (ctypes.c_void_p * 5)(*[ga.handle] * 5)
-        assert L.sketch_linear_gemv_group(five, 5, x.data_ptr(), 0, five, 2, ws.data_ptr(), 1 << 20, None) == skl.SKL_ERR_INVALID_ARG
+        assert L.sketch_linear_gemv_group(five, 5, x.data_ptr(), 0, 96, five, 2, 256, 1, ws.data_ptr(), 1 << 20, None) == skl.SKL_ERR_INVALID_ARG
         t.cuda.synchronize()
 
 
@@ -483,8 +531,9 @@ def test_calls_replay_correctly_from_a_hip_graph():
                                    sk.out_features, 300, ws[1].data_ptr(), sizes[1], stream)
             skl.sketch_linear_gemv(gq.handle, x.data_ptr(), skl.SKL_F16, sk.in_features, y["lowbit"].data_ptr(), skl.SKL_F32,
                                    sk.out_features, 1, ws[2].data_ptr(), sizes[2], stream)
-            skl.sketch_linear_gemv_group([g.handle, g.handle], x.data_ptr(), skl.SKL_F16,
-                                         [y["grp0"].data_ptr(), y["grp1"].data_ptr()], skl.SKL_F32, ws[3].data_ptr(), sizes[3], stream)
+            skl.sketch_linear_gemv_group([g.handle, g.handle], x.data_ptr(), skl.SKL_F16, sk.in_features,
+                                         [y["grp0"].data_ptr(), y["grp1"].data_ptr()], skl.SKL_F32, sk.out_features, 1,
+                                         ws[3].data_ptr(), sizes[3], stream)
 
         enqueue(g.stream())                                   # eager (also the one-time kernel attribute calls)
         t.cuda.synchronize()

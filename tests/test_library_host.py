@@ -213,8 +213,9 @@ def test_build_workspace_and_argument_checks():
 def test_grouped_decode_null_arguments():
     L = skl.load_library()
     n = ctypes.c_uint64(0)
-    assert L.sketch_linear_gemv_group_workspace_bytes(None, 1, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_gemv_group_workspace_bytes(None, 1, 1, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
     one = (ctypes.c_void_p * 1)(None)
-    assert L.sketch_linear_gemv_group_workspace_bytes(one, 1, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
-    assert L.sketch_linear_gemv_group_workspace_bytes(one, 0, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
-    assert L.sketch_linear_gemv_group(one, 1, None, 0, one, 0, None, 0, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_gemv_group_workspace_bytes(one, 1, 1, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_gemv_group_workspace_bytes(one, 0, 1, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_gemv_group(one, 1, None, 0, 0, one, 0, 0, 1, None, 0, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_gemv_gate_up(None, None, None, 0, 0, None, 0, 0, 1, None, 0, None) == skl.SKL_ERR_INVALID_ARG

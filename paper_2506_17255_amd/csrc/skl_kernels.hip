@@ -1584,7 +1584,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __syncthreads();
 
     const uint32_t n = lane & 31, q = lane >> 5;
-    const uint32_t sub = lane >> 3, cw = lane & 7;              // (output, word) of the rebuild gathers, 8 words per state row
     uint32_t t0 = 0, o_first = 0;                               // of the current tile: first token of the wavefront; first
                                                                 // output of the two column blocks it rebuilds (2*wave, 2*wave + 1)
     float16v acc[16];                                           // [row block][column block]
@@ -1628,32 +1627,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         a[s][0] = src[0];
         a[s][1] = src1[0];
     };
-    // ---- rebuild state for 8-word blocks: LDS byte offsets inside a table, [column block][set][row]
-    uint32_t off[2][4][D];
+    // ---- rebuild state for blocks of NB = 8 or 4 words per state row: a gather instruction of the wavefront
+    // covers 64 / NB outputs times NB words (a "set"); a column block has NB / 2 sets, the wavefront's two
+    // column blocks have NB, numbered column block first.  LDS byte offsets inside a table, [set][row]
+    uint32_t off[8][D];
 #pragma unroll
-    for (int c2 = 0; c2 < 2; ++c2)
+    for (int st = 0; st < 8; ++st)
 #pragma unroll
-        for (int st = 0; st < 4; ++st)
-#pragma unroll
-            for (int r = 0; r < D; ++r) off[c2][st][r] = cw * 16;
-    uint32_t K_prev = 0;
-    auto fast_offsets = [&](uint32_t K) {
-        if (K == K_prev) return;
+        for (int r = 0; r < D; ++r) off[st][r] = (lane & 3) * 16;
+    uint32_t K_prev = 0, nb_prev = 0;
+    auto fast_offsets = [&](bool nb4, uint32_t K) {
+        const uint32_t NB = nb4 ? 4 : 8;
+        if (K == K_prev && nb_prev == NB) return;
         K_prev = K;
-        const uint32_t Kq = K << 8;
+        nb_prev = NB;
+        const uint32_t Kq = K << 8, sub = nb4 ? lane >> 2 : lane >> 3, cw = nb4 ? lane & 3 : lane & 7;
+        const uint32_t sh = nb4 ? 1 : 2, ops = nb4 ? 16 : 8;   // sets per column block (as a shift), outputs per set
         uint32_t of = o_first;
         asm volatile("" : "+v"(of));
 #pragma unroll
-        for (int c2 = 0; c2 < 2; ++c2)
+        for (int st = 0; st < 8; ++st) {
+            const uint32_t se = nb4 ? st & 3 : st;             // four words per state row: sets 4..7 repeat sets 0..3
+            const uint32_t o = min(of + (se >> sh) * 32 + (se & ((1u << sh) - 1)) * ops + sub, p.out - 1);
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                const uint32_t o = min(of + c2 * 32 + st * 8 + sub, p.out - 1);
-#pragma unroll
-                for (int r = 0; r < D; ++r) {
-                    const uint32_t t = __umul24(p.h.A[r], o) + p.h.C[r];
-                    off[c2][st][r] = ((r * K + select_index(t, Kq)) * 8 + cw) * 16;
-                }
+            for (int r = 0; r < D; ++r) {
+                const uint32_t t = __umul24(p.h.A[r], o) + p.h.C[r];
+                off[st][r] = ((r * K + select_index(t, Kq)) * NB + cw) * 16;
             }
+        }
     };
     // rebuild before the MFMAs (first block, and blocks of the narrow classes)
     auto build_plain = [&](uint32_t b) {
@@ -1681,16 +1682,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     uint4 *const dummy_w = smem + (dummy_addr - lds0) / 16;
     // ---- the MFMAs of block b with everything else of the pipeline between them: operand words of
     // the next step, the rebuild of the next block's operand words for this wavefront's two column
-    // blocks (when that block has eight words per state row), table chunks, activation words
+    // blocks (when that block has eight or four words per state row; with four, two steps complete
+    // the rebuild and the other two repeat it), table chunks, activation words
     auto block_mma = [&](uint32_t b) {
         const uint32_t P = b & 1;
         const uint32_t bn = min(b + 1, p.n_blocks - 1);
-        const bool fast = b + 1 < p.n_blocks && sm_meta[2 * bn].w == 8 && D <= 6;
+        const uint32_t nb_next = __builtin_amdgcn_readfirstlane(sm_meta[2 * bn].w);
+        const bool nb4 = nb_next == 4;
+        const bool fast = b + 1 < p.n_blocks && (nb_next == 8 || nb4) && D <= 6;
         if (b + 1 < p.n_blocks && !fast) build_plain(b + 1);
-        if (fast) fast_offsets(sm_meta[2 * bn].y);
+        if (fast) fast_offsets(nb4, sm_meta[2 * bn].y);
+        const uint32_t sub = nb4 ? lane >> 2 : lane >> 3, cw = nb4 ? lane & 3 : lane & 7;
         const uint32_t baddr = b_lane + P * G3_SLOT_BYTES;
         const uint32_t tab_next = lds0 + (bn & 1) * tab_bytes;
         const uint32_t slot_next = slot_base + (bn & 1) * G3_SLOT_BYTES;
+        // where this lane's rebuilt words go: word cw of output sub of a set; without a rebuild a place nobody reads
+        const uint32_t w_lane = fast ? slot_next + ((wave * 16 + cw) * G2_ROW + sub) * 16 : dummy_addr;
+        const uint32_t w_sets = __builtin_amdgcn_readfirstlane(fast ? ~0u : 0u);
         const uint32_t a_ns = (sm_meta[2 * bn].w + 1) >> 1, a_s0 = sm_meta[2 * bn + 1].z;     // next block's activation steps
         const uint4 *src2, *src3; uint4 *dst2, *dst3; uint32_t last2, last3;
         table_of(b + 2, src2, dst2, last2);
@@ -1710,14 +1718,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
                 for (int cb = 0; cb < 8; ++cb) bw[cb] = lds_word_at(baddr + (cb * G3_CB_WORDS) * 16);
             }
-            // rebuild: step s does column block s / 2, sets 2 * (s % 2) and 2 * (s % 2) + 1.  Its gathers went
+            // rebuild: step s does sets 2 s and 2 s + 1.  Its gathers went
             // out late in the step before (the wavefront has nobody to hide an LDS round trip behind); those
             // of the first step cannot: the table is complete only after the block's barrier
             if (s == 0) {
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
-                    for (int r = 0; r < D; ++r) g[h][r] = lds_word_at(tab_next + off[0][h][r]);
+                    for (int r = 0; r < D; ++r) g[h][r] = lds_word_at(tab_next + off[h][r]);
             }
             __builtin_amdgcn_sched_barrier(0);
             uint4 m[2];
@@ -1739,15 +1747,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                     const int h = (cb - 4) >> 1;
                     w[h].x = keys_to_neg_half2_mad(m[h].x); w[h].y = keys_to_neg_half2_mad(m[h].y);
                     w[h].z = keys_to_neg_half2_mad(m[h].z); w[h].w = keys_to_neg_half2_mad(m[h].w);
-                    const uint32_t cbn = wave * 2 + (s >> 1), nn = (2 * (s & 1) + h) * 8 + sub;
-                    const uint32_t dst = fast ? slot_next + ((cbn * 8 + cw) * G2_ROW + nn) * 16 : dummy_addr;
+                    // set 2 s + h; with four words per state row the sets of steps 2 and 3 are those of steps
+                    // 0 and 1 again (same gathers, same words, same place: no branch in the MFMA stream)
+                    const uint32_t set8 = 2 * s + h, set4 = set8 & 3;
+                    const uint32_t term8 = ((set8 >> 2) * 8 * G2_ROW + (set8 & 3) * 8) * 16;
+                    const uint32_t term4 = ((set4 >> 1) * 8 * G2_ROW + (set4 & 1) * 16) * 16;
+                    const uint32_t dst = w_lane + ((nb4 ? term4 : term8) & w_sets);
                     *(__attribute__((address_space(3))) u32x4v *)(uintptr_t)dst = w[h];
                 }
                 if (cb == 6 && s < 3) {             // the next step's gathers
 #pragma unroll
                     for (int h = 0; h < 2; ++h)
 #pragma unroll
-                        for (int r = 0; r < D; ++r) g[h][r] = lds_word_at(tab_next + off[(s + 1) >> 1][2 * ((s + 1) & 1) + h][r]);
+                        for (int r = 0; r < D; ++r) g[h][r] = lds_word_at(tab_next + off[2 * (s + 1) + h][r]);
                 }
                 if (cb == 7) {                      // the table group requested a step ago
                     uint4 *d0 = t_store ? dst2 + chunk_at(s, 0, last2) : dummy_w;

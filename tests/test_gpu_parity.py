@@ -55,6 +55,14 @@ def small_case(name):
         return custom_layer(name, 16, 2048, 1, 2048, 4, [1100] * 16, 7)
     if name == "row_single":                 # degenerate: one input channel, one output
         return custom_layer(name, 1, 1, 1, 1, 3, [1], 8)
+    if name == "row_four_words":             # mostly blocks of four words per state row, three widths among them,
+        widths = np.array([11] * 40 + [100] * 70 + [129] * 50 + [150] * 40)   # ragged last block of each width
+        np.random.default_rng(13).shuffle(widths)
+        return custom_layer(name, 200, 300, 1, 300, 4, widths, 13)
+    if name == "row_four_words_d6":          # the same with six sketch rows (four words from width 58 on)
+        widths = np.array([20] * 30 + [60] * 45 + [100] * 60 + [150] * 9)
+        np.random.default_rng(14).shuffle(widths)
+        return custom_layer(name, 144, 520, 1, 520, 6, widths, 14)
     if name == "tile_ragged":                # 2-D groups, per-group widths, tile_out < workgroup
         return custom_layer(name, 96, 160, 32, 80, 3, rng.integers(5, 60, size=6), 9)
     if name == "tile_wide":                  # tile_out above one workgroup of lanes, tile_in % 16 != 0
@@ -186,6 +194,27 @@ def test_gemm_strides_and_several_token_tiles(name):
     assert np.array_equal(y_odd, y_al)
     assert rel_fro(y_al, round_to_bf16(ref)) <= TOL
     assert rel_fro(y16, ref) <= TOL
+
+
+@pytest.mark.parametrize("tokens", [1, 300, 700])
+@pytest.mark.parametrize("name", ["row_four_words", "row_four_words_d6"])
+def test_gemm_blocks_of_four_words(name, tokens):
+    """Layers whose blocks hold 32 channels (four words per state row): the prefill kernel rebuilds their
+    operand words between the MFMAs of the block before, with its own lane layout."""
+    W, sk = small_case(name)
+    W_hat = oracle.query(sk)
+    rng = np.random.default_rng(900 + tokens)
+    Xb = wk.f32_to_bf16_bits(rng.standard_normal((tokens, sk.in_features)).astype(np.float32))
+    ref = oracle.linear(W_hat, Xb, x_kind="bf16")
+    with GpuLayer(sk) as g:
+        assert np.array_equal(g.reconstruct(), W_hat)
+        y32 = g.gemm(Xb, "bf16", "f32")
+        ybf = g.gemm(Xb, "bf16", "bf16", ldx=sk.in_features + 8, ldy=sk.out_features + 8)
+        x1 = rng.standard_normal((1, sk.in_features)).astype(np.float16)
+        y1 = g.gemv(x1, "f32")
+    assert rel_fro(y32, ref) <= 1e-5, rel_fro(y32, ref)
+    assert rel_fro(ybf, round_to_bf16(ref)) <= TOL
+    assert rel_fro(y1, oracle.linear(W_hat, x1)) <= 1e-5
 
 
 def test_gemm_is_bit_identical_from_run_to_run():

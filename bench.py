@@ -190,6 +190,81 @@ def stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream, n_bloc
                     "event recording between launches adds to each figure"}
 
 
+def stack_mixed_bpw(torch, np, skl, wk, oracle, GpuLayer, dev, stream, n_blocks=32, passes=5):
+    """The same 224-layer decode pass with the sketch space divided by layer-wise importance (Sec. 3.2):
+    every layer's bits per weight follow a synthetic per-layer scale (log-uniform over a factor of four)
+    times its row-wise values, 0.5 bit/weight on average over the stack.  Widths come from the
+    allocation rule; the states of the 224 distinct sketches are built on the device (Eq. 4) from the
+    seven weight matrices of one block."""
+    shapes = wk.cfg5_stack(n_blocks)
+    kinds = wk.cfg5_stack(1)
+    scales = wk.gen_layer_scales(len(shapes))
+    row_imp = [wk.gen_importance(wl) for wl in kinds]           # of the block whose weights every layer reuses
+    imp = [oracle.layer_importance(s * row_imp[i % len(kinds)]) for i, s in enumerate(scales)]
+    sizes = [wl.n_weights for wl in shapes]
+    budgets = oracle.allocate_layer_budgets(imp, sum(sizes) // 32, sizes=sizes)
+    Wd = [torch.from_numpy(np.ascontiguousarray(wk.gen_weight(wl)).view(np.int16)).to(dev) for wl in kinds]
+    hp = [wk.gen_hash_params(wl) for wl in kinds]
+    layers, bpw = [], []
+    t0 = time.perf_counter()
+    for i, wl in enumerate(shapes):
+        k = i % len(kinds)
+        widths = oracle.allocate_widths(row_imp[k], int(budgets[i]), wl.d)
+        n_states = int(widths.sum()) * wl.d
+        A, C = (np.ascontiguousarray(v, dtype=np.uint32) for v in hp[k])
+        desc = skl.make_desc(wl.in_features, wl.out_features, wl.tile_in, wl.tile_out, wl.d, A, C, widths, None,
+                             n_states=n_states)
+        states = torch.empty(n_states, dtype=torch.int16, device=dev)
+        need = skl.sketch_linear_build_workspace_bytes(desc)
+        wsb = torch.empty(need + 256, dtype=torch.uint8, device=dev)
+        skl.sketch_linear_build_states(desc, Wd[k].data_ptr(), states.data_ptr(), wsb.data_ptr() + (-wsb.data_ptr()) % 256,
+                                       need, stream)
+        sk = oracle.Sketch(wl.in_features, wl.out_features, wl.tile_in, wl.tile_out, wl.d, A, C, widths,
+                           states.cpu().numpy().view(np.uint16))
+        layers.append(GpuLayer(sk))
+        bpw.append(sk.bits_per_weight)
+    build_s = time.perf_counter() - t0
+    del Wd
+    xin = {f: torch.from_numpy(wk.gen_x(wl, 1).view(np.int16)).to(dev) for wl in kinds for f in [wl.in_features]}
+    yout = {f: torch.empty(1, f, dtype=torch.float16, device=dev) for f in {wl.out_features for wl in kinds}}
+    need = max(skl.sketch_linear_workspace_bytes(g.handle, 0, 1) for g in layers)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    calls = [(g.handle, xin[wl.in_features].data_ptr(), skl.SKL_F16, wl.in_features, yout[wl.out_features].data_ptr(),
+              skl.SKL_F16, wl.out_features, 1, ws.data_ptr(), ws.numel(), stream) for wl, g in zip(shapes, layers)]
+    n = len(calls)
+    for _ in range(2):
+        for a in calls:
+            skl.sketch_linear_gemv(*a)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(passes):
+        for a in calls:
+            skl.sketch_linear_gemv(*a)
+    e1.record()
+    torch.cuda.synchronize()
+    plain_us = e0.elapsed_time(e1) * 1e3 / passes
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    ev[0].record()
+    for i, a in enumerate(calls):
+        skl.sketch_linear_gemv(*a)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    per_layer = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(n)]) * 1e3
+    bpw = np.array(bpw)
+    ups = [i for i, wl in enumerate(shapes) if wl.name.endswith("_up")]
+    lo, hi = min(ups, key=lambda i: bpw[i]), max(ups, key=lambda i: bpw[i])
+    for g in layers:
+        g.close()
+    return {"layers": n, "us_per_pass_without_events": plain_us,
+            "bits_per_weight": {"mean_over_weights": float((bpw * np.array(sizes)).sum() / sum(sizes)),
+                                "min": float(bpw.min()), "max": float(bpw.max())},
+            "up_projection_us": {"at_%.2f_bpw" % bpw[lo]: float(per_layer[lo]), "at_%.2f_bpw" % bpw[hi]: float(per_layer[hi])},
+            "build_224_layers_s": build_s,
+            "note": "layer budgets from the layer-wise importance share, widths from the row-wise share; states built "
+                    "on the device; build time includes the host side (widths, descriptors, copies, layer creation)"}
+
+
 def low_bit_states(torch, np, skl, wk, oracle, GpuLayer, build_sketch, dev, stream, steps, warmup):
     """Batch-1 decode of the benchmark layer with low-bit sketch states (Sec. 3.3 last paragraph, Sec. 4):
     codes and scales resident, expanded into the kernels' tables in the workspace by every call."""
@@ -387,7 +462,9 @@ def main():
                                                            args.steps, args.warmup)}))
         return
     if args.stack_only:
-        print(json.dumps({"stack": stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream)}))
+        import oracle as _oracle                                 # width allocation of the mixed stack
+        print(json.dumps({"stack": stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream),
+                          "stack_layer_wise_importance": stack_mixed_bpw(torch, np, skl, wk, _oracle, GpuLayer, dev, stream)}))
         return
     if args.prefill_only:
         print(json.dumps({"prefill_2048_tokens": {"4096x11008": prefill(11008, max(args.steps // 10, 5), 3)}}))
@@ -485,6 +562,8 @@ def main():
         # prefill GEMM, 2048 tokens (uniform widths, 0.5 bit/weight)
         result["prefill_2048_tokens"] = {f"4096x{o}": prefill(o, max(args.steps // 10, 5), 3) for o in (4096, 11008)}
         result["stack"] = stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream)
+        import oracle as _oracle                                 # width allocation of the mixed stack
+        result["stack_layer_wise_importance"] = stack_mixed_bpw(torch, np, skl, wk, _oracle, GpuLayer, dev, stream)
         import oracle as _oracle                                 # offline generator of the quantised sketches
         result["low_bit_states"] = low_bit_states(torch, np, skl, wk, _oracle, GpuLayer, build_sketch, dev, stream,
                                                   args.steps, args.warmup)

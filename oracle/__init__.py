@@ -246,6 +246,38 @@ def allocate_widths(importance, budget_states: int, d: int) -> np.ndarray:
     return k.astype(np.uint32)
 
 
+def row_importance(activations) -> np.ndarray:
+    """Importance of the input channels of a layer (Sec. 3.2): I_j = E[a_j^2], the mean over the sampled
+    activation vectors (rows of ``activations``) of the squared j-th component, in binary64."""
+    a = np.asarray(activations, dtype=np.float64)
+    if a.ndim != 2 or a.shape[0] == 0:
+        raise ValueError("activations must be [samples][channels] with at least one sample")
+    return (a * a).sum(axis=0) / a.shape[0]
+
+
+def layer_importance(row_imp) -> float:
+    """Layer-wise importance (Sec. 3.2): the mean of the layer's row-wise values."""
+    r = np.asarray(row_imp, dtype=np.float64).ravel()
+    if r.size == 0:
+        raise ValueError("no rows")
+    return float(r.sum() / r.size)
+
+
+def allocate_layer_budgets(layer_imp, total_states: int, sizes=None) -> np.ndarray:
+    """Sketch space per layer (Sec. 3.2): layer l receives the share I_l / sum(I) of the total space,
+    rounded down to whole states.  The paper's formula has no size term; its units (the rows of one
+    matrix) are all of one size.  For layers of different sizes ``sizes`` (weights per layer) may be
+    given: the share is then I_l n_l / sum(I n), i.e. the bits per weight of a layer are proportional
+    to its importance; with equal sizes this is the paper's formula."""
+    imp = np.asarray(layer_imp, dtype=np.float64).ravel()
+    if imp.size == 0 or np.any(imp < 0) or not np.all(np.isfinite(imp)) or imp.sum() <= 0:
+        raise ValueError("importance must be finite, non-negative, not all zero")
+    w = imp if sizes is None else imp * np.asarray(sizes, dtype=np.float64).ravel()
+    if w.shape != imp.shape:
+        raise ValueError("one size per layer")
+    return np.floor(w / w.sum() * float(total_states)).astype(np.int64)
+
+
 def gate_up(gate, up) -> np.ndarray:
     """First half of the feed-forward block, Eq. (2): Activation(x W_gate) * (x W_up), element-wise, in
     binary64.  The paper leaves the activation open; the Llama-shaped configurations use SiLU,

@@ -137,3 +137,39 @@ def test_sketch_construction_of_the_up_projection():
     W, sk = build_sketch(wl)
     got = build_states_on_gpu(W, sk.tile_in, sk.tile_out, sk.d, sk.hash_a, sk.hash_c, sk.group_width)
     assert np.array_equal(got, sk.states)
+
+
+def mixed_stack_budgets(n_blocks=32):
+    """Sketch space of every layer of the Llama-2-7B-shaped stack under layer-wise importance (Sec. 3.2):
+    synthetic layer scales times the row-wise values, 0.5 bit/weight on average."""
+    shapes = wk.cfg5_stack(n_blocks)
+    scales = wk.gen_layer_scales(len(shapes))
+    imp = [oracle.layer_importance(s * wk.gen_importance(wl)) for s, wl in zip(scales, shapes)]
+    sizes = [wl.n_weights for wl in shapes]
+    return shapes, oracle.allocate_layer_budgets(imp, sum(sizes) // 32, sizes=sizes)
+
+
+@pytest.mark.parametrize("which", ["least", "most"])
+def test_layer_with_a_layer_wise_budget(which):
+    """The up projection that the layer-wise allocation gives the least / the most space: other width
+    classes and table sizes than the uniform 0.5 bit/weight layers, same kernels, same bar."""
+    shapes, budgets = mixed_stack_budgets()
+    ups = [i for i, wl in enumerate(shapes) if wl.name.endswith("_up")]
+    bpw = [16.0 * budgets[i] / shapes[i].n_weights for i in ups]
+    i = ups[int(np.argmin(bpw) if which == "least" else np.argmax(bpw))]
+    wl = shapes[i]
+    widths = oracle.allocate_widths(wk.gen_importance(wl), int(budgets[i]), wl.d)
+    W, sk = build_sketch(wl, widths=widths)
+    print(f"[full-size] {wl.name}: {sk.bits_per_weight:.4f} bit/weight, widths {sorted(set(widths.tolist()))}", flush=True)
+    assert (sk.bits_per_weight < 0.35) if which == "least" else (sk.bits_per_weight > 0.7)
+    W_hat = oracle.query(sk)
+    x = wk.gen_x(wl, 1)
+    X = wk.gen_X_bf16(wl, 300)
+    cols = np.sort(np.random.default_rng(6).choice(wl.out_features, size=192, replace=False))
+    with GpuLayer(sk) as g:
+        assert np.array_equal(g.reconstruct(), W_hat)
+        assert rel_fro(g.gemv(x, "f32"), oracle.linear(W_hat, x)) <= 1e-5
+        x8 = wk.gen_x(wl, 8)
+        assert rel_fro(g.gemv(x8, "f32")[:, cols], oracle.linear(W_hat, x8, cols=cols)) <= 1e-5
+        y = g.gemm(X, "bf16", "f32")
+        assert rel_fro(y[:, cols], oracle.linear(W_hat, X, x_kind="bf16", cols=cols)) <= 1e-5

@@ -360,6 +360,43 @@ def test_allocate_widths_proportional_share():
         oracle.allocate_widths(np.zeros(3), 10, 1)
 
 
+def test_row_and_layer_importance_by_hand():
+    # Sec. 3.2: I_j = mean over the samples of a_j^2; the layer's value is the mean over its rows
+    a = np.array([[1.0, -2.0, 0.0], [3.0, 2.0, 0.5]])
+    imp = oracle.row_importance(a)
+    assert list(imp) == [5.0, 4.0, 0.125]
+    assert oracle.layer_importance(imp) == pytest.approx(9.125 / 3, rel=1e-15)
+    assert np.array_equal(oracle.row_importance(-a), imp)            # signs do not matter
+    assert np.array_equal(oracle.row_importance(a[::-1]), imp)        # nor the order of the samples
+    assert np.allclose(oracle.row_importance(3 * a), 9 * imp)
+    # a constant activation vector: its own squares
+    assert list(oracle.row_importance(np.tile([[2.0, 0.5]], (7, 1)))) == [4.0, 0.25]
+    with pytest.raises(ValueError):
+        oracle.row_importance(np.zeros((0, 4)))
+
+
+def test_layer_budgets_follow_the_importance_share():
+    # the paper's formula: share I_l / sum(I) of the total space, whole states
+    assert list(oracle.allocate_layer_budgets([1, 1, 2], 4000)) == [1000, 1000, 2000]
+    assert list(oracle.allocate_layer_budgets([1, 2, 4], 100)) == [14, 28, 57]          # floors of 100/7 * {1, 2, 4}
+    b = oracle.allocate_layer_budgets([0.3, 0.5, 0.2, 1.7], 10 ** 6)
+    assert int(b.sum()) <= 10 ** 6 and int(b.sum()) > 10 ** 6 - 4
+    assert np.array_equal(oracle.allocate_layer_budgets([3, 5, 2, 17], 10 ** 6), b)     # a common factor changes nothing
+    # equal sizes: the size-weighted share is the paper's formula
+    assert np.array_equal(oracle.allocate_layer_budgets([1, 2, 4], 100, sizes=[9, 9, 9]), [14, 28, 57])
+    # equal importance: every layer gets the same bits per weight
+    sizes = np.array([4096 * 4096, 4096 * 11008, 11008 * 4096])
+    bud = oracle.allocate_layer_budgets([1, 1, 1], int(sizes.sum()) // 32, sizes=sizes)
+    assert np.allclose(16.0 * bud / sizes, 0.5, rtol=1e-6)
+    # bits per weight proportional to importance
+    bud = oracle.allocate_layer_budgets([1, 3], 10 ** 7, sizes=[10 ** 6, 5 * 10 ** 6])
+    assert (bud[1] / 5e6) / (bud[0] / 1e6) == pytest.approx(3.0, rel=1e-5)
+    with pytest.raises(ValueError):
+        oracle.allocate_layer_budgets([0, 0], 10)
+    with pytest.raises(ValueError):
+        oracle.allocate_layer_budgets([1, 2], 10, sizes=[1, 2, 3])
+
+
 def test_configured_geometry_stays_within_budget():
     for wl in (wk.cfg1(), wk.cfg2(), wk.cfg2(True), wk.cfg3("up"), wk.cfg3("down"),
                wk.cfg4(4096, 0.5), wk.cfg4(4096, 0.75), wk.cfg4(11008, 0.5), wk.cfg4(11008, 0.75),

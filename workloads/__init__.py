@@ -166,6 +166,13 @@ def cfg5_stack(n_layers: int = 32):
     return out
 
 
+def gen_layer_scales(n_layers: int, lo: float = 0.5, hi: float = 2.0) -> np.ndarray:
+    """Synthetic mean squared activation per layer of a stack, log-uniform in [lo, hi]: stands in for
+    the layer-wise importance statistics of a calibration set."""
+    rng = np.random.default_rng(BASE_SEED + 5000 + 77)
+    return np.exp(rng.uniform(np.log(lo), np.log(hi), size=n_layers))
+
+
 def cfg5_70b() -> Workload:
     return Workload("cfg5_70b_8192x28672", 5, 8192, 28672, 1, 28672, 4, 0.5, outlier_frac=0.01,
                     width_mult=4.0, layer_index=900, tokens=2048)

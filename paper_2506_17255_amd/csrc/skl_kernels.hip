@@ -128,10 +128,9 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float f)
 
 __device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
 {
-    const uint32_t u = __builtin_bit_cast(uint32_t, f);
-    const uint32_t nan = (u >> 16) | 0x40u;                                    // NaN stays NaN
-    const uint32_t rne = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;               // nearest even
-    return (uint16_t)((u & 0x7FFFFFFFu) > 0x7F800000u ? nan : rne);
+    // the conversion instruction of the hardware: nearest even, denormals kept, NaN stays a quiet NaN
+    // (checked against the integer formulation over all 2^32 binary32 patterns)
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
 }
 
 __device__ __forceinline__ void store_out(void *y, uint32_t dt, size_t idx, float v)

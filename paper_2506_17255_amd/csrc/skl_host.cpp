@@ -132,10 +132,16 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
     const uint32_t units = (d->out_features + 63) / 64;
     const uint32_t nblk = L.n_blocks;
     std::vector<uint32_t> cum(nblk + 1, 0);
-    for (uint32_t b = 0; b < nblk; ++b) cum[b + 1] = cum[b] + P->bmeta[b].nb;
+    // Cost of a block in quarter words of an eight-word block (measured on MI355X: decode time of six
+    // layer shapes against these weights).  A block costs about the same whatever its word count -- its
+    // table is about as large and it takes the same barriers -- so a word of a narrow block is dearer:
+    // 8 words 32, 4 words 40, 2 words 20, 1 word 28.  With plain word counts the group that received
+    // the outlier channels' one-word blocks ran 2.5 us longer than the others on the 4096 x 11008 layer.
+    auto block_cost = [](uint32_t nb) { return nb >= 8 ? 4 * nb : nb == 4 ? 40u : nb == 2 ? 20u : 28u; };
+    for (uint32_t b = 0; b < nblk; ++b) cum[b + 1] = cum[b] + block_cost(P->bmeta[b].nb);
     const uint32_t total_nb = cum[nblk];
-    // group boundaries for G groups: equal shares of the 16-byte words per state
-    // row, every group at least one block; returns the most blocks in a group
+    // group boundaries for G groups: equal shares of the block costs,
+    // every group at least one block; returns the most blocks in a group
     auto cut_groups = [&](uint32_t G, std::vector<uint32_t> &start) -> uint32_t {
         start.assign(G + 1, 0);
         uint32_t b = 0, most = 0;
@@ -161,7 +167,7 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
     std::vector<uint32_t> scratch_start;
     for (uint32_t G = (nblk + SKL_MAX_GROUP_BLOCKS - 1) / SKL_MAX_GROUP_BLOCKS; G <= nblk; ++G) {
         if (cut_groups(G, scratch_start) > SKL_MAX_GROUP_BLOCKS) continue;   // block metadata of a group sits in LDS
-        const double share = std::ceil((double)total_nb / G + 0.5 * P->bmeta[0].nb);   // groups end on block boundaries
+        const double share = std::ceil((double)total_nb / 4.0 / G + 0.5 * P->bmeta[0].nb);   // in words; groups end on block boundaries
         // one 64-output unit per wavefront of a 1024-thread workgroup: 16 at most; fewer than 6 never pays
         for (uint32_t want = 16; want >= 6; --want) {
             const uint32_t S = (units + want - 1) / want;

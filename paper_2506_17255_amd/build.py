@@ -1,44 +1,69 @@
-"""Builds libsketch_linear.so (HIP, gfx950 only) in-tree with hipcc."""
+"""Builds libsketch_linear.so (HIP, gfx950 only) in-tree with hipcc.
+
+Every source file is one translation unit; they are compiled side by side
+into `_build/` at the repository root and linked into the shared library.
+"""
 from __future__ import annotations
 
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libsketch_linear.so")
-SOURCES = ["skl_host.cpp", "skl_kernels.hip"]
+SOURCES = ["skl_host.cpp", "skl_decode.hip", "skl_reconstruct.hip", "skl_prefill.hip", "skl_prefill_fallback.hip",
+           "skl_tile.hip", "skl_lowbit.hip", "skl_build.hip"]
 
 
 def lib_path() -> str:
     return LIB
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every source for gfx950 and link the shared library."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-fvisibility=hidden", "-x", "hip",
-           # packed-fp32 VALU forms are kept out of the generated code
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument", "-Wno-ignored-attributes",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    if os.environ.get("SKL_DEV_D4_ONLY"):
-        cmd += ["-DSKL_DEV_D4_ONLY"]      # development builds: only the d = 4 kernels
-    cmd += [os.path.join(CSRC, s) for s in SOURCES]
-    cmd += ["-o", LIB]
+def _flags():
+    return ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-x", "hip",
+            # packed-fp32 VALU forms are kept out of the generated code
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-Wno-unused-command-line-argument", "-Wno-ignored-attributes", "-Wno-inline-asm",
+            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
-    out = "\n".join(l for l in (res.stdout + res.stderr).splitlines()
-                    if "packed-fp32-ops" not in l)
+    out = "\n".join(l for l in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def _stale(src: str, obj: str) -> bool:
+    if not os.path.exists(obj):
+        return True
+    deps = [src] + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    deps += [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))]
+    return any(os.path.getmtime(d) > os.path.getmtime(obj) for d in deps)
+
+
+def build_library(verbose: bool = False, jobs: int | None = None, incremental: bool = False) -> str:
+    """Compile every source for gfx950 and link the shared library.  With
+    `incremental`, objects newer than their source and every header are kept."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    jobs = jobs or min(len(SOURCES), max(1, min(os.cpu_count() or 1, 8)))
+    objs = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+    cmds = [[hipcc] + _flags() + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)
+            if not incremental or _stale(os.path.join(CSRC, s), o)]
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden"] + objs + ["-o", LIB], verbose)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    import sys
+    print(build_library(verbose=True, incremental="--incremental" in sys.argv))

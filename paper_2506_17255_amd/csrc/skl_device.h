@@ -1,0 +1,282 @@
+// Device-side helpers and host-side launch plumbing shared by the kernel
+// files of the sketch-linear library (gfx950 only).
+//
+// Common ground of every kernel (Sec. 3.1 of the paper):
+//   select  Eq. 3   t = (A_r * a + C_r) mod 2^24,  k = floor(t * K / 2^24)
+//                   -> one 24-bit multiply-add and one 24-bit multiply-high
+//   gather          the d candidate states come from an LDS-resident copy of
+//                   the group's sketch table
+//   query   Eq. 5   the states are stored as 16-bit order keys
+//                   key = magnitude << 1 | (sign bit clear), so the AbsMaxMin
+//                   query is a plain unsigned 16-bit maximum (two weights per
+//                   packed instruction)
+//   decode          the winning key is turned back into binary16 with the
+//                   sign bit inverted: -w = (key >> 1) | (key << 15 & 0x8000);
+//                   the activations are negated once when they are staged, so
+//                   every product x * w keeps its sign and value.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <type_traits>
+#include <mutex>
+#include <unordered_map>
+
+#include "skl_internal.h"
+
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+
+extern __shared__ uint4 smem[];
+
+// --------------------------------------------------------------- helpers
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    ushort2v m = __builtin_elementwise_max(__builtin_bit_cast(ushort2v, a), __builtin_bit_cast(ushort2v, b));
+    return __builtin_bit_cast(uint32_t, m);
+}
+
+__device__ __forceinline__ uint4 pk_max_u16x8(uint4 a, uint4 b)
+{
+    return make_uint4(pk_max_u16(a.x, b.x), pk_max_u16(a.y, b.y), pk_max_u16(a.z, b.z), pk_max_u16(a.w, b.w));
+}
+
+// two keys -> two binary16 values with inverted sign bits
+__device__ __forceinline__ uint32_t keys_to_neg_half2(uint32_t k)
+{
+    return ((k >> 1) & 0x7FFF7FFFu) | ((k << 15) & 0x80008000u);
+}
+
+// The same in two instructions instead of three, for loops bound by the vector
+// ALU: per 16-bit half, (k >> 1) + k * 0x8000 (the product keeps bit 0 of k in
+// bit 15; the two terms share no bit).  The compiler turns the multiply back
+// into a shift and an OR, hence the explicit packed multiply-add.
+__device__ __forceinline__ uint32_t keys_to_neg_half2_mad(uint32_t k)
+{
+    uint32_t t, r;
+    asm("v_pk_lshrrev_b16 %0, 1, %1 op_sel_hi:[0,1]" : "=v"(t) : "v"(k));
+    asm("v_pk_mad_u16 %0, %1, %2, %3" : "=v"(r) : "v"(k), "s"(0x80008000u), "v"(t));
+    return r;
+}
+
+__device__ __forceinline__ uint4 keys_to_neg_half8(uint4 k)
+{
+    return make_uint4(keys_to_neg_half2(k.x), keys_to_neg_half2(k.y), keys_to_neg_half2(k.z), keys_to_neg_half2(k.w));
+}
+
+// value or zero, component by component (a select of whole 16-byte objects
+// would be turned into a select of addresses and spill the object to memory)
+__device__ __forceinline__ uint4 keep_if(bool keep, uint4 v)
+{
+    return make_uint4(keep ? v.x : 0u, keep ? v.y : 0u, keep ? v.z : 0u, keep ? v.w : 0u);
+}
+
+// Asynchronous copy global -> LDS without passing through registers
+// (global_load_lds_dwordx4): a wavefront moves 64 consecutive 16-byte words,
+// lane i's word landing at dst + i.  The copy is complete after
+// wait_async_copies() by the issuing wavefront (and a barrier for everybody
+// else).
+typedef __attribute__((address_space(3))) void lds_void;
+
+// One global_load_lds_dwordx4: every active lane moves 16 bytes from its own
+// global address to lds_dst + lane (lds_dst is the same for the whole
+// wavefront).  Written as inline assembly on purpose: the compiler then does
+// not know that LDS is being written behind its back and does not force the
+// copy to complete before the next LDS read; completion is awaited explicitly
+// (wait_async_copies / wait_vmcnt_le) before a barrier publishes the data.
+__device__ __forceinline__ void lds_dma_16(const void *gptr, uint4 *lds_dst)
+{
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void *)lds_dst);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory", "m0");
+}
+
+// A source padded to whole 64-word chunks (no bounds check per lane), copied
+// by a workgroup of nw wavefronts: wavefront w moves chunks w, w + nw, ..
+__device__ __forceinline__ void copy_chunks_to_lds_async(uint4 *dst, const uint4 *src, uint32_t n16, uint32_t nw)
+{
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t n_chunks = (n16 + 63) >> 6;
+    for (uint32_t ch = wave; ch < n_chunks; ch += nw) lds_dma_16(src + ch * 64 + lane, dst + ch * 64);
+}
+
+__device__ __forceinline__ void wait_async_copies()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0), other counters untouched
+}
+
+// Eq. 3: index inside a sketch row of width K; Kq = K << 8 (< 2^24).  Only the
+// low 24 bits of t count, so t may be kept as a wrapping 32-bit number.
+__device__ __forceinline__ uint32_t select_index(uint32_t t, uint32_t Kq)
+{
+    return (uint32_t)(((uint64_t)(t & 0xFFFFFFu) * (uint64_t)(Kq & 0xFFFFFFu)) >> 32);
+}
+
+__device__ __forceinline__ float dot2_acc(uint32_t w2, uint32_t x2, float acc)
+{
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, w2), __builtin_bit_cast(half2v, x2), acc, false);
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, h);
+}
+
+__device__ __forceinline__ uint16_t float_to_half_bits(float f)
+{
+    return __builtin_bit_cast(uint16_t, (_Float16)f);   // round to nearest even
+}
+
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    // the conversion instruction of the hardware: nearest even, denormals kept, NaN stays a quiet NaN
+    // (checked against the integer formulation over all 2^32 binary32 patterns)
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+
+__device__ __forceinline__ void store_out(void *y, uint32_t dt, size_t idx, float v)
+{
+    if (dt == SKL_F32) static_cast<float *>(y)[idx] = v;
+    else if (dt == SKL_F16) static_cast<uint16_t *>(y)[idx] = float_to_half_bits(v);
+    else static_cast<uint16_t *>(y)[idx] = float_to_bf16_bits(v);
+}
+
+// activation element -> binary16 bits with the sign inverted
+__device__ __forceinline__ uint16_t load_neg_half(const uint16_t *X, uint32_t x_dt, size_t idx)
+{
+    uint16_t b = X[idx];
+    if (x_dt == SKL_BF16) b = float_to_half_bits(__builtin_bit_cast(float, (uint32_t)b << 16));
+    return b ^ 0x8000u;
+}
+
+static_assert(sizeof(skl_block_meta) == 32, "block metadata is read as two 16-byte words");
+
+struct HashArgs {
+    uint32_t A[SKL_MAX_D];
+    uint32_t C[SKL_MAX_D];
+};
+
+// 16 bytes at an absolute LDS address
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 lds_word_at(uint32_t addr)
+{
+    const u32x4v v = *(const __attribute__((address_space(3))) u32x4v *)(uintptr_t)addr;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// ========================================================================
+// Path 1: row sketches.  One sketch per input channel over all d_out outputs,
+// so the state index of (j, o) depends on o and on the channel's width only.
+// ========================================================================
+struct RowArgs {
+    HashArgs h;
+    const skl_block_meta *bmeta;
+    const uint32_t *chan;
+    const uint4 *tables;
+    uint32_t in, out, n_blocks, n_otiles, n_seg;
+};
+
+__device__ __forceinline__ void stage_table(uint4 *dst, const uint4 *src, uint32_t n16)
+{
+    for (uint32_t i = threadIdx.x; i < n16; i += SKL_WG) dst[i] = src[i];
+}
+
+// word offsets (r*K + k_r(o)) * rs of output channel o in a block table
+template <int D>
+__device__ __forceinline__ void row_offsets(const HashArgs &h, uint32_t o, uint32_t K, uint32_t rs, uint32_t (&off)[D])
+{
+    const uint32_t Kq = K << 8;
+#pragma unroll
+    for (int r = 0; r < D; ++r) {
+        const uint32_t t = __umul24(h.A[r], o) + h.C[r];
+        off[r] = (r * K + select_index(t, Kq)) * rs;
+    }
+}
+
+// query for 8 consecutive channels of the block: word c of every row
+template <int D>
+__device__ __forceinline__ uint4 row_query8(const uint4 *tab, const uint32_t (&off)[D], uint32_t c)
+{
+    uint4 m = tab[off[0] + c];
+#pragma unroll
+    for (int r = 1; r < D; ++r) m = pk_max_u16x8(m, tab[off[r] + c]);
+    return m;
+}
+
+
+// ========================================================================
+// Host side: what every launcher needs
+// ========================================================================
+// the tables a call's kernels read: the resident ones, or for low-bit states their expansion in `area`
+struct TableSrc {
+    const uint4 *tables = nullptr, *ptables = nullptr;
+    const uint16_t *keys = nullptr;
+};
+
+static inline uint64_t round256(uint64_t v) { return (v + 255) / 256 * 256; }
+
+
+// the tables a call's kernels read (low-bit states: expanded into `area` first); skl_lowbit.hip
+skl_status_t skl_table_source(const skl_layer *L, void *area, bool want_padded, bool want_unpadded, hipStream_t stream,
+                              TableSrc *src);
+
+// launchers of the per-weight path (skl_tile.hip)
+skl_status_t skl_tile_launch_reconstruct(const skl_layer *L, const TableSrc &src, uint16_t *W_hat, hipStream_t stream);
+skl_status_t skl_tile_launch_gemv(const skl_layer *L, const TableSrc &src, const uint16_t *x, uint32_t ldx, uint32_t batch,
+                                  float *partial, hipStream_t stream);
+skl_status_t skl_tile_launch_gemm(const skl_layer *L, const TableSrc &src, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx,
+                                  void *Y, skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, hipStream_t stream);
+
+static inline skl_status_t check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        skl_set_error("launch of %s failed: %s", what, hipGetErrorString(e));
+        return SKL_ERR_HIP;
+    }
+    return SKL_OK;
+}
+
+static inline RowArgs make_row_args(const skl_layer *L, const TableSrc &src)
+{
+    RowArgs a;
+    for (int r = 0; r < SKL_MAX_D; ++r) { a.h.A[r] = L->A[r]; a.h.C[r] = L->C[r]; }
+    a.bmeta = reinterpret_cast<const skl_block_meta *>(L->dev + L->off_bmeta);
+    a.chan = reinterpret_cast<const uint32_t *>(L->dev + L->off_chan);
+    a.tables = src.tables;
+    a.in = L->in; a.out = L->out; a.n_blocks = L->n_blocks; a.n_otiles = L->n_otiles; a.n_seg = L->n_seg;
+    return a;
+}
+
+// Kernels that need more than 64 KiB of dynamic LDS must be told so once.
+template <typename K>
+static skl_status_t allow_lds(K kernel, size_t bytes)
+{
+    if (bytes <= 65536) return SKL_OK;
+    static std::mutex mu;
+    static std::unordered_map<const void *, size_t> granted;
+    const void *fn = reinterpret_cast<const void *>(kernel);
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = granted.find(fn);
+    if (it != granted.end() && it->second >= bytes) return SKL_OK;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) {
+        skl_set_error("cannot reserve %zu bytes of LDS: %s", bytes, hipGetErrorString(e));
+        return SKL_ERR_HIP;
+    }
+    granted[fn] = bytes;
+    return SKL_OK;
+}
+
+#define DISPATCH_D(d, CALL)                                         \
+    switch (d) {                                                    \
+    case 1: { constexpr int D = 1; CALL; } break;                   \
+    case 2: { constexpr int D = 2; CALL; } break;                   \
+    case 3: { constexpr int D = 3; CALL; } break;                   \
+    case 4: { constexpr int D = 4; CALL; } break;                   \
+    case 5: { constexpr int D = 5; CALL; } break;                   \
+    case 6: { constexpr int D = 6; CALL; } break;                   \
+    case 7: { constexpr int D = 7; CALL; } break;                   \
+    default: { constexpr int D = 8; CALL; } break;                  \
+    }

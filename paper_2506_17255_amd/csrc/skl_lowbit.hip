@@ -1,0 +1,119 @@
+#include "skl_device.h"
+
+// ========================================================================
+// Low-bit states: codes -> order keys.  A layer with 8- or 4-bit states keeps
+// only codes and one binary16 scale per (group, sketch row) resident; every
+// call first expands them into the 16-bit tables its kernels read (the same
+// layouts create() builds on the host for binary16 states).  The state a code
+// stands for is q * scale / qmax rounded once to binary16: the product is
+// exact in float32 (7 x 11 significant bits), the correctly rounded float32
+// quotient is either exact or far from any binary16 rounding boundary (qmax is
+// odd), so the second rounding never changes the result.
+// ========================================================================
+template <int BITS>
+__device__ __forceinline__ int code_at(const uint8_t *codes, uint32_t i)
+{
+    if (BITS == 8) return static_cast<int8_t>(codes[i]);
+    const uint32_t b = codes[i >> 1];
+    return (int)(((i & 1) ? b >> 4 : b & 15u) ^ 8u) - 8;      // sign-extend the nibble
+}
+
+template <int BITS>
+__device__ __forceinline__ uint16_t key_of_code(int q, uint16_t scale_bits)
+{
+    const float v = __fdiv_rn((float)q * half_bits_to_float(scale_bits), BITS == 8 ? 127.0f : 7.0f);
+    const uint16_t h = float_to_half_bits(v);
+    return (uint16_t)(((h & 0x7FFFu) << 1) | (1u - (h >> 15)));
+}
+
+// row sketches: grid (channel blocks, chunks of 256 words), one thread per 16-byte word: word (r, k, c) of a
+// block holds the keys of channels 8c .. 8c + 7; writes the padded layout, the unpadded one, or both
+template <int BITS>
+__global__ __launch_bounds__(SKL_WG) void k_expand_rows(const skl_block_meta *__restrict__ bmeta, const uint32_t *__restrict__ chan,
+                                                         const uint32_t *__restrict__ choff, const uint8_t *__restrict__ codes,
+                                                         const uint16_t *__restrict__ scales, uint32_t d,
+                                                         uint4 *__restrict__ padded, uint4 *__restrict__ unpadded)
+{
+    const skl_block_meta bm = bmeta[blockIdx.x];
+    const uint32_t K = bm.K, nb = bm.nb;
+    const uint32_t idx = blockIdx.y * SKL_WG + threadIdx.x;
+    if (idx >= d * nb * K) return;
+    const uint32_t k = idx % K, c = (idx / K) % nb, r = idx / (K * nb);         // k fastest: neighbouring lanes read neighbouring codes
+    uint32_t ch[8], at[8], sc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ch[i] = chan[bm.chan_off + 8 * c + i];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t cc = ch[i] != SKL_NO_CHANNEL ? ch[i] : 0;                // every lane issues the same loads; unused ones are dropped below
+        at[i] = choff[cc] + r * K + k;
+        sc[i] = scales[cc * d + r];
+    }
+    uint32_t key[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t kk = key_of_code<BITS>(code_at<BITS>(codes, at[i]), (uint16_t)sc[i]);
+        key[i] = ch[i] != SKL_NO_CHANNEL ? kk : 1u;                              // a channel slot past the end: +0.0
+    }
+    const uint4 w = make_uint4(key[0] | key[1] << 16, key[2] | key[3] << 16, key[4] | key[5] << 16, key[6] | key[7] << 16);
+    if (padded) padded[bm.table_off16 + (size_t)(r * K + k) * bm.rs + c] = w;
+    if (unpadded) unpadded[bm.ptable_off16 + (size_t)(r * K + k) * nb + c] = w;
+}
+
+// 2-D groups: keys in the caller's state order; grid (groups)
+template <int BITS>
+__global__ __launch_bounds__(SKL_WG) void k_expand_groups(const skl_group_meta *__restrict__ gmeta, const uint8_t *__restrict__ codes,
+                                                           const uint16_t *__restrict__ scales, uint32_t d, uint16_t *__restrict__ keys)
+{
+    const skl_group_meta gm = gmeta[blockIdx.x];
+    for (uint32_t idx = threadIdx.x; idx < d * gm.K; idx += SKL_WG)
+        keys[gm.key_off + idx] = key_of_code<BITS>(code_at<BITS>(codes, gm.key_off + idx), scales[blockIdx.x * d + idx / gm.K]);
+}
+
+
+uint64_t skl_dequant_bytes(const skl_layer *L)
+{
+    if (!L->qbits) return 0;
+    return L->path == 1 ? round256(L->table_bytes) + round256(L->ptable_bytes) : round256(L->table_bytes + 16);
+}
+
+skl_status_t skl_table_source(const skl_layer *L, void *area, bool want_padded, bool want_unpadded, hipStream_t stream,
+                                 TableSrc *src)
+{
+    if (!L->qbits) {
+        if (L->path == 1) {
+            src->tables = reinterpret_cast<const uint4 *>(L->dev + L->off_tables);
+            src->ptables = reinterpret_cast<const uint4 *>(L->dev + L->off_ptables);
+        } else {
+            src->keys = reinterpret_cast<const uint16_t *>(L->dev + L->off_keys);
+        }
+        return SKL_OK;
+    }
+    const uint8_t *codes = L->dev + L->off_codes;
+    const uint16_t *scales = reinterpret_cast<const uint16_t *>(L->dev + L->off_scales);
+    if (L->path == 1) {
+        uint4 *padded = static_cast<uint4 *>(area);
+        uint4 *unpadded = reinterpret_cast<uint4 *>(static_cast<char *>(area) + round256(L->table_bytes));
+        src->tables = padded; src->ptables = unpadded;
+        const skl_block_meta *bmeta = reinterpret_cast<const skl_block_meta *>(L->dev + L->off_bmeta);
+        const uint32_t *chan = reinterpret_cast<const uint32_t *>(L->dev + L->off_chan);
+        const uint32_t *choff = reinterpret_cast<const uint32_t *>(L->dev + L->off_choff);
+        // max_ptable_bytes: the largest block's unpadded table, rounded up to KiB: 16-byte words per block
+        const dim3 grid(L->n_blocks, (L->max_ptable_bytes / 16 + SKL_WG - 1) / SKL_WG);
+        if (L->qbits == 8)
+            hipLaunchKernelGGL(k_expand_rows<8>, grid, dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
+                               L->d, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
+        else
+            hipLaunchKernelGGL(k_expand_rows<4>, grid, dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
+                               L->d, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
+    } else {
+        uint16_t *keys = static_cast<uint16_t *>(area);
+        src->keys = keys;
+        const skl_group_meta *gmeta = reinterpret_cast<const skl_group_meta *>(L->dev + L->off_gmeta);
+        if (L->qbits == 8)
+            hipLaunchKernelGGL(k_expand_groups<8>, dim3(L->n_groups), dim3(SKL_WG), 0, stream, gmeta, codes, scales, L->d, keys);
+        else
+            hipLaunchKernelGGL(k_expand_groups<4>, dim3(L->n_groups), dim3(SKL_WG), 0, stream, gmeta, codes, scales, L->d, keys);
+    }
+    return check_launch("expansion of low-bit states");
+}
+

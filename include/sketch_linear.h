@@ -9,8 +9,8 @@
  *     W_hat[j][o] = Max_r  S_g[r][ H_r(Addr(j,o)) ]          (Sec. 3.1, Eq. 5)
  *
  * with the select function of Eq. 3 and per-group sketch widths (importance
- * aware allocation, Sec. 3.2; "K may vary based on the importance metric",
- * Sec. 3.3), and multiplies them into the activations, y = x W_hat
+ * aware allocation, Sec. 3.2; a width per group, Sec. 3.3), and multiplies
+ * them into the activations, y = x W_hat
  * (Sec. 2.1, Eq. 1/2: W is d_in x d_out, activations multiply from the left).
  * W_hat is never written to device memory, except by the diagnostic call
  * sketch_linear_reconstruct().
@@ -70,7 +70,8 @@ typedef enum {
                                      (e.g. a group table that does not fit in LDS) */
     SKL_ERR_BUFFER_TOO_SMALL = 3, /* dev_buf or workspace smaller than required */
     SKL_ERR_NONFINITE = 4,        /* a state is NaN or infinite */
-    SKL_ERR_HIP = 5               /* a HIP runtime call failed; see last_error */
+    SKL_ERR_HIP = 5,              /* a HIP runtime call failed; see last_error */
+    SKL_ERR_NO_MEMORY = 6         /* the host ran out of memory while planning or staging a layer */
 } skl_status_t;
 
 typedef enum { SKL_F16 = 0, SKL_BF16 = 1, SKL_F32 = 2 } skl_dtype_t;
@@ -117,7 +118,24 @@ typedef struct {
     uint64_t table_bytes;      /* bytes of sketch tables (or of codes and scales) resident in dev_buf */
     uint64_t n_weights;        /* in_features * out_features */
     uint64_t n_states;
+    /* -- end of the first version of this struct (40 bytes, still accepted) -- */
+    uint32_t decode_segments;  /* path 1: output segments of the decode plan */
+    uint32_t decode_groups;    /* path 1: block groups of the decode plan (= n_units) */
+    uint32_t block_classes;    /* path 1: bit i set when some channel block has 2^i 16-byte words per
+                                  state row (8 * 2^i input channels per block) */
+    uint32_t prefill_kernel;   /* what sketch_linear_gemm runs: SKL_PREFILL_* */
+    uint32_t n_blocks;         /* path 1: channel blocks */
+    uint32_t reserved;
 } skl_info_t;
+
+#define SKL_INFO_SIZE_V1 40u
+
+/* skl_info_t.prefill_kernel */
+#define SKL_PREFILL_PER_WEIGHT 0u   /* 2-D groups: weights hashed one by one, 64 x 64 tiles */
+#define SKL_PREFILL_FUSED 3u        /* row sketches, tables of two blocks resident in LDS: weights rebuilt
+                                       between the matrix instructions of a 256 x 256 tile */
+#define SKL_PREFILL_STAGED 4u       /* row sketches with larger tables: weights rebuilt once per call into a
+                                       cache-sized slab of the workspace, then a 256 x 256-tile product */
 
 /* Bytes of device memory create() needs for this description.
  * Validates the whole description (Sec. 3.1 states must be finite). */
@@ -188,7 +206,9 @@ SKL_API skl_status_t sketch_linear_gemv_partials(const skl_layer_t *layer, const
                                          uint32_t ldx, uint32_t batch, void *workspace,
                                          uint64_t workspace_bytes, void *hip_stream);
 
-/* Prefill:  Y[t][o] = sum_j X[t][j] * W_hat[j][o],  t < tokens (>= 1).
+/* Prefill (Sec. 3 inference flow, decompression and product fused; Eq. 5 for
+ * W_hat, Sec. 2.1 Eq. 1/2 for the product):
+ *     Y[t][o] = sum_j X[t][j] * W_hat[j][o],  t < tokens (>= 1).
  *   X  DEVICE, bfloat16 or binary16, [tokens][ldx]; |X| must not exceed 65504:
  *      bfloat16 inputs are converted to binary16 (exact inside that range,
  *      down to the binary16 subnormal step) so that W_hat enters the matrix

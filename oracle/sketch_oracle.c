@@ -11,7 +11,7 @@
  * What follows the paper and where:
  *   select   Sec. 3.1 "AbsMaxMin Sketch Design", Eq. (3):  I_r = H_r(Addr(w))
  *   update   Sec. 3.1, Eq. (4):  S[r,I_r] <- w  iff |S[r,I_r]| > |w|;
- *            states start at +inf (Sec. 3.1, "initialized as inf")
+ *            states start at +inf (Sec. 3.1, initial state of the sketch)
  *   query    Sec. 3.1, Eq. (5):  w' = Max_r S[r][H_r(Addr(w))]
  *   groups   Sec. 3.3 "Matrix-based Sketch Operator Mapping": W (d_in x d_out,
  *            row major) is cut into disjoint groups, each with its own sketch
@@ -20,8 +20,8 @@
  *
  * Readings taken where the paper is silent (each is listed in the design
  * notes of the repository):
- *   - Hash.  The paper only says "independent hash functions" fixed by a
- *     seed.  Here  t_r(a) = (A_r * a + C_r) mod 2^24  and
+ *   - Hash.  The paper asks for independent hash functions fixed by a
+ *     seed and names none.  Here  t_r(a) = (A_r * a + C_r) mod 2^24  and
  *     H_r(a) = floor(t_r(a) * K / 2^24); A_r, C_r are explicit inputs.
  *   - Addr(w) is the offset of the weight inside its group: a group is a tile
  *     of tile_in x tile_out weights, a = j_local * tile_out + o_local.

@@ -20,12 +20,17 @@ SKL_ERR_UNSUPPORTED = 2
 SKL_ERR_BUFFER_TOO_SMALL = 3
 SKL_ERR_NONFINITE = 4
 SKL_ERR_HIP = 5
+SKL_ERR_NO_MEMORY = 6
 
 SKL_F16, SKL_BF16, SKL_F32 = 0, 1, 2
 FLAG_HASH_PER_WEIGHT = 1
 
 STATUS_NAMES = {0: "SKL_OK", 1: "SKL_ERR_INVALID_ARG", 2: "SKL_ERR_UNSUPPORTED",
-                3: "SKL_ERR_BUFFER_TOO_SMALL", 4: "SKL_ERR_NONFINITE", 5: "SKL_ERR_HIP"}
+                3: "SKL_ERR_BUFFER_TOO_SMALL", 4: "SKL_ERR_NONFINITE", 5: "SKL_ERR_HIP",
+                6: "SKL_ERR_NO_MEMORY"}
+
+# skl_info_t.prefill_kernel
+SKL_PREFILL_PER_WEIGHT, SKL_PREFILL_FUSED, SKL_PREFILL_STAGED = 0, 3, 4
 
 EXPORTS = ("sketch_linear_device_bytes", "sketch_linear_create", "sketch_linear_info",
            "sketch_linear_workspace_bytes", "sketch_linear_gemv", "sketch_linear_gemm",
@@ -62,8 +67,14 @@ class skl_info_t(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("path", ctypes.c_uint32),
                 ("n_units", ctypes.c_uint32), ("max_table_bytes", ctypes.c_uint32),
                 ("table_bytes", ctypes.c_uint64), ("n_weights", ctypes.c_uint64),
-                ("n_states", ctypes.c_uint64)]
+                ("n_states", ctypes.c_uint64),
+                # end of the first version of the struct (SKL_INFO_SIZE_V1 bytes)
+                ("decode_segments", ctypes.c_uint32), ("decode_groups", ctypes.c_uint32),
+                ("block_classes", ctypes.c_uint32), ("prefill_kernel", ctypes.c_uint32),
+                ("n_blocks", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
+
+SKL_INFO_SIZE_V1 = 40
 
 _lib = None
 
@@ -100,7 +111,7 @@ def load_library(path: str | None = None):
     L.sketch_linear_destroy.restype = None
     L.sketch_linear_last_error.argtypes = []
     L.sketch_linear_last_error.restype = ctypes.c_char_p
-    for n in EXPORTS[:14]:
+    for n in EXPORTS[:-2]:
         getattr(L, n).restype = ctypes.c_int
     _lib = L
     return L

@@ -306,7 +306,7 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
                 P->chan.push_back(s + c < e ? order[s + c] : SKL_NO_CHANNEL);
             const uint64_t words = (uint64_t)d->d * K * rs;
             off16 += words;
-            if (off16 >= (1ull << 32)) return false;
+            if (off16 >= (1ull << 32) || poff16 >= (1ull << 32)) return false;   // both copies are addressed with 32-bit word offsets
             max_table = std::max<uint32_t>(max_table, (uint32_t)(words * 16));
             P->bmeta.push_back(bm);
         }
@@ -320,8 +320,11 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
     L.table_bytes = off16 * 16;
     L.ptable_bytes = poff16 * 16;
     L.max_ptable_bytes = 0;
-    for (const skl_block_meta &bm : P->bmeta)
+    L.block_classes = 0;
+    for (const skl_block_meta &bm : P->bmeta) {
         L.max_ptable_bytes = std::max<uint32_t>(L.max_ptable_bytes, (d->d * bm.K * bm.nb + 63) / 64 * 1024u);
+        L.block_classes |= bm.nb == 8 ? 8u : bm.nb == 4 ? 4u : bm.nb == 2 ? 2u : 1u;
+    }
     L.n_otiles = (d->out_features + SKL_WG - 1) / SKL_WG;
     // about three workgroups per CU on 256 CUs, split over blocks x output segments
     uint32_t seg = (768 + L.n_blocks / 2) / L.n_blocks;
@@ -364,7 +367,19 @@ static skl_status_t plan_tiles(const skl_desc_t *d, uint64_t n_groups, skl_plan 
     return SKL_OK;
 }
 
+static skl_status_t make_plan(const skl_desc_t *user, skl_plan *P);
+
+// nothing may leave the C ABI as an exception: the planner's containers can run out of host memory
 skl_status_t skl_make_plan(const skl_desc_t *user, skl_plan *P)
+{
+    try {
+        return make_plan(user, P);
+    } catch (const std::bad_alloc &) {
+        FAIL(SKL_ERR_NO_MEMORY, "out of host memory while planning the layer");
+    }
+}
+
+static skl_status_t make_plan(const skl_desc_t *user, skl_plan *P)
 {
     uint64_t n_groups = 0;
     skl_status_t st = normalize_desc(user, &P->desc);
@@ -441,10 +456,12 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
              (unsigned long long)P.dev_bytes);
 
     std::vector<uint8_t> img;
+    std::vector<uint64_t> base;
     try {
         img.assign(P.dev_bytes, 0);
+        base.assign((size_t)P.L.in + 1, 0);
     } catch (const std::bad_alloc &) {
-        FAIL(SKL_ERR_INVALID_ARG, "out of host memory for a %llu-byte staging image", (unsigned long long)P.dev_bytes);
+        FAIL(SKL_ERR_NO_MEMORY, "out of host memory for a %llu-byte staging image", (unsigned long long)P.dev_bytes);
     }
     skl_layer &L = P.L;
     desc = &P.desc;                 // from here on: the description in the current struct layout
@@ -459,7 +476,6 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         memcpy(img.data() + L.off_gunits, P.gunits.data(), P.gunits.size() * sizeof(skl_gemm_unit));
         memcpy(img.data() + L.off_gsteps, P.gsteps.data(), P.gsteps.size() * sizeof(skl_gemm_step));
         // state offset of every input channel (one group per channel)
-        std::vector<uint64_t> base(L.in + 1, 0);
         for (uint32_t j = 0; j < L.in; ++j) base[j + 1] = base[j] + (uint64_t)L.d * desc->group_width[j];
         if (L.qbits) {
             uint32_t *choff = reinterpret_cast<uint32_t *>(img.data() + L.off_choff);
@@ -497,7 +513,7 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
     if (e != hipSuccess) FAIL(SKL_ERR_HIP, "copy of the layer image failed: %s", hipGetErrorString(e));
 
     skl_layer *out = new (std::nothrow) skl_layer(L);
-    if (!out) FAIL(SKL_ERR_INVALID_ARG, "out of host memory");
+    if (!out) FAIL(SKL_ERR_NO_MEMORY, "out of host memory");
     out->dev = static_cast<uint8_t *>(dev_buf);
     out->dev_bytes = P.dev_bytes;
     *out_layer = out;
@@ -509,13 +525,22 @@ void sketch_linear_destroy(skl_layer_t *layer) { delete layer; }
 skl_status_t sketch_linear_info(const skl_layer_t *L, skl_info_t *info)
 {
     if (!L || !info) FAIL(SKL_ERR_INVALID_ARG, "layer or info is NULL");
-    if (info->struct_size != sizeof(skl_info_t)) FAIL(SKL_ERR_INVALID_ARG, "info.struct_size mismatch");
+    if (info->struct_size != sizeof(skl_info_t) && info->struct_size != SKL_INFO_SIZE_V1)
+        FAIL(SKL_ERR_INVALID_ARG, "info.struct_size is %u, expected %zu (or %u, the first version)", info->struct_size,
+             sizeof(skl_info_t), SKL_INFO_SIZE_V1);
     info->path = L->path;
     info->n_units = L->n_units;
     info->max_table_bytes = L->max_table_bytes;
     info->table_bytes = L->qbits ? L->code_bytes + (uint64_t)L->n_groups * L->d * sizeof(uint16_t) : L->table_bytes;
     info->n_weights = (uint64_t)L->in * L->out;
     info->n_states = L->n_states;
+    if (info->struct_size == SKL_INFO_SIZE_V1) return SKL_OK;
+    info->decode_segments = L->path == 1 ? L->n_sseg : 0;
+    info->decode_groups = L->path == 1 ? L->n_bg : 0;
+    info->block_classes = L->block_classes;
+    info->prefill_kernel = L->path == 1 ? (L->gemm_v3 ? SKL_PREFILL_FUSED : L->gemm_v2 ? 2u : 1u) : SKL_PREFILL_PER_WEIGHT;
+    info->n_blocks = L->path == 1 ? L->n_blocks : 0;
+    info->reserved = 0;
     return SKL_OK;
 }
 
@@ -608,6 +633,9 @@ skl_status_t sketch_linear_gemm(const skl_layer_t *L, const void *X, skl_dtype_t
     if (tokens > (1u << 24)) FAIL(SKL_ERR_UNSUPPORTED, "more than 2^24 tokens in one call");
     if (x_dt != SKL_F16 && x_dt != SKL_BF16) FAIL(SKL_ERR_UNSUPPORTED, "gemm activations must be bfloat16 or binary16");
     if (y_dt != SKL_F16 && y_dt != SKL_BF16 && y_dt != SKL_F32) FAIL(SKL_ERR_INVALID_ARG, "bad output dtype");
+    // grid limits of the kernels behind this call, checked before anything is enqueued
+    if (L->path == 1 && tokens > 8191u * 256u) FAIL(SKL_ERR_UNSUPPORTED, "more than %u tokens in one call through a row-sketch layer", 8191u * 256u);
+    if (L->path == 0 && tokens > 65535u * 64u) FAIL(SKL_ERR_UNSUPPORTED, "more than %u tokens in one call through the per-weight path", 65535u * 64u);
     skl_status_t st = check_io(L, X, ldx, 2, Y, ldy, dtype_size(y_dt), tokens, ws, ws_bytes,
                                skl_gemm_workspace_bytes(L, tokens));
     if (st != SKL_OK) return st;
@@ -713,7 +741,12 @@ skl_status_t sketch_linear_build_states(const skl_desc_t *user, const uint16_t *
     if (overlap(ws, need, W_dev, w_bytes) || overlap(ws, need, states_dev, d.n_states * 2) ||
         overlap(W_dev, w_bytes, states_dev, d.n_states * 2))
         FAIL(SKL_ERR_INVALID_ARG, "W_dev, states_dev and workspace overlap");
-    std::vector<uint64_t> base(n_groups + 1, 0);
+    std::vector<uint64_t> base;
+    try {
+        base.assign(n_groups + 1, 0);
+    } catch (const std::bad_alloc &) {
+        FAIL(SKL_ERR_NO_MEMORY, "out of host memory for the offsets of %llu groups", (unsigned long long)n_groups);
+    }
     for (uint64_t g = 0; g < n_groups; ++g) base[g + 1] = base[g] + (uint64_t)d.d * d.group_width[g];
     return skl_launch_build(&d, n_groups, base.data(), W_dev, states_dev, ws, stream_);
 }

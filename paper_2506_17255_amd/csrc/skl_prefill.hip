@@ -159,7 +159,9 @@ struct G3Split {
         sg.k0 = u_next - l * nb;
         sg.k1 = sg.k0 + (u_end - u_next) < nb ? sg.k0 + (u_end - u_next) : nb;
         sg.k = n_rounds * gx + l;
-        sg.whole = sg.k0 == 0 && sg.k1 == nb;
+        // a share of the leftover tiles always leaves a partial, also when it happens to cover a whole
+        // tile: the fix-up pass stores every leftover tile from its slots
+        sg.whole = 0;
         sg.part_slot = slot(x, l, wg - owner(x, l * nb));
         u_next += sg.k1 - sg.k0;
         return true;

@@ -171,3 +171,48 @@ def build_states_on_gpu(W: np.ndarray, tile_in, tile_out, d, hash_a, hash_c, wid
     skl.sketch_linear_build_states(desc, Wd.data_ptr(), states.data_ptr(), ws.data_ptr() + off, need,
                                    t.cuda.current_stream().cuda_stream)
     return states.cpu().numpy().view(np.uint16)
+
+
+def stratified_sample(tokens: int, out_features: int, seed: int, per_tile_rows: int = 3, per_tile_cols: int = 4, tile: int = 256):
+    """Sorted rows and columns such that every tile x tile output tile holds per_tile_rows x per_tile_cols
+    elements of the grid rows x cols (fewer in a ragged last tile that is narrower than that)."""
+    rng = np.random.default_rng(seed)
+    rows, cols = [], []
+    for t0 in range(0, tokens, tile):
+        n = min(tile, tokens - t0)
+        rows += (t0 + rng.choice(n, size=min(per_tile_rows, n), replace=False)).tolist()
+    for o0 in range(0, out_features, tile):
+        n = min(tile, out_features - o0)
+        cols += (o0 + rng.choice(n, size=min(per_tile_cols, n), replace=False)).tolist()
+    return np.sort(np.array(rows)), np.sort(np.array(cols))
+
+
+def matmul_f64(W_hat_bits: np.ndarray, X: np.ndarray, x_kind: str = "bf16") -> np.ndarray:
+    """All outputs at once: numpy's binary64 matrix product of the oracle's reconstructed weights (a library
+    routine on the oracle's W_hat; the oracle's own linear() is pinned against the same routine)."""
+    Xf = wk.bf16_bits_to_f32(X).astype(np.float64) if x_kind == "bf16" else np.asarray(X, dtype=np.float16).astype(np.float64)
+    return Xf @ W_hat_bits.view(np.float16).astype(np.float64)
+
+
+def worst_tile_rel_fro(got, ref, tile: int = 256) -> float:
+    """Largest relative Frobenius error over the tile x tile output tiles: one wrong tile cannot hide in the
+    norm of the whole output."""
+    got = np.asarray(got, dtype=np.float64)
+    worst = 0.0
+    for t0 in range(0, ref.shape[0], tile):
+        for o0 in range(0, ref.shape[1], tile):
+            r = ref[t0:t0 + tile, o0:o0 + tile]
+            g = got[t0:t0 + tile, o0:o0 + tile]
+            worst = max(worst, float(np.linalg.norm(g - r) / max(np.linalg.norm(r), 1e-300)))
+    return worst
+
+
+def oracle_stack_layer(index: int):
+    """Worker for process pools (no GPU, no torch): the sketch of layer `index` of the Llama-2-7B-shaped
+    stack from the oracle's update, a digest of the oracle's reconstructed weights and its batch-1 output."""
+    import hashlib
+    wl = wk.cfg5_stack(32)[index]
+    W, sk = build_sketch(wl)
+    W_hat = oracle.query(sk)
+    y = oracle.linear(W_hat, wk.gen_x(wl, 1))
+    return index, sk, hashlib.sha1(np.ascontiguousarray(W_hat).tobytes()).hexdigest(), y

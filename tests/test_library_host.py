@@ -42,7 +42,8 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_header_layout():
     assert ctypes.sizeof(skl.skl_desc_t) == 96
     assert skl.skl_desc_t.state_bits.offset == skl.SKL_DESC_SIZE_V1 == 72
-    assert ctypes.sizeof(skl.skl_info_t) == 40
+    assert ctypes.sizeof(skl.skl_info_t) == 64
+    assert skl.skl_info_t.decode_segments.offset == skl.SKL_INFO_SIZE_V1 == 40
 
 
 def good(**over):

@@ -43,7 +43,13 @@ def test_every_block_of_every_tile_is_multiplied_once(out_features, n_blocks, to
         assert xcd < 8 and wg < gx
         assert tm < m_tiles and tn < n_col
         assert 0 <= k0 < k1 <= n_blocks
-        assert whole == int(k0 == 0 and k1 == n_blocks)
+        # tiles dealt out in whole rounds are stored by the main kernel; every share of a leftover tile
+        # leaves a partial for the fix-up pass, also a share that happens to cover the tile
+        tiles_of = (n_tiles - xcd + 7) // 8 if n_tiles > xcd else 0
+        in_round = ((tn * m_tiles + tm) // 8) < (tiles_of // gx) * gx
+        assert whole == int(in_round)
+        if in_round:
+            assert k0 == 0 and k1 == n_blocks
         assert (tn * m_tiles + tm) % 8 == xcd          # a tile stays on one XCD
         for b in range(k0, k1):
             assert (tm, tn, b) not in seen
@@ -107,6 +113,52 @@ def test_small_exhaustive_sweep():
             for b in range(k0, k1):
                 keys.add((tm, tn, b))
         assert len(keys) == covered
+
+
+def leftover_tiles(shape, tokens):
+    """(xcd, l, token tile, output tile) of every tile the fix-up pass finishes."""
+    gx, l_max, p_cap, n_tiles = shape
+    m_tiles = (tokens + 255) // 256
+    for xcd in range(8):
+        tiles_of = (n_tiles - xcd + 7) // 8 if n_tiles > xcd else 0
+        rounds = tiles_of // gx
+        for l in range(tiles_of - rounds * gx):
+            t = xcd + 8 * (rounds * gx + l)
+            yield xcd, l, t % m_tiles, t // m_tiles
+
+
+def check_fixup_reads_only_written_slots(out_features, n_blocks, tokens):
+    """The fix-up pass adds slots [base, base + parts) of every leftover tile: each must have been written
+    by a partial segment of that tile, and whole-tile segments never belong to a leftover tile."""
+    segs, shape = split(out_features, n_blocks, tokens)
+    gx, l_max, p_cap, n_tiles = shape
+    written = {}
+    for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
+        if not whole:
+            written.setdefault((tm, tn), []).append(slot)
+    left = list(leftover_tiles(shape, tokens))
+    assert len(left) == len(written)
+    for xcd, l, tm, tn in left:
+        assert l < l_max
+        slots = sorted(written[(tm, tn)])
+        base = (xcd * l_max + l) * p_cap
+        assert slots == list(range(base, base + len(slots))), (out_features, n_blocks, tokens, xcd, l)
+    for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
+        if whole:
+            assert (tm, tn) not in written
+
+
+@pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES + [(7936, 16, 2048), (256 * 57, 1, 256), (4864, 1, 768)])
+def test_fixup_reads_only_written_slots(out_features, n_blocks, tokens):
+    check_fixup_reads_only_written_slots(out_features, n_blocks, tokens)
+
+
+def test_fixup_slots_with_few_blocks():
+    """Layers with fewer channel blocks than workgroups per XCD: a leftover share can cover exactly one tile."""
+    for n_blocks in range(1, 33):
+        for n_tiles_out in (1, 2, 7, 19, 31, 57, 64):
+            for tokens in (256, 768, 2048):
+                check_fixup_reads_only_written_slots(256 * n_tiles_out, n_blocks, tokens)
 
 
 def test_argument_errors():

@@ -171,6 +171,20 @@ SKL_API skl_status_t sketch_linear_gemv(const skl_layer_t *layer, const void *x,
                                 uint32_t batch, void *workspace, uint64_t workspace_bytes,
                                 void *hip_stream);
 
+/* The same decode for callers that cannot allocate device memory or pass a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation): the call's scratch lives in a device array inside
+ * the library, SKL_STATIC_SCRATCH_MAX bytes per GPU, held until the process
+ * ends.  The call allocates nothing and returns SKL_ERR_UNSUPPORTED when
+ * sketch_linear_workspace_bytes(layer, 0, batch) exceeds that size.  All such
+ * calls on one GPU share the array: calls that may overlap in time (different
+ * streams, different host threads without ordering) race; order them on one
+ * stream.  Arguments, results and summation order as sketch_linear_gemv. */
+#define SKL_STATIC_SCRATCH_MAX (16u << 20)
+SKL_API skl_status_t sketch_linear_gemv_static(const skl_layer_t *layer, const void *x, skl_dtype_t x_dtype,
+                                       uint32_t ldx, void *y, skl_dtype_t y_dtype, uint32_t ldy,
+                                       uint32_t batch, void *hip_stream);
+
 /* Decode through 1..4 layers that read the same activations (the q/k/v or
  * the gate/up projections of a block; Sec. 2.1, Eq. 1/2) in one pair of
  * launches:  ys[i][b][o] = sum_j x[b][j] * W_hat_i[j][o],  b < batch (1..16).

@@ -37,6 +37,7 @@ EXPORTS = ("sketch_linear_device_bytes", "sketch_linear_create", "sketch_linear_
            "sketch_linear_reconstruct", "sketch_linear_gemv_partials", "sketch_linear_prefill_split",
            "sketch_linear_build_workspace_bytes", "sketch_linear_build_states",
            "sketch_linear_gemv_group_workspace_bytes", "sketch_linear_gemv_group", "sketch_linear_gemv_gate_up",
+           "sketch_linear_gemv_static",
            "sketch_linear_destroy", "sketch_linear_last_error")
 
 
@@ -61,6 +62,7 @@ class skl_desc_t(ctypes.Structure):
 
 
 SKL_DESC_SIZE_V1 = 72
+SKL_STATIC_SCRATCH_MAX = 16 << 20     # bytes of the device array behind sketch_linear_gemv_static
 
 
 class skl_info_t(ctypes.Structure):
@@ -111,6 +113,7 @@ def load_library(path: str | None = None):
     L.sketch_linear_destroy.restype = None
     L.sketch_linear_last_error.argtypes = []
     L.sketch_linear_last_error.restype = ctypes.c_char_p
+    L.sketch_linear_gemv_static.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp]
     for n in EXPORTS[:-2]:
         getattr(L, n).restype = ctypes.c_int
     _lib = L
@@ -199,6 +202,11 @@ def sketch_linear_gemv(layer: int, x: int, x_dtype: int, ldx: int, y: int, y_dty
                        workspace: int, workspace_bytes: int, hip_stream: int = 0) -> None:
     _check(load_library().sketch_linear_gemv(layer, x, x_dtype, ldx, y, y_dtype, ldy, batch, workspace,
                                              workspace_bytes, hip_stream))
+
+
+def sketch_linear_gemv_static(layer: int, x: int, x_dtype: int, ldx: int, y: int, y_dtype: int, ldy: int, batch: int,
+                              hip_stream: int = 0) -> None:
+    _check(load_library().sketch_linear_gemv_static(layer, x, x_dtype, ldx, y, y_dtype, ldy, batch, hip_stream))
 
 
 def sketch_linear_gemm(layer: int, X: int, x_dtype: int, ldx: int, Y: int, y_dtype: int, ldy: int, tokens: int,

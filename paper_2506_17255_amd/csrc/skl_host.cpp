@@ -606,6 +606,22 @@ skl_status_t sketch_linear_gemv(const skl_layer_t *L, const void *x, skl_dtype_t
     return skl_launch_gemv(L, x, ldx, y, y_dt, ldy, batch, ws, stream, true);
 }
 
+skl_status_t sketch_linear_gemv_static(const skl_layer_t *L, const void *x, skl_dtype_t x_dt, uint32_t ldx, void *y,
+                                       skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *stream)
+{
+    if (!L) FAIL(SKL_ERR_INVALID_ARG, "layer is NULL");
+    if (batch < 1 || batch > 16) FAIL(SKL_ERR_INVALID_ARG, "batch = %u, must be 1..16", batch);
+    if (x_dt != SKL_F16) FAIL(SKL_ERR_UNSUPPORTED, "gemv activations must be binary16");
+    if (y_dt != SKL_F16 && y_dt != SKL_F32) FAIL(SKL_ERR_UNSUPPORTED, "gemv output must be binary16 or float32");
+    const uint64_t need = skl_gemv_workspace_bytes(L, batch);
+    if (need > skl_static_scratch_bytes())
+        FAIL(SKL_ERR_UNSUPPORTED, "this call needs %llu bytes of scratch, the static array holds %llu; use sketch_linear_gemv",
+             (unsigned long long)need, (unsigned long long)skl_static_scratch_bytes());
+    skl_status_t st = check_io(L, x, ldx, 2, y, ldy, dtype_size(y_dt), batch, nullptr, 0, 0);
+    if (st != SKL_OK) return st;
+    return skl_launch_gemv_static(L, x, ldx, y, y_dt, ldy, batch, stream);
+}
+
 skl_status_t sketch_linear_gemv_partials(const skl_layer_t *L, const void *x, skl_dtype_t x_dt, uint32_t ldx,
                                          uint32_t batch, void *ws, uint64_t ws_bytes, void *stream)
 {

@@ -26,6 +26,8 @@
 // most blocks whose metadata it keeps in LDS.
 #define SKL_G2_SLOT_BYTES (4u * 8u * 34u * 16u)
 #define SKL_G2_MAX_BLOCKS 512u
+// file-scope device array behind sketch_linear_gemv_static: the workspace of one decode call
+#define SKL_STATIC_SCRATCH_BYTES SKL_STATIC_SCRATCH_MAX
 
 // ---- path 0: 2-D groups, one hash evaluation per weight and sketch row ----
 struct skl_group_meta {
@@ -172,6 +174,10 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X, skl_dtype_t x_dt
                              void *Y, skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, void *ws,
                              void *stream);
 uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch);
+// decode with the library's static device array as workspace (at most skl_static_scratch_bytes())
+uint64_t skl_static_scratch_bytes();
+skl_status_t skl_launch_gemv_static(const skl_layer *L, const void *x, uint32_t ldx, void *y, skl_dtype_t y_dt, uint32_t ldy,
+                                    uint32_t batch, void *stream);
 uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens);
 // decode of 1..4 row-sketch layers of one shape that share x; gate_up: n = 2 (gate, up), ys[0] receives SiLU(gate) * up
 uint64_t skl_gemv_group_workspace_bytes(const skl_layer *const *layers, uint32_t n, uint32_t batch);

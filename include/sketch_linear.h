@@ -86,7 +86,11 @@ typedef struct {
     uint32_t d;                /* sketch rows, 1..8 */
     uint32_t query_mode;       /* 0 = magnitude Max as described above; others reserved */
     uint32_t flags;            /* bit 0: always hash per weight (path 0) even when the geometry
-                                  allows the row-sketch path; other bits must be 0 */
+                                  allows the row-sketch path; bit 1: row sketches take the staged
+                                  prefill (SKL_PREFILL_STAGED) at every token count; bit 2: they take
+                                  the fused prefill whenever their tables allow (bits 1 and 2 exclude
+                                  each other; without either the library chooses per call); other bits
+                                  must be 0 */
     const uint32_t *hash_a;    /* [d], each < 2^24 */
     const uint32_t *hash_c;    /* [d], each < 2^24 */
     const uint32_t *group_width; /* [(in/tile_in) * (out/tile_out)], each 1..65535 */
@@ -123,9 +127,11 @@ typedef struct {
     uint32_t decode_groups;    /* path 1: block groups of the decode plan (= n_units) */
     uint32_t block_classes;    /* path 1: bit i set when some channel block has 2^i 16-byte words per
                                   state row (8 * 2^i input channels per block) */
-    uint32_t prefill_kernel;   /* what sketch_linear_gemm runs: SKL_PREFILL_* */
+    uint32_t prefill_kernel;   /* what sketch_linear_gemm runs on calls with fewer than
+                                  prefill_staged_from tokens: SKL_PREFILL_* */
     uint32_t n_blocks;         /* path 1: channel blocks */
-    uint32_t reserved;
+    uint32_t prefill_staged_from; /* row sketches: calls with at least this many tokens take
+                                  SKL_PREFILL_STAGED (0: every call, 0xFFFFFFFF: none) */
 } skl_info_t;
 
 #define SKL_INFO_SIZE_V1 40u
@@ -134,8 +140,9 @@ typedef struct {
 #define SKL_PREFILL_PER_WEIGHT 0u   /* 2-D groups: weights hashed one by one, 64 x 64 tiles */
 #define SKL_PREFILL_FUSED 3u        /* row sketches, tables of two blocks resident in LDS: weights rebuilt
                                        between the matrix instructions of a 256 x 256 tile */
-#define SKL_PREFILL_STAGED 4u       /* row sketches with larger tables: weights rebuilt once per call into a
-                                       cache-sized slab of the workspace, then a 256 x 256-tile product */
+#define SKL_PREFILL_STAGED 4u       /* row sketches with larger tables, and long calls: weights rebuilt once per
+                                       call into a cache-sized slab of the workspace, then a 256 x 256-tile
+                                       product */
 
 /* Bytes of device memory create() needs for this description.
  * Validates the whole description (Sec. 3.1 states must be finite). */
@@ -236,21 +243,28 @@ SKL_API skl_status_t sketch_linear_gemm(const skl_layer_t *layer, const void *X,
 
 /* Diagnostic, host only (no GPU call): how sketch_linear_gemm divides a
  * prefill of `tokens` tokens through a row-sketch layer with `out_features`
- * outputs and `n_blocks` input-channel blocks over the workgroups of its main
- * kernel.  Output tiles are 256 tokens x 256 outputs; every (tile, block)
- * product belongs to exactly one segment.  Each segment is eight words in
- * `segments` (HOST, room for `capacity` segments): XCD, workgroup within the
- * XCD, token tile, output tile, first block, end block, 1 if the segment is a
- * whole tile (stored directly) else 0, and the float32 partial-tile slot a
- * partial segment leaves for the fix-up pass (partials of one tile occupy
- * consecutive slots in workgroup order, which fixes the summation order).
+ * outputs over the workgroups of its main kernel.  `kernel` is
+ * SKL_PREFILL_FUSED (a block is one input-channel block of the layer) or
+ * SKL_PREFILL_STAGED (a block is 64 entries of the layer's channel list);
+ * `n_blocks` is the number of such blocks.  Output tiles are 256 tokens x 256
+ * outputs; every (tile, block) product belongs to exactly one segment.  Each
+ * segment is eight words in `segments` (HOST, room for `capacity` segments):
+ * XCD, workgroup within the XCD, token tile, output tile, first block, end
+ * block, 1 if the segment is a whole tile stored by the main kernel else 0,
+ * and the float32 partial-tile slot a partial segment leaves for the fix-up
+ * pass (partials of one tile occupy consecutive slots in workgroup order,
+ * which fixes the summation order).  Tiles are dealt to the 8 XCDs in units
+ * of mu token tiles of one output-tile column, unit
+ * u = output tile * (token tiles / mu) + token tile / mu to XCD u % 8; the
+ * fused kernel has mu = 1, the staged kernel the largest mu that keeps the
+ * XCDs balanced.
  * *n_segments receives the number of segments (also when it exceeds
  * `capacity`; then only the first `capacity` are written).  `shape` (HOST,
- * 4 words, may be NULL) receives workgroups per XCD, partial tiles per XCD,
- * slots per partial tile, and the tile count. */
-SKL_API skl_status_t sketch_linear_prefill_split(uint32_t out_features, uint32_t n_blocks, uint32_t tokens,
-                                         uint32_t *segments, uint64_t capacity, uint64_t *n_segments,
-                                         uint32_t *shape);
+ * 5 words, may be NULL) receives workgroups per XCD, partial tiles per XCD,
+ * slots per partial tile, the tile count, and mu. */
+SKL_API skl_status_t sketch_linear_prefill_split(uint32_t kernel, uint32_t out_features, uint32_t n_blocks,
+                                         uint32_t tokens, uint32_t *segments, uint64_t capacity,
+                                         uint64_t *n_segments, uint32_t *shape);
 
 /* Sketch construction on the device (Sec. 3.1, Eq. 4: a state keeps the
  * weight of smallest magnitude that maps to it, the first one in address order

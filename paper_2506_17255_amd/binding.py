@@ -24,6 +24,8 @@ SKL_ERR_NO_MEMORY = 6
 
 SKL_F16, SKL_BF16, SKL_F32 = 0, 1, 2
 FLAG_HASH_PER_WEIGHT = 1
+FLAG_STAGED_PREFILL = 2
+FLAG_FUSED_PREFILL = 4
 
 STATUS_NAMES = {0: "SKL_OK", 1: "SKL_ERR_INVALID_ARG", 2: "SKL_ERR_UNSUPPORTED",
                 3: "SKL_ERR_BUFFER_TOO_SMALL", 4: "SKL_ERR_NONFINITE", 5: "SKL_ERR_HIP",
@@ -73,7 +75,7 @@ class skl_info_t(ctypes.Structure):
                 # end of the first version of the struct (SKL_INFO_SIZE_V1 bytes)
                 ("decode_segments", ctypes.c_uint32), ("decode_groups", ctypes.c_uint32),
                 ("block_classes", ctypes.c_uint32), ("prefill_kernel", ctypes.c_uint32),
-                ("n_blocks", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("n_blocks", ctypes.c_uint32), ("prefill_staged_from", ctypes.c_uint32)]
 
 
 SKL_INFO_SIZE_V1 = 40
@@ -101,7 +103,7 @@ def load_library(path: str | None = None):
     L.sketch_linear_gemm.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_reconstruct.argtypes = [vp, vp, vp, u64, vp]
     L.sketch_linear_gemv_partials.argtypes = [vp, vp, ctypes.c_int, u32, u32, vp, u64, vp]
-    L.sketch_linear_prefill_split.argtypes = [u32, u32, u32, ctypes.POINTER(u32), u64, ctypes.POINTER(u64),
+    L.sketch_linear_prefill_split.argtypes = [u32, u32, u32, u32, ctypes.POINTER(u32), u64, ctypes.POINTER(u64),
                                               ctypes.POINTER(u32)]
     L.sketch_linear_build_workspace_bytes.argtypes = [ctypes.POINTER(skl_desc_t), ctypes.POINTER(u64)]
     L.sketch_linear_build_states.argtypes = [ctypes.POINTER(skl_desc_t), vp, vp, vp, u64, vp]
@@ -221,16 +223,16 @@ def sketch_linear_gemv_partials(layer: int, x: int, x_dtype: int, ldx: int, batc
                                                       hip_stream))
 
 
-def sketch_linear_prefill_split(out_features: int, n_blocks: int, tokens: int):
+def sketch_linear_prefill_split(out_features: int, n_blocks: int, tokens: int, kernel: int = SKL_PREFILL_FUSED):
     """Host only.  Returns (segments, shape): segments is a list of 8-tuples (xcd, workgroup, token tile,
     output tile, first block, end block, whole, slot), shape is (workgroups per XCD, partial tiles per XCD,
-    slots per partial tile, tiles)."""
+    slots per partial tile, tiles, token tiles per dealing unit)."""
     L = load_library()
     n = ctypes.c_uint64(0)
-    shape = (ctypes.c_uint32 * 4)()
-    _check(L.sketch_linear_prefill_split(out_features, n_blocks, tokens, None, 0, ctypes.byref(n), shape))
+    shape = (ctypes.c_uint32 * 5)()
+    _check(L.sketch_linear_prefill_split(kernel, out_features, n_blocks, tokens, None, 0, ctypes.byref(n), shape))
     buf = (ctypes.c_uint32 * (8 * max(n.value, 1)))()
-    _check(L.sketch_linear_prefill_split(out_features, n_blocks, tokens, buf, n.value, ctypes.byref(n), shape))
+    _check(L.sketch_linear_prefill_split(kernel, out_features, n_blocks, tokens, buf, n.value, ctypes.byref(n), shape))
     segs = [tuple(buf[8 * i:8 * i + 8]) for i in range(n.value)]
     return segs, tuple(shape)
 

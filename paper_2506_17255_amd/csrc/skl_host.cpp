@@ -68,7 +68,8 @@ static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out, b
         FAIL(SKL_ERR_INVALID_ARG, "group of %ux%u weights exceeds 2^24 addresses", d->tile_in, d->tile_out);
     if (d->d < 1 || d->d > SKL_MAX_D) FAIL(SKL_ERR_INVALID_ARG, "d = %u sketch rows, must be 1..8", d->d);
     if (d->query_mode != 0) FAIL(SKL_ERR_UNSUPPORTED, "query_mode %u is reserved", d->query_mode);
-    if (d->flags & ~1u) FAIL(SKL_ERR_INVALID_ARG, "unknown bits in flags: 0x%x", d->flags);
+    if (d->flags & ~7u) FAIL(SKL_ERR_INVALID_ARG, "unknown bits in flags: 0x%x", d->flags);
+    if ((d->flags & 6u) == 6u) FAIL(SKL_ERR_INVALID_ARG, "flags ask for the staged and for the fused prefill at once");
     if (d->state_bits != 0 && d->state_bits != 16 && d->state_bits != 8 && d->state_bits != 4)
         FAIL(SKL_ERR_INVALID_ARG, "state_bits = %u, must be 0, 16, 8 or 4", d->state_bits);
     if (d->reserved != 0) FAIL(SKL_ERR_INVALID_ARG, "desc.reserved must be 0");
@@ -210,43 +211,11 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
            (L.two_bufs || (uint64_t)L.max_table_bytes + act <= SKL_LDS_HARD_BYTES);
 }
 
-// Prefill plan for row sketches.  LDS holds two table buffers (one if the
-// tables are too large) and a ring of activation tiles of 256 rows x uw words;
-// 8-word units with a ring of at least three tiles when that fits, else
-// 4-word units.  A deeper ring hides more of the global -> LDS latency.
+// Prefill plan for row sketches: the 16-channel step lists of the two kernels and which one a call takes.
 static void plan_prefill(const skl_desc_t *d, skl_plan *P)
 {
     skl_layer &L = P->L;
-    const uint64_t tab = L.max_table_bytes;
-    auto ring_for = [&](uint32_t uw, uint32_t n_tab) -> uint32_t {
-        const uint64_t tile = 256ull * uw * 16;
-        if (n_tab * tab + 2 * tile > SKL_LDS_HARD_BYTES) return 0;
-        return (uint32_t)std::min<uint64_t>(4, (SKL_LDS_HARD_BYTES - n_tab * tab) / tile);
-    };
-    // no wider than the words per state row of the class that holds most channels
-    uint32_t nb_main = 1, best_count = 0;
-    for (uint32_t nb : {1u, 2u, 4u, 8u}) {
-        uint32_t count = 0;
-        for (const skl_block_meta &bm : P->bmeta) count += bm.nb == nb ? bm.nb : 0;
-        if (count > best_count) { best_count = count; nb_main = nb; }
-    }
-    uint32_t uw = std::min(8u, std::max(nb_main, 2u)), two = 1, ring = ring_for(uw, 2);
-    if (ring < 3 && uw == 8) { uw = 4; ring = ring_for(4, 2); }
-    if (ring < 2) { two = 0; uw = std::min(uw, 4u); ring = ring_for(uw, 1); }
-    L.gemm_uw = uw; L.gemm_ring = ring; L.gemm_two_tabs = two;
-    P->gunits.clear();
-    for (size_t b = 0; b < P->bmeta.size(); ++b) {
-        const skl_block_meta &bm = P->bmeta[b];
-        const bool has_next = b + 1 < P->bmeta.size();
-        const uint32_t nt_off = has_next ? P->bmeta[b + 1].table_off16 : 0;
-        const uint32_t nt_words = has_next ? d->d * P->bmeta[b + 1].K * P->bmeta[b + 1].rs : 0;
-        for (uint32_t c = 0; c < bm.nb; c += uw)
-            P->gunits.push_back(skl_gemm_unit{bm.chan_off + 8 * c, std::min(bm.nb - c, uw), c, bm.K, bm.rs,
-                                              bm.table_off16, c == 0 ? 1u : 0u, c == 0 ? nt_off : 0u,
-                                              c == 0 ? nt_words : 0u, 0u});
-    }
-    L.n_gunits = (uint32_t)P->gunits.size();
-    // step list of the second kernel: ceil(nb / 2) steps of 16 channels per block
+    // fused kernel: ceil(nb / 2) steps of 16 channels per block, in block order
     P->gsteps.clear();
     for (skl_block_meta &bm : P->bmeta) {
         bm.step_off = (uint32_t)P->gsteps.size();
@@ -254,13 +223,24 @@ static void plan_prefill(const skl_desc_t *d, skl_plan *P)
             P->gsteps.push_back(skl_gemm_step{bm.chan_off + 8 * c, std::min(bm.nb - c, 2u)});
     }
     L.n_gsteps = (uint32_t)P->gsteps.size();
-    L.gemm_ns = 1;
-    for (const skl_block_meta &bm : P->bmeta) L.gemm_ns = std::max(L.gemm_ns, (bm.nb + 1) / 2);
-    // third kernel: operand slots of 8 column blocks (34816 B each), a 1 KiB dummy row, tables of at most 48 chunks
+    // the fused kernel keeps two block tables (at most 48 chunks of 1 KiB each), two operand slots of 8 column
+    // blocks (34816 B each), a 1 KiB dummy row and the block metadata in LDS
     L.gemm_v3 = L.max_ptable_bytes <= 48 * 1024 &&
                 2ull * L.max_ptable_bytes + 2ull * 34816 + 1024 + 32ull * P->bmeta.size() + 256 <= SKL_LDS_HARD_BYTES ? 1 : 0;
-    L.gemm_v2 = P->bmeta.size() <= SKL_G2_MAX_BLOCKS &&
-                2ull * L.max_ptable_bytes + 2ull * SKL_G2_SLOT_BYTES + 32ull * P->bmeta.size() + 256 <= SKL_LDS_HARD_BYTES ? 1 : 0;
+    // staged kernel: dense 16-entry steps along the channel list, four per 64-channel block; entries past
+    // the end of the list are empty steps (zero activation words)
+    L.gemm_kb = (L.n_packed + 63) / 64;
+    P->ssteps.clear();
+    for (uint32_t st = 0; st < 4 * L.gemm_kb; ++st) {
+        const uint32_t c0 = 16 * st;
+        P->ssteps.push_back(skl_gemm_step{std::min(c0, L.n_packed), c0 >= L.n_packed ? 0u : std::min(2u, (L.n_packed - c0) / 8)});
+    }
+    // Which kernel a call takes.  Layers whose tables the fused kernel cannot keep in LDS always rebuild
+    // their weights once per call.  The others do so from 513 tokens on: measured on MI355X
+    // (4096 x 4096 and 4096 x 11008, 0.5 bit/weight) the two kernels tie up to 512 tokens, where a call
+    // is a single round of tiles either way, and the staged one is 10 % faster at 1024 tokens and 25 % at
+    // 2048.  flags bit 1: always staged; bit 2: fused whenever the tables allow.
+    L.gemm_staged_from = !L.gemm_v3 || (d->flags & 2u) ? 0u : (d->flags & 4u) ? 0xFFFFFFFFu : 513u;
 }
 
 // Row-sketch plan.  Returns false when some width is too large for any block
@@ -405,8 +385,8 @@ static skl_status_t make_plan(const skl_desc_t *user, skl_plan *P)
         L.off_bmeta = off;  off = align_up(off + P->bmeta.size() * sizeof(skl_block_meta), 256);
         L.off_chan = off;   off = align_up(off + P->chan.size() * sizeof(uint32_t), 256);
         L.off_ginfo = off;  off = align_up(off + P->ginfo.size() * sizeof(skl_group_info), 256);
-        L.off_gunits = off; off = align_up(off + P->gunits.size() * sizeof(skl_gemm_unit), 256);
         L.off_gsteps = off; off = align_up(off + P->gsteps.size() * sizeof(skl_gemm_step), 256);
+        L.off_ssteps = off; off = align_up(off + P->ssteps.size() * sizeof(skl_gemm_step), 256);
         if (!L.qbits) {
             L.off_tables = off; off = align_up(off + L.table_bytes, 256);
             L.off_ptables = off; off = align_up(off + L.ptable_bytes, 256);
@@ -473,8 +453,8 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         memcpy(img.data() + L.off_bmeta, P.bmeta.data(), P.bmeta.size() * sizeof(skl_block_meta));
         memcpy(img.data() + L.off_chan, P.chan.data(), P.chan.size() * sizeof(uint32_t));
         memcpy(img.data() + L.off_ginfo, P.ginfo.data(), P.ginfo.size() * sizeof(skl_group_info));
-        memcpy(img.data() + L.off_gunits, P.gunits.data(), P.gunits.size() * sizeof(skl_gemm_unit));
         memcpy(img.data() + L.off_gsteps, P.gsteps.data(), P.gsteps.size() * sizeof(skl_gemm_step));
+        memcpy(img.data() + L.off_ssteps, P.ssteps.data(), P.ssteps.size() * sizeof(skl_gemm_step));
         // state offset of every input channel (one group per channel)
         for (uint32_t j = 0; j < L.in; ++j) base[j + 1] = base[j] + (uint64_t)L.d * desc->group_width[j];
         if (L.qbits) {
@@ -538,9 +518,9 @@ skl_status_t sketch_linear_info(const skl_layer_t *L, skl_info_t *info)
     info->decode_segments = L->path == 1 ? L->n_sseg : 0;
     info->decode_groups = L->path == 1 ? L->n_bg : 0;
     info->block_classes = L->block_classes;
-    info->prefill_kernel = L->path == 1 ? (L->gemm_v3 ? SKL_PREFILL_FUSED : L->gemm_v2 ? 2u : 1u) : SKL_PREFILL_PER_WEIGHT;
+    info->prefill_kernel = L->path == 1 ? (L->gemm_staged_from == 0 ? SKL_PREFILL_STAGED : SKL_PREFILL_FUSED) : SKL_PREFILL_PER_WEIGHT;
     info->n_blocks = L->path == 1 ? L->n_blocks : 0;
-    info->reserved = 0;
+    info->prefill_staged_from = L->path == 1 ? L->gemm_staged_from : 0xFFFFFFFFu;
     return SKL_OK;
 }
 
@@ -767,14 +747,16 @@ skl_status_t sketch_linear_build_states(const skl_desc_t *user, const uint16_t *
     return skl_launch_build(&d, n_groups, base.data(), W_dev, states_dev, ws, stream_);
 }
 
-skl_status_t sketch_linear_prefill_split(uint32_t out_features, uint32_t n_blocks, uint32_t tokens, uint32_t *segments,
-                                         uint64_t capacity, uint64_t *n_segments, uint32_t *shape)
+skl_status_t sketch_linear_prefill_split(uint32_t kernel, uint32_t out_features, uint32_t n_blocks, uint32_t tokens,
+                                         uint32_t *segments, uint64_t capacity, uint64_t *n_segments, uint32_t *shape)
 {
+    if (kernel != SKL_PREFILL_FUSED && kernel != SKL_PREFILL_STAGED)
+        FAIL(SKL_ERR_INVALID_ARG, "kernel = %u, must be SKL_PREFILL_FUSED or SKL_PREFILL_STAGED", kernel);
     if (!n_segments) FAIL(SKL_ERR_INVALID_ARG, "n_segments is NULL");
     if (!segments && capacity) FAIL(SKL_ERR_INVALID_ARG, "segments is NULL with a non-zero capacity");
     if (out_features < 1 || n_blocks < 1 || tokens < 1) FAIL(SKL_ERR_INVALID_ARG, "out_features, n_blocks and tokens must be positive");
     if (tokens > (1u << 24)) FAIL(SKL_ERR_UNSUPPORTED, "more than 2^24 tokens in one call");
-    *n_segments = skl_gemm3_segments(out_features, n_blocks, tokens, segments, capacity, shape);
+    *n_segments = skl_gemm3_segments(out_features, n_blocks, tokens, kernel == SKL_PREFILL_STAGED, segments, capacity, shape);
     return SKL_OK;
 }
 

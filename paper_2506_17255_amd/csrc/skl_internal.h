@@ -21,11 +21,6 @@
 // Distance between the two table buffers of the batch-1 decode kernel: below
 // 2^16, so that the buffer is chosen by the offset field of the LDS reads.
 #define SKL_PBUF_DIST 65280u
-// Second prefill kernel: bytes of one reconstructed-operand slot (4 column
-// blocks x 8 rows of 32 lanes x 16 bytes, rows padded to 34 words) and the
-// most blocks whose metadata it keeps in LDS.
-#define SKL_G2_SLOT_BYTES (4u * 8u * 34u * 16u)
-#define SKL_G2_MAX_BLOCKS 512u
 // file-scope device array behind sketch_linear_gemv_static: the workspace of one decode call
 #define SKL_STATIC_SCRATCH_BYTES SKL_STATIC_SCRATCH_MAX
 
@@ -60,19 +55,6 @@ struct skl_group_info {
     uint32_t b_lo, b_hi, c_lo, c_hi;
     uint32_t K0, rs0, table_off16_0, chan_off0;
     uint32_t ptable_off16_0, pad0, pad1, pad2;
-};
-
-// One unit of the prefill walk over the channel blocks: `w` 16-byte words
-// (8*w channels) of one block, starting at word c_base of its state rows.
-struct skl_gemm_unit {
-    uint32_t chan0;        // first entry of the unit in the channel list
-    uint32_t w;            // words in the unit (1, 2, 4 or 8; at most gemm_uw)
-    uint32_t c_base;       // first word inside the block's state rows
-    uint32_t K, rs;        // width class of the block
-    uint32_t table_off16;  // the block's table
-    uint32_t first;        // 1: the unit opens its block (a new table)
-    uint32_t next_table_off16, next_table_words;   // units that open a block: the following block's table (0 words: none)
-    uint32_t pad;
 };
 
 // One 16-channel step of the prefill walk: two 16-byte words of a block (one
@@ -117,15 +99,14 @@ struct skl_layer {
     uint32_t two_bufs = 1;          // double-buffered tables fit in LDS (batched decode, padded tables)
     uint32_t two_pbufs = 1;         // the same for the batch-1 kernel and the unpadded tables
     uint64_t off_ginfo = 0;
-    // prefill plan: unit width (words), activation ring depth, unit list
-    uint32_t gemm_uw = 0, gemm_ring = 0, gemm_two_tabs = 0, n_gunits = 0;
-    uint64_t off_gunits = 0;
-    // second prefill kernel (weights rebuilt once per workgroup by producer
-    // wavefronts): usable when two unpadded tables, two operand slots and the
-    // block metadata fit in LDS
-    uint32_t gemm_v3 = 0;     // third prefill kernel (256 x 256 tile): two tables and two wide operand slots fit in LDS, at most 12 KiB of table per wavefront
-    uint32_t gemm_v2 = 0, n_gsteps = 0, gemm_ns = 1;   // gemm_ns: steps per block of the widest class
+    // fused prefill kernel (256 x 256 tile, weights rebuilt between the matrix instructions): usable when two
+    // unpadded block tables (at most 48 KiB each), two operand slots and the block metadata fit in LDS
+    uint32_t gemm_v3 = 0, n_gsteps = 0;
     uint64_t off_gsteps = 0;
+    // staged prefill (weights rebuilt once per call into the workspace): 64-channel blocks along the channel
+    // list, and its dense step list (4 steps of 16 list entries per block)
+    uint32_t gemm_staged_from = 0, gemm_kb = 0;     // calls with at least gemm_staged_from tokens are staged
+    uint64_t off_ssteps = 0;
 
     // low-bit states: only codes, scales and (path 1) the state offset of every input channel are
     // resident; every call expands them into 16-bit tables at the end of its workspace
@@ -144,9 +125,11 @@ struct skl_plan {
     std::vector<uint32_t> chan;
     std::vector<uint32_t> bg_start;
     std::vector<skl_group_info> ginfo;
-    std::vector<skl_gemm_unit> gunits;
     std::vector<skl_gemm_step> gsteps;
+    std::vector<skl_gemm_step> ssteps;
 };
+
+static inline bool skl_gemm_is_staged(const skl_layer *L, uint32_t tokens) { return tokens >= L->gemm_staged_from; }
 
 // error text of the calling thread
 void skl_set_error(const char *fmt, ...);
@@ -186,4 +169,5 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
 // sketch construction: group_base holds n_groups + 1 state offsets (host); synchronises the stream once
 skl_status_t skl_launch_build(const skl_desc_t *d, uint64_t n_groups, const uint64_t *group_base, const uint16_t *W,
                               uint16_t *states, void *ws, void *stream);
-uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, uint32_t *segs, uint64_t cap, uint32_t *shape);
+uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, bool by_col, uint32_t *segs, uint64_t cap,
+                            uint32_t *shape);

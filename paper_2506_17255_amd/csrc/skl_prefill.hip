@@ -31,71 +31,14 @@ __global__ __launch_bounds__(SKL_WG) void k_pack_activations2(const uint16_t *__
     Xp[(((size_t)tile_m * n_steps + step) * 8 + rb) * 64 + q * 32 + n] = w;
 }
 
-// The same re-ordering with the rows staged in LDS: a workgroup reads TOK whole token rows with
-// coalesced loads (converting them to negated binary16 once), then gathers every step's channels from
-// LDS.
-// grid (ceil(tokens / TOK)); TOK divides 32; LDS TOK * (in + 4) * 2 bytes.
+// the re-ordering with the rows staged in LDS (pack_rows_lds); grid (ceil(tokens / TOK))
 template <int TOK>
 __global__ __launch_bounds__(SKL_WG) void k_pack_activations3(const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
                                                                uint32_t tokens, uint32_t in, const uint32_t *__restrict__ chan,
                                                                const skl_gemm_step *__restrict__ steps, uint32_t n_steps,
                                                                uint4 *__restrict__ Xp)
 {
-    uint16_t *rows = reinterpret_cast<uint16_t *>(smem);
-    const uint32_t stride = ((in + 1) & ~1u) + 2;               // elements: even, and off the power-of-two bank pattern
-    const uint32_t t_first = blockIdx.x * TOK;
-    const bool vec = ldx % 8 == 0;
-    for (uint32_t j = 0; j < TOK; ++j) {
-        const uint32_t t = t_first + j;
-        if (t >= tokens) break;
-        const uint16_t *src = X + (size_t)t * ldx;
-        uint16_t *dst = rows + j * stride;
-        if (vec) {
-            for (uint32_t c = threadIdx.x * 8; c < in; c += SKL_WG * 8) {
-                if (c + 8 <= in) {
-                    const uint4 w = *reinterpret_cast<const uint4 *>(src + c);
-                    const uint32_t e[4] = {w.x, w.y, w.z, w.w};
-                    uint32_t *d32 = reinterpret_cast<uint32_t *>(dst + c);      // rows and c are even: dword aligned
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        uint32_t lo = e[i] & 0xFFFFu, hi = e[i] >> 16;
-                        if (x_dt == SKL_BF16) {
-                            lo = float_to_half_bits(__builtin_bit_cast(float, lo << 16));
-                            hi = float_to_half_bits(__builtin_bit_cast(float, hi << 16));
-                        }
-                        d32[i] = (lo | (hi << 16)) ^ 0x80008000u;
-                    }
-                } else {
-                    for (uint32_t i = c; i < in; ++i) dst[i] = load_neg_half(src, x_dt, i);
-                }
-            }
-        } else {
-            for (uint32_t c = threadIdx.x; c < in; c += SKL_WG) dst[c] = load_neg_half(src, x_dt, c);
-        }
-    }
-    __syncthreads();
-    // a thread takes one 8-channel word position and fills it for all TOK tokens: its channel list is
-    // read once, and its TOK words are neighbours in the packed layout
-    const uint32_t tile_m = t_first / GM_MT, rb = (t_first % GM_MT) / 32, n0 = t_first % 32;
-    for (uint32_t item = threadIdx.x; item < 2 * n_steps; item += SKL_WG) {
-        const uint32_t step = item >> 1, q = item & 1;
-        const skl_gemm_step st = steps[step];
-        uint32_t ch[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) ch[i] = q < st.n_words ? chan[st.chan0 + 8 * q + i] : SKL_NO_CHANNEL;
-        uint4 *dst = Xp + (((size_t)tile_m * n_steps + step) * 8 + rb) * 64 + q * 32 + n0;
-#pragma unroll
-        for (uint32_t j = 0; j < TOK; ++j) {
-            const uint16_t *row = rows + j * stride;
-            uint16_t v[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = ch[i] != SKL_NO_CHANNEL && t_first + j < tokens ? row[ch[i]] : (uint16_t)0;
-            uint4 w;
-            w.x = v[0] | ((uint32_t)v[1] << 16); w.y = v[2] | ((uint32_t)v[3] << 16);
-            w.z = v[4] | ((uint32_t)v[5] << 16); w.w = v[6] | ((uint32_t)v[7] << 16);
-            dst[j] = w;
-        }
-    }
+    pack_rows_lds<TOK>(blockIdx.x, X, x_dt, ldx, tokens, in, chan, steps, n_steps, Xp);
 }
 
 
@@ -110,151 +53,6 @@ __global__ __launch_bounds__(SKL_WG) void k_pack_activations3(const uint16_t *__
 // fetches the table of block k+2 through registers and requests its
 // activation words two blocks ahead.  Blocks with fewer than eight words per
 // state row are rebuilt before the MFMAs instead (rare classes).
-#define GM3_NT 256
-#define G3_CB_WORDS (8u * G2_ROW)
-#define G3_SLOT_BYTES (8u * G3_CB_WORDS * 16u)
-
-// Work split of the third kernel.  Tile t = tile_n * m_tiles + tile_m belongs to XCD t % 8 (workgroup
-// ids go round the XCDs, so with eight or more token tiles an XCD keeps one token tile's activations
-// in its L2).  An XCD runs gx workgroups; its tiles are dealt out in rounds of gx whole tiles, and the
-// blocks of the tiles left over after the last whole round are cut into equal contiguous shares, one
-// per workgroup, so that every workgroup multiplies the same number of blocks (within one).  A share
-// that covers part of a tile leaves a float32 partial in the workspace; the fix-up kernel adds a
-// tile's partials in workgroup order, which keeps the result independent of timing.
-struct G3Split {
-    uint32_t T, m_tiles, nb, gx;        // tiles, token tiles, blocks per tile, workgroups per XCD
-    uint32_t l_max, p_cap;              // workspace slots: [xcd][l_max leftover tiles][p_cap parts]
-    __host__ __device__ uint32_t tiles_of(uint32_t x) const { return T > x ? (T - x + 7) / 8 : 0; }
-    __host__ __device__ uint32_t rounds(uint32_t x) const { return tiles_of(x) / gx; }
-    __host__ __device__ uint32_t left(uint32_t x) const { return tiles_of(x) - rounds(x) * gx; }
-    __host__ __device__ uint32_t units(uint32_t x) const { return left(x) * nb; }
-    // workgroups that take a share of the leftover units: every share holds at least one unit
-    __host__ __device__ uint32_t sharers(uint32_t x) const { const uint32_t u = units(x); return u < gx ? u : gx; }
-    __host__ __device__ uint32_t share_begin(uint32_t x, uint32_t j) const
-    {
-        const uint32_t g = sharers(x);
-        return j >= g ? units(x) : (uint32_t)(((uint64_t)j * units(x)) / g);
-    }
-    // the workgroup whose share holds unit v
-    __host__ __device__ uint32_t owner(uint32_t x, uint32_t v) const
-    {
-        return (uint32_t)((((uint64_t)v + 1) * sharers(x) - 1) / units(x));
-    }
-    __host__ __device__ uint32_t parts(uint32_t x, uint32_t l) const { return owner(x, (l + 1) * nb - 1) - owner(x, l * nb) + 1; }
-    __host__ __device__ size_t slot(uint32_t x, uint32_t l, uint32_t part) const { return ((size_t)x * l_max + l) * p_cap + part; }
-    // next segment of workgroup wg of XCD x: blocks [k0, k1) of the XCD's k-th tile.  round and u_next
-    // carry the position (start: 0 and share_begin(x, wg)); false when the workgroup is done.
-    struct Seg { uint32_t k, k0, k1, whole; size_t part_slot; };
-    __host__ __device__ bool next(uint32_t x, uint32_t wg, uint32_t &round, uint32_t &u_next, Seg &sg) const
-    {
-        const uint32_t n_rounds = rounds(x), u_end = share_begin(x, wg + 1);
-        sg.part_slot = 0;
-        if (round < n_rounds) {
-            sg.k = wg + round * gx; sg.k0 = 0; sg.k1 = nb; sg.whole = 1;
-            ++round;
-            return true;
-        }
-        if (u_next >= u_end) return false;
-        const uint32_t l = u_next / nb;
-        sg.k0 = u_next - l * nb;
-        sg.k1 = sg.k0 + (u_end - u_next) < nb ? sg.k0 + (u_end - u_next) : nb;
-        sg.k = n_rounds * gx + l;
-        // a share of the leftover tiles always leaves a partial, also when it happens to cover a whole
-        // tile: the fix-up pass stores every leftover tile from its slots
-        sg.whole = 0;
-        sg.part_slot = slot(x, l, wg - owner(x, l * nb));
-        u_next += sg.k1 - sg.k0;
-        return true;
-    }
-};
-#define G3_SLOT_FLOATS 65536u           // one 256 x 256 partial
-
-// One accumulator element, read where it is used.  Left to itself the compiler copies all 256
-// elements out of the accumulation registers after the block loop and parks half of them in scratch memory.
-__device__ __forceinline__ float acc_elem(float v)
-{
-    float r;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(v));
-    return r;
-}
-
-template <int DT>
-__device__ __forceinline__ void gemm3_store(const float16v (&acc)[16], void *Y, uint32_t ldy, uint32_t t0, uint32_t tokens,
-                                            uint32_t o0, uint32_t out, uint32_t q)
-{
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb) {
-        const uint32_t o = o0 + cb * 32;
-        if (o >= out) continue;
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const uint32_t t = t0 + rb * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
-                if (t < tokens) {
-                    const size_t idx = (size_t)t * ldy + o;
-                    const float v = acc_elem(acc[rb * 8 + cb][i]);
-                    if (DT == SKL_F32) static_cast<float *>(Y)[idx] = v;
-                    else if (DT == SKL_F16) static_cast<uint16_t *>(Y)[idx] = float_to_half_bits(v);
-                    else static_cast<uint16_t *>(Y)[idx] = float_to_bf16_bits(v);
-                }
-            }
-        }
-    }
-}
-
-// Row-major epilogue of the third kernel: a wavefront turns its 64 x 256 results round in a private LDS
-// area, one group of rows at a time, and stores 16-byte pieces, so that every store instruction writes
-// whole 512-byte (1 KiB for float32) rows of Y instead of 2-byte elements.  Needs 16-byte aligned rows.
-#define G3_EPI_BYTES 16896u             // per wavefront: 32 rows x (512 + 16) bytes, or 16 rows x (1024 + 16)
-static_assert(4 * G3_EPI_BYTES <= 2 * G3_SLOT_BYTES + 1024, "the epilogue areas must end below the block metadata");
-template <int DT>
-__device__ __forceinline__ void gemm3_store_rows(const float16v (&acc)[16], uint32_t lds_wave, void *Y, uint32_t ldy,
-                                                 uint32_t t0, uint32_t tokens, uint32_t o_tile, uint32_t out, uint32_t lane)
-{
-    constexpr uint32_t ES = DT == SKL_F32 ? 4 : 2;
-    constexpr uint32_t ROWB = 256 * ES + 16;                    // padded: the two token groups of a store land on other banks
-    constexpr int GROUPS = DT == SKL_F32 ? 2 : 1;               // row groups per 32-row block
-    constexpr uint32_t ROWS = 32 / GROUPS, CH = 256 * ES / 16;  // rows per group, 16-byte pieces per row
-    const uint32_t n = lane & 31, q = lane >> 5;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int gr = 0; gr < GROUPS; ++gr) {
-#pragma unroll
-            for (int cb = 0; cb < 8; ++cb)
-#pragma unroll
-                for (int ii = 0; ii < 16 / GROUPS; ++ii) {
-                    const int i = gr * (16 / GROUPS) + ii;
-                    const uint32_t row = (ii >> 2) * 8 + q * 4 + (ii & 3);
-                    const uint32_t addr = lds_wave + row * ROWB + (cb * 32 + n) * ES;
-                    const float v = acc_elem(acc[rb * 8 + cb][i]);
-                    if (DT == SKL_F32) *(__attribute__((address_space(3))) float *)(uintptr_t)addr = v;
-                    else *(__attribute__((address_space(3))) uint16_t *)(uintptr_t)addr =
-                        DT == SKL_F16 ? float_to_half_bits(v) : float_to_bf16_bits(v);
-                }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (uint32_t it = 0; it < ROWS * CH / 64; ++it) {
-                const uint32_t idx = it * 64 + lane, row = idx / CH, c = idx % CH;
-                const uint4 w = lds_word_at(lds_wave + row * ROWB + c * 16);
-                const uint32_t t = t0 + rb * 32 + gr * ROWS + row, o = o_tile + c * (16 / ES);
-                if (t < tokens && o < out) {
-                    char *dst = static_cast<char *>(Y) + ((size_t)t * ldy + o) * ES;
-                    if (o + 16 / ES <= out) {
-                        *reinterpret_cast<uint4 *>(dst) = w;
-                    } else {                                    // ragged last piece of the layer
-                        const uint32_t e[4] = {w.x, w.y, w.z, w.w};
-                        for (uint32_t b = 0; b < (out - o) * ES; b += 2)
-                            *reinterpret_cast<uint16_t *>(dst + b) = (uint16_t)(e[b >> 2] >> ((b & 2) * 8));
-                    }
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
-}
 
 template <int D>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_row_gemm3(Gemm2Args p)
@@ -262,6 +60,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const uint32_t xcd = blockIdx.x & 7, wg = blockIdx.x >> 3;
     G3Split sp;
     sp.T = p.T; sp.m_tiles = p.m_tiles; sp.nb = p.n_blocks; sp.gx = p.gx; sp.l_max = p.l_max; sp.p_cap = p.p_cap;
+    sp.mu = 1; sp.n_col = p.n_col;
     uint32_t round = 0, u_next = sp.share_begin(xcd, wg);
     if (sp.rounds(xcd) == 0 && u_next >= sp.share_begin(xcd, wg + 1)) return;
     const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -476,7 +275,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const uint32_t k = sg.k, k0 = sg.k0, k1 = sg.k1;
         const bool whole = sg.whole != 0;
         const size_t part_slot = sg.part_slot;
-        const uint32_t t = xcd + 8 * k, tile_m = t % p.m_tiles, tile_n = t / p.m_tiles;
+        uint32_t tile_m, tile_n;
+        sp.tile_of(xcd, k, tile_m, tile_n);
         t0 = tile_m * GM_MT + wave * 64;
         o_first = tile_n * GM3_NT + wave * 64;
         xa = p.Xp + ((size_t)tile_m * p.n_steps * 8 + wave * 2) * 64 + lane;
@@ -534,12 +334,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 // adds the partials of one accumulator block of a leftover tile in workgroup order and stores it;
 // grid (8 * l_max, 16), 256 threads laid out as in the third kernel
 __global__ __launch_bounds__(256) void k_gemm3_fixup(G3Split sp, const float *__restrict__ parts, void *Y, uint32_t y_dt,
-                                                     uint32_t ldy, uint32_t tokens, uint32_t out)
+                                                     uint32_t ldy, uint32_t tokens, uint32_t out, uint32_t tile0)
 {
     const uint32_t xcd = blockIdx.x / sp.l_max, l = blockIdx.x % sp.l_max, ab = blockIdx.y;
     if (l >= sp.left(xcd)) return;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 31, q = lane >> 5;
-    const uint32_t k = sp.rounds(xcd) * sp.gx + l, t = xcd + 8 * k, tile_m = t % sp.m_tiles, tile_n = t / sp.m_tiles;
+    uint32_t tile_m, tile_n;
+    sp.tile_of(xcd, sp.rounds(xcd) * sp.gx + l, tile_m, tile_n);
     const uint32_t n_parts = sp.parts(xcd, l);
     float4 v[4];
 #pragma unroll
@@ -554,7 +355,7 @@ __global__ __launch_bounds__(256) void k_gemm3_fixup(G3Split sp, const float *__
         }
     }
     const uint32_t rb = ab >> 3, cb = ab & 7;
-    const uint32_t o = tile_n * GM3_NT + cb * 32 + n;
+    const uint32_t o = (tile0 + tile_n) * GM3_NT + cb * 32 + n;    // tile0: first output tile of the slab the split covers
     if (o >= out) return;
 #pragma unroll
     for (int i4 = 0; i4 < 4; ++i4) {
@@ -571,32 +372,15 @@ __global__ __launch_bounds__(256) void k_gemm3_fixup(G3Split sp, const float *__
 // ========================================================================
 // Launchers
 // ========================================================================
-// split of the third prefill kernel for a call with this many tokens (256 CUs: 32 workgroups per XCD,
-// fewer when an XCD's share of the work is under four blocks per workgroup)
-static G3Split gemm3_split(const skl_layer *L, uint32_t tokens)
-{
-    G3Split sp;
-    sp.m_tiles = (tokens + GM_MT - 1) / GM_MT;
-    sp.T = sp.m_tiles * ((L->out + GM3_NT - 1) / GM3_NT);
-    sp.nb = L->n_blocks;
-    const uint64_t units0 = (uint64_t)((sp.T + 7) / 8) * sp.nb;
-    sp.gx = (uint32_t)std::min<uint64_t>(32, std::max<uint64_t>(1, units0 / 4));
-    sp.l_max = 0; sp.p_cap = 0;
-    for (uint32_t x = 0; x < 8; ++x) {
-        sp.l_max = std::max(sp.l_max, sp.left(x));
-        for (uint32_t l = 0; l < sp.left(x); ++l) sp.p_cap = std::max(sp.p_cap, sp.parts(x, l));
-    }
-    return sp;
-}
+static G3Split gemm3_split(const skl_layer *L, uint32_t tokens) { return skl_make_split(L->out, L->n_blocks, tokens, false); }
 
 // every segment of the split, eight words each: xcd, workgroup, token tile, output tile, first block,
 // end block, whole-tile flag, partial slot; returns the number of segments (writes at most cap of them)
-uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, uint32_t *segs, uint64_t cap, uint32_t *shape)
+uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, bool grouped, uint32_t *segs, uint64_t cap,
+                            uint32_t *shape)
 {
-    skl_layer L;
-    L.out = out; L.n_blocks = n_blocks;
-    const G3Split sp = gemm3_split(&L, tokens);
-    if (shape) { shape[0] = sp.gx; shape[1] = sp.l_max; shape[2] = sp.p_cap; shape[3] = sp.T; }
+    const G3Split sp = skl_make_split(out, n_blocks, tokens, grouped);
+    if (shape) { shape[0] = sp.gx; shape[1] = sp.l_max; shape[2] = sp.p_cap; shape[3] = sp.T; shape[4] = sp.mu; }
     uint64_t n = 0;
     for (uint32_t x = 0; x < 8; ++x)
         for (uint32_t wg = 0; wg < sp.gx; ++wg) {
@@ -604,10 +388,10 @@ uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, ui
             G3Split::Seg sg;
             while (sp.next(x, wg, round, u_next, sg)) {
                 if (n < cap) {
-                    const uint32_t t = x + 8 * sg.k;
                     uint32_t *o = segs + 8 * n;
-                    o[0] = x; o[1] = wg; o[2] = t % sp.m_tiles; o[3] = t / sp.m_tiles; o[4] = sg.k0; o[5] = sg.k1;
-                    o[6] = sg.whole; o[7] = (uint32_t)sg.part_slot;
+                    o[0] = x; o[1] = wg;
+                    sp.tile_of(x, sg.k, o[2], o[3]);
+                    o[4] = sg.k0; o[5] = sg.k1; o[6] = sg.whole; o[7] = (uint32_t)sg.part_slot;
                 }
                 ++n;
             }
@@ -618,20 +402,15 @@ uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, ui
 static uint64_t gemm_pack_bytes(const skl_layer *L, uint32_t tokens)
 {
     const uint64_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
-    // second and third kernel: 8 row blocks of 64 lanes x 16 bytes per (token tile, step);
-    // first kernel: one tile of 256 rows x gemm_uw words per (token tile, unit)
-    return L->gemm_v2 || L->gemm_v3 ? m_tiles * L->n_gsteps * 8192ull : m_tiles * L->n_gunits * GM_MT * L->gemm_uw * 16;
+    return m_tiles * L->n_gsteps * 8192ull;      // 8 row blocks of 64 lanes x 16 bytes per (token tile, step)
 }
 
 static uint64_t gemm_own_bytes(const skl_layer *L, uint32_t tokens)
 {
     if (L->path != 1) return 0;
-    uint64_t bytes = gemm_pack_bytes(L, tokens);
-    if (L->gemm_v3) {
-        const G3Split sp = gemm3_split(L, tokens);
-        bytes += 8ull * sp.l_max * sp.p_cap * G3_SLOT_FLOATS * sizeof(float);      // partial tiles
-    }
-    return bytes;
+    if (skl_gemm_is_staged(L, tokens)) return skl_gemm_staged_bytes(L, tokens);
+    const G3Split sp = gemm3_split(L, tokens);
+    return gemm_pack_bytes(L, tokens) + 8ull * sp.l_max * sp.p_cap * G3_SLOT_FLOATS * sizeof(float);      // + partial tiles
 }
 
 uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
@@ -643,7 +422,7 @@ uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
 // activation re-ordering for the second and third prefill kernels: rows staged in LDS when four
 // of them fit, else gathered from global memory
 skl_status_t skl_launch_pack(const skl_layer *L, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx, uint32_t tokens,
-                                const uint32_t *chan, const skl_gemm_step *steps, uint4 *Xp, hipStream_t stream)
+                             const uint32_t *chan, const skl_gemm_step *steps, uint32_t n_steps, uint4 *Xp, hipStream_t stream)
 {
     const uint32_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
     const size_t row_bytes = ((size_t)L->in + 4) * 2;           // an even number of elements plus one dword of padding
@@ -652,12 +431,19 @@ skl_status_t skl_launch_pack(const skl_layer *L, const uint16_t *X, skl_dtype_t 
         st = allow_lds(k_pack_activations3<4>, 4 * row_bytes);
         if (st != SKL_OK) return st;
         hipLaunchKernelGGL(k_pack_activations3<4>, dim3((tokens + 3) / 4), dim3(SKL_WG), 4 * row_bytes, stream, X, (uint32_t)x_dt,
-                           ldx, tokens, L->in, chan, steps, L->n_gsteps, Xp);
+                           ldx, tokens, L->in, chan, steps, n_steps, Xp);
     } else {
-        hipLaunchKernelGGL(k_pack_activations2, dim3((L->n_gsteps + 3) / 4, 8 * m_tiles), dim3(SKL_WG), 0, stream, X,
-                           (uint32_t)x_dt, ldx, tokens, chan, steps, L->n_gsteps, Xp);
+        hipLaunchKernelGGL(k_pack_activations2, dim3((n_steps + 3) / 4, 8 * m_tiles), dim3(SKL_WG), 0, stream, X,
+                           (uint32_t)x_dt, ldx, tokens, chan, steps, n_steps, Xp);
     }
     return check_launch("activation packing");
+}
+
+skl_status_t skl_launch_gemm3_fixup(const G3Split &sp, const float *parts, void *Y, skl_dtype_t y_dt, uint32_t ldy,
+                                    uint32_t tokens, uint32_t out, uint32_t tile0, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_gemm3_fixup, dim3(8 * sp.l_max, 16), dim3(256), 0, stream, sp, parts, Y, (uint32_t)y_dt, ldy, tokens, out, tile0);
+    return check_launch("gemm fix-up");
 }
 
 skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_dt, uint32_t ldx, void *Y,
@@ -665,10 +451,10 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const uint16_t *X = static_cast<const uint16_t *>(X_);
-    const bool rebuilt_once = L->gemm_v3 || L->gemm_v2;      // the kernels that read the unpadded tables
+    const bool staged = L->path == 1 && skl_gemm_is_staged(L, tokens);      // the rebuild kernel reads the padded tables, the fused kernel the unpadded ones
     TableSrc src;
     skl_status_t st = skl_table_source(L, static_cast<char *>(ws) + round256(gemm_own_bytes(L, tokens)),
-                                   L->path == 1 && !rebuilt_once, L->path == 1 && rebuilt_once, stream, &src);
+                                   L->path == 1 && staged, L->path == 1 && !staged, stream, &src);
     if (st != SKL_OK) return st;
     if (L->path == 1) {
         const RowArgs a = make_row_args(L, src);
@@ -677,9 +463,10 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
             skl_set_error("more than 8191 token tiles in one call");
             return SKL_ERR_UNSUPPORTED;
         }
-        if (L->gemm_v3) {
+        if (staged) return skl_launch_gemm_staged(L, src, X, x_dt, ldx, Y, y_dt, ldy, tokens, ws, stream);
+        {
             const skl_gemm_step *steps = reinterpret_cast<const skl_gemm_step *>(L->dev + L->off_gsteps);
-            st = skl_launch_pack(L, X, x_dt, ldx, tokens, a.chan, steps, static_cast<uint4 *>(ws), stream);
+            st = skl_launch_pack(L, X, x_dt, ldx, tokens, a.chan, steps, L->n_gsteps, static_cast<uint4 *>(ws), stream);
             if (st != SKL_OK) return st;
             Gemm2Args g;
             g.h = a.h; g.ptables = src.ptables; g.bmeta = a.bmeta;
@@ -699,13 +486,8 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
             })
             if (st == SKL_OK) st = check_launch("gemm");
             if (st != SKL_OK || sp.l_max == 0) return st;
-            hipLaunchKernelGGL(k_gemm3_fixup, dim3(8 * sp.l_max, 16), dim3(256), 0, stream, sp, g.parts, Y, (uint32_t)y_dt, ldy,
-                               tokens, L->out);
-            return check_launch("gemm fix-up");
+            return skl_launch_gemm3_fixup(sp, g.parts, Y, y_dt, ldy, tokens, L->out, 0, stream);
         }
-        return skl_launch_gemm_fallback(L, src, X, x_dt, ldx, Y, y_dt, ldy, tokens, ws, stream);
-    } else {
-        return skl_tile_launch_gemm(L, src, X, x_dt, ldx, Y, y_dt, ldy, tokens, stream);
     }
-    return st == SKL_OK ? check_launch("gemm") : st;
+    return skl_tile_launch_gemm(L, src, X, x_dt, ldx, Y, y_dt, ldy, tokens, stream);
 }

@@ -6,15 +6,82 @@
 struct skl_gemm_step;
 // activation re-ordering for the second and third prefill kernels (skl_prefill.hip)
 skl_status_t skl_launch_pack(const skl_layer *L, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx, uint32_t tokens,
-                             const uint32_t *chan, const skl_gemm_step *steps, uint4 *Xp, hipStream_t stream);
-// first and second prefill kernel (skl_prefill_fallback.hip)
-skl_status_t skl_launch_gemm_fallback(const skl_layer *L, const TableSrc &src, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx,
-                                      void *Y, skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, void *ws, hipStream_t stream);
+                             const uint32_t *chan, const skl_gemm_step *steps, uint32_t n_steps, uint4 *Xp, hipStream_t stream);
+// staged prefill (skl_prefill_staged.hip): workspace bytes of a call (activation words, partial tiles, weight words)
+uint64_t skl_gemm_staged_bytes(const skl_layer *L, uint32_t tokens);
+skl_status_t skl_launch_gemm_staged(const skl_layer *L, const TableSrc &src, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx,
+                                    void *Y, skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, void *ws, hipStream_t stream);
 
 #define GM_MT 256            // tokens per workgroup
 #define GM_NT 128            // outputs per workgroup
 #define GM_THREADS 512       // four compute + four copy wavefronts
 
+
+// Activation re-ordering with the rows staged in LDS: a workgroup reads TOK whole token rows with
+// coalesced loads (converting them to negated binary16 once), then gathers every step's channels from
+// LDS.  Workgroup `block` of ceil(tokens / TOK); TOK divides 32; LDS TOK * (in + 4) * 2 bytes.
+template <int TOK>
+__device__ __forceinline__ void pack_rows_lds(uint32_t block, const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
+                                              uint32_t tokens, uint32_t in, const uint32_t *__restrict__ chan,
+                                              const skl_gemm_step *__restrict__ steps, uint32_t n_steps,
+                                              uint4 *__restrict__ Xp)
+{
+    uint16_t *rows = reinterpret_cast<uint16_t *>(smem);
+    const uint32_t stride = ((in + 1) & ~1u) + 2;               // elements: even, and off the power-of-two bank pattern
+    const uint32_t t_first = block * TOK;
+    const bool vec = ldx % 8 == 0;
+    for (uint32_t j = 0; j < TOK; ++j) {
+        const uint32_t t = t_first + j;
+        if (t >= tokens) break;
+        const uint16_t *src = X + (size_t)t * ldx;
+        uint16_t *dst = rows + j * stride;
+        if (vec) {
+            for (uint32_t c = threadIdx.x * 8; c < in; c += SKL_WG * 8) {
+                if (c + 8 <= in) {
+                    const uint4 w = *reinterpret_cast<const uint4 *>(src + c);
+                    const uint32_t e[4] = {w.x, w.y, w.z, w.w};
+                    uint32_t *d32 = reinterpret_cast<uint32_t *>(dst + c);      // rows and c are even: dword aligned
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        uint32_t lo = e[i] & 0xFFFFu, hi = e[i] >> 16;
+                        if (x_dt == SKL_BF16) {
+                            lo = float_to_half_bits(__builtin_bit_cast(float, lo << 16));
+                            hi = float_to_half_bits(__builtin_bit_cast(float, hi << 16));
+                        }
+                        d32[i] = (lo | (hi << 16)) ^ 0x80008000u;
+                    }
+                } else {
+                    for (uint32_t i = c; i < in; ++i) dst[i] = load_neg_half(src, x_dt, i);
+                }
+            }
+        } else {
+            for (uint32_t c = threadIdx.x; c < in; c += SKL_WG) dst[c] = load_neg_half(src, x_dt, c);
+        }
+    }
+    __syncthreads();
+    // a thread takes one 8-channel word position and fills it for all TOK tokens: its channel list is
+    // read once, and its TOK words are neighbours in the packed layout
+    const uint32_t tile_m = t_first / GM_MT, rb = (t_first % GM_MT) / 32, n0 = t_first % 32;
+    for (uint32_t item = threadIdx.x; item < 2 * n_steps; item += SKL_WG) {
+        const uint32_t step = item >> 1, q = item & 1;
+        const skl_gemm_step st = steps[step];
+        uint32_t ch[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ch[i] = q < st.n_words ? chan[st.chan0 + 8 * q + i] : SKL_NO_CHANNEL;
+        uint4 *dst = Xp + (((size_t)tile_m * n_steps + step) * 8 + rb) * 64 + q * 32 + n0;
+#pragma unroll
+        for (uint32_t j = 0; j < TOK; ++j) {
+            const uint16_t *row = rows + j * stride;
+            uint16_t v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = ch[i] != SKL_NO_CHANNEL && t_first + j < tokens ? row[ch[i]] : (uint16_t)0;
+            uint4 w;
+            w.x = v[0] | ((uint32_t)v[1] << 16); w.y = v[2] | ((uint32_t)v[3] << 16);
+            w.z = v[4] | ((uint32_t)v[5] << 16); w.w = v[6] | ((uint32_t)v[7] << 16);
+            dst[j] = w;
+        }
+    }
+}
 
 // Operand slot: word (cb, row = 2*step + k-group, n) at ((cb*8 + row)*34 + n);
 // 34 instead of 32 words per row keeps the producers' scattered writes (eight
@@ -87,3 +154,206 @@ __device__ __forceinline__ void g2_build(const uint32_t (&off)[4][D], uint32_t t
     }
 }
 
+
+// ---- 256 x 256 output tiles: shared by the fused and the staged prefill kernel ----
+#define GM3_NT 256
+#define G3_CB_WORDS (8u * G2_ROW)
+#define G3_SLOT_BYTES (8u * G3_CB_WORDS * 16u)
+
+// Work split of the 256 x 256-tile kernels.  Workgroup ids go round the 8 XCDs (each with its own L2), so
+// XCD x runs the workgroups blockIdx.x % 8 == x, gx of them.  Tiles are dealt to the XCDs in units of mu
+// token tiles of one output-tile column (mu divides the number of token tiles): unit
+// u = tile_n * (m_tiles / mu) + token-tile group belongs to XCD u % 8.
+//   mu = 1 (fused kernel: every workgroup streams the same tables, only the activations differ by tile):
+//           tile t = tile_n * m_tiles + tile_m belongs to XCD t % 8, so with eight or more token tiles an
+//           XCD keeps one token tile's activations in its L2;
+//   mu > 1 (staged kernel: both operands come from memory): the workgroups of an XCD that run side by
+//           side share weight words as well as activation words; the largest mu that still balances the
+//           XCDs is taken (whole columns at best: 8 + 4 distinct operand streams for 32 workgroups at
+//           2048 tokens instead of 1 + 32).
+// An XCD's tiles are dealt out in rounds of gx whole tiles, and the blocks of the tiles left over after
+// the last whole round are cut into equal contiguous shares, one per workgroup, so that every workgroup
+// multiplies the same number of blocks (within one).  A share of a leftover tile leaves a float32 partial
+// in the workspace; the fix-up kernel adds a tile's partials in workgroup order, which keeps the result
+// independent of timing.
+struct G3Split {
+    uint32_t T, m_tiles, nb, gx;        // tiles, token tiles, blocks per tile, workgroups per XCD
+    uint32_t l_max, p_cap;              // workspace slots: [xcd][l_max leftover tiles][p_cap parts]
+    uint32_t mu, n_col;                 // token tiles per dealing unit; output tile columns
+    __host__ __device__ uint32_t tiles_of(uint32_t x) const
+    {
+        const uint32_t U = n_col * (m_tiles / mu);
+        return U > x ? mu * ((U - x + 7) / 8) : 0;
+    }
+    // the k-th tile of XCD x
+    __host__ __device__ void tile_of(uint32_t x, uint32_t k, uint32_t &tile_m, uint32_t &tile_n) const
+    {
+        const uint32_t n_mg = m_tiles / mu, u = x + 8 * (k / mu);
+        tile_n = u / n_mg;
+        tile_m = (u % n_mg) * mu + k % mu;
+    }
+    __host__ __device__ uint32_t rounds(uint32_t x) const { return tiles_of(x) / gx; }
+    __host__ __device__ uint32_t left(uint32_t x) const { return tiles_of(x) - rounds(x) * gx; }
+    __host__ __device__ uint32_t units(uint32_t x) const { return left(x) * nb; }
+    // workgroups that take a share of the leftover units: every share holds at least one unit
+    __host__ __device__ uint32_t sharers(uint32_t x) const { const uint32_t u = units(x); return u < gx ? u : gx; }
+    __host__ __device__ uint32_t share_begin(uint32_t x, uint32_t j) const
+    {
+        const uint32_t g = sharers(x);
+        return j >= g ? units(x) : (uint32_t)(((uint64_t)j * units(x)) / g);
+    }
+    // the workgroup whose share holds unit v
+    __host__ __device__ uint32_t owner(uint32_t x, uint32_t v) const
+    {
+        return (uint32_t)((((uint64_t)v + 1) * sharers(x) - 1) / units(x));
+    }
+    __host__ __device__ uint32_t parts(uint32_t x, uint32_t l) const { return owner(x, (l + 1) * nb - 1) - owner(x, l * nb) + 1; }
+    __host__ __device__ size_t slot(uint32_t x, uint32_t l, uint32_t part) const { return ((size_t)x * l_max + l) * p_cap + part; }
+    // next segment of workgroup wg of XCD x: blocks [k0, k1) of the XCD's k-th tile.  round and u_next
+    // carry the position (start: 0 and share_begin(x, wg)); false when the workgroup is done.
+    struct Seg { uint32_t k, k0, k1, whole; size_t part_slot; };
+    __host__ __device__ bool next(uint32_t x, uint32_t wg, uint32_t &round, uint32_t &u_next, Seg &sg) const
+    {
+        const uint32_t n_rounds = rounds(x), u_end = share_begin(x, wg + 1);
+        sg.part_slot = 0;
+        if (round < n_rounds) {
+            sg.k = wg + round * gx; sg.k0 = 0; sg.k1 = nb; sg.whole = 1;
+            ++round;
+            return true;
+        }
+        if (u_next >= u_end) return false;
+        const uint32_t l = u_next / nb;
+        sg.k0 = u_next - l * nb;
+        sg.k1 = sg.k0 + (u_end - u_next) < nb ? sg.k0 + (u_end - u_next) : nb;
+        sg.k = n_rounds * gx + l;
+        // a share of the leftover tiles always leaves a partial, also when it happens to cover a whole
+        // tile: the fix-up pass stores every leftover tile from its slots
+        sg.whole = 0;
+        sg.part_slot = slot(x, l, wg - owner(x, l * nb));
+        u_next += sg.k1 - sg.k0;
+        return true;
+    }
+};
+#define G3_SLOT_FLOATS 65536u           // one 256 x 256 partial
+
+// The split of a call: nb blocks per tile, 256 CUs = 32 workgroups per XCD (fewer when the busiest XCD's
+// share of the work is under four blocks per workgroup).  grouped: deal tiles in units of several token
+// tiles of one column -- the largest unit (halving from a whole column) whose busiest XCD is within 3 %
+// of the best.
+static inline G3Split skl_make_split(uint32_t out, uint32_t nb, uint32_t tokens, bool grouped)
+{
+    G3Split sp;
+    sp.m_tiles = (tokens + GM_MT - 1) / GM_MT;
+    sp.n_col = (out + GM3_NT - 1) / GM3_NT;
+    sp.T = sp.m_tiles * sp.n_col;
+    sp.nb = nb;
+    sp.mu = 1;
+    sp.gx = 1; sp.l_max = 0; sp.p_cap = 0;
+    auto most = [&]() { uint32_t m = 0; for (uint32_t x = 0; x < 8; ++x) m = std::max(m, sp.tiles_of(x)); return m; };
+    if (grouped) {
+        const uint32_t best = (sp.T + 7) / 8;                   // tiles of the busiest XCD when dealt one by one
+        for (uint32_t mu = sp.m_tiles; mu >= 1; mu /= 2) {
+            if (sp.m_tiles % mu) continue;
+            sp.mu = mu;
+            if (most() * 100 <= best * 103) break;
+        }
+    }
+    sp.gx = (uint32_t)std::min<uint64_t>(32, std::max<uint64_t>(1, (uint64_t)most() * nb / 4));
+    for (uint32_t x = 0; x < 8; ++x) {
+        sp.l_max = std::max(sp.l_max, sp.left(x));
+        for (uint32_t l = 0; l < sp.left(x); ++l) sp.p_cap = std::max(sp.p_cap, sp.parts(x, l));
+    }
+    return sp;
+}
+
+// One accumulator element, read where it is used.  Left to itself the compiler copies all 256
+// elements out of the accumulation registers after the block loop and parks half of them in scratch memory.
+__device__ __forceinline__ float acc_elem(float v)
+{
+    float r;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(v));
+    return r;
+}
+
+template <int DT>
+__device__ __forceinline__ void gemm3_store(const float16v (&acc)[16], void *Y, uint32_t ldy, uint32_t t0, uint32_t tokens,
+                                            uint32_t o0, uint32_t out, uint32_t q)
+{
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+        const uint32_t o = o0 + cb * 32;
+        if (o >= out) continue;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t t = t0 + rb * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
+                if (t < tokens) {
+                    const size_t idx = (size_t)t * ldy + o;
+                    const float v = acc_elem(acc[rb * 8 + cb][i]);
+                    if (DT == SKL_F32) static_cast<float *>(Y)[idx] = v;
+                    else if (DT == SKL_F16) static_cast<uint16_t *>(Y)[idx] = float_to_half_bits(v);
+                    else static_cast<uint16_t *>(Y)[idx] = float_to_bf16_bits(v);
+                }
+            }
+        }
+    }
+}
+
+// Row-major epilogue of the third kernel: a wavefront turns its 64 x 256 results round in a private LDS
+// area, one group of rows at a time, and stores 16-byte pieces, so that every store instruction writes
+// whole 512-byte (1 KiB for float32) rows of Y instead of 2-byte elements.  Needs 16-byte aligned rows.
+#define G3_EPI_BYTES 16896u             // per wavefront: 32 rows x (512 + 16) bytes, or 16 rows x (1024 + 16)
+static_assert(4 * G3_EPI_BYTES <= 2 * G3_SLOT_BYTES + 1024, "the epilogue areas must end below the block metadata");
+template <int DT>
+__device__ __forceinline__ void gemm3_store_rows(const float16v (&acc)[16], uint32_t lds_wave, void *Y, uint32_t ldy,
+                                                 uint32_t t0, uint32_t tokens, uint32_t o_tile, uint32_t out, uint32_t lane)
+{
+    constexpr uint32_t ES = DT == SKL_F32 ? 4 : 2;
+    constexpr uint32_t ROWB = 256 * ES + 16;                    // padded: the two token groups of a store land on other banks
+    constexpr int GROUPS = DT == SKL_F32 ? 2 : 1;               // row groups per 32-row block
+    constexpr uint32_t ROWS = 32 / GROUPS, CH = 256 * ES / 16;  // rows per group, 16-byte pieces per row
+    const uint32_t n = lane & 31, q = lane >> 5;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int gr = 0; gr < GROUPS; ++gr) {
+#pragma unroll
+            for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+                for (int ii = 0; ii < 16 / GROUPS; ++ii) {
+                    const int i = gr * (16 / GROUPS) + ii;
+                    const uint32_t row = (ii >> 2) * 8 + q * 4 + (ii & 3);
+                    const uint32_t addr = lds_wave + row * ROWB + (cb * 32 + n) * ES;
+                    const float v = acc_elem(acc[rb * 8 + cb][i]);
+                    if (DT == SKL_F32) *(__attribute__((address_space(3))) float *)(uintptr_t)addr = v;
+                    else *(__attribute__((address_space(3))) uint16_t *)(uintptr_t)addr =
+                        DT == SKL_F16 ? float_to_half_bits(v) : float_to_bf16_bits(v);
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (uint32_t it = 0; it < ROWS * CH / 64; ++it) {
+                const uint32_t idx = it * 64 + lane, row = idx / CH, c = idx % CH;
+                const uint4 w = lds_word_at(lds_wave + row * ROWB + c * 16);
+                const uint32_t t = t0 + rb * 32 + gr * ROWS + row, o = o_tile + c * (16 / ES);
+                if (t < tokens && o < out) {
+                    char *dst = static_cast<char *>(Y) + ((size_t)t * ldy + o) * ES;
+                    if (o + 16 / ES <= out) {
+                        *reinterpret_cast<uint4 *>(dst) = w;
+                    } else {                                    // ragged last piece of the layer
+                        const uint32_t e[4] = {w.x, w.y, w.z, w.w};
+                        for (uint32_t b = 0; b < (out - o) * ES; b += 2)
+                            *reinterpret_cast<uint16_t *>(dst + b) = (uint16_t)(e[b >> 2] >> ((b & 2) * 8));
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+}
+
+
+// adds the partials of the leftover tiles in workgroup order and stores them (skl_prefill.hip)
+skl_status_t skl_launch_gemm3_fixup(const G3Split &sp, const float *parts, void *Y, skl_dtype_t y_dt, uint32_t ldy,
+                                    uint32_t tokens, uint32_t out, uint32_t tile0, hipStream_t stream);

@@ -68,13 +68,17 @@ def check_prefill(g, W_hat, X, seed, expect_kernel=None):
     return y32
 
 
+@pytest.mark.parametrize("kernel", ["by_call", "fused"])
 @pytest.mark.parametrize("key", ["cfg4_4096_0.5", "cfg4_4096_0.75", "cfg4_11008_0.5", "cfg4_11008_0.75"])
-def test_prefill_layers(key):
-    """Configuration 4: 2048 tokens through 4096 x 4096 and 4096 x 11008 at 0.5 and 0.75 bit/weight."""
+def test_prefill_layers(key, kernel):
+    """Configuration 4: 2048 tokens through 4096 x 4096 and 4096 x 11008 at 0.5 and 0.75 bit/weight, with the
+    kernel the library picks for a call of this length (the staged one) and with the fused kernel asked for."""
     wl, sk, W_hat = layer(key)
     X = wk.gen_X_bf16(wl, wl.tokens)
-    with GpuLayer(sk) as g:
-        print(f"[full-size] {wl.name}: prefill kernel {g.info['prefill_kernel']}, block classes {g.info['block_classes']:#x}", flush=True)
+    with GpuLayer(sk, skl.FLAG_FUSED_PREFILL if kernel == "fused" else 0) as g:
+        print(f"[full-size] {wl.name}: prefill kernel {g.info['prefill_kernel']}, staged from {g.info['prefill_staged_from']} tokens, "
+              f"block classes {g.info['block_classes']:#x}", flush=True)
+        assert g.info["prefill_staged_from"] == (0xFFFFFFFF if kernel == "fused" else 513)
         assert np.array_equal(g.reconstruct(), W_hat)
         y32 = check_prefill(g, W_hat, X, 4, expect_kernel=skl.SKL_PREFILL_FUSED)
         # property that holds at any size: every row of the prefill equals the decode of that row

@@ -14,6 +14,7 @@ import numpy as np
 import pytest
 
 import oracle
+import paper_2506_17255_amd as skl
 import workloads as wk
 from skl_harness import GpuLayer, build_sketch, rel_fro, round_to_bf16
 
@@ -80,6 +81,31 @@ SMALL = ["cfg1", "row_ragged", "row_classes", "row_d1", "row_d2_importance", "ro
 
 def flags_of(name):
     return 1 if name == "tile_forced_1d" else 0
+
+
+def prefill_cases(names):
+    """(name, flags) pairs: every layer with the kernel its plan picks, row-sketch layers also with the
+    staged prefill asked for (weights rebuilt once per call into the workspace)."""
+    out = []
+    for n in names:
+        out.append((n, flags_of(n)))
+        if n.startswith("row"):
+            out.append((n, skl.FLAG_STAGED_PREFILL))
+            out.append((n, skl.FLAG_FUSED_PREFILL))
+    return out
+
+
+def expect_prefill_kernel(g, name, flags):
+    if not name.startswith("row"):
+        want = skl.SKL_PREFILL_PER_WEIGHT
+    elif flags & skl.FLAG_STAGED_PREFILL or name == "row_big_table":     # a table above the fused kernel's LDS plan
+        want = skl.SKL_PREFILL_STAGED
+    else:
+        want = skl.SKL_PREFILL_FUSED
+    assert g.info["prefill_kernel"] == want
+    if name.startswith("row"):
+        from_tokens = 0 if want == skl.SKL_PREFILL_STAGED else 0xFFFFFFFF if flags & skl.FLAG_FUSED_PREFILL else 513
+        assert g.info["prefill_staged_from"] == from_tokens
 
 
 @functools.lru_cache(maxsize=None)
@@ -151,15 +177,16 @@ def test_gemv_one_hot_probe_is_exact(name, batch):
 
 # ------------------------------------------------------------------ gemm
 @pytest.mark.parametrize("tokens", [1, 70, 200])
-@pytest.mark.parametrize("name", SMALL)
-def test_gemm_matches_oracle(name, tokens):
+@pytest.mark.parametrize("name,flags", prefill_cases(SMALL))
+def test_gemm_matches_oracle(name, flags, tokens):
     W, sk = small_case(name)
     W_hat = expected_W_hat(name)
     rng = np.random.default_rng(200 + tokens)
     Xf = rng.standard_normal((tokens, sk.in_features)).astype(np.float32)
     Xb = wk.f32_to_bf16_bits(Xf)
     ref = oracle.linear(W_hat, Xb, x_kind="bf16")
-    with GpuLayer(sk, flags_of(name)) as g:
+    with GpuLayer(sk, flags) as g:
+        expect_prefill_kernel(g, name, flags)
         y32 = g.gemm(Xb, "bf16", "f32", ldx=sk.in_features + 8, ldy=sk.out_features + 8)
         ybf = g.gemm(Xb, "bf16", "bf16")
         y16 = g.gemm(Xb, "bf16", "f16")
@@ -171,8 +198,8 @@ def test_gemm_matches_oracle(name, tokens):
     assert rel_fro(yh, oracle.linear(W_hat, Xh)) <= 1e-5
 
 
-@pytest.mark.parametrize("name", ["row_ragged", "row_classes", "row_d5", "row_big_table", "row_single"])
-def test_gemm_strides_and_several_token_tiles(name):
+@pytest.mark.parametrize("name,flags", prefill_cases(["row_ragged", "row_classes", "row_d5", "row_big_table", "row_single"]))
+def test_gemm_strides_and_several_token_tiles(name, flags):
     """Three token tiles with a ragged last one (the work split then shares tiles between workgroups),
     rows of X that are not 16-byte aligned, rows of Y that are and that are not."""
     W, sk = small_case(name)
@@ -183,7 +210,8 @@ def test_gemm_strides_and_several_token_tiles(name):
     Xb = wk.f32_to_bf16_bits(Xf)
     ref = oracle.linear(W_hat, Xb, x_kind="bf16")
     pad = (-sk.out_features) % 8
-    with GpuLayer(sk, flags_of(name)) as g:
+    with GpuLayer(sk, flags) as g:
+        expect_prefill_kernel(g, name, flags)
         y_odd = g.gemm(Xb, "bf16", "bf16", ldx=sk.in_features + 3, ldy=sk.out_features + pad + 5)
         y_al = g.gemm(Xb, "bf16", "bf16", ldx=sk.in_features + 8, ldy=sk.out_features + pad + 16)
         y16 = g.gemm(Xb, "bf16", "f16", ldy=sk.out_features + pad + 8)
@@ -197,8 +225,8 @@ def test_gemm_strides_and_several_token_tiles(name):
 
 
 @pytest.mark.parametrize("tokens", [1, 300, 700])
-@pytest.mark.parametrize("name", ["row_four_words", "row_four_words_d6"])
-def test_gemm_blocks_of_four_words(name, tokens):
+@pytest.mark.parametrize("name,flags", prefill_cases(["row_four_words", "row_four_words_d6"]))
+def test_gemm_blocks_of_four_words(name, flags, tokens):
     """Layers whose blocks hold 32 channels (four words per state row): the prefill kernel rebuilds their
     operand words between the MFMAs of the block before, with its own lane layout."""
     W, sk = small_case(name)
@@ -206,7 +234,8 @@ def test_gemm_blocks_of_four_words(name, tokens):
     rng = np.random.default_rng(900 + tokens)
     Xb = wk.f32_to_bf16_bits(rng.standard_normal((tokens, sk.in_features)).astype(np.float32))
     ref = oracle.linear(W_hat, Xb, x_kind="bf16")
-    with GpuLayer(sk) as g:
+    with GpuLayer(sk, flags) as g:
+        expect_prefill_kernel(g, name, flags)
         assert np.array_equal(g.reconstruct(), W_hat)
         y32 = g.gemm(Xb, "bf16", "f32")
         ybf = g.gemm(Xb, "bf16", "bf16", ldx=sk.in_features + 8, ldy=sk.out_features + 8)
@@ -217,24 +246,45 @@ def test_gemm_blocks_of_four_words(name, tokens):
     assert rel_fro(y1, oracle.linear(W_hat, x1)) <= 1e-5
 
 
-def test_gemm_is_bit_identical_from_run_to_run():
+@pytest.mark.parametrize("flags", [0, skl.FLAG_STAGED_PREFILL, skl.FLAG_FUSED_PREFILL])
+def test_gemm_is_bit_identical_from_run_to_run(flags):
     W, sk = small_case("row_classes")
     rng = np.random.default_rng(78)
     Xb = wk.f32_to_bf16_bits(rng.standard_normal((700, sk.in_features)).astype(np.float32))
-    with GpuLayer(sk) as g:
+    with GpuLayer(sk, flags) as g:
         runs = [g.gemm(Xb, "bf16", "f32") for _ in range(3)]
     assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
 
 
-@pytest.mark.parametrize("name", ["row_ragged", "row_classes", "tile_ragged", "cfg1"])
-def test_gemm_identity_probe_is_exact(name):
+@pytest.mark.parametrize("name,flags", prefill_cases(["row_ragged", "row_classes", "tile_ragged", "cfg1"]))
+def test_gemm_identity_probe_is_exact(name, flags):
     """X = I  =>  Y = W_hat exactly (float32 output)."""
     W, sk = small_case(name)
     W_hat = expected_W_hat(name).view(np.float16).astype(np.float32)
     X = np.eye(sk.in_features, dtype=np.float32)
-    with GpuLayer(sk, flags_of(name)) as g:
+    with GpuLayer(sk, flags) as g:
         y = g.gemm(wk.f32_to_bf16_bits(X), "bf16", "f32")
     assert np.array_equal(y, W_hat)
+
+
+@pytest.mark.parametrize("flags", [skl.FLAG_FUSED_PREFILL, skl.FLAG_STAGED_PREFILL])
+def test_gemm_with_fewer_blocks_than_workgroups_and_a_dirty_workspace(flags):
+    """64 input channels (one channel block), 4864 outputs, 768 tokens: 57 tiles, so some XCDs finish a
+    leftover tile with a single share that covers it whole.  The workspace starts full of NaN patterns:
+    whatever the fix-up pass adds must have been written by this call."""
+    W, sk = custom_layer("few_blocks", 64, 4864, 1, 4864, 4, [40] * 64, 21)
+    W_hat = oracle.query(sk)
+    rng = np.random.default_rng(79)
+    Xb = wk.f32_to_bf16_bits(rng.standard_normal((768, 64)).astype(np.float32))
+    ref = oracle.linear(W_hat, Xb, x_kind="bf16")
+    with GpuLayer(sk, flags) as g:
+        ws, need = g.workspace(1, 768)
+        ws.fill_(0xFF)
+        y32 = g.gemm(Xb, "bf16", "f32")
+        ws.fill_(0xFF)
+        ybf = g.gemm(Xb, "bf16", "bf16")
+    assert rel_fro(y32, ref) <= 1e-5
+    assert rel_fro(ybf, round_to_bf16(ref)) <= TOL
 
 
 def test_gemm_row_equals_gemv():

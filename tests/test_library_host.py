@@ -76,7 +76,8 @@ def test_valid_description_is_accepted():
     (dict(d=0), skl.SKL_ERR_INVALID_ARG),
     (dict(d=9), skl.SKL_ERR_INVALID_ARG),
     (dict(query_mode=1), skl.SKL_ERR_UNSUPPORTED),
-    (dict(flags=2), skl.SKL_ERR_INVALID_ARG),
+    (dict(flags=8), skl.SKL_ERR_INVALID_ARG),
+    (dict(flags=6), skl.SKL_ERR_INVALID_ARG),
     (dict(hash_a=None), skl.SKL_ERR_INVALID_ARG),
     (dict(states=None, n_states=36), skl.SKL_ERR_INVALID_ARG),
     (dict(hash_a=np.uint32([1 << 24, 5])), skl.SKL_ERR_INVALID_ARG),

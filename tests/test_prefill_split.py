@@ -13,9 +13,36 @@ import pytest
 import paper_2506_17255_amd as skl
 
 
-def split(out_features, n_blocks, tokens):
-    segs, shape = skl.sketch_linear_prefill_split(out_features, n_blocks, tokens)
+KERNELS = [skl.SKL_PREFILL_FUSED, skl.SKL_PREFILL_STAGED]
+
+
+def split(out_features, n_blocks, tokens, kernel=skl.SKL_PREFILL_FUSED):
+    segs, shape = skl.sketch_linear_prefill_split(out_features, n_blocks, tokens, kernel)
     return segs, shape
+
+
+def m_tiles_of(tokens):
+    return (tokens + 255) // 256
+
+
+def tiles_of_xcd(mu, xcd, n_tiles, m_tiles):
+    """Tiles dealt to an XCD: units of mu token tiles of one output-tile column go round the XCDs
+    (mu = 1: single tiles, the fused kernel; the staged kernel takes the largest mu that stays balanced)."""
+    n_units = (n_tiles // m_tiles) * (m_tiles // mu)
+    return mu * ((n_units - xcd + 7) // 8) if n_units > xcd else 0
+
+
+def unit_of_tile(mu, tm, tn, m_tiles):
+    return tn * (m_tiles // mu) + tm // mu
+
+
+def xcd_of_tile(mu, tm, tn, m_tiles):
+    return unit_of_tile(mu, tm, tn, m_tiles) % 8
+
+
+def index_on_xcd(mu, tm, tn, m_tiles):
+    """Position of a tile in its XCD's list."""
+    return (unit_of_tile(mu, tm, tn, m_tiles) // 8) * mu + tm % mu
 
 
 SHAPES = [
@@ -32,9 +59,10 @@ SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("kernel", KERNELS)
 @pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES)
-def test_every_block_of_every_tile_is_multiplied_once(out_features, n_blocks, tokens):
-    segs, (gx, l_max, p_cap, n_tiles) = split(out_features, n_blocks, tokens)
+def test_every_block_of_every_tile_is_multiplied_once(out_features, n_blocks, tokens, kernel):
+    segs, (gx, l_max, p_cap, n_tiles, mu) = split(out_features, n_blocks, tokens, kernel)
     m_tiles = (tokens + 255) // 256
     n_col = (out_features + 255) // 256
     assert n_tiles == m_tiles * n_col
@@ -45,21 +73,22 @@ def test_every_block_of_every_tile_is_multiplied_once(out_features, n_blocks, to
         assert 0 <= k0 < k1 <= n_blocks
         # tiles dealt out in whole rounds are stored by the main kernel; every share of a leftover tile
         # leaves a partial for the fix-up pass, also a share that happens to cover the tile
-        tiles_of = (n_tiles - xcd + 7) // 8 if n_tiles > xcd else 0
-        in_round = ((tn * m_tiles + tm) // 8) < (tiles_of // gx) * gx
+        tiles_of = tiles_of_xcd(mu, xcd, n_tiles, m_tiles)
+        in_round = index_on_xcd(mu, tm, tn, m_tiles) < (tiles_of // gx) * gx
         assert whole == int(in_round)
         if in_round:
             assert k0 == 0 and k1 == n_blocks
-        assert (tn * m_tiles + tm) % 8 == xcd          # a tile stays on one XCD
+        assert xcd_of_tile(mu, tm, tn, m_tiles) == xcd          # a tile stays on one XCD
         for b in range(k0, k1):
             assert (tm, tn, b) not in seen
             seen[(tm, tn, b)] = (xcd, wg)
     assert len(seen) == n_tiles * n_blocks
 
 
+@pytest.mark.parametrize("kernel", KERNELS)
 @pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES)
-def test_partial_slots_are_distinct_dense_and_in_workgroup_order(out_features, n_blocks, tokens):
-    segs, (gx, l_max, p_cap, n_tiles) = split(out_features, n_blocks, tokens)
+def test_partial_slots_are_distinct_dense_and_in_workgroup_order(out_features, n_blocks, tokens, kernel):
+    segs, (gx, l_max, p_cap, n_tiles, mu) = split(out_features, n_blocks, tokens, kernel)
     by_tile = {}
     slots = set()
     for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
@@ -83,9 +112,10 @@ def test_partial_slots_are_distinct_dense_and_in_workgroup_order(out_features, n
             assert e == b
 
 
+@pytest.mark.parametrize("kernel", KERNELS)
 @pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES)
-def test_workgroups_get_equal_work(out_features, n_blocks, tokens):
-    segs, (gx, l_max, p_cap, n_tiles) = split(out_features, n_blocks, tokens)
+def test_workgroups_get_equal_work(out_features, n_blocks, tokens, kernel):
+    segs, (gx, l_max, p_cap, n_tiles, mu) = split(out_features, n_blocks, tokens, kernel)
     load = {}
     for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
         load[(xcd, wg)] = load.get((xcd, wg), 0) + k1 - k0
@@ -97,15 +127,20 @@ def test_workgroups_get_equal_work(out_features, n_blocks, tokens):
             assert max(mine) - min(mine) <= 1 or len(mine) < gx
     total = sum(load.values())
     assert total == n_tiles * n_blocks
-    # the busiest workgroup is close to the ideal share when there is enough work to go round
+    if kernel == skl.SKL_PREFILL_FUSED:
+        assert mu == 1
+    assert m_tiles_of(tokens) % mu == 0
+    # the busiest workgroup is close to the ideal share when there is enough work to go round (the staged
+    # kernel's dealing units are chosen so that the busiest XCD stays within 3 % of dealing single tiles)
     if total >= 8 * gx * 8:
         assert max(load.values()) <= total / (8 * gx) + n_blocks / 8 + 1
 
 
-def test_small_exhaustive_sweep():
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_small_exhaustive_sweep(kernel):
     for n_tiles_out, n_blocks, tokens in itertools.product(range(1, 41), (1, 2, 5, 31, 64), (1, 256, 257, 2048)):
         out_features = 256 * n_tiles_out - 3
-        segs, (gx, l_max, p_cap, n_tiles) = split(out_features, n_blocks, tokens)
+        segs, (gx, l_max, p_cap, n_tiles, mu) = split(out_features, n_blocks, tokens, kernel)
         covered = sum(k1 - k0 for *_, k0, k1, _, _ in segs)
         assert covered == n_tiles * n_blocks
         keys = set()
@@ -115,28 +150,30 @@ def test_small_exhaustive_sweep():
         assert len(keys) == covered
 
 
-def leftover_tiles(shape, tokens):
+def leftover_tiles(shape, tokens, kernel):
     """(xcd, l, token tile, output tile) of every tile the fix-up pass finishes."""
-    gx, l_max, p_cap, n_tiles = shape
+    gx, l_max, p_cap, n_tiles, mu = shape
     m_tiles = (tokens + 255) // 256
+    n_mg = m_tiles // mu
     for xcd in range(8):
-        tiles_of = (n_tiles - xcd + 7) // 8 if n_tiles > xcd else 0
+        tiles_of = tiles_of_xcd(mu, xcd, n_tiles, m_tiles)
         rounds = tiles_of // gx
         for l in range(tiles_of - rounds * gx):
-            t = xcd + 8 * (rounds * gx + l)
-            yield xcd, l, t % m_tiles, t // m_tiles
+            k = rounds * gx + l
+            u = xcd + 8 * (k // mu)
+            yield xcd, l, (u % n_mg) * mu + k % mu, u // n_mg
 
 
-def check_fixup_reads_only_written_slots(out_features, n_blocks, tokens):
+def check_fixup_reads_only_written_slots(out_features, n_blocks, tokens, kernel=skl.SKL_PREFILL_FUSED):
     """The fix-up pass adds slots [base, base + parts) of every leftover tile: each must have been written
     by a partial segment of that tile, and whole-tile segments never belong to a leftover tile."""
-    segs, shape = split(out_features, n_blocks, tokens)
-    gx, l_max, p_cap, n_tiles = shape
+    segs, shape = split(out_features, n_blocks, tokens, kernel)
+    gx, l_max, p_cap, n_tiles, mu = shape
     written = {}
     for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
         if not whole:
             written.setdefault((tm, tn), []).append(slot)
-    left = list(leftover_tiles(shape, tokens))
+    left = list(leftover_tiles(shape, tokens, kernel))
     assert len(left) == len(written)
     for xcd, l, tm, tn in left:
         assert l < l_max
@@ -148,26 +185,30 @@ def check_fixup_reads_only_written_slots(out_features, n_blocks, tokens):
             assert (tm, tn) not in written
 
 
+@pytest.mark.parametrize("kernel", KERNELS)
 @pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES + [(7936, 16, 2048), (256 * 57, 1, 256), (4864, 1, 768)])
-def test_fixup_reads_only_written_slots(out_features, n_blocks, tokens):
-    check_fixup_reads_only_written_slots(out_features, n_blocks, tokens)
+def test_fixup_reads_only_written_slots(out_features, n_blocks, tokens, kernel):
+    check_fixup_reads_only_written_slots(out_features, n_blocks, tokens, kernel)
 
 
-def test_fixup_slots_with_few_blocks():
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_fixup_slots_with_few_blocks(kernel):
     """Layers with fewer channel blocks than workgroups per XCD: a leftover share can cover exactly one tile."""
     for n_blocks in range(1, 33):
         for n_tiles_out in (1, 2, 7, 19, 31, 57, 64):
             for tokens in (256, 768, 2048):
-                check_fixup_reads_only_written_slots(256 * n_tiles_out, n_blocks, tokens)
+                check_fixup_reads_only_written_slots(256 * n_tiles_out, n_blocks, tokens, kernel)
 
 
 def test_argument_errors():
     L = skl.load_library()
     import ctypes
     n = ctypes.c_uint64(0)
-    assert L.sketch_linear_prefill_split(4096, 64, 2048, None, 0, None, None) == skl.SKL_ERR_INVALID_ARG
-    assert L.sketch_linear_prefill_split(4096, 64, 2048, None, 5, ctypes.byref(n), None) == skl.SKL_ERR_INVALID_ARG
-    assert L.sketch_linear_prefill_split(0, 64, 2048, None, 0, ctypes.byref(n), None) == skl.SKL_ERR_INVALID_ARG
-    assert L.sketch_linear_prefill_split(4096, 64, 0, None, 0, ctypes.byref(n), None) == skl.SKL_ERR_INVALID_ARG
-    assert L.sketch_linear_prefill_split(4096, 64, 2048, None, 0, ctypes.byref(n), None) == skl.SKL_OK
+    F = skl.SKL_PREFILL_FUSED
+    assert L.sketch_linear_prefill_split(F, 4096, 64, 2048, None, 0, None, None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_prefill_split(F, 4096, 64, 2048, None, 5, ctypes.byref(n), None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_prefill_split(F, 0, 64, 2048, None, 0, ctypes.byref(n), None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_prefill_split(F, 4096, 64, 0, None, 0, ctypes.byref(n), None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_prefill_split(1, 4096, 64, 2048, None, 0, ctypes.byref(n), None) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_prefill_split(F, 4096, 64, 2048, None, 0, ctypes.byref(n), None) == skl.SKL_OK
     assert n.value >= 8

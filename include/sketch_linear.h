@@ -288,6 +288,15 @@ SKL_API skl_status_t sketch_linear_build_states(const skl_desc_t *desc, const ui
 SKL_API skl_status_t sketch_linear_reconstruct(const skl_layer_t *layer, uint16_t *W_hat_dev, void *workspace,
                                        uint64_t workspace_bytes, void *hip_stream);
 
+/* Comparator: the same W_hat through the hash-based operator the paper starts
+ * from (Sec. 3.3, the operation its matrix form replaces; Sec. 4, the
+ * decompression speed-up figure): one select (Eq. 3) per weight and sketch
+ * row, every candidate state fetched from device memory, nothing staged or
+ * shared.  Same arguments and result as sketch_linear_reconstruct; exists to
+ * be timed against it and against the fused calls. */
+SKL_API skl_status_t sketch_linear_reconstruct_hash_op(const skl_layer_t *layer, uint16_t *W_hat_dev, void *workspace,
+                                               uint64_t workspace_bytes, void *hip_stream);
+
 /* Frees the host object only; dev_buf stays the caller's. NULL is accepted. */
 SKL_API void sketch_linear_destroy(skl_layer_t *layer);
 

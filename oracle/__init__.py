@@ -51,6 +51,8 @@ def _bind(L):
     L.ora_update.argtypes = geom + [_u16p, _u16p, ctypes.c_uint64]
     L.ora_query.restype = ctypes.c_int
     L.ora_query.argtypes = geom + [_u16p, ctypes.c_uint64, _u16p]
+    L.ora_query_mode.restype = ctypes.c_int
+    L.ora_query_mode.argtypes = geom + [_u16p, ctypes.c_uint64, ctypes.c_int, _u16p]
     _i8p = ctypes.POINTER(ctypes.c_int8)
     qgeom = [ctypes.c_uint32] * 5 + [_u32p]
     L.ora_quantize_states.restype = ctypes.c_int
@@ -163,14 +165,18 @@ def update(W, tile_in, tile_out, d, hash_a, hash_c, group_width) -> Sketch:
     return Sketch(in_f, out_f, tile_in, tile_out, d, A, C, wd, states)
 
 
-def query(sk: Sketch) -> np.ndarray:
-    """Eq. (5): reconstruct W_hat ([in][out] binary16 bit patterns)."""
+QUERY_ABS_MAX, QUERY_SIGNED_MAX = 0, 1
+
+
+def query(sk: Sketch, mode: int = QUERY_ABS_MAX) -> np.ndarray:
+    """Eq. (5): reconstruct W_hat ([in][out] binary16 bit patterns).  mode 0: Max by magnitude (default
+    reading); mode 1: Max of the signed values, Eq. (5) as printed."""
     W_hat = np.empty((sk.in_features, sk.out_features), dtype=np.uint16)
     st = _u16(sk.states)
-    rc = _load().ora_query(sk.in_features, sk.out_features, sk.tile_in, sk.tile_out, sk.d,
-                           _p(_u32(sk.hash_a), _u32p), _p(_u32(sk.hash_c), _u32p),
-                           _p(_u32(sk.group_width), _u32p), _p(st, _u16p), st.size,
-                           _p(W_hat, _u16p))
+    rc = _load().ora_query_mode(sk.in_features, sk.out_features, sk.tile_in, sk.tile_out, sk.d,
+                                _p(_u32(sk.hash_a), _u32p), _p(_u32(sk.hash_c), _u32p),
+                                _p(_u32(sk.group_width), _u32p), _p(st, _u16p), st.size, int(mode),
+                                _p(W_hat, _u16p))
     _check(rc, "query")
     return W_hat
 

@@ -28,6 +28,8 @@
  *   - "Max" in Eq. (5) is taken by magnitude (the sketch is called AbsMaxMin
  *     and is stated to under-estimate magnitudes); between two candidates of
  *     equal magnitude the one whose sign bit is clear wins.
+ *     The literal reading -- Max of the signed values, as Eq. (5) is printed --
+ *     is available as query mode 1 (+0 wins over -0).
  *   - Update ties (|S| == |w|) keep the older value (Eq. (4) is strict).
  *   - States that no weight ever reached are written as +0.0 at the end of
  *     the update stream (no query can reach them).
@@ -182,15 +184,30 @@ static uint16_t absmax_pick(uint16_t best, uint16_t cand)
     return best;
 }
 
-int ora_query(uint32_t in, uint32_t out, uint32_t tj, uint32_t to, uint32_t d,
-              const uint32_t *A, const uint32_t *C, const uint32_t *width,
-              const uint16_t *states, uint64_t n_states,
-              uint16_t *W_hat /* [in][out] binary16 */)
+/* Eq. (5) read literally: the printed formula is a plain Max over the d
+ * candidates, with no magnitude signs.  The larger signed value wins; the
+ * only equal values with different bit patterns are +0 and -0, and there the
+ * pattern with the clear sign bit wins (as in the magnitude reading). */
+static uint16_t signedmax_pick(uint16_t best, uint16_t cand)
+{
+    double vb = ora_half_to_double(best), vc = ora_half_to_double(cand);
+    if (vc > vb) return cand;
+    if (vc == vb && (cand >> 15) == 0) return cand;
+    return best;
+}
+
+/* mode 0: Max by magnitude (the reading this build takes as default);
+ * mode 1: Max of the signed values (Eq. (5) as printed). */
+int ora_query_mode(uint32_t in, uint32_t out, uint32_t tj, uint32_t to, uint32_t d,
+                   const uint32_t *A, const uint32_t *C, const uint32_t *width,
+                   const uint16_t *states, uint64_t n_states, int mode,
+                   uint16_t *W_hat /* [in][out] binary16 */)
 {
     geom_t g;
     int rc = geom_init(&g, in, out, tj, to, d, A, C, width);
     if (rc) return rc;
     if (!states || !W_hat) return ORA_BAD_ARG;
+    if (mode != 0 && mode != 1) return ORA_BAD_ARG;
     if (n_states != ora_count_states(in, out, tj, to, d, width)) return ORA_BAD_ARG;
     for (uint64_t i = 0; i < n_states; ++i)
         if (!half_is_finite(states[i])) return ORA_NONFINITE;
@@ -204,13 +221,23 @@ int ora_query(uint32_t in, uint32_t out, uint32_t tj, uint32_t to, uint32_t d,
                 for (uint32_t ol = 0; ol < to; ++ol) {
                     uint32_t a = jl * to + ol;
                     uint16_t best = S[ora_select(A[0], C[0], K, a)];
-                    for (uint32_t r = 1; r < d; ++r)
-                        best = absmax_pick(best, S[(uint64_t)r * K + ora_select(A[r], C[r], K, a)]);
+                    for (uint32_t r = 1; r < d; ++r) {
+                        uint16_t cand = S[(uint64_t)r * K + ora_select(A[r], C[r], K, a)];
+                        best = mode == 1 ? signedmax_pick(best, cand) : absmax_pick(best, cand);
+                    }
                     W_hat[(uint64_t)(jb * tj + jl) * out + (ob * to + ol)] = best;
                 }
             base += (uint64_t)d * K;
         }
     return ORA_OK;
+}
+
+int ora_query(uint32_t in, uint32_t out, uint32_t tj, uint32_t to, uint32_t d,
+              const uint32_t *A, const uint32_t *C, const uint32_t *width,
+              const uint16_t *states, uint64_t n_states,
+              uint16_t *W_hat /* [in][out] binary16 */)
+{
+    return ora_query_mode(in, out, tj, to, d, A, C, width, states, n_states, 0, W_hat);
 }
 
 /* ---- low-bit states (Sec. 3.3 last paragraph; Sec. 4 ablation "sketch

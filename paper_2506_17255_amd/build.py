@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libsketch_linear.so")
 SOURCES = ["skl_host.cpp", "skl_decode.hip", "skl_reconstruct.hip", "skl_prefill.hip", "skl_prefill_staged.hip",
-           "skl_tile.hip", "skl_lowbit.hip", "skl_build.hip"]
+           "skl_tile.hip", "skl_lowbit.hip", "skl_build.hip", "skl_naive.hip"]
 
 
 def lib_path() -> str:

@@ -760,8 +760,7 @@ skl_status_t sketch_linear_prefill_split(uint32_t kernel, uint32_t out_features,
     return SKL_OK;
 }
 
-skl_status_t sketch_linear_reconstruct(const skl_layer_t *L, uint16_t *W_hat_dev, void *ws, uint64_t ws_bytes,
-                                       void *stream)
+static skl_status_t reconstruct_with(const skl_layer_t *L, uint16_t *W_hat_dev, void *ws, uint64_t ws_bytes, void *stream, bool naive)
 {
     if (!L || !W_hat_dev) FAIL(SKL_ERR_INVALID_ARG, "layer or W_hat_dev is NULL");
     if ((uintptr_t)W_hat_dev % 16) FAIL(SKL_ERR_INVALID_ARG, "W_hat_dev not 16-byte aligned");
@@ -775,7 +774,18 @@ skl_status_t sketch_linear_reconstruct(const skl_layer_t *L, uint16_t *W_hat_dev
         if (overlap(ws, need, W_hat_dev, (uint64_t)L->in * L->out * 2))
             FAIL(SKL_ERR_INVALID_ARG, "workspace overlaps W_hat_dev");
     }
-    return skl_launch_reconstruct(L, W_hat_dev, ws, stream);
+    return naive ? skl_launch_reconstruct_naive(L, W_hat_dev, ws, stream) : skl_launch_reconstruct(L, W_hat_dev, ws, stream);
+}
+
+skl_status_t sketch_linear_reconstruct(const skl_layer_t *L, uint16_t *W_hat_dev, void *ws, uint64_t ws_bytes, void *stream)
+{
+    return reconstruct_with(L, W_hat_dev, ws, ws_bytes, stream, false);
+}
+
+skl_status_t sketch_linear_reconstruct_hash_op(const skl_layer_t *L, uint16_t *W_hat_dev, void *ws, uint64_t ws_bytes,
+                                               void *stream)
+{
+    return reconstruct_with(L, W_hat_dev, ws, ws_bytes, stream, true);
 }
 
 }  // extern "C"

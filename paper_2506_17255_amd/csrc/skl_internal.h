@@ -146,6 +146,8 @@ static inline uint16_t skl_key_of_half(uint16_t b)
 
 // ---- launchers implemented in skl_kernels.hip (all enqueue only) -----------
 skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *ws, void *stream);
+// the hash-based operator as a comparator: per-weight select, states fetched from device memory (skl_naive.hip)
+skl_status_t skl_launch_reconstruct_naive(const skl_layer *L, uint16_t *W_hat, void *ws, void *stream);
 // bytes of expanded tables at the end of every workspace of a layer with low-bit states (else 0)
 uint64_t skl_dequant_bytes(const skl_layer *L);
 uint64_t skl_reconstruct_workspace_bytes(const skl_layer *L);

@@ -82,11 +82,13 @@ class GpuLayer:
             self._ws = self.torch.empty(max(need, 16), dtype=self.torch.uint8, device=self.dev)
         return self._ws, need
 
-    def reconstruct(self) -> np.ndarray:
+    def reconstruct(self, hash_op: bool = False) -> np.ndarray:
+        """W_hat through the LDS-staged reconstruction, or (hash_op) through the per-weight comparator."""
         t = self.torch
         out = t.full((self.sk.in_features, self.sk.out_features), 0x7E00, dtype=t.int16, device=self.dev)
         ws, need = self.workspace(2, 0)
-        skl.sketch_linear_reconstruct(self.handle, out.data_ptr(), ws.data_ptr(), ws.numel(), self.stream())
+        call = skl.sketch_linear_reconstruct_hash_op if hash_op else skl.sketch_linear_reconstruct
+        call(self.handle, out.data_ptr(), ws.data_ptr(), ws.numel(), self.stream())
         t.cuda.synchronize()
         return out.cpu().numpy().view(np.uint16)
 

@@ -36,6 +36,7 @@ def test_decode_layers(key):
     print(f"[full-size] {wl.name}: {sk.bits_per_weight:.4f} bit/weight", flush=True)
     with GpuLayer(sk) as g:
         assert np.array_equal(g.reconstruct(), W_hat)
+        assert np.array_equal(g.reconstruct(hash_op=True), W_hat)
         for batch in wl.batches:
             x = wk.gen_x(wl, batch)
             ref = oracle.linear(W_hat, x)              # every output of every batch row

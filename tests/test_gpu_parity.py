@@ -123,6 +123,15 @@ def test_reconstruct_bit_exact(name):
     assert np.array_equal(got, expected_W_hat(name))
 
 
+@pytest.mark.parametrize("name", SMALL)
+def test_hash_operator_comparator_bit_exact(name):
+    """The per-weight hash operator (states fetched from device memory, nothing staged) gives the same W_hat."""
+    W, sk = small_case(name)
+    with GpuLayer(sk, flags_of(name)) as g:
+        got = g.reconstruct(hash_op=True)
+    assert np.array_equal(got, expected_W_hat(name))
+
+
 # ------------------------------------------------------------------ gemv
 @pytest.mark.parametrize("batch", [1, 2, 5, 8, 16])
 @pytest.mark.parametrize("name", SMALL)

@@ -38,11 +38,21 @@ MUTANTS = {
     "query takes the minimum magnitude":
         ("if (mc > mb) return cand;", "if (mc < mb) return cand;"),
     "query skips the last row":
-        ("for (uint32_t r = 1; r < d; ++r)\n                        best", "for (uint32_t r = 1; r + 1 < d; ++r)\n                        best"),
+        ("for (uint32_t r = 1; r < d; ++r) {\n                        uint16_t cand", "for (uint32_t r = 1; r + 1 < d; ++r) {\n                        uint16_t cand"),
     "rows share the first row's table":
-        ("best = absmax_pick(best, S[(uint64_t)r * K + ora_select", "best = absmax_pick(best, S[ora_select"),
+        ("uint16_t cand = S[(uint64_t)r * K + ora_select", "uint16_t cand = S[ora_select"),
+    "signed query compares magnitudes":
+        ("if (vc > vb) return cand;", "if (fabs(vc) > fabs(vb)) return cand;"),
+    "signed query takes the minimum":
+        ("if (vc > vb) return cand;", "if (vc < vb) return cand;"),
+    "signed query lets -0 win the zero tie":
+        ("if (vc == vb && (cand >> 15) == 0) return cand;", "if (vc == vb && (cand >> 15) == 1) return cand;"),
+    "signed query keeps the first row on a zero tie":
+        ("if (vc == vb && (cand >> 15) == 0) return cand;", ""),
+    "query modes are swapped":
+        ("best = mode == 1 ? signedmax_pick(best, cand)", "best = mode == 0 ? signedmax_pick(best, cand)"),
     "group base advances by one row only":
-        ("base += (uint64_t)d * K;\n        }\n    return ORA_OK;\n}\n\n/* ---- low-bit", "base += K;\n        }\n    return ORA_OK;\n}\n\n/* ---- low-bit"),
+        ("base += (uint64_t)d * K;\n        }\n    return ORA_OK;\n}\n\nint ora_query(", "base += K;\n        }\n    return ORA_OK;\n}\n\nint ora_query("),
     "groups are numbered column-major":
         ("uint32_t K = width[(uint64_t)jb * g.n_ob + ob];\n            const uint16_t *S", "uint32_t K = width[(uint64_t)ob * g.n_jb + jb];\n            const uint16_t *S"),
     "linear reads W transposed":
@@ -78,6 +88,7 @@ PIN_FUNCS = [
     "test_query_matrix_form_eq9_single_row", "test_query_signed_zero_tie",
     "test_invariants_on_cfg1", "test_row_order_invariance_and_more_rows_never_hurt",
     "test_linear_against_numpy_fp64_and_one_hot",
+    "test_worked_example_signed_max_query", "test_signed_max_query_zero_tie_and_negative_candidates",
 ]
 
 
@@ -108,6 +119,11 @@ def _run_pins():
             pins.test_query_multi_row_via_matrix_forms(d)
         except (AssertionError, ValueError, IndexError):
             failed.append("test_query_multi_row_via_matrix_forms")
+    for d in (2, 3):
+        try:
+            pins.test_signed_max_query_via_matrix_forms_and_numpy_max(d)
+        except (AssertionError, ValueError, IndexError):
+            failed.append("test_signed_max_query_via_matrix_forms_and_numpy_max")
     try:
         pins.test_identity_hash_reproduces_W(2)
     except (AssertionError, ValueError, IndexError):

@@ -54,6 +54,14 @@ def test_worked_example_update_query_linear(ex):
     assert y.tolist() == [ex["y"]]
 
 
+def test_worked_example_signed_max_query(ex):
+    """Query mode 1, Eq. (5) as printed: the hand-derived result on the worked example's states."""
+    sk = oracle.update(f16(ex["W"]), ex["tile_in"], ex["tile_out"], ex["d"], ex["A"], ex["C"], [ex["K"]])
+    W_hat = oracle.query(sk, oracle.QUERY_SIGNED_MAX)
+    assert as_f16(W_hat).astype(np.float64).tolist() == ex["W_hat_signed_max"]
+    assert oracle.linear(W_hat, f16([ex["x"]])).tolist() == [ex["y_signed_max"]]
+
+
 # ------------------------------------------------------------- conversions
 def test_half_to_double_all_patterns():
     b = np.arange(65536, dtype=np.uint16)
@@ -229,6 +237,58 @@ def test_query_multi_row_via_matrix_forms(d):
             blk = got[jb * tj:(jb + 1) * tj, ob * to:(ob + 1) * to].astype(np.float64)
             assert np.array_equal(blk, ref)
             assert np.array_equal(np.signbit(blk), np.signbit(ref))
+
+
+@pytest.mark.parametrize("d", [2, 3, 8])
+def test_signed_max_query_via_matrix_forms_and_numpy_max(d):
+    """Query mode 1: the d per-row results of the one-hot matrix form (Eq. 9) combined by numpy's maximum
+    of the signed values; tables drawn from seven values so that equal candidates and sign clashes abound.
+    Also: the result is one of the candidates and no candidate exceeds it."""
+    rng = np.random.default_rng(190 + d)
+    in_f, out_f, tj, to = 4, 36, 2, 12
+    n_jb, n_ob = in_f // tj, out_f // to
+    widths = np.array([5, 2, 7, 3, 6, 4], dtype=np.uint32)
+    A = 2 * rng.integers(0, 1 << 23, size=d) + 1
+    C = rng.integers(0, 1 << 24, size=d)
+    tables = [(rng.integers(-3, 4, size=(d, int(K))) * 0.25).astype(np.float16) for K in widths]
+    for t in tables:
+        t[t == 0] = np.float16(0.0)              # +0 only: the sign of a zero result is pinned separately
+    flat = np.concatenate([t.ravel() for t in tables]).view(np.uint16)
+    sk = oracle.Sketch(in_f, out_f, tj, to, d, A, C, widths, flat)
+    got = as_f16(oracle.query(sk, oracle.QUERY_SIGNED_MAX)).astype(np.float64)
+    magnitude = as_f16(oracle.query(sk)).astype(np.float64)
+    G = tj * to
+    differs = 0
+    for jb in range(n_jb):
+        for ob in range(n_ob):
+            g = jb * n_ob + ob
+            K = int(widths[g])
+            per_row = []
+            for r in range(d):
+                P = np.zeros((G, K))
+                for a in range(G):
+                    P[a, (((int(A[r]) * a + int(C[r])) % (1 << 24)) * K) >> 24] = 1.0
+                per_row.append(P @ tables[g][r].astype(np.float64))
+            cands = np.stack(per_row)
+            ref = np.max(cands, axis=0).reshape(tj, to)
+            blk = got[jb * tj:(jb + 1) * tj, ob * to:(ob + 1) * to]
+            assert np.array_equal(blk, ref)
+            assert np.all((cands == ref.reshape(1, G)).any(axis=0))
+            differs += int(np.sum(blk != magnitude[jb * tj:(jb + 1) * tj, ob * to:(ob + 1) * to]))
+    assert differs > 0                           # the two readings of Eq. (5) are told apart on this data
+
+
+def test_signed_max_query_zero_tie_and_negative_candidates():
+    # +0 and -0 are equal values: the pattern with the clear sign bit wins, whatever the row order
+    for order in ([0x0000, 0x8000], [0x8000, 0x0000]):
+        sk = oracle.Sketch(1, 1, 1, 1, 2, np.uint32([1, 1]), np.uint32([0, 0]), np.uint32([1]), np.uint16(order))
+        assert oracle.query(sk, oracle.QUERY_SIGNED_MAX)[0, 0] == 0x0000
+    # all candidates negative: the one of smallest magnitude is the maximum (-0.5 over -2); -0 over -0.5
+    for cands, want in (([0xC000, 0xB800], 0xB800), ([0xB800, 0xC000], 0xB800), ([0xB800, 0x8000], 0x8000),
+                        ([0x3800, 0xC000], 0x3800)):
+        sk = oracle.Sketch(1, 1, 1, 1, 2, np.uint32([1, 1]), np.uint32([0, 0]), np.uint32([1]), np.uint16(cands))
+        assert oracle.query(sk, oracle.QUERY_SIGNED_MAX)[0, 0] == want
+        assert oracle.query(sk)[0, 0] == max(cands, key=lambda b: (b & 0x7FFF, -(b >> 15)))
 
 
 def test_query_signed_zero_tie():

@@ -84,7 +84,8 @@ typedef struct {
     uint32_t tile_in;          /* divides in_features  */
     uint32_t tile_out;         /* divides out_features; tile_in * tile_out <= 2^24 */
     uint32_t d;                /* sketch rows, 1..8 */
-    uint32_t query_mode;       /* 0 = magnitude Max as described above; others reserved */
+    uint32_t query_mode;       /* 0 = Max by magnitude as described above (default reading of Eq. 5);
+                                  1 = Max of the signed values, Eq. 5 as printed (+0 wins over -0) */
     uint32_t flags;            /* bit 0: always hash per weight (path 0) even when the geometry
                                   allows the row-sketch path; bit 1: row sketches take the staged
                                   prefill (SKL_PREFILL_STAGED) at every token count; bit 2: they take

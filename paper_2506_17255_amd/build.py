@@ -14,8 +14,12 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libsketch_linear.so")
-SOURCES = ["skl_host.cpp", "skl_decode.hip", "skl_reconstruct.hip", "skl_prefill.hip", "skl_prefill_staged.hip",
-           "skl_tile.hip", "skl_lowbit.hip", "skl_build.hip", "skl_naive.hip"]
+# compiled once
+COMMON_SOURCES = ["skl_host.cpp", "skl_dispatch.cpp", "skl_lowbit.hip", "skl_build.hip"]
+# compiled once per query mode (-DSKL_QM=0 / 1): their kernels and launchers live in a namespace per mode
+MODE_SOURCES = ["skl_prefill.hip", "skl_decode.hip", "skl_prefill_staged.hip", "skl_reconstruct.hip", "skl_tile.hip",
+                "skl_naive.hip"]
+SOURCES = COMMON_SOURCES + MODE_SOURCES
 
 
 def lib_path() -> str:
@@ -54,9 +58,12 @@ def build_library(verbose: bool = False, jobs: int | None = None, incremental: b
     `incremental`, objects newer than their source and every header are kept."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ_DIR, exist_ok=True)
-    jobs = jobs or min(len(SOURCES), max(1, min(os.cpu_count() or 1, 8)))
-    objs = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in SOURCES]
-    cmds = [[hipcc] + _flags() + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)
+    jobs = jobs or max(1, min(os.cpu_count() or 1, 8))
+    units = [(s, [], os.path.splitext(s)[0] + ".o") for s in COMMON_SOURCES]
+    # the long compilations first, so that the pool ends evenly
+    units = [(s, [f"-DSKL_QM={m}"], f"{os.path.splitext(s)[0]}_qm{m}.o") for s in MODE_SOURCES for m in (0, 1)] + units
+    objs = [os.path.join(OBJ_DIR, o) for _, _, o in units]
+    cmds = [[hipcc] + _flags() + defs + ["-c", os.path.join(CSRC, s), "-o", o] for (s, defs, _), o in zip(units, objs)
             if not incremental or _stale(os.path.join(CSRC, s), o)]
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(lambda c: _run(c, verbose), cmds))

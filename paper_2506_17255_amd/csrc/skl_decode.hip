@@ -3,6 +3,9 @@
 // variants for layers that share their input, and the split reduction.
 #include "skl_device.h"
 
+namespace SKL_NS {
+
+
 // ---- decode GEMV -----------------------------------------------------------
 // One workgroup per CU (one wavefront per 64 outputs, up to 16) owns an output
 // segment and a group of consecutive channel blocks.  The block tables are
@@ -727,46 +730,6 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
     return check_launch("gemv reduction");
 }
 
-// ---- decode without a caller workspace ----------------------------------------
-// For callers that cannot allocate (code under HIP graph capture, serving loops, harnesses that forbid it):
-// the partial sums of the split reduction (and, for low-bit layers, the expanded tables) go to a file-scope
-// device array instead of a workspace argument.  Every GPU the library runs on holds its own copy of the
-// array at its own address until the process ends; the address is looked up once per device, with that
-// device current, and only that pointer (never the array's name) is handed to kernels.
-static __device__ __align__(256) unsigned char scratch[SKL_STATIC_SCRATCH_BYTES];
-
-#define SKL_MAX_DEVICES 64
-static std::mutex g_scratch_mu;
-static void *g_scratch_ptr[SKL_MAX_DEVICES];
-
-uint64_t skl_static_scratch_bytes() { return SKL_STATIC_SCRATCH_BYTES; }
-
-skl_status_t skl_launch_gemv_static(const skl_layer *L, const void *x, uint32_t ldx, void *y, skl_dtype_t y_dt, uint32_t ldy,
-                                    uint32_t batch, void *stream)
-{
-    int dev = -1;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess || dev < 0 || dev >= SKL_MAX_DEVICES) {
-        skl_set_error("cannot identify the current device: %s", e != hipSuccess ? hipGetErrorString(e) : "device number out of range");
-        return SKL_ERR_HIP;
-    }
-    void *ptr = nullptr;
-    {
-        std::lock_guard<std::mutex> lock(g_scratch_mu);
-        if (!g_scratch_ptr[dev]) {
-            void *p = nullptr;
-            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
-            if (e != hipSuccess || !p) {
-                skl_set_error("address of the static scratch array on device %d: %s", dev, hipGetErrorString(e));
-                return SKL_ERR_HIP;
-            }
-            g_scratch_ptr[dev] = p;
-        }
-        ptr = g_scratch_ptr[dev];
-    }
-    return skl_launch_gemv(L, x, ldx, y, y_dt, ldy, batch, ptr, stream, true);
-}
-
 // ---- batch-1 decode of up to four layers that share their activations --------
 static bool group_layer_ok(const skl_layer *L, const skl_layer *first)
 {
@@ -872,3 +835,45 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
                            batch, F->out, (uint32_t)y_dt, ldy);
     return check_launch("grouped gemv reduction");
 }
+
+}  // namespace SKL_NS
+
+#if SKL_QM == 0
+// ---- decode without a caller workspace ----------------------------------------
+// For callers that cannot allocate (code under HIP graph capture, serving loops, harnesses that forbid it):
+// the partial sums of the split reduction (and, for low-bit layers, the expanded tables) go to a file-scope
+// device array instead of a workspace argument.  Every GPU the library runs on holds its own copy of the
+// array at its own address until the process ends; the address is looked up once per device, with that
+// device current, and only that pointer (never the array's name) is handed on: the decode kernels of either
+// query mode take it as their workspace argument.
+static __device__ __align__(256) unsigned char scratch[SKL_STATIC_SCRATCH_BYTES];
+
+#define SKL_MAX_DEVICES 64
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[SKL_MAX_DEVICES];
+
+uint64_t skl_static_scratch_bytes() { return SKL_STATIC_SCRATCH_BYTES; }
+
+// device address of the current device's copy of the array
+skl_status_t skl_static_scratch(void **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= SKL_MAX_DEVICES) {
+        skl_set_error("cannot identify the current device: %s", e != hipSuccess ? hipGetErrorString(e) : "device number out of range");
+        return SKL_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            skl_set_error("address of the static scratch array on device %d: %s", dev, hipGetErrorString(e));
+            return SKL_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return SKL_OK;
+}
+#endif

@@ -24,6 +24,22 @@
 
 #include "skl_internal.h"
 
+// Query mode this translation unit is compiled for (Sec. 3.1 Eq. 5): 0 = Max by magnitude, 1 = Max of the
+// signed values.  The kernel files are compiled once per mode, their kernels and launchers in a namespace
+// of their own; skl_dispatch.cpp picks the namespace by the layer's mode.  The modes differ only in the
+// order-key encoding (host side, at create) and in the decode below; the query is an unsigned 16-bit
+// maximum in both.
+//   mode 0   key = magnitude << 1 | (sign clear);        -w = rotate-right(key, 1) with the sign inverted
+//   mode 1   key = w | 0x8000 for w >= +0, ~w for w < 0;  -w = key ^ (key >= 0x8000 ? 0 : 0x7FFF)
+#ifndef SKL_QM
+#define SKL_QM 0
+#endif
+#if SKL_QM == 0
+#define SKL_NS skl_qm0
+#else
+#define SKL_NS skl_qm1
+#endif
+
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef _Float16 half8v __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
@@ -43,27 +59,48 @@ __device__ __forceinline__ uint4 pk_max_u16x8(uint4 a, uint4 b)
     return make_uint4(pk_max_u16(a.x, b.x), pk_max_u16(a.y, b.y), pk_max_u16(a.z, b.z), pk_max_u16(a.w, b.w));
 }
 
+typedef short short2v __attribute__((ext_vector_type(2)));
+
 // two keys -> two binary16 values with inverted sign bits
 __device__ __forceinline__ uint32_t keys_to_neg_half2(uint32_t k)
 {
+#if SKL_QM == 0
     return ((k >> 1) & 0x7FFF7FFFu) | ((k << 15) & 0x80008000u);
+#else
+    const uint32_t top = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2v, k) >> 15);    // 0xFFFF per half with the top bit set
+    return k ^ (~top & 0x7FFF7FFFu);
+#endif
 }
 
-// The same in two instructions instead of three, for loops bound by the vector
+// The same in two instructions instead of three (mode 0), for loops bound by the vector
 // ALU: per 16-bit half, (k >> 1) + k * 0x8000 (the product keeps bit 0 of k in
 // bit 15; the two terms share no bit).  The compiler turns the multiply back
 // into a shift and an OR, hence the explicit packed multiply-add.
 __device__ __forceinline__ uint32_t keys_to_neg_half2_mad(uint32_t k)
 {
+#if SKL_QM == 0
     uint32_t t, r;
     asm("v_pk_lshrrev_b16 %0, 1, %1 op_sel_hi:[0,1]" : "=v"(t) : "v"(k));
     asm("v_pk_mad_u16 %0, %1, %2, %3" : "=v"(r) : "v"(k), "s"(0x80008000u), "v"(t));
     return r;
+#else
+    return keys_to_neg_half2(k);
+#endif
 }
 
 __device__ __forceinline__ uint4 keys_to_neg_half8(uint4 k)
 {
     return make_uint4(keys_to_neg_half2(k.x), keys_to_neg_half2(k.y), keys_to_neg_half2(k.z), keys_to_neg_half2(k.w));
+}
+
+// one key -> the binary16 pattern it stands for
+__device__ __forceinline__ uint16_t key_to_half_bits(uint32_t k)
+{
+#if SKL_QM == 0
+    return (uint16_t)((k >> 1) | ((~k & 1u) << 15));
+#else
+    return (uint16_t)(k & 0x8000u ? k & 0x7FFFu : ~k);
+#endif
 }
 
 // value or zero, component by component (a select of whole 16-byte objects
@@ -222,11 +259,13 @@ skl_status_t skl_table_source(const skl_layer *L, void *area, bool want_padded, 
                               TableSrc *src);
 
 // launchers of the per-weight path (skl_tile.hip)
+namespace SKL_NS {
 skl_status_t skl_tile_launch_reconstruct(const skl_layer *L, const TableSrc &src, uint16_t *W_hat, hipStream_t stream);
 skl_status_t skl_tile_launch_gemv(const skl_layer *L, const TableSrc &src, const uint16_t *x, uint32_t ldx, uint32_t batch,
                                   float *partial, hipStream_t stream);
 skl_status_t skl_tile_launch_gemm(const skl_layer *L, const TableSrc &src, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx,
                                   void *Y, skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, hipStream_t stream);
+}  // namespace SKL_NS
 
 static inline skl_status_t check_launch(const char *what)
 {

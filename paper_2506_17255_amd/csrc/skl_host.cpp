@@ -67,7 +67,7 @@ static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out, b
     if ((uint64_t)d->tile_in * d->tile_out > (1ull << 24))
         FAIL(SKL_ERR_INVALID_ARG, "group of %ux%u weights exceeds 2^24 addresses", d->tile_in, d->tile_out);
     if (d->d < 1 || d->d > SKL_MAX_D) FAIL(SKL_ERR_INVALID_ARG, "d = %u sketch rows, must be 1..8", d->d);
-    if (d->query_mode != 0) FAIL(SKL_ERR_UNSUPPORTED, "query_mode %u is reserved", d->query_mode);
+    if (d->query_mode > 1) FAIL(SKL_ERR_INVALID_ARG, "query_mode = %u, must be 0 (Max by magnitude) or 1 (Max of the signed values)", d->query_mode);
     if (d->flags & ~7u) FAIL(SKL_ERR_INVALID_ARG, "unknown bits in flags: 0x%x", d->flags);
     if ((d->flags & 6u) == 6u) FAIL(SKL_ERR_INVALID_ARG, "flags ask for the staged and for the fused prefill at once");
     if (d->state_bits != 0 && d->state_bits != 16 && d->state_bits != 8 && d->state_bits != 4)
@@ -372,6 +372,7 @@ static skl_status_t make_plan(const skl_desc_t *user, skl_plan *P)
     L.n_groups = (uint32_t)n_groups;
     L.code_bytes = L.qbits == 8 ? d->n_states : L.qbits == 4 ? (d->n_states + 1) / 2 : 0;
     L.in = d->in_features; L.out = d->out_features; L.tj = d->tile_in; L.to = d->tile_out; L.d = d->d;
+    L.query_mode = d->query_mode;
     for (uint32_t r = 0; r < d->d; ++r) { L.A[r] = d->hash_a[r]; L.C[r] = d->hash_c[r]; }
     L.n_states = d->n_states;
     const bool rows_ok = d->tile_in == 1 && d->tile_out == d->out_features && !(d->flags & 1u);
@@ -473,7 +474,7 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
                 const uint32_t c = c8 / 8, i = c8 % 8;
                 for (uint32_t r = 0; r < L.d; ++r)
                     for (uint32_t k = 0; k < bm.K; ++k) {
-                        const uint16_t key = s ? skl_key_of_half(s[(uint64_t)r * bm.K + k]) : (uint16_t)1;
+                        const uint16_t key = skl_key_of_half(s ? s[(uint64_t)r * bm.K + k] : (uint16_t)0, L.query_mode);    // a slot without a channel: +0.0
                         t[(((uint64_t)r * bm.K + k) * bm.rs + c) * 8 + i] = key;
                         pt[(((uint64_t)r * bm.K + k) * bm.nb + c) * 8 + i] = key;
                     }
@@ -483,7 +484,7 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         memcpy(img.data() + L.off_gmeta, P.gmeta.data(), P.gmeta.size() * sizeof(skl_group_meta));
         if (!L.qbits) {
             uint16_t *keys = reinterpret_cast<uint16_t *>(img.data() + L.off_keys);
-            for (uint64_t i = 0; i < desc->n_states; ++i) keys[i] = skl_key_of_half(desc->states[i]);
+            for (uint64_t i = 0; i < desc->n_states; ++i) keys[i] = skl_key_of_half(desc->states[i], L.query_mode);
         }
     }
 

@@ -68,6 +68,7 @@ struct skl_layer {
     uint32_t in = 0, out = 0, tj = 0, to = 0, d = 0;
     uint32_t A[SKL_MAX_D] = {0}, C[SKL_MAX_D] = {0};
     uint32_t path = 0;
+    uint32_t query_mode = 0;        // 0: Max by magnitude, 1: Max of the signed values (Sec. 3.1 Eq. 5 as printed)
     uint8_t *dev = nullptr;
     uint64_t dev_bytes = 0;
     uint64_t n_states = 0;
@@ -138,10 +139,13 @@ void skl_set_error(const char *fmt, ...);
 // beyond the finiteness check
 skl_status_t skl_make_plan(const skl_desc_t *desc, skl_plan *plan);
 
-// order key of a binary16 bit pattern: magnitude first, clear sign bit wins
-static inline uint16_t skl_key_of_half(uint16_t b)
+// Order key of a binary16 bit pattern: the query (Eq. 5) becomes an unsigned 16-bit maximum of keys.
+//   mode 0: magnitude first, the clear sign bit wins a tie;
+//   mode 1: the order of the signed values, +0 above -0.
+static inline uint16_t skl_key_of_half(uint16_t b, uint32_t mode)
 {
-    return (uint16_t)(((b & 0x7FFFu) << 1) | (1u - (b >> 15)));
+    if (mode == 0) return (uint16_t)(((b & 0x7FFFu) << 1) | (1u - (b >> 15)));
+    return (uint16_t)(b & 0x8000u ? ~b : b | 0x8000u);
 }
 
 // ---- launchers implemented in skl_kernels.hip (all enqueue only) -----------

@@ -18,12 +18,14 @@ __device__ __forceinline__ int code_at(const uint8_t *codes, uint32_t i)
     return (int)(((i & 1) ? b >> 4 : b & 15u) ^ 8u) - 8;      // sign-extend the nibble
 }
 
+// mode: the layer's query mode (the order-key encoding of skl_key_of_half)
 template <int BITS>
-__device__ __forceinline__ uint16_t key_of_code(int q, uint16_t scale_bits)
+__device__ __forceinline__ uint16_t key_of_code(int q, uint16_t scale_bits, uint32_t mode)
 {
     const float v = __fdiv_rn((float)q * half_bits_to_float(scale_bits), BITS == 8 ? 127.0f : 7.0f);
     const uint16_t h = float_to_half_bits(v);
-    return (uint16_t)(((h & 0x7FFFu) << 1) | (1u - (h >> 15)));
+    if (mode == 0) return (uint16_t)(((h & 0x7FFFu) << 1) | (1u - (h >> 15)));
+    return (uint16_t)(h & 0x8000u ? ~h : h | 0x8000u);
 }
 
 // row sketches: grid (channel blocks, chunks of 256 words), one thread per 16-byte word: word (r, k, c) of a
@@ -31,7 +33,7 @@ __device__ __forceinline__ uint16_t key_of_code(int q, uint16_t scale_bits)
 template <int BITS>
 __global__ __launch_bounds__(SKL_WG) void k_expand_rows(const skl_block_meta *__restrict__ bmeta, const uint32_t *__restrict__ chan,
                                                          const uint32_t *__restrict__ choff, const uint8_t *__restrict__ codes,
-                                                         const uint16_t *__restrict__ scales, uint32_t d,
+                                                         const uint16_t *__restrict__ scales, uint32_t d, uint32_t mode,
                                                          uint4 *__restrict__ padded, uint4 *__restrict__ unpadded)
 {
     const skl_block_meta bm = bmeta[blockIdx.x];
@@ -51,8 +53,8 @@ __global__ __launch_bounds__(SKL_WG) void k_expand_rows(const skl_block_meta *__
     uint32_t key[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const uint32_t kk = key_of_code<BITS>(code_at<BITS>(codes, at[i]), (uint16_t)sc[i]);
-        key[i] = ch[i] != SKL_NO_CHANNEL ? kk : 1u;                              // a channel slot past the end: +0.0
+        const uint32_t kk = key_of_code<BITS>(code_at<BITS>(codes, at[i]), (uint16_t)sc[i], mode);
+        key[i] = ch[i] != SKL_NO_CHANNEL ? kk : (mode == 0 ? 1u : 0x8000u);      // a channel slot past the end: +0.0
     }
     const uint4 w = make_uint4(key[0] | key[1] << 16, key[2] | key[3] << 16, key[4] | key[5] << 16, key[6] | key[7] << 16);
     if (padded) padded[bm.table_off16 + (size_t)(r * K + k) * bm.rs + c] = w;
@@ -62,11 +64,12 @@ __global__ __launch_bounds__(SKL_WG) void k_expand_rows(const skl_block_meta *__
 // 2-D groups: keys in the caller's state order; grid (groups)
 template <int BITS>
 __global__ __launch_bounds__(SKL_WG) void k_expand_groups(const skl_group_meta *__restrict__ gmeta, const uint8_t *__restrict__ codes,
-                                                           const uint16_t *__restrict__ scales, uint32_t d, uint16_t *__restrict__ keys)
+                                                           const uint16_t *__restrict__ scales, uint32_t d, uint32_t mode,
+                                                           uint16_t *__restrict__ keys)
 {
     const skl_group_meta gm = gmeta[blockIdx.x];
     for (uint32_t idx = threadIdx.x; idx < d * gm.K; idx += SKL_WG)
-        keys[gm.key_off + idx] = key_of_code<BITS>(code_at<BITS>(codes, gm.key_off + idx), scales[blockIdx.x * d + idx / gm.K]);
+        keys[gm.key_off + idx] = key_of_code<BITS>(code_at<BITS>(codes, gm.key_off + idx), scales[blockIdx.x * d + idx / gm.K], mode);
 }
 
 
@@ -101,18 +104,18 @@ skl_status_t skl_table_source(const skl_layer *L, void *area, bool want_padded, 
         const dim3 grid(L->n_blocks, (L->max_ptable_bytes / 16 + SKL_WG - 1) / SKL_WG);
         if (L->qbits == 8)
             hipLaunchKernelGGL(k_expand_rows<8>, grid, dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
-                               L->d, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
+                               L->d, L->query_mode, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
         else
             hipLaunchKernelGGL(k_expand_rows<4>, grid, dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
-                               L->d, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
+                               L->d, L->query_mode, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
     } else {
         uint16_t *keys = static_cast<uint16_t *>(area);
         src->keys = keys;
         const skl_group_meta *gmeta = reinterpret_cast<const skl_group_meta *>(L->dev + L->off_gmeta);
         if (L->qbits == 8)
-            hipLaunchKernelGGL(k_expand_groups<8>, dim3(L->n_groups), dim3(SKL_WG), 0, stream, gmeta, codes, scales, L->d, keys);
+            hipLaunchKernelGGL(k_expand_groups<8>, dim3(L->n_groups), dim3(SKL_WG), 0, stream, gmeta, codes, scales, L->d, L->query_mode, keys);
         else
-            hipLaunchKernelGGL(k_expand_groups<4>, dim3(L->n_groups), dim3(SKL_WG), 0, stream, gmeta, codes, scales, L->d, keys);
+            hipLaunchKernelGGL(k_expand_groups<4>, dim3(L->n_groups), dim3(SKL_WG), 0, stream, gmeta, codes, scales, L->d, L->query_mode, keys);
     }
     return check_launch("expansion of low-bit states");
 }

@@ -6,6 +6,9 @@
 // against sketch_linear_reconstruct and the fused calls.
 #include "skl_device.h"
 
+namespace SKL_NS {
+
+
 struct NaiveRowArgs {
     HashArgs h;
     const skl_block_meta *bmeta;
@@ -31,7 +34,7 @@ __global__ __launch_bounds__(SKL_WG) void k_naive_rows(NaiveRowArgs p, uint16_t 
             const uint32_t key = tab[((size_t)(r * bm.K + k) * bm.rs + (c8 >> 3)) * 8 + (c8 & 7)];
             best = key > best ? key : best;
         }
-        W_hat[(size_t)ch * p.out + o] = (uint16_t)((best >> 1) | ((~best & 1u) << 15));
+        W_hat[(size_t)ch * p.out + o] = key_to_half_bits(best);
     }
 }
 
@@ -56,7 +59,7 @@ __global__ __launch_bounds__(SKL_WG) void k_naive_tiles(NaiveTileArgs p, uint16_
             const uint32_t key = p.keys[(size_t)gm.key_off + (size_t)r * gm.K + select_index(t, gm.K << 8)];
             best = key > best ? key : best;
         }
-        W_hat[(size_t)j * p.out + o] = (uint16_t)((best >> 1) | ((~best & 1u) << 15));
+        W_hat[(size_t)j * p.out + o] = key_to_half_bits(best);
     }
 }
 
@@ -89,3 +92,5 @@ skl_status_t skl_launch_reconstruct_naive(const skl_layer *L, uint16_t *W_hat, v
     }
     return check_launch("hash-based reconstruction");
 }
+
+}  // namespace SKL_NS

@@ -3,6 +3,9 @@
 // the fix-up pass, and the launcher that picks a kernel.
 #include "skl_prefill_common.h"
 
+namespace SKL_NS {
+
+
 // ---- activation re-ordering pre-pass ----------------------------------------
 // grid (ceil(steps / 4), 8 * token tiles); a workgroup re-orders 32 tokens x 4 steps
 __global__ __launch_bounds__(SKL_WG) void k_pack_activations2(const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
@@ -491,3 +494,5 @@ skl_status_t skl_launch_gemm(const skl_layer *L, const void *X_, skl_dtype_t x_d
     }
     return skl_tile_launch_gemm(L, src, X, x_dt, ldx, Y, y_dt, ldy, tokens, stream);
 }
+
+}  // namespace SKL_NS

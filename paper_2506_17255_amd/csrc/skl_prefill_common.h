@@ -4,6 +4,8 @@
 #include "skl_device.h"
 
 struct skl_gemm_step;
+struct G3Split;
+namespace SKL_NS {
 // activation re-ordering for the second and third prefill kernels (skl_prefill.hip)
 skl_status_t skl_launch_pack(const skl_layer *L, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx, uint32_t tokens,
                              const uint32_t *chan, const skl_gemm_step *steps, uint32_t n_steps, uint4 *Xp, hipStream_t stream);
@@ -11,6 +13,10 @@ skl_status_t skl_launch_pack(const skl_layer *L, const uint16_t *X, skl_dtype_t 
 uint64_t skl_gemm_staged_bytes(const skl_layer *L, uint32_t tokens);
 skl_status_t skl_launch_gemm_staged(const skl_layer *L, const TableSrc &src, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx,
                                     void *Y, skl_dtype_t y_dt, uint32_t ldy, uint32_t tokens, void *ws, hipStream_t stream);
+// adds the partials of the leftover tiles in workgroup order and stores them (skl_prefill.hip)
+skl_status_t skl_launch_gemm3_fixup(const G3Split &sp, const float *parts, void *Y, skl_dtype_t y_dt, uint32_t ldy,
+                                    uint32_t tokens, uint32_t out, uint32_t tile0, hipStream_t stream);
+}  // namespace SKL_NS
 
 #define GM_MT 256            // tokens per workgroup
 #define GM_NT 128            // outputs per workgroup
@@ -354,6 +360,3 @@ __device__ __forceinline__ void gemm3_store_rows(const float16v (&acc)[16], uint
 }
 
 
-// adds the partials of the leftover tiles in workgroup order and stores them (skl_prefill.hip)
-skl_status_t skl_launch_gemm3_fixup(const G3Split &sp, const float *parts, void *Y, skl_dtype_t y_dt, uint32_t ldy,
-                                    uint32_t tokens, uint32_t out, uint32_t tile0, hipStream_t stream);

@@ -15,6 +15,9 @@
 // The work split, partial tiles and fix-up pass are those of the fused kernel, dealt by output-tile column.
 #include "skl_prefill_common.h"
 
+namespace SKL_NS {
+
+
 #define SG_SLOT_WORDS 2048u             // 64 channels x 256 outputs: [column block 8][row 8 = (step, half)][32 outputs] words
 #define SG_SLOT_BYTES (SG_SLOT_WORDS * 16u)
 static_assert(4 * G3_EPI_BYTES >= 2 * SG_SLOT_BYTES, "the epilogue areas are the larger use of LDS");
@@ -292,3 +295,5 @@ skl_status_t skl_launch_gemm_staged(const skl_layer *L, const TableSrc &src, con
     }
     return SKL_OK;
 }
+
+}  // namespace SKL_NS

@@ -2,6 +2,9 @@
 // same tables, offsets and query as the fused kernels, written to memory.
 #include "skl_device.h"
 
+namespace SKL_NS {
+
+
 // ---- reconstruct (diagnostic): the same table, offsets and query ----------
 template <int D, int RS>
 __device__ __forceinline__ void row_reconstruct_body(const RowArgs &p, const skl_block_meta &bm, const uint4 *tab,
@@ -66,3 +69,5 @@ skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *w
     }
     return st == SKL_OK ? check_launch("reconstruct") : st;
 }
+
+}  // namespace SKL_NS

@@ -2,6 +2,9 @@
 // weight and sketch row.
 #include "skl_device.h"
 
+namespace SKL_NS {
+
+
 // ========================================================================
 // Path 0: 2-D groups, one hash evaluation per weight and sketch row.
 // A workgroup owns (group, chunk of the group's input rows, 256 outputs).
@@ -63,10 +66,6 @@ struct TileHash {
     }
 };
 
-__device__ __forceinline__ uint16_t key_to_half_bits(uint16_t k)
-{
-    return (uint16_t)((k >> 1) | ((~k & 1u) << 15));
-}
 
 template <int D>
 __global__ __launch_bounds__(SKL_WG) void k_tile_reconstruct(TileArgs p, uint16_t *__restrict__ W_hat)
@@ -273,3 +272,5 @@ skl_status_t skl_tile_launch_gemm(const skl_layer *L, const TableSrc &src, const
     });
     return st == SKL_OK ? check_launch("gemm") : st;
 }
+
+}  // namespace SKL_NS

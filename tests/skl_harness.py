@@ -27,7 +27,7 @@ def build_sketch(wl: wk.Workload, W=None, widths=None):
     return W, oracle.update(W, wl.tile_in, wl.tile_out, wl.d, A, C, widths)
 
 
-def desc_of(sk: oracle.Sketch, flags: int = 0):
+def desc_of(sk: oracle.Sketch, flags: int = 0, query_mode: int = 0):
     if isinstance(sk, oracle.QuantSketch):
         codes = np.ascontiguousarray(sk.codes, dtype=np.int8)
         packed = codes.view(np.uint8) if sk.bits == 8 else wk.pack_nibbles(codes)
@@ -35,26 +35,26 @@ def desc_of(sk: oracle.Sketch, flags: int = 0):
                              np.ascontiguousarray(sk.hash_a, dtype=np.uint32),
                              np.ascontiguousarray(sk.hash_c, dtype=np.uint32),
                              np.ascontiguousarray(sk.group_width, dtype=np.uint32), None, n_states=codes.size,
-                             flags=flags, state_bits=sk.bits, codes=packed,
+                             flags=flags, query_mode=query_mode, state_bits=sk.bits, codes=packed,
                              scales=np.ascontiguousarray(sk.scales, dtype=np.uint16))
     return skl.make_desc(sk.in_features, sk.out_features, sk.tile_in, sk.tile_out, sk.d,
                          np.ascontiguousarray(sk.hash_a, dtype=np.uint32),
                          np.ascontiguousarray(sk.hash_c, dtype=np.uint32),
                          np.ascontiguousarray(sk.group_width, dtype=np.uint32),
-                         np.ascontiguousarray(sk.states, dtype=np.uint16), flags=flags)
+                         np.ascontiguousarray(sk.states, dtype=np.uint16), flags=flags, query_mode=query_mode)
 
 
 class GpuLayer:
     """A layer resident on cuda:0 plus the buffers its calls need."""
 
-    def __init__(self, sk: oracle.Sketch, flags: int = 0):
+    def __init__(self, sk: oracle.Sketch, flags: int = 0, query_mode: int = 0):
         torch = torch_mod()
         if not torch.cuda.is_available():
             raise RuntimeError("GPU tests need a GPU")
         self.torch = torch
         self.sk = sk
         self.dev = torch.device("cuda:0")
-        desc = desc_of(sk, flags)
+        desc = desc_of(sk, flags, query_mode)
         nbytes = skl.sketch_linear_device_bytes(desc)
         self.dev_buf = torch.zeros(nbytes, dtype=torch.uint8, device=self.dev)
         self.handle = skl.sketch_linear_create(desc, self.dev_buf.data_ptr(), nbytes, self.stream())

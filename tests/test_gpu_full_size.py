@@ -88,6 +88,19 @@ def test_prefill_layers(key, kernel):
             assert rel_fro(y32[t:t + 1], g.gemv(xh, "f32")) <= 1e-5
 
 
+def test_signed_max_query_mode_on_the_up_projection():
+    """Query mode 1 (Eq. 5 as printed) at full size: 4096 x 11008, importance widths, decode and prefill."""
+    wl, sk, _ = layer("cfg3_up")
+    W_hat = oracle.query(sk, oracle.QUERY_SIGNED_MAX)
+    x = wk.gen_x(wl, 8)
+    X = wk.gen_X_bf16(wl, 2048)
+    with GpuLayer(sk, query_mode=1) as g:
+        assert np.array_equal(g.reconstruct(), W_hat)
+        assert rel_fro(g.gemv(x[:1], "f32"), oracle.linear(W_hat, x[:1])) <= 1e-5
+        assert rel_fro(g.gemv(x, "f32"), oracle.linear(W_hat, x)) <= 1e-5
+        check_prefill(g, W_hat, X, 11)
+
+
 @pytest.mark.parametrize("index", range(7))
 def test_stack_block_layers(index):
     """The seven linear layers of the first decoder block of the Llama-2-7B-shaped stack (q, k, v, o, gate,

@@ -306,6 +306,49 @@ def test_gemm_row_equals_gemv():
     assert rel_fro(Y, y) <= 1e-5
 
 
+# ------------------------------------------- query mode 1: Eq. (5) as printed
+SIGNED = ["cfg1", "row_ragged", "row_classes", "row_d1", "row_d5", "row_d8", "row_big_table", "row_four_words",
+          "tile_ragged", "tile_d8_K1", "tile_forced_1d"]
+
+
+@pytest.mark.parametrize("name", SIGNED)
+def test_signed_max_query_mode(name):
+    """Max of the signed values instead of Max by magnitude: another order-key encoding and decode, the same
+    kernels.  Reconstruction (staged kernel and hash-operator comparator) bit-exact, one-hot probes of the fused decode
+    exact, decode at batch 1 and 8 and both prefill kernels against the oracle in the same mode."""
+    W, sk = small_case(name)
+    W_hat = oracle.query(sk, oracle.QUERY_SIGNED_MAX)
+    assert not np.array_equal(W_hat, oracle.query(sk)) or sk.d == 1          # the two readings differ on this layer
+    rng = np.random.default_rng(400)
+    x = rng.standard_normal((8, sk.in_features)).astype(np.float16)
+    Xb = wk.f32_to_bf16_bits(rng.standard_normal((300, sk.in_features)).astype(np.float32))
+    ref = oracle.linear(W_hat, x)
+    ref_X = oracle.linear(W_hat, Xb, x_kind="bf16")
+    j = rng.choice(sk.in_features, size=min(16, sk.in_features), replace=False)
+    probe = np.zeros((j.size, sk.in_features), dtype=np.float16)
+    probe[np.arange(j.size), j] = 1.0
+    for flags in ([flags_of(name)] if not name.startswith("row") else [skl.FLAG_FUSED_PREFILL, skl.FLAG_STAGED_PREFILL]):
+        with GpuLayer(sk, flags, query_mode=1) as g:
+            assert np.array_equal(g.reconstruct(), W_hat)
+            assert np.array_equal(g.reconstruct(hash_op=True), W_hat)
+            assert rel_fro(g.gemv(x[:1], "f32"), ref[:1]) <= 1e-5
+            assert rel_fro(g.gemv(x, "f32"), ref) <= 1e-5
+            assert np.array_equal(g.gemv(probe, "f32"), W_hat.view(np.float16).astype(np.float32)[j])
+            assert np.array_equal(g.gemv(probe[:1], "f32"), W_hat.view(np.float16).astype(np.float32)[j[:1]])
+            assert rel_fro(g.gemm(Xb, "bf16", "f32"), ref_X) <= 1e-5
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_signed_max_query_mode_with_low_bit_states(bits):
+    W, sk = small_case("row_classes")
+    q = oracle.quantize(sk, bits)
+    W_hat = oracle.query(q, oracle.QUERY_SIGNED_MAX)
+    x = np.random.default_rng(401).standard_normal((3, sk.in_features)).astype(np.float16)
+    with GpuLayer(q, query_mode=1) as g:
+        assert np.array_equal(g.reconstruct(), W_hat)
+        assert rel_fro(g.gemv(x, "f32"), oracle.linear(W_hat, x)) <= 1e-5
+
+
 # ------------------------------------------------------- low-bit states
 LOWBIT = ["cfg1", "row_ragged", "row_classes", "row_d1", "row_d5", "row_d8", "row_big_table", "row_single",
           "tile_ragged", "tile_d8_K1", "tile_forced_1d"]

@@ -75,7 +75,7 @@ def test_valid_description_is_accepted():
     (dict(tile_out=5), skl.SKL_ERR_INVALID_ARG),
     (dict(d=0), skl.SKL_ERR_INVALID_ARG),
     (dict(d=9), skl.SKL_ERR_INVALID_ARG),
-    (dict(query_mode=1), skl.SKL_ERR_UNSUPPORTED),
+    (dict(query_mode=2), skl.SKL_ERR_INVALID_ARG),
     (dict(flags=8), skl.SKL_ERR_INVALID_ARG),
     (dict(flags=6), skl.SKL_ERR_INVALID_ARG),
     (dict(hash_a=None), skl.SKL_ERR_INVALID_ARG),

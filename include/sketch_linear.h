@@ -298,6 +298,25 @@ SKL_API skl_status_t sketch_linear_reconstruct(const skl_layer_t *layer, uint16_
 SKL_API skl_status_t sketch_linear_reconstruct_hash_op(const skl_layer_t *layer, uint16_t *W_hat_dev, void *workspace,
                                                uint64_t workspace_bytes, void *hip_stream);
 
+/* Diagnostic: one launch of a small kernel that measures a ceiling of the
+ * machine as this library's kernels can reach it, for stating roofline
+ * fractions against measured figures as well as data-sheet ones.
+ *   kind 0  vector ALU: packed 16-bit maximum and packed multiply-add on
+ *           registers (the instruction classes of the query and decode stages);
+ *           *work = lane-instructions issued;
+ *   kind 1  LDS: 16-byte reads at lane-dependent addresses without bank
+ *           conflicts; *work = bytes read;
+ *   kind 2  matrix cores: f16 MFMA 32x32x16 on registers, one wavefront per
+ *           SIMD; *work = floating-point operations;
+ *   kind 3  HBM: streaming read of the workspace past its first 4 MiB;
+ *           *work = bytes read.
+ * `iters` scales the work of kinds 0..2 (1..2^20; ignored for kind 3).
+ * workspace: DEVICE, 256-byte aligned, more than 4 MiB (kind 3: as much as
+ * should be streamed; use several times the cache sizes).  Only enqueues;
+ * time the launch with events on hip_stream. */
+SKL_API skl_status_t sketch_linear_microbench(uint32_t kind, uint32_t iters, void *workspace, uint64_t workspace_bytes,
+                                      void *hip_stream, uint64_t *work);
+
 /* Frees the host object only; dev_buf stays the caller's. NULL is accepted. */
 SKL_API void sketch_linear_destroy(skl_layer_t *layer);
 

@@ -39,7 +39,7 @@ EXPORTS = ("sketch_linear_device_bytes", "sketch_linear_create", "sketch_linear_
            "sketch_linear_reconstruct", "sketch_linear_gemv_partials", "sketch_linear_prefill_split",
            "sketch_linear_build_workspace_bytes", "sketch_linear_build_states",
            "sketch_linear_gemv_group_workspace_bytes", "sketch_linear_gemv_group", "sketch_linear_gemv_gate_up",
-           "sketch_linear_gemv_static", "sketch_linear_reconstruct_hash_op",
+           "sketch_linear_gemv_static", "sketch_linear_reconstruct_hash_op", "sketch_linear_microbench",
            "sketch_linear_destroy", "sketch_linear_last_error")
 
 
@@ -103,6 +103,7 @@ def load_library(path: str | None = None):
     L.sketch_linear_gemm.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_reconstruct.argtypes = [vp, vp, vp, u64, vp]
     L.sketch_linear_reconstruct_hash_op.argtypes = [vp, vp, vp, u64, vp]
+    L.sketch_linear_microbench.argtypes = [u32, u32, vp, u64, vp, ctypes.POINTER(u64)]
     L.sketch_linear_gemv_partials.argtypes = [vp, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_prefill_split.argtypes = [u32, u32, u32, u32, ctypes.POINTER(u32), u64, ctypes.POINTER(u64),
                                               ctypes.POINTER(u32)]
@@ -281,6 +282,13 @@ def sketch_linear_reconstruct(layer: int, W_hat_dev: int, workspace: int = 0, wo
 def sketch_linear_reconstruct_hash_op(layer: int, W_hat_dev: int, workspace: int = 0, workspace_bytes: int = 0,
                                       hip_stream: int = 0) -> None:
     _check(load_library().sketch_linear_reconstruct_hash_op(layer, W_hat_dev, workspace, workspace_bytes, hip_stream))
+
+
+def sketch_linear_microbench(kind: int, iters: int, workspace: int, workspace_bytes: int, hip_stream: int = 0) -> int:
+    """Enqueues one ceiling kernel; returns the work it does (lane-instructions, bytes or flops)."""
+    work = ctypes.c_uint64(0)
+    _check(load_library().sketch_linear_microbench(kind, iters, workspace, workspace_bytes, hip_stream, ctypes.byref(work)))
+    return work.value
 
 
 def sketch_linear_destroy(layer: int) -> None:

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libsketch_linear.so")
 # compiled once
-COMMON_SOURCES = ["skl_host.cpp", "skl_dispatch.cpp", "skl_lowbit.hip", "skl_build.hip"]
+COMMON_SOURCES = ["skl_host.cpp", "skl_dispatch.cpp", "skl_lowbit.hip", "skl_build.hip", "skl_microbench.hip"]
 # compiled once per query mode (-DSKL_QM=0 / 1): their kernels and launchers live in a namespace per mode
 MODE_SOURCES = ["skl_prefill.hip", "skl_decode.hip", "skl_prefill_staged.hip", "skl_reconstruct.hip", "skl_tile.hip",
                 "skl_naive.hip"]

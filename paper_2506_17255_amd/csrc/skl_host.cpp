@@ -256,7 +256,7 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
     P->bmeta.clear();
     P->chan.clear();
     uint64_t off16 = 0, poff16 = 0;
-    uint32_t max_table = 0;
+    uint32_t max_table = 0, soff16 = 0;
     static const uint32_t rs_options[4] = {9, 5, 3, 1};
     uint32_t i = 0;
     while (i < in) {
@@ -281,6 +281,8 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
             bm.nb = nb;
             bm.chan_off = (uint32_t)P->chan.size();
             bm.ptable_off16 = (uint32_t)poff16;
+            bm.scale_off16 = soff16;
+            soff16 += d->d * nb;
             poff16 += ((uint64_t)d->d * K * nb + 63) / 64 * 64;    // whole 64-word chunks: copied without bounds checks
             for (uint32_t c = 0; c < 8 * nb; ++c)
                 P->chan.push_back(s + c < e ? order[s + c] : SKL_NO_CHANNEL);
@@ -299,6 +301,7 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
     L.max_table_bytes = max_table;
     L.table_bytes = off16 * 16;
     L.ptable_bytes = poff16 * 16;
+    L.scale_words = soff16;
     L.max_ptable_bytes = 0;
     L.block_classes = 0;
     for (const skl_block_meta &bm : P->bmeta) {
@@ -391,8 +394,6 @@ static skl_status_t make_plan(const skl_desc_t *user, skl_plan *P)
         if (!L.qbits) {
             L.off_tables = off; off = align_up(off + L.table_bytes, 256);
             L.off_ptables = off; off = align_up(off + L.ptable_bytes, 256);
-        } else {
-            L.off_choff = off;  off = align_up(off + ((uint64_t)L.in + 1) * sizeof(uint32_t), 256);
         }
     } else {
         L.off_gmeta = off;  off = align_up(off + P->gmeta.size() * sizeof(skl_group_meta), 256);
@@ -400,8 +401,15 @@ static skl_status_t make_plan(const skl_desc_t *user, skl_plan *P)
     }
     if (L.qbits) {
         if (n_groups >= (1ull << 32) / SKL_MAX_D) FAIL(SKL_ERR_UNSUPPORTED, "too many groups for low-bit states");
+        if (L.path == 1) {
+            // re-ordered: eight codes per word of the unpadded tables, eight scales per (block, row, word)
+            L.code_bytes = L.ptable_bytes / 16 * (L.qbits == 8 ? 8 : 4);
+            L.scale_bytes = (uint64_t)L.scale_words * 16;
+        } else {
+            L.scale_bytes = n_groups * d->d * sizeof(uint16_t);
+        }
         L.off_codes = off;  off = align_up(off + L.code_bytes + 16, 256);
-        L.off_scales = off; off = align_up(off + n_groups * d->d * sizeof(uint16_t), 256);
+        L.off_scales = off; off = align_up(off + L.scale_bytes, 256);
     }
     P->dev_bytes = off;
     return SKL_OK;
@@ -446,9 +454,9 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
     }
     skl_layer &L = P.L;
     desc = &P.desc;                 // from here on: the description in the current struct layout
-    if (L.qbits) {
+    if (L.qbits && L.path == 0) {
         memcpy(img.data() + L.off_codes, desc->codes, L.code_bytes);
-        memcpy(img.data() + L.off_scales, desc->scales, (uint64_t)L.n_groups * L.d * sizeof(uint16_t));
+        memcpy(img.data() + L.off_scales, desc->scales, L.scale_bytes);
     }
     if (L.path == 1) {
         memcpy(img.data() + L.off_bmeta, P.bmeta.data(), P.bmeta.size() * sizeof(skl_block_meta));
@@ -459,8 +467,24 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         // state offset of every input channel (one group per channel)
         for (uint32_t j = 0; j < L.in; ++j) base[j + 1] = base[j] + (uint64_t)L.d * desc->group_width[j];
         if (L.qbits) {
-            uint32_t *choff = reinterpret_cast<uint32_t *>(img.data() + L.off_choff);
-            for (uint32_t j = 0; j <= L.in; ++j) choff[j] = (uint32_t)base[j];
+            // codes and scales in the word order of the block tables (expanded on the device, per call)
+            uint8_t *tc = img.data() + L.off_codes;
+            uint16_t *ts = reinterpret_cast<uint16_t *>(img.data() + L.off_scales);
+            const uint32_t wb = L.qbits == 8 ? 8 : 4;           // bytes of codes per table word
+            for (const skl_block_meta &bm : P.bmeta)
+                for (uint32_t c8 = 0; c8 < 8 * bm.nb; ++c8) {
+                    const uint32_t ch = P.chan[bm.chan_off + c8], c = c8 / 8, i = c8 % 8;
+                    if (ch == SKL_NO_CHANNEL) continue;         // code 0 and scale 0: +0.0
+                    for (uint32_t r = 0; r < L.d; ++r) {
+                        ts[((uint64_t)bm.scale_off16 + r * bm.nb + c) * 8 + i] = desc->scales[(uint64_t)ch * L.d + r];
+                        for (uint32_t k = 0; k < bm.K; ++k) {
+                            const int q = code_at(desc, base[ch] + (uint64_t)r * bm.K + k);
+                            uint8_t *w = tc + ((uint64_t)bm.ptable_off16 + ((uint64_t)r * bm.K + k) * bm.nb + c) * wb;
+                            if (L.qbits == 8) w[i] = (uint8_t)q;
+                            else w[i >> 1] |= (uint8_t)((q & 15) << ((i & 1) * 4));
+                        }
+                    }
+                }
         }
         uint16_t *tab = reinterpret_cast<uint16_t *>(img.data() + L.off_tables);
         uint16_t *ptab = reinterpret_cast<uint16_t *>(img.data() + L.off_ptables);
@@ -512,7 +536,7 @@ skl_status_t sketch_linear_info(const skl_layer_t *L, skl_info_t *info)
     info->path = L->path;
     info->n_units = L->n_units;
     info->max_table_bytes = L->max_table_bytes;
-    info->table_bytes = L->qbits ? L->code_bytes + (uint64_t)L->n_groups * L->d * sizeof(uint16_t) : L->table_bytes;
+    info->table_bytes = L->qbits ? L->code_bytes + L->scale_bytes : L->table_bytes;
     info->n_weights = (uint64_t)L->in * L->out;
     info->n_states = L->n_states;
     if (info->struct_size == SKL_INFO_SIZE_V1) return SKL_OK;
@@ -787,6 +811,17 @@ skl_status_t sketch_linear_reconstruct_hash_op(const skl_layer_t *L, uint16_t *W
                                                void *stream)
 {
     return reconstruct_with(L, W_hat_dev, ws, ws_bytes, stream, true);
+}
+
+skl_status_t sketch_linear_microbench(uint32_t kind, uint32_t iters, void *ws, uint64_t ws_bytes, void *stream, uint64_t *work)
+{
+    if (kind > 3) FAIL(SKL_ERR_INVALID_ARG, "kind = %u, must be 0 (vector ALU), 1 (LDS), 2 (matrix cores) or 3 (HBM read)", kind);
+    if (!ws || (uintptr_t)ws % 256) FAIL(SKL_ERR_INVALID_ARG, "workspace is NULL or not 256-byte aligned");
+    if (kind < 3 && (iters < 1 || iters > (1u << 20))) FAIL(SKL_ERR_INVALID_ARG, "iters = %u, must be 1..2^20", iters);
+    if (!work) FAIL(SKL_ERR_INVALID_ARG, "work is NULL");
+    const skl_status_t st = skl_launch_microbench(kind, iters, ws, ws_bytes, stream);
+    if (st == SKL_OK) *work = skl_microbench_work(kind, iters, ws_bytes);
+    return st;
 }
 
 }  // extern "C"

@@ -45,7 +45,7 @@ struct skl_block_meta {
                            // (= first packed activation column of the block)
     uint32_t ptable_off16; // the block's table in the unpadded copy ([r][k][nb] words)
     uint32_t step_off;     // first 16-channel MFMA step of the block in the prefill walk
-    uint32_t pad2;
+    uint32_t scale_off16;  // low-bit states: the block's scale words ([r][c] x eight binary16 scales) from the scale base
 };
 
 // One block group of the decode plan: consecutive blocks [b_lo, b_hi), their
@@ -109,10 +109,11 @@ struct skl_layer {
     uint32_t gemm_staged_from = 0, gemm_kb = 0;     // calls with at least gemm_staged_from tokens are staged
     uint64_t off_ssteps = 0;
 
-    // low-bit states: only codes, scales and (path 1) the state offset of every input channel are
-    // resident; every call expands them into 16-bit tables at the end of its workspace
+    // low-bit states: only codes and scales are resident (row sketches: re-ordered into the word order of the
+    // block tables); every call expands them into 16-bit tables at the end of its workspace
     uint32_t qbits = 0;             // 0 (binary16 states), 8 or 4
-    uint64_t off_codes = 0, off_scales = 0, off_choff = 0, code_bytes = 0;
+    uint64_t off_codes = 0, off_scales = 0, code_bytes = 0, scale_bytes = 0;
+    uint32_t scale_words = 0;       // row sketches: 16-byte scale words over all blocks
     uint32_t n_groups = 0;
 };
 
@@ -175,5 +176,8 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
 // sketch construction: group_base holds n_groups + 1 state offsets (host); synchronises the stream once
 skl_status_t skl_launch_build(const skl_desc_t *d, uint64_t n_groups, const uint64_t *group_base, const uint16_t *W,
                               uint16_t *states, void *ws, void *stream);
+// ceilings of the machine: four small kernels (skl_microbench.hip)
+uint64_t skl_microbench_work(uint32_t kind, uint32_t iters, uint64_t ws_bytes);
+skl_status_t skl_launch_microbench(uint32_t kind, uint32_t iters, void *ws, uint64_t ws_bytes, void *stream);
 uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, bool by_col, uint32_t *segs, uint64_t cap,
                             uint32_t *shape);

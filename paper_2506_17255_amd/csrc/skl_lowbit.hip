@@ -5,10 +5,13 @@
 // only codes and one binary16 scale per (group, sketch row) resident; every
 // call first expands them into the 16-bit tables its kernels read (the same
 // layouts create() builds on the host for binary16 states).  The state a code
-// stands for is q * scale / qmax rounded once to binary16: the product is
-// exact in float32 (7 x 11 significant bits), the correctly rounded float32
-// quotient is either exact or far from any binary16 rounding boundary (qmax is
-// odd), so the second rounding never changes the result.
+// stands for is q * scale / qmax rounded once to binary16.  The product
+// q * scale is exact in float32 (7 x 11 significant bits); it is multiplied by
+// the float32 reciprocal of qmax, which is within 1.5 units in the last place
+// of the exact quotient.  The exact quotient m / qmax (m an integer of at most
+// 18 bits) is never closer to a binary16 rounding boundary than 1 / (2 qmax) of
+// a binary16 spacing -- 32 float32 spacings for qmax = 127, 585 for qmax = 7 --
+// so rounding the approximation to binary16 gives the correctly rounded state.
 // ========================================================================
 template <int BITS>
 __device__ __forceinline__ int code_at(const uint8_t *codes, uint32_t i)
@@ -22,43 +25,41 @@ __device__ __forceinline__ int code_at(const uint8_t *codes, uint32_t i)
 template <int BITS>
 __device__ __forceinline__ uint16_t key_of_code(int q, uint16_t scale_bits, uint32_t mode)
 {
-    const float v = __fdiv_rn((float)q * half_bits_to_float(scale_bits), BITS == 8 ? 127.0f : 7.0f);
+    const float v = (float)q * half_bits_to_float(scale_bits) * (BITS == 8 ? 1.0f / 127.0f : 1.0f / 7.0f);
     const uint16_t h = float_to_half_bits(v);
     if (mode == 0) return (uint16_t)(((h & 0x7FFFu) << 1) | (1u - (h >> 15)));
     return (uint16_t)(h & 0x8000u ? ~h : h | 0x8000u);
 }
 
-// row sketches: grid (channel blocks, chunks of 256 words), one thread per 16-byte word: word (r, k, c) of a
-// block holds the keys of channels 8c .. 8c + 7; writes the padded layout, the unpadded one, or both
+// Row sketches.  create() keeps the codes in the order of the block tables: word (r, k, c) of a block holds
+// the eight codes of channels 8c .. 8c + 7 for state (r, k) -- 4 bytes (nibble i = channel 8c + i) or
+// 8 bytes per word, at the word's index in the unpadded table -- and the scales as one 16-byte word of
+// eight binary16 values per (r, c) of a block.  grid (channel blocks, chunks of 256 words), one thread per
+// table word: one load of codes, one (cached) load of scales, eight conversions, one or two 16-byte stores.
 template <int BITS>
-__global__ __launch_bounds__(SKL_WG) void k_expand_rows(const skl_block_meta *__restrict__ bmeta, const uint32_t *__restrict__ chan,
-                                                         const uint32_t *__restrict__ choff, const uint8_t *__restrict__ codes,
-                                                         const uint16_t *__restrict__ scales, uint32_t d, uint32_t mode,
+__global__ __launch_bounds__(SKL_WG) void k_expand_rows(const skl_block_meta *__restrict__ bmeta, const uint8_t *__restrict__ tcodes,
+                                                         const uint4 *__restrict__ tscales, uint32_t d, uint32_t mode,
                                                          uint4 *__restrict__ padded, uint4 *__restrict__ unpadded)
 {
     const skl_block_meta bm = bmeta[blockIdx.x];
     const uint32_t K = bm.K, nb = bm.nb;
-    const uint32_t idx = blockIdx.y * SKL_WG + threadIdx.x;
+    const uint32_t idx = blockIdx.y * SKL_WG + threadIdx.x;     // (r * K + k) * nb + c
     if (idx >= d * nb * K) return;
-    const uint32_t k = idx % K, c = (idx / K) % nb, r = idx / (K * nb);         // k fastest: neighbouring lanes read neighbouring codes
-    uint32_t ch[8], at[8], sc[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) ch[i] = chan[bm.chan_off + 8 * c + i];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const uint32_t cc = ch[i] != SKL_NO_CHANNEL ? ch[i] : 0;                // every lane issues the same loads; unused ones are dropped below
-        at[i] = choff[cc] + r * K + k;
-        sc[i] = scales[cc * d + r];
-    }
+    const uint32_t c = idx % nb, rk = idx / nb, r = rk / K;
+    uint64_t packed;
+    if (BITS == 8) packed = reinterpret_cast<const uint64_t *>(tcodes)[(size_t)bm.ptable_off16 + idx];
+    else packed = reinterpret_cast<const uint32_t *>(tcodes)[(size_t)bm.ptable_off16 + idx];
+    const uint4 sw = tscales[bm.scale_off16 + r * nb + c];
+    const uint32_t sc[4] = {sw.x, sw.y, sw.z, sw.w};
     uint32_t key[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const uint32_t kk = key_of_code<BITS>(code_at<BITS>(codes, at[i]), (uint16_t)sc[i], mode);
-        key[i] = ch[i] != SKL_NO_CHANNEL ? kk : (mode == 0 ? 1u : 0x8000u);      // a channel slot past the end: +0.0
+        const int q = BITS == 8 ? (int)(int8_t)(packed >> (8 * i)) : (int)(((uint32_t)(packed >> (4 * i)) & 15u) ^ 8u) - 8;
+        key[i] = key_of_code<BITS>(q, (uint16_t)(sc[i >> 1] >> ((i & 1) * 16)), mode);     // a slot without a channel has code 0: +0.0
     }
     const uint4 w = make_uint4(key[0] | key[1] << 16, key[2] | key[3] << 16, key[4] | key[5] << 16, key[6] | key[7] << 16);
-    if (padded) padded[bm.table_off16 + (size_t)(r * K + k) * bm.rs + c] = w;
-    if (unpadded) unpadded[bm.ptable_off16 + (size_t)(r * K + k) * nb + c] = w;
+    if (padded) padded[bm.table_off16 + (size_t)rk * bm.rs + c] = w;
+    if (unpadded) unpadded[bm.ptable_off16 + (size_t)idx] = w;
 }
 
 // 2-D groups: keys in the caller's state order; grid (groups)
@@ -98,15 +99,14 @@ skl_status_t skl_table_source(const skl_layer *L, void *area, bool want_padded, 
         uint4 *unpadded = reinterpret_cast<uint4 *>(static_cast<char *>(area) + round256(L->table_bytes));
         src->tables = padded; src->ptables = unpadded;
         const skl_block_meta *bmeta = reinterpret_cast<const skl_block_meta *>(L->dev + L->off_bmeta);
-        const uint32_t *chan = reinterpret_cast<const uint32_t *>(L->dev + L->off_chan);
-        const uint32_t *choff = reinterpret_cast<const uint32_t *>(L->dev + L->off_choff);
+        const uint4 *tscales = reinterpret_cast<const uint4 *>(scales);
         // max_ptable_bytes: the largest block's unpadded table, rounded up to KiB: 16-byte words per block
         const dim3 grid(L->n_blocks, (L->max_ptable_bytes / 16 + SKL_WG - 1) / SKL_WG);
         if (L->qbits == 8)
-            hipLaunchKernelGGL(k_expand_rows<8>, grid, dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
+            hipLaunchKernelGGL(k_expand_rows<8>, grid, dim3(SKL_WG), 0, stream, bmeta, codes, tscales,
                                L->d, L->query_mode, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
         else
-            hipLaunchKernelGGL(k_expand_rows<4>, grid, dim3(SKL_WG), 0, stream, bmeta, chan, choff, codes, scales,
+            hipLaunchKernelGGL(k_expand_rows<4>, grid, dim3(SKL_WG), 0, stream, bmeta, codes, tscales,
                                L->d, L->query_mode, want_padded ? padded : nullptr, want_unpadded ? unpadded : nullptr);
     } else {
         uint16_t *keys = static_cast<uint16_t *>(area);

@@ -391,6 +391,26 @@ def test_low_bit_states_match_oracle(name, bits):
     assert rel_fro(Ybf, round_to_bf16(refX[:70])) <= TOL
 
 
+@pytest.mark.parametrize("bits", [8, 4])
+def test_low_bit_dequantisation_over_every_scale_and_code(bits):
+    """Every finite positive binary16 scale (31744 of them, one input channel each) with every code in its
+    sketch row: the states the library expands on the device are those of the oracle, bit for bit.  (The
+    device multiplies by the reciprocal of qmax instead of dividing; this is the exhaustive check of that.)"""
+    qmax = 127 if bits == 8 else 7
+    K = 2 * qmax + 1
+    in_f, out_f, d = 31744, 2048, 1
+    scales = np.arange(in_f, dtype=np.uint16)                       # patterns 0x0000 .. 0x7BFF
+    codes = np.tile(np.arange(-qmax, qmax + 1, dtype=np.int8), in_f)
+    widths = np.full(in_f, K, dtype=np.uint32)
+    states = oracle.dequantize_states(in_f, out_f, 1, out_f, d, widths, bits, codes, scales)
+    q = oracle.QuantSketch(in_f, out_f, 1, out_f, d, np.uint32([0x9E3779]), np.uint32([0x12345]), widths, states,
+                           bits=bits, codes=codes, scales=scales)
+    W_hat = oracle.query(q)
+    assert len(np.unique(W_hat[-1])) == K                           # every state of a row is reached by some output
+    with GpuLayer(q) as g:
+        assert np.array_equal(g.reconstruct(), W_hat)
+
+
 def test_low_bit_workspace_holds_the_expanded_tables():
     import paper_2506_17255_amd as skl
     W, sk = small_case("row_classes")

@@ -17,7 +17,8 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sketch_oracle.c")
-_LIB = os.path.join(_HERE, "libsketch_oracle.so")
+# SKETCH_ORACLE_LIB: an already built library to load instead (the sanitizer run of the test suite uses it)
+_LIB = os.environ.get("SKETCH_ORACLE_LIB") or os.path.join(_HERE, "libsketch_oracle.so")
 
 _u32p = ctypes.POINTER(ctypes.c_uint32)
 _u16p = ctypes.POINTER(ctypes.c_uint16)
@@ -26,6 +27,8 @@ _f64p = ctypes.POINTER(ctypes.c_double)
 
 def build(force: bool = False) -> str:
     """Compile the C oracle (gcc -O2, no intrinsics, no OpenMP)."""
+    if os.environ.get("SKETCH_ORACLE_LIB"):
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
             ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",

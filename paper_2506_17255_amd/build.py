@@ -23,7 +23,9 @@ SOURCES = COMMON_SOURCES + MODE_SOURCES
 
 
 def lib_path() -> str:
-    return LIB
+    """The built library; SKETCH_LINEAR_LIB names another build to load instead (the host-only sanitizer
+    build of the test suite)."""
+    return os.environ.get("SKETCH_LINEAR_LIB") or LIB
 
 
 def _flags():

@@ -20,8 +20,6 @@
     skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, const void *x, uint32_t ldx,                  \
                                        void *const *ys, skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *ws, void *stream,  \
                                        bool gate_up);                                                                            \
-    uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, bool grouped, uint32_t *segs, uint64_t cap,    \
-                                uint32_t *shape);                                                                                \
     }
 SKL_DECLARE_MODE(skl_qm0)
 SKL_DECLARE_MODE(skl_qm1)
@@ -78,8 +76,4 @@ uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens) { return 
 uint64_t skl_gemv_group_workspace_bytes(const skl_layer *const *layers, uint32_t n, uint32_t batch)
 {
     return skl_qm0::skl_gemv_group_workspace_bytes(layers, n, batch);
-}
-uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, bool grouped, uint32_t *segs, uint64_t cap, uint32_t *shape)
-{
-    return skl_qm0::skl_gemm3_segments(out, n_blocks, tokens, grouped, segs, cap, shape);
 }

@@ -25,8 +25,10 @@ __device__ __forceinline__ int code_at(const uint8_t *codes, uint32_t i)
 template <int BITS>
 __device__ __forceinline__ uint16_t key_of_code(int q, uint16_t scale_bits, uint32_t mode)
 {
-    const float v = (float)q * half_bits_to_float(scale_bits) * (BITS == 8 ? 1.0f / 127.0f : 1.0f / 7.0f);
-    const uint16_t h = float_to_half_bits(v);
+    // magnitude and sign apart: the sign of a zero state (negative code, zero scale) must survive, and a
+    // multiply fused with the conversion (fma with a +0 addend) would lose it
+    const float mag = (float)(q < 0 ? -q : q) * half_bits_to_float(scale_bits) * (BITS == 8 ? 1.0f / 127.0f : 1.0f / 7.0f);
+    const uint16_t h = (uint16_t)(float_to_half_bits(mag) | (q < 0 ? 0x8000u : 0u));
     if (mode == 0) return (uint16_t)(((h & 0x7FFFu) << 1) | (1u - (h >> 15)));
     return (uint16_t)(h & 0x8000u ? ~h : h | 0x8000u);
 }

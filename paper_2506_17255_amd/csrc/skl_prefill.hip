@@ -377,31 +377,6 @@ __global__ __launch_bounds__(256) void k_gemm3_fixup(G3Split sp, const float *__
 // ========================================================================
 static G3Split gemm3_split(const skl_layer *L, uint32_t tokens) { return skl_make_split(L->out, L->n_blocks, tokens, false); }
 
-// every segment of the split, eight words each: xcd, workgroup, token tile, output tile, first block,
-// end block, whole-tile flag, partial slot; returns the number of segments (writes at most cap of them)
-uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, bool grouped, uint32_t *segs, uint64_t cap,
-                            uint32_t *shape)
-{
-    const G3Split sp = skl_make_split(out, n_blocks, tokens, grouped);
-    if (shape) { shape[0] = sp.gx; shape[1] = sp.l_max; shape[2] = sp.p_cap; shape[3] = sp.T; shape[4] = sp.mu; }
-    uint64_t n = 0;
-    for (uint32_t x = 0; x < 8; ++x)
-        for (uint32_t wg = 0; wg < sp.gx; ++wg) {
-            uint32_t round = 0, u_next = sp.share_begin(x, wg);
-            G3Split::Seg sg;
-            while (sp.next(x, wg, round, u_next, sg)) {
-                if (n < cap) {
-                    uint32_t *o = segs + 8 * n;
-                    o[0] = x; o[1] = wg;
-                    sp.tile_of(x, sg.k, o[2], o[3]);
-                    o[4] = sg.k0; o[5] = sg.k1; o[6] = sg.whole; o[7] = (uint32_t)sg.part_slot;
-                }
-                ++n;
-            }
-        }
-    return n;
-}
-
 static uint64_t gemm_pack_bytes(const skl_layer *L, uint32_t tokens)
 {
     const uint64_t m_tiles = (tokens + GM_MT - 1) / GM_MT;

@@ -159,6 +159,18 @@ SKL_API skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf,
 
 SKL_API skl_status_t sketch_linear_info(const skl_layer_t *layer, skl_info_t *info);
 
+/* Diagnostic, host only (no GPU call, no device memory): what create() would
+ * decide for this description, and the decode planner's own cost model (Sec.
+ * 3.2 / 3.3 widths -> channel blocks -> output segments x block groups, one
+ * workgroup each).  segments = groups = 0: the plan the library picks.
+ * Otherwise: the same layer planned with that decode split --
+ * SKL_ERR_UNSUPPORTED if the kernels cannot run it (more than 16 wave units
+ * of 64 outputs per segment, or more than 64 channel blocks per group).
+ * *decode_cost_us (may be NULL) receives the model's microseconds for the
+ * split (0 for layers on the per-weight path). */
+SKL_API skl_status_t sketch_linear_plan(const skl_desc_t *desc, uint32_t segments, uint32_t groups, skl_info_t *info,
+                                double *decode_cost_us);
+
 /* Bytes of DEVICE workspace needed by gemv (op = 0, n = batch), gemm
  * (op = 1, n = tokens) or reconstruct (op = 2, n ignored).  The workspace
  * holds the partial sums of the split reduction (gemv), the re-ordered fp16

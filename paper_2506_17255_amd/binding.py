@@ -39,7 +39,7 @@ EXPORTS = ("sketch_linear_device_bytes", "sketch_linear_create", "sketch_linear_
            "sketch_linear_reconstruct", "sketch_linear_gemv_partials", "sketch_linear_prefill_split",
            "sketch_linear_build_workspace_bytes", "sketch_linear_build_states",
            "sketch_linear_gemv_group_workspace_bytes", "sketch_linear_gemv_group", "sketch_linear_gemv_gate_up",
-           "sketch_linear_gemv_static", "sketch_linear_reconstruct_hash_op", "sketch_linear_microbench",
+           "sketch_linear_plan", "sketch_linear_gemv_static", "sketch_linear_reconstruct_hash_op", "sketch_linear_microbench",
            "sketch_linear_destroy", "sketch_linear_last_error")
 
 
@@ -98,6 +98,7 @@ def load_library(path: str | None = None):
     L.sketch_linear_device_bytes.argtypes = [ctypes.POINTER(skl_desc_t), ctypes.POINTER(u64)]
     L.sketch_linear_create.argtypes = [ctypes.POINTER(skl_desc_t), vp, u64, vp, ctypes.POINTER(vp)]
     L.sketch_linear_info.argtypes = [vp, ctypes.POINTER(skl_info_t)]
+    L.sketch_linear_plan.argtypes = [ctypes.POINTER(skl_desc_t), u32, u32, ctypes.POINTER(skl_info_t), ctypes.POINTER(ctypes.c_double)]
     L.sketch_linear_workspace_bytes.argtypes = [vp, u32, u32, ctypes.POINTER(u64)]
     L.sketch_linear_gemv.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
     L.sketch_linear_gemm.argtypes = [vp, vp, ctypes.c_int, u32, vp, ctypes.c_int, u32, u32, vp, u64, vp]
@@ -194,6 +195,16 @@ def sketch_linear_info(layer: int) -> dict:
     info.struct_size = ctypes.sizeof(skl_info_t)
     _check(load_library().sketch_linear_info(layer, ctypes.byref(info)))
     return {n: getattr(info, n) for n, _ in skl_info_t._fields_ if n != "struct_size"}
+
+
+def sketch_linear_plan(desc: skl_desc_t, segments: int = 0, groups: int = 0):
+    """Host only.  (info dict, decode cost in microseconds by the planner's model) for the library's plan, or
+    for the decode split (segments, groups) if given."""
+    info = skl_info_t()
+    info.struct_size = ctypes.sizeof(skl_info_t)
+    cost = ctypes.c_double(0.0)
+    _check(load_library().sketch_linear_plan(ctypes.byref(desc), segments, groups, ctypes.byref(info), ctypes.byref(cost)))
+    return {n: getattr(info, n) for n, _ in skl_info_t._fields_ if n != "struct_size"}, cost.value
 
 
 def sketch_linear_workspace_bytes(layer: int, op: int, n: int) -> int:

@@ -128,9 +128,25 @@ static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out, b
 // the busiest workgroup (segment wave-units x 16-byte words per state row of
 // its blocks); among equal splits the one with fewer segments stages fewer
 // table bytes.
+// Cost model of a decode split (microseconds, fitted to measurements on MI355X): a workgroup pays a start-up
+// latency and then 0.033 us per (64-output wave unit x 16-byte word per state row) of its share; fewer than
+// six active wavefronts cannot keep the LDS pipeline busy.  Workgroups are dealt round-robin to the 8 XCDs
+// of 32 CUs each and a group's segments all land on one XCD, so ceil(G/8)*S workgroups compete for 32 CUs.
+// total_nb: block costs of the layer in quarter words; nb0: words per state row of the first block.
+static double decode_cost(uint32_t units, uint32_t total_nb, uint32_t nb0, uint32_t S, uint32_t G)
+{
+    const double share = std::ceil((double)total_nb / 4.0 / G + 0.5 * nb0);   // in words; groups end on block boundaries
+    const uint32_t seg_units = (units + S - 1) / S;
+    const uint32_t per_xcd = ((G + 7) / 8) * S;
+    const uint32_t rounds = (per_xcd + 31) / 32;
+    return rounds * (1.8 + 0.033 * std::max(seg_units, 6u) * share) + 0.02 * G;
+}
+
+// P->want_s, P->want_g: 0, or a split to plan instead of the cheapest one (diagnostic; false if the kernels cannot run it)
 static bool plan_decode(const skl_desc_t *d, skl_plan *P)
 {
     skl_layer &L = P->L;
+    const uint32_t want_s = P->want_s, want_g = P->want_g;
     const uint32_t units = (d->out_features + 63) / 64;
     const uint32_t nblk = L.n_blocks;
     std::vector<uint32_t> cum(nblk + 1, 0);
@@ -158,28 +174,27 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
         start[G] = nblk;
         return most;
     };
-    // Cost model (microseconds, fitted to measurements on MI355X): a workgroup
-    // pays a start-up latency and then 0.033 us per (64-output wave unit x
-    // 16-byte word per state row) of its share; fewer than six active
-    // wavefronts cannot keep the LDS pipeline busy.  Workgroups are dealt
-    // round-robin to the 8 XCDs of 32 CUs each and a group's segments all land
-    // on one XCD, so ceil(G/8)*S workgroups compete for 32 CUs.
+    // Every split the kernels can run: S output segments of at most 16 wave units (one 64-output unit per
+    // wavefront of a 1024-thread workgroup), G block groups of at most SKL_MAX_GROUP_BLOCKS blocks; the
+    // cheapest under decode_cost() wins (the first one found among equals: fewer groups, then fewer segments).
     double best = 1e300;
     uint32_t best_s = 1, best_g = nblk;
     std::vector<uint32_t> scratch_start;
     for (uint32_t G = (nblk + SKL_MAX_GROUP_BLOCKS - 1) / SKL_MAX_GROUP_BLOCKS; G <= nblk; ++G) {
         if (cut_groups(G, scratch_start) > SKL_MAX_GROUP_BLOCKS) continue;   // block metadata of a group sits in LDS
-        const double share = std::ceil((double)total_nb / 4.0 / G + 0.5 * P->bmeta[0].nb);   // in words; groups end on block boundaries
-        // one 64-output unit per wavefront of a 1024-thread workgroup: 16 at most; fewer than 6 never pays
-        for (uint32_t want = 16; want >= 6; --want) {
-            const uint32_t S = (units + want - 1) / want;
-            const uint32_t seg_units = (units + S - 1) / S;
-            const uint32_t per_xcd = ((G + 7) / 8) * S;
-            const uint32_t rounds = (per_xcd + 31) / 32;
-            const double t = rounds * (1.8 + 0.033 * std::max(seg_units, 6u) * share) + 0.02 * G;
+        for (uint32_t S = (units + 15) / 16; S <= units; ++S) {
+            const double t = decode_cost(units, total_nb, P->bmeta[0].nb, S, G);
             if (t < best) { best = t; best_s = S; best_g = G; }
         }
     }
+    if (want_s && want_g) {                     // the model's figure for a split the caller names
+        if (want_g < 1 || want_g > nblk || want_s < (units + 15) / 16 || want_s > units ||
+            cut_groups(want_g, scratch_start) > SKL_MAX_GROUP_BLOCKS)
+            return false;
+        best = decode_cost(units, total_nb, P->bmeta[0].nb, want_s, want_g);
+        best_s = want_s; best_g = want_g;
+    }
+    L.decode_cost_us = best;
     L.n_sseg = best_s;
     L.n_bg = best_g;
     L.n_wunits = units;
@@ -554,9 +569,8 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
 
 void sketch_linear_destroy(skl_layer_t *layer) { delete layer; }
 
-skl_status_t sketch_linear_info(const skl_layer_t *L, skl_info_t *info)
+static skl_status_t fill_info(const skl_layer *L, skl_info_t *info)
 {
-    if (!L || !info) FAIL(SKL_ERR_INVALID_ARG, "layer or info is NULL");
     if (info->struct_size != sizeof(skl_info_t) && info->struct_size != SKL_INFO_SIZE_V1)
         FAIL(SKL_ERR_INVALID_ARG, "info.struct_size is %u, expected %zu (or %u, the first version)", info->struct_size,
              sizeof(skl_info_t), SKL_INFO_SIZE_V1);
@@ -574,6 +588,26 @@ skl_status_t sketch_linear_info(const skl_layer_t *L, skl_info_t *info)
     info->n_blocks = L->path == 1 ? L->n_blocks : 0;
     info->prefill_staged_from = L->path == 1 ? L->gemm_staged_from : 0xFFFFFFFFu;
     return SKL_OK;
+}
+
+skl_status_t sketch_linear_info(const skl_layer_t *L, skl_info_t *info)
+{
+    if (!L || !info) FAIL(SKL_ERR_INVALID_ARG, "layer or info is NULL");
+    return fill_info(L, info);
+}
+
+skl_status_t sketch_linear_plan(const skl_desc_t *desc, uint32_t segments, uint32_t groups, skl_info_t *info, double *decode_cost_us)
+{
+    if (!info) FAIL(SKL_ERR_INVALID_ARG, "info is NULL");
+    if ((segments == 0) != (groups == 0)) FAIL(SKL_ERR_INVALID_ARG, "segments and groups must both be 0 or both be given");
+    skl_plan P;
+    P.want_s = segments; P.want_g = groups;
+    skl_status_t st = skl_make_plan(desc, &P);
+    if (st != SKL_OK) return st;
+    if (segments && (P.L.path != 1 || P.L.n_sseg != segments || P.L.n_bg != groups))
+        FAIL(SKL_ERR_UNSUPPORTED, "the decode kernels cannot run %u output segments x %u block groups on this layer", segments, groups);
+    if (decode_cost_us) *decode_cost_us = P.L.path == 1 ? P.L.decode_cost_us : 0.0;
+    return fill_info(&P.L, info);
 }
 
 skl_status_t sketch_linear_workspace_bytes(const skl_layer_t *L, uint32_t op, uint32_t n, uint64_t *bytes)

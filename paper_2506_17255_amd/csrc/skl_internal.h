@@ -95,6 +95,7 @@ struct skl_layer {
     // wave units) and block group g (consecutive channel blocks bg_start[g] ..
     // bg_start[g+1]); n_sseg * n_bg workgroups of 1024 threads, one per CU
     uint32_t n_sseg = 0, n_bg = 0, n_wunits = 0;
+    double decode_cost_us = 0;      // the planner's model for this split
     uint32_t max_group_chan = 0;    // most channel-list entries in one block group
     uint32_t opl = 1;               // outputs per lane: ceil(segment length / 1024)
     uint32_t two_bufs = 1;          // double-buffered tables fit in LDS (batched decode, padded tables)
@@ -121,6 +122,7 @@ struct skl_layer {
 struct skl_plan {
     skl_layer L;
     skl_desc_t desc;                // the caller's description in the current layout of the struct
+    uint32_t want_s = 0, want_g = 0;   // diagnostic: plan this decode split (segments, groups) instead of the cheapest
     uint64_t dev_bytes = 0;
     std::vector<skl_group_meta> gmeta;
     std::vector<skl_block_meta> bmeta;

@@ -1,0 +1,66 @@
+"""Host-only checks of the decode planner (no GPU call): for the benchmark's layer shapes the split the library
+picks is the cheapest one under its own cost model among all splits the kernels can run, and the plans the
+measurements in the design notes were taken with are still the ones picked."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2506_17255_amd as skl
+import workloads as wk
+
+
+def description(wl):
+    widths = oracle.allocate_widths(wk.gen_importance(wl), wl.budget_states, wl.d).astype(np.uint32)
+    A, C = wk.gen_hash_params(wl)
+    n = int(widths.sum()) * wl.d
+    return skl.make_desc(wl.in_features, wl.out_features, wl.tile_in, wl.tile_out, wl.d, A, C, widths,
+                         np.zeros(n, dtype=np.uint16))
+
+
+SHAPES = {"cfg2_q_proj": wk.cfg2(), "cfg3_up": wk.cfg3("up"), "cfg3_down": wk.cfg3("down"), "cfg4_4096": wk.cfg4(4096, 0.5),
+          "cfg4_11008_0.75": wk.cfg4(11008, 0.75), "cfg5_70b": wk.cfg5_70b()}
+
+
+@pytest.mark.parametrize("name", sorted(SHAPES))
+def test_the_picked_decode_split_is_the_cheapest_the_kernels_can_run(name):
+    wl = SHAPES[name]
+    desc = description(wl)
+    info, cost = skl.sketch_linear_plan(desc)
+    assert info["path"] == 1 and cost > 0
+    units = (wl.out_features + 63) // 64
+    S0, G0 = info["decode_segments"], info["decode_groups"]
+    assert (units + S0 - 1) // S0 <= 16                       # one 64-output unit per wavefront, 16 wavefronts at most
+    again, cost_again = skl.sketch_linear_plan(desc, S0, G0)
+    assert again == info and cost_again == cost
+    best, feasible = cost, 0
+    groups = sorted(set(list(range(1, 65)) + [G0, 96, 128, 256, info["n_blocks"]]))
+    for G in (g for g in groups if g <= info["n_blocks"]):
+        for S in range((units + 15) // 16, min(units, 64) + 1):
+            try:
+                other, c = skl.sketch_linear_plan(desc, S, G)
+            except skl.SketchLinearError as e:
+                assert e.status == skl.SKL_ERR_UNSUPPORTED
+                continue
+            feasible += 1
+            assert other["decode_segments"] == S and other["decode_groups"] == G
+            best = min(best, c)
+    assert feasible > 50
+    assert cost <= best * (1 + 1e-12), (S0, G0, cost, best)
+
+
+def test_splits_the_kernels_cannot_run_are_refused():
+    desc = description(wk.cfg3("up"))
+    for S, G in ((1, 16), (10, 16), (16, 1), (16, 71), (16, 10000)):   # > 16 units per segment; > 64 blocks per group; > blocks
+        with pytest.raises(skl.SketchLinearError) as err:
+            skl.sketch_linear_plan(desc, S, G)
+        assert err.value.status == skl.SKL_ERR_UNSUPPORTED
+    with pytest.raises(skl.SketchLinearError) as err:
+        skl.sketch_linear_plan(desc, 16, 0)
+    assert err.value.status == skl.SKL_ERR_INVALID_ARG
+
+
+def test_benchmark_layers_keep_their_measured_plans():
+    """The splits the design notes' timings were taken with."""
+    for name, want in (("cfg3_up", (16, 16)), ("cfg3_down", (8, 32)), ("cfg2_q_proj", (8, 32))):
+        info, _ = skl.sketch_linear_plan(description(SHAPES[name]))
+        assert (info["decode_segments"], info["decode_groups"]) == want, name

@@ -546,7 +546,8 @@ def main():
         b.copy_(a)
         torch.cuda.synchronize()
 
-    ceilings = None if args.quick else measured_ceilings(torch, skl, dev, stream)
+    full_run = not (args.quick or args.prefill_only or args.low_bit_only or args.stack_only)
+    ceilings = measured_ceilings(torch, skl, dev, stream) if full_run else None
 
     if args.low_bit_only:
         import oracle as _oracle

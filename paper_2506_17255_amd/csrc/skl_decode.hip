@@ -19,8 +19,9 @@ struct StreamArgs {
     uint32_t n_wunits;      // 64-output wave units of the layer
     uint32_t n_sseg;        // output segments
     uint32_t n_bg;          // block groups
-    uint32_t buf_words;     // 16-byte words per table buffer
-    uint32_t two_bufs;
+    uint32_t tab_bytes;     // LDS bytes of the table area: two buffers SKL_PBUF_DIST apart, or the largest table
+    uint32_t upw;           // 64-output units per wavefront (a segment holds at most upw x 16)
+    uint32_t buf_flag;      // which bit of a group's flags says that its tables are double-buffered (1: unpadded, 2: padded)
 };
 
 
@@ -28,6 +29,7 @@ struct StreamCtx {
     uint32_t s, g, b_lo, b_hi, c_lo, c_hi, o_lo, o_hi;
     uint32_t K0, rs0, toff0, chan_off0, ptoff0;
     bool live;
+    bool two_bufs;          // every table of the group fits one of the two buffers: the next table streams in during a block
 };
 
 // Workgroup id -> (segment, group).  Consecutive workgroup ids go to
@@ -46,6 +48,7 @@ __device__ __forceinline__ StreamCtx stream_ctx(const StreamArgs &p)
     c.b_lo = gi.b_lo; c.b_hi = gi.b_hi; c.c_lo = gi.c_lo; c.c_hi = gi.c_hi;
     c.K0 = gi.K0; c.rs0 = gi.rs0; c.toff0 = gi.table_off16_0; c.chan_off0 = gi.chan_off0;
     c.ptoff0 = gi.ptable_off16_0;
+    c.two_bufs = (gi.flags & p.buf_flag) != 0;
     c.o_lo = (uint32_t)(((uint64_t)s * p.n_wunits) / p.n_sseg) * 64;
     c.o_hi = min((uint32_t)(((uint64_t)(s + 1) * p.n_wunits) / p.n_sseg) * 64, p.r.out);
     return c;
@@ -63,11 +66,16 @@ __device__ __forceinline__ StreamCtx stream_ctx(const StreamArgs &p)
 // they are folded across the nb lanes of an output and parked in LDS when the
 // class changes and at the end.
 //
-// LDS: [table buffer 0][table buffer 1 at SKL_PBUF_DIST][1024 sums][block
+// A wavefront owns U units of 64 outputs, unit u of wavefront w being unit w + u * (wavefronts) of the
+// segment: with U = 2 a segment is twice as long, half as many workgroups stage each table and a block step
+// carries twice the arithmetic between its barriers -- what layers with wide sketches (large tables behind
+// few channels) need.
+//
+// LDS: [table buffer 0][table buffer 1 at SKL_PBUF_DIST][1024 x U sums][block
 // metadata][state-row addresses, 1024 x d][activations].  The kernel has no static LDS, so the dynamic region
 // starts at LDS address 0 and the second buffer is reached through the 16-bit
 // offset field of the read instruction: no address arithmetic per gather.
-#define SKL_G1_FIXED_LDS(d) (SKL_SWG * 4 + SKL_MAX_GROUP_BLOCKS * 32 + SKL_SWG * 4 * (d))
+#define SKL_G1_FIXED_LDS(d, u) (SKL_SWG * 4 * (u) + SKL_MAX_GROUP_BLOCKS * 32 + SKL_SWG * 4 * (d))
 
 // 16 bytes at an absolute LDS address
 
@@ -157,37 +165,45 @@ struct G1Walk {
     uint32_t *row_addr_w;    // the wavefront's scratch for state-row addresses, [64][D]
     uint32_t nblk, bi;       // blocks of the group, current block
     uint32_t K, rs, chan_off;   // current block
-    uint32_t lane, o_base;
+    uint32_t lane, o_base;   // o_base: first output of the wavefront's unit 0; unit u starts unit_stride outputs further on
+    uint32_t unit_stride, o_hi;
     bool wave_live;
     bool first_wait;         // the first table, the activations and the metadata are still on their way
 };
 
 // A run of consecutive blocks of one width class (NB words per state row).
 // The partial sums and the table offsets of the run live in registers.
-template <int D, int NB, int MAXW>
+template <int D, int NB, int MAXW, int U>
 __device__ __forceinline__ void g1_run(const StreamArgs &p, const StreamCtx &c, G1Walk &w)
 {
     const uint32_t nw = blockDim.x >> 6;
     constexpr uint32_t OPI = 64 / NB;
     uint4 *const buf0 = smem, *const buf1 = smem + SKL_PBUF_DIST / 16;
-    float acc[NB];
-    uint32_t off[NB][D];
+    float acc[U][NB];
+    uint32_t off[U][NB][D];
+    bool live[U];            // wavefront-uniform: unit u of this wavefront lies inside the segment
 #pragma unroll
-    for (int i = 0; i < NB; ++i) acc[i] = 0.f;
+    for (int u = 0; u < U; ++u) {
+        live[u] = w.o_base + u * w.unit_stride < w.o_hi;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) acc[u][i] = 0.f;
+    }
     uint32_t K_prev = 0;
     const uint32_t rs_run = w.rs;
-    // one block out of the buffer at byte offset BO (a compile-time constant, so
-    // that it ends up in the offset field of the LDS reads); meanwhile the
-    // next block's table streams into the other buffer
-    auto step = [&](auto bo_tag) {
+    // One block out of the buffer at byte offset BO (a compile-time constant, so that it ends up in the
+    // offset field of the LDS reads); with two buffers the next block's table streams into the other one
+    // meanwhile, with one it is copied after the block.
+    auto step = [&](auto bo_tag, auto bufs_tag) {
         constexpr uint32_t BO = decltype(bo_tag)::value;
-        uint4 *nxt = BO || !p.two_bufs ? buf0 : buf1;
+        constexpr int BUFS = decltype(bufs_tag)::value;
         const bool more = w.bi + 1 < w.nblk;
         const uint32_t bn = min(w.bi + 1, w.nblk - 1);
         // the state-row addresses need no table: at the start of the workgroup they are computed while
         // the first table is still arriving
         if (w.wave_live && w.K != K_prev) {
-            lane_offsets<D, NB>(p.r.h, w.o_base, p.r.out, w.K, w.lane, w.row_addr_w, off);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (live[u]) lane_offsets<D, NB>(p.r.h, w.o_base + u * w.unit_stride, p.r.out, w.K, w.lane, w.row_addr_w, off[u]);
             K_prev = w.K;
         }
         if (w.first_wait) {
@@ -197,61 +213,70 @@ __device__ __forceinline__ void g1_run(const StreamArgs &p, const StreamCtx &c, 
         }
         const uint4 m0 = w.sm_meta[2 * bn];          // {table_off16, K, rs, nb}
         const uint4 m1 = w.sm_meta[2 * bn + 1];      // {chan_off, ptable_off16, ..}
-        if (more && p.two_bufs) copy_chunks_to_lds_async(nxt, p.r.tables + m1.y, D * m0.y * m0.w, nw);
+        if (BUFS == 2 && more) copy_chunks_to_lds_async(BO ? buf0 : buf1, p.r.tables + m1.y, D * m0.y * m0.w, nw);
         if (w.wave_live) {
             const uint4 xv = reinterpret_cast<const uint4 *>(w.xs + (w.chan_off - c.c_lo))[w.lane % NB];
-            lane_block_dot<D, NB, BO, MAXW>(off, xv, acc);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (live[u]) lane_block_dot<D, NB, BO, MAXW>(off[u], xv, acc[u]);
         }
-        if (more && !p.two_bufs) {
+        if (BUFS == 1 && more) {
             __syncthreads();                 // everyone is done with the only buffer
-            copy_chunks_to_lds_async(nxt, p.r.tables + m1.y, D * m0.y * m0.w, nw);
+            copy_chunks_to_lds_async(buf0, p.r.tables + m1.y, D * m0.y * m0.w, nw);
         }
         wait_async_copies();
         __syncthreads();
         w.K = m0.y; w.rs = m0.z; w.chan_off = m1.x;
         ++w.bi;
     };
-    const std::integral_constant<uint32_t, 0> first_buf;
-    const std::integral_constant<uint32_t, SKL_PBUF_DIST> second_buf;
+    const std::integral_constant<uint32_t, 0> at_0;
+    const std::integral_constant<uint32_t, SKL_PBUF_DIST> at_dist;
+    const std::integral_constant<int, 1> one_buf;
+    const std::integral_constant<int, 2> two_bufs;
     auto in_run = [&]() { return w.bi < w.nblk && w.rs == rs_run; };
-    if (p.two_bufs) {
+    if (c.two_bufs) {
         // even blocks sit in the first buffer, odd blocks in the second
-        if (w.bi & 1) step(second_buf);
+        if (w.bi & 1) step(at_dist, two_bufs);
         while (in_run()) {
-            step(first_buf);
+            step(at_0, two_bufs);
             if (!in_run()) break;
-            step(second_buf);
+            step(at_dist, two_bufs);
         }
     } else {
-        while (in_run()) step(first_buf);
+        while (in_run()) step(at_0, one_buf);
     }
     // fold the NB lanes of every output, add the totals to the wavefront's sums
-    if (w.wave_live) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (!live[u]) continue;
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             // LDS add without a returned value: nothing to wait for between the NB updates
-            const float v = sum_over_words<NB>(acc[i]);
+            const float v = sum_over_words<NB>(acc[u][i]);
             if (w.lane % NB == 0)
-                __hip_atomic_fetch_add(&w.yw[w.lane / NB + OPI * i], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&w.yw[u * w.unit_stride + w.lane / NB + OPI * i], v, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
 }
 
-template <int D, int MAXW>
+template <int D, int MAXW, int U>
 __device__ __forceinline__ void gemv1_body(const StreamArgs &p, const uint16_t *__restrict__ x, float *__restrict__ partial)
 {
     const StreamCtx c = stream_ctx(p);
     if (!c.live) return;
     char *lds = reinterpret_cast<char *>(smem);
-    const uint32_t tab_bytes = p.two_bufs ? 2 * SKL_PBUF_DIST : p.buf_words * 16;
+    const uint32_t tab_bytes = p.tab_bytes;
     float *ysum = reinterpret_cast<float *>(lds + tab_bytes);
-    uint4 *sm_meta = reinterpret_cast<uint4 *>(lds + tab_bytes + SKL_SWG * 4);
-    uint32_t *row_addr = reinterpret_cast<uint32_t *>(lds + tab_bytes + SKL_SWG * 4 + SKL_MAX_GROUP_BLOCKS * 32);
-    uint16_t *xs = reinterpret_cast<uint16_t *>(lds + tab_bytes + SKL_G1_FIXED_LDS(D));
+    uint4 *sm_meta = reinterpret_cast<uint4 *>(lds + tab_bytes + SKL_SWG * 4 * U);
+    uint32_t *row_addr = reinterpret_cast<uint32_t *>(lds + tab_bytes + SKL_SWG * 4 * U + SKL_MAX_GROUP_BLOCKS * 32);
+    uint16_t *xs = reinterpret_cast<uint16_t *>(lds + tab_bytes + SKL_G1_FIXED_LDS(D, U));
     G1Walk w;
     w.lane = threadIdx.x & 63;
     const uint32_t wave = threadIdx.x >> 6;
     w.o_base = c.o_lo + wave * 64;
+    w.unit_stride = blockDim.x;          // 64 outputs x wavefronts
+    w.o_hi = c.o_hi;
     w.wave_live = w.o_base < c.o_hi;
     w.yw = ysum + wave * 64;
     w.row_addr_w = row_addr + wave * 64 * D;
@@ -263,7 +288,8 @@ __device__ __forceinline__ void gemv1_body(const StreamArgs &p, const uint16_t *
     copy_chunks_to_lds_async(smem, p.r.tables + c.ptoff0, D * w.K * (w.rs == 1 ? 1u : w.rs - 1), blockDim.x >> 6);
     // the plan keeps a group at SKL_MAX_GROUP_BLOCKS blocks or fewer
     for (uint32_t i = threadIdx.x; i < 2 * w.nblk; i += blockDim.x) sm_meta[i] = reinterpret_cast<const uint4 *>(p.r.bmeta + c.b_lo)[i];
-    w.yw[w.lane] = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) w.yw[u * w.unit_stride + w.lane] = 0.f;
     for (uint32_t i = threadIdx.x; i < c.c_hi - c.c_lo; i += blockDim.x) {
         const uint32_t ch = p.r.chan[c.c_lo + i];
         xs[i] = ch != SKL_NO_CHANNEL ? (uint16_t)(x[ch] ^ 0x8000u) : (uint16_t)0;
@@ -272,13 +298,17 @@ __device__ __forceinline__ void gemv1_body(const StreamArgs &p, const uint16_t *
     while (w.bi < w.nblk) {
         switch (w.rs) {
         case 9:
-            if constexpr (D <= 6) {      // the plan uses 8-word blocks for d <= 6 only
-                g1_run<D, 8, MAXW>(p, c, w);
+            if constexpr (D <= 6 && U == 1) {      // the plan uses 8-word blocks for d <= 6 only,
+                g1_run<D, 8, MAXW, U>(p, c, w);    // and two units per wavefront only for layers of one- and two-word blocks
+                break;                              // (the row addresses of two units x 4 or 8 words do not fit the registers)
+            }
+        case 5:
+            if constexpr (U == 1) {
+                g1_run<D, 4, MAXW, U>(p, c, w);
                 break;
             }
-        case 5: g1_run<D, 4, MAXW>(p, c, w); break;
-        case 3: g1_run<D, 2, MAXW>(p, c, w); break;
-        default: g1_run<D, 1, MAXW>(p, c, w); break;
+        case 3: g1_run<D, 2, MAXW, U>(p, c, w); break;
+        default: g1_run<D, 1, MAXW, U>(p, c, w); break;
         }
     }
     if (w.first_wait) {                  // a group without blocks: nothing may stay in flight
@@ -287,16 +317,19 @@ __device__ __forceinline__ void gemv1_body(const StreamArgs &p, const uint16_t *
     }
     if (w.wave_live) {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        const uint32_t o = w.o_base + w.lane;
-        if (o < c.o_hi) partial[(size_t)c.g * p.r.out + o] = w.yw[w.lane];     // ordinary store: measured 0.25 us faster per call than a non-temporal one
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t o = w.o_base + u * w.unit_stride + w.lane;
+            if (o < c.o_hi) partial[(size_t)c.g * p.r.out + o] = w.yw[u * w.unit_stride + w.lane];     // ordinary store: measured 0.25 us faster per call than a non-temporal one
+        }
     }
 }
 
-template <int D, int MAXW>
+template <int D, int MAXW, int U>
 __global__ __launch_bounds__(MAXW * 64) void k_row_gemv1(StreamArgs p, const uint16_t *__restrict__ x,
                                                           float *__restrict__ partial)
 {
-    gemv1_body<D, MAXW>(p, x, partial);
+    gemv1_body<D, MAXW, U>(p, x, partial);
 }
 
 // Several layers that read the same activations in one launch (q/k/v, gate/up): grid row y runs layer y.
@@ -309,11 +342,11 @@ struct GroupArgs {
     uint32_t xs_stride[SKL_MAX_GROUP_LAYERS];   // batched kernel: halfs per staged activation row
 };
 
-template <int D, int MAXW>
+template <int D, int MAXW, int U>
 __global__ __launch_bounds__(MAXW * 64) void k_row_gemv1_group(GroupArgs m, const uint16_t *__restrict__ x,
                                                                 float *__restrict__ partial)
 {
-    gemv1_body<D, MAXW>(m.a[blockIdx.y], x, partial + blockIdx.y * m.partial_stride);
+    gemv1_body<D, MAXW, U>(m.a[blockIdx.y], x, partial + blockIdx.y * m.partial_stride);
 }
 
 // ---- decode GEMV, batch 2..16: the reconstructed weights feed the matrix
@@ -408,12 +441,12 @@ __device__ __forceinline__ void gn_run(const StreamArgs &p, const StreamCtx &c, 
     };
     auto step = [&](auto bo_tag) {
         constexpr uint32_t BO = decltype(bo_tag)::value;
-        uint4 *nxt = BO || !p.two_bufs ? buf0 : buf1;
+        uint4 *nxt = BO || !c.two_bufs ? buf0 : buf1;
         const bool more = w.bi + 1 < w.nblk;
         const uint32_t bn = min(w.bi + 1, w.nblk - 1);
         const uint4 m0 = w.sm_meta[2 * bn];          // {table_off16, K, rs, nb}
         const uint4 m1 = w.sm_meta[2 * bn + 1];      // {chan_off, ..}
-        if (more && p.two_bufs) copy_next(nxt, p.r.tables + m0.x, D * m0.y * m0.z);
+        if (more && c.two_bufs) copy_next(nxt, p.r.tables + m0.x, D * m0.y * m0.z);
         if (w.wave_live) {
             if (w.K != K_prev) {
                 gn_offsets<D, NB>(p.r.h, w.o_base, p.r.out, w.K, w.lane, off);
@@ -421,7 +454,7 @@ __device__ __forceinline__ void gn_run(const StreamArgs &p, const StreamCtx &c, 
             }
             gn_block<D, NB, BO>(off, w.xs_addr + (w.chan_off - c.c_lo) * 2 + (x_live ? (w.lane >> 4) * 16 : 0), x_live, acc);
         }
-        if (more && !p.two_bufs) {
+        if (more && !c.two_bufs) {
             __syncthreads();                 // everyone is done with the only buffer
             copy_next(nxt, p.r.tables + m0.x, D * m0.y * m0.z);
         }
@@ -433,7 +466,7 @@ __device__ __forceinline__ void gn_run(const StreamArgs &p, const StreamCtx &c, 
     const std::integral_constant<uint32_t, 0> first_buf;
     const std::integral_constant<uint32_t, SKL_PBUF_DIST> second_buf;
     auto in_run = [&]() { return w.bi < w.nblk && w.rs == rs_run; };
-    if (p.two_bufs) {
+    if (c.two_bufs) {
         if (w.bi & 1) step(second_buf);
         while (in_run()) {
             step(first_buf);
@@ -454,24 +487,21 @@ __device__ __forceinline__ void gemvN_body(const StreamArgs &p, const uint16_t *
     const StreamCtx c = stream_ctx(p);
     if (!c.live) return;
     char *lds = reinterpret_cast<char *>(smem);
-    const uint32_t tab_bytes = p.two_bufs ? 2 * SKL_PBUF_DIST : p.buf_words * 16;
+    const uint32_t tab_bytes = p.tab_bytes;
     uint4 *sm_meta = reinterpret_cast<uint4 *>(lds + tab_bytes);
     uint16_t *xs = reinterpret_cast<uint16_t *>(lds + tab_bytes + SKL_GN_FIXED_LDS);   // 16 rows of xs_stride halfs
     GnWalk w;
     w.lane = threadIdx.x & 63;
-    const uint32_t wave = threadIdx.x >> 6;
-    w.o_base = c.o_lo + wave * 64;
-    w.wave_live = w.o_base < c.o_hi;
+    const uint32_t wave = threadIdx.x >> 6, nwv = blockDim.x >> 6;
     w.nblk = min(c.b_hi - c.b_lo, (uint32_t)SKL_MAX_GROUP_BLOCKS);
-    w.bi = 0;
     w.sm_meta = sm_meta;
-    w.K = c.K0; w.rs = c.rs0; w.chan_off = c.chan_off0;
     w.xs_addr = (uint32_t)(uintptr_t)(lds_void *)xs + (w.lane & 15) * xs_stride * 2;
-    {
-        const uint32_t nwv = blockDim.x >> 6, n16 = D * w.K * w.rs;
+    auto first_table = [&]() {
+        const uint32_t n16 = D * c.K0 * c.rs0;
         for (uint32_t base = wave * 64; base < n16; base += 64 * nwv)
             if (base + w.lane < n16) lds_dma_16(p.r.tables + c.toff0 + base + w.lane, smem + base);
-    }
+    };
+    first_table();
     for (uint32_t i = threadIdx.x; i < 2 * w.nblk; i += blockDim.x) sm_meta[i] = reinterpret_cast<const uint4 *>(p.r.bmeta + c.b_lo)[i];
     // activations of the group's channels, 16 rows (rows >= batch are zero): one
     // thread per (channel, half of the rows), so that the channel number is
@@ -489,30 +519,40 @@ __device__ __forceinline__ void gemvN_body(const StreamArgs &p, const uint16_t *
 #pragma unroll
         for (int k = 0; k < 8; ++k) xs[(b0 + k) * xs_stride + cc] = v[k];
     }
-    wait_async_copies();
-    __syncthreads();
-    float4v acc[4];
+    // A segment of more than 16 units (plans made for the batch-1 kernel's two units per wavefront) is
+    // walked in passes: the wavefronts take units 0 .. nwv - 1, then nwv .. 2 nwv - 1, streaming the group's
+    // tables again for each pass.
+    for (uint32_t pass = 0; pass < p.upw; ++pass) {
+        w.o_base = c.o_lo + (pass * nwv + wave) * 64;
+        w.wave_live = w.o_base < c.o_hi;
+        w.bi = 0;
+        w.K = c.K0; w.rs = c.rs0; w.chan_off = c.chan_off0;
+        if (pass) first_table();             // the last step of the previous pass ended with a barrier: the first buffer is free
+        wait_async_copies();
+        __syncthreads();
+        float4v acc[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] = (float4v){0.f, 0.f, 0.f, 0.f};
-    while (w.bi < w.nblk) {
-        switch (w.rs) {
-        case 9: gn_run<D, 8>(p, c, w, acc); break;
-        case 5: gn_run<D, 4>(p, c, w, acc); break;
-        case 3: gn_run<D, 2>(p, c, w, acc); break;
-        default: gn_run<D, 1>(p, c, w, acc); break;
+        for (int j = 0; j < 4; ++j) acc[j] = (float4v){0.f, 0.f, 0.f, 0.f};
+        while (w.bi < w.nblk) {
+            switch (w.rs) {
+            case 9: gn_run<D, 8>(p, c, w, acc); break;
+            case 5: gn_run<D, 4>(p, c, w, acc); break;
+            case 3: gn_run<D, 2>(p, c, w, acc); break;
+            default: gn_run<D, 1>(p, c, w, acc); break;
+            }
         }
-    }
-    if (w.wave_live) {
-        // acc[j][i]: batch row 4 * (lane / 16) + i, output o_base + 16 * j + lane % 16
-        float *pblk = partial + (size_t)c.g * batch * p.r.out;
+        if (w.wave_live) {
+            // acc[j][i]: batch row 4 * (lane / 16) + i, output o_base + 16 * j + lane % 16
+            float *pblk = partial + (size_t)c.g * batch * p.r.out;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t o = w.o_base + 16 * j + (w.lane & 15);
-            if (o < c.o_hi) {
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t o = w.o_base + 16 * j + (w.lane & 15);
+                if (o < c.o_hi) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t m = 4 * (w.lane >> 4) + i;
-                    if (m < batch) __builtin_nontemporal_store(acc[j][i], &pblk[(size_t)m * p.r.out + o]);
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t m = 4 * (w.lane >> 4) + i;
+                        if (m < batch) __builtin_nontemporal_store(acc[j][i], &pblk[(size_t)m * p.r.out + o]);
+                    }
                 }
             }
         }
@@ -667,6 +707,35 @@ uint64_t skl_gemv_workspace_bytes(const skl_layer *L, uint32_t batch)
 
 uint64_t skl_reconstruct_workspace_bytes(const skl_layer *L) { return skl_dequant_bytes(L); }
 
+// LDS bytes of the batch-1 kernel for a layer
+static size_t gemv1_lds_bytes(const skl_layer *L)
+{
+    return (size_t)L->ptab_bytes + SKL_G1_FIXED_LDS(L->d, L->decode_upw) + (size_t)(L->max_group_chan + 64) * sizeof(uint16_t);
+}
+
+// the batch-1 kernel by sketch rows, register budget (workgroups of up to 12 wavefronts may use 168 registers
+// per lane, larger ones 128) and units per wavefront
+template <int MAXW, int U>
+static skl_status_t launch_gemv1_as(uint32_t d, uint32_t waves, dim3 grid, size_t lds, hipStream_t stream, const StreamArgs &a,
+                                    const uint16_t *x, float *partial)
+{
+    skl_status_t st = SKL_OK;
+    DISPATCH_D(d, {
+        st = allow_lds(k_row_gemv1<D, MAXW, U>, lds);
+        if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemv1<D, MAXW, U>), grid, dim3(64 * waves), lds, stream, a, x, partial);
+    })
+    return st;
+}
+
+static skl_status_t launch_gemv1(uint32_t d, uint32_t waves, uint32_t upw, dim3 grid, size_t lds, hipStream_t stream,
+                                 const StreamArgs &a, const uint16_t *x, float *partial)
+{
+    if (upw == 1) return waves <= 12 ? launch_gemv1_as<12, 1>(d, waves, grid, lds, stream, a, x, partial)
+                                     : launch_gemv1_as<16, 1>(d, waves, grid, lds, stream, a, x, partial);
+    return waves <= 12 ? launch_gemv1_as<12, 2>(d, waves, grid, lds, stream, a, x, partial)
+                       : launch_gemv1_as<16, 2>(d, waves, grid, lds, stream, a, x, partial);
+}
+
 skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, void *y, skl_dtype_t y_dt,
                              uint32_t ldy, uint32_t batch, void *ws, void *stream_, bool with_reduction)
 {
@@ -681,42 +750,29 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
         StreamArgs a;
         a.r = make_row_args(L, src);
         a.ginfo = reinterpret_cast<const skl_group_info *>(L->dev + L->off_ginfo);
-        a.n_wunits = L->n_wunits; a.n_sseg = L->n_sseg; a.n_bg = L->n_bg; a.buf_words = L->max_table_bytes / 16;
-        a.two_bufs = L->two_bufs;
+        a.n_wunits = L->n_wunits; a.n_sseg = L->n_sseg; a.n_bg = L->n_bg;
+        a.upw = L->decode_upw;
         const dim3 grid(8 * ((L->n_bg + 7) / 8) * L->n_sseg);
+        // one wavefront per upw 64-output units of the longest segment (at least two for the start-up loads)
+        const uint32_t seg_units = (L->n_wunits + L->n_sseg - 1) / L->n_sseg;
+        const uint32_t waves = std::max(2u, (seg_units + L->decode_upw - 1) / L->decode_upw);
         if (batch == 1) {
             // unpadded tables; buffers at fixed LDS addresses
             a.r.tables = src.ptables;
-            a.buf_words = L->max_ptable_bytes / 16;
-            a.two_bufs = L->two_pbufs;
-            // one wavefront per 64-output unit of the longest segment (at least two for the start-up loads)
-            const uint32_t g1_waves = std::max(2u, (L->n_wunits + L->n_sseg - 1) / L->n_sseg);
-            const size_t lds = (L->two_pbufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_ptable_bytes) + SKL_G1_FIXED_LDS(L->d) +
-                               (size_t)(L->max_group_chan + 64) * sizeof(uint16_t);
-            if (g1_waves <= 12) {
-                DISPATCH_D(L->d, {
-                    st = allow_lds(k_row_gemv1<D, 12>, lds);
-                    if (st == SKL_OK)
-                        hipLaunchKernelGGL((k_row_gemv1<D, 12>), grid, dim3(64 * g1_waves), lds, stream, a, x, partial);
-                })
-            } else {
-                DISPATCH_D(L->d, {
-                    st = allow_lds(k_row_gemv1<D, 16>, lds);
-                    if (st == SKL_OK)
-                        hipLaunchKernelGGL((k_row_gemv1<D, 16>), grid, dim3(64 * g1_waves), lds, stream, a, x, partial);
-                })
-            }
+            a.tab_bytes = L->ptab_bytes;
+            a.buf_flag = 1;
+            const size_t lds = gemv1_lds_bytes(L);
+            st = launch_gemv1(L->d, waves, L->decode_upw, grid, lds, stream, a, x, partial);
         } else {
             // padded tables; 16 activation rows of xs_stride halfs, xs_stride / 8 odd (bank spread of the MFMA A reads)
             const uint32_t xs_stride = (L->max_group_chan / 8 | 1u) * 8;
-            a.two_bufs = L->two_bufs;
-            const uint32_t gn_waves = std::max(2u, (L->n_wunits + L->n_sseg - 1) / L->n_sseg);
-            const size_t lds = (L->two_bufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_table_bytes) + SKL_GN_FIXED_LDS +
-                               (size_t)16 * xs_stride * sizeof(uint16_t);
+            a.tab_bytes = L->tab_bytes;
+            a.buf_flag = 2;
+            const size_t lds = (size_t)L->tab_bytes + SKL_GN_FIXED_LDS + (size_t)16 * xs_stride * sizeof(uint16_t);
             DISPATCH_D(L->d, {
                 st = allow_lds(k_row_gemvN<D>, lds);
                 if (st == SKL_OK)
-                    hipLaunchKernelGGL((k_row_gemvN<D>), grid, dim3(64 * gn_waves), lds, stream, a, x, ldx, batch, xs_stride, partial);
+                    hipLaunchKernelGGL((k_row_gemvN<D>), grid, dim3(64 * waves), lds, stream, a, x, ldx, batch, xs_stride, partial);
             })
         }
     } else {
@@ -733,7 +789,7 @@ skl_status_t skl_launch_gemv(const skl_layer *L, const void *x_, uint32_t ldx, v
 // ---- batch-1 decode of up to four layers that share their activations --------
 static bool group_layer_ok(const skl_layer *L, const skl_layer *first)
 {
-    return L->path == 1 && L->in == first->in && L->out == first->out && L->d == first->d;
+    return L->path == 1 && L->in == first->in && L->out == first->out && L->d == first->d && L->decode_upw == first->decode_upw;
 }
 
 static uint64_t group_partial_stride(const skl_layer *const *layers, uint32_t n, uint32_t batch)
@@ -750,6 +806,27 @@ uint64_t skl_gemv_group_workspace_bytes(const skl_layer *const *layers, uint32_t
     return group_partial_stride(layers, n, batch) * n + expanded;
 }
 
+template <int MAXW, int U>
+static skl_status_t launch_gemv1_group_as(uint32_t d, uint32_t waves, dim3 grid, size_t lds, hipStream_t stream, const GroupArgs &m,
+                                          const uint16_t *x, float *partial)
+{
+    skl_status_t st = SKL_OK;
+    DISPATCH_D(d, {
+        st = allow_lds(k_row_gemv1_group<D, MAXW, U>, lds);
+        if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemv1_group<D, MAXW, U>), grid, dim3(64 * waves), lds, stream, m, x, partial);
+    })
+    return st;
+}
+
+static skl_status_t launch_gemv1_group(uint32_t d, uint32_t waves, uint32_t upw, dim3 grid, size_t lds, hipStream_t stream,
+                                       const GroupArgs &m, const uint16_t *x, float *partial)
+{
+    if (upw == 1) return waves <= 12 ? launch_gemv1_group_as<12, 1>(d, waves, grid, lds, stream, m, x, partial)
+                                     : launch_gemv1_group_as<16, 1>(d, waves, grid, lds, stream, m, x, partial);
+    return waves <= 12 ? launch_gemv1_group_as<12, 2>(d, waves, grid, lds, stream, m, x, partial)
+                       : launch_gemv1_group_as<16, 2>(d, waves, grid, lds, stream, m, x, partial);
+}
+
 skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, const void *x_, uint32_t ldx, void *const *ys,
                                    skl_dtype_t y_dt, uint32_t ldy, uint32_t batch, void *ws, void *stream_, bool gate_up)
 {
@@ -757,7 +834,7 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
     const skl_layer *F = layers[0];
     for (uint32_t i = 0; i < n; ++i)
         if (!group_layer_ok(layers[i], F)) {
-            skl_set_error("layer %u of the group is not a row-sketch layer of the first layer's shape", i);
+            skl_set_error("layer %u of the group is not a row-sketch layer of the first layer's shape and decode plan (units per wavefront)", i);
             return SKL_ERR_UNSUPPORTED;
         }
     const bool one = batch == 1;                               // the batch-1 kernel reads the unpadded tables
@@ -781,26 +858,26 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
         a.r = make_row_args(L, src);
         a.ginfo = reinterpret_cast<const skl_group_info *>(L->dev + L->off_ginfo);
         a.n_wunits = L->n_wunits; a.n_sseg = L->n_sseg; a.n_bg = L->n_bg;
+        a.upw = L->decode_upw;
         const uint32_t xs_stride = (L->max_group_chan / 8 | 1u) * 8;
         m.xs_stride[i] = xs_stride;
         size_t need;
         if (one) {
             a.r.tables = src.ptables;
-            a.buf_words = L->max_ptable_bytes / 16;
-            a.two_bufs = L->two_pbufs;
-            need = (L->two_pbufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_ptable_bytes) + SKL_G1_FIXED_LDS(L->d) +
-                   (size_t)(L->max_group_chan + 64) * sizeof(uint16_t);
+            a.tab_bytes = L->ptab_bytes;
+            a.buf_flag = 1;
+            need = gemv1_lds_bytes(L);
         } else {
-            a.buf_words = L->max_table_bytes / 16;
-            a.two_bufs = L->two_bufs;
-            need = (L->two_bufs ? 2 * (size_t)SKL_PBUF_DIST : (size_t)L->max_table_bytes) + SKL_GN_FIXED_LDS +
-                   (size_t)16 * xs_stride * sizeof(uint16_t);
+            a.tab_bytes = L->tab_bytes;
+            a.buf_flag = 2;
+            need = (size_t)L->tab_bytes + SKL_GN_FIXED_LDS + (size_t)16 * xs_stride * sizeof(uint16_t);
         }
         gr.y[i] = ys[i < n ? i : 0];
         gr.n_units[i] = L->n_units;
         if (i >= n) continue;
         grid_x = std::max(grid_x, 8 * ((L->n_bg + 7) / 8) * L->n_sseg);
-        waves = std::max(waves, (L->n_wunits + L->n_sseg - 1) / L->n_sseg);
+        const uint32_t seg_units = (L->n_wunits + L->n_sseg - 1) / L->n_sseg;
+        waves = std::max(waves, (seg_units + L->decode_upw - 1) / L->decode_upw);
         lds = std::max(lds, need);
     }
     const uint16_t *x = static_cast<const uint16_t *>(x_);
@@ -813,16 +890,8 @@ skl_status_t skl_launch_gemv_group(const skl_layer *const *layers, uint32_t n, c
             if (st == SKL_OK)
                 hipLaunchKernelGGL((k_row_gemvN_group<D>), grid, dim3(64 * waves), lds, stream, m, x, ldx, batch, partial);
         })
-    } else if (waves <= 12) {
-        DISPATCH_D(F->d, {
-            st = allow_lds(k_row_gemv1_group<D, 12>, lds);
-            if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemv1_group<D, 12>), grid, dim3(64 * waves), lds, stream, m, x, partial);
-        })
     } else {
-        DISPATCH_D(F->d, {
-            st = allow_lds(k_row_gemv1_group<D, 16>, lds);
-            if (st == SKL_OK) hipLaunchKernelGGL((k_row_gemv1_group<D, 16>), grid, dim3(64 * waves), lds, stream, m, x, partial);
-        })
+        st = launch_gemv1_group(F->d, waves, F->decode_upw, grid, lds, stream, m, x, partial);
     }
     if (st != SKL_OK) return st;
     st = check_launch("grouped gemv");

@@ -123,23 +123,51 @@ static skl_status_t validate_desc(const skl_desc_t *d, uint64_t *n_groups_out, b
 }
 
 // Decode plan for row sketches: cut the layer into n_sseg output segments x
-// n_bg block groups, one 1024-thread workgroup each and at most one workgroup
-// per CU.  The kernels are bound by LDS gathers, so what counts is the work of
-// the busiest workgroup (segment wave-units x 16-byte words per state row of
-// its blocks); among equal splits the one with fewer segments stages fewer
-// table bytes.
-// Cost model of a decode split (microseconds, fitted to measurements on MI355X): a workgroup pays a start-up
-// latency and then 0.033 us per (64-output wave unit x 16-byte word per state row) of its share; fewer than
-// six active wavefronts cannot keep the LDS pipeline busy.  Workgroups are dealt round-robin to the 8 XCDs
-// of 32 CUs each and a group's segments all land on one XCD, so ceil(G/8)*S workgroups compete for 32 CUs.
-// total_nb: block costs of the layer in quarter words; nb0: words per state row of the first block.
-static double decode_cost(uint32_t units, uint32_t total_nb, uint32_t nb0, uint32_t S, uint32_t G)
+// n_bg block groups, one workgroup each and at most one workgroup per CU.
+// Workgroup ids are dealt round-robin to the 8 XCDs of 32 CUs each and a group's
+// segments all land on one XCD, so ceil(G/8)*S workgroups compete for 32 CUs.
+//
+// Cost model of a decode split (microseconds; constants fitted to measurements on MI355X).  A workgroup walks
+// the blocks of its group; a block step costs a fixed part (barrier, metadata, issuing the next table's
+// copy) plus the larger of its work and the time to stream the next table into LDS -- their sum when the
+// group's tables are too large for two buffers.  The work of a step is its vector time on the busiest SIMD
+// (ceil(wavefronts / 4) wavefronts x units per wavefront x words per state row) plus its gather time on the
+// CU's LDS (all wavefronts; narrow blocks put more unrelated state rows into one clock's 16 lanes and pay
+// more bank conflicts), each scaled by a fitted factor.
+struct DecodeShape {
+    uint32_t seg_units;     // 64-output units of the longest segment
+    uint32_t upw;           // units per wavefront
+    uint32_t waves;         // wavefronts per workgroup
+};
+
+static DecodeShape decode_shape(uint32_t units, uint32_t S)
 {
-    const double share = std::ceil((double)total_nb / 4.0 / G + 0.5 * nb0);   // in words; groups end on block boundaries
-    const uint32_t seg_units = (units + S - 1) / S;
-    const uint32_t per_xcd = ((G + 7) / 8) * S;
-    const uint32_t rounds = (per_xcd + 31) / 32;
-    return rounds * (1.8 + 0.033 * std::max(seg_units, 6u) * share) + 0.02 * G;
+    DecodeShape sh;
+    sh.seg_units = (units + S - 1) / S;
+    sh.upw = sh.seg_units > 16 ? 2 : 1;
+    sh.waves = std::max(2u, (sh.seg_units + sh.upw - 1) / sh.upw);
+    return sh;
+}
+
+// Fitted (least squares over 27 measured splits of five layer shapes, errors mostly within 10 %):
+#define SKL_COST_START_US 3.5        // launch, first table, activations, row addresses, fold and store
+#define SKL_COST_STEP_US 0.25        // per block step: barrier, metadata, issuing the next table's copy
+#define SKL_COST_VEC 1.32            // x the ideal vector issue time of the step on the busiest SIMD
+#define SKL_COST_LDS 0.39            // x the gather time of the step at the conflict rate of its words per state row
+#define SKL_COST_FILL_US_PER_KB 0.0149
+#define SKL_COST_GROUP_US 0.0168     // per block group: partial sums the reduction reads
+#define SKL_COST_CLOCK_MHZ 2170.0
+
+static double block_step_cost(const skl_block_meta &bm, uint32_t d, const DecodeShape &sh, bool two_bufs)
+{
+    // 6 d vector instructions per (lane, output): d - 1 packed maxima x 4, 8 decode, 4 dot products for d = 4
+    const double vec = (double)((sh.waves + 3) / 4) * sh.upw * bm.nb * 6 * d * 4 / SKL_COST_CLOCK_MHZ;
+    // the 16 lanes served in one clock read 16 / nb different state rows: expected passes per gather
+    const double conflicts = bm.nb >= 8 ? 1.5 : bm.nb == 4 ? 2.1 : bm.nb == 2 ? 2.8 : 3.1;
+    const double lds = (double)sh.waves * sh.upw * bm.nb * d * 4 * conflicts / SKL_COST_CLOCK_MHZ;
+    const double fill = SKL_COST_FILL_US_PER_KB * (((uint64_t)d * bm.K * bm.nb + 63) / 64);
+    const double work = SKL_COST_VEC * vec + SKL_COST_LDS * lds;
+    return SKL_COST_STEP_US + (two_bufs ? std::max(work, fill) : work + fill + SKL_COST_STEP_US);
 }
 
 // P->want_s, P->want_g: 0, or a split to plan instead of the cheapest one (diagnostic; false if the kernels cannot run it)
@@ -149,24 +177,22 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
     const uint32_t want_s = P->want_s, want_g = P->want_g;
     const uint32_t units = (d->out_features + 63) / 64;
     const uint32_t nblk = L.n_blocks;
-    std::vector<uint32_t> cum(nblk + 1, 0);
-    // Cost of a block in quarter words of an eight-word block (measured on MI355X: decode time of six
-    // layer shapes against these weights).  A block costs about the same whatever its word count -- its
-    // table is about as large and it takes the same barriers -- so a word of a narrow block is dearer:
-    // 8 words 32, 4 words 40, 2 words 20, 1 word 28.  With plain word counts the group that received
-    // the outlier channels' one-word blocks ran 2.5 us longer than the others on the 4096 x 11008 layer.
-    auto block_cost = [](uint32_t nb) { return nb >= 8 ? 4 * nb : nb == 4 ? 40u : nb == 2 ? 20u : 28u; };
-    for (uint32_t b = 0; b < nblk; ++b) cum[b + 1] = cum[b] + block_cost(P->bmeta[b].nb);
-    const uint32_t total_nb = cum[nblk];
-    // group boundaries for G groups: equal shares of the block costs,
-    // every group at least one block; returns the most blocks in a group
+    auto ptable_bytes = [&](const skl_block_meta &bm) { return (d->d * bm.K * bm.nb + 63) / 64 * 1024u; };
+    auto table_bytes = [&](const skl_block_meta &bm) { return d->d * bm.K * bm.rs * 16u; };
+    // Group boundaries for G groups under a decode shape: equal shares of the blocks' step costs (priced as
+    // double-buffered steps), every group at least one block.
+    std::vector<double> cum(nblk + 1, 0.0);
+    auto price_blocks = [&](const DecodeShape &sh) {
+        for (uint32_t b = 0; b < nblk; ++b)
+            cum[b + 1] = cum[b] + block_step_cost(P->bmeta[b], d->d, sh, ptable_bytes(P->bmeta[b]) <= SKL_PBUF_DIST);
+    };
     auto cut_groups = [&](uint32_t G, std::vector<uint32_t> &start) -> uint32_t {
         start.assign(G + 1, 0);
         uint32_t b = 0, most = 0;
         for (uint32_t g = 0; g < G; ++g) {
             start[g] = b;
-            const uint64_t target = (uint64_t)total_nb * (g + 1) / G;
-            while (b < nblk && (cum[b + 1] <= target || b == start[g])) ++b;
+            const double target = cum[nblk] * (g + 1) / G;
+            while (b < nblk && (cum[b + 1] <= target * (1 + 1e-12) || b == start[g])) ++b;
             if (nblk - b < G - 1 - g) b = nblk - (G - 1 - g);    // leave a block for every later group
             if (g + 1 == G) b = nblk;
             most = std::max(most, b - start[g]);
@@ -174,57 +200,109 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
         start[G] = nblk;
         return most;
     };
-    // Every split the kernels can run: S output segments of at most 16 wave units (one 64-output unit per
-    // wavefront of a 1024-thread workgroup), G block groups of at most SKL_MAX_GROUP_BLOCKS blocks; the
-    // cheapest under decode_cost() wins (the first one found among equals: fewer groups, then fewer segments).
-    double best = 1e300;
-    uint32_t best_s = 1, best_g = nblk;
-    std::vector<uint32_t> scratch_start;
-    for (uint32_t G = (nblk + SKL_MAX_GROUP_BLOCKS - 1) / SKL_MAX_GROUP_BLOCKS; G <= nblk; ++G) {
-        if (cut_groups(G, scratch_start) > SKL_MAX_GROUP_BLOCKS) continue;   // block metadata of a group sits in LDS
-        for (uint32_t S = (units + 15) / 16; S <= units; ++S) {
-            const double t = decode_cost(units, total_nb, P->bmeta[0].nb, S, G);
-            if (t < best) { best = t; best_s = S; best_g = G; }
+    // LDS plan of a cut: which groups run double-buffered, the table areas of the two kernels, the longest
+    // channel range; false if some kernel's LDS need exceeds the CU's.
+    struct Lds { uint32_t ptab, tab, max_chan; std::vector<uint32_t> flags; };
+    auto lds_plan = [&](const std::vector<uint32_t> &start, uint32_t G, uint32_t upw, Lds &o) -> bool {
+        o.flags.assign(G, 0);
+        o.max_chan = 0;
+        bool any1 = false, anyN = false;
+        for (uint32_t g = 0; g < G; ++g) {
+            uint32_t mp = 0, mt = 0;
+            for (uint32_t b = start[g]; b < start[g + 1]; ++b) {
+                mp = std::max(mp, ptable_bytes(P->bmeta[b]));
+                mt = std::max(mt, table_bytes(P->bmeta[b]));
+            }
+            if (mp <= SKL_PBUF_DIST) { o.flags[g] |= 1u; any1 = true; }
+            if (mt <= SKL_PBUF_DIST) { o.flags[g] |= 2u; anyN = true; }
+            const uint32_t c_lo = P->bmeta[start[g]].chan_off;
+            const uint32_t c_hi = start[g + 1] < nblk ? P->bmeta[start[g + 1]].chan_off : (uint32_t)P->chan.size();
+            o.max_chan = std::max(o.max_chan, c_hi - c_lo);
         }
-    }
+        // batch-1 kernel: sums of upw x 1024 outputs, block metadata, state-row addresses, the group's activations
+        const uint64_t g1_rest = 4096ull * upw + SKL_MAX_GROUP_BLOCKS * 32 + 4096ull * d->d + 2ull * (o.max_chan + 64);
+        // batched kernel: block metadata, 16 activation rows of the group
+        const uint64_t gn_rest = 16ull * (o.max_chan + 16) * 2 + 2048;
+        o.ptab = std::max<uint32_t>(any1 ? 2 * SKL_PBUF_DIST : 0, L.max_ptable_bytes);
+        o.tab = std::max<uint32_t>(anyN ? 2 * SKL_PBUF_DIST : 0, L.max_table_bytes);
+        if (o.ptab + g1_rest > SKL_LDS_HARD_BYTES) {             // no room for two buffers: one for every group
+            o.ptab = L.max_ptable_bytes;
+            for (uint32_t &f : o.flags) f &= ~1u;
+        }
+        if (o.tab + gn_rest > SKL_LDS_HARD_BYTES) {
+            o.tab = L.max_table_bytes;
+            for (uint32_t &f : o.flags) f &= ~2u;
+        }
+        return o.ptab + g1_rest <= SKL_LDS_HARD_BYTES && o.tab + gn_rest <= SKL_LDS_HARD_BYTES;
+    };
+    // cost of a split: start-up + rounds x the dearest group's steps + the reduction's share
+    auto split_cost = [&](const std::vector<uint32_t> &start, uint32_t G, uint32_t S, const DecodeShape &sh, const Lds &lds) {
+        double worst = 0;
+        for (uint32_t g = 0; g < G; ++g) {
+            double t = 0;
+            for (uint32_t b = start[g]; b < start[g + 1]; ++b) t += block_step_cost(P->bmeta[b], d->d, sh, lds.flags[g] & 1u);
+            worst = std::max(worst, t);
+        }
+        const uint32_t per_xcd = ((G + 7) / 8) * S;
+        const uint32_t rounds = (per_xcd + 31) / 32;
+        return rounds * (SKL_COST_START_US + worst) + SKL_COST_GROUP_US * G;
+    };
+    // Every split the kernels can run: S output segments of at most 32 wave units (one or two 64-output
+    // units per wavefront of a workgroup of at most 1024 threads), G block groups of at most
+    // SKL_MAX_GROUP_BLOCKS blocks; the cheapest under the model wins (the first one found among equals:
+    // fewer groups, then fewer segments).
+    double best = 1e300;
+    uint32_t best_s = 0, best_g = 0;
+    std::vector<uint32_t> start;
+    Lds lds;
+    auto try_split = [&](uint32_t S, uint32_t G) -> double {
+        const DecodeShape sh = decode_shape(units, S);
+        price_blocks(sh);
+        if (sh.upw > 1 && (L.block_classes & ~3u)) return -1.0;              // two units per wavefront: one- and two-word blocks only
+        if (cut_groups(G, start) > SKL_MAX_GROUP_BLOCKS) return -1.0;       // block metadata of a group sits in LDS
+        if (!lds_plan(start, G, sh.upw, lds)) return -1.0;
+        return split_cost(start, G, S, sh, lds);
+    };
     if (want_s && want_g) {                     // the model's figure for a split the caller names
-        if (want_g < 1 || want_g > nblk || want_s < (units + 15) / 16 || want_s > units ||
-            cut_groups(want_g, scratch_start) > SKL_MAX_GROUP_BLOCKS)
-            return false;
-        best = decode_cost(units, total_nb, P->bmeta[0].nb, want_s, want_g);
+        if (want_g > nblk || want_s < (units + 31) / 32 || want_s > units) return false;
+        best = try_split(want_s, want_g);
+        if (best < 0) return false;
         best_s = want_s; best_g = want_g;
+    } else {
+        for (uint32_t S = (units + 31) / 32; S <= units; ++S)
+            for (uint32_t G = (nblk + SKL_MAX_GROUP_BLOCKS - 1) / SKL_MAX_GROUP_BLOCKS; G <= nblk; ++G) {
+                // a split cannot cost less than its rounds' start-ups: most of the plane is skipped on this bound
+                const uint32_t rounds = (((G + 7) / 8) * S + 31) / 32;
+                if (rounds * SKL_COST_START_US + SKL_COST_GROUP_US * G >= best) continue;
+                const double t = try_split(S, G);
+                if (t >= 0 && t < best) { best = t; best_s = S; best_g = G; }
+            }
+        if (!best_s) return false;
     }
+    const DecodeShape sh = decode_shape(units, best_s);
+    price_blocks(sh);
+    cut_groups(best_g, P->bg_start);
+    if (!lds_plan(P->bg_start, best_g, sh.upw, lds)) return false;
     L.decode_cost_us = best;
     L.n_sseg = best_s;
     L.n_bg = best_g;
     L.n_wunits = units;
+    L.decode_upw = sh.upw;
     L.opl = 1;
-    cut_groups(best_g, P->bg_start);
-    uint32_t max_chan = 0;
+    L.tab_bytes = lds.tab;
+    L.ptab_bytes = lds.ptab;
+    L.max_group_chan = lds.max_chan;
     P->ginfo.assign(best_g, skl_group_info{});
     for (uint32_t g = 0; g < best_g; ++g) {
         const uint32_t lo = P->bg_start[g], hi = P->bg_start[g + 1];
         const uint32_t c_lo = P->bmeta[lo].chan_off;
         const uint32_t c_hi = hi < nblk ? P->bmeta[hi].chan_off : (uint32_t)P->chan.size();
-        max_chan = std::max(max_chan, c_hi - c_lo);
         P->ginfo[g] = skl_group_info{lo, hi, c_lo, c_hi, P->bmeta[lo].K, P->bmeta[lo].rs,
                                      P->bmeta[lo].table_off16, P->bmeta[lo].chan_off, P->bmeta[lo].ptable_off16,
-                                     0u, 0u, 0u};
+                                     lds.flags[g], 0u, 0u};
     }
-    L.max_group_chan = max_chan;
-    // batched decode (padded tables): two buffers SKL_PBUF_DIST apart, block metadata, 16 activation rows of the group
-    const uint64_t act = 16ull * (max_chan + 16) * 2 + 2048;
-    L.two_bufs = L.max_table_bytes <= SKL_PBUF_DIST && 2ull * SKL_PBUF_DIST + act <= SKL_LDS_HARD_BYTES ? 1 : 0;
-    const uint64_t g1_fixed = 6144 + 4096ull * d->d;   // output sums, block metadata, state-row addresses
-    // batch-1 kernel: the second buffer sits SKL_PBUF_DIST bytes after the first
-    // (reachable through the offset field of an LDS read), followed by the
-    // per-output sums and the group's activations
-    L.two_pbufs = L.max_ptable_bytes <= SKL_PBUF_DIST &&
-                  2ull * SKL_PBUF_DIST + g1_fixed + 2ull * (max_chan + 64) <= SKL_LDS_HARD_BYTES ? 1 : 0;
     L.n_units = L.n_bg;
-    // a single table buffer must at least fit beside the sums and activations
-    return (L.two_pbufs || (uint64_t)L.max_ptable_bytes + g1_fixed + 2ull * (max_chan + 64) <= SKL_LDS_HARD_BYTES) &&
-           (L.two_bufs || (uint64_t)L.max_table_bytes + act <= SKL_LDS_HARD_BYTES);
+    return true;
 }
 
 // Prefill plan for row sketches: the 16-channel step lists of the two kernels and which one a call takes.
@@ -426,6 +504,9 @@ static skl_status_t make_plan(const skl_desc_t *user, skl_plan *P)
         }
         L.off_codes = off;  off = align_up(off + L.code_bytes + 16, 256);
         L.off_scales = off; off = align_up(off + L.scale_bytes, 256);
+        if (L.path == 1) {      // channel block of every 64-word chunk of the unpadded tables (the expansion kernel's index)
+            L.off_chunk_block = off; off = align_up(off + L.ptable_bytes / 1024 * sizeof(uint32_t), 256);
+        }
     }
     P->dev_bytes = off;
     return SKL_OK;
@@ -509,6 +590,12 @@ skl_status_t sketch_linear_create(const skl_desc_t *desc, void *dev_buf, uint64_
         // state offset of every input channel (one group per channel)
         for (uint32_t j = 0; j < L.in; ++j) base[j + 1] = base[j] + (uint64_t)L.d * desc->group_width[j];
         if (L.qbits) {
+            uint32_t *cb = reinterpret_cast<uint32_t *>(img.data() + L.off_chunk_block);
+            for (uint32_t b = 0; b < L.n_blocks; ++b) {
+                const uint64_t first = P.bmeta[b].ptable_off16 / 64;
+                const uint64_t end = b + 1 < L.n_blocks ? P.bmeta[b + 1].ptable_off16 / 64 : L.ptable_bytes / 1024;
+                for (uint64_t ch = first; ch < end; ++ch) cb[ch] = b;
+            }
             // codes and scales in the word order of the block tables (expanded on the device, per call)
             uint8_t *tc = img.data() + L.off_codes;
             uint16_t *ts = reinterpret_cast<uint16_t *>(img.data() + L.off_scales);

@@ -14,9 +14,9 @@
 #define SKL_NO_CHANNEL 0xFFFFFFFFu
 #define SKL_MAX_GROUP_BLOCKS 64   // most channel blocks in one block group of the decode plan (metadata kept in LDS)
 
-// LDS budgets.  A CU of gfx950 has 160 KiB of LDS; keeping a workgroup's
-// table at or below the soft limit lets three workgroups share a CU.
-#define SKL_LDS_SOFT_TABLE_BYTES 50688u
+// LDS budgets.  A CU of gfx950 has 160 KiB of LDS.  A block takes the most words per state row (8, 4, 2, 1)
+// whose padded table still fits one of the decode kernels' two table buffers.
+#define SKL_LDS_SOFT_TABLE_BYTES 65280u
 #define SKL_LDS_HARD_BYTES 163840u
 // Distance between the two table buffers of the batch-1 decode kernel: below
 // 2^16, so that the buffer is chosen by the offset field of the LDS reads.
@@ -54,7 +54,10 @@ struct skl_block_meta {
 struct skl_group_info {
     uint32_t b_lo, b_hi, c_lo, c_hi;
     uint32_t K0, rs0, table_off16_0, chan_off0;
-    uint32_t ptable_off16_0, pad0, pad1, pad2;
+    uint32_t ptable_off16_0;
+    uint32_t flags;        // bit 0: every unpadded table of the group fits one of the two LDS buffers (batch-1 kernel);
+                           // bit 1: the same for the padded tables (batched kernel)
+    uint32_t pad1, pad2;
 };
 
 // One 16-channel step of the prefill walk: two 16-byte words of a block (one
@@ -98,8 +101,10 @@ struct skl_layer {
     double decode_cost_us = 0;      // the planner's model for this split
     uint32_t max_group_chan = 0;    // most channel-list entries in one block group
     uint32_t opl = 1;               // outputs per lane: ceil(segment length / 1024)
-    uint32_t two_bufs = 1;          // double-buffered tables fit in LDS (batched decode, padded tables)
-    uint32_t two_pbufs = 1;         // the same for the batch-1 kernel and the unpadded tables
+    uint32_t decode_upw = 1;        // 64-output units per wavefront of the batch-1 kernel (segments of up to 16 x upw units)
+    uint32_t tab_bytes = 0;         // LDS table area of the batched kernel (padded tables): two buffers SKL_PBUF_DIST apart
+                                    // if any block group is double-buffered, and never less than the largest table
+    uint32_t ptab_bytes = 0;        // the same for the batch-1 kernel and the unpadded tables
     uint64_t off_ginfo = 0;
     // fused prefill kernel (256 x 256 tile, weights rebuilt between the matrix instructions): usable when two
     // unpadded block tables (at most 48 KiB each), two operand slots and the block metadata fit in LDS
@@ -115,6 +120,7 @@ struct skl_layer {
     uint32_t qbits = 0;             // 0 (binary16 states), 8 or 4
     uint64_t off_codes = 0, off_scales = 0, code_bytes = 0, scale_bytes = 0;
     uint32_t scale_words = 0;       // row sketches: 16-byte scale words over all blocks
+    uint64_t off_chunk_block = 0;   // row sketches: channel block of every 64-word chunk of the unpadded tables
     uint32_t n_groups = 0;
 };
 

@@ -1,6 +1,8 @@
 """Host-only checks of the decode planner (no GPU call): for the benchmark's layer shapes the split the library
 picks is the cheapest one under its own cost model among all splits the kernels can run, and the plans the
 measurements in the design notes were taken with are still the ones picked."""
+import dataclasses
+
 import numpy as np
 import pytest
 
@@ -18,7 +20,15 @@ def description(wl):
 
 
 SHAPES = {"cfg2_q_proj": wk.cfg2(), "cfg3_up": wk.cfg3("up"), "cfg3_down": wk.cfg3("down"), "cfg4_4096": wk.cfg4(4096, 0.5),
-          "cfg4_11008_0.75": wk.cfg4(11008, 0.75), "cfg5_70b": wk.cfg5_70b()}
+          "cfg4_11008_0.75": wk.cfg4(11008, 0.75), "cfg5_70b": wk.cfg5_70b(),
+          # four times the states of cfg3_up (the state count of the paper's 4-bit recipe): wide sketches, narrow blocks
+          "cfg3_up_4x_states": dataclasses.replace(wk.cfg3("up"), bpw=2.0)}
+
+
+def units_per_segment_limit(info):
+    """One 64-output unit per wavefront and 16 wavefronts at most; two units per wavefront for layers made of
+    one- and two-word blocks only."""
+    return 32 if info["block_classes"] & ~3 == 0 else 16
 
 
 @pytest.mark.parametrize("name", sorted(SHAPES))
@@ -29,18 +39,20 @@ def test_the_picked_decode_split_is_the_cheapest_the_kernels_can_run(name):
     assert info["path"] == 1 and cost > 0
     units = (wl.out_features + 63) // 64
     S0, G0 = info["decode_segments"], info["decode_groups"]
-    assert (units + S0 - 1) // S0 <= 16                       # one 64-output unit per wavefront, 16 wavefronts at most
+    limit = units_per_segment_limit(info)
+    assert (units + S0 - 1) // S0 <= limit
     again, cost_again = skl.sketch_linear_plan(desc, S0, G0)
     assert again == info and cost_again == cost
     best, feasible = cost, 0
     groups = sorted(set(list(range(1, 65)) + [G0, 96, 128, 256, info["n_blocks"]]))
     for G in (g for g in groups if g <= info["n_blocks"]):
-        for S in range((units + 15) // 16, min(units, 64) + 1):
+        for S in range((units + 31) // 32, min(units, 64) + 1):
             try:
                 other, c = skl.sketch_linear_plan(desc, S, G)
             except skl.SketchLinearError as e:
                 assert e.status == skl.SKL_ERR_UNSUPPORTED
                 continue
+            assert (units + S - 1) // S <= limit
             feasible += 1
             assert other["decode_segments"] == S and other["decode_groups"] == G
             best = min(best, c)
@@ -50,7 +62,8 @@ def test_the_picked_decode_split_is_the_cheapest_the_kernels_can_run(name):
 
 def test_splits_the_kernels_cannot_run_are_refused():
     desc = description(wk.cfg3("up"))
-    for S, G in ((1, 16), (10, 16), (16, 1), (16, 71), (16, 10000)):   # > 16 units per segment; > 64 blocks per group; > blocks
+    # more than 32 units per segment; more than 16 on a layer with eight-word blocks; > 64 blocks per group; > blocks
+    for S, G in ((1, 16), (10, 16), (16, 1), (16, 71), (16, 10000)):
         with pytest.raises(skl.SketchLinearError) as err:
             skl.sketch_linear_plan(desc, S, G)
         assert err.value.status == skl.SKL_ERR_UNSUPPORTED
@@ -61,6 +74,17 @@ def test_splits_the_kernels_cannot_run_are_refused():
 
 def test_benchmark_layers_keep_their_measured_plans():
     """The splits the design notes' timings were taken with."""
-    for name, want in (("cfg3_up", (16, 16)), ("cfg3_down", (8, 32)), ("cfg2_q_proj", (8, 32))):
+    for name, want in (("cfg3_up", (16, 16)), ("cfg3_down", (8, 32)), ("cfg2_q_proj", (8, 32)), ("cfg5_70b", (16, 16)),
+                       ("cfg3_up_4x_states", (8, 27))):
         info, _ = skl.sketch_linear_plan(description(SHAPES[name]))
         assert (info["decode_segments"], info["decode_groups"]) == want, name
+
+
+def test_layers_of_narrow_blocks_take_two_units_per_wavefront():
+    desc = description(SHAPES["cfg3_up_4x_states"])
+    info, _ = skl.sketch_linear_plan(desc)
+    assert info["block_classes"] & ~3 == 0
+    units = (11008 + 63) // 64
+    assert 16 < (units + info["decode_segments"] - 1) // info["decode_segments"] <= 32
+    other, _ = skl.sketch_linear_plan(desc, 6, 38)          # 29 units per segment: 15 wavefronts of two units
+    assert (other["decode_segments"], other["decode_groups"]) == (6, 38)

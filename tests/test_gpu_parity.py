@@ -40,7 +40,7 @@ def small_case(name):
     if name == "row_ragged":                 # row sketches; in % 8 != 0, out % 32 != 0
         return custom_layer(name, 100, 300, 1, 300, 4, [11] * 100, 1)
     if name == "row_classes":                # four width classes -> all four table layouts in one layer
-        widths = np.array([11] * 150 + [100] * 20 + [200] * 13 + [300] * 9)
+        widths = np.array([11] * 150 + [120] * 20 + [220] * 13 + [350] * 9)
         np.random.default_rng(2).shuffle(widths)
         return custom_layer(name, 192, 520, 1, 520, 4, widths, 2)
     if name == "row_d1":
@@ -57,11 +57,11 @@ def small_case(name):
     if name == "row_single":                 # degenerate: one input channel, one output
         return custom_layer(name, 1, 1, 1, 1, 3, [1], 8)
     if name == "row_four_words":             # mostly blocks of four words per state row, three widths among them,
-        widths = np.array([11] * 40 + [100] * 70 + [129] * 50 + [150] * 40)   # ragged last block of each width
+        widths = np.array([11] * 40 + [120] * 70 + [129] * 50 + [150] * 40)   # ragged last block of each width
         np.random.default_rng(13).shuffle(widths)
         return custom_layer(name, 200, 300, 1, 300, 4, widths, 13)
-    if name == "row_four_words_d6":          # the same with six sketch rows (four words from width 58 on)
-        widths = np.array([20] * 30 + [60] * 45 + [100] * 60 + [150] * 9)
+    if name == "row_four_words_d6":          # the same with six sketch rows (four words from width 76 on)
+        widths = np.array([20] * 30 + [80] * 45 + [100] * 60 + [150] * 9)
         np.random.default_rng(14).shuffle(widths)
         return custom_layer(name, 144, 520, 1, 520, 6, widths, 14)
     if name == "tile_ragged":                # 2-D groups, per-group widths, tile_out < workgroup

@@ -149,22 +149,28 @@ static DecodeShape decode_shape(uint32_t units, uint32_t S)
     return sh;
 }
 
-// Fitted (least squares over 27 measured splits of five layer shapes, errors mostly within 10 %):
-#define SKL_COST_START_US 3.5        // launch, first table, activations, row addresses, fold and store
-#define SKL_COST_STEP_US 0.25        // per block step: barrier, metadata, issuing the next table's copy
-#define SKL_COST_VEC 1.32            // x the ideal vector issue time of the step on the busiest SIMD
-#define SKL_COST_LDS 0.39            // x the gather time of the step at the conflict rate of its words per state row
-#define SKL_COST_FILL_US_PER_KB 0.0149
-#define SKL_COST_GROUP_US 0.0168     // per block group: partial sums the reduction reads
+// Fitted by least squares to the batch-1 kernel times of 46 splits of nine layer shapes measured on MI355X
+// (root-mean-square error 8 %):
+#define SKL_COST_START_US 2.47       // launch, first table, activations, row addresses, fold and store
+#define SKL_COST_STEP_US 0.16        // per block step: barrier, metadata, issuing the next table's copy
+#define SKL_COST_VEC 1.25            // x the ideal vector issue time of the step on the busiest SIMD
+#define SKL_COST_LDS 0.63            // x the gather time of the step at the conflict rate of its words per state row
+#define SKL_COST_MIN_WAVES 6u        // fewer wavefronts do not hide each other's LDS latency: priced as this many
+#define SKL_COST_FILL_US_PER_KB 0.0154
+#define SKL_COST_WORST_SHARE 0.70    // the kernel's time follows the dearest group this much and the mean load per CU for the rest
+#define SKL_COST_GROUP_US 0.0289     // per block group, in the kernel
+#define SKL_COST_CLASS_US 0.78        // a change of sketch width inside a group: new state-row addresses, per unit of a wavefront
+#define SKL_COST_REDUCE_US_PER_MB 1.7   // the reduction pass reads one float per (group, output)
 #define SKL_COST_CLOCK_MHZ 2170.0
 
 static double block_step_cost(const skl_block_meta &bm, uint32_t d, const DecodeShape &sh, bool two_bufs)
 {
+    const uint32_t waves = std::max(sh.waves, SKL_COST_MIN_WAVES);
     // 6 d vector instructions per (lane, output): d - 1 packed maxima x 4, 8 decode, 4 dot products for d = 4
-    const double vec = (double)((sh.waves + 3) / 4) * sh.upw * bm.nb * 6 * d * 4 / SKL_COST_CLOCK_MHZ;
+    const double vec = (double)((waves + 3) / 4) * sh.upw * bm.nb * 6 * d * 4 / SKL_COST_CLOCK_MHZ;
     // the 16 lanes served in one clock read 16 / nb different state rows: expected passes per gather
     const double conflicts = bm.nb >= 8 ? 1.5 : bm.nb == 4 ? 2.1 : bm.nb == 2 ? 2.8 : 3.1;
-    const double lds = (double)sh.waves * sh.upw * bm.nb * d * 4 * conflicts / SKL_COST_CLOCK_MHZ;
+    const double lds = (double)waves * sh.upw * bm.nb * d * 4 * conflicts / SKL_COST_CLOCK_MHZ;
     const double fill = SKL_COST_FILL_US_PER_KB * (((uint64_t)d * bm.K * bm.nb + 63) / 64);
     const double work = SKL_COST_VEC * vec + SKL_COST_LDS * lds;
     return SKL_COST_STEP_US + (two_bufs ? std::max(work, fill) : work + fill + SKL_COST_STEP_US);
@@ -179,12 +185,21 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
     const uint32_t nblk = L.n_blocks;
     auto ptable_bytes = [&](const skl_block_meta &bm) { return (d->d * bm.K * bm.nb + 63) / 64 * 1024u; };
     auto table_bytes = [&](const skl_block_meta &bm) { return d->d * bm.K * bm.rs * 16u; };
-    // Group boundaries for G groups under a decode shape: equal shares of the blocks' step costs (priced as
-    // double-buffered steps), every group at least one block.
+    // Group boundaries for G groups: equal shares of the blocks' relative costs, every group at least one block.
     std::vector<double> cum(nblk + 1, 0.0);
-    auto price_blocks = [&](const DecodeShape &sh) {
-        for (uint32_t b = 0; b < nblk; ++b)
-            cum[b + 1] = cum[b] + block_step_cost(P->bmeta[b], d->d, sh, ptable_bytes(P->bmeta[b]) <= SKL_PBUF_DIST);
+    // The shares of the groups are cut by relative block costs measured directly (decode time of six layer
+    // shapes against these weights), which the step model above does not resolve: a block costs about the same
+    // whatever its word count -- its table is about as large, it takes the same barriers, a new sketch width
+    // means new state-row addresses -- so a word of a narrow block is dearer: 8 words 32, 4 words 40, 2 words
+    // 20, 1 word 28.  With plain word counts the group that received the outlier channels' narrow blocks ran
+    // 2.5 us longer than the others on the 4096 x 11008 layer.  A table too large for double buffering is
+    // copied after, not during, the block before it: half as much again.
+    auto price_blocks = [&](const DecodeShape &) {
+        for (uint32_t b = 0; b < nblk; ++b) {
+            const skl_block_meta &bm = P->bmeta[b];
+            const double w = bm.nb >= 8 ? 32.0 : bm.nb == 4 ? 40.0 : bm.nb == 2 ? 20.0 : 28.0;
+            cum[b + 1] = cum[b] + (ptable_bytes(bm) <= SKL_PBUF_DIST ? w : 1.5 * w);
+        }
     };
     auto cut_groups = [&](uint32_t G, std::vector<uint32_t> &start) -> uint32_t {
         start.assign(G + 1, 0);
@@ -235,30 +250,39 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
         }
         return o.ptab + g1_rest <= SKL_LDS_HARD_BYTES && o.tab + gn_rest <= SKL_LDS_HARD_BYTES;
     };
-    // cost of a split: start-up + rounds x the dearest group's steps + the reduction's share
+    // Cost of a split: rounds x (start-up + a blend of the dearest group's time and the mean load of a CU)
+    // + what the number of groups costs in the kernel and in the reduction pass.  The step model gives the
+    // time of all blocks together; a group's part of it is its share of the relative block costs the cut
+    // was made with (the model does not resolve the cost of one narrow block against one wide block).
     auto split_cost = [&](const std::vector<uint32_t> &start, uint32_t G, uint32_t S, const DecodeShape &sh, const Lds &lds) {
-        double worst = 0;
+        double total = 0, heaviest = 0;
         for (uint32_t g = 0; g < G; ++g) {
-            double t = 0;
-            for (uint32_t b = start[g]; b < start[g + 1]; ++b) t += block_step_cost(P->bmeta[b], d->d, sh, lds.flags[g] & 1u);
-            worst = std::max(worst, t);
+            for (uint32_t b = start[g]; b < start[g + 1]; ++b) {
+                total += block_step_cost(P->bmeta[b], d->d, sh, lds.flags[g] & 1u);
+                if (b > start[g] && P->bmeta[b].K != P->bmeta[b - 1].K) total += SKL_COST_CLASS_US * sh.upw;
+            }
+            heaviest = std::max(heaviest, cum[start[g + 1]] - cum[start[g]]);
         }
+        const double worst = total * heaviest / cum[nblk];
         const uint32_t per_xcd = ((G + 7) / 8) * S;
         const uint32_t rounds = (per_xcd + 31) / 32;
-        return rounds * (SKL_COST_START_US + worst) + SKL_COST_GROUP_US * G;
+        const double mean = total * S / ((double)SKL_N_CU * rounds);
+        return rounds * (SKL_COST_START_US + SKL_COST_WORST_SHARE * worst + (1 - SKL_COST_WORST_SHARE) * mean) +
+               SKL_COST_GROUP_US * G + SKL_COST_REDUCE_US_PER_MB * G * d->out_features * 4e-6;
     };
-    // Every split the kernels can run: S output segments of at most 32 wave units (one or two 64-output
-    // units per wavefront of a workgroup of at most 1024 threads), G block groups of at most
-    // SKL_MAX_GROUP_BLOCKS blocks; the cheapest under the model wins (the first one found among equals:
-    // fewer groups, then fewer segments).
+    // Candidates: S output segments of at most 32 wave units (one or two 64-output units per wavefront of a
+    // workgroup of at most 1024 threads), G block groups of at most SKL_MAX_GROUP_BLOCKS blocks; for layers of
+    // 16 blocks or more G is a multiple of 8, so that every XCD runs the same number of groups.  The model
+    // cannot rank splits that it prices within 3 % of each other (its own error is larger): among those the
+    // one that occupies the most CUs wins, then the one with fewer segments (fewer copies of every table).
     double best = 1e300;
     uint32_t best_s = 0, best_g = 0;
     std::vector<uint32_t> start;
     Lds lds;
     auto try_split = [&](uint32_t S, uint32_t G) -> double {
         const DecodeShape sh = decode_shape(units, S);
-        price_blocks(sh);
         if (sh.upw > 1 && (L.block_classes & ~3u)) return -1.0;              // two units per wavefront: one- and two-word blocks only
+        price_blocks(sh);
         if (cut_groups(G, start) > SKL_MAX_GROUP_BLOCKS) return -1.0;       // block metadata of a group sits in LDS
         if (!lds_plan(start, G, sh.upw, lds)) return -1.0;
         return split_cost(start, G, S, sh, lds);
@@ -269,15 +293,27 @@ static bool plan_decode(const skl_desc_t *d, skl_plan *P)
         if (best < 0) return false;
         best_s = want_s; best_g = want_g;
     } else {
+        struct Cand { double t; uint32_t S, G, cus; };
+        std::vector<Cand> cands;
+        const uint32_t g_step = nblk >= 16 ? 8 : 1;
+        const uint32_t g_lo = (nblk + SKL_MAX_GROUP_BLOCKS - 1) / SKL_MAX_GROUP_BLOCKS;
         for (uint32_t S = (units + 31) / 32; S <= units; ++S)
-            for (uint32_t G = (nblk + SKL_MAX_GROUP_BLOCKS - 1) / SKL_MAX_GROUP_BLOCKS; G <= nblk; ++G) {
+            for (uint32_t G = (g_lo + g_step - 1) / g_step * g_step; G <= nblk; G += g_step) {
                 // a split cannot cost less than its rounds' start-ups: most of the plane is skipped on this bound
                 const uint32_t rounds = (((G + 7) / 8) * S + 31) / 32;
-                if (rounds * SKL_COST_START_US + SKL_COST_GROUP_US * G >= best) continue;
+                if (rounds * SKL_COST_START_US + SKL_COST_GROUP_US * G >= best * 1.03) continue;
                 const double t = try_split(S, G);
-                if (t >= 0 && t < best) { best = t; best_s = S; best_g = G; }
+                if (t < 0) continue;
+                cands.push_back(Cand{t, S, G, std::min<uint32_t>(S * G, SKL_N_CU)});
+                best = std::min(best, t);
             }
-        if (!best_s) return false;
+        if (cands.empty()) return false;
+        const Cand *pick = nullptr;
+        for (const Cand &c : cands) {
+            if (c.t > best * 1.03) continue;
+            if (!pick || c.cus > pick->cus || (c.cus == pick->cus && (c.S < pick->S || (c.S == pick->S && c.t < pick->t)))) pick = &c;
+        }
+        best = pick->t; best_s = pick->S; best_g = pick->G;
     }
     const DecodeShape sh = decode_shape(units, best_s);
     price_blocks(sh);
@@ -398,6 +434,14 @@ static bool plan_rows(const skl_desc_t *d, skl_plan *P)
     L.scale_words = soff16;
     L.max_ptable_bytes = 0;
     L.block_classes = 0;
+    L.n_small_blocks = 0;
+    L.small_table_bytes = 0;
+    for (const skl_block_meta &bm : P->bmeta) {             // three workgroups with tables of 49.5 KiB share a CU
+        const uint32_t bytes = d->d * bm.K * bm.rs * 16u;
+        if (bytes > 50688u) break;
+        ++L.n_small_blocks;
+        L.small_table_bytes = std::max(L.small_table_bytes, bytes);
+    }
     for (const skl_block_meta &bm : P->bmeta) {
         L.max_ptable_bytes = std::max<uint32_t>(L.max_ptable_bytes, (d->d * bm.K * bm.nb + 63) / 64 * 1024u);
         L.block_classes |= bm.nb == 8 ? 8u : bm.nb == 4 ? 4u : bm.nb == 2 ? 2u : 1u;

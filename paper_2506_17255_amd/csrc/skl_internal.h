@@ -94,6 +94,8 @@ struct skl_layer {
     uint64_t off_ptables = 0, ptable_bytes = 0;
     uint32_t max_ptable_bytes = 0;
     uint32_t block_classes = 0;     // bit log2(nb) set for every words-per-state-row class present
+    uint32_t n_small_blocks = 0;    // blocks before the first one whose padded table exceeds 49.5 KiB,
+    uint32_t small_table_bytes = 0; // and the largest padded table among them
     // decode plan: workgroup (s, g) owns output segment s (a range of 64-output
     // wave units) and block group g (consecutive channel blocks bg_start[g] ..
     // bg_start[g+1]); n_sseg * n_bg workgroups of 1024 threads, one per CU

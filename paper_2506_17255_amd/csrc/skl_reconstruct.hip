@@ -32,10 +32,11 @@ __device__ __forceinline__ void row_reconstruct_body(const RowArgs &p, const skl
     }
 }
 
+// grid (channel blocks from block0 on, output segments)
 template <int D>
-__global__ __launch_bounds__(SKL_WG) void k_row_reconstruct(RowArgs p, uint16_t *__restrict__ W_hat)
+__global__ __launch_bounds__(SKL_WG) void k_row_reconstruct(RowArgs p, uint32_t block0, uint16_t *__restrict__ W_hat)
 {
-    const skl_block_meta bm = p.bmeta[blockIdx.x];
+    const skl_block_meta bm = p.bmeta[block0 + blockIdx.x];
     const uint32_t n16 = D * bm.K * bm.rs;
     stage_table(smem, p.tables + bm.table_off16, n16);
     uint32_t *chs = reinterpret_cast<uint32_t *>(smem + n16);
@@ -58,11 +59,17 @@ skl_status_t skl_launch_reconstruct(const skl_layer *L, uint16_t *W_hat, void *w
     if (st != SKL_OK) return st;
     if (L->path == 1) {
         const RowArgs a = make_row_args(L, src);
+        // The blocks are sorted by sketch width.  Those before the first large table are launched with the LDS
+        // they need (three workgroups per CU for tables up to 49.5 KiB), the rest with room for the largest table.
+        const uint32_t n_small = L->n_small_blocks;
+        const size_t lds_small = (size_t)L->small_table_bytes + 64 * sizeof(uint32_t);
         const size_t lds = (size_t)L->max_table_bytes + 64 * sizeof(uint32_t);
-        const dim3 grid(L->n_blocks, L->n_seg);
         DISPATCH_D(L->d, {
             st = allow_lds(k_row_reconstruct<D>, lds);
-            if (st == SKL_OK) hipLaunchKernelGGL(k_row_reconstruct<D>, grid, dim3(SKL_WG), lds, stream, a, W_hat);
+            if (st == SKL_OK && n_small)
+                hipLaunchKernelGGL(k_row_reconstruct<D>, dim3(n_small, L->n_seg), dim3(SKL_WG), lds_small, stream, a, 0u, W_hat);
+            if (st == SKL_OK && n_small < L->n_blocks)
+                hipLaunchKernelGGL(k_row_reconstruct<D>, dim3(L->n_blocks - n_small, L->n_seg), dim3(SKL_WG), lds, stream, a, n_small, W_hat);
         });
     } else {
         return skl_tile_launch_reconstruct(L, src, W_hat, stream);

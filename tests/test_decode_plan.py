@@ -1,6 +1,7 @@
 """Host-only checks of the decode planner (no GPU call): for the benchmark's layer shapes the split the library
-picks is the cheapest one under its own cost model among all splits the kernels can run, and the plans the
-measurements in the design notes were taken with are still the ones picked."""
+picks is the cheapest one under its own cost model among its candidates (up to the model's 3 % resolution, where
+occupied CUs and fewer segments decide), and the plans the measurements in the design notes were taken with are
+still the ones picked."""
 import dataclasses
 
 import numpy as np
@@ -43,8 +44,11 @@ def test_the_picked_decode_split_is_the_cheapest_the_kernels_can_run(name):
     assert (units + S0 - 1) // S0 <= limit
     again, cost_again = skl.sketch_linear_plan(desc, S0, G0)
     assert again == info and cost_again == cost
-    best, feasible = cost, 0
-    groups = sorted(set(list(range(1, 65)) + [G0, 96, 128, 256, info["n_blocks"]]))
+    # the planner's candidates: for layers of 16 blocks or more the groups come in multiples of 8 (one share per XCD)
+    step = 8 if info["n_blocks"] >= 16 else 1
+    assert G0 % step == 0
+    found = {}
+    groups = sorted(set(list(range(step, 65, step)) + [G0, 96, 128, 256]))
     for G in (g for g in groups if g <= info["n_blocks"]):
         for S in range((units + 31) // 32, min(units, 64) + 1):
             try:
@@ -53,11 +57,17 @@ def test_the_picked_decode_split_is_the_cheapest_the_kernels_can_run(name):
                 assert e.status == skl.SKL_ERR_UNSUPPORTED
                 continue
             assert (units + S - 1) // S <= limit
-            feasible += 1
             assert other["decode_segments"] == S and other["decode_groups"] == G
-            best = min(best, c)
-    assert feasible > 50
-    assert cost <= best * (1 + 1e-12), (S0, G0, cost, best)
+            found[(S, G)] = c
+    assert len(found) > 50
+    best = min(found.values())
+    # splits priced within 3 % of the cheapest are equals for the model: the pick is the one among them that
+    # occupies the most CUs, then the one with the fewest segments
+    equals = {k: c for k, c in found.items() if c <= best * 1.03}
+    assert (S0, G0) in equals, (S0, G0, cost, best)
+    cus = lambda k: min(k[0] * k[1], 256)
+    for k in equals:
+        assert cus(k) < cus((S0, G0)) or (cus(k) == cus((S0, G0)) and k[0] >= S0), (k, equals[k], (S0, G0), cost)
 
 
 def test_splits_the_kernels_cannot_run_are_refused():
@@ -75,7 +85,7 @@ def test_splits_the_kernels_cannot_run_are_refused():
 def test_benchmark_layers_keep_their_measured_plans():
     """The splits the design notes' timings were taken with."""
     for name, want in (("cfg3_up", (16, 16)), ("cfg3_down", (8, 32)), ("cfg2_q_proj", (8, 32)), ("cfg5_70b", (16, 16)),
-                       ("cfg3_up_4x_states", (8, 27))):
+                       ("cfg3_up_4x_states", (8, 32))):
         info, _ = skl.sketch_linear_plan(description(SHAPES[name]))
         assert (info["decode_segments"], info["decode_groups"]) == want, name
 

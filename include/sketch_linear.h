@@ -329,6 +329,43 @@ SKL_API skl_status_t sketch_linear_reconstruct_hash_op(const skl_layer_t *layer,
 SKL_API skl_status_t sketch_linear_microbench(uint32_t kind, uint32_t iters, void *workspace, uint64_t workspace_bytes,
                                       void *hip_stream, uint64_t *work);
 
+/* Layer file: a description (the sketch state S of Sec. 3.1 with its select
+ * parameters of Eq. 3 and the per-group widths of Sec. 3.2 / 3.3 -- everything
+ * create() takes) as one flat little-endian image: a 128-byte header (magic
+ * "SKLAYER1", version, geometry, section offsets, 64-bit FNV-1a checksum),
+ * then hash_a, hash_c, group_width, the states (or codes) and the scales,
+ * each section 64-byte aligned.  Host only, no GPU call.
+ *   file_bytes  size of the image of a (fully validated) description;
+ *   file_write  writes the image into `image` (HOST, >= file_bytes);
+ *   file_save   the same into a file at `path`;
+ *   file_open   checks an image (magic, version, size, checksum, section
+ *               offsets against the geometry, then the whole validation of
+ *               create()) and fills *desc with pointers INTO the image --
+ *               nothing is copied, so a file can be mapped and used in
+ *               place; the image must be 8-byte aligned and outlive every
+ *               use of *desc.  SKL_ERR_INVALID_ARG for anything that is not
+ *               an intact layer file, SKL_ERR_UNSUPPORTED for another
+ *               version of the format. */
+SKL_API skl_status_t sketch_linear_file_bytes(const skl_desc_t *desc, uint64_t *bytes);
+SKL_API skl_status_t sketch_linear_file_write(const skl_desc_t *desc, void *image, uint64_t image_bytes);
+SKL_API skl_status_t sketch_linear_file_save(const skl_desc_t *desc, const char *path);
+SKL_API skl_status_t sketch_linear_file_open(const void *image, uint64_t image_bytes, skl_desc_t *desc);
+
+/* Debug build only (libsketch_linear_debug.so, compiled with
+ * -DSKL_DEBUG_BOUNDS): its kernels check the index ranges they rely on --
+ * select indices (Eq. 3) against the sketch width, LDS addresses of gathers
+ * and table copies, channel and block numbers -- and count violations
+ * instead of faulting (the offending access is redirected).  *count receives
+ * the violations since the library was loaded (synchronise the streams
+ * first); first[5] (may be NULL) the first one: code, value, limit,
+ * workgroup, thread.  SKL_ERR_UNSUPPORTED in the normal build, whose kernels
+ * carry no checks. */
+SKL_API skl_status_t sketch_linear_debug_violations(uint64_t *count, uint32_t first[5]);
+/* Debug build only: enqueues one thread that evaluates the range assert
+ * `value < limit` (code 7) and touches no memory -- lets a test watch a
+ * violation being counted.  SKL_ERR_UNSUPPORTED in the normal build. */
+SKL_API skl_status_t sketch_linear_debug_selftest(uint32_t value, uint32_t limit, void *hip_stream);
+
 /* Frees the host object only; dev_buf stays the caller's. NULL is accepted. */
 SKL_API void sketch_linear_destroy(skl_layer_t *layer);
 

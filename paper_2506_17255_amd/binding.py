@@ -40,6 +40,8 @@ EXPORTS = ("sketch_linear_device_bytes", "sketch_linear_create", "sketch_linear_
            "sketch_linear_build_workspace_bytes", "sketch_linear_build_states",
            "sketch_linear_gemv_group_workspace_bytes", "sketch_linear_gemv_group", "sketch_linear_gemv_gate_up",
            "sketch_linear_plan", "sketch_linear_gemv_static", "sketch_linear_reconstruct_hash_op", "sketch_linear_microbench",
+           "sketch_linear_file_bytes", "sketch_linear_file_write", "sketch_linear_file_save", "sketch_linear_file_open",
+           "sketch_linear_debug_violations", "sketch_linear_debug_selftest",
            "sketch_linear_destroy", "sketch_linear_last_error")
 
 
@@ -300,6 +302,47 @@ def sketch_linear_microbench(kind: int, iters: int, workspace: int, workspace_by
     work = ctypes.c_uint64(0)
     _check(load_library().sketch_linear_microbench(kind, iters, workspace, workspace_bytes, hip_stream, ctypes.byref(work)))
     return work.value
+
+
+def sketch_linear_file_bytes(desc: skl_desc_t) -> int:
+    n = ctypes.c_uint64(0)
+    _check(load_library().sketch_linear_file_bytes(ctypes.byref(desc), ctypes.byref(n)))
+    return n.value
+
+
+def sketch_linear_file_write(desc: skl_desc_t, image) -> None:
+    """Writes the layer file of ``desc`` into ``image`` (a writable object with the buffer protocol)."""
+    mv = memoryview(image)
+    buf = (ctypes.c_char * mv.nbytes).from_buffer(mv)
+    _check(load_library().sketch_linear_file_write(ctypes.byref(desc), buf, mv.nbytes))
+
+
+def sketch_linear_file_save(desc: skl_desc_t, path: str) -> None:
+    _check(load_library().sketch_linear_file_save(ctypes.byref(desc), os.fsencode(path)))
+
+
+def sketch_linear_file_open(image) -> skl_desc_t:
+    """The description held by a layer file image (a writable, 8-byte aligned object with the buffer
+    protocol: a bytearray, a numpy array, a writable memory map).  The description points into the image
+    and keeps it alive."""
+    mv = memoryview(image)
+    buf = (ctypes.c_char * mv.nbytes).from_buffer(mv)
+    desc = skl_desc_t()
+    _check(load_library().sketch_linear_file_open(buf, mv.nbytes, ctypes.byref(desc)))
+    desc._keep = [image, buf]
+    return desc
+
+
+def sketch_linear_debug_selftest(value: int, limit: int, hip_stream: int = 0) -> None:
+    _check(load_library().sketch_linear_debug_selftest(value, limit, hip_stream))
+
+
+def sketch_linear_debug_violations():
+    """(count, first) of the range asserts of the debug build; raises SKL_ERR_UNSUPPORTED in the normal build."""
+    count = ctypes.c_uint64(0)
+    first = (ctypes.c_uint32 * 5)()
+    _check(load_library().sketch_linear_debug_violations(ctypes.byref(count), first))
+    return count.value, dict(zip(("code", "value", "limit", "workgroup", "thread"), first))
 
 
 def sketch_linear_destroy(layer: int) -> None:

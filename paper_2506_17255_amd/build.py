@@ -14,8 +14,10 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libsketch_linear.so")
+# the same library with range asserts in its kernels (-DSKL_DEBUG_BOUNDS): violations are counted, not trapped
+DEBUG_LIB = os.path.join(HERE, "libsketch_linear_debug.so")
 # compiled once
-COMMON_SOURCES = ["skl_host.cpp", "skl_dispatch.cpp", "skl_lowbit.hip", "skl_build.hip", "skl_microbench.hip"]
+COMMON_SOURCES = ["skl_host.cpp", "skl_file.cpp", "skl_dispatch.cpp", "skl_lowbit.hip", "skl_build.hip", "skl_microbench.hip"]
 # compiled once per query mode (-DSKL_QM=0 / 1): their kernels and launchers live in a namespace per mode
 MODE_SOURCES = ["skl_prefill.hip", "skl_decode.hip", "skl_prefill_staged.hip", "skl_reconstruct.hip", "skl_tile.hip",
                 "skl_naive.hip"]
@@ -55,24 +57,28 @@ def _stale(src: str, obj: str) -> bool:
     return any(os.path.getmtime(d) > os.path.getmtime(obj) for d in deps)
 
 
-def build_library(verbose: bool = False, jobs: int | None = None, incremental: bool = False) -> str:
+def build_library(verbose: bool = False, jobs: int | None = None, incremental: bool = False, debug_bounds: bool = False) -> str:
     """Compile every source for gfx950 and link the shared library.  With
-    `incremental`, objects newer than their source and every header are kept."""
+    `incremental`, objects newer than their source and every header are kept.
+    `debug_bounds` builds the variant whose kernels carry range asserts."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    os.makedirs(OBJ_DIR, exist_ok=True)
+    obj_dir = os.path.join(OBJ_DIR, "debug") if debug_bounds else OBJ_DIR
+    os.makedirs(obj_dir, exist_ok=True)
     jobs = jobs or max(1, min(os.cpu_count() or 1, 8))
-    units = [(s, [], os.path.splitext(s)[0] + ".o") for s in COMMON_SOURCES]
+    extra = ["-DSKL_DEBUG_BOUNDS"] if debug_bounds else []
+    units = [(s, extra, os.path.splitext(s)[0] + ".o") for s in COMMON_SOURCES]
     # the long compilations first, so that the pool ends evenly
-    units = [(s, [f"-DSKL_QM={m}"], f"{os.path.splitext(s)[0]}_qm{m}.o") for s in MODE_SOURCES for m in (0, 1)] + units
-    objs = [os.path.join(OBJ_DIR, o) for _, _, o in units]
+    units = [(s, extra + [f"-DSKL_QM={m}"], f"{os.path.splitext(s)[0]}_qm{m}.o") for s in MODE_SOURCES for m in (0, 1)] + units
+    objs = [os.path.join(obj_dir, o) for _, _, o in units]
     cmds = [[hipcc] + _flags() + defs + ["-c", os.path.join(CSRC, s), "-o", o] for (s, defs, _), o in zip(units, objs)
             if not incremental or _stale(os.path.join(CSRC, s), o)]
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(lambda c: _run(c, verbose), cmds))
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden"] + objs + ["-o", LIB], verbose)
-    return LIB
+    lib = DEBUG_LIB if debug_bounds else LIB
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden"] + objs + ["-o", lib], verbose)
+    return lib
 
 
 if __name__ == "__main__":
     import sys
-    print(build_library(verbose=True, incremental="--incremental" in sys.argv))
+    print(build_library(verbose=True, incremental="--incremental" in sys.argv, debug_bounds="--debug-bounds" in sys.argv))

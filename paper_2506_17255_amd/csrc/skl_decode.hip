@@ -49,6 +49,7 @@ __device__ __forceinline__ StreamCtx stream_ctx(const StreamArgs &p)
     c.K0 = gi.K0; c.rs0 = gi.rs0; c.toff0 = gi.table_off16_0; c.chan_off0 = gi.chan_off0;
     c.ptoff0 = gi.ptable_off16_0;
     c.two_bufs = (gi.flags & p.buf_flag) != 0;
+    if (!skl_in_range(c.b_hi, p.r.n_blocks + 1, SKL_DBG_BLOCK) || !skl_in_range(c.b_lo, c.b_hi + 1, SKL_DBG_BLOCK)) c.live = false;
     c.o_lo = (uint32_t)(((uint64_t)s * p.n_wunits) / p.n_sseg) * 64;
     c.o_hi = min((uint32_t)(((uint64_t)(s + 1) * p.n_wunits) / p.n_sseg) * 64, p.r.out);
     return c;
@@ -292,7 +293,7 @@ __device__ __forceinline__ void gemv1_body(const StreamArgs &p, const uint16_t *
     for (int u = 0; u < U; ++u) w.yw[u * w.unit_stride + w.lane] = 0.f;
     for (uint32_t i = threadIdx.x; i < c.c_hi - c.c_lo; i += blockDim.x) {
         const uint32_t ch = p.r.chan[c.c_lo + i];
-        xs[i] = ch != SKL_NO_CHANNEL ? (uint16_t)(x[ch] ^ 0x8000u) : (uint16_t)0;
+        xs[i] = ch != SKL_NO_CHANNEL && skl_in_range(ch, p.r.in, SKL_DBG_CHANNEL) ? (uint16_t)(x[ch] ^ 0x8000u) : (uint16_t)0;
     }
     w.first_wait = true;                 // waited for in the first step of the first run
     while (w.bi < w.nblk) {
@@ -514,7 +515,7 @@ __device__ __forceinline__ void gemvN_body(const StreamArgs &p, const uint16_t *
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             v[k] = 0;
-            if (ch != SKL_NO_CHANNEL && b0 + k < batch) v[k] = x[(size_t)(b0 + k) * ldx + ch] ^ 0x8000u;
+            if (ch != SKL_NO_CHANNEL && b0 + k < batch && skl_in_range(ch, p.r.in, SKL_DBG_CHANNEL)) v[k] = x[(size_t)(b0 + k) * ldx + ch] ^ 0x8000u;
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) xs[(b0 + k) * xs_stride + cc] = v[k];

@@ -47,6 +47,54 @@ typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
 
 extern __shared__ uint4 smem[];
 
+// ---------------------------------------------------------- range asserts
+// The debug build of the library (-DSKL_DEBUG_BOUNDS, libsketch_linear_debug.so) checks the index ranges the
+// kernels rely on: select indices against the sketch width, LDS addresses of gathers and table copies
+// against the CU's LDS, channel numbers against d_in, block numbers against the layer's blocks.  A violation
+// never traps (a faulting kernel can take the machine down): it is counted in a device array of the
+// translation unit, the first one is kept with its code, value, limit, workgroup and thread, and the access
+// is redirected to a harmless place.  sketch_linear_debug_violations() adds the arrays of all translation
+// units up.  In the normal build the checks compile to nothing.
+#define SKL_DBG_SELECT 1u        // select index >= sketch width K
+#define SKL_DBG_LDS_READ 2u      // 16-byte LDS read outside the CU's LDS or misaligned
+#define SKL_DBG_LDS_COPY 3u      // table copy lands outside the CU's LDS
+#define SKL_DBG_CHANNEL 4u       // input channel number >= d_in
+#define SKL_DBG_BLOCK 5u         // channel block number >= blocks of the layer
+#define SKL_DBG_OUTPUT 6u        // output index >= d_out
+#define SKL_DBG_SELFTEST 7u      // sketch_linear_debug_selftest
+#ifdef SKL_DEBUG_BOUNDS
+namespace {
+__device__ uint32_t skl_debug_rec[8];              // count, then the first violation: code, value, limit, workgroup, thread
+skl_status_t skl_debug_read_this_unit(uint32_t rec[8])
+{
+    hipError_t e = hipMemcpyFromSymbol(rec, HIP_SYMBOL(skl_debug_rec), 8 * sizeof(uint32_t));
+    if (e != hipSuccess) {
+        skl_set_error("reading the range-assert record: %s", hipGetErrorString(e));
+        return SKL_ERR_HIP;
+    }
+    return SKL_OK;
+}
+struct SklDebugRegistrar { SklDebugRegistrar() { skl_debug_register(&skl_debug_read_this_unit); } } skl_debug_registrar;
+}  // namespace
+namespace {
+__device__ __attribute__((noinline)) void skl_debug_record(uint32_t value, uint32_t limit, uint32_t code)
+{
+    if (atomicAdd(&skl_debug_rec[0], 1u) == 0) {
+        skl_debug_rec[1] = code; skl_debug_rec[2] = value; skl_debug_rec[3] = limit;
+        skl_debug_rec[4] = blockIdx.x; skl_debug_rec[5] = threadIdx.x;
+    }
+}
+}  // namespace
+__device__ __forceinline__ bool skl_in_range(uint32_t value, uint32_t limit, uint32_t code)
+{
+    if (__builtin_expect(value < limit, 1)) return true;
+    skl_debug_record(value, limit, code);       // out of line: the checks sit at every gather of unrolled loops
+    return false;
+}
+#else
+__device__ __forceinline__ bool skl_in_range(uint32_t, uint32_t, uint32_t) { return true; }
+#endif
+
 // --------------------------------------------------------------- helpers
 __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
 {
@@ -126,6 +174,7 @@ typedef __attribute__((address_space(3))) void lds_void;
 __device__ __forceinline__ void lds_dma_16(const void *gptr, uint4 *lds_dst)
 {
     const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void *)lds_dst);
+    if (!skl_in_range(lds_addr, SKL_LDS_HARD_BYTES - 1023u, SKL_DBG_LDS_COPY)) return;
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory", "m0");
 }
 
@@ -147,7 +196,8 @@ __device__ __forceinline__ void wait_async_copies()
 // low 24 bits of t count, so t may be kept as a wrapping 32-bit number.
 __device__ __forceinline__ uint32_t select_index(uint32_t t, uint32_t Kq)
 {
-    return (uint32_t)(((uint64_t)(t & 0xFFFFFFu) * (uint64_t)(Kq & 0xFFFFFFu)) >> 32);
+    const uint32_t k = (uint32_t)(((uint64_t)(t & 0xFFFFFFu) * (uint64_t)(Kq & 0xFFFFFFu)) >> 32);
+    return skl_in_range(k, Kq >> 8, SKL_DBG_SELECT) ? k : 0u;
 }
 
 __device__ __forceinline__ float dot2_acc(uint32_t w2, uint32_t x2, float acc)
@@ -198,6 +248,7 @@ struct HashArgs {
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 lds_word_at(uint32_t addr)
 {
+    if (!skl_in_range(addr | (addr & 15u ? 0xFFFFFFFFu : 0u), SKL_LDS_HARD_BYTES - 15u, SKL_DBG_LDS_READ)) addr = 0;
     const u32x4v v = *(const __attribute__((address_space(3))) u32x4v *)(uintptr_t)addr;
     return make_uint4(v.x, v.y, v.z, v.w);
 }

@@ -582,8 +582,37 @@ uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, bo
     return n;
 }
 
+// ---------------------------------------------------------- debug build
+static std::vector<skl_debug_reader> &debug_readers()
+{
+    static std::vector<skl_debug_reader> readers;      // filled by static initialisers of the kernel files
+    return readers;
+}
+
+void skl_debug_register(skl_debug_reader fn) { debug_readers().push_back(fn); }
+
 // -------------------------------------------------------------------- ABI
 extern "C" {
+
+skl_status_t sketch_linear_debug_selftest(uint32_t value, uint32_t limit, void *hip_stream)
+{
+    return skl_launch_debug_selftest(value, limit, hip_stream);
+}
+
+skl_status_t sketch_linear_debug_violations(uint64_t *count, uint32_t first[5])
+{
+    if (!count) FAIL(SKL_ERR_INVALID_ARG, "count is NULL");
+    if (debug_readers().empty()) FAIL(SKL_ERR_UNSUPPORTED, "this build of the library carries no range asserts");
+    *count = 0;
+    for (skl_debug_reader fn : debug_readers()) {
+        uint32_t rec[8];
+        skl_status_t st = fn(rec);
+        if (st != SKL_OK) return st;
+        if (rec[0] && !*count && first) memcpy(first, rec + 1, 5 * sizeof(uint32_t));
+        *count += rec[0];
+    }
+    return SKL_OK;
+}
 
 const char *sketch_linear_last_error(void) { return g_err; }
 

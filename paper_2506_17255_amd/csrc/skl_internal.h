@@ -146,6 +146,11 @@ static inline bool skl_gemm_is_staged(const skl_layer *L, uint32_t tokens) { ret
 // error text of the calling thread
 void skl_set_error(const char *fmt, ...);
 
+// Debug build (-DSKL_DEBUG_BOUNDS): every translation unit with kernels registers a reader of its
+// range-assert record (count, then code, value, limit, workgroup, thread of the first violation).
+typedef skl_status_t (*skl_debug_reader)(uint32_t rec[8]);
+void skl_debug_register(skl_debug_reader fn);
+
 // validation + planning (host only); fills `plan` without touching `states`
 // beyond the finiteness check
 skl_status_t skl_make_plan(const skl_desc_t *desc, skl_plan *plan);
@@ -189,5 +194,6 @@ skl_status_t skl_launch_build(const skl_desc_t *d, uint64_t n_groups, const uint
 // ceilings of the machine: four small kernels (skl_microbench.hip)
 uint64_t skl_microbench_work(uint32_t kind, uint32_t iters, uint64_t ws_bytes);
 skl_status_t skl_launch_microbench(uint32_t kind, uint32_t iters, void *ws, uint64_t ws_bytes, void *stream);
+skl_status_t skl_launch_debug_selftest(uint32_t value, uint32_t limit, void *stream);
 uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, bool by_col, uint32_t *segs, uint64_t cap,
                             uint32_t *shape);

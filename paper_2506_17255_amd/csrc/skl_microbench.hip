@@ -126,3 +126,24 @@ skl_status_t skl_launch_microbench(uint32_t kind, uint32_t iters, void *ws, uint
     }
     return check_launch("microbenchmark");
 }
+
+// ---- range asserts of the debug build: one thread evaluates `value < limit` and touches no memory, so
+// that a test can watch a violation being counted -----------------------------------------------
+#ifdef SKL_DEBUG_BOUNDS
+__global__ void k_debug_selftest(uint32_t value, uint32_t limit)
+{
+    if (threadIdx.x == 0) skl_in_range(value, limit, SKL_DBG_SELFTEST);
+}
+#endif
+
+skl_status_t skl_launch_debug_selftest(uint32_t value, uint32_t limit, void *stream_)
+{
+#ifdef SKL_DEBUG_BOUNDS
+    hipLaunchKernelGGL(k_debug_selftest, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream_), value, limit);
+    return check_launch("range-assert self-test");
+#else
+    (void)value; (void)limit; (void)stream_;
+    skl_set_error("this build of the library carries no range asserts");
+    return SKL_ERR_UNSUPPORTED;
+#endif
+}

@@ -62,6 +62,7 @@ template <int D>
 __device__ __forceinline__ void rebuild_block(const RebuildArgs &p, uint32_t idx)
 {
     const uint32_t blk = idx % p.n_blocks, seg = idx / p.n_blocks;
+    if (!skl_in_range(blk, p.n_blocks, SKL_DBG_BLOCK) || !skl_in_range(seg, p.n_oseg, SKL_DBG_OUTPUT)) return;
     const skl_block_meta bm = p.bmeta[blk];
     stage_table(smem, p.tables + bm.table_off16, D * bm.K * bm.rs);
     __syncthreads();

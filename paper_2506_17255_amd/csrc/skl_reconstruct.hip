@@ -26,7 +26,8 @@ __device__ __forceinline__ void row_reconstruct_body(const RowArgs &p, const skl
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const uint32_t ch = chs[c * 8 + i];
-                if (ch != SKL_NO_CHANNEL) W_hat[(size_t)ch * p.out + o] = (uint16_t)(v[i >> 1] >> ((i & 1) * 16));
+                if (ch != SKL_NO_CHANNEL && skl_in_range(ch, p.in, SKL_DBG_CHANNEL))
+                    W_hat[(size_t)ch * p.out + o] = (uint16_t)(v[i >> 1] >> ((i & 1) * 16));
             }
         }
     }
@@ -36,6 +37,7 @@ __device__ __forceinline__ void row_reconstruct_body(const RowArgs &p, const skl
 template <int D>
 __global__ __launch_bounds__(SKL_WG) void k_row_reconstruct(RowArgs p, uint32_t block0, uint16_t *__restrict__ W_hat)
 {
+    if (!skl_in_range(block0 + blockIdx.x, p.n_blocks, SKL_DBG_BLOCK)) return;
     const skl_block_meta bm = p.bmeta[block0 + blockIdx.x];
     const uint32_t n16 = D * bm.K * bm.rs;
     stage_table(smem, p.tables + bm.table_off16, n16);

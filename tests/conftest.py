@@ -30,3 +30,23 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_sessionfinish(session, exitstatus):
+    """A session that ran on the debug build of the library (SKETCH_LINEAR_LIB names it) fails if any of its
+    kernels counted a range-assert violation."""
+    if "debug" not in os.path.basename(os.environ.get("SKETCH_LINEAR_LIB", "")):
+        return
+    import paper_2506_17255_amd as skl
+    try:
+        import torch
+        if torch.cuda.is_available():
+            torch.cuda.synchronize()
+        count, first = skl.sketch_linear_debug_violations()
+    except skl.SketchLinearError as e:
+        print(f"\nrange asserts: {e}")
+        session.exitstatus = 1
+        return
+    print(f"\nrange asserts of the debug build: {count} violation(s)" + (f", first {first}" if count else ""))
+    if count:
+        session.exitstatus = 1

@@ -41,3 +41,4 @@ skl_status_t skl_launch_build(const skl_desc_t *, uint64_t, const uint64_t *, co
 }
 uint64_t skl_microbench_work(uint32_t, uint32_t, uint64_t) { return 0; }
 skl_status_t skl_launch_microbench(uint32_t, uint32_t, void *, uint64_t, void *) { return no_device("microbenchmark"); }
+skl_status_t skl_launch_debug_selftest(uint32_t, uint32_t, void *) { return no_device("range-assert self-test"); }

@@ -47,7 +47,7 @@ def desc_of(sk: oracle.Sketch, flags: int = 0, query_mode: int = 0):
 class GpuLayer:
     """A layer resident on cuda:0 plus the buffers its calls need."""
 
-    def __init__(self, sk: oracle.Sketch, flags: int = 0, query_mode: int = 0):
+    def __init__(self, sk: oracle.Sketch, flags: int = 0, query_mode: int = 0, through_file: bool = False):
         torch = torch_mod()
         if not torch.cuda.is_available():
             raise RuntimeError("GPU tests need a GPU")
@@ -55,6 +55,10 @@ class GpuLayer:
         self.sk = sk
         self.dev = torch.device("cuda:0")
         desc = desc_of(sk, flags, query_mode)
+        if through_file:                    # the description as a flat layer file image, opened in place
+            image = np.zeros(skl.sketch_linear_file_bytes(desc), dtype=np.uint8)
+            skl.sketch_linear_file_write(desc, image)
+            desc = skl.sketch_linear_file_open(image)
         nbytes = skl.sketch_linear_device_bytes(desc)
         self.dev_buf = torch.zeros(nbytes, dtype=torch.uint8, device=self.dev)
         self.handle = skl.sketch_linear_create(desc, self.dev_buf.data_ptr(), nbytes, self.stream())

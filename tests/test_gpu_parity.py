@@ -739,3 +739,19 @@ def test_call_time_validation():
         assert status(y=x.data_ptr()) == skl.SKL_ERR_INVALID_ARG          # aliasing
         assert status(x=0) == skl.SKL_ERR_INVALID_ARG
         t.cuda.synchronize()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,bits,mode", [("row_classes", 0, 0), ("row_classes", 4, 1), ("cfg1", 0, 0), ("tile_ragged", 8, 0)])
+def test_a_layer_created_from_its_file_image_is_the_same_layer(name, bits, mode):
+    """Sec. 3.1: the states, select parameters and widths are the whole layer; written to the flat file format
+    and opened in place they give the oracle's reconstruction (Eq. 5) bit for bit and the same decode output."""
+    W, sk = small_case(name)
+    if bits:
+        sk = oracle.quantize(sk, bits)
+    want = oracle.query(sk, mode)
+    x = np.random.default_rng(31).standard_normal((2, sk.in_features)).astype(np.float16)
+    with GpuLayer(sk, flags_of(name), mode, through_file=True) as g, GpuLayer(sk, flags_of(name), mode) as direct:
+        assert g.info == direct.info
+        assert np.array_equal(g.reconstruct(), want)
+        assert np.array_equal(g.gemv(x, "f32"), direct.gemv(x, "f32"))

@@ -10,7 +10,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = os.path.join(ROOT, "paper_2506_17255_amd", "csrc")
 SAN = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g", "-O1"]
-SUITE = ["tests/test_oracle_pins.py", "tests/test_oracle_lowbit.py", "tests/test_library_host.py", "tests/test_prefill_split.py"]
+SUITE = ["tests/test_oracle_pins.py", "tests/test_oracle_lowbit.py", "tests/test_library_host.py", "tests/test_prefill_split.py",
+         "tests/test_layer_file.py", "tests/test_decode_plan.py"]
 
 
 def _runtime():
@@ -40,7 +41,8 @@ def test_cpu_suite_under_address_and_undefined_behaviour_sanitizers(tmp_path):
     host_so = tmp_path / "libsketch_linear_host_san.so"
     subprocess.check_call(["g++", "-std=c++17", "-fPIC", "-shared", *SAN, "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
                            "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", str(host_so),
-                           os.path.join(CSRC, "skl_host.cpp"), os.path.join(ROOT, "tests", "sanitize", "host_stubs.cpp"),
+                           os.path.join(CSRC, "skl_host.cpp"), os.path.join(CSRC, "skl_file.cpp"),
+                           os.path.join(ROOT, "tests", "sanitize", "host_stubs.cpp"),
                            "-L/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib"])
     env = dict(os.environ, LD_PRELOAD=asan, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0",
                UBSAN_OPTIONS="print_stacktrace=1", SKETCH_ORACLE_LIB=str(oracle_so), SKETCH_LINEAR_LIB=str(host_so))

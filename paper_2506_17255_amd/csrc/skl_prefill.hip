@@ -7,41 +7,90 @@ namespace SKL_NS {
 
 
 // ---- activation re-ordering pre-pass ----------------------------------------
-// grid (ceil(steps / 4), 8 * token tiles); a workgroup re-orders 32 tokens x 4 steps
-__global__ __launch_bounds__(SKL_WG) void k_pack_activations2(const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
+// Converts X to negated binary16 and lays it out as the matrix-core A words of the product kernels:
+// word (token tile, step, row block of 32 tokens, half q, token n) holds the eight channels 8q .. 8q + 7 of
+// the step for one token.  A workgroup takes one row block x PK_STEPS steps.  Phase 1: a thread owns one of
+// the 2 * PK_STEPS words and fetches it for 32 / PK_PARTS of the 32 tokens into LDS rows (all loads in flight at once): with one 16-byte load per
+// token where the word's eight channels are neighbours in X and aligned (the width order moves few channels,
+// so nearly every word; a wavefront then reads one contiguous KiB of a token's row), else channel by
+// channel.  Phase 2: a wavefront writes one step's 64 words -- one contiguous KiB -- from 16-byte LDS reads
+// that spread over all banks (row stride 2064 bytes).
+// grid (ceil(tokens / 32), ceil(steps / PK_STEPS)); LDS PK_LDS_BYTES
+#define PK_STEPS 32u
+#define PK_STRIDE (PK_STEPS * 16u + 8u)          // halfs per LDS row
+#define PK_LDS_BYTES (32u * PK_STRIDE * 2u)
+#define PK_PARTS (SKL_WG / (2u * PK_STEPS))     // threads per word: each takes 32 / PK_PARTS tokens
+static_assert(2 * PK_STEPS * PK_PARTS == SKL_WG && 32 % PK_PARTS == 0, "one thread per (word, part of the row block)");
+
+__device__ __forceinline__ uint32_t neg_half_pair(uint32_t e, uint32_t x_dt)
+{
+    if (x_dt == SKL_BF16) {
+        const uint32_t lo = float_to_half_bits(__builtin_bit_cast(float, e << 16));
+        const uint32_t hi = float_to_half_bits(__builtin_bit_cast(float, e & 0xFFFF0000u));
+        e = lo | (hi << 16);
+    }
+    return e ^ 0x80008000u;
+}
+
+__global__ __launch_bounds__(SKL_WG) void k_pack_activations3(const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
                                                                uint32_t tokens, const uint32_t *__restrict__ chan,
                                                                const skl_gemm_step *__restrict__ steps, uint32_t n_steps,
                                                                uint4 *__restrict__ Xp)
 {
-    const uint32_t g = threadIdx.x & 7, n = threadIdx.x >> 3;      // k-group (step, half) and token of the 32-token row block
-    const uint32_t step = blockIdx.x * 4 + (g >> 1), q = g & 1;
-    if (step >= n_steps) return;
-    const uint32_t rb = blockIdx.y & 7, tile_m = blockIdx.y >> 3;
-    const uint32_t t = tile_m * GM_MT + rb * 32 + n;
-    const skl_gemm_step st = steps[step];
-    uint16_t v[8];
+    uint16_t *rows = reinterpret_cast<uint16_t *>(smem);
+    const uint32_t t0 = blockIdx.x * 32, s0 = blockIdx.y * PK_STEPS;
+    const uint32_t ns = min(PK_STEPS, n_steps - s0);
+    {
+        const uint32_t word = threadIdx.x & (2 * PK_STEPS - 1), part = threadIdx.x / (2 * PK_STEPS);   // word = 2 * step + q
+        const uint32_t step = word >> 1, q = word & 1;
+        uint32_t ch[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        v[i] = 0;
-        if (q < st.n_words && t < tokens) {
-            const uint32_t ch = chan[st.chan0 + 8 * q + i];
-            if (ch != SKL_NO_CHANNEL) v[i] = load_neg_half(X, x_dt, (size_t)t * ldx + ch);
+        for (int i = 0; i < 8; ++i) ch[i] = SKL_NO_CHANNEL;
+        if (step < ns) {
+            const skl_gemm_step st = steps[s0 + step];
+            if (q < st.n_words) {
+                const uint4 c0 = *reinterpret_cast<const uint4 *>(chan + st.chan0 + 8 * q);       // chan0 is a multiple of 8
+                const uint4 c1 = *reinterpret_cast<const uint4 *>(chan + st.chan0 + 8 * q + 4);
+                ch[0] = c0.x; ch[1] = c0.y; ch[2] = c0.z; ch[3] = c0.w; ch[4] = c1.x; ch[5] = c1.y; ch[6] = c1.z; ch[7] = c1.w;
+            }
+        }
+        bool run = ch[0] != SKL_NO_CHANNEL && (ch[0] & 7u) == 0 && (ldx & 7u) == 0 && (reinterpret_cast<uintptr_t>(X) & 15u) == 0;
+#pragma unroll
+        for (int i = 1; i < 8; ++i) run = run && ch[i] == ch[0] + i;
+        constexpr uint32_t TPT = 32 / PK_PARTS;                     // tokens per thread
+        if (run) {
+            uint4 e[TPT];
+#pragma unroll
+            for (uint32_t j = 0; j < TPT; ++j) {
+                const uint32_t t = min(t0 + part * TPT + j, tokens - 1);           // rows past the end re-read the last one
+                e[j] = *reinterpret_cast<const uint4 *>(X + (size_t)t * ldx + ch[0]);
+            }
+#pragma unroll
+            for (uint32_t j = 0; j < TPT; ++j) {
+                const uint32_t t = part * TPT + j;
+                uint4 w = make_uint4(neg_half_pair(e[j].x, x_dt), neg_half_pair(e[j].y, x_dt), neg_half_pair(e[j].z, x_dt), neg_half_pair(e[j].w, x_dt));
+                if (t0 + t >= tokens) w = make_uint4(0, 0, 0, 0);
+                *reinterpret_cast<uint4 *>(rows + t * PK_STRIDE + word * 8) = w;
+            }
+        } else {
+            for (uint32_t j = 0; j < TPT; ++j) {
+                const uint32_t t = part * TPT + j;
+                uint32_t v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    v[i] = ch[i] != SKL_NO_CHANNEL && t0 + t < tokens ? load_neg_half(X + (size_t)(t0 + t) * ldx, x_dt, ch[i]) : 0u;
+                *reinterpret_cast<uint4 *>(rows + t * PK_STRIDE + word * 8) =
+                    make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+            }
         }
     }
-    uint4 w;
-    w.x = v[0] | ((uint32_t)v[1] << 16); w.y = v[2] | ((uint32_t)v[3] << 16);
-    w.z = v[4] | ((uint32_t)v[5] << 16); w.w = v[6] | ((uint32_t)v[7] << 16);
-    Xp[(((size_t)tile_m * n_steps + step) * 8 + rb) * 64 + q * 32 + n] = w;
-}
-
-// the re-ordering with the rows staged in LDS (pack_rows_lds); grid (ceil(tokens / TOK))
-template <int TOK>
-__global__ __launch_bounds__(SKL_WG) void k_pack_activations3(const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
-                                                               uint32_t tokens, uint32_t in, const uint32_t *__restrict__ chan,
-                                                               const skl_gemm_step *__restrict__ steps, uint32_t n_steps,
-                                                               uint4 *__restrict__ Xp)
-{
-    pack_rows_lds<TOK>(blockIdx.x, X, x_dt, ldx, tokens, in, chan, steps, n_steps, Xp);
+    __syncthreads();
+    const uint32_t n = threadIdx.x & 31, q = (threadIdx.x >> 5) & 1;
+    const uint32_t tile_m = t0 / GM_MT, rb = (t0 % GM_MT) / 32;
+    for (uint32_t step = threadIdx.x >> 6; step < ns; step += SKL_WG / 64) {
+        const uint4 w = *reinterpret_cast<const uint4 *>(rows + n * PK_STRIDE + step * 16 + q * 8);
+        Xp[(((size_t)tile_m * n_steps + s0 + step) * 8 + rb) * 64 + q * 32 + n] = w;
+    }
 }
 
 
@@ -397,23 +446,15 @@ uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
     return L->qbits ? round256(own) + skl_dequant_bytes(L) : own;
 }
 
-// activation re-ordering for the second and third prefill kernels: rows staged in LDS when four
-// of them fit, else gathered from global memory
+// activation re-ordering for the prefill kernels
 skl_status_t skl_launch_pack(const skl_layer *L, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx, uint32_t tokens,
                              const uint32_t *chan, const skl_gemm_step *steps, uint32_t n_steps, uint4 *Xp, hipStream_t stream)
 {
-    const uint32_t m_tiles = (tokens + GM_MT - 1) / GM_MT;
-    const size_t row_bytes = ((size_t)L->in + 4) * 2;           // an even number of elements plus one dword of padding
-    skl_status_t st = SKL_OK;
-    if (4 * row_bytes <= 160 * 1024) {                          // up to 10 KiB rows: four workgroups per CU overlap their phases
-        st = allow_lds(k_pack_activations3<4>, 4 * row_bytes);
-        if (st != SKL_OK) return st;
-        hipLaunchKernelGGL(k_pack_activations3<4>, dim3((tokens + 3) / 4), dim3(SKL_WG), 4 * row_bytes, stream, X, (uint32_t)x_dt,
-                           ldx, tokens, L->in, chan, steps, n_steps, Xp);
-    } else {
-        hipLaunchKernelGGL(k_pack_activations2, dim3((n_steps + 3) / 4, 8 * m_tiles), dim3(SKL_WG), 0, stream, X,
-                           (uint32_t)x_dt, ldx, tokens, chan, steps, n_steps, Xp);
-    }
+    (void)L;
+    skl_status_t st = allow_lds(k_pack_activations3, PK_LDS_BYTES);
+    if (st != SKL_OK) return st;
+    hipLaunchKernelGGL(k_pack_activations3, dim3((tokens + 31) / 32, (n_steps + PK_STEPS - 1) / PK_STEPS), dim3(SKL_WG), PK_LDS_BYTES,
+                       stream, X, (uint32_t)x_dt, ldx, tokens, chan, steps, n_steps, Xp);
     return check_launch("activation packing");
 }
 

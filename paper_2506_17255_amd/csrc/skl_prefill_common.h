@@ -22,73 +22,6 @@ skl_status_t skl_launch_gemm3_fixup(const G3Split &sp, const float *parts, void 
 #define GM_NT 128            // outputs per workgroup
 #define GM_THREADS 512       // four compute + four copy wavefronts
 
-
-// Activation re-ordering with the rows staged in LDS: a workgroup reads TOK whole token rows with
-// coalesced loads (converting them to negated binary16 once), then gathers every step's channels from
-// LDS.  Workgroup `block` of ceil(tokens / TOK); TOK divides 32; LDS TOK * (in + 4) * 2 bytes.
-template <int TOK>
-__device__ __forceinline__ void pack_rows_lds(uint32_t block, const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
-                                              uint32_t tokens, uint32_t in, const uint32_t *__restrict__ chan,
-                                              const skl_gemm_step *__restrict__ steps, uint32_t n_steps,
-                                              uint4 *__restrict__ Xp)
-{
-    uint16_t *rows = reinterpret_cast<uint16_t *>(smem);
-    const uint32_t stride = ((in + 1) & ~1u) + 2;               // elements: even, and off the power-of-two bank pattern
-    const uint32_t t_first = block * TOK;
-    const bool vec = ldx % 8 == 0;
-    for (uint32_t j = 0; j < TOK; ++j) {
-        const uint32_t t = t_first + j;
-        if (t >= tokens) break;
-        const uint16_t *src = X + (size_t)t * ldx;
-        uint16_t *dst = rows + j * stride;
-        if (vec) {
-            for (uint32_t c = threadIdx.x * 8; c < in; c += SKL_WG * 8) {
-                if (c + 8 <= in) {
-                    const uint4 w = *reinterpret_cast<const uint4 *>(src + c);
-                    const uint32_t e[4] = {w.x, w.y, w.z, w.w};
-                    uint32_t *d32 = reinterpret_cast<uint32_t *>(dst + c);      // rows and c are even: dword aligned
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        uint32_t lo = e[i] & 0xFFFFu, hi = e[i] >> 16;
-                        if (x_dt == SKL_BF16) {
-                            lo = float_to_half_bits(__builtin_bit_cast(float, lo << 16));
-                            hi = float_to_half_bits(__builtin_bit_cast(float, hi << 16));
-                        }
-                        d32[i] = (lo | (hi << 16)) ^ 0x80008000u;
-                    }
-                } else {
-                    for (uint32_t i = c; i < in; ++i) dst[i] = load_neg_half(src, x_dt, i);
-                }
-            }
-        } else {
-            for (uint32_t c = threadIdx.x; c < in; c += SKL_WG) dst[c] = load_neg_half(src, x_dt, c);
-        }
-    }
-    __syncthreads();
-    // a thread takes one 8-channel word position and fills it for all TOK tokens: its channel list is
-    // read once, and its TOK words are neighbours in the packed layout
-    const uint32_t tile_m = t_first / GM_MT, rb = (t_first % GM_MT) / 32, n0 = t_first % 32;
-    for (uint32_t item = threadIdx.x; item < 2 * n_steps; item += SKL_WG) {
-        const uint32_t step = item >> 1, q = item & 1;
-        const skl_gemm_step st = steps[step];
-        uint32_t ch[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) ch[i] = q < st.n_words ? chan[st.chan0 + 8 * q + i] : SKL_NO_CHANNEL;
-        uint4 *dst = Xp + (((size_t)tile_m * n_steps + step) * 8 + rb) * 64 + q * 32 + n0;
-#pragma unroll
-        for (uint32_t j = 0; j < TOK; ++j) {
-            const uint16_t *row = rows + j * stride;
-            uint16_t v[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = ch[i] != SKL_NO_CHANNEL && t_first + j < tokens ? row[ch[i]] : (uint16_t)0;
-            uint4 w;
-            w.x = v[0] | ((uint32_t)v[1] << 16); w.y = v[2] | ((uint32_t)v[3] << 16);
-            w.z = v[4] | ((uint32_t)v[5] << 16); w.w = v[6] | ((uint32_t)v[7] << 16);
-            dst[j] = w;
-        }
-    }
-}
-
 // Operand slot: word (cb, row = 2*step + k-group, n) at ((cb*8 + row)*34 + n);
 // 34 instead of 32 words per row keeps the producers' scattered writes (eight
 // rows, two neighbouring n per 16 lanes) on distinct banks.

@@ -9,16 +9,18 @@ namespace SKL_NS {
 // ---- activation re-ordering pre-pass ----------------------------------------
 // Converts X to negated binary16 and lays it out as the matrix-core A words of the product kernels:
 // word (token tile, step, row block of 32 tokens, half q, token n) holds the eight channels 8q .. 8q + 7 of
-// the step for one token.  A workgroup takes one row block x PK_STEPS steps.  Phase 1: a thread owns one of
-// the 2 * PK_STEPS words and fetches it for 32 / PK_PARTS of the 32 tokens into LDS rows (all loads in flight at once): with one 16-byte load per
-// token where the word's eight channels are neighbours in X and aligned (the width order moves few channels,
-// so nearly every word; a wavefront then reads one contiguous KiB of a token's row), else channel by
-// channel.  Phase 2: a wavefront writes one step's 64 words -- one contiguous KiB -- from 16-byte LDS reads
-// that spread over all banks (row stride 2064 bytes).
+// the step for one token.  A workgroup takes one row block x PK_STEPS steps and builds its words in LDS rows.
+// Phase 1: a thread owns one of the 2 * PK_STEPS words for 32 / PK_PARTS of the 32 tokens.  Where the word's
+// eight channels are neighbours in X (the width order moves few channels, so nearly every word) it is cut
+// out of the one or two aligned 16-byte pieces of the row that hold it, all loads in flight at once; a
+// wavefront then reads about one contiguous KiB of a token's row.  The other words (they span a moved
+// channel, or end the channel list) are noted and fetched channel by channel by the whole workgroup, so that
+// no wavefront walks the slow path for a few of its lanes.  Phase 2: a wavefront writes one step's 64 words
+// -- one contiguous KiB -- from 16-byte LDS reads that spread over all banks (row stride 1040 bytes).
 // grid (ceil(tokens / 32), ceil(steps / PK_STEPS)); LDS PK_LDS_BYTES
 #define PK_STEPS 32u
 #define PK_STRIDE (PK_STEPS * 16u + 8u)          // halfs per LDS row
-#define PK_LDS_BYTES (32u * PK_STRIDE * 2u)
+#define PK_LDS_BYTES (32u * PK_STRIDE * 2u + 4u * (1u + 9u * 2u * PK_STEPS) + 12u)
 #define PK_PARTS (SKL_WG / (2u * PK_STEPS))     // threads per word: each takes 32 / PK_PARTS tokens
 static_assert(2 * PK_STEPS * PK_PARTS == SKL_WG && 32 % PK_PARTS == 0, "one thread per (word, part of the row block)");
 
@@ -33,13 +35,16 @@ __device__ __forceinline__ uint32_t neg_half_pair(uint32_t e, uint32_t x_dt)
 }
 
 __global__ __launch_bounds__(SKL_WG) void k_pack_activations3(const uint16_t *__restrict__ X, uint32_t x_dt, uint32_t ldx,
-                                                               uint32_t tokens, const uint32_t *__restrict__ chan,
+                                                               uint32_t tokens, uint32_t in, const uint32_t *__restrict__ chan,
                                                                const skl_gemm_step *__restrict__ steps, uint32_t n_steps,
                                                                uint4 *__restrict__ Xp)
 {
     uint16_t *rows = reinterpret_cast<uint16_t *>(smem);
+    uint32_t *slow = reinterpret_cast<uint32_t *>(rows + 32 * PK_STRIDE);     // count, then (word, eight channels) per noted word
     const uint32_t t0 = blockIdx.x * 32, s0 = blockIdx.y * PK_STEPS;
     const uint32_t ns = min(PK_STEPS, n_steps - s0);
+    if (threadIdx.x == 0) slow[0] = 0;
+    __syncthreads();
     {
         const uint32_t word = threadIdx.x & (2 * PK_STEPS - 1), part = threadIdx.x / (2 * PK_STEPS);   // word = 2 * step + q
         const uint32_t step = word >> 1, q = word & 1;
@@ -54,34 +59,55 @@ __global__ __launch_bounds__(SKL_WG) void k_pack_activations3(const uint16_t *__
                 ch[0] = c0.x; ch[1] = c0.y; ch[2] = c0.z; ch[3] = c0.w; ch[4] = c1.x; ch[5] = c1.y; ch[6] = c1.z; ch[7] = c1.w;
             }
         }
-        bool run = ch[0] != SKL_NO_CHANNEL && (ch[0] & 7u) == 0 && (ldx & 7u) == 0 && (reinterpret_cast<uintptr_t>(X) & 15u) == 0;
+        // a word whose eight channels are neighbours in X is cut out of the one or two aligned 16-byte pieces
+        // of the row that hold it (rows must be 16-byte aligned and long enough for the second piece)
+        bool run = ch[0] != SKL_NO_CHANNEL && (ldx & 7u) == 0 && (reinterpret_cast<uintptr_t>(X) & 15u) == 0;
 #pragma unroll
         for (int i = 1; i < 8; ++i) run = run && ch[i] == ch[0] + i;
+        const uint32_t sh = ch[0] & 7u, base = ch[0] - sh;                 // the word starts sh halfs into the piece at column base
+        run = run && (sh == 0 || base + 16 <= in);                          // the second piece lies inside the row
         constexpr uint32_t TPT = 32 / PK_PARTS;                     // tokens per thread
         if (run) {
-            uint4 e[TPT];
+            uint4 e[TPT], f[TPT];
 #pragma unroll
             for (uint32_t j = 0; j < TPT; ++j) {
                 const uint32_t t = min(t0 + part * TPT + j, tokens - 1);           // rows past the end re-read the last one
-                e[j] = *reinterpret_cast<const uint4 *>(X + (size_t)t * ldx + ch[0]);
+                const uint4 *src = reinterpret_cast<const uint4 *>(X + (size_t)t * ldx + base);
+                e[j] = src[0];
+                f[j] = sh ? src[1] : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (uint32_t j = 0; j < TPT; ++j) {
                 const uint32_t t = part * TPT + j;
-                uint4 w = make_uint4(neg_half_pair(e[j].x, x_dt), neg_half_pair(e[j].y, x_dt), neg_half_pair(e[j].z, x_dt), neg_half_pair(e[j].w, x_dt));
+                // halfs sh .. sh + 7 of the sixteen: drop four, two, one half in turn
+                uint32_t d[8] = {e[j].x, e[j].y, e[j].z, e[j].w, f[j].x, f[j].y, f[j].z, f[j].w};
+                if (sh & 4u) { d[0] = d[2]; d[1] = d[3]; d[2] = d[4]; d[3] = d[5]; d[4] = d[6]; d[5] = d[7]; }
+                if (sh & 2u) { d[0] = d[1]; d[1] = d[2]; d[2] = d[3]; d[3] = d[4]; d[4] = d[5]; }
+                if (sh & 1u) {
+                    d[0] = __builtin_amdgcn_alignbit(d[1], d[0], 16); d[1] = __builtin_amdgcn_alignbit(d[2], d[1], 16);
+                    d[2] = __builtin_amdgcn_alignbit(d[3], d[2], 16); d[3] = __builtin_amdgcn_alignbit(d[4], d[3], 16);
+                }
+                uint4 w = make_uint4(neg_half_pair(d[0], x_dt), neg_half_pair(d[1], x_dt), neg_half_pair(d[2], x_dt), neg_half_pair(d[3], x_dt));
                 if (t0 + t >= tokens) w = make_uint4(0, 0, 0, 0);
                 *reinterpret_cast<uint4 *>(rows + t * PK_STRIDE + word * 8) = w;
             }
-        } else {
-            for (uint32_t j = 0; j < TPT; ++j) {
-                const uint32_t t = part * TPT + j;
-                uint32_t v[8];
+        } else if (part == 0) {
+            // a word that spans a moved channel (or ends the channel list): noted for the pass below, where the
+            // whole workgroup fetches such words channel by channel
+            const uint32_t e = atomicAdd(&slow[0], 1u);
+            slow[1 + 9 * e] = word;
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    v[i] = ch[i] != SKL_NO_CHANNEL && t0 + t < tokens ? load_neg_half(X + (size_t)(t0 + t) * ldx, x_dt, ch[i]) : 0u;
-                *reinterpret_cast<uint4 *>(rows + t * PK_STRIDE + word * 8) =
-                    make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
-            }
+            for (int i = 0; i < 8; ++i) slow[2 + 9 * e + i] = ch[i];
+        }
+    }
+    __syncthreads();
+    {
+        const uint32_t n_slow = slow[0];
+        for (uint32_t idx = threadIdx.x; idx < n_slow * 256; idx += SKL_WG) {      // (word, token, channel slot)
+            const uint32_t e = idx >> 8, t = (idx >> 3) & 31, i = idx & 7;
+            const uint32_t word = slow[1 + 9 * e], c = slow[2 + 9 * e + i];
+            rows[t * PK_STRIDE + word * 8 + i] =
+                c != SKL_NO_CHANNEL && t0 + t < tokens ? load_neg_half(X + (size_t)(t0 + t) * ldx, x_dt, c) : (uint16_t)0;
         }
     }
     __syncthreads();
@@ -450,11 +476,10 @@ uint64_t skl_gemm_workspace_bytes(const skl_layer *L, uint32_t tokens)
 skl_status_t skl_launch_pack(const skl_layer *L, const uint16_t *X, skl_dtype_t x_dt, uint32_t ldx, uint32_t tokens,
                              const uint32_t *chan, const skl_gemm_step *steps, uint32_t n_steps, uint4 *Xp, hipStream_t stream)
 {
-    (void)L;
     skl_status_t st = allow_lds(k_pack_activations3, PK_LDS_BYTES);
     if (st != SKL_OK) return st;
     hipLaunchKernelGGL(k_pack_activations3, dim3((tokens + 31) / 32, (n_steps + PK_STEPS - 1) / PK_STEPS), dim3(SKL_WG), PK_LDS_BYTES,
-                       stream, X, (uint32_t)x_dt, ldx, tokens, chan, steps, n_steps, Xp);
+                       stream, X, (uint32_t)x_dt, ldx, tokens, L->in, chan, steps, n_steps, Xp);
     return check_launch("activation packing");
 }
 

@@ -82,10 +82,13 @@ def time_calls(torch, fn, steps, warmup, np=None):
 
 def measured_ceilings(torch, skl, dev, stream):
     """What the machine delivers to kernels of this library's kind: vector-ALU lane-instructions/s, conflict-free
-    16-byte LDS reads, f16 MFMA on registers, streaming HBM read (sketch_linear_microbench, median of 5 launches)."""
+    16-byte LDS reads, f16 MFMA on registers (two constant operand words; then operands of random bits, at
+    whose switching activity the chip lowers its clock), streaming HBM read (sketch_linear_microbench, median of
+    5 launches)."""
     ws = torch.empty((4 << 20) + (2 << 30), dtype=torch.uint8, device=dev)
     out = {}
-    for key, kind, iters in (("valu_lane_instr_per_s", 0, 1000), ("lds_bytes_per_s", 1, 1000), ("mfma_f16_flops_per_s", 2, 2000),
+    for key, kind, iters in (("valu_lane_instr_per_s", 0, 1000), ("lds_bytes_per_s", 1, 1000), ("mfma_f16_flops_per_s", 2, 20000),
+                             ("mfma_f16_random_operands_flops_per_s", 4, 20000),
                              ("hbm_read_bytes_per_s", 3, 1)):
         ts = []
         for _ in range(6):
@@ -535,6 +538,8 @@ def main():
                     "roofline": {"bound": "mfma", "achieved": flops / best / 1e6, "peak": MFMA_F16_PEAK / 1e12,
                                  "unit": "TFLOP/s", "frac": flops / best / 1e6 / (MFMA_F16_PEAK / 1e12),
                                  "frac_of_measured_ceiling": flops / (best * 1e-6) / ceilings["mfma_f16_flops_per_s"] if ceilings else None,
+                                 "frac_of_measured_ceiling_random_operands":
+                                     flops / (best * 1e-6) / ceilings["mfma_f16_random_operands_flops_per_s"] if ceilings else None,
                                  "traffic": measured_traffic(pmc) if pmc else None,
                                  "note": "time of the whole entry point of the faster kernel (activation re-ordering, weight "
                                          "rebuild, product, fix-up of shared tiles)"}})

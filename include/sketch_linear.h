@@ -270,11 +270,14 @@ SKL_API skl_status_t sketch_linear_gemm(const skl_layer_t *layer, const void *X,
  * of mu token tiles of one output-tile column, unit
  * u = output tile * (token tiles / mu) + token tile / mu to XCD u % 8; the
  * fused kernel has mu = 1, the staged kernel the largest mu that keeps the
- * XCDs balanced.
+ * XCDs balanced.  Tiles are 256 tokens high, except in staged calls whose
+ * 128-token tiles number between 225 and 256 (2048 tokens x 4096 outputs):
+ * there every workgroup takes one whole tile of 128 tokens and nothing is left
+ * over.
  * *n_segments receives the number of segments (also when it exceeds
  * `capacity`; then only the first `capacity` are written).  `shape` (HOST,
- * 5 words, may be NULL) receives workgroups per XCD, partial tiles per XCD,
- * slots per partial tile, the tile count, and mu. */
+ * 6 words, may be NULL) receives workgroups per XCD, partial tiles per XCD,
+ * slots per partial tile, the tile count, mu, and the tokens per tile. */
 SKL_API skl_status_t sketch_linear_prefill_split(uint32_t kernel, uint32_t out_features, uint32_t n_blocks,
                                          uint32_t tokens, uint32_t *segments, uint64_t capacity,
                                          uint64_t *n_segments, uint32_t *shape);
@@ -321,8 +324,12 @@ SKL_API skl_status_t sketch_linear_reconstruct_hash_op(const skl_layer_t *layer,
  *   kind 2  matrix cores: f16 MFMA 32x32x16 on registers, one wavefront per
  *           SIMD; *work = floating-point operations;
  *   kind 3  HBM: streaming read of the workspace past its first 4 MiB;
- *           *work = bytes read.
- * `iters` scales the work of kinds 0..2 (1..2^20; ignored for kind 3).
+ *           *work = bytes read;
+ *   kind 4  matrix cores as kind 2, but every MFMA takes other operand words
+ *           of random sign and mantissa bits (kind 2 multiplies two constant
+ *           words): the rate at the switching activity of real data, where the
+ *           chip runs below its top clock; *work = floating-point operations.
+ * `iters` scales the work of kinds 0..2 and 4 (1..2^20; ignored for kind 3).
  * workspace: DEVICE, 256-byte aligned, more than 4 MiB (kind 3: as much as
  * should be streamed; use several times the cache sizes).  Only enqueues;
  * time the launch with events on hip_stream. */

@@ -241,10 +241,10 @@ def sketch_linear_gemv_partials(layer: int, x: int, x_dtype: int, ldx: int, batc
 def sketch_linear_prefill_split(out_features: int, n_blocks: int, tokens: int, kernel: int = SKL_PREFILL_FUSED):
     """Host only.  Returns (segments, shape): segments is a list of 8-tuples (xcd, workgroup, token tile,
     output tile, first block, end block, whole, slot), shape is (workgroups per XCD, partial tiles per XCD,
-    slots per partial tile, tiles, token tiles per dealing unit)."""
+    slots per partial tile, tiles, token tiles per dealing unit, tokens per tile)."""
     L = load_library()
     n = ctypes.c_uint64(0)
-    shape = (ctypes.c_uint32 * 5)()
+    shape = (ctypes.c_uint32 * 6)()
     _check(L.sketch_linear_prefill_split(kernel, out_features, n_blocks, tokens, None, 0, ctypes.byref(n), shape))
     buf = (ctypes.c_uint32 * (8 * max(n.value, 1)))()
     _check(L.sketch_linear_prefill_split(kernel, out_features, n_blocks, tokens, buf, n.value, ctypes.byref(n), shape))

@@ -563,7 +563,7 @@ uint64_t skl_gemm3_segments(uint32_t out, uint32_t n_blocks, uint32_t tokens, bo
                             uint32_t *shape)
 {
     const G3Split sp = skl_make_split(out, n_blocks, tokens, grouped);
-    if (shape) { shape[0] = sp.gx; shape[1] = sp.l_max; shape[2] = sp.p_cap; shape[3] = sp.T; shape[4] = sp.mu; }
+    if (shape) { shape[0] = sp.gx; shape[1] = sp.l_max; shape[2] = sp.p_cap; shape[3] = sp.T; shape[4] = sp.mu; shape[5] = sp.mt; }
     uint64_t n = 0;
     for (uint32_t x = 0; x < 8; ++x)
         for (uint32_t wg = 0; wg < sp.gx; ++wg) {
@@ -1036,9 +1036,10 @@ skl_status_t sketch_linear_reconstruct_hash_op(const skl_layer_t *L, uint16_t *W
 
 skl_status_t sketch_linear_microbench(uint32_t kind, uint32_t iters, void *ws, uint64_t ws_bytes, void *stream, uint64_t *work)
 {
-    if (kind > 3) FAIL(SKL_ERR_INVALID_ARG, "kind = %u, must be 0 (vector ALU), 1 (LDS), 2 (matrix cores) or 3 (HBM read)", kind);
+    if (kind > 4)
+        FAIL(SKL_ERR_INVALID_ARG, "kind = %u, must be 0 (vector ALU), 1 (LDS), 2 (matrix cores), 3 (HBM read) or 4 (matrix cores, random operand bits)", kind);
     if (!ws || (uintptr_t)ws % 256) FAIL(SKL_ERR_INVALID_ARG, "workspace is NULL or not 256-byte aligned");
-    if (kind < 3 && (iters < 1 || iters > (1u << 20))) FAIL(SKL_ERR_INVALID_ARG, "iters = %u, must be 1..2^20", iters);
+    if (kind != 3 && (iters < 1 || iters > (1u << 20))) FAIL(SKL_ERR_INVALID_ARG, "iters = %u, must be 1..2^20", iters);
     if (!work) FAIL(SKL_ERR_INVALID_ARG, "work is NULL");
     const skl_status_t st = skl_launch_microbench(kind, iters, ws, ws_bytes, stream);
     if (st == SKL_OK) *work = skl_microbench_work(kind, iters, ws_bytes);

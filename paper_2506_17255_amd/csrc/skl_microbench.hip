@@ -4,7 +4,9 @@
 //      classes of the query and decode stages), no memory access;
 //   1  LDS gathers: 16-byte reads at lane-dependent addresses without bank conflicts;
 //   2  matrix cores: v_mfma_f32_32x32x16_f16 on registers only, one wavefront per SIMD;
-//   3  HBM: a streaming read of the workspace (16-byte loads, every byte once).
+//   3  HBM: a streaming read of the workspace (16-byte loads, every byte once);
+//   4  matrix cores as in 2, with operands of random sign and mantissa bits that change from one MFMA to
+//      the next: the switching activity of real data, at which the chip lowers its clock.
 // Each kernel runs `iters` rounds of a fixed amount of work per lane (stated in skl_microbench_work) and
 // leaves one value per lane in the workspace so that nothing is optimised away.
 #include "skl_device.h"
@@ -76,6 +78,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     out[blockIdx.x * blockDim.x + threadIdx.x] = __builtin_bit_cast(uint32_t, t);
 }
 
+// Kind 2 multiplies the same two operand words over and over.  Here every MFMA gets another pair out of
+// eight words of random bits (binary16 values in +-[0.5, 1)), so that the operand buses and the multiplier
+// arrays toggle as they do on real activations and weights.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_mb_mfma_random(uint32_t iters, uint32_t *out)
+{
+    float16v acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = (float16v){0.f};
+    uint4 a[8], b[8];
+    uint32_t h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    auto bits = [&]() { h ^= h << 13; h ^= h >> 17; h ^= h << 5; return (h & 0x83FF83FFu) | 0x38003800u; };
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = make_uint4(bits(), bits(), bits(), bits());
+        b[i] = make_uint4(bits(), bits(), bits(), bits());
+    }
+    for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < (int)MB_MFMA_PER_ROUND; ++r)
+            acc[r & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a[r & 7]),
+                                                               __builtin_bit_cast(half8v, b[(r + 3) & 7]), acc[r & 3], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t += acc[i][0] + acc[i][7];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = __builtin_bit_cast(uint32_t, t);
+}
+
 // grid-stride streaming read of n16 16-byte words
 __global__ __launch_bounds__(256) void k_mb_stream(const u32x4v *__restrict__ src, uint64_t n16, uint32_t *out)
 {
@@ -93,7 +123,8 @@ uint64_t skl_microbench_work(uint32_t kind, uint32_t iters, uint64_t ws_bytes)
     switch (kind) {
     case 0: return (uint64_t)SKL_N_CU * 4 * 1024 * iters * MB_VALU_PER_ROUND;                  // 4 workgroups of 1024 lanes per CU
     case 1: return (uint64_t)SKL_N_CU * 2 * 1024 * iters * MB_LDS_PER_ROUND * 16;              // 2 workgroups (64 KiB of LDS each) per CU
-    case 2: return (uint64_t)SKL_N_CU * 4 * iters * MB_MFMA_PER_ROUND * (2ull * 32 * 32 * 16); // one wavefront per SIMD
+    case 2:
+    case 4: return (uint64_t)SKL_N_CU * 4 * iters * MB_MFMA_PER_ROUND * (2ull * 32 * 32 * 16); // one wavefront per SIMD
     default: return (ws_bytes - MB_RESULT_BYTES) / 16 * 16;
     }
 }
@@ -117,6 +148,9 @@ skl_status_t skl_launch_microbench(uint32_t kind, uint32_t iters, void *ws, uint
         break;
     case 2:
         hipLaunchKernelGGL(k_mb_mfma, dim3(SKL_N_CU), dim3(256), 0, stream, iters, static_cast<uint32_t *>(ws));
+        break;
+    case 4:
+        hipLaunchKernelGGL(k_mb_mfma_random, dim3(SKL_N_CU), dim3(256), 0, stream, iters, static_cast<uint32_t *>(ws));
         break;
     default:
         hipLaunchKernelGGL(k_mb_stream, dim3(SKL_N_CU * 16), dim3(256), 0, stream,

@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const uint32_t xcd = blockIdx.x & 7, wg = blockIdx.x >> 3;
     G3Split sp;
     sp.T = p.T; sp.m_tiles = p.m_tiles; sp.nb = p.n_blocks; sp.gx = p.gx; sp.l_max = p.l_max; sp.p_cap = p.p_cap;
-    sp.mu = 1; sp.n_col = p.n_col;
+    sp.mu = 1; sp.n_col = p.n_col; sp.mt = GM_MT; sp.single = 0;
     uint32_t round = 0, u_next = sp.share_begin(xcd, wg);
     if (sp.rounds(xcd) == 0 && u_next >= sp.share_begin(xcd, wg + 1)) return;
     const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

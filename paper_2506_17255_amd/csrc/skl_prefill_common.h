@@ -107,8 +107,9 @@ __device__ __forceinline__ float acc_elem(float v)
     return r;
 }
 
-template <int DT>
-__device__ __forceinline__ void gemm3_store(const float16v (&acc)[16], void *Y, uint32_t ldy, uint32_t t0, uint32_t tokens,
+// RB: 32-row blocks per wavefront (2: 64 tokens x 256 outputs; 1: the half-height tiles of the staged kernel)
+template <int DT, int RB = 2>
+__device__ __forceinline__ void gemm3_store(const float16v (&acc)[8 * RB], void *Y, uint32_t ldy, uint32_t t0, uint32_t tokens,
                                             uint32_t o0, uint32_t out, uint32_t q)
 {
 #pragma unroll
@@ -116,7 +117,7 @@ __device__ __forceinline__ void gemm3_store(const float16v (&acc)[16], void *Y, 
         const uint32_t o = o0 + cb * 32;
         if (o >= out) continue;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const uint32_t t = t0 + rb * 32 + (i >> 2) * 8 + q * 4 + (i & 3);
@@ -137,8 +138,8 @@ __device__ __forceinline__ void gemm3_store(const float16v (&acc)[16], void *Y, 
 // whole 512-byte (1 KiB for float32) rows of Y instead of 2-byte elements.  Needs 16-byte aligned rows.
 #define G3_EPI_BYTES 16896u             // per wavefront: 32 rows x (512 + 16) bytes, or 16 rows x (1024 + 16)
 static_assert(4 * G3_EPI_BYTES <= 2 * G3_SLOT_BYTES + 1024, "the epilogue areas must end below the block metadata");
-template <int DT>
-__device__ __forceinline__ void gemm3_store_rows(const float16v (&acc)[16], uint32_t lds_wave, void *Y, uint32_t ldy,
+template <int DT, int RB = 2>
+__device__ __forceinline__ void gemm3_store_rows(const float16v (&acc)[8 * RB], uint32_t lds_wave, void *Y, uint32_t ldy,
                                                  uint32_t t0, uint32_t tokens, uint32_t o_tile, uint32_t out, uint32_t lane)
 {
     constexpr uint32_t ES = DT == SKL_F32 ? 4 : 2;
@@ -147,7 +148,7 @@ __device__ __forceinline__ void gemm3_store_rows(const float16v (&acc)[16], uint
     constexpr uint32_t ROWS = 32 / GROUPS, CH = 256 * ES / 16;  // rows per group, 16-byte pieces per row
     const uint32_t n = lane & 31, q = lane >> 5;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int gr = 0; gr < GROUPS; ++gr) {
 #pragma unroll

@@ -91,6 +91,8 @@ struct StagedArgs {
     G3Split sp;
 };
 
+// RB: 32-token row blocks per wavefront: 2 (256 x 256 tiles) or 1 (128 x 256 tiles, the single-round mode of the split)
+template <int RB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_staged_gemm(StagedArgs p)
 {
     const uint32_t xcd = blockIdx.x & 7, wg = blockIdx.x >> 3;
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // where this lane's eight copied words go inside a slot (+ 64 i); native vectors, so that the words in flight stay in registers
     u32x4v *const copy_w = reinterpret_cast<u32x4v *>(smem) + wave * 512 + lane;
     const uint32_t last_kb = p.KB - 1;
-    float16v acc[16];                                           // [row block][column block]
+    float16v acc[8 * RB];                                       // [row block][column block]
     for (;;) {
         G3Split::Seg sg;
         if (!sp.next(xcd, wg, round, u_next, sg)) break;
@@ -113,23 +115,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const size_t part_slot = sg.part_slot;
         uint32_t tile_m, tile_n;
         sp.tile_of(xcd, sg.k, tile_m, tile_n);
-        const uint32_t t0 = tile_m * GM_MT + wave * 64;
+        const uint32_t t0 = tile_m * (128 * RB) + wave * (32 * RB);
         const uint32_t o_tile = (p.tile0 + tile_n) * GM3_NT;        // first output of the tile in the layer
-        const uint4 *xa = p.Xp + ((size_t)tile_m * p.KB * 32 + wave * 2) * 64 + lane;          // step st: + 512 st; second row block: + 64
+        // activation words of the wavefront's first row block (step st: + 512 st; second row block: + 64); the
+        // words are laid out by 256-token tiles of eight row blocks, a half-height tile is four of them
+        const uint4 *xa = RB == 2 ? p.Xp + ((size_t)tile_m * p.KB * 32 + wave * 2) * 64 + lane
+                                  : p.Xp + ((size_t)(tile_m >> 1) * p.KB * 32 + (tile_m & 1) * 4 + wave) * 64 + lane;
         const u32x4v *wb = reinterpret_cast<const u32x4v *>(p.Wp) + (size_t)tile_n * p.KB * SG_SLOT_WORDS + wave * 512 + lane;    // block kb: + 2048 kb; word i: + 64 i
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = (float16v){0.f};
-        uint4 a[4][2];
+        for (int i = 0; i < 8 * RB; ++i) acc[i] = (float16v){0.f};
+        uint4 a[4][RB];
         u32x4v tb[8];
         {
             const u32x4v *w0 = wb + (size_t)k0 * SG_SLOT_WORDS;
 #pragma unroll
             for (int i = 0; i < 8; ++i) tb[i] = w0[i * 64];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                a[s][0] = xa[(size_t)(k0 * 4 + s) * 512];
-                a[s][1] = xa[(size_t)(k0 * 4 + s) * 512 + 64];
-            }
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int r = 0; r < RB; ++r) a[s][r] = xa[(size_t)(k0 * 4 + s) * 512 + r * 64];
             u32x4v *dst = copy_w + (k0 & 1) * SG_SLOT_WORDS;
 #pragma unroll
             for (int i = 0; i < 8; ++i) dst[i * 64] = tb[i];
@@ -151,10 +155,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int cb = 0; cb < 8; ++cb) {
-                    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                        __builtin_bit_cast(half8v, a[s][0]), __builtin_bit_cast(half8v, bw[cb]), acc[cb], 0, 0, 0);
-                    acc[8 + cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                        __builtin_bit_cast(half8v, a[s][1]), __builtin_bit_cast(half8v, bw[cb]), acc[8 + cb], 0, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < RB; ++r)
+                        acc[8 * r + cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                            __builtin_bit_cast(half8v, a[s][r]), __builtin_bit_cast(half8v, bw[cb]), acc[8 * r + cb], 0, 0, 0);
                     if (s < 3) bw[cb] = lds_word_at(baddr + cb * 4096 + (s + 1) * 1024);
                     if (cb == 3) {                  // two of the next block's weight words into the other slot, their successors requested
                         nxt[(2 * s) * 64] = tb[2 * s];
@@ -167,8 +171,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 // next block's activation words into the registers just used
-                a[s][0] = xn[s * 512];
-                a[s][1] = xn[s * 512 + 64];
+#pragma unroll
+                for (int r = 0; r < RB; ++r) a[s][r] = xn[s * 512 + r * 64];
             }
             __syncthreads();                                    // everyone is done with this block's slot; the other one is complete
         }
@@ -178,15 +182,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(ln));       // also: the last MFMA has left the pipeline
         if (whole && p.rows_aligned) {
             const uint32_t lw = lds0 + wave * G3_EPI_BYTES;
-            if (p.y_dt == SKL_F32) gemm3_store_rows<SKL_F32>(acc, lw, p.Y, p.ldy, t0, p.tokens, o_tile, p.out, ln);
-            else if (p.y_dt == SKL_F16) gemm3_store_rows<SKL_F16>(acc, lw, p.Y, p.ldy, t0, p.tokens, o_tile, p.out, ln);
-            else gemm3_store_rows<SKL_BF16>(acc, lw, p.Y, p.ldy, t0, p.tokens, o_tile, p.out, ln);
+            if (p.y_dt == SKL_F32) gemm3_store_rows<SKL_F32, RB>(acc, lw, p.Y, p.ldy, t0, p.tokens, o_tile, p.out, ln);
+            else if (p.y_dt == SKL_F16) gemm3_store_rows<SKL_F16, RB>(acc, lw, p.Y, p.ldy, t0, p.tokens, o_tile, p.out, ln);
+            else gemm3_store_rows<SKL_BF16, RB>(acc, lw, p.Y, p.ldy, t0, p.tokens, o_tile, p.out, ln);
         } else if (whole) {
             const uint32_t ne = ln & 31, qe = ln >> 5;
-            if (p.y_dt == SKL_F32) gemm3_store<SKL_F32>(acc, p.Y, p.ldy, t0, p.tokens, o_tile + ne, p.out, qe);
-            else if (p.y_dt == SKL_F16) gemm3_store<SKL_F16>(acc, p.Y, p.ldy, t0, p.tokens, o_tile + ne, p.out, qe);
-            else gemm3_store<SKL_BF16>(acc, p.Y, p.ldy, t0, p.tokens, o_tile + ne, p.out, qe);
-        } else {
+            if (p.y_dt == SKL_F32) gemm3_store<SKL_F32, RB>(acc, p.Y, p.ldy, t0, p.tokens, o_tile + ne, p.out, qe);
+            else if (p.y_dt == SKL_F16) gemm3_store<SKL_F16, RB>(acc, p.Y, p.ldy, t0, p.tokens, o_tile + ne, p.out, qe);
+            else gemm3_store<SKL_BF16, RB>(acc, p.Y, p.ldy, t0, p.tokens, o_tile + ne, p.out, qe);
+        } else if constexpr (RB == 2) {         // (the single-round mode of the half-height tiles has no partial tiles)
             // partial tile: [wavefront][accumulator block][4 elements][lane], whole 1 KiB rows per store
             float4 *dst = reinterpret_cast<float4 *>(p.parts + part_slot * G3_SLOT_FLOATS) + (size_t)wave * 4096 + ln;
 #pragma unroll
@@ -284,9 +288,15 @@ skl_status_t skl_launch_gemm_staged(const skl_layer *L, const TableSrc &src, con
         g.rows_aligned = ((size_t)ldy * (y_dt == SKL_F32 ? 4 : 2)) % 16 == 0;
         g.tile0 = tile0;
         g.sp = skl_make_split(cols * GM3_NT, KB, tokens, true);
-        st = allow_lds(k_staged_gemm, SG_LDS_BYTES);
-        if (st != SKL_OK) return st;
-        hipLaunchKernelGGL(k_staged_gemm, dim3(8 * g.sp.gx), dim3(256), SG_LDS_BYTES, stream, g);
+        if (g.sp.mt == GM_MT) {
+            st = allow_lds(k_staged_gemm<2>, SG_LDS_BYTES);
+            if (st != SKL_OK) return st;
+            hipLaunchKernelGGL(k_staged_gemm<2>, dim3(8 * g.sp.gx), dim3(256), SG_LDS_BYTES, stream, g);
+        } else {
+            st = allow_lds(k_staged_gemm<1>, SG_LDS_BYTES);
+            if (st != SKL_OK) return st;
+            hipLaunchKernelGGL(k_staged_gemm<1>, dim3(8 * g.sp.gx), dim3(256), SG_LDS_BYTES, stream, g);
+        }
         st = check_launch("staged gemm");
         if (st != SKL_OK) return st;
         if (g.sp.l_max) {

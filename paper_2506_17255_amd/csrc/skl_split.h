@@ -38,6 +38,8 @@ struct G3Split {
     uint32_t T, m_tiles, nb, gx;        // tiles, token tiles, blocks per tile, workgroups per XCD
     uint32_t l_max, p_cap;              // workspace slots: [xcd][l_max leftover tiles][p_cap parts]
     uint32_t mu, n_col;                 // token tiles per dealing unit; output tile columns
+    uint32_t mt;                        // tokens per tile: GM_MT, or GM_MT / 2 in the single-round mode below
+    uint32_t single;                    // every workgroup takes at most one whole tile: no leftovers, no partials
     __host__ __device__ uint32_t tiles_of(uint32_t x) const
     {
         const uint32_t U = n_col * (m_tiles / mu);
@@ -50,8 +52,8 @@ struct G3Split {
         tile_n = u / n_mg;
         tile_m = (u % n_mg) * mu + k % mu;
     }
-    __host__ __device__ uint32_t rounds(uint32_t x) const { return tiles_of(x) / gx; }
-    __host__ __device__ uint32_t left(uint32_t x) const { return tiles_of(x) - rounds(x) * gx; }
+    __host__ __device__ uint32_t rounds(uint32_t x) const { return single ? 1 : tiles_of(x) / gx; }
+    __host__ __device__ uint32_t left(uint32_t x) const { return single ? 0 : tiles_of(x) - rounds(x) * gx; }
     __host__ __device__ uint32_t units(uint32_t x) const { return left(x) * nb; }
     // workgroups that take a share of the leftover units: every share holds at least one unit
     __host__ __device__ uint32_t sharers(uint32_t x) const { const uint32_t u = units(x); return u < gx ? u : gx; }
@@ -75,6 +77,7 @@ struct G3Split {
         const uint32_t n_rounds = rounds(x), u_end = share_begin(x, wg + 1);
         sg.part_slot = 0;
         if (round < n_rounds) {
+            if (single && wg >= tiles_of(x)) return false;
             sg.k = wg + round * gx; sg.k0 = 0; sg.k1 = nb; sg.whole = 1;
             ++round;
             return true;
@@ -101,21 +104,42 @@ struct G3Split {
 static inline G3Split skl_make_split(uint32_t out, uint32_t nb, uint32_t tokens, bool grouped)
 {
     G3Split sp;
-    sp.m_tiles = (tokens + GM_MT - 1) / GM_MT;
     sp.n_col = (out + GM3_NT - 1) / GM3_NT;
-    sp.T = sp.m_tiles * sp.n_col;
     sp.nb = nb;
-    sp.mu = 1;
-    sp.gx = 1; sp.l_max = 0; sp.p_cap = 0;
     auto most = [&]() { uint32_t m = 0; for (uint32_t x = 0; x < 8; ++x) m = std::max(m, sp.tiles_of(x)); return m; };
+    auto deal = [&](uint32_t mt) {
+        sp.mt = mt;
+        sp.m_tiles = (tokens + mt - 1) / mt;
+        sp.T = sp.m_tiles * sp.n_col;
+        sp.mu = 1;
+        if (grouped) {
+            const uint32_t best = (sp.T + 7) / 8;               // tiles of the busiest XCD when dealt one by one
+            for (uint32_t mu = sp.m_tiles; mu >= 1; mu /= 2) {
+                if (sp.m_tiles % mu) continue;
+                sp.mu = mu;
+                if (most() * 100 <= best * 103) break;
+            }
+        }
+    };
+    sp.single = 0;
+    sp.gx = 1; sp.l_max = 0; sp.p_cap = 0;
+    // Staged kernel, calls whose tiles of half the height (128 tokens: 32 per wavefront instead of 64) fill
+    // at least seven eighths of the CUs exactly once: every workgroup multiplies one whole such tile.  With
+    // full-height tiles these calls have fewer tiles than CUs, so that every tile would be shared by two
+    // workgroups, written as float32 partials and passed through the fix-up.  (A block of a half-height
+    // tile takes 0.55 of the time of a full-height one, measured; below 225 tiles sharing is faster.)
     if (grouped) {
-        const uint32_t best = (sp.T + 7) / 8;                   // tiles of the busiest XCD when dealt one by one
-        for (uint32_t mu = sp.m_tiles; mu >= 1; mu /= 2) {
-            if (sp.m_tiles % mu) continue;
-            sp.mu = mu;
-            if (most() * 100 <= best * 103) break;
+        const uint32_t t_half = ((tokens + GM_MT / 2 - 1) / (GM_MT / 2)) * sp.n_col;
+        if (t_half > 224 && t_half <= 256) {
+            deal(GM_MT / 2);
+            if (most() <= 32) {
+                sp.single = 1;
+                sp.gx = 32;
+                return sp;
+            }
         }
     }
+    deal(GM_MT);
     sp.gx = (uint32_t)std::min<uint64_t>(32, std::max<uint64_t>(1, (uint64_t)most() * nb / 4));
     for (uint32_t x = 0; x < 8; ++x) {
         sp.l_max = std::max(sp.l_max, sp.left(x));
@@ -123,4 +147,3 @@ static inline G3Split skl_make_split(uint32_t out, uint32_t nb, uint32_t tokens,
     }
     return sp;
 }
-

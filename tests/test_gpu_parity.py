@@ -296,6 +296,41 @@ def test_gemm_with_fewer_blocks_than_workgroups_and_a_dirty_workspace(flags):
     assert rel_fro(ybf, round_to_bf16(ref)) <= TOL
 
 
+def test_gemm_with_one_half_height_tile_per_workgroup():
+    """Calls whose 128-token tiles number between 225 and 256 (here 58 token tiles x 4 output-tile columns,
+    both ragged; 160 channels are three channel blocks, the last one partly filled) take the staged
+    kernel's single-round mode: one whole tile per workgroup, no partials, no fix-up pass.  The workspace
+    starts full of NaN patterns."""
+    widths = np.array([30] * 120 + [140] * 40)
+    np.random.default_rng(5).shuffle(widths)
+    W, sk = custom_layer("half_tiles", 160, 1000, 1, 1000, 4, widths, 23)
+    W_hat = oracle.query(sk)
+    tokens = 128 * 58 - 37
+    segs, shape = skl.sketch_linear_prefill_split(1000, 3, tokens, skl.SKL_PREFILL_STAGED)
+    assert shape[5] == 128 and shape[3] == 232
+    rng = np.random.default_rng(81)
+    Xb = wk.f32_to_bf16_bits(rng.standard_normal((tokens, 160)).astype(np.float32))
+    ref = oracle.linear(W_hat, Xb, x_kind="bf16")
+    with GpuLayer(sk, skl.FLAG_STAGED_PREFILL) as g:
+        ws, need = g.workspace(1, tokens)
+        ws.fill_(0xFF)
+        y32 = g.gemm(Xb, "bf16", "f32")
+        ws.fill_(0xFF)
+        y32_odd = g.gemm(Xb, "bf16", "f32", ldx=163, ldy=1003)
+        ybf = g.gemm(Xb, "bf16", "bf16")
+        ybf_odd = g.gemm(Xb, "bf16", "bf16", ldy=1005)
+        y16 = g.gemm(Xb, "bf16", "f16", ldy=1008)
+        again = g.gemm(Xb, "bf16", "f32")
+    with GpuLayer(sk, skl.FLAG_FUSED_PREFILL) as g:
+        y_fused = g.gemm(Xb, "bf16", "f32")
+    assert rel_fro(y32, ref) <= 1e-5, rel_fro(y32, ref)
+    assert np.array_equal(y32, y32_odd) and np.array_equal(y32, again)
+    assert np.array_equal(ybf, ybf_odd)
+    assert rel_fro(ybf, round_to_bf16(ref)) <= TOL
+    assert rel_fro(y16, ref) <= TOL
+    assert rel_fro(y_fused, ref) <= 1e-5
+
+
 def test_gemm_row_equals_gemv():
     W, sk = small_case("row_classes")
     rng = np.random.default_rng(5)
@@ -755,3 +790,28 @@ def test_a_layer_created_from_its_file_image_is_the_same_layer(name, bits, mode)
         assert g.info == direct.info
         assert np.array_equal(g.reconstruct(), want)
         assert np.array_equal(g.gemv(x, "f32"), direct.gemv(x, "f32"))
+
+
+def test_ceiling_kernels_run_and_report_their_work():
+    """The five small kernels behind the measured ceilings of the benchmark: each launches, finishes and
+    reports a positive amount of work; the matrix-core rate with operands of random bits is a real rate
+    (positive, not above the constant-operand one by more than measurement noise)."""
+    import torch
+    dev = torch.device("cuda:0")
+    ws = torch.empty((4 << 20) + (64 << 20), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    rate = {}
+    for kind in range(5):
+        iters = 200 if kind < 2 else 4000
+        ts = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            work = skl.sketch_linear_microbench(kind, iters, ws.data_ptr(), ws.numel(), stream)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e-3)
+        assert work > 0
+        rate[kind] = work / min(ts)
+    assert rate[2] > 1e14 and rate[4] > 1e14
+    assert rate[4] <= 1.1 * rate[2]

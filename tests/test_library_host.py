@@ -221,3 +221,17 @@ def test_grouped_decode_null_arguments():
     assert L.sketch_linear_gemv_group_workspace_bytes(one, 0, 1, ctypes.byref(n)) == skl.SKL_ERR_INVALID_ARG
     assert L.sketch_linear_gemv_group(one, 1, None, 0, 0, one, 0, 0, 1, None, 0, None) == skl.SKL_ERR_INVALID_ARG
     assert L.sketch_linear_gemv_gate_up(None, None, None, 0, 0, None, 0, 0, 1, None, 0, None) == skl.SKL_ERR_INVALID_ARG
+
+
+def test_microbench_argument_checks():
+    """The ceiling kernels (kinds 0..4) check their arguments before anything is launched."""
+    L = skl.load_library()
+    work = ctypes.c_uint64(0)
+    fake = ctypes.c_void_p(256)                 # aligned, never dereferenced by the checks
+    assert L.sketch_linear_microbench(5, 10, fake, 1 << 23, None, ctypes.byref(work)) == skl.SKL_ERR_INVALID_ARG
+    assert b"kind" in L.sketch_linear_last_error()
+    assert L.sketch_linear_microbench(4, 10, None, 1 << 23, None, ctypes.byref(work)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_microbench(4, 10, ctypes.c_void_p(264), 1 << 23, None, ctypes.byref(work)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_microbench(4, 0, fake, 1 << 23, None, ctypes.byref(work)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_microbench(2, (1 << 20) + 1, fake, 1 << 23, None, ctypes.byref(work)) == skl.SKL_ERR_INVALID_ARG
+    assert L.sketch_linear_microbench(4, 10, fake, 1 << 23, None, None) == skl.SKL_ERR_INVALID_ARG

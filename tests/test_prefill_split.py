@@ -21,8 +21,8 @@ def split(out_features, n_blocks, tokens, kernel=skl.SKL_PREFILL_FUSED):
     return segs, shape
 
 
-def m_tiles_of(tokens):
-    return (tokens + 255) // 256
+def m_tiles_of(tokens, mt=256):
+    return (tokens + mt - 1) // mt
 
 
 def tiles_of_xcd(mu, xcd, n_tiles, m_tiles):
@@ -47,7 +47,10 @@ def index_on_xcd(mu, tm, tn, m_tiles):
 
 SHAPES = [
     (11008, 64, 2048),    # the benchmark layer: 344 tiles on 256 workgroups
-    (4096, 64, 2048),     # fewer tiles than workgroups: every tile is shared
+    (4096, 64, 2048),     # fewer tiles than workgroups (staged kernel: one half-height tile per workgroup)
+    (4096, 64, 1900),     # the same with a ragged last token tile
+    (3840, 64, 2048),     # 240 half-height tiles
+    (3584, 64, 2048),     # 224 half-height tiles: full-height tiles again
     (4096, 172, 2048),    # the down projection's block count
     (28672, 128, 2048),   # 896 tiles: three whole rounds and a leftover
     (256, 1, 1),          # a single tile of a single block
@@ -62,8 +65,9 @@ SHAPES = [
 @pytest.mark.parametrize("kernel", KERNELS)
 @pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES)
 def test_every_block_of_every_tile_is_multiplied_once(out_features, n_blocks, tokens, kernel):
-    segs, (gx, l_max, p_cap, n_tiles, mu) = split(out_features, n_blocks, tokens, kernel)
-    m_tiles = (tokens + 255) // 256
+    segs, (gx, l_max, p_cap, n_tiles, mu, mt) = split(out_features, n_blocks, tokens, kernel)
+    assert mt in (128, 256) and (mt == 256 or kernel == skl.SKL_PREFILL_STAGED)
+    m_tiles = m_tiles_of(tokens, mt)
     n_col = (out_features + 255) // 256
     assert n_tiles == m_tiles * n_col
     seen = {}
@@ -75,6 +79,9 @@ def test_every_block_of_every_tile_is_multiplied_once(out_features, n_blocks, to
         # leaves a partial for the fix-up pass, also a share that happens to cover the tile
         tiles_of = tiles_of_xcd(mu, xcd, n_tiles, m_tiles)
         in_round = index_on_xcd(mu, tm, tn, m_tiles) < (tiles_of // gx) * gx
+        if mt == 128:                   # half-height tiles: one whole tile per workgroup, nothing left over
+            assert tiles_of <= gx == 32 and l_max == 0
+            in_round = True
         assert whole == int(in_round)
         if in_round:
             assert k0 == 0 and k1 == n_blocks
@@ -88,7 +95,7 @@ def test_every_block_of_every_tile_is_multiplied_once(out_features, n_blocks, to
 @pytest.mark.parametrize("kernel", KERNELS)
 @pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES)
 def test_partial_slots_are_distinct_dense_and_in_workgroup_order(out_features, n_blocks, tokens, kernel):
-    segs, (gx, l_max, p_cap, n_tiles, mu) = split(out_features, n_blocks, tokens, kernel)
+    segs, (gx, l_max, p_cap, n_tiles, mu, mt) = split(out_features, n_blocks, tokens, kernel)
     by_tile = {}
     slots = set()
     for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
@@ -115,7 +122,7 @@ def test_partial_slots_are_distinct_dense_and_in_workgroup_order(out_features, n
 @pytest.mark.parametrize("kernel", KERNELS)
 @pytest.mark.parametrize("out_features,n_blocks,tokens", SHAPES)
 def test_workgroups_get_equal_work(out_features, n_blocks, tokens, kernel):
-    segs, (gx, l_max, p_cap, n_tiles, mu) = split(out_features, n_blocks, tokens, kernel)
+    segs, (gx, l_max, p_cap, n_tiles, mu, mt) = split(out_features, n_blocks, tokens, kernel)
     load = {}
     for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
         load[(xcd, wg)] = load.get((xcd, wg), 0) + k1 - k0
@@ -129,10 +136,12 @@ def test_workgroups_get_equal_work(out_features, n_blocks, tokens, kernel):
     assert total == n_tiles * n_blocks
     if kernel == skl.SKL_PREFILL_FUSED:
         assert mu == 1
-    assert m_tiles_of(tokens) % mu == 0
+    assert m_tiles_of(tokens, mt) % mu == 0
     # the busiest workgroup is close to the ideal share when there is enough work to go round (the staged
     # kernel's dealing units are chosen so that the busiest XCD stays within 3 % of dealing single tiles)
-    if total >= 8 * gx * 8:
+    if mt == 128:
+        assert max(load.values()) == n_blocks               # one whole tile each
+    elif total >= 8 * gx * 8:
         assert max(load.values()) <= total / (8 * gx) + n_blocks / 8 + 1
 
 
@@ -140,7 +149,7 @@ def test_workgroups_get_equal_work(out_features, n_blocks, tokens, kernel):
 def test_small_exhaustive_sweep(kernel):
     for n_tiles_out, n_blocks, tokens in itertools.product(range(1, 41), (1, 2, 5, 31, 64), (1, 256, 257, 2048)):
         out_features = 256 * n_tiles_out - 3
-        segs, (gx, l_max, p_cap, n_tiles, mu) = split(out_features, n_blocks, tokens, kernel)
+        segs, (gx, l_max, p_cap, n_tiles, mu, mt) = split(out_features, n_blocks, tokens, kernel)
         covered = sum(k1 - k0 for *_, k0, k1, _, _ in segs)
         assert covered == n_tiles * n_blocks
         keys = set()
@@ -152,7 +161,10 @@ def test_small_exhaustive_sweep(kernel):
 
 def leftover_tiles(shape, tokens, kernel):
     """(xcd, l, token tile, output tile) of every tile the fix-up pass finishes."""
-    gx, l_max, p_cap, n_tiles, mu = shape
+    gx, l_max, p_cap, n_tiles, mu, mt = shape
+    if mt == 128:                       # one whole half-height tile per workgroup: nothing for the fix-up pass
+        assert l_max == 0
+        return
     m_tiles = (tokens + 255) // 256
     n_mg = m_tiles // mu
     for xcd in range(8):
@@ -168,7 +180,7 @@ def check_fixup_reads_only_written_slots(out_features, n_blocks, tokens, kernel=
     """The fix-up pass adds slots [base, base + parts) of every leftover tile: each must have been written
     by a partial segment of that tile, and whole-tile segments never belong to a leftover tile."""
     segs, shape = split(out_features, n_blocks, tokens, kernel)
-    gx, l_max, p_cap, n_tiles, mu = shape
+    gx, l_max, p_cap, n_tiles, mu, mt = shape
     written = {}
     for xcd, wg, tm, tn, k0, k1, whole, slot in segs:
         if not whole:
@@ -198,6 +210,21 @@ def test_fixup_slots_with_few_blocks(kernel):
         for n_tiles_out in (1, 2, 7, 19, 31, 57, 64):
             for tokens in (256, 768, 2048):
                 check_fixup_reads_only_written_slots(256 * n_tiles_out, n_blocks, tokens, kernel)
+
+
+def test_half_height_tiles_are_used_where_they_fill_the_chip_once():
+    S = skl.SKL_PREFILL_STAGED
+    for out_features, tokens, want in [(4096, 2048, 128), (4096, 1900, 128), (3840, 2048, 128), (3584, 2048, 256),
+                                        (4352, 2048, 256), (11008, 2048, 256), (8192, 1024, 128), (8192, 1000, 128),
+                                        (16384, 512, 128), (4096, 4096, 256), (4096, 1024, 256)]:
+        segs, (gx, l_max, p_cap, n_tiles, mu, mt) = split(out_features, 64, tokens, S)
+        assert mt == want, (out_features, tokens)
+        if mt == 128:
+            assert gx == 32 and l_max == 0 and p_cap == 0
+            assert len(segs) == n_tiles and all(s[6] == 1 for s in segs)
+            assert len({(s[0], s[1]) for s in segs}) == n_tiles     # one tile per workgroup
+    segs, shape = split(4096, 64, 2048, skl.SKL_PREFILL_FUSED)
+    assert shape[5] == 256
 
 
 def test_argument_errors():

@@ -479,8 +479,10 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="decode GEMV at batch 1 only (for profiling runs)")
-    ap.add_argument("--prefill-only", action="store_true", help="prefill GEMM 4096x11008 only (for profiling runs)")
+    ap.add_argument("--prefill-only", action="store_true", help="prefill GEMM of one layer only (for profiling runs)")
     ap.add_argument("--bpw", type=float, default=0.5, help="bits per weight of the --prefill-only layer (0.5 or 0.75)")
+    ap.add_argument("--out-features", type=int, choices=(4096, 11008), default=11008,
+                    help="output features of the --prefill-only layer (4096: one 128-token tile per workgroup)")
     ap.add_argument("--prefill-kernel", choices=("by_call", "fused"), default="by_call",
                     help="kernel of the --prefill-only run: the library's choice (staged at 2048 tokens) or the fused one")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
@@ -565,8 +567,8 @@ def main():
                           "stack_layer_wise_importance": stack_mixed_bpw(torch, np, skl, wk, _oracle, GpuLayer, dev, stream)}))
         return
     if args.prefill_only:
-        print(json.dumps({"prefill_2048_tokens": {"4096x11008": prefill(11008, max(args.steps // 10, 5), 3, bpw=args.bpw,
-                                                                        kernels=(args.prefill_kernel,))}}))
+        print(json.dumps({"prefill_2048_tokens": {f"4096x{args.out_features}": prefill(args.out_features, max(args.steps // 10, 5), 3,
+                                                                                       bpw=args.bpw, kernels=(args.prefill_kernel,))}}))
         if args.calib_copy:
             calib_copy()
         return

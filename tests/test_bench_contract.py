@@ -21,5 +21,5 @@ def test_documented_flags_exist():
     r = run("--help")
     assert r.returncode == 0
     for flag in ("--gpus", "--steps", "--warmup", "--quick", "--prefill-only", "--stack-only", "--low-bit-only",
-                 "--no-cpu", "--calib-copy", "--prefill-kernel"):
+                 "--no-cpu", "--calib-copy", "--prefill-kernel", "--out-features"):
         assert flag in r.stdout

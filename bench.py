@@ -80,6 +80,41 @@ def time_calls(torch, fn, steps, warmup, np=None):
             "p90_us": float(numpy.percentile(per, 90)), "wall_us": wall * 1e6, "calls": steps}
 
 
+def sclk_while_running(torch, fn, seconds=1.5):
+    """Shader clock as `rocm-smi --showclocks` reports it while `fn` runs back to back (the tool runs as a child
+    process and reads the driver's files; it touches no HIP state).  None where the tool is missing or prints
+    something else: the figure is context for the timings, never an input to them."""
+    import re
+    import subprocess
+    import threading
+    stop, seen = threading.Event(), []
+
+    def sample():
+        while not stop.is_set():
+            try:
+                r = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=10)
+                card = next(iter(json.loads(r.stdout).values()))
+                for k, v in card.items():
+                    m = re.search(r"(\d+)\s*mhz", str(v), re.I)
+                    if k.lower().startswith("sclk clock speed") and m:
+                        seen.append(int(m.group(1)))
+            except Exception:
+                return
+            time.sleep(0.2)
+
+    th = threading.Thread(target=sample, daemon=True)
+    th.start()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+    stop.set()
+    th.join(timeout=15)
+    seen = seen[1:] if len(seen) > 2 else seen      # the first sample may predate the load
+    return {"sclk_mhz_median": sorted(seen)[len(seen) // 2], "sclk_mhz_min": min(seen), "samples": len(seen)} if seen else None
+
+
 def measured_ceilings(torch, skl, dev, stream):
     """What the machine delivers to kernels of this library's kind: vector-ALU lane-instructions/s, conflict-free
     16-byte LDS reads, f16 MFMA on registers (two constant operand words; then operands of random bits, at
@@ -519,6 +554,7 @@ def main():
         Y = torch.empty(wl4.tokens, out_f, dtype=torch.bfloat16, device=dev)
         flops = 2.0 * wl4.tokens * wl4.in_features * out_f
         res = {}
+        clock = None
         for kern in kernels:
             g4 = GpuLayer(sk4, skl.FLAG_FUSED_PREFILL if kern == "fused" else 0)
             need = skl.sketch_linear_workspace_bytes(g4.handle, 1, wl4.tokens)
@@ -528,6 +564,8 @@ def main():
             t = time_calls(torch, lambda: skl.sketch_linear_gemm(*a4), steps, warmup)
             staged = g4.info["prefill_staged_from"] <= wl4.tokens
             res["staged" if staged else "fused"] = dict(t, tflops=flops / t["mean_us"] / 1e6, workspace_MB=need / 1e6)
+            if full_run and kern == "by_call" and out_f == 11008 and bpw == 0.5:
+                clock = sclk_while_running(torch, lambda: skl.sketch_linear_gemm(*a4))
             g4.close()
             del ws
         Xd = X.view(torch.bfloat16)
@@ -536,6 +574,7 @@ def main():
         best = min(v["mean_us"] for v in res.values())
         pmc = "gemm_staged_4096x11008_t2048_pmc.txt" if out_f == 11008 and bpw == 0.5 else None
         res.update({"sketch_us": best, "tflops": flops / best / 1e6, "dense_bf16_us": td["mean_us"], "dense_bf16": td,
+                    "clock_under_load": clock,
                     "dense_tflops": flops / td["mean_us"] / 1e6, "speedup_vs_dense": td["mean_us"] / best,
                     "roofline": {"bound": "mfma", "achieved": flops / best / 1e6, "peak": MFMA_F16_PEAK / 1e12,
                                  "unit": "TFLOP/s", "frac": flops / best / 1e6 / (MFMA_F16_PEAK / 1e12),
@@ -639,6 +678,7 @@ def main():
                              "of LDS gathers per weight; issued instructions per weight and stall shares are in "
                              "profiles/gemv_row_4096x11008_b1_counters.txt"},
         "ceilings": ceilings,
+        "clock_under_load": sclk_while_running(torch, fn1) if full_run else None,
     }
 
     if not args.quick:

@@ -435,11 +435,7 @@ __device__ __forceinline__ void gn_run(const StreamArgs &p, const StreamCtx &c, 
     uint32_t K_prev = 0;
     const uint32_t rs_run = w.rs;
     const bool x_live = NB >= 4 || (w.lane >> 4) < (uint32_t)NB;
-    auto copy_next = [&](uint4 *dst, const uint4 *src, uint32_t n16) {
-        const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-        for (uint32_t base = wave * 64; base < n16; base += 64 * nw)
-            if (base + lane < n16) lds_dma_16(src + base + lane, dst + base);
-    };
+    auto copy_next = [&](uint4 *dst, const uint4 *src, uint32_t n16) { copy_words_to_lds_async(dst, src, n16, nw); };
     auto step = [&](auto bo_tag) {
         constexpr uint32_t BO = decltype(bo_tag)::value;
         uint4 *nxt = BO || !c.two_bufs ? buf0 : buf1;
@@ -497,11 +493,7 @@ __device__ __forceinline__ void gemvN_body(const StreamArgs &p, const uint16_t *
     w.nblk = min(c.b_hi - c.b_lo, (uint32_t)SKL_MAX_GROUP_BLOCKS);
     w.sm_meta = sm_meta;
     w.xs_addr = (uint32_t)(uintptr_t)(lds_void *)xs + (w.lane & 15) * xs_stride * 2;
-    auto first_table = [&]() {
-        const uint32_t n16 = D * c.K0 * c.rs0;
-        for (uint32_t base = wave * 64; base < n16; base += 64 * nwv)
-            if (base + w.lane < n16) lds_dma_16(p.r.tables + c.toff0 + base + w.lane, smem + base);
-    };
+    auto first_table = [&]() { copy_words_to_lds_async(smem, p.r.tables + c.toff0, D * c.K0 * c.rs0, nwv); };
     first_table();
     for (uint32_t i = threadIdx.x; i < 2 * w.nblk; i += blockDim.x) sm_meta[i] = reinterpret_cast<const uint4 *>(p.r.bmeta + c.b_lo)[i];
     // activations of the group's channels, 16 rows (rows >= batch are zero): one

@@ -165,26 +165,50 @@ __device__ __forceinline__ uint4 keep_if(bool keep, uint4 v)
 // else).
 typedef __attribute__((address_space(3))) void lds_void;
 
-// One global_load_lds_dwordx4: every active lane moves 16 bytes from its own
-// global address to lds_dst + lane (lds_dst is the same for the whole
-// wavefront).  Written as inline assembly on purpose: the compiler then does
-// not know that LDS is being written behind its back and does not force the
-// copy to complete before the next LDS read; completion is awaited explicitly
-// (wait_async_copies / wait_vmcnt_le) before a barrier publishes the data.
-__device__ __forceinline__ void lds_dma_16(const void *gptr, uint4 *lds_dst)
+// One global_load_lds_dwordx4: every active lane moves 16 bytes from gbase + lane_bytes to LDS byte address
+// lds_addr + 16 * lane.  gbase and lds_addr are the same for the whole wavefront and sit in scalar registers
+// (the saddr form of the instruction: scalar base plus the lane's own 32-bit byte offset).  Written as inline
+// assembly on purpose: the compiler then does not know that LDS is being written behind its back and does
+// not force the copy to complete before the next LDS read; completion is awaited explicitly
+// (wait_async_copies) before a barrier publishes the data.
+__device__ __forceinline__ void lds_dma_16_uniform(const void *gbase, uint32_t lane_bytes, uint32_t lds_addr)
 {
-    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void *)lds_dst);
     if (!skl_in_range(lds_addr, SKL_LDS_HARD_BYTES - 1023u, SKL_DBG_LDS_COPY)) return;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_bytes), "s"(gbase), "s"(lds_addr) : "memory", "m0");
 }
 
 // A source padded to whole 64-word chunks (no bounds check per lane), copied
 // by a workgroup of nw wavefronts: wavefront w moves chunks w, w + nw, ..
+// Everything but the lane's offset inside a chunk is the same for the whole wavefront and is kept in scalar
+// registers, so that a chunk costs a handful of scalar instructions and the copy instruction (with the
+// addresses formed per lane a chunk took 18 instructions, 8 of them vector, and the six chunks a wavefront
+// issues per block were a sixth of a block's time).
 __device__ __forceinline__ void copy_chunks_to_lds_async(uint4 *dst, const uint4 *src, uint32_t n16, uint32_t nw)
 {
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const uint32_t n_chunks = (n16 + 63) >> 6;
-    for (uint32_t ch = wave; ch < n_chunks; ch += nw) lds_dma_16(src + ch * 64 + lane, dst + ch * 64);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const uint32_t n_chunks = __builtin_amdgcn_readfirstlane((n16 + 63) >> 6);
+    const uint32_t step = __builtin_amdgcn_readfirstlane(nw);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void *)dst);
+    const uint64_t s = reinterpret_cast<uint64_t>(src);
+    // (the builtin returns a signed int: without the casts the low word would be sign-extended over the high one)
+    const uint32_t s_lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)s), s_hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(s >> 32));
+    const uint64_t base = (uint64_t)s_hi << 32 | (uint64_t)s_lo;
+    for (uint32_t ch = wave; ch < n_chunks; ch += step)
+        lds_dma_16_uniform(reinterpret_cast<const char *>(base + (uint64_t)ch * 1024), lane * 16, lds0 + ch * 1024);
+}
+
+// The same for a source of any length (the padded tables end inside a chunk): the lanes past the end sit out.
+__device__ __forceinline__ void copy_words_to_lds_async(uint4 *dst, const uint4 *src, uint32_t n16, uint32_t nw)
+{
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const uint32_t n = __builtin_amdgcn_readfirstlane(n16), step = __builtin_amdgcn_readfirstlane(nw);
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void *)dst);
+    const uint64_t s = reinterpret_cast<uint64_t>(src);
+    const uint32_t s_lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)s), s_hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(s >> 32));
+    const uint64_t base = (uint64_t)s_hi << 32 | (uint64_t)s_lo;
+    for (uint32_t ch = wave; ch * 64 < n; ch += step)
+        if (ch * 64 + lane < n)
+            lds_dma_16_uniform(reinterpret_cast<const char *>(base + (uint64_t)ch * 1024), lane * 16, lds0 + ch * 1024);
 }
 
 __device__ __forceinline__ void wait_async_copies()

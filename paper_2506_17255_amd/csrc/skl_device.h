@@ -289,11 +289,6 @@ struct RowArgs {
     uint32_t in, out, n_blocks, n_otiles, n_seg;
 };
 
-__device__ __forceinline__ void stage_table(uint4 *dst, const uint4 *src, uint32_t n16)
-{
-    for (uint32_t i = threadIdx.x; i < n16; i += SKL_WG) dst[i] = src[i];
-}
-
 // word offsets (r*K + k_r(o)) * rs of output channel o in a block table
 template <int D>
 __device__ __forceinline__ void row_offsets(const HashArgs &h, uint32_t o, uint32_t K, uint32_t rs, uint32_t (&off)[D])

@@ -64,7 +64,9 @@ __device__ __forceinline__ void rebuild_block(const RebuildArgs &p, uint32_t idx
     const uint32_t blk = idx % p.n_blocks, seg = idx / p.n_blocks;
     if (!skl_in_range(blk, p.n_blocks, SKL_DBG_BLOCK) || !skl_in_range(seg, p.n_oseg, SKL_DBG_OUTPUT)) return;
     const skl_block_meta bm = p.bmeta[blk];
-    stage_table(smem, p.tables + bm.table_off16, D * bm.K * bm.rs);
+    // global -> LDS without passing through registers: all of a wavefront's chunks are in flight at once
+    copy_words_to_lds_async(smem, p.tables + bm.table_off16, D * bm.K * bm.rs, SKL_WG / 64);
+    wait_async_copies();
     __syncthreads();
     switch (bm.rs) {
     case 9: rebuild_body<D, 9>(p, blk, seg, bm, smem); break;

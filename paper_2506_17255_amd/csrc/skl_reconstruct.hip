@@ -40,9 +40,10 @@ __global__ __launch_bounds__(SKL_WG) void k_row_reconstruct(RowArgs p, uint32_t 
     if (!skl_in_range(block0 + blockIdx.x, p.n_blocks, SKL_DBG_BLOCK)) return;
     const skl_block_meta bm = p.bmeta[block0 + blockIdx.x];
     const uint32_t n16 = D * bm.K * bm.rs;
-    stage_table(smem, p.tables + bm.table_off16, n16);
+    copy_words_to_lds_async(smem, p.tables + bm.table_off16, n16, SKL_WG / 64);    // global -> LDS, no registers in between
     uint32_t *chs = reinterpret_cast<uint32_t *>(smem + n16);
     if (threadIdx.x < 8 * bm.nb) chs[threadIdx.x] = p.chan[bm.chan_off + threadIdx.x];
+    wait_async_copies();
     __syncthreads();
     switch (bm.rs) {
     case 9: row_reconstruct_body<D, 9>(p, bm, smem, chs, W_hat); break;
